@@ -1,0 +1,996 @@
+/*
+ * CPU oracle for the batched rigid-body step -- TEST INFRASTRUCTURE ONLY.
+ * See oracle.h.  Plain scalar C, fp64 everywhere except the contact *selection*
+ * predicate, which is evaluated in fp32 with a fixed operation order (no fused
+ * multiply-add; compile with -ffp-contract=off) so that the integer outcome
+ * (which slots are active and against which terrain feature) is a pure function
+ * of the fp32-rounded state.
+ *
+ * Paper basis (Section 3.1): maximal coordinates, torque control, speculative
+ * contacts as unilateral constraints, isotropic Coulomb friction, restitution
+ * 0, implicit-style velocity-level time stepping.  The paper's Newton/Krylov
+ * solver is replaced by a fixed-count projected-Jacobi iteration; where the
+ * paper is silent the readings are listed in the design document.
+ * Observation: Table 2 ("Ours").  Reward: Eq. (1)-(3).  Episode rules: Section
+ * 4.1 (fall threshold, 1000-frame cap).
+ */
+#include "oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define MAXB 32
+#define MAXJ 32
+#define MAXS 96
+#define MAXD 64
+
+typedef struct { double x, y, z; } v3;
+typedef struct { double w, x, y, z; } quat;
+
+static v3 V(double x, double y, double z) { v3 r = {x, y, z}; return r; }
+static v3 vadd(v3 a, v3 b) { return V(a.x + b.x, a.y + b.y, a.z + b.z); }
+static v3 vsub(v3 a, v3 b) { return V(a.x - b.x, a.y - b.y, a.z - b.z); }
+static v3 vscale(v3 a, double s) { return V(a.x * s, a.y * s, a.z * s); }
+static double vdot(v3 a, v3 b) { return a.x * b.x + a.y * b.y + a.z * b.z; }
+static v3 vcross(v3 a, v3 b) {
+  return V(a.y * b.z - a.z * b.y, a.z * b.x - a.x * b.z, a.x * b.y - a.y * b.x);
+}
+static double vnorm(v3 a) { return sqrt(vdot(a, a)); }
+static double vget(v3 a, int k) { return k == 0 ? a.x : (k == 1 ? a.y : a.z); }
+
+static quat qmul(quat a, quat b) {
+  quat r;
+  r.w = a.w * b.w - a.x * b.x - a.y * b.y - a.z * b.z;
+  r.x = a.w * b.x + a.x * b.w + a.y * b.z - a.z * b.y;
+  r.y = a.w * b.y - a.x * b.z + a.y * b.w + a.z * b.x;
+  r.z = a.w * b.z + a.x * b.y - a.y * b.x + a.z * b.w;
+  return r;
+}
+static quat qconj(quat a) { quat r = {a.w, -a.x, -a.y, -a.z}; return r; }
+static quat qnormalize(quat a) {
+  double n = sqrt(a.w * a.w + a.x * a.x + a.y * a.y + a.z * a.z);
+  quat r = {a.w / n, a.x / n, a.y / n, a.z / n};
+  return r;
+}
+/* rotation matrix columns of a unit quaternion: m[c] is the image of body axis c */
+static void qmat(quat q, v3 m[3]) {
+  double w = q.w, x = q.x, y = q.y, z = q.z;
+  m[0] = V(1 - 2 * (y * y + z * z), 2 * (x * y + w * z), 2 * (x * z - w * y));
+  m[1] = V(2 * (x * y - w * z), 1 - 2 * (x * x + z * z), 2 * (y * z + w * x));
+  m[2] = V(2 * (x * z + w * y), 2 * (y * z - w * x), 1 - 2 * (x * x + y * y));
+}
+static v3 mrot(const v3 m[3], v3 a) { /* R a */
+  return vadd(vadd(vscale(m[0], a.x), vscale(m[1], a.y)), vscale(m[2], a.z));
+}
+static v3 mrot_t(const v3 m[3], v3 a) { /* R^T a */
+  return V(vdot(m[0], a), vdot(m[1], a), vdot(m[2], a));
+}
+/* rotation vector of a unit quaternion, sign-fixed to the short way round */
+static v3 qlog(quat q) {
+  if (q.w < 0) { q.w = -q.w; q.x = -q.x; q.y = -q.y; q.z = -q.z; }
+  v3 u = V(q.x, q.y, q.z);
+  double s = vnorm(u);
+  if (s < 1e-12) return vscale(u, 2.0);
+  return vscale(u, 2.0 * atan2(s, q.w) / s);
+}
+static quat qexp(v3 phi) {
+  double a = vnorm(phi);
+  quat r;
+  if (a < 1e-12) { r.w = 1; r.x = 0.5 * phi.x; r.y = 0.5 * phi.y; r.z = 0.5 * phi.z; return r; }
+  double s = sin(0.5 * a) / a;
+  r.w = cos(0.5 * a); r.x = s * phi.x; r.y = s * phi.y; r.z = s * phi.z;
+  return r;
+}
+
+/* ------------------------------------------------------------------ model */
+
+typedef struct {
+  int body, kind; /* kind 0: end sphere at -l, 1: end sphere at +l (or the sphere itself), 2: mid-segment */
+} slot_def;
+
+typedef struct {
+  int B, J, D, S, F;
+  double radius[MAXB], half_len[MAXB], mass[MAXB];
+  int axis[MAXB];
+  v3 inertia[MAXB], rest_pos[MAXB];
+  int jp[MAXJ], jc[MAXJ];
+  v3 la[MAXJ], lb[MAXJ];       /* anchor in parent / child frame */
+  v3 jaxes[MAXJ][3];
+  int jmode[MAXJ][3], jact[MAXJ][3];
+  double jlo[MAXJ][3], jhi[MAXJ][3], jgear[MAXJ][3];
+  int root, feet[8];
+  int body_joint_count[MAXB];
+  slot_def slots[MAXS];
+  double term_height, alive_bonus;
+  int terrain_kind, nx, ny;
+  double cell, hox, hoy;
+  float* heights;
+  v3 g;
+  double mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
+  int gyro, contacts, max_steps;
+} model;
+
+typedef struct {
+  v3 x[MAXB], v[MAXB], w[MAXB];
+  quat q[MAXB];
+  v3 origin;
+  double target[2];
+  double u[MAXD]; /* clipped actions of the last step */
+  int steps;
+  oracle_contact con[MAXS];
+} env_state;
+
+struct oracle_sim {
+  model m;
+  int N, threads;
+  env_state* env;
+  int trace_env, trace_cap, trace_n;
+  oracle_sweep_trace* trace;
+};
+
+/* ------------------------------------------------- fp32 contact selection */
+/* Everything in this block is single precision with the operation order
+ * written out; it decides integers only (active, kind, feature id).           */
+
+typedef struct { float x, y, z; } f3;
+static f3 F3(float x, float y, float z) { f3 r = {x, y, z}; return r; }
+static f3 fsub(f3 a, f3 b) { return F3(a.x - b.x, a.y - b.y, a.z - b.z); }
+static float fdot(f3 a, f3 b) { float s = a.x * b.x; float t = a.y * b.y; s = s + t; t = a.z * b.z; return s + t; }
+static f3 fcross(f3 a, f3 b) {
+  float cx0 = a.y * b.z, cx1 = a.z * b.y;
+  float cy0 = a.z * b.x, cy1 = a.x * b.z;
+  float cz0 = a.x * b.y, cz1 = a.y * b.x;
+  return F3(cx0 - cx1, cy0 - cy1, cz0 - cz1);
+}
+
+typedef struct {
+  int nx, ny;
+  float cell, inv_cell, ox, oy;
+  const float* h;
+} hf32;
+
+static f3 hf_vertex(const hf32* H, int i, int j) {
+  float fx = (float)i * H->cell, fy = (float)j * H->cell;
+  return F3(H->ox + fx, H->oy + fy, H->h[(size_t)j * H->nx + i]);
+}
+
+/* squared distance from P to triangle (A,B,C); closest point through the six
+ * projections of P onto the two edge directions at the three corners */
+static float tri_dist2_f32(f3 P, f3 A, f3 B, f3 C) {
+  f3 ab = fsub(B, A), ac = fsub(C, A), ap = fsub(P, A);
+  float g11 = fdot(ab, ab), g12 = fdot(ab, ac), g22 = fdot(ac, ac);
+  float d1 = fdot(ab, ap), d2 = fdot(ac, ap);
+  float d3 = d1 - g11, d4 = d2 - g12, d5 = d1 - g12, d6 = d2 - g22;
+  float v, w;
+  if (d1 <= 0.0f && d2 <= 0.0f) { v = 0.0f; w = 0.0f; }
+  else if (d3 >= 0.0f && d4 <= d3) { v = 1.0f; w = 0.0f; }
+  else if (d6 >= 0.0f && d5 <= d6) { v = 0.0f; w = 1.0f; }
+  else {
+    float vc = d1 * d4 - d3 * d2;
+    float vb = d5 * d2 - d1 * d6;
+    float va = d3 * d6 - d5 * d4;
+    float e43 = d4 - d3, e56 = d5 - d6;
+    if (vc <= 0.0f && d1 >= 0.0f && d3 <= 0.0f) { v = d1 / g11; w = 0.0f; }
+    else if (vb <= 0.0f && d2 >= 0.0f && d6 <= 0.0f) { v = 0.0f; w = d2 / g22; }
+    else if (va <= 0.0f && e43 >= 0.0f && e56 >= 0.0f) { w = e43 / (e43 + e56); v = 1.0f - w; }
+    else { float s = (va + vb) + vc; v = vb / s; w = vc / s; }
+  }
+  f3 c = F3(A.x + (ab.x * v + ac.x * w), A.y + (ab.y * v + ac.y * w), A.z + (ab.z * v + ac.z * w));
+  f3 df = fsub(P, c);
+  return fdot(df, df);
+}
+
+static void cell_range(const hf32* H, float lo, float hi, float origin, int ncell, int* c0, int* c1) {
+  float a = floorf((lo - origin) * H->inv_cell), b = floorf((hi - origin) * H->inv_cell);
+  /* compare in float first so huge values cannot overflow the int conversion */
+  if (b < 0.0f || a > (float)(ncell - 1)) { *c0 = 0; *c1 = -1; return; }
+  if (a < 0.0f) a = 0.0f;
+  if (b > (float)(ncell - 1)) b = (float)(ncell - 1);
+  *c0 = (int)a; *c1 = (int)b;
+}
+
+#define SEL_SLACK 1e-3f
+
+/* sphere of radius r centred at world point P against the heightfield.
+ * Returns 1 and (kind, feat) if the slot is active. */
+static int select_sphere_hf(const hf32* H, f3 P, float r, float margin, int brute, int* kind, int* feat) {
+  int ncx = H->nx - 1, ncy = H->ny - 1;
+  /* underneath rule: centre below the plane of the triangle that contains its xy */
+  {
+    float ux = (P.x - H->ox) * H->inv_cell, uy = (P.y - H->oy) * H->inv_cell;
+    float fi = floorf(ux), fj = floorf(uy);
+    if (fi >= 0.0f && fi <= (float)(ncx - 1) && fj >= 0.0f && fj <= (float)(ncy - 1)) {
+      int i = (int)fi, j = (int)fj;
+      float fx = ux - fi, fy = uy - fj;
+      int t = (fx >= fy) ? 0 : 1;
+      f3 A = hf_vertex(H, i, j);
+      f3 Bv = t == 0 ? hf_vertex(H, i + 1, j) : hf_vertex(H, i + 1, j + 1);
+      f3 Cv = t == 0 ? hf_vertex(H, i + 1, j + 1) : hf_vertex(H, i, j + 1);
+      f3 nt = fcross(fsub(Bv, A), fsub(Cv, A));
+      float face = fdot(fsub(P, A), nt);
+      if (face < 0.0f) {
+        *kind = 2; *feat = 2 * (j * ncx + i) + t;
+        return 1; /* d < -r < margin always */
+      }
+    }
+  }
+  float Rq = (r + margin) + SEL_SLACK;
+  int i0, i1, j0, j1;
+  if (brute) { i0 = 0; i1 = ncx - 1; j0 = 0; j1 = ncy - 1; }
+  else {
+    cell_range(H, P.x - Rq, P.x + Rq, H->ox, ncx, &i0, &i1);
+    cell_range(H, P.y - Rq, P.y + Rq, H->oy, ncy, &j0, &j1);
+  }
+  float best = INFINITY; int best_id = -1;
+  for (int j = j0; j <= j1; ++j)
+    for (int i = i0; i <= i1; ++i) {
+      f3 A = hf_vertex(H, i, j), B1 = hf_vertex(H, i + 1, j), C1 = hf_vertex(H, i + 1, j + 1),
+         D1 = hf_vertex(H, i, j + 1);
+      for (int t = 0; t < 2; ++t) {
+        f3 Bv = t == 0 ? B1 : C1, Cv = t == 0 ? C1 : D1;
+        f3 nt = fcross(fsub(Bv, A), fsub(Cv, A));
+        float face = fdot(fsub(P, A), nt);
+        if (face < 0.0f) continue; /* back-facing */
+        float d2 = tri_dist2_f32(P, A, Bv, Cv);
+        if (d2 < best) { best = d2; best_id = 2 * (j * ncx + i) + t; }
+      }
+    }
+  if (best_id < 0) return 0;
+  float dist = sqrtf(best);
+  float d = dist - r;
+  if (d < margin) { *kind = 1; *feat = best_id; return 1; }
+  return 0;
+}
+
+static float clamp01f(float s) { return s < 0.0f ? 0.0f : (s > 1.0f ? 1.0f : s); }
+
+/* closest points between segment P0+s*(P1-P0) and edge Q0+t*(Q1-Q0); returns
+ * squared distance, s and the sign of the vertical offset */
+static float seg_edge_f32(f3 P0, f3 P1, f3 Q0, f3 Q1, float* s_out, float* dz_out) {
+  f3 d1 = fsub(P1, P0), d2 = fsub(Q1, Q0), rr = fsub(P0, Q0);
+  float a = fdot(d1, d1), e = fdot(d2, d2), f = fdot(d2, rr), c = fdot(d1, rr), b = fdot(d1, d2);
+  float ae = a * e, bb = b * b;
+  float denom = ae - bb;
+  float s, t;
+  if (denom > 1e-6f * ae) { float bf = b * f, ce = c * e; s = clamp01f((bf - ce) / denom); }
+  else s = 0.5f;
+  { float bs = b * s; t = (bs + f) / e; }
+  if (t < 0.0f) { t = 0.0f; s = clamp01f((0.0f - c) / a); }
+  else if (t > 1.0f) { t = 1.0f; s = clamp01f((b - c) / a); }
+  f3 c1 = F3(P0.x + d1.x * s, P0.y + d1.y * s, P0.z + d1.z * s);
+  f3 c2 = F3(Q0.x + d2.x * t, Q0.y + d2.y * t, Q0.z + d2.z * t);
+  f3 df = fsub(c1, c2);
+  *s_out = s; *dz_out = df.z;
+  return fdot(df, df);
+}
+
+/* capsule segment [P0,P1] (interior only) against heightfield edges */
+static int select_segment_hf(const hf32* H, f3 P0, f3 P1, float r, float margin, int brute, int* feat) {
+  int ncx = H->nx - 1, ncy = H->ny - 1;
+  float Rq = (r + margin) + SEL_SLACK;
+  int i0, i1, j0, j1;
+  if (brute) { i0 = 0; i1 = ncx - 1; j0 = 0; j1 = ncy - 1; }
+  else {
+    float xl = P0.x < P1.x ? P0.x : P1.x, xh = P0.x < P1.x ? P1.x : P0.x;
+    float yl = P0.y < P1.y ? P0.y : P1.y, yh = P0.y < P1.y ? P1.y : P0.y;
+    cell_range(H, xl - Rq, xh + Rq, H->ox, ncx, &i0, &i1);
+    cell_range(H, yl - Rq, yh + Rq, H->oy, ncy, &j0, &j1);
+  }
+  if (i1 < i0 || j1 < j0) return 0;
+  float best = INFINITY; int best_id = -1;
+  for (int j = j0; j <= j1 + 1; ++j)
+    for (int i = i0; i <= i1 + 1; ++i) {
+      f3 Q0 = hf_vertex(H, i, j);
+      for (int k = 0; k < 3; ++k) {
+        if ((k == 0 || k == 2) && i > i1) continue;
+        if ((k == 1 || k == 2) && j > j1) continue;
+        f3 Q1 = k == 0 ? hf_vertex(H, i + 1, j) : (k == 1 ? hf_vertex(H, i, j + 1) : hf_vertex(H, i + 1, j + 1));
+        float s, dz;
+        float d2 = seg_edge_f32(P0, P1, Q0, Q1, &s, &dz);
+        if (!(s > 0.001f && s < 0.999f)) continue; /* the ends belong to the end-sphere slots */
+        if (!(dz > 0.0f)) continue;                /* axis must be above the edge */
+        if (d2 < best) { best = d2; best_id = 3 * (j * H->nx + i) + k; }
+      }
+    }
+  if (best_id < 0) return 0;
+  float dist = sqrtf(best);
+  float d = dist - r;
+  if (d < margin) { *feat = best_id; return 1; }
+  return 0;
+}
+
+/* fp32 end points of a body's segment from the fp32-rounded state */
+static void body_ends_f32(const model* m, const env_state* e, int b, int world, f3* p0, f3* p1) {
+  float x = (float)e->x[b].x, y = (float)e->x[b].y, z = (float)e->x[b].z;
+  float qw = (float)e->q[b].w, qx = (float)e->q[b].x, qy = (float)e->q[b].y, qz = (float)e->q[b].z;
+  float l = (float)m->half_len[b];
+  f3 c;
+  if (m->axis[b] == 0) {
+    float yy = qy * qy, zz = qz * qz, xy = qx * qy, wz = qw * qz, xz = qx * qz, wy = qw * qy;
+    c = F3(1.0f - 2.0f * (yy + zz), 2.0f * (xy + wz), 2.0f * (xz - wy));
+  } else if (m->axis[b] == 1) {
+    float xx = qx * qx, zz = qz * qz, xy = qx * qy, wz = qw * qz, yz = qy * qz, wx = qw * qx;
+    c = F3(2.0f * (xy - wz), 1.0f - 2.0f * (xx + zz), 2.0f * (yz + wx));
+  } else {
+    float xx = qx * qx, yy = qy * qy, xz = qx * qz, wy = qw * qy, yz = qy * qz, wx = qw * qx;
+    c = F3(2.0f * (xz + wy), 2.0f * (yz - wx), 1.0f - 2.0f * (xx + yy));
+  }
+  f3 a = F3(l * c.x, l * c.y, l * c.z);
+  *p0 = F3(x - a.x, y - a.y, z - a.z);
+  *p1 = F3(x + a.x, y + a.y, z + a.z);
+  if (world) {
+    float ox = (float)e->origin.x, oy = (float)e->origin.y, oz = (float)e->origin.z;
+    *p0 = F3(p0->x + ox, p0->y + oy, p0->z + oz);
+    *p1 = F3(p1->x + ox, p1->y + oy, p1->z + oz);
+  }
+}
+
+/* ----------------------------------- fp64 geometry of the selected feature */
+
+static v3 hf_vertex64(const model* m, int i, int j) {
+  /* vertex coordinates are the fp32 numbers the selection used */
+  float fx = (float)i * (float)m->cell, fy = (float)j * (float)m->cell;
+  float px = (float)m->hox + fx, py = (float)m->hoy + fy;
+  return V((double)px, (double)py, (double)m->heights[(size_t)j * m->nx + i]);
+}
+static void tri_vertices64(const model* m, int tri, v3* A, v3* B, v3* C) {
+  int ncx = m->nx - 1;
+  int t = tri & 1, c = tri >> 1, i = c % ncx, j = c / ncx;
+  *A = hf_vertex64(m, i, j);
+  if (t == 0) { *B = hf_vertex64(m, i + 1, j); *C = hf_vertex64(m, i + 1, j + 1); }
+  else { *B = hf_vertex64(m, i + 1, j + 1); *C = hf_vertex64(m, i, j + 1); }
+}
+static v3 closest_on_triangle64(v3 P, v3 A, v3 B, v3 C) {
+  v3 ab = vsub(B, A), ac = vsub(C, A), ap = vsub(P, A);
+  double g11 = vdot(ab, ab), g12 = vdot(ab, ac), g22 = vdot(ac, ac);
+  double d1 = vdot(ab, ap), d2 = vdot(ac, ap);
+  double d3 = d1 - g11, d4 = d2 - g12, d5 = d1 - g12, d6 = d2 - g22;
+  double v, w;
+  if (d1 <= 0 && d2 <= 0) { v = 0; w = 0; }
+  else if (d3 >= 0 && d4 <= d3) { v = 1; w = 0; }
+  else if (d6 >= 0 && d5 <= d6) { v = 0; w = 1; }
+  else {
+    double vc = d1 * d4 - d3 * d2, vb = d5 * d2 - d1 * d6, va = d3 * d6 - d5 * d4;
+    if (vc <= 0 && d1 >= 0 && d3 <= 0) { v = d1 / g11; w = 0; }
+    else if (vb <= 0 && d2 >= 0 && d6 <= 0) { v = 0; w = d2 / g22; }
+    else if (va <= 0 && d4 - d3 >= 0 && d5 - d6 >= 0) { w = (d4 - d3) / ((d4 - d3) + (d5 - d6)); v = 1 - w; }
+    else { double s = va + vb + vc; v = vb / s; w = vc / s; }
+  }
+  return vadd(A, vadd(vscale(ab, v), vscale(ac, w)));
+}
+static double clamp01(double s) { return s < 0 ? 0 : (s > 1 ? 1 : s); }
+static void seg_edge64(v3 P0, v3 P1, v3 Q0, v3 Q1, v3* c1, v3* c2) {
+  v3 d1 = vsub(P1, P0), d2 = vsub(Q1, Q0), rr = vsub(P0, Q0);
+  double a = vdot(d1, d1), e = vdot(d2, d2), f = vdot(d2, rr), c = vdot(d1, rr), b = vdot(d1, d2);
+  double denom = a * e - b * b, s, t;
+  if (denom > 1e-6 * a * e) s = clamp01((b * f - c * e) / denom); else s = 0.5;
+  t = (b * s + f) / e;
+  if (t < 0) { t = 0; s = clamp01(-c / a); }
+  else if (t > 1) { t = 1; s = clamp01((b - c) / a); }
+  *c1 = vadd(P0, vscale(d1, s));
+  *c2 = vadd(Q0, vscale(d2, t));
+}
+
+static void clear_contact(oracle_contact* c) {
+  memset(c, 0, sizeof(*c));
+  c->kind = -1; c->feat = -1;
+}
+
+/* Speculative contact generation from positions (Section 3.1: contacts are
+ * detected speculatively and enter as unilateral constraints). */
+static void generate_contacts(const model* m, env_state* e, int brute, oracle_contact* out) {
+  hf32 H;
+  H.nx = m->nx; H.ny = m->ny; H.cell = (float)m->cell; H.inv_cell = 1.0f / (float)m->cell;
+  H.ox = (float)m->hox; H.oy = (float)m->hoy; H.h = m->heights;
+  float marginf = (float)m->margin;
+  for (int s = 0; s < m->S; ++s) {
+    oracle_contact* c = &out[s];
+    clear_contact(c);
+    if (!m->contacts) continue;
+    int b = m->slots[s].body, kind = m->slots[s].kind;
+    float rf = (float)m->radius[b];
+    double r = m->radius[b];
+    v3 R[3];
+    qmat(e->q[b], R);
+    v3 half = vscale(R[m->axis[b]], m->half_len[b]);
+    v3 p0 = vsub(e->x[b], half), p1 = vadd(e->x[b], half); /* env-local fp64 */
+    v3 p = kind == 0 ? p0 : p1;
+    f3 f0, f1;
+    body_ends_f32(m, e, b, m->terrain_kind == 1, &f0, &f1);
+    if (m->terrain_kind == 0) {
+      if (kind == 2) continue;
+      f3 fp = kind == 0 ? f0 : f1;
+      float df = fp.z - rf;
+      if (!(df < marginf)) continue;
+      c->active = 1; c->kind = 0; c->feat = -1;
+      c->d = p.z - r; c->n[0] = 0; c->n[1] = 0; c->n[2] = 1;
+      v3 rc = vsub(vsub(p, V(0, 0, r)), e->x[b]);
+      c->rc[0] = rc.x; c->rc[1] = rc.y; c->rc[2] = rc.z;
+      continue;
+    }
+    if (kind < 2) {
+      int ck = -1, feat = -1;
+      if (!select_sphere_hf(&H, kind == 0 ? f0 : f1, rf, marginf, brute, &ck, &feat)) continue;
+      v3 Pw = vadd(p, e->origin), A, Bv, Cv, n;
+      tri_vertices64(m, feat, &A, &Bv, &Cv);
+      v3 nt = vcross(vsub(Bv, A), vsub(Cv, A));
+      nt = vscale(nt, 1.0 / vnorm(nt));
+      double d;
+      if (ck == 2) { n = nt; d = vdot(vsub(Pw, A), nt) - r; }
+      else {
+        v3 cp = closest_on_triangle64(Pw, A, Bv, Cv);
+        v3 df = vsub(Pw, cp);
+        double dist = vnorm(df);
+        n = dist < 1e-9 ? nt : vscale(df, 1.0 / dist);
+        d = dist - r;
+      }
+      c->active = 1; c->kind = ck; c->feat = feat; c->d = d;
+      c->n[0] = n.x; c->n[1] = n.y; c->n[2] = n.z;
+      v3 rc = vsub(vsub(p, vscale(n, r)), e->x[b]);
+      c->rc[0] = rc.x; c->rc[1] = rc.y; c->rc[2] = rc.z;
+    } else {
+      int feat = -1;
+      if (!select_segment_hf(&H, f0, f1, rf, marginf, brute, &feat)) continue;
+      int k = feat % 3, vtx = feat / 3, i = vtx % m->nx, j = vtx / m->nx;
+      v3 Q0 = hf_vertex64(m, i, j);
+      v3 Q1 = k == 0 ? hf_vertex64(m, i + 1, j) : (k == 1 ? hf_vertex64(m, i, j + 1) : hf_vertex64(m, i + 1, j + 1));
+      v3 c1, c2;
+      seg_edge64(vadd(p0, e->origin), vadd(p1, e->origin), Q0, Q1, &c1, &c2);
+      v3 df = vsub(c1, c2);
+      double dist = vnorm(df);
+      v3 n = dist < 1e-9 ? V(0, 0, 1) : vscale(df, 1.0 / dist);
+      c->active = 1; c->kind = 3; c->feat = feat; c->d = dist - r;
+      c->n[0] = n.x; c->n[1] = n.y; c->n[2] = n.z;
+      v3 rc = vsub(vsub(vsub(c1, e->origin), vscale(n, r)), e->x[b]);
+      c->rc[0] = rc.x; c->rc[1] = rc.y; c->rc[2] = rc.z;
+    }
+  }
+}
+
+/* ------------------------------------------------------------ the substep */
+
+/* world-frame inverse inertia applied to a vector: R I^-1 R^T a */
+static v3 inv_inertia_apply(const v3 R[3], v3 inertia, v3 a) {
+  v3 b = mrot_t(R, a);
+  b = V(b.x / inertia.x, b.y / inertia.y, b.z / inertia.z);
+  return mrot(R, b);
+}
+
+typedef struct {
+  /* one scalar constraint row between body a (may be -1 = static) and body b */
+  int a, b;
+  v3 jla, jaa, jlb, jab; /* J blocks: linear/angular on a, linear/angular on b */
+  double bias, meff, lambda;
+  int type;  /* 0 bilateral, 1 one-sided (lambda >= 0), 2 friction (paired with the next/prev row) */
+  int slot;  /* contact rows: slot index, else -1 */
+} row_t;
+
+#define MAXROWS (6 * MAXJ + 3 * MAXS)
+
+static double row_jv(const row_t* r, const v3* v, const v3* w) {
+  double s = 0;
+  if (r->a >= 0) s += vdot(r->jla, v[r->a]) + vdot(r->jaa, w[r->a]);
+  if (r->b >= 0) s += vdot(r->jlb, v[r->b]) + vdot(r->jab, w[r->b]);
+  return s;
+}
+
+static void joint_frames(const model* m, const env_state* e, int j, v3 Ra[3], v3* xa, quat* qa) {
+  int a = m->jp[j];
+  if (a >= 0) { qmat(e->q[a], Ra); *xa = e->x[a]; *qa = e->q[a]; }
+  else { Ra[0] = V(1, 0, 0); Ra[1] = V(0, 1, 0); Ra[2] = V(0, 0, 1); *xa = V(0, 0, 0); qa->w = 1; qa->x = qa->y = qa->z = 0; }
+}
+
+/* joint angles: components of the rotation vector of q_a^-1 q_b along the joint axes */
+static void joint_theta(const model* m, const env_state* e, int j, double th[3]) {
+  v3 Ra[3], xa; quat qa;
+  joint_frames(m, e, j, Ra, &xa, &qa);
+  v3 phi = qlog(qmul(qconj(qa), e->q[m->jc[j]]));
+  for (int k = 0; k < 3; ++k) th[k] = vdot(m->jaxes[j][k], phi);
+}
+
+static void substep(const model* m, env_state* e, double h, int iterations, int phases,
+                    oracle_sweep_trace* trace, int* trace_n, int trace_cap) {
+  const int B = m->B, J = m->J, S = m->S;
+  v3 R[MAXB][3];
+  /* 1. contacts from positions at substep start */
+  if (phases & ORACLE_PH_CONTACTS) generate_contacts(m, e, 0, e->con);
+  for (int b = 0; b < B; ++b) qmat(e->q[b], R[b]);
+
+  /* 2. forces -> velocities: gravity, joint torques (+ on child, - on parent),
+   *    explicit gyroscopic term in the body frame */
+  if (phases & ORACLE_PH_FORCES) {
+    v3 tau[MAXB];
+    for (int b = 0; b < B; ++b) tau[b] = V(0, 0, 0);
+    for (int j = 0; j < J; ++j) {
+      v3 Ra[3], xa; quat qa;
+      joint_frames(m, e, j, Ra, &xa, &qa);
+      for (int k = 0; k < 3; ++k) {
+        if (m->jmode[j][k] != 1) continue;
+        v3 ak = mrot(Ra, m->jaxes[j][k]);
+        double t = m->jgear[j][k] * e->u[m->jact[j][k]];
+        tau[m->jc[j]] = vadd(tau[m->jc[j]], vscale(ak, t));
+        if (m->jp[j] >= 0) tau[m->jp[j]] = vsub(tau[m->jp[j]], vscale(ak, t));
+      }
+    }
+    for (int b = 0; b < B; ++b) {
+      e->v[b] = vadd(e->v[b], vscale(m->g, h));
+      v3 wb = mrot_t(R[b], e->w[b]), tb = mrot_t(R[b], tau[b]), I = m->inertia[b];
+      v3 Iw = V(I.x * wb.x, I.y * wb.y, I.z * wb.z);
+      v3 rhs = m->gyro ? vsub(tb, vcross(wb, Iw)) : tb;
+      wb = vadd(wb, V(h * rhs.x / I.x, h * rhs.y / I.y, h * rhs.z / I.z));
+      e->w[b] = mrot(R[b], wb);
+    }
+  }
+
+  if (phases & ORACLE_PH_SOLVE) {
+    /* 3. row setup.  A *block* is one joint (6 rows: 3 positional, 3 angular)
+     * or one active contact slot (3 rows: normal, two tangents).  nb[i] counts
+     * the blocks that touch body i this substep (mass splitting: inside a block
+     * body i acts with inverse mass scaled by nb[i]). */
+    static _Thread_local row_t rows[MAXROWS];
+    int nrows = 0;
+    int nb[MAXB];
+    for (int b = 0; b < B; ++b) nb[b] = m->body_joint_count[b];
+    for (int s = 0; s < S; ++s) if (e->con[s].active) nb[m->slots[s].body] += 1;
+    double pos_err_max = 0;
+    for (int j = 0; j < J; ++j) {
+      int a = m->jp[j], b = m->jc[j];
+      v3 Ra[3], xa; quat qa;
+      joint_frames(m, e, j, Ra, &xa, &qa);
+      v3 pa = vadd(xa, mrot(Ra, m->la[j])), pb = vadd(e->x[b], mrot(R[b], m->lb[j]));
+      v3 C = vsub(pb, pa), mid = vscale(vadd(pa, pb), 0.5);
+      v3 ra = vsub(mid, xa), rb = vsub(mid, e->x[b]);
+      double cn = vnorm(C);
+      if (cn > pos_err_max) pos_err_max = cn;
+      double th[3];
+      joint_theta(m, e, j, th);
+      for (int k = 0; k < 6; ++k) {
+        row_t* r = &rows[nrows++];
+        r->a = a; r->b = b; r->slot = -1; r->lambda = 0;
+        if (k < 3) {
+          v3 ex = V(k == 0, k == 1, k == 2);
+          r->jla = vscale(ex, -1); r->jaa = vscale(vcross(ra, ex), -1);
+          r->jlb = ex; r->jab = vcross(rb, ex);
+          r->bias = m->beta_j / h * vget(C, k);
+          r->type = 0;
+        } else {
+          int kk = k - 3;
+          v3 ak = mrot(Ra, m->jaxes[j][kk]);
+          r->jla = V(0, 0, 0); r->jlb = V(0, 0, 0);
+          if (m->jmode[j][kk] == 0) {
+            r->jaa = vscale(ak, -1); r->jab = ak;
+            r->bias = m->beta_j / h * th[kk];
+            r->type = 0;
+          } else {
+            double glo = th[kk] - m->jlo[j][kk], ghi = m->jhi[j][kk] - th[kk], g;
+            if (glo < ghi) { g = glo; r->jaa = vscale(ak, -1); r->jab = ak; }
+            else { g = ghi; r->jaa = ak; r->jab = vscale(ak, -1); }
+            r->bias = g >= 0 ? g / h : m->beta_j * g / h;
+            r->type = 1;
+          }
+        }
+      }
+    }
+    for (int s = 0; s < S; ++s) {
+      const oracle_contact* c = &e->con[s];
+      if (!c->active) continue;
+      int b = m->slots[s].body;
+      v3 n = V(c->n[0], c->n[1], c->n[2]), rc = V(c->rc[0], c->rc[1], c->rc[2]);
+      /* tangent basis; the branch is decided in single precision like the contact selection */
+      v3 t1 = (fabsf((float)n.x) < 0.57735f) ? vcross(n, V(1, 0, 0)) : vcross(n, V(0, 1, 0));
+      t1 = vscale(t1, 1.0 / vnorm(t1));
+      v3 t2 = vcross(n, t1);
+      v3 dirs[3] = {n, t1, t2};
+      for (int k = 0; k < 3; ++k) {
+        row_t* r = &rows[nrows++];
+        r->a = -1; r->b = b; r->slot = s; r->lambda = 0;
+        r->jla = V(0, 0, 0); r->jaa = V(0, 0, 0);
+        r->jlb = dirs[k]; r->jab = vcross(rc, dirs[k]);
+        if (k == 0) {
+          double bias = c->d >= 0 ? c->d / h : m->beta_c * c->d / h;
+          if (c->d < 0 && bias < -m->v_depen) bias = -m->v_depen;
+          r->bias = bias; r->type = 1;
+        } else { r->bias = 0; r->type = 2; }
+      }
+    }
+    for (int i = 0; i < nrows; ++i) {
+      row_t* r = &rows[i];
+      double k = 0;
+      if (r->a >= 0)
+        k += nb[r->a] * (vdot(r->jla, r->jla) / m->mass[r->a] +
+                         vdot(r->jaa, inv_inertia_apply(R[r->a], m->inertia[r->a], r->jaa)));
+      if (r->b >= 0)
+        k += nb[r->b] * (vdot(r->jlb, r->jlb) / m->mass[r->b] +
+                         vdot(r->jab, inv_inertia_apply(R[r->b], m->inertia[r->b], r->jab)));
+      r->meff = k > 0 ? 1.0 / k : 0.0;
+    }
+
+    /* 4. projected-Jacobi sweeps over blocks: every block starts from the same
+     * velocity snapshot; inside a block the rows are relaxed one after another
+     * on the block's private copy of its bodies (inverse mass scaled by nb). */
+    for (int it = 0; it < iterations; ++it) {
+      v3 v0[MAXB], w0[MAXB], pl[MAXB], pa[MAXB];
+      for (int b = 0; b < B; ++b) { v0[b] = e->v[b]; w0[b] = e->w[b]; pl[b] = V(0, 0, 0); pa[b] = V(0, 0, 0); }
+      double sq = 0, mx = 0, viol = 0, cone = -INFINITY; int nbil = 0;
+      /* diagnostics are taken on the snapshot, before any block is relaxed */
+      for (int i = 0; i < nrows; ++i) {
+        double res = row_jv(&rows[i], v0, w0) + rows[i].bias;
+        if (rows[i].type == 0) { sq += res * res; nbil++; if (fabs(res) > mx) mx = fabs(res); }
+        if (rows[i].type == 1 && -res > viol) viol = -res;
+      }
+      int i = 0;
+      while (i < nrows) {
+        int cnt = rows[i].slot < 0 ? 6 : 3;
+        int a = rows[i].a, b = rows[i].b;
+        v3 va = V(0, 0, 0), wa = V(0, 0, 0), vb = v0[b], wb = w0[b];
+        if (a >= 0) { va = v0[a]; wa = w0[a]; }
+        for (int k = 0; k < cnt; ++k) {
+          row_t* r = &rows[i + k];
+          int pair = (r->type == 2); /* friction rows come as a (t1,t2) pair solved together */
+          int nr = pair ? 2 : 1;
+          double dl[2];
+          for (int t = 0; t < nr; ++t) {
+            row_t* rr = &rows[i + k + t];
+            double jv = vdot(rr->jlb, vb) + vdot(rr->jab, wb);
+            if (a >= 0) jv += vdot(rr->jla, va) + vdot(rr->jaa, wa);
+            dl[t] = -rr->meff * (jv + rr->bias);
+          }
+          if (r->type == 1) {
+            double ln = r->lambda + dl[0];
+            if (ln < 0) ln = 0;
+            dl[0] = ln - r->lambda;
+          } else if (pair) {
+            row_t *rn = &rows[i], *r2 = &rows[i + k + 1];
+            double l1 = r->lambda + dl[0], l2 = r2->lambda + dl[1];
+            double lim = m->mu * rn->lambda, nrm = sqrt(l1 * l1 + l2 * l2);
+            if (nrm > lim) { double sc = nrm > 0 ? lim / nrm : 0; l1 *= sc; l2 *= sc; }
+            dl[0] = l1 - r->lambda; dl[1] = l2 - r2->lambda;
+            double ex = sqrt(l1 * l1 + l2 * l2) - lim;
+            if (ex > cone) cone = ex;
+          }
+          for (int t = 0; t < nr; ++t) {
+            row_t* rr = &rows[i + k + t];
+            rr->lambda += dl[t];
+            if (a >= 0) {
+              va = vadd(va, vscale(rr->jla, nb[a] * dl[t] / m->mass[a]));
+              wa = vadd(wa, vscale(inv_inertia_apply(R[a], m->inertia[a], rr->jaa), nb[a] * dl[t]));
+              pl[a] = vadd(pl[a], vscale(rr->jla, dl[t]));
+              pa[a] = vadd(pa[a], vscale(rr->jaa, dl[t]));
+            }
+            vb = vadd(vb, vscale(rr->jlb, nb[b] * dl[t] / m->mass[b]));
+            wb = vadd(wb, vscale(inv_inertia_apply(R[b], m->inertia[b], rr->jab), nb[b] * dl[t]));
+            pl[b] = vadd(pl[b], vscale(rr->jlb, dl[t]));
+            pa[b] = vadd(pa[b], vscale(rr->jab, dl[t]));
+          }
+          if (pair) ++k;
+        }
+        i += cnt;
+      }
+      /* every body receives the plain sum of the impulses of its blocks
+       * (accumulated above in ascending block order) */
+      for (int b = 0; b < B; ++b) {
+        e->v[b] = vadd(e->v[b], vscale(pl[b], 1.0 / m->mass[b]));
+        e->w[b] = vadd(e->w[b], inv_inertia_apply(R[b], m->inertia[b], pa[b]));
+      }
+      if (trace && *trace_n < trace_cap) {
+        oracle_sweep_trace* t = &trace[(*trace_n)++];
+        t->bilateral_rms = nbil ? sqrt(sq / nbil) : 0;
+        t->bilateral_max = mx;
+        t->onesided_viol = viol;
+        t->pos_err_max = pos_err_max;
+        double sl = 0;
+        for (int r = 0; r < nrows; ++r)
+          if (rows[r].slot >= 0 && rows[r].type == 1) sl += rows[r].lambda;
+        t->sum_lambda_n = sl;
+        t->cone_excess = cone;
+      }
+    }
+  }
+
+  /* 5. damping, angular-velocity cap, position integration */
+  if (phases & ORACLE_PH_INTEGRATE) {
+    for (int b = 0; b < B; ++b) {
+      e->v[b] = vscale(e->v[b], 1.0 / (1.0 + h * m->c_lin));
+      e->w[b] = vscale(e->w[b], 1.0 / (1.0 + h * m->c_ang));
+      double wn = vnorm(e->w[b]);
+      if (wn > m->w_max) e->w[b] = vscale(e->w[b], m->w_max / wn);
+      e->x[b] = vadd(e->x[b], vscale(e->v[b], h));
+      quat wq = {0, e->w[b].x, e->w[b].y, e->w[b].z};
+      quat dq = qmul(wq, e->q[b]);
+      quat qn = {e->q[b].w + 0.5 * h * dq.w, e->q[b].x + 0.5 * h * dq.x, e->q[b].y + 0.5 * h * dq.y,
+                 e->q[b].z + 0.5 * h * dq.z};
+      e->q[b] = qnormalize(qn);
+    }
+  }
+}
+
+/* ------------------------------------------------------------ obs / reward */
+
+static double terrain_height_at(const model* m, double wx, double wy) {
+  if (m->terrain_kind == 0) return 0.0;
+  double ux = (wx - (double)(float)m->hox) / m->cell, uy = (wy - (double)(float)m->hoy) / m->cell;
+  int ncx = m->nx - 1, ncy = m->ny - 1;
+  double fi = floor(ux), fj = floor(uy);
+  if (fi < 0) fi = 0; if (fi > ncx - 1) fi = ncx - 1;
+  if (fj < 0) fj = 0; if (fj > ncy - 1) fj = ncy - 1;
+  int i = (int)fi, j = (int)fj;
+  double fx = ux - fi, fy = uy - fj;
+  if (fx < 0) fx = 0; if (fx > 1) fx = 1;
+  if (fy < 0) fy = 0; if (fy > 1) fy = 1;
+  double h00 = m->heights[(size_t)j * m->nx + i], h10 = m->heights[(size_t)j * m->nx + i + 1];
+  double h11 = m->heights[(size_t)(j + 1) * m->nx + i + 1], h01 = m->heights[(size_t)(j + 1) * m->nx + i];
+  /* plane of the triangle on this side of the (i,j)-(i+1,j+1) diagonal */
+  if (fx >= fy) return h00 + fx * (h10 - h00) + fy * (h11 - h10);
+  return h00 + fx * (h11 - h01) + fy * (h01 - h00);
+}
+
+static void pack_obs(const model* m, const env_state* e, double* obs, double* reward, uint8_t* done) {
+  int D = m->D, rb = m->root, o = 0;
+  quat q = e->q[rb];
+  v3 x = e->x[rb];
+  double height = x.z + e->origin.z - terrain_height_at(m, x.x + e->origin.x, x.y + e->origin.y);
+  if (m->terrain_kind == 0) height = x.z;
+  double roll = atan2(2 * (q.w * q.x + q.y * q.z), 1 - 2 * (q.x * q.x + q.y * q.y));
+  double sp = 2 * (q.w * q.y - q.z * q.x);
+  if (sp > 1) sp = 1; if (sp < -1) sp = -1;
+  double pitch = asin(sp);
+  double yaw = atan2(2 * (q.w * q.z + q.x * q.y), 1 - 2 * (q.y * q.y + q.z * q.z));
+  double tx = e->target[0] - x.x, ty = e->target[1] - x.y;
+  double psi = atan2(ty, tx) - yaw;
+  obs[o++] = height; obs[o++] = roll; obs[o++] = pitch;
+  obs[o++] = e->v[rb].x; obs[o++] = e->v[rb].y; obs[o++] = e->v[rb].z;
+  obs[o++] = e->w[rb].x; obs[o++] = e->w[rb].y; obs[o++] = e->w[rb].z;
+  obs[o++] = sin(psi); obs[o++] = cos(psi);
+  int n_limit = 0;
+  for (int j = 0; j < m->J; ++j) {
+    double th[3];
+    joint_theta(m, e, j, th);
+    v3 Ra[3], xa; quat qa;
+    joint_frames(m, e, j, Ra, &xa, &qa);
+    v3 wrel = e->w[m->jc[j]];
+    if (m->jp[j] >= 0) wrel = vsub(wrel, e->w[m->jp[j]]);
+    for (int k = 0; k < 3; ++k) {
+      if (m->jmode[j][k] != 1) continue;
+      int a = m->jact[j][k];
+      obs[11 + a] = th[k];
+      obs[11 + D + a] = vdot(mrot(Ra, m->jaxes[j][k]), wrel);
+      obs[11 + 2 * D + a] = e->u[a];
+      double g = th[k] - m->jlo[j][k], g2 = m->jhi[j][k] - th[k];
+      if (g2 < g) g = g2;
+      if (g <= 0) n_limit++;
+    }
+  }
+  int n_feet = 0;
+  for (int f = 0; f < m->F; ++f) {
+    int flag = 0;
+    for (int s = 0; s < m->S; ++s)
+      if (m->slots[s].body == m->feet[f] && e->con[s].active && e->con[s].d <= 0.005) flag = 1;
+    obs[11 + 3 * D + f] = flag;
+    n_feet += flag;
+  }
+  /* reward, Eq. (1)-(3) */
+  double tn = sqrt(tx * tx + ty * ty);
+  double S = tn > 0 ? (e->v[rb].x * tx + e->v[rb].y * ty) / tn : 0.0;
+  double ct = cos(psi);
+  double r_heading = ct > 0.8 ? 1.0 : ct / 0.8;
+  double cvert = 1 - 2 * (q.x * q.x + q.y * q.y);
+  double r_standing = cvert > 0.93 ? 1.0 : 0.0;
+  double l1 = 0, l2 = 0;
+  for (int a = 0; a < D; ++a) { l1 += fabs(e->u[a]); l2 += e->u[a] * e->u[a]; }
+  *reward = m->alive_bonus + S + 0.5 * r_heading + 0.05 * r_standing - 4.0 * l1 - 0.5 * l2 -
+            0.2 * n_limit - 1.0 * n_feet;
+  *done = (height < m->term_height || e->steps >= m->max_steps) ? 1 : 0;
+}
+
+/* -------------------------------------------------------------- interface */
+
+oracle_sim* oracle_create(const oracle_desc* d, int32_t N) {
+  if (d->n_bodies > MAXB || d->n_joints > MAXJ || d->n_dofs > MAXD || d->n_feet > 8) return NULL;
+  oracle_sim* o = (oracle_sim*)calloc(1, sizeof(oracle_sim));
+  model* m = &o->m;
+  m->B = d->n_bodies; m->J = d->n_joints; m->D = d->n_dofs; m->F = d->n_feet;
+  for (int b = 0; b < m->B; ++b) {
+    m->radius[b] = d->radius[b]; m->half_len[b] = d->half_len[b]; m->axis[b] = d->axis[b];
+    m->mass[b] = d->mass[b];
+    m->inertia[b] = V(d->inertia[3 * b], d->inertia[3 * b + 1], d->inertia[3 * b + 2]);
+    m->rest_pos[b] = V(d->rest_pos[3 * b], d->rest_pos[3 * b + 1], d->rest_pos[3 * b + 2]);
+  }
+  for (int j = 0; j < m->J; ++j) {
+    int a = d->j_parent[j], b = d->j_child[j];
+    m->jp[j] = a; m->jc[j] = b;
+    v3 anc = V(d->j_anchor[3 * j], d->j_anchor[3 * j + 1], d->j_anchor[3 * j + 2]);
+    m->la[j] = a >= 0 ? vsub(anc, m->rest_pos[a]) : anc;
+    m->lb[j] = vsub(anc, m->rest_pos[b]);
+    for (int k = 0; k < 3; ++k) {
+      const double* ax = &d->j_axes[9 * j + 3 * k];
+      m->jaxes[j][k] = V(ax[0], ax[1], ax[2]);
+      m->jmode[j][k] = d->j_mode[3 * j + k]; m->jact[j][k] = d->j_act[3 * j + k];
+      m->jlo[j][k] = d->j_lo[3 * j + k]; m->jhi[j][k] = d->j_hi[3 * j + k];
+      m->jgear[j][k] = d->j_gear[3 * j + k];
+    }
+    if (a >= 0) m->body_joint_count[a]++;
+    m->body_joint_count[b]++;
+  }
+  m->root = d->root_body;
+  for (int f = 0; f < m->F; ++f) m->feet[f] = d->feet[f];
+  m->term_height = d->term_height; m->alive_bonus = d->alive_bonus;
+  m->terrain_kind = d->terrain_kind; m->nx = d->hf_nx; m->ny = d->hf_ny;
+  m->cell = d->hf_cell; m->hox = d->hf_origin[0]; m->hoy = d->hf_origin[1];
+  if (m->terrain_kind == 1) {
+    size_t n = (size_t)m->nx * m->ny;
+    m->heights = (float*)malloc(n * sizeof(float));
+    memcpy(m->heights, d->hf_heights, n * sizeof(float));
+  }
+  int S = 0;
+  for (int b = 0; b < m->B; ++b) {
+    if (m->half_len[b] > 0) {
+      m->slots[S].body = b; m->slots[S++].kind = 0;
+      m->slots[S].body = b; m->slots[S++].kind = 1;
+      if (m->terrain_kind == 1) { m->slots[S].body = b; m->slots[S++].kind = 2; }
+    } else { m->slots[S].body = b; m->slots[S++].kind = 1; }
+  }
+  m->S = S;
+  m->g = V(d->gravity[0], d->gravity[1], d->gravity[2]);
+  m->mu = d->mu; m->margin = d->margin; m->beta_j = d->beta_joint; m->beta_c = d->beta_contact;
+  m->v_depen = d->max_depen_vel; m->c_lin = d->lin_damping; m->c_ang = d->ang_damping;
+  m->w_max = d->max_ang_vel; m->reset_noise = d->reset_noise;
+  m->gyro = d->gyroscopic; m->contacts = d->contacts; m->max_steps = d->max_episode_steps;
+  o->N = N; o->threads = 1;
+  o->env = (env_state*)calloc((size_t)N, sizeof(env_state));
+  for (int e = 0; e < N; ++e) {
+    o->env[e].origin = V(d->env_origins[3 * e], d->env_origins[3 * e + 1], d->env_origins[3 * e + 2]);
+    o->env[e].target[0] = 1000.0; o->env[e].target[1] = 0.0;
+    for (int s = 0; s < MAXS; ++s) clear_contact(&o->env[e].con[s]);
+  }
+  o->trace_env = -1;
+  oracle_reset(o, NULL, 0);
+  return o;
+}
+
+void oracle_destroy(oracle_sim* o) {
+  if (!o) return;
+  free(o->m.heights); free(o->env); free(o);
+}
+int32_t oracle_n_slots(const oracle_sim* o) { return o->m.S; }
+int32_t oracle_obs_dim(const oracle_sim* o) { return 11 + 3 * o->m.D + o->m.F; }
+void oracle_set_threads(oracle_sim* o, int32_t n) { o->threads = n < 1 ? 1 : n; }
+int32_t oracle_get_threads(const oracle_sim* o) { return o->threads; }
+
+/* counter-based uniform generator: one splitmix64 finaliser per (seed, env, idx) */
+static uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ULL;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  return z ^ (z >> 31);
+}
+double oracle_uniform(uint64_t seed, uint64_t env, uint64_t idx) {
+  uint64_t z = mix64(seed + env * 0x632BE59BD9B4E019ULL + idx * 0xD1B54A32D192ED03ULL);
+  return (double)(z >> 40) * (1.0 / 16777216.0);
+}
+
+/* Reset (Section 4.1, initial state perturbed slightly): rest pose translated by
+ * uniform noise, common linear velocity noise, every hinge angle perturbed and
+ * clipped to its limits; bodies placed parents-first through the joint list. */
+void oracle_reset(oracle_sim* o, const uint8_t* mask, uint64_t seed) {
+  const model* m = &o->m;
+  double a = m->reset_noise;
+  for (int ei = 0; ei < o->N; ++ei) {
+    if (mask && !mask[ei]) continue;
+    env_state* e = &o->env[ei];
+    v3 off, vel;
+    off = V(a * (2 * oracle_uniform(seed, ei, 0) - 1), a * (2 * oracle_uniform(seed, ei, 1) - 1),
+            a * (2 * oracle_uniform(seed, ei, 2) - 1));
+    vel = V(a * (2 * oracle_uniform(seed, ei, 3) - 1), a * (2 * oracle_uniform(seed, ei, 4) - 1),
+            a * (2 * oracle_uniform(seed, ei, 5) - 1));
+    for (int b = 0; b < m->B; ++b) {
+      e->x[b] = vadd(m->rest_pos[b], off);
+      e->q[b].w = 1; e->q[b].x = e->q[b].y = e->q[b].z = 0;
+      e->v[b] = vel; e->w[b] = V(0, 0, 0);
+    }
+    for (int j = 0; j < m->J; ++j) {
+      v3 phi = V(0, 0, 0);
+      for (int k = 0; k < 3; ++k) {
+        if (m->jmode[j][k] != 1) continue;
+        double th = a * (2 * oracle_uniform(seed, ei, 8 + 3 * j + k) - 1);
+        if (th < m->jlo[j][k]) th = m->jlo[j][k];
+        if (th > m->jhi[j][k]) th = m->jhi[j][k];
+        phi = vadd(phi, vscale(m->jaxes[j][k], th));
+      }
+      int pa = m->jp[j], b = m->jc[j];
+      quat qa; v3 xa, Ra[3], Rb[3];
+      joint_frames(m, e, j, Ra, &xa, &qa);
+      (void)pa;
+      e->q[b] = qnormalize(qmul(qa, qexp(phi)));
+      qmat(e->q[b], Rb);
+      e->x[b] = vsub(vadd(xa, mrot(Ra, m->la[j])), mrot(Rb, m->lb[j]));
+    }
+    e->steps = 0;
+    for (int d = 0; d < m->D; ++d) e->u[d] = 0;
+    for (int s = 0; s < MAXS; ++s) clear_contact(&e->con[s]);
+  }
+}
+
+void oracle_set_state(oracle_sim* o, const double* st) {
+  int B = o->m.B;
+  for (int e = 0; e < o->N; ++e)
+    for (int b = 0; b < B; ++b) {
+      const double* s = st + ((size_t)e * B + b) * 13;
+      env_state* E = &o->env[e];
+      E->x[b] = V(s[0], s[1], s[2]);
+      E->q[b].w = s[3]; E->q[b].x = s[4]; E->q[b].y = s[5]; E->q[b].z = s[6];
+      E->v[b] = V(s[7], s[8], s[9]); E->w[b] = V(s[10], s[11], s[12]);
+    }
+}
+void oracle_get_state(const oracle_sim* o, double* st) {
+  int B = o->m.B;
+  for (int e = 0; e < o->N; ++e)
+    for (int b = 0; b < B; ++b) {
+      double* s = st + ((size_t)e * B + b) * 13;
+      const env_state* E = &o->env[e];
+      s[0] = E->x[b].x; s[1] = E->x[b].y; s[2] = E->x[b].z;
+      s[3] = E->q[b].w; s[4] = E->q[b].x; s[5] = E->q[b].y; s[6] = E->q[b].z;
+      s[7] = E->v[b].x; s[8] = E->v[b].y; s[9] = E->v[b].z;
+      s[10] = E->w[b].x; s[11] = E->w[b].y; s[12] = E->w[b].z;
+    }
+}
+void oracle_set_targets(oracle_sim* o, const double* t) {
+  for (int e = 0; e < o->N; ++e) { o->env[e].target[0] = t[2 * e]; o->env[e].target[1] = t[2 * e + 1]; }
+}
+void oracle_set_step_count(oracle_sim* o, const int32_t* c) {
+  for (int e = 0; e < o->N; ++e) o->env[e].steps = c[e];
+}
+
+static void load_actions(oracle_sim* o, const double* actions) {
+  int D = o->m.D;
+  for (int e = 0; e < o->N; ++e)
+    for (int d = 0; d < D; ++d) {
+      double u = actions ? actions[(size_t)e * D + d] : 0.0;
+      o->env[e].u[d] = u < -1 ? -1 : (u > 1 ? 1 : u);
+    }
+}
+
+void oracle_substep_phases(oracle_sim* o, const double* actions, double h, int32_t iterations, int32_t phases) {
+  load_actions(o, actions);
+  for (int e = 0; e < o->N; ++e) {
+    int tr = (e == o->trace_env);
+    substep(&o->m, &o->env[e], h, iterations, phases, tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
+  }
+}
+
+void oracle_step(oracle_sim* o, const double* actions, double dt, int32_t substeps, int32_t iterations) {
+  load_actions(o, actions);
+  double h = dt / substeps;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(o->threads)
+#endif
+  for (int e = 0; e < o->N; ++e) {
+    int tr = (e == o->trace_env);
+    for (int s = 0; s < substeps; ++s)
+      substep(&o->m, &o->env[e], h, iterations, ORACLE_PH_ALL, tr ? o->trace : NULL, &o->trace_n,
+              o->trace_cap);
+    o->env[e].steps++;
+  }
+}
+
+void oracle_get_obs(const oracle_sim* o, double* obs, double* reward, uint8_t* done) {
+  int od = oracle_obs_dim(o);
+  for (int e = 0; e < o->N; ++e) pack_obs(&o->m, &o->env[e], obs + (size_t)e * od, &reward[e], &done[e]);
+}
+void oracle_get_contacts(const oracle_sim* o, oracle_contact* recs) {
+  for (int e = 0; e < o->N; ++e) memcpy(recs + (size_t)e * o->m.S, o->env[e].con, o->m.S * sizeof(oracle_contact));
+}
+void oracle_generate_contacts(oracle_sim* o, int32_t brute, oracle_contact* recs) {
+  for (int e = 0; e < o->N; ++e) generate_contacts(&o->m, &o->env[e], brute, recs + (size_t)e * o->m.S);
+}
+void oracle_set_trace(oracle_sim* o, int32_t env, oracle_sweep_trace* buf, int32_t cap) {
+  o->trace_env = buf ? env : -1; o->trace = buf; o->trace_cap = cap; o->trace_n = 0;
+}
+int32_t oracle_trace_count(const oracle_sim* o) { return o->trace_n; }
+void oracle_joint_angles(const oracle_sim* o, double* theta) {
+  for (int e = 0; e < o->N; ++e)
+    for (int j = 0; j < o->m.J; ++j) joint_theta(&o->m, &o->env[e], j, theta + ((size_t)e * o->m.J + j) * 3);
+}

@@ -1,0 +1,116 @@
+/*
+ * CPU oracle for the batched rigid-body step -- TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, scalar fp64 implementation of the per-substep physics step
+ * (maximal coordinates, torque actuation, speculative unilateral contacts with
+ * isotropic Coulomb friction mu, restitution 0, implicit-style velocity
+ * stepping: Section 3.1 of the paper) with a fixed-count projected-Jacobi
+ * solve, followed by the observation vector of Table 2 ("Ours" column) and the
+ * reward of Eq. (1)-(3).  It shares no code with the HIP library and must only
+ * be used by tests, the smoke check and the benchmark's CPU-baseline leg.
+ *
+ * All arrays are host memory.  State interchange: state[N][B][13] =
+ * position(3), quaternion(w,x,y,z), linear velocity(3), angular velocity(3),
+ * positions env-local, velocities world-frame.
+ */
+#ifndef ORACLE_H
+#define ORACLE_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct oracle_desc {
+  int32_t n_bodies, n_joints, n_dofs, n_feet;
+  const double* radius;    /* [B] */
+  const double* half_len;  /* [B] 0 = sphere */
+  const int32_t* axis;     /* [B] body axis of the capsule segment */
+  const double* mass;      /* [B] */
+  const double* inertia;   /* [B][3] body-frame diagonal */
+  const double* rest_pos;  /* [B][3] */
+  const int32_t* j_parent; /* [J] -1 = world */
+  const int32_t* j_child;  /* [J] */
+  const double* j_anchor;  /* [J][3] rest-pose anchor */
+  const double* j_axes;    /* [J][3][3] rows e_0,e_1,e_2 in the parent frame */
+  const int32_t* j_mode;   /* [J][3] 0 lock, 1 limited actuated hinge */
+  const double* j_lo;      /* [J][3] */
+  const double* j_hi;      /* [J][3] */
+  const double* j_gear;    /* [J][3] */
+  const int32_t* j_act;    /* [J][3] action index or -1 */
+  int32_t root_body;
+  const int32_t* feet;     /* [n_feet] body indices */
+  double term_height, alive_bonus;
+  int32_t terrain_kind;    /* 0 plane z=0, 1 heightfield */
+  int32_t hf_nx, hf_ny;
+  double hf_cell, hf_origin[2];
+  const float* hf_heights; /* [ny][nx] */
+  const double* env_origins; /* [N][3] */
+  double gravity[3], mu, margin, beta_joint, beta_contact, max_depen_vel;
+  double lin_damping, ang_damping, max_ang_vel, reset_noise;
+  int32_t gyroscopic, contacts, max_episode_steps;
+} oracle_desc;
+
+typedef struct oracle_contact {
+  int32_t active; /* 0/1 */
+  int32_t kind;   /* -1 none, 0 plane, 1 triangle closest point, 2 triangle underneath, 3 edge (mid-segment) */
+  int32_t feat;   /* -1, triangle id or edge id */
+  int32_t pad;
+  double d, n[3], rc[3];
+} oracle_contact;
+
+/* per-sweep diagnostics of one env (used by the invariant pins) */
+typedef struct oracle_sweep_trace {
+  double bilateral_rms;   /* rms of (J v + bias) over bilateral rows, velocity snapshot of this sweep */
+  double bilateral_max;
+  double onesided_viol;   /* max over one-sided rows of max(0, -(J v + bias)) */
+  double sum_lambda_n;    /* sum of accumulated normal impulses after the sweep */
+  double cone_excess;     /* max over slots of |lambda_t| - mu*lambda_n_prev after the sweep */
+  double pos_err_max;     /* max |C| over joints (constant within a substep) */
+} oracle_sweep_trace;
+
+typedef struct oracle_sim oracle_sim;
+
+oracle_sim* oracle_create(const oracle_desc* desc, int32_t num_envs);
+void oracle_destroy(oracle_sim*);
+int32_t oracle_n_slots(const oracle_sim*);
+int32_t oracle_obs_dim(const oracle_sim*);
+void oracle_set_threads(oracle_sim*, int32_t n);       /* OpenMP threads over envs */
+int32_t oracle_get_threads(const oracle_sim*);
+
+void oracle_reset(oracle_sim*, const uint8_t* env_mask /*NULL=all*/, uint64_t seed);
+void oracle_set_state(oracle_sim*, const double* state);
+void oracle_get_state(const oracle_sim*, double* state);
+void oracle_set_targets(oracle_sim*, const double* target_xy /*[N][2] env-local*/);
+void oracle_set_step_count(oracle_sim*, const int32_t* counts /*[N]*/);
+
+/* phase mask for oracle_step_phases */
+#define ORACLE_PH_CONTACTS 1
+#define ORACLE_PH_FORCES 2
+#define ORACLE_PH_SOLVE 4
+#define ORACLE_PH_INTEGRATE 8
+#define ORACLE_PH_ALL 15
+
+void oracle_step(oracle_sim*, const double* actions /*[N][D]*/, double dt, int32_t substeps,
+                 int32_t iterations);
+/* one substep of length h restricted to the given phases (no obs packing, no step count) */
+void oracle_substep_phases(oracle_sim*, const double* actions, double h, int32_t iterations,
+                           int32_t phase_mask);
+void oracle_get_obs(const oracle_sim*, double* obs /*[N][obs_dim]*/, double* reward /*[N]*/,
+                    uint8_t* done /*[N]*/);
+/* contact records of the last substep, [N][S] */
+void oracle_get_contacts(const oracle_sim*, oracle_contact* recs);
+/* contact generation alone on the current state; brute != 0 scans every triangle/edge */
+void oracle_generate_contacts(oracle_sim*, int32_t brute, oracle_contact* recs);
+/* trace env `env`: buf receives one record per sweep of subsequent steps, up to cap */
+void oracle_set_trace(oracle_sim*, int32_t env, oracle_sweep_trace* buf, int32_t cap);
+int32_t oracle_trace_count(const oracle_sim*);
+/* joint angles theta[N][J][3] of the current state (rotation-vector components) */
+void oracle_joint_angles(const oracle_sim*, double* theta);
+/* uniform [0,1) draw of the reset generator, exposed so it can be pinned */
+double oracle_uniform(uint64_t seed, uint64_t env, uint64_t idx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
