@@ -1,0 +1,177 @@
+/*
+ * sim.h -- C ABI of the batched articulated rigid-body simulator for MI355X.
+ *
+ * Many independent robots (capsule/sphere bodies joined by limited hinge and
+ * lock constraints) are advanced together on one GPU, in the many-agents-per-
+ * call, Gym-like framing of the paper (Section 1 and Section 3.1: all robots
+ * are loaded into one simulation and stepped by a single call).  One sim_step
+ * advances every environment by dt, split into `substeps` substeps of
+ *   contact generation -> torque/gravity integration -> fixed-count block
+ *   projected-Jacobi solve of joint, joint-limit and contact/friction rows ->
+ *   position integration,
+ * and then packs the observation vector (Table 2, "Ours"), the reward
+ * (Eq. 1-3) and the done flag (Section 4.1 episode rules).
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; every
+ *    other pointer is HOST memory.  The library never allocates, frees or
+ *    retains caller memory except the workspace handed to sim_create, which it
+ *    uses until sim_destroy and never frees.
+ *  - `stream` is the caller's hipStream_t passed as void* (NULL = default
+ *    stream).  Calls enqueue work on it and return without synchronising,
+ *    except sim_create (synchronous uploads) and sim_check.
+ *  - External arrays are env-major, row-major: actions [N][act_dim], obs
+ *    [N][obs_dim], state [N][B][13] = position(3, env-local), quaternion
+ *    (w,x,y,z), linear velocity(3), angular velocity(3) (world frame).
+ *  - Return value 0 = success; SIM_ERR_* (negative) otherwise, with a message
+ *    available from sim_last_error().  Nothing throws or aborts across the ABI.
+ */
+#ifndef PAPER_1810_05762_SIM_H
+#define PAPER_1810_05762_SIM_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SIM_OK 0
+#define SIM_ERR_ARG (-1)        /* invalid argument */
+#define SIM_ERR_WORKSPACE (-2)  /* workspace too small or misaligned */
+#define SIM_ERR_HIP (-3)        /* a HIP runtime call failed */
+#define SIM_ERR_NONFINITE (-4)  /* sim_check found a NaN/Inf in the state */
+
+#define SIM_MAX_BODIES 16
+#define SIM_MAX_JOINTS 16
+#define SIM_MAX_DOFS 32
+#define SIM_MAX_FEET 4
+
+typedef struct sim sim_t; /* opaque; created by sim_create, released by sim_destroy */
+
+/* A rigid body: a capsule whose segment runs along body axis `axis` (0,1,2)
+ * with half length half_len, or a sphere when half_len == 0.  Body frames are
+ * world-aligned in the rest pose; inertia is diagonal in the body frame. */
+typedef struct sim_body_desc {
+  int32_t axis;
+  int32_t pad;
+  double radius, half_len, mass;
+  double inertia[3];
+  double rest_pos[3]; /* env-local rest position of the centre */
+} sim_body_desc_t;
+
+/* A joint pins `anchor` (given in the rest pose) of parent and child together
+ * (3 positional rows) and constrains the three components of their relative
+ * rotation vector along axes[k] (parent frame): mode 0 = locked, 1 = actuated
+ * hinge limited to [lo, hi] rad with torque gear * action[act].  parent = -1
+ * attaches the child to the static world.  Joints must be listed parents-first. */
+typedef struct sim_joint_desc {
+  int32_t parent, child;
+  double anchor[3];
+  double axes[3][3];
+  int32_t mode[3];
+  int32_t act[3];
+  double lo[3], hi[3], gear[3];
+} sim_joint_desc_t;
+
+typedef struct sim_desc {
+  int32_t n_bodies, n_joints; /* <= SIM_MAX_BODIES / SIM_MAX_JOINTS */
+  const sim_body_desc_t* bodies;
+  const sim_joint_desc_t* joints;
+  int32_t root_body;              /* body whose pose feeds the root observations */
+  int32_t n_feet;                 /* <= SIM_MAX_FEET */
+  int32_t foot_bodies[SIM_MAX_FEET];
+  double term_height;             /* done when root height falls below this (Section 4.1) */
+  double alive_bonus;             /* R_alive of Eq. (1): 0.5 ant, 2 humanoid */
+  int32_t max_episode_steps;      /* done when reached (1000 in Section 4.1) */
+  int32_t terrain_kind;           /* 0 = plane z = 0 (env-local), 1 = heightfield */
+  int32_t hf_nx, hf_ny;           /* height samples per axis (cells = n - 1) */
+  double hf_cell, hf_origin[2];   /* world xy of sample (0,0) and sample spacing */
+  const float* hf_heights;        /* host, [hf_ny][hf_nx] */
+  const double* env_origins;      /* host, [num_envs][3] world position of each env's origin */
+  double gravity[3];
+  double mu;                      /* isotropic Coulomb friction coefficient (1.0 in Section 3.1) */
+  double contact_margin;          /* speculative contacts are created below this gap */
+  double beta_joint, beta_contact;/* positional error feedback factors */
+  double max_depen_vel;           /* cap on the penetration recovery speed */
+  double lin_damping, ang_damping, max_ang_vel;
+  double reset_noise;             /* amplitude of the uniform reset perturbation */
+  int32_t gyroscopic;             /* 1 = explicit gyroscopic torque */
+  int32_t contacts;               /* 0 disables contact generation */
+} sim_desc_t;
+
+/* One contact slot of one env.  Slots are static: for each body in order, a
+ * capsule owns slot "end -" and "end +" (plus "mid-segment" on a heightfield),
+ * a sphere owns one.  kind: -1 none, 0 plane, 1 closest point of triangle
+ * `feat`, 2 centre underneath triangle `feat` (plane distance), 3 heightfield
+ * edge `feat` against the segment interior.  Triangle id = 2*(j*(nx-1)+i)+t with
+ * t = 0 for corners (i,j),(i+1,j),(i+1,j+1) and t = 1 for (i,j),(i+1,j+1),
+ * (i,j+1); edge id = 3*(j*nx+i)+k from sample (i,j) towards +x, +y, +x+y. */
+typedef struct sim_contact_rec {
+  int32_t active, kind, feat;
+  float d;     /* signed gap along n */
+  float n[3];  /* unit normal, terrain -> body */
+  float rc[3]; /* lever arm from the body centre to the body's surface point */
+  float w;     /* share of its body this contact block gets in the solver's mass splitting, (0,1]:
+                  rises from 0 at the margin to 1 at half the margin; the mid-segment slot also
+                  fades towards the segment ends.  0 when inactive. */
+  int32_t pad;
+} sim_contact_rec_t;
+
+/* Bytes of device workspace sim_create needs for this description (256-byte aligned base). */
+int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t* out_bytes);
+
+/* Builds the static tables from `desc` (copied; the caller may free it afterwards),
+ * uploads them and the heightfield into `workspace_dev` and puts every env in its
+ * unperturbed rest pose.  Synchronous.  SIM_ERR_ARG on an inconsistent description,
+ * SIM_ERR_WORKSPACE if workspace_bytes < sim_workspace_bytes(). */
+int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t workspace_bytes,
+               sim_t** out);
+int sim_destroy(sim_t* sim);
+
+int sim_num_envs(const sim_t* sim);
+int sim_num_bodies(const sim_t* sim);
+int sim_num_slots(const sim_t* sim); /* contact slots per env */
+int sim_obs_dim(const sim_t* sim);   /* 11 + 3 * act_dim + n_feet */
+int sim_act_dim(const sim_t* sim);   /* number of actuated hinge DoF */
+
+/* Seeded reset (Section 4.1: initial state perturbed slightly): rest pose shifted by
+ * uniform noise, a common linear velocity, every hinge angle perturbed and clipped to its
+ * limits.  env_mask_dev: one byte per env, non-zero = reset; NULL = all envs. */
+int sim_reset(sim_t* sim, const uint8_t* env_mask_dev, uint64_t seed, void* stream);
+
+/* Advances all envs by dt in `substeps` substeps of `iterations` solver sweeps each and
+ * packs obs/reward/done.  actions_dev: [N][act_dim] in [-1,1] (clipped inside); NULL = zeros.
+ * SIM_ERR_ARG if dt <= 0, substeps < 1 or iterations < 0. */
+int sim_step(sim_t* sim, const float* actions_dev, float dt, int substeps, int iterations,
+             void* stream);
+
+/* Copies what the last sim_step packed (or, before any step, the values of the current
+ * state) into caller arrays; any of the three pointers may be NULL. */
+int sim_get_obs(sim_t* sim, float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream);
+
+/* Per-env target position, env-local xy, [N][2] (Section 4.1 flagrun targets; the plain
+ * running tasks keep the default (1000, 0), i.e. "forwards"). */
+int sim_set_targets(sim_t* sim, const float* target_xy_dev, void* stream);
+
+/* Parity / checkpoint interface (not on the timed path). */
+int sim_get_state(sim_t* sim, float* state_dev, void* stream);
+int sim_set_state(sim_t* sim, const float* state_dev, void* stream);
+int sim_set_step_count(sim_t* sim, const int32_t* counts_dev, void* stream);
+/* When enabled, sim_step also stores the contact records of its last substep. */
+int sim_record_contacts(sim_t* sim, int enable);
+int sim_get_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
+/* Contact generation alone on the current state, straight into recs_dev. */
+int sim_generate_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
+/* Synchronises `stream` and scans the state: SIM_ERR_NONFINITE if any value is NaN/Inf. */
+int sim_check(sim_t* sim, void* stream);
+
+/* Launch shape of sim_step: envs per workgroup (0 = library default). */
+int sim_set_envs_per_block(sim_t* sim, int envs_per_block);
+
+/* Message for the last error on the calling thread (never NULL). */
+const char* sim_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -49,11 +49,12 @@ class _Desc(C.Structure):
 
 class Contact(C.Structure):
     _fields_ = [("active", C.c_int32), ("kind", C.c_int32), ("feat", C.c_int32), ("pad", C.c_int32),
-                ("d", C.c_double), ("n", C.c_double * 3), ("rc", C.c_double * 3)]
+                ("d", C.c_double), ("n", C.c_double * 3), ("rc", C.c_double * 3), ("w", C.c_double)]
 
 
 CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.int32), ("pad", np.int32),
-                          ("d", np.float64), ("n", np.float64, 3), ("rc", np.float64, 3)])
+                          ("d", np.float64), ("n", np.float64, 3), ("rc", np.float64, 3),
+                          ("w", np.float64)])
 TRACE_DTYPE = np.dtype([("bilateral_rms", np.float64), ("bilateral_max", np.float64),
                         ("onesided_viol", np.float64), ("sum_lambda_n", np.float64),
                         ("cone_excess", np.float64), ("pos_err_max", np.float64)])

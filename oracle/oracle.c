@@ -197,7 +197,8 @@ static void cell_range(const hf32* H, float lo, float hi, float origin, int ncel
 
 /* sphere of radius r centred at world point P against the heightfield.
  * Returns 1 and (kind, feat) if the slot is active. */
-static int select_sphere_hf(const hf32* H, f3 P, float r, float margin, int brute, int* kind, int* feat) {
+static int select_sphere_hf(const hf32* H, f3 P, float r, float margin, int brute, int* kind, int* feat,
+                            int range[4]) {
   int ncx = H->nx - 1, ncy = H->ny - 1;
   /* underneath rule: centre below the plane of the triangle that contains its xy */
   {
@@ -225,6 +226,7 @@ static int select_sphere_hf(const hf32* H, f3 P, float r, float margin, int brut
     cell_range(H, P.x - Rq, P.x + Rq, H->ox, ncx, &i0, &i1);
     cell_range(H, P.y - Rq, P.y + Rq, H->oy, ncy, &j0, &j1);
   }
+  range[0] = i0; range[1] = i1; range[2] = j0; range[3] = j1;
   float best = INFINITY; int best_id = -1;
   for (int j = j0; j <= j1; ++j)
     for (int i = i0; i <= i1; ++i) {
@@ -269,7 +271,8 @@ static float seg_edge_f32(f3 P0, f3 P1, f3 Q0, f3 Q1, float* s_out, float* dz_ou
 }
 
 /* capsule segment [P0,P1] (interior only) against heightfield edges */
-static int select_segment_hf(const hf32* H, f3 P0, f3 P1, float r, float margin, int brute, int* feat) {
+static int select_segment_hf(const hf32* H, f3 P0, f3 P1, float r, float margin, int brute, int* feat,
+                             int range[4]) {
   int ncx = H->nx - 1, ncy = H->ny - 1;
   float Rq = (r + margin) + SEL_SLACK;
   int i0, i1, j0, j1;
@@ -281,6 +284,7 @@ static int select_segment_hf(const hf32* H, f3 P0, f3 P1, float r, float margin,
     cell_range(H, yl - Rq, yh + Rq, H->oy, ncy, &j0, &j1);
   }
   if (i1 < i0 || j1 < j0) return 0;
+  range[0] = i0; range[1] = i1; range[2] = j0; range[3] = j1;
   float best = INFINITY; int best_id = -1;
   for (int j = j0; j <= j1 + 1; ++j)
     for (int i = i0; i <= i1 + 1; ++i) {
@@ -363,7 +367,7 @@ static v3 closest_on_triangle64(v3 P, v3 A, v3 B, v3 C) {
   return vadd(A, vadd(vscale(ab, v), vscale(ac, w)));
 }
 static double clamp01(double s) { return s < 0 ? 0 : (s > 1 ? 1 : s); }
-static void seg_edge64(v3 P0, v3 P1, v3 Q0, v3 Q1, v3* c1, v3* c2) {
+static double seg_edge64(v3 P0, v3 P1, v3 Q0, v3 Q1, v3* c1, v3* c2) {
   v3 d1 = vsub(P1, P0), d2 = vsub(Q1, Q0), rr = vsub(P0, Q0);
   double a = vdot(d1, d1), e = vdot(d2, d2), f = vdot(d2, rr), c = vdot(d1, rr), b = vdot(d1, d2);
   double denom = a * e - b * b, s, t;
@@ -373,11 +377,21 @@ static void seg_edge64(v3 P0, v3 P1, v3 Q0, v3 Q1, v3* c1, v3* c2) {
   else if (t > 1) { t = 1; s = clamp01((b - c) / a); }
   *c1 = vadd(P0, vscale(d1, s));
   *c2 = vadd(Q0, vscale(d2, t));
+  return s;
 }
 
 static void clear_contact(oracle_contact* c) {
   memset(c, 0, sizeof(*c));
   c->kind = -1; c->feat = -1;
+}
+
+static double block_weight(const model* m, double d, double ramp_s) {
+  /* share of its body a contact block gets in the mass splitting: rises from 0 at the margin
+   * to 1 at half the margin, times a fade of the mid-segment slot towards the segment ends */
+  double w = m->margin > 0 ? (m->margin - d) / (0.5 * m->margin) : 1.0;
+  if (w > 1.0) w = 1.0;
+  w *= ramp_s;
+  return w < 1e-6 ? 1e-6 : w;
 }
 
 /* Speculative contact generation from positions (Section 3.1: contacts are
@@ -408,13 +422,14 @@ static void generate_contacts(const model* m, env_state* e, int brute, oracle_co
       if (!(df < marginf)) continue;
       c->active = 1; c->kind = 0; c->feat = -1;
       c->d = p.z - r; c->n[0] = 0; c->n[1] = 0; c->n[2] = 1;
+      c->w = block_weight(m, c->d, 1.0);
       v3 rc = vsub(vsub(p, V(0, 0, r)), e->x[b]);
       c->rc[0] = rc.x; c->rc[1] = rc.y; c->rc[2] = rc.z;
       continue;
     }
     if (kind < 2) {
-      int ck = -1, feat = -1;
-      if (!select_sphere_hf(&H, kind == 0 ? f0 : f1, rf, marginf, brute, &ck, &feat)) continue;
+      int ck = -1, feat = -1, rg[4];
+      if (!select_sphere_hf(&H, kind == 0 ? f0 : f1, rf, marginf, brute, &ck, &feat, rg)) continue;
       v3 Pw = vadd(p, e->origin), A, Bv, Cv, n;
       tri_vertices64(m, feat, &A, &Bv, &Cv);
       v3 nt = vcross(vsub(Bv, A), vsub(Cv, A));
@@ -432,14 +447,15 @@ static void generate_contacts(const model* m, env_state* e, int brute, oracle_co
       c->n[0] = n.x; c->n[1] = n.y; c->n[2] = n.z;
       v3 rc = vsub(vsub(p, vscale(n, r)), e->x[b]);
       c->rc[0] = rc.x; c->rc[1] = rc.y; c->rc[2] = rc.z;
+      c->w = block_weight(m, d, 1.0);
     } else {
-      int feat = -1;
-      if (!select_segment_hf(&H, f0, f1, rf, marginf, brute, &feat)) continue;
+      int feat = -1, rg[4];
+      if (!select_segment_hf(&H, f0, f1, rf, marginf, brute, &feat, rg)) continue;
       int k = feat % 3, vtx = feat / 3, i = vtx % m->nx, j = vtx / m->nx;
       v3 Q0 = hf_vertex64(m, i, j);
       v3 Q1 = k == 0 ? hf_vertex64(m, i + 1, j) : (k == 1 ? hf_vertex64(m, i, j + 1) : hf_vertex64(m, i + 1, j + 1));
       v3 c1, c2;
-      seg_edge64(vadd(p0, e->origin), vadd(p1, e->origin), Q0, Q1, &c1, &c2);
+      double sp = seg_edge64(vadd(p0, e->origin), vadd(p1, e->origin), Q0, Q1, &c1, &c2);
       v3 df = vsub(c1, c2);
       double dist = vnorm(df);
       v3 n = dist < 1e-9 ? V(0, 0, 1) : vscale(df, 1.0 / dist);
@@ -447,6 +463,13 @@ static void generate_contacts(const model* m, env_state* e, int brute, oracle_co
       c->n[0] = n.x; c->n[1] = n.y; c->n[2] = n.z;
       v3 rc = vsub(vsub(vsub(c1, e->origin), vscale(n, r)), e->x[b]);
       c->rc[0] = rc.x; c->rc[1] = rc.y; c->rc[2] = rc.z;
+      /* the mid-segment block fades out towards the segment ends, where the end-sphere
+       * slots take over the same contact point */
+      double se = sp < 1 - sp ? sp : 1 - sp;
+      double ramp_s = (se - 0.001) / 0.1;
+      if (ramp_s > 1) ramp_s = 1;
+      if (ramp_s < 0) ramp_s = 0;
+      c->w = block_weight(m, c->d, ramp_s);
     }
   }
 }
@@ -465,6 +488,7 @@ typedef struct {
   int a, b;
   v3 jla, jaa, jlb, jab; /* J blocks: linear/angular on a, linear/angular on b */
   double bias, meff, lambda;
+  double sca, scb; /* inverse-mass scale of body a / b inside this row's block */
   int type;  /* 0 bilateral, 1 one-sided (lambda >= 0), 2 friction (paired with the next/prev row) */
   int slot;  /* contact rows: slot index, else -1 */
 } row_t;
@@ -528,14 +552,22 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
 
   if (phases & ORACLE_PH_SOLVE) {
     /* 3. row setup.  A *block* is one joint (6 rows: 3 positional, 3 angular)
-     * or one active contact slot (3 rows: normal, two tangents).  nb[i] counts
-     * the blocks that touch body i this substep (mass splitting: inside a block
-     * body i acts with inverse mass scaled by nb[i]). */
+     * or one active contact slot (3 rows: normal, two tangents).  Mass
+     * splitting: body i is shared out among its blocks in proportion to block
+     * weights (1 for a joint; for a contact the record's weight, which rises
+     * from 0 at the margin, so a slot that has just become active changes
+     * nothing).  W[i] is the weight sum; inside block c body i acts with
+     * its inverse mass scaled by W[i] / w_c. */
     static _Thread_local row_t rows[MAXROWS];
     int nrows = 0;
-    int nb[MAXB];
-    for (int b = 0; b < B; ++b) nb[b] = m->body_joint_count[b];
-    for (int s = 0; s < S; ++s) if (e->con[s].active) nb[m->slots[s].body] += 1;
+    double W[MAXB], wslot[MAXS];
+    for (int b = 0; b < B; ++b) W[b] = m->body_joint_count[b];
+    for (int s = 0; s < S; ++s) {
+      wslot[s] = 0;
+      if (!e->con[s].active) continue;
+      wslot[s] = e->con[s].w;
+      W[m->slots[s].body] += wslot[s];
+    }
     double pos_err_max = 0;
     for (int j = 0; j < J; ++j) {
       int a = m->jp[j], b = m->jc[j];
@@ -551,6 +583,7 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
       for (int k = 0; k < 6; ++k) {
         row_t* r = &rows[nrows++];
         r->a = a; r->b = b; r->slot = -1; r->lambda = 0;
+        r->sca = a >= 0 ? W[a] : 0.0; r->scb = W[b];
         if (k < 3) {
           v3 ex = V(k == 0, k == 1, k == 2);
           r->jla = vscale(ex, -1); r->jaa = vscale(vcross(ra, ex), -1);
@@ -588,6 +621,7 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
       for (int k = 0; k < 3; ++k) {
         row_t* r = &rows[nrows++];
         r->a = -1; r->b = b; r->slot = s; r->lambda = 0;
+        r->sca = 0.0; r->scb = W[b] / wslot[s];
         r->jla = V(0, 0, 0); r->jaa = V(0, 0, 0);
         r->jlb = dirs[k]; r->jab = vcross(rc, dirs[k]);
         if (k == 0) {
@@ -601,17 +635,17 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
       row_t* r = &rows[i];
       double k = 0;
       if (r->a >= 0)
-        k += nb[r->a] * (vdot(r->jla, r->jla) / m->mass[r->a] +
+        k += r->sca * (vdot(r->jla, r->jla) / m->mass[r->a] +
                          vdot(r->jaa, inv_inertia_apply(R[r->a], m->inertia[r->a], r->jaa)));
       if (r->b >= 0)
-        k += nb[r->b] * (vdot(r->jlb, r->jlb) / m->mass[r->b] +
+        k += r->scb * (vdot(r->jlb, r->jlb) / m->mass[r->b] +
                          vdot(r->jab, inv_inertia_apply(R[r->b], m->inertia[r->b], r->jab)));
       r->meff = k > 0 ? 1.0 / k : 0.0;
     }
 
     /* 4. projected-Jacobi sweeps over blocks: every block starts from the same
      * velocity snapshot; inside a block the rows are relaxed one after another
-     * on the block's private copy of its bodies (inverse mass scaled by nb). */
+     * on the block's private copy of its bodies (inverse mass scaled as above). */
     for (int it = 0; it < iterations; ++it) {
       v3 v0[MAXB], w0[MAXB], pl[MAXB], pa[MAXB];
       for (int b = 0; b < B; ++b) { v0[b] = e->v[b]; w0[b] = e->w[b]; pl[b] = V(0, 0, 0); pa[b] = V(0, 0, 0); }
@@ -656,13 +690,13 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
             row_t* rr = &rows[i + k + t];
             rr->lambda += dl[t];
             if (a >= 0) {
-              va = vadd(va, vscale(rr->jla, nb[a] * dl[t] / m->mass[a]));
-              wa = vadd(wa, vscale(inv_inertia_apply(R[a], m->inertia[a], rr->jaa), nb[a] * dl[t]));
+              va = vadd(va, vscale(rr->jla, rr->sca * dl[t] / m->mass[a]));
+              wa = vadd(wa, vscale(inv_inertia_apply(R[a], m->inertia[a], rr->jaa), rr->sca * dl[t]));
               pl[a] = vadd(pl[a], vscale(rr->jla, dl[t]));
               pa[a] = vadd(pa[a], vscale(rr->jaa, dl[t]));
             }
-            vb = vadd(vb, vscale(rr->jlb, nb[b] * dl[t] / m->mass[b]));
-            wb = vadd(wb, vscale(inv_inertia_apply(R[b], m->inertia[b], rr->jab), nb[b] * dl[t]));
+            vb = vadd(vb, vscale(rr->jlb, rr->scb * dl[t] / m->mass[b]));
+            wb = vadd(wb, vscale(inv_inertia_apply(R[b], m->inertia[b], rr->jab), rr->scb * dl[t]));
             pl[b] = vadd(pl[b], vscale(rr->jlb, dl[t]));
             pa[b] = vadd(pa[b], vscale(rr->jab, dl[t]));
           }

@@ -57,6 +57,7 @@ typedef struct oracle_contact {
   int32_t feat;   /* -1, triangle id or edge id */
   int32_t pad;
   double d, n[3], rc[3];
+  double w;       /* share of the body this contact block gets in the mass splitting, (0,1] */
 } oracle_contact;
 
 /* per-sweep diagnostics of one env (used by the invariant pins) */

@@ -1,0 +1,57 @@
+// Device-resident static tables of one simulator instance (private layout).
+//
+// Built on the host by sim_create from the caller's description, uploaded once
+// into the workspace and read by every kernel.  Plain data, fp32 / int32.
+#pragma once
+#include <stdint.h>
+
+namespace sim355 {
+
+constexpr int kMaxBodies = 16;
+constexpr int kMaxJoints = 16;
+constexpr int kMaxDofs = 32;
+constexpr int kMaxFeet = 4;
+constexpr int kMaxSlots = 3 * kMaxBodies;
+constexpr int kMaxBodyJoints = 8;  // joint sides touching one body
+
+struct BodyTab {
+  float radius, half_len, inv_mass;
+  float inertia[3], inv_inertia[3];
+  float rest_pos[3];
+  int32_t axis;
+  int32_t n_joint_sides;               // number of joints this body belongs to
+  int32_t joint_sides[kMaxBodyJoints]; // 2*joint + side (0 parent, 1 child), ascending
+  int32_t slot0, n_slots;              // its contact slots are slot0 .. slot0+n_slots-1
+};
+
+struct JointTab {
+  int32_t parent, child;
+  float la[3], lb[3];   // anchor in the parent / child frame
+  float axes[3][3];     // rows e_0,e_1,e_2 in the parent frame
+  int32_t mode[3], act[3];
+  float lo[3], hi[3], gear[3];
+};
+
+struct SlotTab {
+  int32_t body;
+  int32_t kind;  // 0 end sphere at -half_len, 1 end sphere at +half_len (or the sphere), 2 mid-segment
+};
+
+struct Model {
+  int32_t B, J, D, S, F;
+  int32_t root, feet[kMaxFeet];
+  int32_t terrain_kind, nx, ny;
+  float cell, inv_cell, hox, hoy;
+  float g[3];
+  float mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
+  float term_height, alive_bonus;
+  int32_t max_steps, gyro, contacts;
+  BodyTab bodies[kMaxBodies];
+  JointTab joints[kMaxJoints];
+  SlotTab slots[kMaxSlots];
+};
+
+// Contact record as kept in LDS / exported (matches sim_contact_rec_t: 12 words).
+constexpr int kRecWords = 12;
+
+}  // namespace sim355

@@ -1,0 +1,556 @@
+// Host side of the C ABI declared in include/sim.h: description checking, static
+// table construction, workspace layout, kernel launches.  All device work is in
+// hand-written kernels for gfx950; there is no CPU fallback.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/sim.h"
+#include "contact_gen.hpp"
+#include "model.hpp"
+#include "step_kernel.hpp"
+
+using namespace sim355;
+
+static_assert(SIM_MAX_BODIES == kMaxBodies && SIM_MAX_JOINTS == kMaxJoints && SIM_MAX_DOFS == kMaxDofs &&
+                  SIM_MAX_FEET == kMaxFeet,
+              "public limits and table sizes must agree");
+static_assert(sizeof(sim_contact_rec_t) == kRecWords * 4, "contact record is 12 words");
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+static int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) return fail(SIM_ERR_HIP, "%s: %s", #expr, hipGetErrorString(_e)); \
+  } while (0)
+
+extern "C" const char* sim_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------ layout
+struct Layout {
+  size_t model, heights, origins, targets, state, steps, obs, reward, done, recs, flag, total;
+};
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights) {
+  Layout L;
+  size_t o = 0;
+  L.model = o; o = align_up(o + sizeof(Model));
+  L.heights = o; o = align_up(o + (n_heights ? n_heights : 1) * sizeof(float));
+  L.origins = o; o = align_up(o + (size_t)N * 3 * sizeof(float));
+  L.targets = o; o = align_up(o + (size_t)N * 2 * sizeof(float));
+  L.state = o; o = align_up(o + (size_t)13 * B * N * sizeof(float));
+  L.steps = o; o = align_up(o + (size_t)N * sizeof(int32_t));
+  L.obs = o; o = align_up(o + (size_t)N * obs_dim * sizeof(float));
+  L.reward = o; o = align_up(o + (size_t)N * sizeof(float));
+  L.done = o; o = align_up(o + (size_t)N);
+  L.recs = o; o = align_up(o + (size_t)N * S * sizeof(sim_contact_rec_t));
+  L.flag = o; o = align_up(o + 256);
+  L.total = o;
+  return L;
+}
+
+struct sim {
+  Model host_model;
+  Layout lay;
+  char* ws;
+  int N, obs_dim, E;
+  int record;
+  int recs_valid;
+};
+
+// ------------------------------------------------------- description -> Model
+static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
+  if (!d) return fail(SIM_ERR_ARG, "desc is NULL");
+  if (num_envs < 1) return fail(SIM_ERR_ARG, "num_envs must be >= 1 (got %d)", num_envs);
+  if (d->n_bodies < 1 || d->n_bodies > kMaxBodies) return fail(SIM_ERR_ARG, "n_bodies %d outside 1..%d", d->n_bodies, kMaxBodies);
+  if (d->n_joints < 0 || d->n_joints > kMaxJoints) return fail(SIM_ERR_ARG, "n_joints %d outside 0..%d", d->n_joints, kMaxJoints);
+  if (!d->bodies || (d->n_joints && !d->joints)) return fail(SIM_ERR_ARG, "bodies/joints table is NULL");
+  if (!d->env_origins) return fail(SIM_ERR_ARG, "env_origins is NULL");
+  if (d->n_feet < 0 || d->n_feet > kMaxFeet) return fail(SIM_ERR_ARG, "n_feet %d outside 0..%d", d->n_feet, kMaxFeet);
+  if (d->root_body < 0 || d->root_body >= d->n_bodies) return fail(SIM_ERR_ARG, "root_body out of range");
+  if (d->terrain_kind != 0 && d->terrain_kind != 1) return fail(SIM_ERR_ARG, "terrain_kind must be 0 or 1");
+  if (d->terrain_kind == 1) {
+    if (d->hf_nx < 2 || d->hf_ny < 2 || !(d->hf_cell > 0) || !d->hf_heights)
+      return fail(SIM_ERR_ARG, "heightfield needs nx,ny >= 2, cell > 0 and a heights array");
+    if ((long long)d->hf_nx * d->hf_ny > (1LL << 28)) return fail(SIM_ERR_ARG, "heightfield too large");
+  }
+  if (!(d->contact_margin >= 0) || !(d->mu >= 0)) return fail(SIM_ERR_ARG, "margin and mu must be >= 0");
+  std::memset(m, 0, sizeof(*m));
+  m->B = d->n_bodies; m->J = d->n_joints; m->F = d->n_feet;
+  m->root = d->root_body;
+  for (int f = 0; f < m->F; ++f) {
+    if (d->foot_bodies[f] < 0 || d->foot_bodies[f] >= m->B) return fail(SIM_ERR_ARG, "foot body out of range");
+    m->feet[f] = d->foot_bodies[f];
+  }
+  int S = 0;
+  for (int b = 0; b < m->B; ++b) {
+    const sim_body_desc_t& s = d->bodies[b];
+    if (!(s.radius > 0) || !(s.half_len >= 0) || !(s.mass > 0) || s.axis < 0 || s.axis > 2)
+      return fail(SIM_ERR_ARG, "body %d: radius/mass must be > 0, half_len >= 0, axis in 0..2", b);
+    BodyTab& t = m->bodies[b];
+    t.radius = (float)s.radius; t.half_len = (float)s.half_len; t.inv_mass = (float)(1.0 / s.mass);
+    for (int c = 0; c < 3; ++c) {
+      if (!(s.inertia[c] > 0)) return fail(SIM_ERR_ARG, "body %d: inertia must be > 0", b);
+      t.inertia[c] = (float)s.inertia[c];
+      t.inv_inertia[c] = (float)(1.0 / s.inertia[c]);
+      t.rest_pos[c] = (float)s.rest_pos[c];
+    }
+    t.axis = s.axis;
+    t.slot0 = S;
+    t.n_slots = s.half_len > 0 ? (d->terrain_kind == 1 ? 3 : 2) : 1;
+    for (int k = 0; k < t.n_slots; ++k) {
+      m->slots[S].body = b;
+      m->slots[S].kind = s.half_len > 0 ? k : 1;
+      ++S;
+    }
+  }
+  m->S = S;
+  int D = 0;
+  std::vector<char> placed(m->B, 0);
+  placed[0] = 1;
+  for (int j = 0; j < m->J; ++j) {
+    const sim_joint_desc_t& s = d->joints[j];
+    if (s.child < 0 || s.child >= m->B || s.parent < -1 || s.parent >= m->B || s.parent == s.child)
+      return fail(SIM_ERR_ARG, "joint %d: parent/child out of range", j);
+    if (s.parent >= 0 && !placed[s.parent]) return fail(SIM_ERR_ARG, "joint %d: joints must be listed parents-first from body 0", j);
+    placed[s.child] = 1;
+    JointTab& t = m->joints[j];
+    t.parent = s.parent; t.child = s.child;
+    for (int c = 0; c < 3; ++c) {
+      t.la[c] = (float)(s.anchor[c] - (s.parent >= 0 ? d->bodies[s.parent].rest_pos[c] : 0.0));
+      t.lb[c] = (float)(s.anchor[c] - d->bodies[s.child].rest_pos[c]);
+    }
+    for (int k = 0; k < 3; ++k) {
+      double nrm = std::sqrt(s.axes[k][0] * s.axes[k][0] + s.axes[k][1] * s.axes[k][1] + s.axes[k][2] * s.axes[k][2]);
+      if (std::fabs(nrm - 1.0) > 1e-6) return fail(SIM_ERR_ARG, "joint %d: axis %d is not unit length", j, k);
+      for (int c = 0; c < 3; ++c) t.axes[k][c] = (float)s.axes[k][c];
+      t.mode[k] = s.mode[k];
+      t.act[k] = -1;
+      if (s.mode[k] == 1) {
+        if (s.act[k] < 0 || s.act[k] >= kMaxDofs) return fail(SIM_ERR_ARG, "joint %d: action index out of range", j);
+        if (!(s.lo[k] <= s.hi[k])) return fail(SIM_ERR_ARG, "joint %d: lo > hi", j);
+        t.act[k] = s.act[k];
+        if (s.act[k] + 1 > D) D = s.act[k] + 1;
+      } else if (s.mode[k] != 0) {
+        return fail(SIM_ERR_ARG, "joint %d: mode must be 0 or 1", j);
+      }
+      t.lo[k] = (float)s.lo[k]; t.hi[k] = (float)s.hi[k]; t.gear[k] = (float)s.gear[k];
+    }
+    for (int side = 0; side < 2; ++side) {
+      int body = side ? s.child : s.parent;
+      if (body < 0) continue;
+      BodyTab& bt = m->bodies[body];
+      if (bt.n_joint_sides >= kMaxBodyJoints) return fail(SIM_ERR_ARG, "body %d belongs to more than %d joints", body, kMaxBodyJoints);
+      bt.joint_sides[bt.n_joint_sides++] = 2 * j + side;
+    }
+  }
+  m->D = D;
+  m->terrain_kind = d->terrain_kind;
+  m->nx = d->hf_nx; m->ny = d->hf_ny;
+  m->cell = (float)d->hf_cell;
+  m->inv_cell = d->terrain_kind == 1 ? 1.0f / (float)d->hf_cell : 1.0f;
+  m->hox = (float)d->hf_origin[0]; m->hoy = (float)d->hf_origin[1];
+  for (int c = 0; c < 3; ++c) m->g[c] = (float)d->gravity[c];
+  m->mu = (float)d->mu; m->margin = (float)d->contact_margin;
+  m->beta_j = (float)d->beta_joint; m->beta_c = (float)d->beta_contact;
+  m->v_depen = (float)d->max_depen_vel;
+  m->c_lin = (float)d->lin_damping; m->c_ang = (float)d->ang_damping;
+  m->w_max = (float)std::fmin(d->max_ang_vel, 1e30);
+  m->reset_noise = (float)d->reset_noise;
+  m->term_height = (float)d->term_height; m->alive_bonus = (float)d->alive_bonus;
+  m->max_steps = d->max_episode_steps; m->gyro = d->gyroscopic; m->contacts = d->contacts;
+  return SIM_OK;
+}
+
+static int default_envs_per_block(const Model& m, int N) {
+  int bj = m.B > m.J ? m.B : m.J;
+  int lim = kThreads / bj;
+  int lim_c = (kKC * kThreads) / (m.S > 0 ? m.S : 1);
+  if (lim_c < lim) lim = lim_c;
+  if (lim > 16) lim = 16;
+  int want = N / 256;  // keep at least one workgroup per compute unit when N allows
+  if (want < 1) want = 1;
+  return want < lim ? want : lim;
+}
+
+// ----------------------------------------------------------------- kernels
+__global__ void set_state_kernel(const float* __restrict__ aos, float* __restrict__ soa, int B, int N) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;  // over N*B*13, env fastest in the SoA
+  int total = N * B * 13;
+  if (i >= total) return;
+  int env = i % N, rest = i / N, b = rest % B, f = rest / B;
+  soa[i] = aos[((size_t)env * B + b) * 13 + f];
+}
+__global__ void get_state_kernel(const float* __restrict__ soa, float* __restrict__ aos, int B, int N) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  int total = N * B * 13;
+  if (i >= total) return;
+  int env = i % N, rest = i / N, b = rest % B, f = rest / B;
+  aos[((size_t)env * B + b) * 13 + f] = soa[i];
+}
+__global__ void copy_out_kernel(const float* __restrict__ obs, const float* __restrict__ rew,
+                                const uint8_t* __restrict__ done, float* obs_o, float* rew_o, uint8_t* done_o,
+                                int n_obs, int N) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (obs_o && i < n_obs) obs_o[i] = obs[i];
+  if (i < N) {
+    if (rew_o) rew_o[i] = rew[i];
+    if (done_o) done_o[i] = done[i];
+  }
+}
+__global__ void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+__global__ void copy_i32_kernel(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+__global__ void check_kernel(const float* __restrict__ state, int n, int* flag) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n && !isfinite(state[i])) *flag = 1;  // plain store: every writer stores the same value
+}
+
+__global__ void gen_contacts_kernel(const Model* Mp, const float* __restrict__ heights,
+                                    const float* __restrict__ origins, const float* __restrict__ state,
+                                    int32_t* __restrict__ recs, int N) {
+  const Model& M = *Mp;
+  int i = blockIdx.x * blockDim.x + threadIdx.x;  // env fastest
+  if (i >= N * M.S) return;
+  int env = i % N, s = i / N;
+  const SlotTab sl = M.slots[s];
+  const size_t fs = (size_t)M.B * N;
+  const float* st = state + (size_t)sl.body * N + env;
+  float x[3] = {st[0], st[fs], st[2 * fs]};
+  float q[4] = {st[3 * fs], st[4 * fs], st[5 * fs], st[6 * fs]};
+  float o[3] = {origins[3 * env], origins[3 * env + 1], origins[3 * env + 2]};
+  ContactOut c = generate_contact(M, heights, x, q, sl.body, sl.kind, o);
+  int32_t* r = recs + ((size_t)env * M.S + s) * kRecWords;
+  r[0] = c.active; r[1] = c.kind; r[2] = c.feat;
+  r[3] = __float_as_int(c.d);
+  r[4] = __float_as_int(c.n.x); r[5] = __float_as_int(c.n.y); r[6] = __float_as_int(c.n.z);
+  r[7] = __float_as_int(c.rc.x); r[8] = __float_as_int(c.rc.y); r[9] = __float_as_int(c.rc.z);
+  r[10] = __float_as_int(c.w); r[11] = 0;
+}
+
+// counter-based uniform draw: one 64-bit mixing finaliser per (seed, env, index)
+__device__ inline float reset_uniform(uint64_t seed, uint64_t env, uint64_t idx) {
+  uint64_t z = seed + env * 0x632BE59BD9B4E019ULL + idx * 0xD1B54A32D192ED03ULL;
+  z += 0x9E3779B97F4A7C15ULL;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  z ^= z >> 31;
+  return (float)(z >> 40) * (1.0f / 16777216.0f);
+}
+
+// Seeded reset (Section 4.1: initial state perturbed slightly).  One thread per env;
+// bodies are placed parents-first through the joint list.
+__global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t* __restrict__ steps,
+                             const uint8_t* __restrict__ mask, uint64_t seed, int N) {
+  const Model& M = *Mp;
+  int env = blockIdx.x * blockDim.x + threadIdx.x;
+  if (env >= N) return;
+  if (mask && !mask[env]) return;
+  const float a = M.reset_noise;
+  float off[3], vel[3];
+  for (int c = 0; c < 3; ++c) {
+    off[c] = a * (2.0f * reset_uniform(seed, env, c) - 1.0f);
+    vel[c] = a * (2.0f * reset_uniform(seed, env, 3 + c) - 1.0f);
+  }
+  float X[kMaxBodies][3], Q[kMaxBodies][4];
+  for (int b = 0; b < M.B; ++b) {
+    for (int c = 0; c < 3; ++c) X[b][c] = M.bodies[b].rest_pos[c] + off[c];
+    Q[b][0] = 1.0f; Q[b][1] = Q[b][2] = Q[b][3] = 0.0f;
+  }
+  for (int j = 0; j < M.J; ++j) {
+    const JointTab& jt = M.joints[j];
+    float phi[3] = {0, 0, 0};
+    for (int k = 0; k < 3; ++k) {
+      if (jt.mode[k] != 1) continue;
+      float th = a * (2.0f * reset_uniform(seed, env, 8 + 3 * j + k) - 1.0f);
+      th = fminf(fmaxf(th, jt.lo[k]), jt.hi[k]);
+      for (int c = 0; c < 3; ++c) phi[c] += th * jt.axes[k][c];
+    }
+    float ang = sqrtf(dot(phi, phi));
+    float dq[4];
+    if (ang < 1e-12f) { dq[0] = 1.0f; dq[1] = 0.5f * phi[0]; dq[2] = 0.5f * phi[1]; dq[3] = 0.5f * phi[2]; }
+    else { float s = sinf(0.5f * ang) / ang; dq[0] = cosf(0.5f * ang); dq[1] = s * phi[0]; dq[2] = s * phi[1]; dq[3] = s * phi[2]; }
+    float qa[4] = {1, 0, 0, 0}, xa[3] = {0, 0, 0};
+    if (jt.parent >= 0) {
+      for (int c = 0; c < 4; ++c) qa[c] = Q[jt.parent][c];
+      for (int c = 0; c < 3; ++c) xa[c] = X[jt.parent][c];
+    }
+    float qb[4];
+    qb[0] = qa[0] * dq[0] - qa[1] * dq[1] - qa[2] * dq[2] - qa[3] * dq[3];
+    qb[1] = qa[0] * dq[1] + qa[1] * dq[0] + qa[2] * dq[3] - qa[3] * dq[2];
+    qb[2] = qa[0] * dq[2] - qa[1] * dq[3] + qa[2] * dq[0] + qa[3] * dq[1];
+    qb[3] = qa[0] * dq[3] + qa[1] * dq[2] - qa[2] * dq[1] + qa[3] * dq[0];
+    float inv = 1.0f / sqrtf(qb[0] * qb[0] + qb[1] * qb[1] + qb[2] * qb[2] + qb[3] * qb[3]);
+    for (int c = 0; c < 4; ++c) qb[c] *= inv;
+    float Ra[9], Rb[9], t0[3], t1[3];
+    quat_to_mat(qa, Ra);
+    quat_to_mat(qb, Rb);
+    mat_vec(Ra, jt.la, t0);
+    mat_vec(Rb, jt.lb, t1);
+    for (int c = 0; c < 4; ++c) Q[jt.child][c] = qb[c];
+    for (int c = 0; c < 3; ++c) X[jt.child][c] = xa[c] + t0[c] - t1[c];
+  }
+  const size_t fs = (size_t)M.B * N;
+  for (int b = 0; b < M.B; ++b) {
+    float* st = state + (size_t)b * N + env;
+    for (int c = 0; c < 3; ++c) st[c * fs] = X[b][c];
+    for (int c = 0; c < 4; ++c) st[(3 + c) * fs] = Q[b][c];
+    for (int c = 0; c < 3; ++c) { st[(7 + c) * fs] = vel[c]; st[(10 + c) * fs] = 0.0f; }
+  }
+  steps[env] = 0;
+}
+
+// ---------------------------------------------------------------- launches
+static int launch_step(sim* s, const float* actions, float h, int substeps, int iterations, int count_step,
+                       hipStream_t st) {
+  const Model& m = s->host_model;
+  StepArgs a;
+  a.M = reinterpret_cast<const Model*>(s->ws + s->lay.model);
+  a.heights = reinterpret_cast<const float*>(s->ws + s->lay.heights);
+  a.origins = reinterpret_cast<const float*>(s->ws + s->lay.origins);
+  a.targets = reinterpret_cast<const float*>(s->ws + s->lay.targets);
+  a.state = reinterpret_cast<float*>(s->ws + s->lay.state);
+  a.steps = reinterpret_cast<int32_t*>(s->ws + s->lay.steps);
+  a.actions = actions;
+  a.obs = reinterpret_cast<float*>(s->ws + s->lay.obs);
+  a.reward = reinterpret_cast<float*>(s->ws + s->lay.reward);
+  a.done = reinterpret_cast<uint8_t*>(s->ws + s->lay.done);
+  a.recs = (s->record && substeps > 0) ? reinterpret_cast<int32_t*>(s->ws + s->lay.recs) : nullptr;
+  a.N = s->N; a.E = s->E; a.substeps = substeps; a.iterations = iterations; a.count_step = count_step;
+  a.h = h;
+  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, s->E);
+  size_t lds_bytes = (size_t)P.total * sizeof(float);
+  if (lds_bytes > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d needs %zu bytes of LDS (limit 160 KiB)", s->E, lds_bytes);
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&step_kernel<kKC>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+  int grid = (s->N + s->E - 1) / s->E;
+  hipLaunchKernelGGL(step_kernel<kKC>, dim3(grid), dim3(kThreads), lds_bytes, st, a);
+  HIP_TRY(hipGetLastError());
+  if (a.recs) s->recs_valid = 1;
+  return SIM_OK;
+}
+
+static inline int blocks_for(size_t n, int t = 256) { return (int)((n + t - 1) / t); }
+
+// -------------------------------------------------------------------- ABI
+extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t* out_bytes) {
+  Model m;
+  int rc = build_model(desc, num_envs, &m);
+  if (rc) return rc;
+  if (!out_bytes) return fail(SIM_ERR_ARG, "out_bytes is NULL");
+  size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
+  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F, num_envs, nh).total;
+  return SIM_OK;
+}
+
+extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t workspace_bytes,
+                          sim_t** out) {
+  if (!out) return fail(SIM_ERR_ARG, "out is NULL");
+  *out = nullptr;
+  sim* s = new (std::nothrow) sim;
+  if (!s) return fail(SIM_ERR_ARG, "out of host memory");
+  int rc = build_model(desc, num_envs, &s->host_model);
+  if (rc) { delete s; return rc; }
+  const Model& m = s->host_model;
+  size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
+  s->N = num_envs;
+  s->obs_dim = 11 + 3 * m.D + m.F;
+  s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh);
+  s->record = 0; s->recs_valid = 0;
+  s->E = default_envs_per_block(m, num_envs);
+  if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace must be non-NULL and 256-byte aligned"); }
+  if (workspace_bytes < s->lay.total) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, s->lay.total); }
+  s->ws = static_cast<char*>(workspace_dev);
+  auto bail = [&](int code) { delete s; return code; };
+#define HIP_TRY_S(expr)                                                                          \
+  do {                                                                                           \
+    hipError_t _e = (expr);                                                                      \
+    if (_e != hipSuccess) return bail(fail(SIM_ERR_HIP, "%s: %s", #expr, hipGetErrorString(_e))); \
+  } while (0)
+  HIP_TRY_S(hipMemcpy(s->ws + s->lay.model, &s->host_model, sizeof(Model), hipMemcpyHostToDevice));
+  if (nh) HIP_TRY_S(hipMemcpy(s->ws + s->lay.heights, desc->hf_heights, nh * sizeof(float), hipMemcpyHostToDevice));
+  {
+    std::vector<float> org((size_t)num_envs * 3), tgt((size_t)num_envs * 2);
+    for (size_t i = 0; i < org.size(); ++i) org[i] = (float)desc->env_origins[i];
+    for (int e = 0; e < num_envs; ++e) { tgt[2 * e] = 1000.0f; tgt[2 * e + 1] = 0.0f; }
+    HIP_TRY_S(hipMemcpy(s->ws + s->lay.origins, org.data(), org.size() * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY_S(hipMemcpy(s->ws + s->lay.targets, tgt.data(), tgt.size() * sizeof(float), hipMemcpyHostToDevice));
+    std::vector<float> st((size_t)13 * m.B * num_envs, 0.0f);
+    const size_t fs = (size_t)m.B * num_envs;
+    for (int b = 0; b < m.B; ++b)
+      for (int e = 0; e < num_envs; ++e) {
+        for (int c = 0; c < 3; ++c) st[c * fs + (size_t)b * num_envs + e] = m.bodies[b].rest_pos[c];
+        st[3 * fs + (size_t)b * num_envs + e] = 1.0f;
+      }
+    HIP_TRY_S(hipMemcpy(s->ws + s->lay.state, st.data(), st.size() * sizeof(float), hipMemcpyHostToDevice));
+    HIP_TRY_S(hipMemset(s->ws + s->lay.steps, 0, (size_t)num_envs * sizeof(int32_t)));
+    HIP_TRY_S(hipMemset(s->ws + s->lay.recs, 0, (size_t)num_envs * m.S * sizeof(sim_contact_rec_t)));
+    HIP_TRY_S(hipMemset(s->ws + s->lay.flag, 0, 256));
+  }
+  rc = launch_step(s, nullptr, 1.0f, 0, 0, 0, nullptr);
+  if (rc) return bail(rc);
+  HIP_TRY_S(hipDeviceSynchronize());
+#undef HIP_TRY_S
+  *out = s;
+  return SIM_OK;
+}
+
+extern "C" int sim_destroy(sim_t* s) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  delete s;
+  return SIM_OK;
+}
+
+extern "C" int sim_num_envs(const sim_t* s) { return s ? s->N : fail(SIM_ERR_ARG, "sim is NULL"); }
+extern "C" int sim_num_bodies(const sim_t* s) { return s ? s->host_model.B : fail(SIM_ERR_ARG, "sim is NULL"); }
+extern "C" int sim_num_slots(const sim_t* s) { return s ? s->host_model.S : fail(SIM_ERR_ARG, "sim is NULL"); }
+extern "C" int sim_obs_dim(const sim_t* s) { return s ? s->obs_dim : fail(SIM_ERR_ARG, "sim is NULL"); }
+extern "C" int sim_act_dim(const sim_t* s) { return s ? s->host_model.D : fail(SIM_ERR_ARG, "sim is NULL"); }
+
+extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  const Model& m = s->host_model;
+  if (E == 0) { s->E = default_envs_per_block(m, s->N); return SIM_OK; }
+  int bj = m.B > m.J ? m.B : m.J;
+  if (E < 1 || E * bj > kThreads || E * m.S > kKC * kThreads)
+    return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*max(B,J) <= %d and E*S <= %d)", E,
+                kThreads, kThreads, kKC * kThreads);
+  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, E);
+  if ((size_t)P.total * 4 > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d exceeds LDS", E);
+  s->E = E;
+  return SIM_OK;
+}
+
+extern "C" int sim_reset(sim_t* s, const uint8_t* env_mask_dev, uint64_t seed, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(reset_kernel, dim3(blocks_for(s->N, 64)), dim3(64), 0, st,
+                     reinterpret_cast<const Model*>(s->ws + s->lay.model),
+                     reinterpret_cast<float*>(s->ws + s->lay.state),
+                     reinterpret_cast<int32_t*>(s->ws + s->lay.steps), env_mask_dev, seed, s->N);
+  HIP_TRY(hipGetLastError());
+  s->recs_valid = 0;
+  return launch_step(s, nullptr, 1.0f, 0, 0, 0, st);
+}
+
+extern "C" int sim_step(sim_t* s, const float* actions_dev, float dt, int substeps, int iterations, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  if (!(dt > 0.0f) || !std::isfinite(dt)) return fail(SIM_ERR_ARG, "dt must be finite and > 0");
+  if (substeps < 1) return fail(SIM_ERR_ARG, "substeps must be >= 1 (got %d)", substeps);
+  if (iterations < 0) return fail(SIM_ERR_ARG, "iterations must be >= 0 (got %d)", iterations);
+  return launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int sim_get_obs(sim_t* s, float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  int n_obs = s->N * s->obs_dim;
+  hipLaunchKernelGGL(copy_out_kernel, dim3(blocks_for(n_obs)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const float*>(s->ws + s->lay.obs),
+                     reinterpret_cast<const float*>(s->ws + s->lay.reward),
+                     reinterpret_cast<const uint8_t*>(s->ws + s->lay.done), obs_dev, reward_dev, done_dev, n_obs,
+                     s->N);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_set_targets(sim_t* s, const float* target_xy_dev, void* stream) {
+  if (!s || !target_xy_dev) return fail(SIM_ERR_ARG, "sim or targets is NULL");
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for((size_t)s->N * 2)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), target_xy_dev,
+                     reinterpret_cast<float*>(s->ws + s->lay.targets), s->N * 2);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_get_state(sim_t* s, float* state_dev, void* stream) {
+  if (!s || !state_dev) return fail(SIM_ERR_ARG, "sim or state is NULL");
+  size_t n = (size_t)s->N * s->host_model.B * 13;
+  hipLaunchKernelGGL(get_state_kernel, dim3(blocks_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const float*>(s->ws + s->lay.state), state_dev, s->host_model.B, s->N);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_set_state(sim_t* s, const float* state_dev, void* stream) {
+  if (!s || !state_dev) return fail(SIM_ERR_ARG, "sim or state is NULL");
+  size_t n = (size_t)s->N * s->host_model.B * 13;
+  hipLaunchKernelGGL(set_state_kernel, dim3(blocks_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     state_dev, reinterpret_cast<float*>(s->ws + s->lay.state), s->host_model.B, s->N);
+  HIP_TRY(hipGetLastError());
+  s->recs_valid = 0;
+  return launch_step(s, nullptr, 1.0f, 0, 0, 0, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int sim_set_step_count(sim_t* s, const int32_t* counts_dev, void* stream) {
+  if (!s || !counts_dev) return fail(SIM_ERR_ARG, "sim or counts is NULL");
+  hipLaunchKernelGGL(copy_i32_kernel, dim3(blocks_for(s->N)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     counts_dev, reinterpret_cast<int32_t*>(s->ws + s->lay.steps), s->N);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_record_contacts(sim_t* s, int enable) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  s->record = enable ? 1 : 0;
+  if (!enable) s->recs_valid = 0;
+  return SIM_OK;
+}
+
+extern "C" int sim_get_contacts(sim_t* s, sim_contact_rec_t* recs_dev, void* stream) {
+  if (!s || !recs_dev) return fail(SIM_ERR_ARG, "sim or recs is NULL");
+  if (!s->recs_valid) return fail(SIM_ERR_ARG, "no contact records: call sim_record_contacts(sim, 1) before sim_step");
+  size_t n = (size_t)s->N * s->host_model.S * kRecWords;
+  hipLaunchKernelGGL(copy_i32_kernel, dim3(blocks_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const int32_t*>(s->ws + s->lay.recs), reinterpret_cast<int32_t*>(recs_dev),
+                     (int)n);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_generate_contacts(sim_t* s, sim_contact_rec_t* recs_dev, void* stream) {
+  if (!s || !recs_dev) return fail(SIM_ERR_ARG, "sim or recs is NULL");
+  size_t n = (size_t)s->N * s->host_model.S;
+  hipLaunchKernelGGL(gen_contacts_kernel, dim3(blocks_for(n, 64)), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const Model*>(s->ws + s->lay.model),
+                     reinterpret_cast<const float*>(s->ws + s->lay.heights),
+                     reinterpret_cast<const float*>(s->ws + s->lay.origins),
+                     reinterpret_cast<const float*>(s->ws + s->lay.state), reinterpret_cast<int32_t*>(recs_dev),
+                     s->N);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_check(sim_t* s, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int* flag = reinterpret_cast<int*>(s->ws + s->lay.flag);
+  int n = s->N * s->host_model.B * 13;
+  int zero = 0, host_flag = 0;
+  HIP_TRY(hipMemcpyAsync(flag, &zero, sizeof(int), hipMemcpyHostToDevice, st));
+  hipLaunchKernelGGL(check_kernel, dim3(blocks_for(n)), dim3(256), 0, st,
+                     reinterpret_cast<const float*>(s->ws + s->lay.state), n, flag);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(&host_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (host_flag) return fail(SIM_ERR_NONFINITE, "non-finite value in the body state");
+  return SIM_OK;
+}

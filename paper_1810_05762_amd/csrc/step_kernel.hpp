@@ -1,0 +1,677 @@
+// Fused env-step kernel: every substep of one sim_step plus obs/reward packing
+// in a single launch.
+//
+// Mapping.  One workgroup owns E consecutive environments for the whole step.
+// All LDS arrays are laid out [item][component][E] with the env index fastest,
+// and every thread role uses e = tid % E, so the lanes of a wavefront that work
+// on the same item of neighbouring envs touch consecutive LDS banks and
+// consecutive global addresses of the [field][body][env] state arrays.
+// Roles (a thread can hold several):
+//   body thread  (e, b): owns pose and velocity of one body in registers,
+//   joint thread (e, j): owns the six rows of one joint (constants in registers),
+//   contact thread      : owns the three rows of up to KC active contact slots,
+//   env thread   (e)    : packs root observations, reward and done.
+//
+// Per substep (Section 3.1 of the paper: maximal coordinates, torque control,
+// speculative unilateral contacts, isotropic Coulomb friction, restitution 0):
+//   A  body threads publish pose and world inverse inertia
+//   B  contact generation per slot; joint threads turn actions into torques
+//   C  body threads count their blocks, integrate gravity/torque/gyroscopic term
+//   D  joint / contact threads build row constants
+//   S  `iterations` sweeps: every block relaxes its rows one after another on a
+//      private copy of its bodies taken from the shared snapshot; a body is
+//      shared out among its blocks by weight (joint 1, contact a ramp from 0 at
+//      the margin to 1 at half the margin) and acts inside block c with inverse
+//      mass scaled by W / w_c; then every body takes the weighted average of the
+//      copies of its blocks in static order (no atomics)
+//   E  damping, angular-velocity cap, position integration
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "contact_gen.hpp"
+#include "model.hpp"
+
+namespace sim355 {
+
+constexpr int kThreads = 256;
+constexpr int kKC = 3;  // contact slots a thread can own per substep
+
+struct StepArgs {
+  const Model* M;
+  const float* heights;
+  const float* origins;  // [N][3]
+  const float* targets;  // [N][2]
+  float* state;          // [13][B][N]
+  int32_t* steps;        // [N]
+  const float* actions;  // [N][D] or null
+  float* obs;            // [N][obs_dim]
+  float* reward;         // [N]
+  uint8_t* done;         // [N]
+  int32_t* recs;         // [N][S][12] or null
+  int N, E, substeps, iterations, count_step;
+  float h;
+};
+
+struct LdsPlan {
+  int pos, vel, iw, nb, outj, outc, rec, list, u, obs, lim, count, total;
+};
+
+__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E) {
+  LdsPlan p;
+  int o = 0;
+  p.pos = o; o += B * 7 * E;
+  p.vel = o; o += B * 6 * E;
+  p.iw = o; o += B * 6 * E;
+  p.nb = o; o += B * E;
+  p.outj = o; o += J * 12 * E;
+  p.outc = o; o += S * 6 * E;
+  p.rec = o; o += S * kRecWords * E;
+  p.list = o; o += S * E;
+  p.u = o; o += (D > 0 ? D : 1) * E;
+  p.obs = o; o += (11 + 3 * D + F) * E;
+  p.lim = o; o += (D > 0 ? D : 1) * E;
+  p.count = o; o += 4;
+  p.total = o;
+  return p;
+}
+
+__device__ __forceinline__ void quat_to_mat(const float q[4], float R[9]) {
+  // R[3*r + c]: row r, column c; column c is the image of body axis c
+  float w = q[0], x = q[1], y = q[2], z = q[3];
+  R[0] = 1.0f - 2.0f * (y * y + z * z); R[1] = 2.0f * (x * y - w * z); R[2] = 2.0f * (x * z + w * y);
+  R[3] = 2.0f * (x * y + w * z); R[4] = 1.0f - 2.0f * (x * x + z * z); R[5] = 2.0f * (y * z - w * x);
+  R[6] = 2.0f * (x * z - w * y); R[7] = 2.0f * (y * z + w * x); R[8] = 1.0f - 2.0f * (x * x + y * y);
+}
+__device__ __forceinline__ void mat_vec(const float R[9], const float a[3], float o[3]) {
+  o[0] = R[0] * a[0] + R[1] * a[1] + R[2] * a[2];
+  o[1] = R[3] * a[0] + R[4] * a[1] + R[5] * a[2];
+  o[2] = R[6] * a[0] + R[7] * a[1] + R[8] * a[2];
+}
+__device__ __forceinline__ void mat_t_vec(const float R[9], const float a[3], float o[3]) {
+  o[0] = R[0] * a[0] + R[3] * a[1] + R[6] * a[2];
+  o[1] = R[1] * a[0] + R[4] * a[1] + R[7] * a[2];
+  o[2] = R[2] * a[0] + R[5] * a[1] + R[8] * a[2];
+}
+// symmetric 3x3 (xx,xy,xz,yy,yz,zz) times vector
+__device__ __forceinline__ void sym_vec(const float S[6], const float a[3], float o[3]) {
+  o[0] = S[0] * a[0] + S[1] * a[1] + S[2] * a[2];
+  o[1] = S[1] * a[0] + S[3] * a[1] + S[4] * a[2];
+  o[2] = S[2] * a[0] + S[4] * a[1] + S[5] * a[2];
+}
+__device__ __forceinline__ void cross(const float a[3], const float b[3], float o[3]) {
+  o[0] = a[1] * b[2] - a[2] * b[1];
+  o[1] = a[2] * b[0] - a[0] * b[2];
+  o[2] = a[0] * b[1] - a[1] * b[0];
+}
+__device__ __forceinline__ float dot(const float a[3], const float b[3]) {
+  return a[0] * b[0] + a[1] * b[1] + a[2] * b[2];
+}
+// rotation vector of conj(qa) * qb, short way round
+__device__ __forceinline__ void rel_rotvec(const float qa[4], const float qb[4], float phi[3]) {
+  float w = qa[0] * qb[0] + qa[1] * qb[1] + qa[2] * qb[2] + qa[3] * qb[3];
+  float x = qa[0] * qb[1] - qa[1] * qb[0] - qa[2] * qb[3] + qa[3] * qb[2];
+  float y = qa[0] * qb[2] + qa[1] * qb[3] - qa[2] * qb[0] - qa[3] * qb[1];
+  float z = qa[0] * qb[3] - qa[1] * qb[2] + qa[2] * qb[1] - qa[3] * qb[0];
+  if (w < 0.0f) { w = -w; x = -x; y = -y; z = -z; }
+  float s = sqrtf(x * x + y * y + z * z);
+  float k = (s < 1e-12f) ? 2.0f : 2.0f * atan2f(s, w) / s;
+  phi[0] = k * x; phi[1] = k * y; phi[2] = k * z;
+}
+
+// Height of the heightfield surface under a world xy (plane of the containing triangle).
+__device__ inline float terrain_height(const Model& M, const float* __restrict__ hts, float wx, float wy) {
+  if (M.terrain_kind == 0) return 0.0f;
+  float ux = (wx - M.hox) / M.cell, uy = (wy - M.hoy) / M.cell;
+  float fi = floorf(ux), fj = floorf(uy);
+  float mi = (float)(M.nx - 2), mj = (float)(M.ny - 2);
+  fi = fminf(fmaxf(fi, 0.0f), mi); fj = fminf(fmaxf(fj, 0.0f), mj);
+  int i = (int)fi, j = (int)fj;
+  float fx = fminf(fmaxf(ux - fi, 0.0f), 1.0f), fy = fminf(fmaxf(uy - fj, 0.0f), 1.0f);
+  float h00 = hts[j * M.nx + i], h10 = hts[j * M.nx + i + 1];
+  float h11 = hts[(j + 1) * M.nx + i + 1], h01 = hts[(j + 1) * M.nx + i];
+  if (fx >= fy) return h00 + fx * (h10 - h00) + fy * (h11 - h10);
+  return h00 + fx * (h11 - h01) + fy * (h01 - h00);
+}
+
+struct JointRows {
+  // positional rows along world x,y,z
+  float ra[3], rb[3];      // lever arms from each centre to the shared impulse point
+  float Ya[3][3], Yb[3][3];// angular response of parent / child per unit impulse
+  float sa, sb;            // linear response n_a/m_a, n_b/m_b
+  float pbias[3], pmeff[3];
+  // angular rows along the joint axes (sign folded in for upper limits)
+  float ax[3][3];
+  float Za[3][3], Zb[3][3];
+  float abias[3], ameff[3], lam[3];
+  int onesided;            // bit k set: row k is a limit row (impulse >= 0)
+};
+
+struct ContactRows {
+  float dir[3][3];   // n, t1, t2
+  float ang[3][3];   // rc x dir
+  float Y[3][3];     // angular response
+  float ls;          // linear response n_b / m
+  float meff[3], bias, lam[3];
+  int slot_e;        // slot * E + e
+  int body;
+};
+
+template <int KC>
+__global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
+  extern __shared__ float lds[];
+  const Model& M = *a.M;
+  const int B = M.B, J = M.J, S = M.S, D = M.D, F = M.F;
+  const int E = a.E, N = a.N;
+  const int tid = threadIdx.x;
+  const int e = tid % E, idx = tid / E;
+  const int env = blockIdx.x * E + e;
+  const bool env_ok = env < N;
+  const bool is_body = idx < B && env_ok;
+  const bool is_joint = idx < J && env_ok;
+  const int obs_dim = 11 + 3 * D + F;
+  const LdsPlan P = make_plan(B, J, S, D, F, E);
+  float* Lpos = lds + P.pos;
+  float* Lvel = lds + P.vel;
+  float* Liw = lds + P.iw;
+  float* Lnb = lds + P.nb;
+  float* Loutj = lds + P.outj;
+  float* Loutc = lds + P.outc;
+  float* Lrec = lds + P.rec;
+  int* Lreci = reinterpret_cast<int*>(lds + P.rec);
+  int* Llist = reinterpret_cast<int*>(lds + P.list);
+  float* Lu = lds + P.u;
+  float* Lobs = lds + P.obs;
+  int* Llim = reinterpret_cast<int*>(lds + P.lim);
+  int* Lcount = reinterpret_cast<int*>(lds + P.count);
+  const float h = a.h;
+
+  // ---- load: body state into registers, clipped actions into LDS
+  float x[3] = {0, 0, 0}, q[4] = {1, 0, 0, 0}, v[3] = {0, 0, 0}, w[3] = {0, 0, 0};
+  float inv_m = 0, Ib[3] = {1, 1, 1}, invIb[3] = {0, 0, 0};
+  int my_slot0 = 0, my_nslots = 0, my_njs = 0;
+  int my_js_off[kMaxBodyJoints], my_js_tq[kMaxBodyJoints];
+  float my_js_sign[kMaxBodyJoints];
+  const int b = idx;
+  if (is_body) {
+    const float* st = a.state + (size_t)b * N + env;
+    const size_t fs = (size_t)B * N;
+    x[0] = st[0 * fs]; x[1] = st[1 * fs]; x[2] = st[2 * fs];
+    q[0] = st[3 * fs]; q[1] = st[4 * fs]; q[2] = st[5 * fs]; q[3] = st[6 * fs];
+    v[0] = st[7 * fs]; v[1] = st[8 * fs]; v[2] = st[9 * fs];
+    w[0] = st[10 * fs]; w[1] = st[11 * fs]; w[2] = st[12 * fs];
+    const BodyTab& bt = M.bodies[b];
+    inv_m = bt.inv_mass;
+    for (int c = 0; c < 3; ++c) { Ib[c] = bt.inertia[c]; invIb[c] = bt.inv_inertia[c]; }
+    my_slot0 = bt.slot0; my_nslots = bt.n_slots; my_njs = bt.n_joint_sides;
+#pragma unroll
+    for (int k = 0; k < kMaxBodyJoints; ++k) {
+      int js = bt.joint_sides[k];
+      my_js_off[k] = ((js >> 1) * 12 + (js & 1) * 6) * E + e;   // LDS offset of that joint side's copy
+      my_js_tq[k] = (js >> 1) * 12 * E + e;                       // LDS offset of that joint's torque
+      my_js_sign[k] = (js & 1) ? 1.0f : -1.0f;
+    }
+  }
+  // uniform parameters and this thread's joint, read once
+  const float g0 = M.g[0], g1 = M.g[1], g2 = M.g[2];
+  const float p_mu = M.mu, p_margin = M.margin, p_beta_j = M.beta_j, p_beta_c = M.beta_c;
+  const float p_vdepen = M.v_depen, p_clin = M.c_lin, p_cang = M.c_ang, p_wmax = M.w_max;
+  const int p_gyro = M.gyro;
+  int j_pa = -1, j_pb = 0;
+  if (is_joint) { j_pa = M.joints[idx].parent; j_pb = M.joints[idx].child; }
+  for (int i = tid; i < E * D; i += kThreads) {
+    int ee = i / D, d = i - ee * D;
+    int env_i = blockIdx.x * E + ee;
+    float uu = 0.0f;
+    if (env_i < N && a.actions) uu = a.actions[(size_t)env_i * D + d];
+    Lu[d * E + ee] = fminf(fmaxf(uu, -1.0f), 1.0f);
+  }
+  float org[3] = {0, 0, 0};
+  if (env_ok) { org[0] = a.origins[3 * env]; org[1] = a.origins[3 * env + 1]; org[2] = a.origins[3 * env + 2]; }
+  // contact records start cleared (a step with zero substeps packs "no contact")
+  for (int i = tid; i < S * E; i += kThreads) {
+    Lreci[(i / E * kRecWords + 0) * E + i % E] = 0;
+    Lreci[(i / E * kRecWords + 1) * E + i % E] = -1;
+    Lreci[(i / E * kRecWords + 2) * E + i % E] = -1;
+    for (int c = 3; c < kRecWords; ++c) Lrec[(i / E * kRecWords + c) * E + i % E] = 0.0f;
+  }
+
+  float R[9];
+  JointRows jr;
+  ContactRows cr[KC];
+  int n_mine = 0;  // contacts owned by this thread this substep
+
+  for (int sub = 0; sub < a.substeps; ++sub) {
+    // ---- A: publish pose and world inverse inertia
+    if (tid == 0) Lcount[0] = 0;
+    if (is_body) {
+      for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
+      for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
+      quat_to_mat(q, R);
+      float iw[6];
+      iw[0] = R[0] * R[0] * invIb[0] + R[1] * R[1] * invIb[1] + R[2] * R[2] * invIb[2];
+      iw[1] = R[0] * R[3] * invIb[0] + R[1] * R[4] * invIb[1] + R[2] * R[5] * invIb[2];
+      iw[2] = R[0] * R[6] * invIb[0] + R[1] * R[7] * invIb[1] + R[2] * R[8] * invIb[2];
+      iw[3] = R[3] * R[3] * invIb[0] + R[4] * R[4] * invIb[1] + R[5] * R[5] * invIb[2];
+      iw[4] = R[3] * R[6] * invIb[0] + R[4] * R[7] * invIb[1] + R[5] * R[8] * invIb[2];
+      iw[5] = R[6] * R[6] * invIb[0] + R[7] * R[7] * invIb[1] + R[8] * R[8] * invIb[2];
+      for (int c = 0; c < 6; ++c) Liw[(b * 6 + c) * E + e] = iw[c];
+    }
+    __syncthreads();
+
+    // ---- B: joint torques (stored once per joint; the body applies the sign)
+    if (is_joint) {
+      const JointTab& jt = M.joints[idx];
+      float qa[4] = {1, 0, 0, 0};
+      if (jt.parent >= 0)
+        for (int c = 0; c < 4; ++c) qa[c] = Lpos[(jt.parent * 7 + 3 + c) * E + e];
+      float Ra[9];
+      quat_to_mat(qa, Ra);
+      float tq[3] = {0, 0, 0};
+      for (int k = 0; k < 3; ++k) {
+        if (jt.mode[k] != 1) continue;
+        float ak[3];
+        mat_vec(Ra, jt.axes[k], ak);
+        float t = jt.gear[k] * Lu[jt.act[k] * E + e];
+        tq[0] += t * ak[0]; tq[1] += t * ak[1]; tq[2] += t * ak[2];
+      }
+      for (int c = 0; c < 3; ++c) Loutj[(idx * 12 + c) * E + e] = tq[c];
+    }
+    // ---- B: contact generation, one slot at a time
+    for (int i = tid; i < S * E; i += kThreads) {
+      int ee = i % E, s = i / E;
+      int env_i = blockIdx.x * E + ee;
+      ContactOut co;
+      co.active = 0; co.kind = -1; co.feat = -1; co.d = 0.0f;
+      co.n = f3{0, 0, 0}; co.rc = f3{0, 0, 0}; co.w = 0.0f;
+      if (env_i < N) {
+        const SlotTab sl = M.slots[s];
+        float bx[3], bq[4], bo[3];
+        for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
+        for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
+        for (int c = 0; c < 3; ++c) bo[c] = a.origins[3 * env_i + c];
+        co = generate_contact(M, a.heights, bx, bq, sl.body, sl.kind, bo);
+      }
+      Lreci[(s * kRecWords + 0) * E + ee] = co.active;
+      Lreci[(s * kRecWords + 1) * E + ee] = co.kind;
+      Lreci[(s * kRecWords + 2) * E + ee] = co.feat;
+      Lrec[(s * kRecWords + 3) * E + ee] = co.d;
+      Lrec[(s * kRecWords + 4) * E + ee] = co.n.x;
+      Lrec[(s * kRecWords + 5) * E + ee] = co.n.y;
+      Lrec[(s * kRecWords + 6) * E + ee] = co.n.z;
+      Lrec[(s * kRecWords + 7) * E + ee] = co.rc.x;
+      Lrec[(s * kRecWords + 8) * E + ee] = co.rc.y;
+      Lrec[(s * kRecWords + 9) * E + ee] = co.rc.z;
+      Lrec[(s * kRecWords + 10) * E + ee] = co.w;
+      if (co.active) {
+        int pos = atomicAdd(&Lcount[0], 1);
+        Llist[pos] = i;
+      }
+    }
+    __syncthreads();
+
+    // ---- C: block count, forces -> velocities
+    float nbf = 0.0f;
+    if (is_body) {
+      nbf = (float)my_njs;
+      for (int k = 0; k < my_nslots; ++k) nbf += Lrec[((my_slot0 + k) * kRecWords + 10) * E + e];
+      Lnb[b * E + e] = nbf;
+      float tau[3] = {0, 0, 0};
+#pragma unroll
+      for (int k = 0; k < kMaxBodyJoints; ++k) {
+        if (k < my_njs)
+          for (int c = 0; c < 3; ++c) tau[c] += my_js_sign[k] * Loutj[my_js_tq[k] + c * E];
+      }
+      v[0] += h * g0; v[1] += h * g1; v[2] += h * g2;
+      float wb[3], tb[3];
+      mat_t_vec(R, w, wb);
+      mat_t_vec(R, tau, tb);
+      float Iw[3] = {Ib[0] * wb[0], Ib[1] * wb[1], Ib[2] * wb[2]};
+      float gy[3];
+      cross(wb, Iw, gy);
+      if (!p_gyro) { gy[0] = gy[1] = gy[2] = 0.0f; }
+      for (int c = 0; c < 3; ++c) wb[c] += h * (tb[c] - gy[c]) * invIb[c];
+      mat_vec(R, wb, w);
+      for (int c = 0; c < 3; ++c) { Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c]; }
+    }
+    if (a.recs && sub == a.substeps - 1) {
+      // export the records of the last substep, [N][S][12] words
+      for (int i = tid; i < S * E * kRecWords; i += kThreads) {
+        int wd = i % kRecWords, rest = i / kRecWords, s = rest % S, ee = rest / S;
+        int env_i = blockIdx.x * E + ee;
+        if (env_i < N) a.recs[((size_t)env_i * S + s) * kRecWords + wd] = Lreci[(s * kRecWords + wd) * E + ee];
+      }
+    }
+    __syncthreads();
+
+    // ---- D: row constants
+    const int n_active = Lcount[0];
+    if (is_joint) {
+      const JointTab& jt = M.joints[idx];
+      const int pa = j_pa, pb = j_pb;
+      float xa[3] = {0, 0, 0}, qa[4] = {1, 0, 0, 0}, xb[3], qb[4];
+      float iwa[6] = {0, 0, 0, 0, 0, 0}, iwb[6], na = 0.0f, ima = 0.0f;
+      if (pa >= 0) {
+        for (int c = 0; c < 3; ++c) xa[c] = Lpos[(pa * 7 + c) * E + e];
+        for (int c = 0; c < 4; ++c) qa[c] = Lpos[(pa * 7 + 3 + c) * E + e];
+        for (int c = 0; c < 6; ++c) iwa[c] = Liw[(pa * 6 + c) * E + e];
+        na = Lnb[pa * E + e];
+        ima = M.bodies[pa].inv_mass;
+      }
+      for (int c = 0; c < 3; ++c) xb[c] = Lpos[(pb * 7 + c) * E + e];
+      for (int c = 0; c < 4; ++c) qb[c] = Lpos[(pb * 7 + 3 + c) * E + e];
+      for (int c = 0; c < 6; ++c) iwb[c] = Liw[(pb * 6 + c) * E + e];
+      const float nbb = Lnb[pb * E + e], imb = M.bodies[pb].inv_mass;
+      float Ra[9], Rb[9], t0[3], t1[3];
+      quat_to_mat(qa, Ra);
+      quat_to_mat(qb, Rb);
+      mat_vec(Ra, jt.la, t0);
+      mat_vec(Rb, jt.lb, t1);
+      float C[3];
+      for (int c = 0; c < 3; ++c) {
+        float pa_c = xa[c] + t0[c], pb_c = xb[c] + t1[c];
+        C[c] = pb_c - pa_c;
+        float mid = 0.5f * (pa_c + pb_c);
+        jr.ra[c] = mid - xa[c];
+        jr.rb[c] = mid - xb[c];
+      }
+      jr.sa = na * ima; jr.sb = nbb * imb;
+      const float bh = p_beta_j / h;
+      for (int k = 0; k < 3; ++k) {
+        float ex[3] = {k == 0 ? 1.0f : 0.0f, k == 1 ? 1.0f : 0.0f, k == 2 ? 1.0f : 0.0f};
+        float ca[3], cb[3], ya[3], yb[3];
+        cross(jr.ra, ex, ca);
+        cross(jr.rb, ex, cb);
+        sym_vec(iwa, ca, ya);
+        sym_vec(iwb, cb, yb);
+        float keff = na * (ima + dot(ca, ya)) + nbb * (imb + dot(cb, yb));
+        jr.pmeff[k] = keff > 0.0f ? 1.0f / keff : 0.0f;
+        jr.pbias[k] = bh * C[k];
+        for (int c = 0; c < 3; ++c) { jr.Ya[k][c] = -na * ya[c]; jr.Yb[k][c] = nbb * yb[c]; }
+      }
+      float phi[3];
+      rel_rotvec(qa, qb, phi);
+      jr.onesided = 0;
+      for (int k = 0; k < 3; ++k) {
+        float ak[3], za[3], zb[3];
+        mat_vec(Ra, jt.axes[k], ak);
+        float th = dot(jt.axes[k], phi);
+        float sgn = 1.0f, bias;
+        if (jt.mode[k] == 0) {
+          bias = bh * th;
+        } else {
+          float glo = th - jt.lo[k], ghi = jt.hi[k] - th, g;
+          if (glo < ghi) { g = glo; } else { g = ghi; sgn = -1.0f; }
+          bias = g >= 0.0f ? g / h : bh * g;
+          jr.onesided |= 1 << k;
+        }
+        for (int c = 0; c < 3; ++c) ak[c] *= sgn;
+        sym_vec(iwa, ak, za);
+        sym_vec(iwb, ak, zb);
+        float keff = na * dot(ak, za) + nbb * dot(ak, zb);
+        jr.ameff[k] = keff > 0.0f ? 1.0f / keff : 0.0f;
+        jr.abias[k] = bias;
+        jr.lam[k] = 0.0f;
+        for (int c = 0; c < 3; ++c) { jr.ax[k][c] = ak[c]; jr.Za[k][c] = -na * za[c]; jr.Zb[k][c] = nbb * zb[c]; }
+      }
+    }
+    n_mine = 0;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      int li = tid + kc * kThreads;
+      if (li < n_active) {
+        ContactRows& c = cr[kc];
+        int i = Llist[li];
+        int ee = i % E, s = i / E;
+        int body = M.slots[s].body;
+        c.slot_e = s * E + ee;
+        c.body = body;
+        float d = Lrec[(s * kRecWords + 3) * E + ee];
+        float n[3], rc[3], iwb[6];
+        for (int k = 0; k < 3; ++k) { n[k] = Lrec[(s * kRecWords + 4 + k) * E + ee]; rc[k] = Lrec[(s * kRecWords + 7 + k) * E + ee]; }
+        for (int k = 0; k < 6; ++k) iwb[k] = Liw[(body * 6 + k) * E + ee];
+        float nbb = Lnb[body * E + ee] / Lrec[(s * kRecWords + 10) * E + ee], imb = M.bodies[body].inv_mass;
+        float t1[3], t2[3];
+        if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
+        else { t1[0] = -n[2]; t1[1] = 0.0f; t1[2] = n[0]; }
+        float inv = 1.0f / sqrtf(dot(t1, t1));
+        for (int k = 0; k < 3; ++k) t1[k] *= inv;
+        cross(n, t1, t2);
+        for (int k = 0; k < 3; ++k) { c.dir[0][k] = n[k]; c.dir[1][k] = t1[k]; c.dir[2][k] = t2[k]; }
+        c.ls = nbb * imb;
+        for (int r = 0; r < 3; ++r) {
+          float y[3];
+          cross(rc, c.dir[r], c.ang[r]);
+          sym_vec(iwb, c.ang[r], y);
+          float keff = nbb * (imb + dot(c.ang[r], y));
+          c.meff[r] = keff > 0.0f ? 1.0f / keff : 0.0f;
+          for (int k = 0; k < 3; ++k) c.Y[r][k] = nbb * y[k];
+          c.lam[r] = 0.0f;
+        }
+        c.bias = d >= 0.0f ? d / h : fmaxf(p_beta_c * d / h, -p_vdepen);
+        n_mine = kc + 1;
+      }
+    }
+
+    // ---- S: sweeps
+    for (int it = 0; it < a.iterations; ++it) {
+      if (is_joint) {
+        const int pa = j_pa, pb = j_pb;
+        float va[3] = {0, 0, 0}, wa[3] = {0, 0, 0}, vb[3], wb[3];
+        if (pa >= 0)
+          for (int c = 0; c < 3; ++c) { va[c] = Lvel[(pa * 6 + c) * E + e]; wa[c] = Lvel[(pa * 6 + 3 + c) * E + e]; }
+        for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * 6 + c) * E + e]; wb[c] = Lvel[(pb * 6 + 3 + c) * E + e]; }
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          float ex[3] = {k == 0 ? 1.0f : 0.0f, k == 1 ? 1.0f : 0.0f, k == 2 ? 1.0f : 0.0f};
+          float ca[3], cb[3];
+          cross(jr.ra, ex, ca);
+          cross(jr.rb, ex, cb);
+          float jv = (vb[k] - va[k]) + dot(cb, wb) - dot(ca, wa);
+          float dl = -jr.pmeff[k] * (jv + jr.pbias[k]);
+          va[k] -= jr.sa * dl;
+          vb[k] += jr.sb * dl;
+          for (int c = 0; c < 3; ++c) { wa[c] += jr.Ya[k][c] * dl; wb[c] += jr.Yb[k][c] * dl; }
+        }
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          float dw[3] = {wb[0] - wa[0], wb[1] - wa[1], wb[2] - wa[2]};
+          float jv = dot(jr.ax[k], dw);
+          float dl = -jr.ameff[k] * (jv + jr.abias[k]);
+          if (jr.onesided & (1 << k)) {
+            float ln = fmaxf(jr.lam[k] + dl, 0.0f);
+            dl = ln - jr.lam[k];
+            jr.lam[k] = ln;
+          }
+          for (int c = 0; c < 3; ++c) { wa[c] += jr.Za[k][c] * dl; wb[c] += jr.Zb[k][c] * dl; }
+        }
+        for (int c = 0; c < 3; ++c) {
+          Loutj[(idx * 12 + c) * E + e] = va[c];
+          Loutj[(idx * 12 + 3 + c) * E + e] = wa[c];
+          Loutj[(idx * 12 + 6 + c) * E + e] = vb[c];
+          Loutj[(idx * 12 + 9 + c) * E + e] = wb[c];
+        }
+      }
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        if (kc < n_mine) {
+          ContactRows& c = cr[kc];
+          int ee = c.slot_e % E;
+          float vv[3], ww[3];
+          for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(c.body * 6 + k) * E + ee]; ww[k] = Lvel[(c.body * 6 + 3 + k) * E + ee]; }
+          {
+            float jv = dot(c.dir[0], vv) + dot(c.ang[0], ww);
+            float dl = -c.meff[0] * (jv + c.bias);
+            float ln = fmaxf(c.lam[0] + dl, 0.0f);
+            dl = ln - c.lam[0];
+            c.lam[0] = ln;
+            for (int k = 0; k < 3; ++k) { vv[k] += c.ls * c.dir[0][k] * dl; ww[k] += c.Y[0][k] * dl; }
+          }
+          {
+            float jv1 = dot(c.dir[1], vv) + dot(c.ang[1], ww);
+            float jv2 = dot(c.dir[2], vv) + dot(c.ang[2], ww);
+            float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
+            float lim = p_mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
+            if (nrm > lim) { float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
+            float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
+            c.lam[1] = l1; c.lam[2] = l2;
+            for (int k = 0; k < 3; ++k) {
+              vv[k] += c.ls * (c.dir[1][k] * d1 + c.dir[2][k] * d2);
+              ww[k] += c.Y[1][k] * d1 + c.Y[2][k] * d2;
+            }
+          }
+          int s = c.slot_e / E;
+          for (int k = 0; k < 3; ++k) { Loutc[(s * 6 + k) * E + ee] = vv[k]; Loutc[(s * 6 + 3 + k) * E + ee] = ww[k]; }
+        }
+      }
+      __syncthreads();
+      // every body averages the private copies of its blocks (static order)
+      if (is_body && nbf > 0.0f) {
+        float acc[6] = {0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < kMaxBodyJoints; ++k) {
+          if (k < my_njs)
+            for (int c = 0; c < 6; ++c) acc[c] += Loutj[my_js_off[k] + c * E];
+        }
+        for (int k = 0; k < my_nslots; ++k) {
+          int s = my_slot0 + k;
+          float wk = Lrec[(s * kRecWords + 10) * E + e];
+          if (wk > 0.0f)
+            for (int c = 0; c < 6; ++c) acc[c] += wk * Loutc[(s * 6 + c) * E + e];
+        }
+        float inb = 1.0f / nbf;
+        for (int c = 0; c < 3; ++c) {
+          v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
+          Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c];
+        }
+      }
+      __syncthreads();
+    }
+
+    // ---- E: damping, angular-velocity cap, positions
+    if (is_body) {
+      float dl = 1.0f / (1.0f + h * p_clin), da = 1.0f / (1.0f + h * p_cang);
+      for (int c = 0; c < 3; ++c) { v[c] *= dl; w[c] *= da; }
+      float wn = sqrtf(dot(w, w));
+      if (wn > p_wmax) { float sc = p_wmax / wn; for (int c = 0; c < 3; ++c) w[c] *= sc; }
+      for (int c = 0; c < 3; ++c) x[c] += h * v[c];
+      float dq[4];
+      dq[0] = -w[0] * q[1] - w[1] * q[2] - w[2] * q[3];
+      dq[1] = w[0] * q[0] + w[1] * q[3] - w[2] * q[2];
+      dq[2] = -w[0] * q[3] + w[1] * q[0] + w[2] * q[1];
+      dq[3] = w[0] * q[2] - w[1] * q[1] + w[2] * q[0];
+      float hh = 0.5f * h;
+      for (int c = 0; c < 4; ++c) q[c] += hh * dq[c];
+      float inv = 1.0f / sqrtf(q[0] * q[0] + q[1] * q[1] + q[2] * q[2] + q[3] * q[3]);
+      for (int c = 0; c < 4; ++c) q[c] *= inv;
+    }
+    __syncthreads();  // the next substep overwrites pose, counters and lists read above
+  }
+
+  // ---- store state, publish final pose/velocity for packing
+  __syncthreads();
+  if (is_body) {
+    float* st = a.state + (size_t)b * N + env;
+    const size_t fs = (size_t)B * N;
+    if (a.substeps > 0) {
+      st[0 * fs] = x[0]; st[1 * fs] = x[1]; st[2 * fs] = x[2];
+      st[3 * fs] = q[0]; st[4 * fs] = q[1]; st[5 * fs] = q[2]; st[6 * fs] = q[3];
+      st[7 * fs] = v[0]; st[8 * fs] = v[1]; st[9 * fs] = v[2];
+      st[10 * fs] = w[0]; st[11 * fs] = w[1]; st[12 * fs] = w[2];
+    }
+    for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
+    for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
+    for (int c = 0; c < 3; ++c) { Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c]; }
+  }
+  __syncthreads();
+
+  // ---- observation vector (Table 2 "Ours"), per joint part
+  if (is_joint) {
+    const JointTab& jt = M.joints[idx];
+    const int pa = jt.parent, pb = jt.child;
+    float qa[4] = {1, 0, 0, 0}, wa[3] = {0, 0, 0}, qb[4], wb[3];
+    if (pa >= 0) {
+      for (int c = 0; c < 4; ++c) qa[c] = Lpos[(pa * 7 + 3 + c) * E + e];
+      for (int c = 0; c < 3; ++c) wa[c] = Lvel[(pa * 6 + 3 + c) * E + e];
+    }
+    for (int c = 0; c < 4; ++c) qb[c] = Lpos[(pb * 7 + 3 + c) * E + e];
+    for (int c = 0; c < 3; ++c) wb[c] = Lvel[(pb * 6 + 3 + c) * E + e];
+    float Ra[9], phi[3];
+    quat_to_mat(qa, Ra);
+    rel_rotvec(qa, qb, phi);
+    float dw[3] = {wb[0] - wa[0], wb[1] - wa[1], wb[2] - wa[2]};
+    for (int k = 0; k < 3; ++k) {
+      if (jt.mode[k] != 1) continue;
+      int ai = jt.act[k];
+      float ak[3];
+      mat_vec(Ra, jt.axes[k], ak);
+      float th = dot(jt.axes[k], phi);
+      Lobs[e * obs_dim + 11 + ai] = th;
+      Lobs[e * obs_dim + 11 + D + ai] = dot(ak, dw);
+      Lobs[e * obs_dim + 11 + 2 * D + ai] = Lu[ai * E + e];
+      float g = fminf(th - jt.lo[k], jt.hi[k] - th);
+      Llim[ai * E + e] = g <= 0.0f ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  // ---- root part, reward (Eq. 1-3), done (Section 4.1)
+  if (tid < E && (blockIdx.x * E + tid) < N) {
+    const int ee = tid, env_e = blockIdx.x * E + tid;
+    const int rb = M.root;
+    float rx[3], rq[4], rv[3], rw[3];
+    for (int c = 0; c < 3; ++c) rx[c] = Lpos[(rb * 7 + c) * E + ee];
+    for (int c = 0; c < 4; ++c) rq[c] = Lpos[(rb * 7 + 3 + c) * E + ee];
+    for (int c = 0; c < 3; ++c) { rv[c] = Lvel[(rb * 6 + c) * E + ee]; rw[c] = Lvel[(rb * 6 + 3 + c) * E + ee]; }
+    float ox = a.origins[3 * env_e], oy = a.origins[3 * env_e + 1], oz = a.origins[3 * env_e + 2];
+    float height = rx[2];
+    if (M.terrain_kind == 1) height = rx[2] + oz - terrain_height(M, a.heights, rx[0] + ox, rx[1] + oy);
+    float qw = rq[0], qx = rq[1], qy = rq[2], qz = rq[3];
+    float roll = atan2f(2.0f * (qw * qx + qy * qz), 1.0f - 2.0f * (qx * qx + qy * qy));
+    float sp = fminf(fmaxf(2.0f * (qw * qy - qz * qx), -1.0f), 1.0f);
+    float pitch = asinf(sp);
+    float yaw = atan2f(2.0f * (qw * qz + qx * qy), 1.0f - 2.0f * (qy * qy + qz * qz));
+    float tx = a.targets[2 * env_e] - rx[0], ty = a.targets[2 * env_e + 1] - rx[1];
+    float psi = atan2f(ty, tx) - yaw;
+    float sps = sinf(psi), cps = cosf(psi);
+    float* o = Lobs + ee * obs_dim;
+    o[0] = height; o[1] = roll; o[2] = pitch;
+    o[3] = rv[0]; o[4] = rv[1]; o[5] = rv[2];
+    o[6] = rw[0]; o[7] = rw[1]; o[8] = rw[2];
+    o[9] = sps; o[10] = cps;
+    int n_feet = 0;
+    for (int f = 0; f < F; ++f) {
+      const BodyTab& bt = M.bodies[M.feet[f]];
+      int flag = 0;
+      for (int k = 0; k < bt.n_slots; ++k) {
+        int s = bt.slot0 + k;
+        if (Lreci[(s * kRecWords + 0) * E + ee] && Lrec[(s * kRecWords + 3) * E + ee] <= 0.005f) flag = 1;
+      }
+      o[11 + 3 * D + f] = (float)flag;
+      n_feet += flag;
+    }
+    float l1 = 0.0f, l2 = 0.0f;
+    int n_lim = 0;
+    for (int d = 0; d < D; ++d) {
+      float uu = Lu[d * E + ee];
+      l1 += fabsf(uu); l2 += uu * uu;
+      n_lim += Llim[d * E + ee];
+    }
+    float tn = sqrtf(tx * tx + ty * ty);
+    float speed = tn > 0.0f ? (rv[0] * tx + rv[1] * ty) / tn : 0.0f;
+    float r_head = cps > 0.8f ? 1.0f : cps / 0.8f;
+    float cvert = 1.0f - 2.0f * (qx * qx + qy * qy);
+    float r_stand = cvert > 0.93f ? 1.0f : 0.0f;
+    int steps = a.steps[env_e] + (a.count_step ? 1 : 0);
+    a.steps[env_e] = steps;
+    a.reward[env_e] = M.alive_bonus + speed + 0.5f * r_head + 0.05f * r_stand - 4.0f * l1 - 0.5f * l2 -
+                      0.2f * (float)n_lim - (float)n_feet;
+    a.done[env_e] = (height < M.term_height || steps >= M.max_steps) ? 1 : 0;
+  }
+  __syncthreads();
+  {
+    const int env0 = blockIdx.x * E;
+    const int n_here = min(E, N - env0);
+    for (int i = tid; i < n_here * obs_dim; i += kThreads) a.obs[(size_t)env0 * obs_dim + i] = Lobs[i];
+  }
+}
+
+}  // namespace sim355

@@ -50,7 +50,7 @@ def env_grid_origins(num_envs, spacing=5.0):
     return o
 
 
-def env_field_origins(terrain, num_envs, seed, border=2.0, clear_radius=0.5):
+def env_field_origins(terrain, num_envs, seed, border=4.0, clear_radius=0.5):
     """Seeded uniform xy positions inside the heightfield (all envs share it and
     never interact); z is the highest sample within `clear_radius`."""
     rng = np.random.Generator(np.random.Philox(key=int(seed) + 77))
