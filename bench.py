@@ -1,0 +1,172 @@
+"""Benchmark: env-steps/s of the whole hot path on one MI355X.
+
+A step is one sim_step (all substeps: contact generation, force integration,
+block projected-Jacobi sweeps, position integration, obs/reward/done packing)
+followed by sim_get_obs into caller tensors, on the 4096-humanoid heightfield
+workload (configuration 3).  Inputs are seeded and synthetic and already
+resident in HBM when the timed region starts.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+# ---- algorithmic work per env-step (model stated in the design doc, FMA = 2 flops) ----
+F_JOINT_SWEEP = 156.0     # 3 positional rows x 27 + 3 angular rows x 25
+F_CONTACT_SWEEP = 95.0    # normal row 29 + friction pair 66
+F_JOINT_SETUP = 420.0     # two rotation matrices, anchors, 6 effective masses and responses, joint angles
+F_CONTACT_SETUP = 150.0
+F_BODY_SUBSTEP = 240.0    # rotation + world inverse inertia, force/gyroscopic integration, pose integration
+F_SLOT_REJECT = 30.0      # end points + reach test of a slot that is nowhere near the ground
+F_SLOT_NARROW = 2000.0    # ~12 cells x 2 triangles (or 3 edges) x ~85 flops for a slot near the ground
+
+
+def flops_per_env_step(B, J, S, substeps, iterations, active, blocks_per_body):
+    sweep = J * F_JOINT_SWEEP + active * F_CONTACT_SWEEP + B * (6.0 * blocks_per_body + 6.0)
+    setup = (J * F_JOINT_SETUP + active * F_CONTACT_SETUP + B * F_BODY_SUBSTEP
+             + S * F_SLOT_REJECT + active * F_SLOT_NARROW)
+    return substeps * (iterations * sweep + setup)
+
+
+def bytes_per_env_step(B, J, S, D, obs_dim, substeps, iterations, active):
+    """HBM byte accountings: A compulsory (state in+out, actions, obs, reward, done);
+    B state and slot records streamed once per substep; C every sweep streams velocities
+    and rows (what an unfused, one-kernel-per-sweep engine would move)."""
+    state = B * 13 * 4
+    a = 2 * state + D * 4 + obs_dim * 4 + 5
+    b = substeps * (2 * state + S * 40) + D * 4 + obs_dim * 4 + 5
+    rows = 6 * J + 3 * active
+    c = substeps * iterations * (2 * B * 6 * 4 + rows * 52) + a
+    return a, b, c
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload configuration (3 = headline)")
+    ap.add_argument("--envs-per-block", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (envs would be sharded across GPUs with no "
+              "exchange inside a step); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import scenes
+    import paper_1810_05762_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    scene, cfg = scenes.config_scene(args.config)
+    N, rob = scene.num_envs, scene.robot
+    sim = P.Sim(scene, device=dev)
+    if args.envs_per_block:
+        sim.set_envs_per_block(args.envs_per_block)
+    if cfg["fallen"]:
+        sim.set_state(scenes.fallen_states(scene, cfg["seed"]))
+    else:
+        sim.reset(cfg["seed"])
+    dt, sub, its = float(np.float32(cfg["dt"])), cfg["substeps"], cfg["iterations"]
+    ring = [torch.as_tensor(scenes.actions_for_step(cfg["seed"], s, N, rob.n_dofs)).to(dev) for s in range(16)]
+    obs = torch.empty(N, sim.obs_dim, dtype=torch.float32, device=dev)
+    rew = torch.empty(N, dtype=torch.float32, device=dev)
+    done = torch.empty(N, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    def one_step(k):
+        P.sim_step(sim.h, ring[k % 16].data_ptr(), dt, sub, its, stream)
+        P.sim_get_obs(sim.h, obs.data_ptr(), rew.data_ptr(), done.data_ptr(), stream)
+
+    settle = 60          # robots are dropped from their reset height; let them land first (untimed)
+    for k in range(settle + args.warmup):
+        one_step(k)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(settle + args.warmup + k)
+    torch.cuda.synchronize(dev)
+    elapsed = time.perf_counter() - t0
+    sim.check()
+
+    # dominant kernel: the fused step kernel, timed per launch with events on its stream
+    n_ev = min(args.steps, 200)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for k, (e0, e1) in enumerate(evs):
+        e0.record()
+        P.sim_step(sim.h, ring[k % 16].data_ptr(), dt, sub, its, stream)
+        e1.record()
+    torch.cuda.synchronize(dev)
+    kern_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    con = sim.generate_contacts()
+    active = float(con["active"].sum()) / N
+    blocks_per_body = (2.0 * rob.n_joints + active) / rob.n_bodies
+
+    fl = flops_per_env_step(rob.n_bodies, rob.n_joints, sim.S, sub, its, active, blocks_per_body)
+    bA, bB, bC = bytes_per_env_step(rob.n_bodies, rob.n_joints, sim.S, rob.n_dofs, sim.obs_dim, sub, its, active)
+    achieved_tflops = fl * N / (kern_ms * 1e-3) / 1e12
+    peak_tflops = 157.3
+    value = N * args.steps / elapsed
+    out = {
+        "metric": "env-steps/sec on 1 MI355X (4096 humanoids, heightfield); HBM roofline fraction",
+        "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg["name"], "num_envs": N, "robot": rob.name, "bodies": rob.n_bodies,
+                   "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
+                   "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
+                   "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
+                   "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 2},
+        "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,
+                     "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": None,
+                     "flops_per_env_step": fl, "kernel_ms": kern_ms},
+        "hbm_roofline": {
+            "peak_GBps": 8000.0, "kernel_ms": kern_ms,
+            "A_compulsory": {"bytes_per_env_step": bA, "GBps": bA * N / (kern_ms * 1e-3) / 1e9,
+                             "frac": bA * N / (kern_ms * 1e-3) / 8e12},
+            "B_per_substep": {"bytes_per_env_step": bB, "GBps": bB * N / (kern_ms * 1e-3) / 1e9,
+                              "frac": bB * N / (kern_ms * 1e-3) / 8e12},
+            "C_streaming_jacobi": {"bytes_per_env_step": bC, "GBps": bC * N / (kern_ms * 1e-3) / 1e9,
+                                   "frac": bC * N / (kern_ms * 1e-3) / 8e12},
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s = min(N, 256)
+        sub_scene, _ = scenes.config_scene(args.config, num_envs=n_s)
+        sub_scene.env_origins = scene.env_origins[:n_s].copy()
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+        cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+        ref = oracle.OracleSim(sub_scene, threads=cores)
+        ref.set_state(sim.get_state().cpu().numpy()[:n_s].astype(np.float64))
+        acts = [ring[k].cpu().numpy()[:n_s] for k in range(16)]
+        ref.step(acts[0], dt, sub, its)
+        t0 = time.perf_counter()
+        n_steps = 0
+        while True:
+            ref.step(acts[n_steps % 16], dt, sub, its)
+            n_steps += 1
+            el = time.perf_counter() - t0
+            if el > 12.0 or n_steps >= 400:
+                break
+        out["cpu_baseline"] = {"value": n_s * n_steps / el, "unit": "env-steps/s", "cores": cores, "kind": "oracle",
+                               "sample": f"{n_s} envs x {n_steps} steps of the same workload "
+                                         f"(plain fp64 C oracle, OpenMP over envs)"}
+    sim.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

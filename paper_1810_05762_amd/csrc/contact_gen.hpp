@@ -12,8 +12,10 @@
 //   dot(a,b)   = (a.x*b.x + a.y*b.y) + a.z*b.z
 //   cross(a,b) = (a.y*b.z - a.z*b.y, a.z*b.x - a.x*b.z, a.x*b.y - a.y*b.x)
 //   vertex(i,j) = (ox + float(i)*cell, oy + float(j)*cell, h[j][i])
-// Triangles that cannot reach the margin are skipped with a conservative test
-// (1 mm slack), which never changes the outcome.
+// The nearest feature is the lexicographic minimum of (squared distance, id)
+// over all admissible features, so candidates may be visited in any order and
+// by any number of lanes.  Features that cannot reach the margin are skipped
+// with conservative height tests (1 mm slack), which never changes the outcome.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -26,7 +28,6 @@ namespace sim355 {
 struct f3 {
   float x, y, z;
 };
-__device__ __forceinline__ f3 mk3(float x, float y, float z) { return f3{x, y, z}; }
 __device__ __forceinline__ f3 sub3(f3 a, f3 b) { return f3{a.x - b.x, a.y - b.y, a.z - b.z}; }
 __device__ __forceinline__ float dot3(f3 a, f3 b) {
   float s = a.x * b.x;
@@ -42,15 +43,31 @@ __device__ __forceinline__ f3 cross3(f3 a, f3 b) {
   return f3{x0 - x1, y0 - y1, z0 - z1};
 }
 
+typedef __attribute__((address_space(3))) float lds_float;  // LDS-resident data
+
 struct Field {
   int nx, ny;
   float cell, inv_cell, ox, oy;
   const float* __restrict__ h;
+  const float* __restrict__ coarse;  // max height over blocks of kCoarse x kCoarse cells
+  int cnx;
+  // optional copy of the samples [pi0, pi0+ps) x [pj0, pj0+ps) in LDS (ps = 0: none), and the
+  // maxima of its blocks of kMip x kMip cells: block (I,J) covers samples [4I,4I+4] x [4J,4J+4]
+  const lds_float* patch;
+  const lds_float* mip;
+  int pi0, pj0, ps;
 };
+constexpr int kMip = 4;
+
+__device__ __forceinline__ float field_height(const Field& H, int i, int j) {
+  unsigned di = (unsigned)(i - H.pi0), dj = (unsigned)(j - H.pj0);
+  if (di < (unsigned)H.ps && dj < (unsigned)H.ps) return H.patch[dj * H.ps + di];
+  return H.h[j * H.nx + i];
+}
 
 __device__ __forceinline__ f3 field_vertex(const Field& H, int i, int j) {
   float fx = (float)i * H.cell, fy = (float)j * H.cell;
-  return f3{H.ox + fx, H.oy + fy, H.h[j * H.nx + i]};
+  return f3{H.ox + fx, H.oy + fy, field_height(H, i, j)};
 }
 
 // Barycentric coordinates (v,w) of the point of triangle A,B,C closest to P,
@@ -107,6 +124,13 @@ struct ContactOut {
   float w;  // share of the body this block gets in the mass splitting
 };
 
+__device__ __forceinline__ ContactOut no_contact() {
+  ContactOut o;
+  o.active = 0; o.kind = -1; o.feat = -1; o.d = 0.0f;
+  o.n = f3{0.0f, 0.0f, 0.0f}; o.rc = f3{0.0f, 0.0f, 0.0f}; o.w = 0.0f;
+  return o;
+}
+
 // 0 at the margin, 1 from half the margin down, times the fade of the mid-segment slot
 __device__ __forceinline__ float block_weight(float margin, float d, float ramp_s) {
   float w = margin > 0.0f ? fminf((margin - d) / (0.5f * margin), 1.0f) : 1.0f;
@@ -161,184 +185,273 @@ __device__ __forceinline__ void body_ends(const float x[3], const float q[4], fl
   p1 = f3{x[0] + a.x, x[1] + a.y, x[2] + a.z};
 }
 
-// One slot: body pose (x,q env-local), slot kind, env origin -> contact record.
-__device__ inline ContactOut generate_contact(const Model& M, const float* __restrict__ heights,
-                                              const float x[3], const float q[4], int body, int slot_kind,
+// Everything a slot needs to be tested against the terrain.
+struct SlotGeom {
+  f3 xc;          // body centre, env-local
+  f3 p0, p1;      // segment end points, env-local
+  f3 P0, P1;      // the same in world coordinates (env origin added)
+  f3 org;
+  float r, Rq;    // radius, reach = r + margin + slack
+  int kind;       // 0 end -, 1 end +, 2 mid-segment
+  int i0, i1, j0, j1;  // cells the reach box overlaps
+};
+
+__device__ __forceinline__ SlotGeom slot_geom(float radius, float half_len, int axis, float margin,
+                                              const float x[3], const float q[4], int slot_kind,
                                               const float origin[3]) {
-  ContactOut out;
-  out.active = 0; out.kind = -1; out.feat = -1; out.d = 0.0f;
-  out.n = f3{0.0f, 0.0f, 0.0f}; out.rc = f3{0.0f, 0.0f, 0.0f}; out.w = 0.0f;
-  if (!M.contacts) return out;
-  const float r = M.bodies[body].radius;
-  const float margin = M.margin;
-  f3 p0, p1;
-  body_ends(x, q, M.bodies[body].half_len, M.bodies[body].axis, p0, p1);
-  f3 xc = f3{x[0], x[1], x[2]};
+  SlotGeom g;
+  g.kind = slot_kind;
+  g.r = radius;
+  g.Rq = (g.r + margin) + kSelSlack;
+  body_ends(x, q, half_len, axis, g.p0, g.p1);
+  g.xc = f3{x[0], x[1], x[2]};
+  g.org = f3{origin[0], origin[1], origin[2]};
+  g.P0 = f3{g.p0.x + g.org.x, g.p0.y + g.org.y, g.p0.z + g.org.z};
+  g.P1 = f3{g.p1.x + g.org.x, g.p1.y + g.org.y, g.p1.z + g.org.z};
+  g.i0 = 0; g.i1 = -1; g.j0 = 0; g.j1 = -1;
+  return g;
+}
 
-  if (M.terrain_kind == 0) {
-    if (slot_kind == 2) return out;
-    f3 p = slot_kind == 0 ? p0 : p1;
-    float d = p.z - r;
-    if (!(d < margin)) return out;
-    out.active = 1; out.kind = 0; out.feat = -1; out.d = d;
-    out.n = f3{0.0f, 0.0f, 1.0f};
-    out.rc = f3{p.x - xc.x, p.y - xc.y, (p.z - r) - xc.z};
-    out.w = block_weight(margin, d, 1.0f);
-    return out;
-  }
+__device__ __forceinline__ ContactOut plane_contact(const SlotGeom& g, float margin) {
+  ContactOut out = no_contact();
+  if (g.kind == 2) return out;
+  f3 p = g.kind == 0 ? g.p0 : g.p1;
+  float d = p.z - g.r;
+  if (!(d < margin)) return out;
+  out.active = 1; out.kind = 0; out.feat = -1; out.d = d;
+  out.n = f3{0.0f, 0.0f, 1.0f};
+  out.rc = f3{p.x - g.xc.x, p.y - g.xc.y, (p.z - g.r) - g.xc.z};
+  out.w = block_weight(margin, d, 1.0f);
+  return out;
+}
 
-  Field H{M.nx, M.ny, M.cell, M.inv_cell, M.hox, M.hoy, heights};
+// Cells overlapped by the reach box only (no height test).
+__device__ __forceinline__ bool slot_range(const Field& H, SlotGeom& g) {
   const int ncx = H.nx - 1, ncy = H.ny - 1;
-  f3 org = f3{origin[0], origin[1], origin[2]};
-  f3 P0 = f3{p0.x + org.x, p0.y + org.y, p0.z + org.z};
-  f3 P1 = f3{p1.x + org.x, p1.y + org.y, p1.z + org.z};
-  const float Rq = (r + margin) + kSelSlack;
+  float xl, xh, yl, yh;
+  if (g.kind < 2) {
+    f3 P = g.kind == 0 ? g.P0 : g.P1;
+    xl = xh = P.x; yl = yh = P.y;
+  } else {
+    xl = g.P0.x < g.P1.x ? g.P0.x : g.P1.x; xh = g.P0.x < g.P1.x ? g.P1.x : g.P0.x;
+    yl = g.P0.y < g.P1.y ? g.P0.y : g.P1.y; yh = g.P0.y < g.P1.y ? g.P1.y : g.P0.y;
+  }
+  if (!cell_span(H, xl - g.Rq, xh + g.Rq, H.ox, ncx, g.i0, g.i1)) return false;
+  return cell_span(H, yl - g.Rq, yh + g.Rq, H.oy, ncy, g.j0, g.j1);
+}
 
-  if (slot_kind < 2) {
-    f3 P = slot_kind == 0 ? P0 : P1;
-    f3 pl = slot_kind == 0 ? p0 : p1;
-    // centre underneath the surface: triangle containing its xy, plane distance
-    {
-      float ux = (P.x - H.ox) * H.inv_cell, uy = (P.y - H.oy) * H.inv_cell;
-      float fi = floorf(ux), fj = floorf(uy);
-      if (fi >= 0.0f && fi <= (float)(ncx - 1) && fj >= 0.0f && fj <= (float)(ncy - 1)) {
-        int i = (int)fi, j = (int)fj;
-        float fx = ux - fi, fy = uy - fj;
-        int t = (fx >= fy) ? 0 : 1;
-        f3 A = field_vertex(H, i, j);
-        f3 Bv = t == 0 ? field_vertex(H, i + 1, j) : field_vertex(H, i + 1, j + 1);
-        f3 Cv = t == 0 ? field_vertex(H, i + 1, j + 1) : field_vertex(H, i, j + 1);
-        f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
-        f3 pa = sub3(P, A);
-        float face = dot3(pa, nt);
-        if (face < 0.0f) {
-          float inv = 1.0f / sqrtf(dot3(nt, nt));
-          f3 n = f3{nt.x * inv, nt.y * inv, nt.z * inv};
-          out.active = 1; out.kind = 2; out.feat = 2 * (j * ncx + i) + t;
-          out.d = dot3(sub3(pl, sub3(A, org)), n) - r;  // gap measured in env-local coordinates
-          out.n = n;
-          out.rc = f3{(pl.x - r * n.x) - xc.x, (pl.y - r * n.y) - xc.y, (pl.z - r * n.z) - xc.z};
-          out.w = block_weight(margin, out.d, 1.0f);
-          return out;
-        }
-      }
-    }
-    int i0, i1, j0, j1;
-    if (!cell_span(H, P.x - Rq, P.x + Rq, H.ox, ncx, i0, i1)) return out;
-    if (!cell_span(H, P.y - Rq, P.y + Rq, H.oy, ncy, j0, j1)) return out;
-    const float zcut = P.z - Rq;
-    float best = INFINITY;
-    int best_id = -1;
-    for (int j = j0; j <= j1; ++j)
-      for (int i = i0; i <= i1; ++i) {
-        f3 A = field_vertex(H, i, j), B1 = field_vertex(H, i + 1, j), C1 = field_vertex(H, i + 1, j + 1),
-           D1 = field_vertex(H, i, j + 1);
-        float zmax = fmaxf(fmaxf(A.z, B1.z), fmaxf(C1.z, D1.z));
-        if (zcut > zmax) continue;  // whole cell further than r + margin + slack below the sphere
+// Cells overlapped by the reach box; false when the slot cannot touch the field
+// (box outside the field, or higher than every sample of the coarse blocks under it).
+__device__ __forceinline__ bool slot_reach(const Field& H, SlotGeom& g) {
+  const int ncx = H.nx - 1, ncy = H.ny - 1;
+  float xl, xh, yl, yh, zl;
+  if (g.kind < 2) {
+    f3 P = g.kind == 0 ? g.P0 : g.P1;
+    xl = xh = P.x; yl = yh = P.y; zl = P.z;
+  } else {
+    xl = g.P0.x < g.P1.x ? g.P0.x : g.P1.x; xh = g.P0.x < g.P1.x ? g.P1.x : g.P0.x;
+    yl = g.P0.y < g.P1.y ? g.P0.y : g.P1.y; yh = g.P0.y < g.P1.y ? g.P1.y : g.P0.y;
+    zl = g.P0.z < g.P1.z ? g.P0.z : g.P1.z;
+  }
+  if (!cell_span(H, xl - g.Rq, xh + g.Rq, H.ox, ncx, g.i0, g.i1)) return false;
+  if (!cell_span(H, yl - g.Rq, yh + g.Rq, H.oy, ncy, g.j0, g.j1)) return false;
+  const float zcut = zl - g.Rq;
+  float hmax = -INFINITY;
+  if (H.ps > 0 && g.i0 >= H.pi0 && g.i1 + 1 < H.pi0 + H.ps && g.j0 >= H.pj0 && g.j1 + 1 < H.pj0 + H.ps) {
+    // the whole reach box lies inside the LDS copy: maximum over the blocks it touches
+    // (up to 3 x 3 of them read without a loop; larger boxes take the loop)
+    const int nb = (H.ps + kMip - 1) / kMip;
+    const int I0 = (g.i0 - H.pi0) / kMip, I1 = (g.i1 + 1 - H.pi0) / kMip;
+    const int J0 = (g.j0 - H.pj0) / kMip, J1 = (g.j1 + 1 - H.pj0) / kMip;
+    if (I1 - I0 <= 2 && J1 - J0 <= 2) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          f3 Bv = t == 0 ? B1 : C1, Cv = t == 0 ? C1 : D1;
-          f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
-          float face = dot3(sub3(P, A), nt);
-          if (face < 0.0f) continue;
-          float v, w;
-          tri_closest_vw(P, A, Bv, Cv, v, w);
-          f3 df = sub3(P, tri_point(A, Bv, Cv, v, w));
-          float d2 = dot3(df, df);
-          if (d2 < best) { best = d2; best_id = 2 * (j * ncx + i) + t; }
+      for (int dj = 0; dj < 3; ++dj)
+#pragma unroll
+        for (int di = 0; di < 3; ++di) {
+          int I = I0 + di < I1 ? I0 + di : I1, J = J0 + dj < J1 ? J0 + dj : J1;
+          hmax = fmaxf(hmax, H.mip[J * nb + I]);
         }
-      }
-    if (best_id < 0) return out;
-    float dist = sqrtf(best);
-    float d = dist - r;
-    if (!(d < margin)) return out;
-    // geometry of the winner
-    int t = best_id & 1, c = best_id >> 1, i = c % ncx, j = c / ncx;
-    // The winner's geometry is rebuilt in env-local coordinates (vertex minus env
-    // origin), where the sphere centre carries no rounding from the world offset.
-    f3 A = sub3(field_vertex(H, i, j), org);
-    f3 Bv = sub3(t == 0 ? field_vertex(H, i + 1, j) : field_vertex(H, i + 1, j + 1), org);
-    f3 Cv = sub3(t == 0 ? field_vertex(H, i + 1, j + 1) : field_vertex(H, i, j + 1), org);
-    float v, w;
-    tri_closest_vw(pl, A, Bv, Cv, v, w);
-    f3 df = sub3(pl, tri_point(A, Bv, Cv, v, w));
-    dist = sqrtf(dot3(df, df));
-    d = dist - r;
-    f3 n;
-    if (dist < 1e-9f) {
-      f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
-      float inv = 1.0f / sqrtf(dot3(nt, nt));
-      n = f3{nt.x * inv, nt.y * inv, nt.z * inv};
     } else {
-      float inv = 1.0f / dist;
-      n = f3{df.x * inv, df.y * inv, df.z * inv};
+      for (int J = J0; J <= J1; ++J)
+        for (int I = I0; I <= I1; ++I) hmax = fmaxf(hmax, H.mip[J * nb + I]);
     }
-    out.active = 1; out.kind = 1; out.feat = best_id; out.d = d; out.n = n;
-    out.rc = f3{(pl.x - r * n.x) - xc.x, (pl.y - r * n.y) - xc.y, (pl.z - r * n.z) - xc.z};
-    out.w = block_weight(margin, d, 1.0f);
-    return out;
+  } else {
+    for (int J = g.j0 / kCoarse; J <= g.j1 / kCoarse; ++J)
+      for (int I = g.i0 / kCoarse; I <= g.i1 / kCoarse; ++I) hmax = fmaxf(hmax, H.coarse[J * H.cnx + I]);
   }
+  return !(zcut > hmax);
+}
 
-  // mid-segment slot: segment interior against heightfield edges
-  {
-    float xl = P0.x < P1.x ? P0.x : P1.x, xh = P0.x < P1.x ? P1.x : P0.x;
-    float yl = P0.y < P1.y ? P0.y : P1.y, yh = P0.y < P1.y ? P1.y : P0.y;
-    int i0, i1, j0, j1;
-    if (!cell_span(H, xl - Rq, xh + Rq, H.ox, ncx, i0, i1)) return out;
-    if (!cell_span(H, yl - Rq, yh + Rq, H.oy, ncy, j0, j1)) return out;
-    const float zcut = (P0.z < P1.z ? P0.z : P1.z) - Rq;
-    float best = INFINITY;
-    int best_id = -1;
-    for (int j = j0; j <= j1 + 1; ++j)
-      for (int i = i0; i <= i1 + 1; ++i) {
-        f3 Q0 = field_vertex(H, i, j);
+// Centre underneath the surface: triangle containing its xy, plane distance.
+__device__ __forceinline__ bool underneath_contact(const Field& H, const SlotGeom& g, float margin,
+                                                   ContactOut& out) {
+  const int ncx = H.nx - 1, ncy = H.ny - 1;
+  f3 P = g.kind == 0 ? g.P0 : g.P1;
+  f3 pl = g.kind == 0 ? g.p0 : g.p1;
+  float ux = (P.x - H.ox) * H.inv_cell, uy = (P.y - H.oy) * H.inv_cell;
+  float fi = floorf(ux), fj = floorf(uy);
+  if (!(fi >= 0.0f && fi <= (float)(ncx - 1) && fj >= 0.0f && fj <= (float)(ncy - 1))) return false;
+  int i = (int)fi, j = (int)fj;
+  float fx = ux - fi, fy = uy - fj;
+  int t = (fx >= fy) ? 0 : 1;
+  f3 A = field_vertex(H, i, j);
+  f3 Bv = t == 0 ? field_vertex(H, i + 1, j) : field_vertex(H, i + 1, j + 1);
+  f3 Cv = t == 0 ? field_vertex(H, i + 1, j + 1) : field_vertex(H, i, j + 1);
+  f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
+  float face = dot3(sub3(P, A), nt);
+  if (!(face < 0.0f)) return false;
+  float inv = 1.0f / sqrtf(dot3(nt, nt));
+  f3 n = f3{nt.x * inv, nt.y * inv, nt.z * inv};
+  out.active = 1; out.kind = 2; out.feat = 2 * (j * ncx + i) + t;
+  out.d = dot3(sub3(pl, sub3(A, g.org)), n) - g.r;  // gap measured in env-local coordinates
+  out.n = n;
+  out.rc = f3{(pl.x - g.r * n.x) - g.xc.x, (pl.y - g.r * n.y) - g.xc.y, (pl.z - g.r * n.z) - g.xc.z};
+  out.w = block_weight(margin, out.d, 1.0f);
+  return true;
+}
+
+__device__ __forceinline__ void keep_min(float d2, int id, float& best, int& best_id) {
+  if (d2 < best || (d2 == best && id < best_id)) { best = d2; best_id = id; }
+}
+
+// Both triangles of cell (i,j) against the end sphere centred at P.
+__device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float zcut, int i, int j, float& best,
+                                            int& best_id) {
+  const int ncx = H.nx - 1;
+  f3 A = field_vertex(H, i, j), B1 = field_vertex(H, i + 1, j), C1 = field_vertex(H, i + 1, j + 1),
+     D1 = field_vertex(H, i, j + 1);
+  float zmax = fmaxf(fmaxf(A.z, B1.z), fmaxf(C1.z, D1.z));
+  if (zcut > zmax) return;  // whole cell further than r + margin + slack below the sphere
 #pragma unroll
-        for (int k = 0; k < 3; ++k) {
-          if ((k == 0 || k == 2) && i > i1) continue;
-          if ((k == 1 || k == 2) && j > j1) continue;
-          f3 Q1 = k == 0 ? field_vertex(H, i + 1, j)
-                         : (k == 1 ? field_vertex(H, i, j + 1) : field_vertex(H, i + 1, j + 1));
-          if (zcut > fmaxf(Q0.z, Q1.z)) continue;  // edge entirely out of reach below the capsule
-          float s, t;
-          seg_edge_st(P0, P1, Q0, Q1, s, t);
-          if (!(s > 0.001f && s < 0.999f)) continue;
-          f3 d1 = sub3(P1, P0), d2 = sub3(Q1, Q0);
-          f3 c1 = f3{P0.x + d1.x * s, P0.y + d1.y * s, P0.z + d1.z * s};
-          f3 c2 = f3{Q0.x + d2.x * t, Q0.y + d2.y * t, Q0.z + d2.z * t};
-          f3 df = sub3(c1, c2);
-          if (!(df.z > 0.0f)) continue;
-          float dd = dot3(df, df);
-          if (dd < best) { best = dd; best_id = 3 * (j * H.nx + i) + k; }
-        }
-      }
-    if (best_id < 0) return out;
-    float dist = sqrtf(best);
-    float d = dist - r;
-    if (!(d < margin)) return out;
-    int k = best_id % 3, vtx = best_id / 3, i = vtx % H.nx, j = vtx / H.nx;
-    // winner's geometry in env-local coordinates (see the end-sphere case)
-    f3 Q0 = sub3(field_vertex(H, i, j), org);
-    f3 Q1 = sub3(k == 0 ? field_vertex(H, i + 1, j)
-                        : (k == 1 ? field_vertex(H, i, j + 1) : field_vertex(H, i + 1, j + 1)), org);
-    float s, t;
-    seg_edge_st(p0, p1, Q0, Q1, s, t);
-    f3 d1 = sub3(p1, p0), d2 = sub3(Q1, Q0);
-    f3 cl = f3{p0.x + d1.x * s, p0.y + d1.y * s, p0.z + d1.z * s};
-    f3 c2 = f3{Q0.x + d2.x * t, Q0.y + d2.y * t, Q0.z + d2.z * t};
-    f3 df = sub3(cl, c2);
-    dist = sqrtf(dot3(df, df));
-    d = dist - r;
-    f3 n;
-    if (dist < 1e-9f) n = f3{0.0f, 0.0f, 1.0f};
-    else { float inv = 1.0f / dist; n = f3{df.x * inv, df.y * inv, df.z * inv}; }
-    out.active = 1; out.kind = 3; out.feat = best_id; out.d = d; out.n = n;
-    out.rc = f3{(cl.x - r * n.x) - xc.x, (cl.y - r * n.y) - xc.y, (cl.z - r * n.z) - xc.z};
-    {
-      float se = s < 1.0f - s ? s : 1.0f - s;
-      out.w = block_weight(margin, d, fminf(fmaxf((se - 0.001f) / 0.1f, 0.0f), 1.0f));
-    }
-    return out;
+  for (int t = 0; t < 2; ++t) {
+    f3 Bv = t == 0 ? B1 : C1, Cv = t == 0 ? C1 : D1;
+    f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
+    float face = dot3(sub3(P, A), nt);
+    if (face < 0.0f) continue;  // back-facing
+    float v, w;
+    tri_closest_vw(P, A, Bv, Cv, v, w);
+    f3 df = sub3(P, tri_point(A, Bv, Cv, v, w));
+    keep_min(dot3(df, df), 2 * (j * ncx + i) + t, best, best_id);
   }
+}
+
+// The up-to-three edges that start at sample (i,j) against the segment interior.
+__device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g, float zcut, int i, int j,
+                                               float& best, int& best_id) {
+  f3 Q0 = field_vertex(H, i, j);
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    if ((k == 0 || k == 2) && i > g.i1) continue;
+    if ((k == 1 || k == 2) && j > g.j1) continue;
+    f3 Q1 = k == 0 ? field_vertex(H, i + 1, j) : (k == 1 ? field_vertex(H, i, j + 1) : field_vertex(H, i + 1, j + 1));
+    if (zcut > fmaxf(Q0.z, Q1.z)) continue;  // edge entirely out of reach below the capsule
+    float s, t;
+    seg_edge_st(g.P0, g.P1, Q0, Q1, s, t);
+    if (!(s > 0.001f && s < 0.999f)) continue;  // the ends belong to the end-sphere slots
+    f3 d1 = sub3(g.P1, g.P0), d2 = sub3(Q1, Q0);
+    f3 c1 = f3{g.P0.x + d1.x * s, g.P0.y + d1.y * s, g.P0.z + d1.z * s};
+    f3 c2 = f3{Q0.x + d2.x * t, Q0.y + d2.y * t, Q0.z + d2.z * t};
+    f3 df = sub3(c1, c2);
+    if (!(df.z > 0.0f)) continue;  // the axis must be above the edge
+    keep_min(dot3(df, df), 3 * (j * H.nx + i) + k, best, best_id);
+  }
+}
+
+// Record of the selected triangle (end sphere).  The geometry is rebuilt in
+// env-local coordinates (vertex minus env origin), where the sphere centre
+// carries no rounding from the world offset.
+__device__ __forceinline__ ContactOut finish_sphere(const Field& H, const SlotGeom& g, float margin, float best,
+                                                    int best_id) {
+  ContactOut out = no_contact();
+  if (best_id < 0) return out;
+  float dist = sqrtf(best);
+  float d = dist - g.r;
+  if (!(d < margin)) return out;
+  const int ncx = H.nx - 1;
+  f3 pl = g.kind == 0 ? g.p0 : g.p1;
+  int t = best_id & 1, c = best_id >> 1, i = c % ncx, j = c / ncx;
+  f3 A = sub3(field_vertex(H, i, j), g.org);
+  f3 Bv = sub3(t == 0 ? field_vertex(H, i + 1, j) : field_vertex(H, i + 1, j + 1), g.org);
+  f3 Cv = sub3(t == 0 ? field_vertex(H, i + 1, j + 1) : field_vertex(H, i, j + 1), g.org);
+  float v, w;
+  tri_closest_vw(pl, A, Bv, Cv, v, w);
+  f3 df = sub3(pl, tri_point(A, Bv, Cv, v, w));
+  dist = sqrtf(dot3(df, df));
+  d = dist - g.r;
+  f3 n;
+  if (dist < 1e-9f) {
+    f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
+    float inv = 1.0f / sqrtf(dot3(nt, nt));
+    n = f3{nt.x * inv, nt.y * inv, nt.z * inv};
+  } else {
+    float inv = 1.0f / dist;
+    n = f3{df.x * inv, df.y * inv, df.z * inv};
+  }
+  out.active = 1; out.kind = 1; out.feat = best_id; out.d = d; out.n = n;
+  out.rc = f3{(pl.x - g.r * n.x) - g.xc.x, (pl.y - g.r * n.y) - g.xc.y, (pl.z - g.r * n.z) - g.xc.z};
+  out.w = block_weight(margin, d, 1.0f);
+  return out;
+}
+
+// Record of the selected edge (mid-segment slot), geometry in env-local coordinates.
+__device__ __forceinline__ ContactOut finish_segment(const Field& H, const SlotGeom& g, float margin, float best,
+                                                     int best_id) {
+  ContactOut out = no_contact();
+  if (best_id < 0) return out;
+  float dist = sqrtf(best);
+  float d = dist - g.r;
+  if (!(d < margin)) return out;
+  int k = best_id % 3, vtx = best_id / 3, i = vtx % H.nx, j = vtx / H.nx;
+  f3 Q0 = sub3(field_vertex(H, i, j), g.org);
+  f3 Q1 = sub3(k == 0 ? field_vertex(H, i + 1, j) : (k == 1 ? field_vertex(H, i, j + 1) : field_vertex(H, i + 1, j + 1)),
+               g.org);
+  float s, t;
+  seg_edge_st(g.p0, g.p1, Q0, Q1, s, t);
+  f3 d1 = sub3(g.p1, g.p0), d2 = sub3(Q1, Q0);
+  f3 cl = f3{g.p0.x + d1.x * s, g.p0.y + d1.y * s, g.p0.z + d1.z * s};
+  f3 c2 = f3{Q0.x + d2.x * t, Q0.y + d2.y * t, Q0.z + d2.z * t};
+  f3 df = sub3(cl, c2);
+  dist = sqrtf(dot3(df, df));
+  d = dist - g.r;
+  f3 n;
+  if (dist < 1e-9f) n = f3{0.0f, 0.0f, 1.0f};
+  else { float inv = 1.0f / dist; n = f3{df.x * inv, df.y * inv, df.z * inv}; }
+  out.active = 1; out.kind = 3; out.feat = best_id; out.d = d; out.n = n;
+  out.rc = f3{(cl.x - g.r * n.x) - g.xc.x, (cl.y - g.r * n.y) - g.xc.y, (cl.z - g.r * n.z) - g.xc.z};
+  float se = s < 1.0f - s ? s : 1.0f - s;
+  out.w = block_weight(margin, d, fminf(fmaxf((se - 0.001f) / 0.1f, 0.0f), 1.0f));
+  return out;
+}
+
+__device__ __forceinline__ Field make_field(const Model& M, const float* heights, const float* coarse) {
+  return Field{M.nx, M.ny, M.cell, M.inv_cell, M.hox, M.hoy, heights, coarse, M.cnx, nullptr, nullptr, 0, 0, 0};
+}
+
+// One slot handled by one thread (used by the stand-alone contact kernel).
+__device__ inline ContactOut generate_contact(const Model& M, const float* __restrict__ heights,
+                                              const float* __restrict__ coarse, const float x[3],
+                                              const float q[4], int body, int slot_kind, const float origin[3]) {
+  if (!M.contacts) return no_contact();
+  SlotGeom g = slot_geom(M.bodies[body].radius, M.bodies[body].half_len, M.bodies[body].axis, M.margin, x, q, slot_kind,
+                         origin);
+  if (M.terrain_kind == 0) return plane_contact(g, M.margin);
+  Field H = make_field(M, heights, coarse);
+  if (!slot_reach(H, g)) return no_contact();
+  float best = INFINITY;
+  int best_id = -1;
+  if (slot_kind < 2) {
+    ContactOut out = no_contact();
+    if (underneath_contact(H, g, M.margin, out)) return out;
+    f3 P = slot_kind == 0 ? g.P0 : g.P1;
+    const float zcut = P.z - g.Rq;
+    for (int j = g.j0; j <= g.j1; ++j)
+      for (int i = g.i0; i <= g.i1; ++i) sphere_cell(H, P, zcut, i, j, best, best_id);
+    return finish_sphere(H, g, M.margin, best, best_id);
+  }
+  const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
+  for (int j = g.j0; j <= g.j1 + 1; ++j)
+    for (int i = g.i0; i <= g.i1 + 1; ++i) segment_vertex(H, g, zcut, i, j, best, best_id);
+  return finish_segment(H, g, M.margin, best, best_id);
 }
 
 #pragma clang fp contract(fast)

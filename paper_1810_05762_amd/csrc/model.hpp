@@ -13,6 +13,7 @@ constexpr int kMaxDofs = 32;
 constexpr int kMaxFeet = 4;
 constexpr int kMaxSlots = 3 * kMaxBodies;
 constexpr int kMaxBodyJoints = 8;  // joint sides touching one body
+constexpr int kCoarse = 8;         // cells per side of a coarse max-height block
 
 struct BodyTab {
   float radius, half_len, inv_mass;
@@ -41,11 +42,13 @@ struct Model {
   int32_t B, J, D, S, F;
   int32_t root, feet[kMaxFeet];
   int32_t terrain_kind, nx, ny;
+  int32_t cnx, cny;  // coarse max-height grid: block (I,J) covers samples [8I, 8I+8] x [8J, 8J+8]
   float cell, inv_cell, hox, hoy;
   float g[3];
   float mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
   float term_height, alive_bonus;
   int32_t max_steps, gyro, contacts;
+  int32_t max_joint_sides;  // largest n_joint_sides over the bodies
   BodyTab bodies[kMaxBodies];
   JointTab joints[kMaxJoints];
   SlotTab slots[kMaxSlots];

@@ -41,15 +41,16 @@ extern "C" const char* sim_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ layout
 struct Layout {
-  size_t model, heights, origins, targets, state, steps, obs, reward, done, recs, flag, total;
+  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, flag, total;
 };
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights) {
+static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, size_t n_coarse) {
   Layout L;
   size_t o = 0;
   L.model = o; o = align_up(o + sizeof(Model));
   L.heights = o; o = align_up(o + (n_heights ? n_heights : 1) * sizeof(float));
+  L.coarse = o; o = align_up(o + (n_coarse ? n_coarse : 1) * sizeof(float));
   L.origins = o; o = align_up(o + (size_t)N * 3 * sizeof(float));
   L.targets = o; o = align_up(o + (size_t)N * 2 * sizeof(float));
   L.state = o; o = align_up(o + (size_t)13 * B * N * sizeof(float));
@@ -159,8 +160,12 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
     }
   }
   m->D = D;
+  for (int b = 0; b < m->B; ++b)
+    if (m->bodies[b].n_joint_sides > m->max_joint_sides) m->max_joint_sides = m->bodies[b].n_joint_sides;
   m->terrain_kind = d->terrain_kind;
   m->nx = d->hf_nx; m->ny = d->hf_ny;
+  m->cnx = d->terrain_kind == 1 ? (d->hf_nx - 1 + kCoarse - 1) / kCoarse : 0;
+  m->cny = d->terrain_kind == 1 ? (d->hf_ny - 1 + kCoarse - 1) / kCoarse : 0;
   m->cell = (float)d->hf_cell;
   m->inv_cell = d->terrain_kind == 1 ? 1.0f / (float)d->hf_cell : 1.0f;
   m->hox = (float)d->hf_origin[0]; m->hoy = (float)d->hf_origin[1];
@@ -179,8 +184,6 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
 static int default_envs_per_block(const Model& m, int N) {
   int bj = m.B > m.J ? m.B : m.J;
   int lim = kThreads / bj;
-  int lim_c = (kKC * kThreads) / (m.S > 0 ? m.S : 1);
-  if (lim_c < lim) lim = lim_c;
   if (lim > 16) lim = 16;
   int want = N / 256;  // keep at least one workgroup per compute unit when N allows
   if (want < 1) want = 1;
@@ -226,7 +229,7 @@ __global__ void check_kernel(const float* __restrict__ state, int n, int* flag) 
 }
 
 __global__ void gen_contacts_kernel(const Model* Mp, const float* __restrict__ heights,
-                                    const float* __restrict__ origins, const float* __restrict__ state,
+                                    const float* __restrict__ coarse, const float* __restrict__ origins, const float* __restrict__ state,
                                     int32_t* __restrict__ recs, int N) {
   const Model& M = *Mp;
   int i = blockIdx.x * blockDim.x + threadIdx.x;  // env fastest
@@ -238,7 +241,7 @@ __global__ void gen_contacts_kernel(const Model* Mp, const float* __restrict__ h
   float x[3] = {st[0], st[fs], st[2 * fs]};
   float q[4] = {st[3 * fs], st[4 * fs], st[5 * fs], st[6 * fs]};
   float o[3] = {origins[3 * env], origins[3 * env + 1], origins[3 * env + 2]};
-  ContactOut c = generate_contact(M, heights, x, q, sl.body, sl.kind, o);
+  ContactOut c = generate_contact(M, heights, coarse, x, q, sl.body, sl.kind, o);
   int32_t* r = recs + ((size_t)env * M.S + s) * kRecWords;
   r[0] = c.active; r[1] = c.kind; r[2] = c.feat;
   r[3] = __float_as_int(c.d);
@@ -326,6 +329,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   StepArgs a;
   a.M = reinterpret_cast<const Model*>(s->ws + s->lay.model);
   a.heights = reinterpret_cast<const float*>(s->ws + s->lay.heights);
+  a.coarse = reinterpret_cast<const float*>(s->ws + s->lay.coarse);
   a.origins = reinterpret_cast<const float*>(s->ws + s->lay.origins);
   a.targets = reinterpret_cast<const float*>(s->ws + s->lay.targets);
   a.state = reinterpret_cast<float*>(s->ws + s->lay.state);
@@ -337,13 +341,24 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.recs = (s->record && substeps > 0) ? reinterpret_cast<int32_t*>(s->ws + s->lay.recs) : nullptr;
   a.N = s->N; a.E = s->E; a.substeps = substeps; a.iterations = iterations; a.count_step = count_step;
   a.h = h;
-  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, s->E);
+#ifdef EXP_TIMING
+  a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
+#else
+  a.dbg = nullptr;
+#endif
+  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
+  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, s->E, with_patch);
   size_t lds_bytes = (size_t)P.total * sizeof(float);
   if (lds_bytes > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d needs %zu bytes of LDS (limit 160 KiB)", s->E, lds_bytes);
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&step_kernel<kKC>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
   int grid = (s->N + s->E - 1) / s->E;
-  hipLaunchKernelGGL(step_kernel<kKC>, dim3(grid), dim3(kThreads), lds_bytes, st, a);
+  auto launch = [&](auto kern) -> int {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds_bytes, st, a);
+    return SIM_OK;
+  };
+  int lrc = s->E == 16 ? launch(&step_kernel<16>) : (s->E == 8 ? launch(&step_kernel<8>) : launch(&step_kernel<0>));
+  if (lrc) return lrc;
   HIP_TRY(hipGetLastError());
   if (a.recs) s->recs_valid = 1;
   return SIM_OK;
@@ -358,7 +373,7 @@ extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t*
   if (rc) return rc;
   if (!out_bytes) return fail(SIM_ERR_ARG, "out_bytes is NULL");
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
-  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F, num_envs, nh).total;
+  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F, num_envs, nh, (size_t)m.cnx * m.cny).total;
   return SIM_OK;
 }
 
@@ -374,7 +389,7 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
   s->N = num_envs;
   s->obs_dim = 11 + 3 * m.D + m.F;
-  s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh);
+  s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny);
   s->record = 0; s->recs_valid = 0;
   s->E = default_envs_per_block(m, num_envs);
   if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace must be non-NULL and 256-byte aligned"); }
@@ -387,7 +402,22 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
     if (_e != hipSuccess) return bail(fail(SIM_ERR_HIP, "%s: %s", #expr, hipGetErrorString(_e))); \
   } while (0)
   HIP_TRY_S(hipMemcpy(s->ws + s->lay.model, &s->host_model, sizeof(Model), hipMemcpyHostToDevice));
-  if (nh) HIP_TRY_S(hipMemcpy(s->ws + s->lay.heights, desc->hf_heights, nh * sizeof(float), hipMemcpyHostToDevice));
+  if (nh) {
+    HIP_TRY_S(hipMemcpy(s->ws + s->lay.heights, desc->hf_heights, nh * sizeof(float), hipMemcpyHostToDevice));
+    // coarse grid of block maxima: lets a slot that is clear of the terrain skip the fine search
+    std::vector<float> coarse((size_t)m.cnx * m.cny);
+    for (int J = 0; J < m.cny; ++J)
+      for (int I = 0; I < m.cnx; ++I) {
+        float hm = -INFINITY;
+        for (int j = J * kCoarse; j <= J * kCoarse + kCoarse && j < m.ny; ++j)
+          for (int i = I * kCoarse; i <= I * kCoarse + kCoarse && i < m.nx; ++i) {
+            float hv = desc->hf_heights[(size_t)j * m.nx + i];
+            hm = hv > hm ? hv : hm;
+          }
+        coarse[(size_t)J * m.cnx + I] = hm;
+      }
+    HIP_TRY_S(hipMemcpy(s->ws + s->lay.coarse, coarse.data(), coarse.size() * sizeof(float), hipMemcpyHostToDevice));
+  }
   {
     std::vector<float> org((size_t)num_envs * 3), tgt((size_t)num_envs * 2);
     for (size_t i = 0; i < org.size(); ++i) org[i] = (float)desc->env_origins[i];
@@ -431,10 +461,10 @@ extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
   const Model& m = s->host_model;
   if (E == 0) { s->E = default_envs_per_block(m, s->N); return SIM_OK; }
   int bj = m.B > m.J ? m.B : m.J;
-  if (E < 1 || E * bj > kThreads || E * m.S > kKC * kThreads)
-    return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*max(B,J) <= %d and E*S <= %d)", E,
-                kThreads, kThreads, kKC * kThreads);
-  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, E);
+  if (E < 1 || E * bj > kThreads)
+    return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*max(B,J) <= %d)", E, kThreads,
+                kThreads);
+  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, E, (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0);
   if ((size_t)P.total * 4 > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d exceeds LDS", E);
   s->E = E;
   return SIM_OK;
@@ -532,6 +562,7 @@ extern "C" int sim_generate_contacts(sim_t* s, sim_contact_rec_t* recs_dev, void
   hipLaunchKernelGGL(gen_contacts_kernel, dim3(blocks_for(n, 64)), dim3(64), 0, static_cast<hipStream_t>(stream),
                      reinterpret_cast<const Model*>(s->ws + s->lay.model),
                      reinterpret_cast<const float*>(s->ws + s->lay.heights),
+                     reinterpret_cast<const float*>(s->ws + s->lay.coarse),
                      reinterpret_cast<const float*>(s->ws + s->lay.origins),
                      reinterpret_cast<const float*>(s->ws + s->lay.state), reinterpret_cast<int32_t*>(recs_dev),
                      s->N);

@@ -9,7 +9,9 @@
 // Roles (a thread can hold several):
 //   body thread  (e, b): owns pose and velocity of one body in registers,
 //   joint thread (e, j): owns the six rows of one joint (constants in registers),
-//   contact thread      : owns the three rows of up to KC active contact slots,
+//   contact thread      : owns the three rows of one active contact slot (constants in
+//                         registers); a workgroup's contacts beyond one per thread are
+//                         rebuilt from their LDS record every sweep,
 //   env thread   (e)    : packs root observations, reward and done.
 //
 // Per substep (Section 3.1 of the paper: maximal coordinates, torque control,
@@ -33,12 +35,15 @@
 
 namespace sim355 {
 
-constexpr int kThreads = 256;
-constexpr int kKC = 3;  // contact slots a thread can own per substep
+constexpr int kThreads = 512;
+constexpr int kGroup = 8;  // lanes that share the fine terrain search of one slot
+constexpr int kPatch = 28; // samples per side of the per-env heightfield copy kept in LDS
+constexpr int kPatchBlocks = (kPatch + kMip - 1) / kMip;
 
 struct StepArgs {
   const Model* M;
   const float* heights;
+  const float* coarse;   // block maxima of the heightfield
   const float* origins;  // [N][3]
   const float* targets;  // [N][2]
   float* state;          // [13][B][N]
@@ -50,13 +55,14 @@ struct StepArgs {
   int32_t* recs;         // [N][S][12] or null
   int N, E, substeps, iterations, count_step;
   float h;
+  long long* dbg;
 };
 
 struct LdsPlan {
-  int pos, vel, iw, nb, outj, outc, rec, list, u, obs, lim, count, total;
+  int pos, vel, iw, nb, outj, outc, rec, list, surv, cand, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, total;
 };
 
-__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E) {
+__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch) {
   LdsPlan p;
   int o = 0;
   p.pos = o; o += B * 7 * E;
@@ -67,10 +73,19 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.outc = o; o += S * 6 * E;
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
+  p.surv = o; o += S * E;
+  p.cand = o; o += S * E;
+  p.lam = o; o += 3 * (S * E > kThreads ? S * E - kThreads : 0);
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
   p.lim = o; o += (D > 0 ? D : 1) * E;
   p.count = o; o += 4;
+  p.porg = o; o += 2 * E;
+  p.org = o; o += 3 * E;
+  p.tslot = o; o += 2 * S;
+  p.tbody = o; o += 4 * B;
+  p.patch = o; o += with_patch ? E * kPatch * kPatch : 0;
+  p.mip = o; o += with_patch ? E * kPatchBlocks * kPatchBlocks : 0;
   p.total = o;
   return p;
 }
@@ -133,6 +148,20 @@ __device__ inline float terrain_height(const Model& M, const float* __restrict__
   return h00 + fx * (h11 - h01) + fy * (h01 - h00);
 }
 
+__device__ __forceinline__ void store_record(float* Lrec, int* Lreci, int s, int ee, int E, const ContactOut& co) {
+  Lreci[(s * kRecWords + 0) * E + ee] = co.active;
+  Lreci[(s * kRecWords + 1) * E + ee] = co.kind;
+  Lreci[(s * kRecWords + 2) * E + ee] = co.feat;
+  Lrec[(s * kRecWords + 3) * E + ee] = co.d;
+  Lrec[(s * kRecWords + 4) * E + ee] = co.n.x;
+  Lrec[(s * kRecWords + 5) * E + ee] = co.n.y;
+  Lrec[(s * kRecWords + 6) * E + ee] = co.n.z;
+  Lrec[(s * kRecWords + 7) * E + ee] = co.rc.x;
+  Lrec[(s * kRecWords + 8) * E + ee] = co.rc.y;
+  Lrec[(s * kRecWords + 9) * E + ee] = co.rc.z;
+  Lrec[(s * kRecWords + 10) * E + ee] = co.w;
+}
+
 struct JointRows {
   // positional rows along world x,y,z
   float ra[3], rb[3];      // lever arms from each centre to the shared impulse point
@@ -156,12 +185,79 @@ struct ContactRows {
   int body;
 };
 
-template <int KC>
+#ifdef EXP_TIMING
+#define TMARK(k) do { if (tid == 0 && blockIdx.x == 7) { long long _t = clock64(); a.dbg[k] += _t - t_last; t_last = _t; } } while (0)
+#else
+#define TMARK(k) do { } while (0)
+#endif
+
+// Row constants of one active contact slot from its LDS record (d, n, rc, weight), the
+// body's world inverse inertia, weight sum and inverse mass.
+__device__ __forceinline__ void build_contact_rows(ContactRows& c, const float* Lrec, const float* Liw,
+                                                   const float* Lnb, int s, int ee, int E, int body, float imb,
+                                                   float h, float beta_c, float v_depen) {
+  c.body = body;
+  c.slot_e = s * E + ee;
+  float d = Lrec[(s * kRecWords + 3) * E + ee];
+  float n[3], rc[3], iwb[6];
+  for (int k = 0; k < 3; ++k) { n[k] = Lrec[(s * kRecWords + 4 + k) * E + ee]; rc[k] = Lrec[(s * kRecWords + 7 + k) * E + ee]; }
+  for (int k = 0; k < 6; ++k) iwb[k] = Liw[(body * 6 + k) * E + ee];
+  float nbb = Lnb[body * E + ee] / Lrec[(s * kRecWords + 10) * E + ee];
+  float t1[3], t2[3];
+  if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
+  else { t1[0] = -n[2]; t1[1] = 0.0f; t1[2] = n[0]; }
+  float inv = 1.0f / sqrtf(dot(t1, t1));
+  for (int k = 0; k < 3; ++k) t1[k] *= inv;
+  cross(n, t1, t2);
+  for (int k = 0; k < 3; ++k) { c.dir[0][k] = n[k]; c.dir[1][k] = t1[k]; c.dir[2][k] = t2[k]; }
+  c.ls = nbb * imb;
+  for (int r = 0; r < 3; ++r) {
+    float y[3];
+    cross(rc, c.dir[r], c.ang[r]);
+    sym_vec(iwb, c.ang[r], y);
+    float keff = nbb * (imb + dot(c.ang[r], y));
+    c.meff[r] = keff > 0.0f ? 1.0f / keff : 0.0f;
+    for (int k = 0; k < 3; ++k) c.Y[r][k] = nbb * y[k];
+    c.lam[r] = 0.0f;
+  }
+  c.bias = d >= 0.0f ? d / h : fmaxf(beta_c * d / h, -v_depen);
+}
+
+// One sweep of a contact block on its private copy (vv, ww) of the body velocity:
+// normal row (impulse >= 0), then the friction pair projected on the disc mu * lambda_n.
+__device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv[3], float ww[3]) {
+  {
+    float jv = dot(c.dir[0], vv) + dot(c.ang[0], ww);
+    float dl = -c.meff[0] * (jv + c.bias);
+    float ln = fmaxf(c.lam[0] + dl, 0.0f);
+    dl = ln - c.lam[0];
+    c.lam[0] = ln;
+    for (int k = 0; k < 3; ++k) { vv[k] += c.ls * c.dir[0][k] * dl; ww[k] += c.Y[0][k] * dl; }
+  }
+  float jv1 = dot(c.dir[1], vv) + dot(c.ang[1], ww);
+  float jv2 = dot(c.dir[2], vv) + dot(c.ang[2], ww);
+  float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
+  float lim = mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
+  if (nrm > lim) { float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
+  float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
+  c.lam[1] = l1; c.lam[2] = l2;
+  for (int k = 0; k < 3; ++k) {
+    vv[k] += c.ls * (c.dir[1][k] * d1 + c.dir[2][k] * d2);
+    ww[k] += c.Y[1][k] * d1 + c.Y[2][k] * d2;
+  }
+}
+
+// EC > 0: envs per workgroup fixed at compile time (LDS offsets become immediates);
+// EC == 0: taken from the launch arguments.
+template <int EC>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
+#ifdef EXP_TIMING
+  long long t_last = clock64();
+#endif
   extern __shared__ float lds[];
   const Model& M = *a.M;
   const int B = M.B, J = M.J, S = M.S, D = M.D, F = M.F;
-  const int E = a.E, N = a.N;
+  const int E = EC > 0 ? EC : a.E, N = a.N;
   const int tid = threadIdx.x;
   const int e = tid % E, idx = tid / E;
   const int env = blockIdx.x * E + e;
@@ -169,7 +265,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const bool is_body = idx < B && env_ok;
   const bool is_joint = idx < J && env_ok;
   const int obs_dim = 11 + 3 * D + F;
-  const LdsPlan P = make_plan(B, J, S, D, F, E);
+  const bool use_patch = M.terrain_kind == 1 && M.nx >= kPatch && M.ny >= kPatch;
+  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0);
   float* Lpos = lds + P.pos;
   float* Lvel = lds + P.vel;
   float* Liw = lds + P.iw;
@@ -179,10 +276,21 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   float* Lrec = lds + P.rec;
   int* Lreci = reinterpret_cast<int*>(lds + P.rec);
   int* Llist = reinterpret_cast<int*>(lds + P.list);
+  int* Lsurv = reinterpret_cast<int*>(lds + P.surv);
+  int* Lcand = reinterpret_cast<int*>(lds + P.cand);
+  float* Llam = lds + P.lam;                         // impulses of the contacts beyond one per thread
+  float* Lbest = lds + P.outc;                       // fine-search results; the sweeps reuse this space
+  int* Lbesti = reinterpret_cast<int*>(lds + P.outc) + S * E;
   float* Lu = lds + P.u;
   float* Lobs = lds + P.obs;
   int* Llim = reinterpret_cast<int*>(lds + P.lim);
   int* Lcount = reinterpret_cast<int*>(lds + P.count);
+  int* Lporg = reinterpret_cast<int*>(lds + P.porg);
+  float* Lpatch = lds + P.patch;
+  float* Lmip = lds + P.mip;
+  float* Lorg = lds + P.org;                          // env origins, [3][E]
+  int* Ltslot = reinterpret_cast<int*>(lds + P.tslot);  // slot table: body, kind
+  float* Ltbody = lds + P.tbody;                      // body table: radius, half length, axis, 1/mass
   const float h = a.h;
 
   // ---- load: body state into registers, clipped actions into LDS
@@ -225,8 +333,16 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     if (env_i < N && a.actions) uu = a.actions[(size_t)env_i * D + d];
     Lu[d * E + ee] = fminf(fmaxf(uu, -1.0f), 1.0f);
   }
-  float org[3] = {0, 0, 0};
-  if (env_ok) { org[0] = a.origins[3 * env]; org[1] = a.origins[3 * env + 1]; org[2] = a.origins[3 * env + 2]; }
+  // small copies of what the per-slot code looks up all the time
+  for (int i = tid; i < 3 * E; i += kThreads) {
+    int c = i / E, ee = i - c * E, env_i = blockIdx.x * E + ee;
+    Lorg[i] = env_i < N ? a.origins[3 * env_i + c] : 0.0f;
+  }
+  for (int i = tid; i < S; i += kThreads) { Ltslot[2 * i] = M.slots[i].body; Ltslot[2 * i + 1] = M.slots[i].kind; }
+  for (int i = tid; i < B; i += kThreads) {
+    Ltbody[4 * i] = M.bodies[i].radius; Ltbody[4 * i + 1] = M.bodies[i].half_len;
+    Ltbody[4 * i + 2] = __int_as_float(M.bodies[i].axis); Ltbody[4 * i + 3] = M.bodies[i].inv_mass;
+  }
   // contact records start cleared (a step with zero substeps packs "no contact")
   for (int i = tid; i < S * E; i += kThreads) {
     Lreci[(i / E * kRecWords + 0) * E + i % E] = 0;
@@ -235,14 +351,50 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     for (int c = 3; c < kRecWords; ++c) Lrec[(i / E * kRecWords + c) * E + i % E] = 0.0f;
   }
 
+  // per-env copy of the heightfield samples around the root body (the whole robot stays
+  // within it during one step; anything outside falls back to global memory)
+  if (use_patch) {
+    if (tid < E) {
+      int env_e = blockIdx.x * E + tid;
+      int pi0 = 0, pj0 = 0;
+      if (env_e < N) {
+        const size_t fs = (size_t)B * N;
+        float rx = a.state[0 * fs + (size_t)M.root * N + env_e] + a.origins[3 * env_e];
+        float ry = a.state[1 * fs + (size_t)M.root * N + env_e] + a.origins[3 * env_e + 1];
+        float ci = floorf((rx - M.hox) * M.inv_cell), cj = floorf((ry - M.hoy) * M.inv_cell);
+        ci = fminf(fmaxf(ci - (float)(kPatch / 2), 0.0f), (float)(M.nx - kPatch));
+        cj = fminf(fmaxf(cj - (float)(kPatch / 2), 0.0f), (float)(M.ny - kPatch));
+        pi0 = (int)ci; pj0 = (int)cj;
+      }
+      Lporg[2 * tid] = pi0; Lporg[2 * tid + 1] = pj0;
+    }
+    __syncthreads();
+    for (int i = tid; i < E * kPatch * kPatch; i += kThreads) {
+      int ee = i / (kPatch * kPatch), r = i - ee * (kPatch * kPatch), pj = r / kPatch, pi = r - pj * kPatch;
+      Lpatch[i] = a.heights[(Lporg[2 * ee + 1] + pj) * M.nx + Lporg[2 * ee] + pi];
+    }
+    __syncthreads();
+    for (int i = tid; i < E * kPatchBlocks * kPatchBlocks; i += kThreads) {
+      int ee = i / (kPatchBlocks * kPatchBlocks), r = i - ee * (kPatchBlocks * kPatchBlocks);
+      int bj = r / kPatchBlocks, bi = r - bj * kPatchBlocks;
+      float hm = -INFINITY;
+      for (int pj = bj * kMip; pj <= bj * kMip + kMip && pj < kPatch; ++pj)
+        for (int pi = bi * kMip; pi <= bi * kMip + kMip && pi < kPatch; ++pi)
+          hm = fmaxf(hm, Lpatch[ee * (kPatch * kPatch) + pj * kPatch + pi]);
+      Lmip[i] = hm;
+    }
+  }
+
+  TMARK(0);
   float R[9];
   JointRows jr;
-  ContactRows cr[KC];
-  int n_mine = 0;  // contacts owned by this thread this substep
+  ContactRows cr;
+  bool has_contact = false;  // this thread owns an active contact this substep
+  const int max_njs = M.max_joint_sides;
 
   for (int sub = 0; sub < a.substeps; ++sub) {
     // ---- A: publish pose and world inverse inertia
-    if (tid == 0) Lcount[0] = 0;
+    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
@@ -258,6 +410,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     }
     __syncthreads();
 
+    TMARK(1);
     // ---- B: joint torques (stored once per joint; the body applies the sign)
     if (is_joint) {
       const JointTab& jt = M.joints[idx];
@@ -276,38 +429,151 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       }
       for (int c = 0; c < 3; ++c) Loutj[(idx * 12 + c) * E + e] = tq[c];
     }
-    // ---- B: contact generation, one slot at a time
+    // ---- B1: every slot: plane contact, or reach test against the heightfield copy;
+    //          slots that may touch the heightfield are queued for the fine search
+    //          (end spheres from the front of the queue, mid-segments from the back)
     for (int i = tid; i < S * E; i += kThreads) {
       int ee = i % E, s = i / E;
       int env_i = blockIdx.x * E + ee;
-      ContactOut co;
-      co.active = 0; co.kind = -1; co.feat = -1; co.d = 0.0f;
-      co.n = f3{0, 0, 0}; co.rc = f3{0, 0, 0}; co.w = 0.0f;
-      if (env_i < N) {
-        const SlotTab sl = M.slots[s];
+      ContactOut co = no_contact();
+      if (env_i < N && M.contacts) {
+        const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
         float bx[3], bq[4], bo[3];
         for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
         for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
-        for (int c = 0; c < 3; ++c) bo[c] = a.origins[3 * env_i + c];
-        co = generate_contact(M, a.heights, bx, bq, sl.body, sl.kind, bo);
+        for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+        SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
+                               p_margin, bx, bq, sl.kind, bo);
+        if (M.terrain_kind == 0) {
+          co = plane_contact(g, p_margin);
+        } else {
+          Field H = make_field(M, a.heights, a.coarse);
+          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          if (slot_reach(H, g)) Lcand[atomicAdd(&Lcount[3], 1)] = i;
+        }
       }
-      Lreci[(s * kRecWords + 0) * E + ee] = co.active;
-      Lreci[(s * kRecWords + 1) * E + ee] = co.kind;
-      Lreci[(s * kRecWords + 2) * E + ee] = co.feat;
-      Lrec[(s * kRecWords + 3) * E + ee] = co.d;
-      Lrec[(s * kRecWords + 4) * E + ee] = co.n.x;
-      Lrec[(s * kRecWords + 5) * E + ee] = co.n.y;
-      Lrec[(s * kRecWords + 6) * E + ee] = co.n.z;
-      Lrec[(s * kRecWords + 7) * E + ee] = co.rc.x;
-      Lrec[(s * kRecWords + 8) * E + ee] = co.rc.y;
-      Lrec[(s * kRecWords + 9) * E + ee] = co.rc.z;
-      Lrec[(s * kRecWords + 10) * E + ee] = co.w;
       if (co.active) {
-        int pos = atomicAdd(&Lcount[0], 1);
-        Llist[pos] = i;
+        store_record(Lrec, Lreci, s, ee, E, co);
+        Llist[atomicAdd(&Lcount[0], 1)] = i;
+      } else {
+        Lreci[(s * kRecWords + 0) * E + ee] = 0;      // the other words of an inactive record are not read
+        Lrec[(s * kRecWords + 10) * E + ee] = 0.0f;
+      }
+    }
+    TMARK(2);
+    if (M.terrain_kind == 1) {
+      __syncthreads();
+      // ---- B2: fine search, kGroup lanes per queued slot; lanes split the cells (or samples)
+      //          of the reach box and the group keeps the lexicographic minimum of (d2, id).
+      //          The two kinds of slot run in separate loops so a wavefront follows one path.
+      const int grp = tid / kGroup, gl = tid % kGroup;
+      Field H = make_field(M, a.heights, a.coarse);
+      // ---- B1b: the B1 test only looked at block maxima; the lanes of a group now take the
+      //           exact maximum over the samples of the reach box and queue the slot for the
+      //           fine search (end spheres from the front, mid-segments from the back)
+      {
+        const int n_cand = Lcount[3];
+        for (int sv = grp; sv < n_cand; sv += kThreads / kGroup) {
+          const int i = Lcand[sv];
+          const int ee = i % E, s = i / E;
+          const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
+          float bx[3], bq[4], bo[3];
+          for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
+          for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
+          for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+          SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
+                                 p_margin, bx, bq, sl.kind, bo);
+          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          slot_range(H, g);
+          bool can_touch = true;
+          if (use_patch && g.i0 >= H.pi0 && g.i1 + 1 < H.pi0 + kPatch && g.j0 >= H.pj0 && g.j1 + 1 < H.pj0 + kPatch) {
+            const int ni = g.i1 - g.i0 + 2, ns = ni * (g.j1 - g.j0 + 2);
+            float hm = -INFINITY;
+            for (int c = gl; c < ns; c += kGroup)
+              hm = fmaxf(hm, H.patch[(g.j0 - H.pj0 + c / ni) * kPatch + (g.i0 - H.pi0 + c % ni)]);
+#pragma unroll
+            for (int m = kGroup / 2; m >= 1; m >>= 1) hm = fmaxf(hm, __shfl_xor(hm, m));
+            const float zl = sl.kind == 0 ? g.P0.z : (sl.kind == 1 ? g.P1.z : (g.P0.z < g.P1.z ? g.P0.z : g.P1.z));
+            can_touch = !(zl - g.Rq > hm);
+          }
+          if (can_touch && gl == 0) {
+            if (sl.kind < 2) Lsurv[atomicAdd(&Lcount[1], 1)] = i;
+            else Lsurv[S * E - 1 - atomicAdd(&Lcount[2], 1)] = i;
+          }
+        }
+      }
+      __syncthreads();
+      TMARK(10);
+      const int n_end = Lcount[1], n_mid = Lcount[2];
+#ifdef EXP_TIMING
+      if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += Lcount[3]; a.dbg[15] += n_end; a.dbg[13] += n_mid; }
+#endif
+      for (int pass = 0; pass < 2; ++pass) {
+        const int n_q = pass == 0 ? n_end : n_mid;
+        for (int sv = grp; sv < n_q; sv += kThreads / kGroup) {
+          const int qi = pass == 0 ? sv : S * E - 1 - sv;
+          const int i = Lsurv[qi];
+          const int ee = i % E, s = i / E;
+          const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
+          float bx[3], bq[4], bo[3];
+          for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
+          for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
+          for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+          SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
+                                 p_margin, bx, bq, sl.kind, bo);
+          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          slot_range(H, g);
+          float best = INFINITY;
+          int best_id = -1;
+          if (pass == 0) {
+            f3 Pc = sl.kind == 0 ? g.P0 : g.P1;
+            const float zcut = Pc.z - g.Rq;
+            const int ni = g.i1 - g.i0 + 1, nc = ni * (g.j1 - g.j0 + 1);
+            for (int c = gl; c < nc; c += kGroup) sphere_cell(H, Pc, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+          } else {
+            const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
+            const int ni = g.i1 - g.i0 + 2, nc = ni * (g.j1 - g.j0 + 2);
+            for (int c = gl; c < nc; c += kGroup) segment_vertex(H, g, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+          }
+#pragma unroll
+          for (int m = kGroup / 2; m >= 1; m >>= 1) {
+            float ob = __shfl_xor(best, m);
+            int oid = __shfl_xor(best_id, m);
+            if (oid >= 0) keep_min(ob, oid, best, best_id);
+          }
+          if (gl == 0) { Lbest[qi] = best; Lbesti[qi] = best_id; }
+        }
+        __syncthreads();
+        TMARK(11 + pass);
+      }
+      // ---- B3: one thread per queued slot turns the selected feature into a contact record
+      for (int sv = tid; sv < n_end + n_mid; sv += kThreads) {
+        const int qi = sv < n_end ? sv : S * E - 1 - (sv - n_end);
+        const int i = Lsurv[qi];
+        const int ee = i % E, s = i / E;
+        const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
+        float bx[3], bq[4], bo[3];
+        for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
+        for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
+        for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+        SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
+                               p_margin, bx, bq, sl.kind, bo);
+        if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+        ContactOut co = no_contact();
+        if (sl.kind < 2) {
+          // a centre underneath the surface overrides the nearest-triangle search
+          if (!underneath_contact(H, g, p_margin, co)) co = finish_sphere(H, g, p_margin, Lbest[qi], Lbesti[qi]);
+        } else {
+          co = finish_segment(H, g, p_margin, Lbest[qi], Lbesti[qi]);
+        }
+        if (co.active) {
+          store_record(Lrec, Lreci, s, ee, E, co);
+          Llist[atomicAdd(&Lcount[0], 1)] = i;
+        }
       }
     }
     __syncthreads();
+    TMARK(3);
 
     // ---- C: block count, forces -> velocities
     float nbf = 0.0f;
@@ -338,11 +604,16 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       for (int i = tid; i < S * E * kRecWords; i += kThreads) {
         int wd = i % kRecWords, rest = i / kRecWords, s = rest % S, ee = rest / S;
         int env_i = blockIdx.x * E + ee;
-        if (env_i < N) a.recs[((size_t)env_i * S + s) * kRecWords + wd] = Lreci[(s * kRecWords + wd) * E + ee];
+        if (env_i < N) {
+          int word = Lreci[(s * kRecWords + wd) * E + ee];
+          if (!Lreci[(s * kRecWords + 0) * E + ee]) word = (wd == 1 || wd == 2) ? -1 : 0;   // inactive: canonical record
+          a.recs[((size_t)env_i * S + s) * kRecWords + wd] = word;
+        }
       }
     }
     __syncthreads();
 
+    TMARK(4);
     // ---- D: row constants
     const int n_active = Lcount[0];
     if (is_joint) {
@@ -355,12 +626,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         for (int c = 0; c < 4; ++c) qa[c] = Lpos[(pa * 7 + 3 + c) * E + e];
         for (int c = 0; c < 6; ++c) iwa[c] = Liw[(pa * 6 + c) * E + e];
         na = Lnb[pa * E + e];
-        ima = M.bodies[pa].inv_mass;
+        ima = Ltbody[4 * pa + 3];
       }
       for (int c = 0; c < 3; ++c) xb[c] = Lpos[(pb * 7 + c) * E + e];
       for (int c = 0; c < 4; ++c) qb[c] = Lpos[(pb * 7 + 3 + c) * E + e];
       for (int c = 0; c < 6; ++c) iwb[c] = Liw[(pb * 6 + c) * E + e];
-      const float nbb = Lnb[pb * E + e], imb = M.bodies[pb].inv_mass;
+      const float nbb = Lnb[pb * E + e], imb = Ltbody[4 * pb + 3];
       float Ra[9], Rb[9], t0[3], t1[3];
       quat_to_mat(qa, Ra);
       quat_to_mat(qb, Rb);
@@ -414,47 +685,28 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         for (int c = 0; c < 3; ++c) { jr.ax[k][c] = ak[c]; jr.Za[k][c] = -na * za[c]; jr.Zb[k][c] = nbb * zb[c]; }
       }
     }
-    n_mine = 0;
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-      int li = tid + kc * kThreads;
-      if (li < n_active) {
-        ContactRows& c = cr[kc];
-        int i = Llist[li];
-        int ee = i % E, s = i / E;
-        int body = M.slots[s].body;
-        c.slot_e = s * E + ee;
-        c.body = body;
-        float d = Lrec[(s * kRecWords + 3) * E + ee];
-        float n[3], rc[3], iwb[6];
-        for (int k = 0; k < 3; ++k) { n[k] = Lrec[(s * kRecWords + 4 + k) * E + ee]; rc[k] = Lrec[(s * kRecWords + 7 + k) * E + ee]; }
-        for (int k = 0; k < 6; ++k) iwb[k] = Liw[(body * 6 + k) * E + ee];
-        float nbb = Lnb[body * E + ee] / Lrec[(s * kRecWords + 10) * E + ee], imb = M.bodies[body].inv_mass;
-        float t1[3], t2[3];
-        if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
-        else { t1[0] = -n[2]; t1[1] = 0.0f; t1[2] = n[0]; }
-        float inv = 1.0f / sqrtf(dot(t1, t1));
-        for (int k = 0; k < 3; ++k) t1[k] *= inv;
-        cross(n, t1, t2);
-        for (int k = 0; k < 3; ++k) { c.dir[0][k] = n[k]; c.dir[1][k] = t1[k]; c.dir[2][k] = t2[k]; }
-        c.ls = nbb * imb;
-        for (int r = 0; r < 3; ++r) {
-          float y[3];
-          cross(rc, c.dir[r], c.ang[r]);
-          sym_vec(iwb, c.ang[r], y);
-          float keff = nbb * (imb + dot(c.ang[r], y));
-          c.meff[r] = keff > 0.0f ? 1.0f / keff : 0.0f;
-          for (int k = 0; k < 3; ++k) c.Y[r][k] = nbb * y[k];
-          c.lam[r] = 0.0f;
-        }
-        c.bias = d >= 0.0f ? d / h : fmaxf(p_beta_c * d / h, -p_vdepen);
-        n_mine = kc + 1;
+    // contact k of the workgroup's list goes to thread kThreads-1-k (the joint threads sit at
+    // the low end); contacts beyond one per thread start from zero impulse in LDS
+    {
+      const int li = kThreads - 1 - tid;
+      has_contact = li < n_active;
+      if (has_contact) {
+        const int i = Llist[li];
+        const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
+        build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
       }
+      for (int k = kThreads + tid; k < n_active; k += kThreads)
+        for (int r = 0; r < 3; ++r) Llam[3 * (k - kThreads) + r] = 0.0f;
     }
 
+    TMARK(5);
     // ---- S: sweeps
     for (int it = 0; it < a.iterations; ++it) {
+#ifdef EXP_NOJOINT
+      if (false) {
+#else
       if (is_joint) {
+#endif
         const int pa = j_pa, pb = j_pb;
         float va[3] = {0, 0, 0}, wa[3] = {0, 0, 0}, vb[3], wb[3];
         if (pa >= 0)
@@ -491,52 +743,58 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           Loutj[(idx * 12 + 9 + c) * E + e] = wb[c];
         }
       }
-#pragma unroll
-      for (int kc = 0; kc < KC; ++kc) {
-        if (kc < n_mine) {
-          ContactRows& c = cr[kc];
-          int ee = c.slot_e % E;
-          float vv[3], ww[3];
-          for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(c.body * 6 + k) * E + ee]; ww[k] = Lvel[(c.body * 6 + 3 + k) * E + ee]; }
-          {
-            float jv = dot(c.dir[0], vv) + dot(c.ang[0], ww);
-            float dl = -c.meff[0] * (jv + c.bias);
-            float ln = fmaxf(c.lam[0] + dl, 0.0f);
-            dl = ln - c.lam[0];
-            c.lam[0] = ln;
-            for (int k = 0; k < 3; ++k) { vv[k] += c.ls * c.dir[0][k] * dl; ww[k] += c.Y[0][k] * dl; }
-          }
-          {
-            float jv1 = dot(c.dir[1], vv) + dot(c.ang[1], ww);
-            float jv2 = dot(c.dir[2], vv) + dot(c.ang[2], ww);
-            float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
-            float lim = p_mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
-            if (nrm > lim) { float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
-            float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
-            c.lam[1] = l1; c.lam[2] = l2;
-            for (int k = 0; k < 3; ++k) {
-              vv[k] += c.ls * (c.dir[1][k] * d1 + c.dir[2][k] * d2);
-              ww[k] += c.Y[1][k] * d1 + c.Y[2][k] * d2;
-            }
-          }
-          int s = c.slot_e / E;
-          for (int k = 0; k < 3; ++k) { Loutc[(s * 6 + k) * E + ee] = vv[k]; Loutc[(s * 6 + 3 + k) * E + ee] = ww[k]; }
-        }
+#ifdef EXP_NOCONTACT
+      if (false) {
+#else
+      if (has_contact) {
+#endif
+        const int ee = cr.slot_e % E, sl = cr.slot_e / E;
+        float vv[3], ww[3];
+        for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(cr.body * 6 + k) * E + ee]; ww[k] = Lvel[(cr.body * 6 + 3 + k) * E + ee]; }
+        relax_contact(cr, p_mu, vv, ww);
+        for (int k = 0; k < 3; ++k) { Loutc[(sl * 6 + k) * E + ee] = vv[k]; Loutc[(sl * 6 + 3 + k) * E + ee] = ww[k]; }
+      }
+      for (int k = kThreads + (kThreads - 1 - tid); k < n_active; k += kThreads) {
+        // rare: more active contacts in the workgroup than threads; rows rebuilt from the record
+        const int i = Llist[k];
+        const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
+        ContactRows c2;
+        build_contact_rows(c2, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
+        for (int r = 0; r < 3; ++r) c2.lam[r] = Llam[3 * (k - kThreads) + r];
+        float vv[3], ww[3];
+        for (int r = 0; r < 3; ++r) { vv[r] = Lvel[(body * 6 + r) * E + ee]; ww[r] = Lvel[(body * 6 + 3 + r) * E + ee]; }
+        relax_contact(c2, p_mu, vv, ww);
+        for (int r = 0; r < 3; ++r) Llam[3 * (k - kThreads) + r] = c2.lam[r];
+        for (int r = 0; r < 3; ++r) { Loutc[(sl * 6 + r) * E + ee] = vv[r]; Loutc[(sl * 6 + 3 + r) * E + ee] = ww[r]; }
       }
       __syncthreads();
       // every body averages the private copies of its blocks (static order)
+#ifdef EXP_NOGATHER
+      if (false) {
+#else
       if (is_body && nbf > 0.0f) {
+#endif
+        // all loads are unconditional (unused entries read a valid dummy location and are
+        // discarded by a select) so that they are issued together and waited for once
         float acc[6] = {0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < kMaxBodyJoints; ++k) {
-          if (k < my_njs)
-            for (int c = 0; c < 6; ++c) acc[c] += Loutj[my_js_off[k] + c * E];
+          if (k < max_njs) {  // uniform across the workgroup
+            const int off = k < my_njs ? my_js_off[k] : e;
+            for (int c = 0; c < 6; ++c) {
+              float val = Loutj[off + c * E];
+              acc[c] += k < my_njs ? val : 0.0f;
+            }
+          }
         }
-        for (int k = 0; k < my_nslots; ++k) {
-          int s = my_slot0 + k;
-          float wk = Lrec[(s * kRecWords + 10) * E + e];
-          if (wk > 0.0f)
-            for (int c = 0; c < 6; ++c) acc[c] += wk * Loutc[(s * 6 + c) * E + e];
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          const int sl = my_slot0 + (k < my_nslots ? k : 0);
+          float wk = k < my_nslots ? Lrec[(sl * kRecWords + 10) * E + e] : 0.0f;
+          for (int c = 0; c < 6; ++c) {
+            float val = Loutc[(sl * 6 + c) * E + e];
+            acc[c] += wk > 0.0f ? wk * val : 0.0f;
+          }
         }
         float inb = 1.0f / nbf;
         for (int c = 0; c < 3; ++c) {
@@ -547,6 +805,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       __syncthreads();
     }
 
+    TMARK(6);
     // ---- E: damping, angular-velocity cap, positions
     if (is_body) {
       float dl = 1.0f / (1.0f + h * p_clin), da = 1.0f / (1.0f + h * p_cang);
@@ -565,10 +824,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       for (int c = 0; c < 4; ++c) q[c] *= inv;
     }
     __syncthreads();  // the next substep overwrites pose, counters and lists read above
+    TMARK(7);
   }
 
   // ---- store state, publish final pose/velocity for packing
   __syncthreads();
+  TMARK(8);
   if (is_body) {
     float* st = a.state + (size_t)b * N + env;
     const size_t fs = (size_t)B * N;
@@ -672,6 +933,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     const int n_here = min(E, N - env0);
     for (int i = tid; i < n_here * obs_dim; i += kThreads) a.obs[(size_t)env0 * obs_dim + i] = Lobs[i];
   }
+  TMARK(9);
 }
 
 }  // namespace sim355
