@@ -59,7 +59,7 @@ struct StepArgs {
 };
 
 struct LdsPlan {
-  int pos, vel, iw, nb, outj, outc, rec, list, surv, cand, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, total;
+  int pos, vel, iw, nb, outj, outc, tjs, rec, list, surv, cand, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, total;
 };
 
 __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch) {
@@ -71,11 +71,12 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.nb = o; o += B * E;
   p.outj = o; o += J * 12 * E;
   p.outc = o; o += S * 6 * E;
+  p.tjs = o; o += B * (kMaxBodyJoints + 3);
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
   p.surv = o; o += S * E;
   p.cand = o; o += S * E;
-  p.lam = o; o += 3 * (S * E > kThreads ? S * E - kThreads : 0);
+  p.lam = o; o += 3 * (S * E > kThreads - ((J * E + 63) / 64) * 64 ? S * E - (kThreads - ((J * E + 63) / 64) * 64) : 0);
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
   p.lim = o; o += (D > 0 ? D : 1) * E;
@@ -84,6 +85,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.org = o; o += 3 * E;
   p.tslot = o; o += 2 * S;
   p.tbody = o; o += 4 * B;
+  p.tin = o; o += 6 * B;
   p.patch = o; o += with_patch ? E * kPatch * kPatch : 0;
   p.mip = o; o += with_patch ? E * kPatchBlocks * kPatchBlocks : 0;
   p.total = o;
@@ -273,6 +275,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   float* Lnb = lds + P.nb;
   float* Loutj = lds + P.outj;
   float* Loutc = lds + P.outc;
+  int* Ltjs = reinterpret_cast<int*>(lds + P.tjs);  // body table: joint-side count, slot0, slot count, joint sides
   float* Lrec = lds + P.rec;
   int* Lreci = reinterpret_cast<int*>(lds + P.rec);
   int* Llist = reinterpret_cast<int*>(lds + P.list);
@@ -291,14 +294,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   float* Lorg = lds + P.org;                          // env origins, [3][E]
   int* Ltslot = reinterpret_cast<int*>(lds + P.tslot);  // slot table: body, kind
   float* Ltbody = lds + P.tbody;                      // body table: radius, half length, axis, 1/mass
+  float* Ltin = lds + P.tin;                          // body table: inertia(3), inverse inertia(3)
   const float h = a.h;
 
   // ---- load: body state into registers, clipped actions into LDS
   float x[3] = {0, 0, 0}, q[4] = {1, 0, 0, 0}, v[3] = {0, 0, 0}, w[3] = {0, 0, 0};
-  float inv_m = 0, Ib[3] = {1, 1, 1}, invIb[3] = {0, 0, 0};
   int my_slot0 = 0, my_nslots = 0, my_njs = 0;
-  int my_js_off[kMaxBodyJoints], my_js_tq[kMaxBodyJoints];
-  float my_js_sign[kMaxBodyJoints];
   const int b = idx;
   if (is_body) {
     const float* st = a.state + (size_t)b * N + env;
@@ -308,16 +309,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     v[0] = st[7 * fs]; v[1] = st[8 * fs]; v[2] = st[9 * fs];
     w[0] = st[10 * fs]; w[1] = st[11 * fs]; w[2] = st[12 * fs];
     const BodyTab& bt = M.bodies[b];
-    inv_m = bt.inv_mass;
-    for (int c = 0; c < 3; ++c) { Ib[c] = bt.inertia[c]; invIb[c] = bt.inv_inertia[c]; }
     my_slot0 = bt.slot0; my_nslots = bt.n_slots; my_njs = bt.n_joint_sides;
-#pragma unroll
-    for (int k = 0; k < kMaxBodyJoints; ++k) {
-      int js = bt.joint_sides[k];
-      my_js_off[k] = ((js >> 1) * 12 + (js & 1) * 6) * E + e;   // LDS offset of that joint side's copy
-      my_js_tq[k] = (js >> 1) * 12 * E + e;                       // LDS offset of that joint's torque
-      my_js_sign[k] = (js & 1) ? 1.0f : -1.0f;
-    }
   }
   // uniform parameters and this thread's joint, read once
   const float g0 = M.g[0], g1 = M.g[1], g2 = M.g[2];
@@ -342,6 +334,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   for (int i = tid; i < B; i += kThreads) {
     Ltbody[4 * i] = M.bodies[i].radius; Ltbody[4 * i + 1] = M.bodies[i].half_len;
     Ltbody[4 * i + 2] = __int_as_float(M.bodies[i].axis); Ltbody[4 * i + 3] = M.bodies[i].inv_mass;
+    for (int c = 0; c < 3; ++c) { Ltin[6 * i + c] = M.bodies[i].inertia[c]; Ltin[6 * i + 3 + c] = M.bodies[i].inv_inertia[c]; }
+  }
+  for (int i = tid; i < B; i += kThreads) {
+    int* t = Ltjs + i * (kMaxBodyJoints + 3);
+    t[0] = M.bodies[i].n_joint_sides; t[1] = M.bodies[i].slot0; t[2] = M.bodies[i].n_slots;
+    for (int k = 0; k < kMaxBodyJoints; ++k) t[3 + k] = M.bodies[i].joint_sides[k];
   }
   // contact records start cleared (a step with zero substeps packs "no contact")
   for (int i = tid; i < S * E; i += kThreads) {
@@ -386,7 +384,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   }
 
   TMARK(0);
-  float R[9];
+  // wavefronts [0, joint_threads/64) hold the joint threads; contact k of a workgroup goes to
+  // thread kThreads-1-k as long as that thread is not in a joint wavefront (n_reg contacts)
+  const int joint_threads = ((J * E + 63) / 64) * 64;
+  const int n_reg = kThreads - joint_threads;
+  const bool joint_wave = __builtin_amdgcn_readfirstlane(tid) < joint_threads;
   JointRows jr;
   ContactRows cr;
   bool has_contact = false;  // this thread owns an active contact this substep
@@ -398,7 +400,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
+      // velocities are parked in LDS as well: nothing of the body stays in registers while the
+      // contact phases run
+      for (int c = 0; c < 3; ++c) { Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c]; }
+      float R[9], invIb[3];
       quat_to_mat(q, R);
+      for (int c = 0; c < 3; ++c) invIb[c] = Ltin[6 * b + 3 + c];
       float iw[6];
       iw[0] = R[0] * R[0] * invIb[0] + R[1] * R[1] * invIb[1] + R[2] * R[2] * invIb[2];
       iw[1] = R[0] * R[3] * invIb[0] + R[1] * R[4] * invIb[1] + R[2] * R[5] * invIb[2];
@@ -582,11 +589,16 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       for (int k = 0; k < my_nslots; ++k) nbf += Lrec[((my_slot0 + k) * kRecWords + 10) * E + e];
       Lnb[b * E + e] = nbf;
       float tau[3] = {0, 0, 0};
-#pragma unroll
-      for (int k = 0; k < kMaxBodyJoints; ++k) {
-        if (k < my_njs)
-          for (int c = 0; c < 3; ++c) tau[c] += my_js_sign[k] * Loutj[my_js_tq[k] + c * E];
+      for (int k = 0; k < my_njs; ++k) {
+        const int js = Ltjs[b * (kMaxBodyJoints + 3) + 3 + k];
+        const float sg = (js & 1) ? 1.0f : -1.0f;
+        for (int c = 0; c < 3; ++c) tau[c] += sg * Loutj[((js >> 1) * 12 + c) * E + e];
       }
+      float R[9], qq[4], Ib[3], invIb[3];
+      for (int c = 0; c < 4; ++c) qq[c] = Lpos[(b * 7 + 3 + c) * E + e];
+      quat_to_mat(qq, R);
+      for (int c = 0; c < 3; ++c) { Ib[c] = Ltin[6 * b + c]; invIb[c] = Ltin[6 * b + 3 + c]; }
+      for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * 6 + c) * E + e]; w[c] = Lvel[(b * 6 + 3 + c) * E + e]; }
       v[0] += h * g0; v[1] += h * g1; v[2] += h * g2;
       float wb[3], tb[3];
       mat_t_vec(R, w, wb);
@@ -689,125 +701,136 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     // the low end); contacts beyond one per thread start from zero impulse in LDS
     {
       const int li = kThreads - 1 - tid;
-      has_contact = li < n_active;
+      has_contact = li < n_active && li < n_reg;
       if (has_contact) {
         const int i = Llist[li];
         const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
         build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
       }
-      for (int k = kThreads + tid; k < n_active; k += kThreads)
-        for (int r = 0; r < 3; ++r) Llam[3 * (k - kThreads) + r] = 0.0f;
+      for (int k = n_reg + tid; k < n_active; k += kThreads)
+        for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = 0.0f;
     }
 
     TMARK(5);
+    // offsets of the copies this body averages (from the LDS table; only alive during the sweeps)
+    int gat_off[kMaxBodyJoints];
+#pragma unroll
+    for (int k = 0; k < kMaxBodyJoints; ++k) {
+      int js = is_body && k < max_njs ? Ltjs[b * (kMaxBodyJoints + 3) + 3 + k] : 0;
+      gat_off[k] = ((js >> 1) * 12 + (js & 1) * 6) * E + e;
+    }
     // ---- S: sweeps
-    for (int it = 0; it < a.iterations; ++it) {
-#ifdef EXP_NOJOINT
-      if (false) {
-#else
-      if (is_joint) {
-#endif
-        const int pa = j_pa, pb = j_pb;
-        float va[3] = {0, 0, 0}, wa[3] = {0, 0, 0}, vb[3], wb[3];
-        if (pa >= 0)
-          for (int c = 0; c < 3; ++c) { va[c] = Lvel[(pa * 6 + c) * E + e]; wa[c] = Lvel[(pa * 6 + 3 + c) * E + e]; }
-        for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * 6 + c) * E + e]; wb[c] = Lvel[(pb * 6 + 3 + c) * E + e]; }
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-          float ex[3] = {k == 0 ? 1.0f : 0.0f, k == 1 ? 1.0f : 0.0f, k == 2 ? 1.0f : 0.0f};
-          float ca[3], cb[3];
-          cross(jr.ra, ex, ca);
-          cross(jr.rb, ex, cb);
-          float jv = (vb[k] - va[k]) + dot(cb, wb) - dot(ca, wa);
-          float dl = -jr.pmeff[k] * (jv + jr.pbias[k]);
-          va[k] -= jr.sa * dl;
-          vb[k] += jr.sb * dl;
-          for (int c = 0; c < 3; ++c) { wa[c] += jr.Ya[k][c] * dl; wb[c] += jr.Yb[k][c] * dl; }
-        }
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-          float dw[3] = {wb[0] - wa[0], wb[1] - wa[1], wb[2] - wa[2]};
-          float jv = dot(jr.ax[k], dw);
-          float dl = -jr.ameff[k] * (jv + jr.abias[k]);
-          if (jr.onesided & (1 << k)) {
-            float ln = fmaxf(jr.lam[k] + dl, 0.0f);
-            dl = ln - jr.lam[k];
-            jr.lam[k] = ln;
-          }
-          for (int c = 0; c < 3; ++c) { wa[c] += jr.Za[k][c] * dl; wb[c] += jr.Zb[k][c] * dl; }
-        }
-        for (int c = 0; c < 3; ++c) {
-          Loutj[(idx * 12 + c) * E + e] = va[c];
-          Loutj[(idx * 12 + 3 + c) * E + e] = wa[c];
-          Loutj[(idx * 12 + 6 + c) * E + e] = vb[c];
-          Loutj[(idx * 12 + 9 + c) * E + e] = wb[c];
-        }
-      }
-#ifdef EXP_NOCONTACT
-      if (false) {
-#else
-      if (has_contact) {
-#endif
-        const int ee = cr.slot_e % E, sl = cr.slot_e / E;
-        float vv[3], ww[3];
-        for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(cr.body * 6 + k) * E + ee]; ww[k] = Lvel[(cr.body * 6 + 3 + k) * E + ee]; }
-        relax_contact(cr, p_mu, vv, ww);
-        for (int k = 0; k < 3; ++k) { Loutc[(sl * 6 + k) * E + ee] = vv[k]; Loutc[(sl * 6 + 3 + k) * E + ee] = ww[k]; }
-      }
-      for (int k = kThreads + (kThreads - 1 - tid); k < n_active; k += kThreads) {
-        // rare: more active contacts in the workgroup than threads; rows rebuilt from the record
-        const int i = Llist[k];
-        const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
-        ContactRows c2;
-        build_contact_rows(c2, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
-        for (int r = 0; r < 3; ++r) c2.lam[r] = Llam[3 * (k - kThreads) + r];
-        float vv[3], ww[3];
-        for (int r = 0; r < 3; ++r) { vv[r] = Lvel[(body * 6 + r) * E + ee]; ww[r] = Lvel[(body * 6 + 3 + r) * E + ee]; }
-        relax_contact(c2, p_mu, vv, ww);
-        for (int r = 0; r < 3; ++r) Llam[3 * (k - kThreads) + r] = c2.lam[r];
-        for (int r = 0; r < 3; ++r) { Loutc[(sl * 6 + r) * E + ee] = vv[r]; Loutc[(sl * 6 + 3 + r) * E + ee] = ww[r]; }
-      }
-      __syncthreads();
-      // every body averages the private copies of its blocks (static order)
-#ifdef EXP_NOGATHER
-      if (false) {
-#else
-      if (is_body && nbf > 0.0f) {
-#endif
-        // all loads are unconditional (unused entries read a valid dummy location and are
-        // discarded by a select) so that they are issued together and waited for once
-        float acc[6] = {0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int k = 0; k < kMaxBodyJoints; ++k) {
-          if (k < max_njs) {  // uniform across the workgroup
-            const int off = k < my_njs ? my_js_off[k] : e;
-            for (int c = 0; c < 6; ++c) {
-              float val = Loutj[off + c * E];
-              acc[c] += k < my_njs ? val : 0.0f;
+    // Wavefronts that hold joint threads run only the joint rows, the others only the contact
+    // rows (a wave-uniform branch, so neither path carries the other's registers); both paths
+    // execute the same two barriers per sweep.
+    auto gather = [&]() {
+        if (is_body && nbf > 0.0f) {
+          // all loads are unconditional (unused entries read a valid dummy location and are
+          // discarded by a select) so that they are issued together and waited for once
+          float acc[6] = {0, 0, 0, 0, 0, 0};
+  #pragma unroll
+          for (int k = 0; k < kMaxBodyJoints; ++k) {
+            if (k < max_njs) {  // uniform across the workgroup
+              const int off = k < my_njs ? gat_off[k] : e;
+              for (int c = 0; c < 6; ++c) {
+                float val = Loutj[off + c * E];
+                acc[c] += k < my_njs ? val : 0.0f;
+              }
             }
           }
-        }
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-          const int sl = my_slot0 + (k < my_nslots ? k : 0);
-          float wk = k < my_nslots ? Lrec[(sl * kRecWords + 10) * E + e] : 0.0f;
-          for (int c = 0; c < 6; ++c) {
-            float val = Loutc[(sl * 6 + c) * E + e];
-            acc[c] += wk > 0.0f ? wk * val : 0.0f;
+  #pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            const int sl = my_slot0 + (k < my_nslots ? k : 0);
+            float wk = k < my_nslots ? Lrec[(sl * kRecWords + 10) * E + e] : 0.0f;
+            for (int c = 0; c < 6; ++c) {
+              float val = Loutc[(sl * 6 + c) * E + e];
+              acc[c] += wk > 0.0f ? wk * val : 0.0f;
+            }
+          }
+          float inb = 1.0f / nbf;
+          for (int c = 0; c < 3; ++c) {
+            v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
+            Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c];
           }
         }
-        float inb = 1.0f / nbf;
-        for (int c = 0; c < 3; ++c) {
-          v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
-          Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c];
+    };
+    if (joint_wave) {
+      for (int it = 0; it < a.iterations; ++it) {
+        if (is_joint) {
+          const int pa = j_pa, pb = j_pb;
+          float va[3] = {0, 0, 0}, wa[3] = {0, 0, 0}, vb[3], wb[3];
+          if (pa >= 0)
+            for (int c = 0; c < 3; ++c) { va[c] = Lvel[(pa * 6 + c) * E + e]; wa[c] = Lvel[(pa * 6 + 3 + c) * E + e]; }
+          for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * 6 + c) * E + e]; wb[c] = Lvel[(pb * 6 + 3 + c) * E + e]; }
+  #pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            float ex[3] = {k == 0 ? 1.0f : 0.0f, k == 1 ? 1.0f : 0.0f, k == 2 ? 1.0f : 0.0f};
+            float ca[3], cb[3];
+            cross(jr.ra, ex, ca);
+            cross(jr.rb, ex, cb);
+            float jv = (vb[k] - va[k]) + dot(cb, wb) - dot(ca, wa);
+            float dl = -jr.pmeff[k] * (jv + jr.pbias[k]);
+            va[k] -= jr.sa * dl;
+            vb[k] += jr.sb * dl;
+            for (int c = 0; c < 3; ++c) { wa[c] += jr.Ya[k][c] * dl; wb[c] += jr.Yb[k][c] * dl; }
+          }
+  #pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            float dw[3] = {wb[0] - wa[0], wb[1] - wa[1], wb[2] - wa[2]};
+            float jv = dot(jr.ax[k], dw);
+            float dl = -jr.ameff[k] * (jv + jr.abias[k]);
+            if (jr.onesided & (1 << k)) {
+              float ln = fmaxf(jr.lam[k] + dl, 0.0f);
+              dl = ln - jr.lam[k];
+              jr.lam[k] = ln;
+            }
+            for (int c = 0; c < 3; ++c) { wa[c] += jr.Za[k][c] * dl; wb[c] += jr.Zb[k][c] * dl; }
+          }
+          for (int c = 0; c < 3; ++c) {
+            Loutj[(idx * 12 + c) * E + e] = va[c];
+            Loutj[(idx * 12 + 3 + c) * E + e] = wa[c];
+            Loutj[(idx * 12 + 6 + c) * E + e] = vb[c];
+            Loutj[(idx * 12 + 9 + c) * E + e] = wb[c];
+          }
         }
+        __syncthreads();
+        gather();
+        __syncthreads();
       }
-      __syncthreads();
+    } else {
+      for (int it = 0; it < a.iterations; ++it) {
+        if (has_contact) {
+          const int ee = cr.slot_e % E, sl = cr.slot_e / E;
+          float vv[3], ww[3];
+          for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(cr.body * 6 + k) * E + ee]; ww[k] = Lvel[(cr.body * 6 + 3 + k) * E + ee]; }
+          relax_contact(cr, p_mu, vv, ww);
+          for (int k = 0; k < 3; ++k) { Loutc[(sl * 6 + k) * E + ee] = vv[k]; Loutc[(sl * 6 + 3 + k) * E + ee] = ww[k]; }
+        }
+        for (int k = n_reg + (kThreads - 1 - tid); k < n_active; k += n_reg) {
+          // rare: more active contacts in the workgroup than threads; rows rebuilt from the record
+          const int i = Llist[k];
+          const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
+          ContactRows c2;
+          build_contact_rows(c2, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
+          for (int r = 0; r < 3; ++r) c2.lam[r] = Llam[3 * (k - n_reg) + r];
+          float vv[3], ww[3];
+          for (int r = 0; r < 3; ++r) { vv[r] = Lvel[(body * 6 + r) * E + ee]; ww[r] = Lvel[(body * 6 + 3 + r) * E + ee]; }
+          relax_contact(c2, p_mu, vv, ww);
+          for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = c2.lam[r];
+          for (int r = 0; r < 3; ++r) { Loutc[(sl * 6 + r) * E + ee] = vv[r]; Loutc[(sl * 6 + 3 + r) * E + ee] = ww[r]; }
+        }
+        __syncthreads();
+        gather();
+        __syncthreads();
+      }
     }
 
     TMARK(6);
     // ---- E: damping, angular-velocity cap, positions
     if (is_body) {
+      // the pose was parked in LDS during the sweeps (unchanged since phase A)
+      for (int c = 0; c < 3; ++c) x[c] = Lpos[(b * 7 + c) * E + e];
+      for (int c = 0; c < 4; ++c) q[c] = Lpos[(b * 7 + 3 + c) * E + e];
       float dl = 1.0f / (1.0f + h * p_clin), da = 1.0f / (1.0f + h * p_cang);
       for (int c = 0; c < 3; ++c) { v[c] *= dl; w[c] *= da; }
       float wn = sqrtf(dot(w, w));
