@@ -271,6 +271,20 @@ __device__ __forceinline__ bool slot_reach(const Field& H, SlotGeom& g) {
           int I = I0 + di < I1 ? I0 + di : I1, J = J0 + dj < J1 ? J0 + dj : J1;
           hmax = fmaxf(hmax, H.mip[J * nb + I]);
         }
+      // block maxima say "maybe": take the exact maximum over the samples of the box when it
+      // is at most 6 x 6 (all 36 reads are issued together, indices clamped into the box)
+      const int ni = g.i1 - g.i0 + 2, nj = g.j1 - g.j0 + 2;
+      if (!(zcut > hmax) && ni <= 6 && nj <= 6) {
+        const int bi = g.i0 - H.pi0, bj = g.j0 - H.pj0;
+        hmax = -INFINITY;
+#pragma unroll
+        for (int dj = 0; dj < 6; ++dj)
+#pragma unroll
+          for (int di = 0; di < 6; ++di) {
+            int pi = bi + (di < ni ? di : ni - 1), pj = bj + (dj < nj ? dj : nj - 1);
+            hmax = fmaxf(hmax, H.patch[pj * H.ps + pi]);
+          }
+      }
     } else {
       for (int J = J0; J <= J1; ++J)
         for (int I = I0; I <= I1; ++I) hmax = fmaxf(hmax, H.mip[J * nb + I]);
@@ -338,6 +352,18 @@ __device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float zcut, in
 // The up-to-three edges that start at sample (i,j) against the segment interior.
 __device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g, float zcut, int i, int j,
                                                float& best, int& best_id) {
+  {
+    // The three edges lie in the square of cell (i,j), within 0.7072 cell of its centre; if the
+    // centre is further than reach + 0.7072 cell (+ slack) from the segment's line in the xy plane,
+    // or beyond its ends by that much, none of them can reach the margin.
+    float cx = H.ox + ((float)i + 0.5f) * H.cell, cy = H.oy + ((float)j + 0.5f) * H.cell;
+    float dx = g.P1.x - g.P0.x, dy = g.P1.y - g.P0.y, rx = cx - g.P0.x, ry = cy - g.P0.y;
+    float L2 = dx * dx + dy * dy, rr = g.Rq + 0.7072f * H.cell + kSelSlack;
+    float cr = dx * ry - dy * rx, al = dx * rx + dy * ry, lim = rr * rr * L2;
+    if (cr * cr > lim) return;
+    if (al < 0.0f && al * al > lim) return;
+    if (al > L2 && (al - L2) * (al - L2) > lim) return;
+  }
   f3 Q0 = field_vertex(H, i, j);
 #pragma unroll
   for (int k = 0; k < 3; ++k) {

@@ -59,7 +59,7 @@ struct StepArgs {
 };
 
 struct LdsPlan {
-  int pos, vel, iw, nb, outj, outc, tjs, rec, list, surv, cand, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, total;
+  int pos, vel, iw, nb, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, total;
 };
 
 __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch) {
@@ -75,7 +75,6 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
   p.surv = o; o += S * E;
-  p.cand = o; o += S * E;
   p.lam = o; o += 3 * (S * E > kThreads - ((J * E + 63) / 64) * 64 ? S * E - (kThreads - ((J * E + 63) / 64) * 64) : 0);
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
@@ -280,7 +279,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   int* Lreci = reinterpret_cast<int*>(lds + P.rec);
   int* Llist = reinterpret_cast<int*>(lds + P.list);
   int* Lsurv = reinterpret_cast<int*>(lds + P.surv);
-  int* Lcand = reinterpret_cast<int*>(lds + P.cand);
   float* Llam = lds + P.lam;                         // impulses of the contacts beyond one per thread
   float* Lbest = lds + P.outc;                       // fine-search results; the sweeps reuse this space
   int* Lbesti = reinterpret_cast<int*>(lds + P.outc) + S * E;
@@ -396,7 +394,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 
   for (int sub = 0; sub < a.substeps; ++sub) {
     // ---- A: publish pose and world inverse inertia
-    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; }
+    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
@@ -437,8 +435,9 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       for (int c = 0; c < 3; ++c) Loutj[(idx * 12 + c) * E + e] = tq[c];
     }
     // ---- B1: every slot: plane contact, or reach test against the heightfield copy;
-    //          slots that may touch the heightfield are queued for the fine search
-    //          (end spheres from the front of the queue, mid-segments from the back)
+    //          slots that may touch the heightfield (block maxima, then the exact maximum over
+    //          the box) are queued for the fine search: end spheres from the front of the
+    //          queue, mid-segments from the back
     for (int i = tid; i < S * E; i += kThreads) {
       int ee = i % E, s = i / E;
       int env_i = blockIdx.x * E + ee;
@@ -456,7 +455,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         } else {
           Field H = make_field(M, a.heights, a.coarse);
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
-          if (slot_reach(H, g)) Lcand[atomicAdd(&Lcount[3], 1)] = i;
+          if (slot_reach(H, g)) {
+            if (sl.kind < 2) Lsurv[atomicAdd(&Lcount[1], 1)] = i;
+            else Lsurv[S * E - 1 - atomicAdd(&Lcount[2], 1)] = i;
+          }
         }
       }
       if (co.active) {
@@ -475,42 +477,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       //          The two kinds of slot run in separate loops so a wavefront follows one path.
       const int grp = tid / kGroup, gl = tid % kGroup;
       Field H = make_field(M, a.heights, a.coarse);
-      // ---- B1b: the B1 test only looked at block maxima; the lanes of a group now take the
-      //           exact maximum over the samples of the reach box and queue the slot for the
-      //           fine search (end spheres from the front, mid-segments from the back)
-      {
-        const int n_cand = Lcount[3];
-        for (int sv = grp; sv < n_cand; sv += kThreads / kGroup) {
-          const int i = Lcand[sv];
-          const int ee = i % E, s = i / E;
-          const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
-          float bx[3], bq[4], bo[3];
-          for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
-          for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
-          for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
-          SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
-                                 p_margin, bx, bq, sl.kind, bo);
-          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
-          slot_range(H, g);
-          bool can_touch = true;
-          if (use_patch && g.i0 >= H.pi0 && g.i1 + 1 < H.pi0 + kPatch && g.j0 >= H.pj0 && g.j1 + 1 < H.pj0 + kPatch) {
-            const int ni = g.i1 - g.i0 + 2, ns = ni * (g.j1 - g.j0 + 2);
-            float hm = -INFINITY;
-            for (int c = gl; c < ns; c += kGroup)
-              hm = fmaxf(hm, H.patch[(g.j0 - H.pj0 + c / ni) * kPatch + (g.i0 - H.pi0 + c % ni)]);
-#pragma unroll
-            for (int m = kGroup / 2; m >= 1; m >>= 1) hm = fmaxf(hm, __shfl_xor(hm, m));
-            const float zl = sl.kind == 0 ? g.P0.z : (sl.kind == 1 ? g.P1.z : (g.P0.z < g.P1.z ? g.P0.z : g.P1.z));
-            can_touch = !(zl - g.Rq > hm);
-          }
-          if (can_touch && gl == 0) {
-            if (sl.kind < 2) Lsurv[atomicAdd(&Lcount[1], 1)] = i;
-            else Lsurv[S * E - 1 - atomicAdd(&Lcount[2], 1)] = i;
-          }
-        }
-      }
-      __syncthreads();
-      TMARK(10);
       const int n_end = Lcount[1], n_mid = Lcount[2];
 #ifdef EXP_TIMING
       if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += Lcount[3]; a.dbg[15] += n_end; a.dbg[13] += n_mid; }
