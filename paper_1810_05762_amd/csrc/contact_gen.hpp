@@ -65,6 +65,20 @@ __device__ __forceinline__ float field_height(const Field& H, int i, int j) {
   return H.h[j * H.nx + i];
 }
 
+// Heights of the four corners of cell (i,j) with a single inside-the-copy test, so the four
+// reads are issued together.
+__device__ __forceinline__ void field_cell_heights(const Field& H, int i, int j, float& h00, float& h10,
+                                                   float& h11, float& h01) {
+  unsigned di = (unsigned)(i - H.pi0), dj = (unsigned)(j - H.pj0);
+  if (di + 1u < (unsigned)H.ps && dj + 1u < (unsigned)H.ps) {
+    const lds_float* p = H.patch + dj * H.ps + di;
+    h00 = p[0]; h10 = p[1]; h01 = p[H.ps]; h11 = p[H.ps + 1];
+  } else {
+    const float* p = H.h + j * H.nx + i;
+    h00 = p[0]; h10 = p[1]; h01 = p[H.nx]; h11 = p[H.nx + 1];
+  }
+}
+
 __device__ __forceinline__ f3 field_vertex(const Field& H, int i, int j) {
   float fx = (float)i * H.cell, fy = (float)j * H.cell;
   return f3{H.ox + fx, H.oy + fy, field_height(H, i, j)};
@@ -332,10 +346,13 @@ __device__ __forceinline__ void keep_min(float d2, int id, float& best, int& bes
 __device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float zcut, int i, int j, float& best,
                                             int& best_id) {
   const int ncx = H.nx - 1;
-  f3 A = field_vertex(H, i, j), B1 = field_vertex(H, i + 1, j), C1 = field_vertex(H, i + 1, j + 1),
-     D1 = field_vertex(H, i, j + 1);
-  float zmax = fmaxf(fmaxf(A.z, B1.z), fmaxf(C1.z, D1.z));
+  float h00, h10, h11, h01;
+  field_cell_heights(H, i, j, h00, h10, h11, h01);
+  float zmax = fmaxf(fmaxf(h00, h10), fmaxf(h11, h01));
   if (zcut > zmax) return;  // whole cell further than r + margin + slack below the sphere
+  float x0 = H.ox + (float)i * H.cell, x1 = H.ox + (float)(i + 1) * H.cell;
+  float y0 = H.oy + (float)j * H.cell, y1 = H.oy + (float)(j + 1) * H.cell;
+  f3 A = f3{x0, y0, h00}, B1 = f3{x1, y0, h10}, C1 = f3{x1, y1, h11}, D1 = f3{x0, y1, h01};
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     f3 Bv = t == 0 ? B1 : C1, Cv = t == 0 ? C1 : D1;
@@ -364,12 +381,23 @@ __device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g
     if (al < 0.0f && al * al > lim) return;
     if (al > L2 && (al - L2) * (al - L2) > lim) return;
   }
-  f3 Q0 = field_vertex(H, i, j);
+  // corner heights of cell (i,j); at the far border of the box the missing neighbours are
+  // not read (their edges are excluded below)
+  float h00, h10 = 0.0f, h11 = 0.0f, h01 = 0.0f;
+  if (i <= g.i1 && j <= g.j1) field_cell_heights(H, i, j, h00, h10, h11, h01);
+  else {
+    h00 = field_height(H, i, j);
+    if (i <= g.i1) h10 = field_height(H, i + 1, j);
+    if (j <= g.j1) h01 = field_height(H, i, j + 1);
+  }
+  float x0 = H.ox + (float)i * H.cell, x1 = H.ox + (float)(i + 1) * H.cell;
+  float y0 = H.oy + (float)j * H.cell, y1 = H.oy + (float)(j + 1) * H.cell;
+  f3 Q0 = f3{x0, y0, h00};
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
     if ((k == 0 || k == 2) && i > g.i1) continue;
     if ((k == 1 || k == 2) && j > g.j1) continue;
-    f3 Q1 = k == 0 ? field_vertex(H, i + 1, j) : (k == 1 ? field_vertex(H, i, j + 1) : field_vertex(H, i + 1, j + 1));
+    f3 Q1 = k == 0 ? f3{x1, y0, h10} : (k == 1 ? f3{x0, y1, h01} : f3{x1, y1, h11});
     if (zcut > fmaxf(Q0.z, Q1.z)) continue;  // edge entirely out of reach below the capsule
     float s, t;
     seg_edge_st(g.P0, g.P1, Q0, Q1, s, t);

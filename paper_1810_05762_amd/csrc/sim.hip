@@ -357,7 +357,10 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds_bytes, st, a);
     return SIM_OK;
   };
-  int lrc = s->E == 16 ? launch(&step_kernel<16>) : (s->E == 8 ? launch(&step_kernel<8>) : launch(&step_kernel<0>));
+  const bool few = m.max_joint_sides <= 4;
+  int lrc = (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
+            : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
+            : few ? launch(&step_kernel<0, 4>) : launch(&step_kernel<0, kMaxBodyJoints>);
   if (lrc) return lrc;
   HIP_TRY(hipGetLastError());
   if (a.recs) s->recs_valid = 1;

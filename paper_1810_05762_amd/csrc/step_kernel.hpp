@@ -122,6 +122,16 @@ __device__ __forceinline__ void cross(const float a[3], const float b[3], float 
 __device__ __forceinline__ float dot(const float a[3], const float b[3]) {
   return a[0] * b[0] + a[1] * b[1] + a[2] * b[2];
 }
+// (r x e_k) . w for the unit vector e_k, zero terms left out
+__device__ __forceinline__ float cross_unit_dot(const float r[3], int k, const float w[3]) {
+  return k == 0 ? r[2] * w[1] - r[1] * w[2] : (k == 1 ? r[0] * w[2] - r[2] * w[0] : r[1] * w[0] - r[0] * w[1]);
+}
+// r x e_k
+__device__ __forceinline__ void cross_unit(const float r[3], int k, float o[3]) {
+  if (k == 0) { o[0] = 0.0f; o[1] = r[2]; o[2] = -r[1]; }
+  else if (k == 1) { o[0] = -r[2]; o[1] = 0.0f; o[2] = r[0]; }
+  else { o[0] = r[1]; o[1] = -r[0]; o[2] = 0.0f; }
+}
 // rotation vector of conj(qa) * qb, short way round
 __device__ __forceinline__ void rel_rotvec(const float qa[4], const float qb[4], float phi[3]) {
   float w = qa[0] * qb[0] + qa[1] * qb[1] + qa[2] * qb[2] + qa[3] * qb[3];
@@ -249,8 +259,9 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
 }
 
 // EC > 0: envs per workgroup fixed at compile time (LDS offsets become immediates);
-// EC == 0: taken from the launch arguments.
-template <int EC>
+// EC == 0: taken from the launch arguments.  NJ: compile-time bound on the joints one body
+// belongs to (the per-body average reads NJ joint copies without branching).
+template <int EC, int NJ>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 #ifdef EXP_TIMING
   long long t_last = clock64();
@@ -339,6 +350,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     t[0] = M.bodies[i].n_joint_sides; t[1] = M.bodies[i].slot0; t[2] = M.bodies[i].n_slots;
     for (int k = 0; k < kMaxBodyJoints; ++k) t[3 + k] = M.bodies[i].joint_sides[k];
   }
+  for (int i = tid; i < (J * 12 + S * 6) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
   // contact records start cleared (a step with zero substeps packs "no contact")
   for (int i = tid; i < S * E; i += kThreads) {
     Lreci[(i / E * kRecWords + 0) * E + i % E] = 0;
@@ -390,7 +402,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   JointRows jr;
   ContactRows cr;
   bool has_contact = false;  // this thread owns an active contact this substep
-  const int max_njs = M.max_joint_sides;
 
   for (int sub = 0; sub < a.substeps; ++sub) {
     // ---- A: publish pose and world inverse inertia
@@ -478,9 +489,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       const int grp = tid / kGroup, gl = tid % kGroup;
       Field H = make_field(M, a.heights, a.coarse);
       const int n_end = Lcount[1], n_mid = Lcount[2];
-#ifdef EXP_TIMING
-      if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += Lcount[3]; a.dbg[15] += n_end; a.dbg[13] += n_mid; }
-#endif
       for (int pass = 0; pass < 2; ++pass) {
         const int n_q = pass == 0 ? n_end : n_mid;
         for (int sv = grp; sv < n_q; sv += kThreads / kGroup) {
@@ -517,7 +525,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           if (gl == 0) { Lbest[qi] = best; Lbesti[qi] = best_id; }
         }
         __syncthreads();
-        TMARK(11 + pass);
       }
       // ---- B3: one thread per queued slot turns the selected feature into a contact record
       for (int sv = tid; sv < n_end + n_mid; sv += kThreads) {
@@ -544,6 +551,9 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           Llist[atomicAdd(&Lcount[0], 1)] = i;
         }
       }
+      __syncthreads();
+      // the search results shared the space of the contact copies: leave finite numbers behind
+      for (int i = tid; i < 2 * S * E; i += kThreads) Lbest[i] = 0.0f;
     }
     __syncthreads();
     TMARK(3);
@@ -626,10 +636,9 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       jr.sa = na * ima; jr.sb = nbb * imb;
       const float bh = p_beta_j / h;
       for (int k = 0; k < 3; ++k) {
-        float ex[3] = {k == 0 ? 1.0f : 0.0f, k == 1 ? 1.0f : 0.0f, k == 2 ? 1.0f : 0.0f};
         float ca[3], cb[3], ya[3], yb[3];
-        cross(jr.ra, ex, ca);
-        cross(jr.rb, ex, cb);
+        cross_unit(jr.ra, k, ca);
+        cross_unit(jr.rb, k, cb);
         sym_vec(iwa, ca, ya);
         sym_vec(iwb, cb, yb);
         float keff = na * (ima + dot(ca, ya)) + nbb * (imb + dot(cb, yb));
@@ -678,47 +687,53 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     }
 
     TMARK(5);
-    // offsets of the copies this body averages (from the LDS table; only alive during the sweeps)
-    int gat_off[kMaxBodyJoints];
+    // the copies this body averages: NJ joint sides (unused entries point at joint 0's copy
+    // with weight 0) and its three contact slots (weight 0 when inactive)
+    int gat_off[NJ], gat_slot[3];
+    float gat_w[NJ + 3];
 #pragma unroll
-    for (int k = 0; k < kMaxBodyJoints; ++k) {
-      int js = is_body && k < max_njs ? Ltjs[b * (kMaxBodyJoints + 3) + 3 + k] : 0;
+    for (int k = 0; k < NJ; ++k) {
+      const bool used = is_body && k < my_njs;
+      int js = used ? Ltjs[b * (kMaxBodyJoints + 3) + 3 + k] : 0;
       gat_off[k] = ((js >> 1) * 12 + (js & 1) * 6) * E + e;
+      gat_w[k] = used ? 1.0f : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      const bool used = is_body && k < my_nslots;
+      gat_slot[k] = my_slot0 + (used ? k : 0);
+      gat_w[NJ + k] = used ? Lrec[((my_slot0 + k) * kRecWords + 10) * E + e] : 0.0f;
     }
     // ---- S: sweeps
     // Wavefronts that hold joint threads run only the joint rows, the others only the contact
     // rows (a wave-uniform branch, so neither path carries the other's registers); both paths
     // execute the same two barriers per sweep.
     auto gather = [&]() {
-        if (is_body && nbf > 0.0f) {
-          // all loads are unconditional (unused entries read a valid dummy location and are
-          // discarded by a select) so that they are issued together and waited for once
-          float acc[6] = {0, 0, 0, 0, 0, 0};
-  #pragma unroll
-          for (int k = 0; k < kMaxBodyJoints; ++k) {
-            if (k < max_njs) {  // uniform across the workgroup
-              const int off = k < my_njs ? gat_off[k] : e;
-              for (int c = 0; c < 6; ++c) {
-                float val = Loutj[off + c * E];
-                acc[c] += k < my_njs ? val : 0.0f;
-              }
-            }
-          }
-  #pragma unroll
-          for (int k = 0; k < 3; ++k) {
-            const int sl = my_slot0 + (k < my_nslots ? k : 0);
-            float wk = k < my_nslots ? Lrec[(sl * kRecWords + 10) * E + e] : 0.0f;
-            for (int c = 0; c < 6; ++c) {
-              float val = Loutc[(sl * 6 + c) * E + e];
-              acc[c] += wk > 0.0f ? wk * val : 0.0f;
-            }
-          }
-          float inb = 1.0f / nbf;
-          for (int c = 0; c < 3; ++c) {
-            v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
-            Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c];
-          }
+      if (is_body && nbf > 0.0f) {
+        // every load is unconditional: unused entries read a valid location and enter the sum
+        // with weight 0 (the copy arrays only ever hold finite numbers); all reads are issued
+        // before the first use so their LDS latency is paid once
+        float val[NJ + 3][6];
+#pragma unroll
+        for (int k = 0; k < NJ; ++k)
+#pragma unroll
+          for (int c = 0; c < 6; ++c) val[k][c] = Loutj[gat_off[k] + c * E];
+#pragma unroll
+        for (int k = 0; k < 3; ++k)
+#pragma unroll
+          for (int c = 0; c < 6; ++c) val[NJ + k][c] = Loutc[(gat_slot[k] * 6 + c) * E + e];
+        __builtin_amdgcn_sched_group_barrier(0x100, (NJ + 3) * 3, 0);  // the DS reads first
+        float acc[6] = {0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < NJ + 3; ++k)
+#pragma unroll
+          for (int c = 0; c < 6; ++c) acc[c] += gat_w[k] * val[k][c];
+        float inb = 1.0f / nbf;
+        for (int c = 0; c < 3; ++c) {
+          v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
+          Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c];
         }
+      }
     };
     if (joint_wave) {
       for (int it = 0; it < a.iterations; ++it) {
@@ -730,11 +745,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * 6 + c) * E + e]; wb[c] = Lvel[(pb * 6 + 3 + c) * E + e]; }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
-            float ex[3] = {k == 0 ? 1.0f : 0.0f, k == 1 ? 1.0f : 0.0f, k == 2 ? 1.0f : 0.0f};
-            float ca[3], cb[3];
-            cross(jr.ra, ex, ca);
-            cross(jr.rb, ex, cb);
-            float jv = (vb[k] - va[k]) + dot(cb, wb) - dot(ca, wa);
+            float jv = (vb[k] - va[k]) + cross_unit_dot(jr.rb, k, wb) - cross_unit_dot(jr.ra, k, wa);
             float dl = -jr.pmeff[k] * (jv + jr.pbias[k]);
             va[k] -= jr.sa * dl;
             vb[k] += jr.sb * dl;
@@ -759,9 +770,13 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
             Loutj[(idx * 12 + 9 + c) * E + e] = wb[c];
           }
         }
+        TMARK(10);
         __syncthreads();
+        TMARK(11);
         gather();
+        TMARK(12);
         __syncthreads();
+        TMARK(13);
       }
     } else {
       for (int it = 0; it < a.iterations; ++it) {
