@@ -366,48 +366,98 @@ __device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float zcut, in
   }
 }
 
-// The up-to-three edges that start at sample (i,j) against the segment interior.
-__device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g, float zcut, int i, int j,
-                                               float& best, int& best_id) {
+// Per-slot constants of the conservative edge culls of the mid-segment search.  In the xy
+// plane, u = (dx,dy) is the segment's direction (length L): for a point p, cross = u x (p - P0)
+// is L times its distance from the segment's line and along = u . (p - P0) is L times its
+// coordinate along it.  Two points within the reach R of each other differ by at most R L in
+// either, so an edge whose cross interval stays beyond R L, or whose along interval ends before
+// -R L or starts after L^2 + R L, is out of reach; otherwise the part of the segment that can be
+// within R of it has s = along / L^2 in [amin - R L, amax + R L] / L^2, and the edge is out of
+// reach when that part stays more than R above both its ends.
+struct SegCull {
+  float dx, dy, dz, L2, RL, R, inv_L2;  // inv_L2 = 0: segment (nearly) vertical, no s interval
+};
+__device__ __forceinline__ SegCull seg_cull(const SlotGeom& g) {
+  SegCull c;
+  c.dx = g.P1.x - g.P0.x; c.dy = g.P1.y - g.P0.y; c.dz = g.P1.z - g.P0.z;
+  c.L2 = c.dx * c.dx + c.dy * c.dy;
+  c.R = g.Rq + kSelSlack;
+  c.RL = c.R * sqrtf(c.L2);
+  c.inv_L2 = c.L2 > 1e-8f ? 1.0f / c.L2 : 0.0f;
+  return c;
+}
+
+// Cheap part of the mid-segment search at sample (i,j): bit k of the result is set when edge k
+// of the up-to-three edges starting there belongs to the box and may be within reach of the
+// segment.  The three edges lie in the square of cell (i,j), so one test of that square (cross
+// and along intervals of its corners, height of the reachable part of the segment above its
+// highest corner) serves all three.
+__device__ __forceinline__ int segment_candidates(const Field& H, const SlotGeom& g, const SegCull& sc, float zcut,
+                                                  int i, int j) {
+  const float x0 = H.ox + (float)i * H.cell, y0 = H.oy + (float)j * H.cell;
+  const float rx0 = x0 - g.P0.x, ry0 = y0 - g.P0.y;
+  const float c0 = sc.dx * ry0 - sc.dy * rx0, a0 = sc.dx * rx0 + sc.dy * ry0;
+  // a step of one cell along +x changes (cross, along) by (-se, ce), along +y by (ce, se)
+  const float ce = sc.dx * H.cell, se = sc.dy * H.cell;
+  const float cmin = c0 + fminf(ce, 0.0f) + fminf(-se, 0.0f), cmax = c0 + fmaxf(ce, 0.0f) + fmaxf(-se, 0.0f);
+  const float amin = a0 + fminf(se, 0.0f) + fminf(ce, 0.0f), amax = a0 + fmaxf(se, 0.0f) + fmaxf(ce, 0.0f);
+  // sample coordinates carry the rounding of ox + i * cell: 1 mm more on top of R
+  const float lim = sc.RL + 1e-3f * (fabsf(sc.dx) + fabsf(sc.dy));
+  if (cmin > lim || cmax < -lim) return 0;
+  if (amax < -lim || amin > sc.L2 + lim) return 0;
+  // corner heights; neighbours beyond the last sample are clamped (their edges are excluded below)
+  const int ip = i + 1 < H.nx ? i + 1 : i, jp = j + 1 < H.ny ? j + 1 : j;
+  float h00, h10, h11, h01;
   {
-    // The three edges lie in the square of cell (i,j), within 0.7072 cell of its centre; if the
-    // centre is further than reach + 0.7072 cell (+ slack) from the segment's line in the xy plane,
-    // or beyond its ends by that much, none of them can reach the margin.
-    float cx = H.ox + ((float)i + 0.5f) * H.cell, cy = H.oy + ((float)j + 0.5f) * H.cell;
-    float dx = g.P1.x - g.P0.x, dy = g.P1.y - g.P0.y, rx = cx - g.P0.x, ry = cy - g.P0.y;
-    float L2 = dx * dx + dy * dy, rr = g.Rq + 0.7072f * H.cell + kSelSlack;
-    float cr = dx * ry - dy * rx, al = dx * rx + dy * ry, lim = rr * rr * L2;
-    if (cr * cr > lim) return;
-    if (al < 0.0f && al * al > lim) return;
-    if (al > L2 && (al - L2) * (al - L2) > lim) return;
+    unsigned di = (unsigned)(i - H.pi0), dj = (unsigned)(j - H.pj0);
+    if (di + 1u < (unsigned)H.ps && dj + 1u < (unsigned)H.ps) {
+      const lds_float* p = H.patch + dj * H.ps + di;
+      h00 = p[0]; h10 = p[1]; h01 = p[H.ps]; h11 = p[H.ps + 1];
+    } else {
+      h00 = H.h[j * H.nx + i]; h10 = H.h[j * H.nx + ip]; h01 = H.h[jp * H.nx + i]; h11 = H.h[jp * H.nx + ip];
+    }
   }
-  // corner heights of cell (i,j); at the far border of the box the missing neighbours are
-  // not read (their edges are excluded below)
-  float h00, h10 = 0.0f, h11 = 0.0f, h01 = 0.0f;
-  if (i <= g.i1 && j <= g.j1) field_cell_heights(H, i, j, h00, h10, h11, h01);
-  else {
-    h00 = field_height(H, i, j);
-    if (i <= g.i1) h10 = field_height(H, i + 1, j);
-    if (j <= g.j1) h01 = field_height(H, i, j + 1);
+  const float zq = fmaxf(fmaxf(h00, h10), fmaxf(h01, h11));
+  if (zcut > zq) return 0;  // the whole square is out of reach below the capsule
+  if (sc.inv_L2 > 0.0f) {
+    const float s_lo = fmaxf((amin - lim) * sc.inv_L2 - 1e-4f, 0.0f);
+    const float s_hi = fminf((amax + lim) * sc.inv_L2 + 1e-4f, 1.0f);
+    const float zs = g.P0.z + sc.dz * (sc.dz >= 0.0f ? s_lo : s_hi);
+    if (zs - sc.R > zq) return 0;
   }
-  float x0 = H.ox + (float)i * H.cell, x1 = H.ox + (float)(i + 1) * H.cell;
-  float y0 = H.oy + (float)j * H.cell, y1 = H.oy + (float)(j + 1) * H.cell;
-  f3 Q0 = f3{x0, y0, h00};
+  int mask = 7;
+  if (i > g.i1) mask &= 2;   // edges 0 and 2 leave the box in x
+  if (j > g.j1) mask &= 1;   // edges 1 and 2 leave the box in y
+  return mask;
+}
+
+// Exact part: edge k of sample (i,j) against the interior of segment P0->P1.  False when the
+// edge is not admissible (closest point at an end of the segment, or the axis not above it).
+__device__ __forceinline__ bool segment_edge_d2(const Field& H, f3 P0, f3 P1, int i, int j, int k, float& d2) {
+  const int i1 = i + (k == 1 ? 0 : 1), j1 = j + (k == 0 ? 0 : 1);
+  f3 Q0 = f3{H.ox + (float)i * H.cell, H.oy + (float)j * H.cell, field_height(H, i, j)};
+  f3 Q1 = f3{H.ox + (float)i1 * H.cell, H.oy + (float)j1 * H.cell, field_height(H, i1, j1)};
+  float s, t;
+  seg_edge_st(P0, P1, Q0, Q1, s, t);
+  if (!(s > 0.001f && s < 0.999f)) return false;  // the ends belong to the end-sphere slots
+  f3 d1 = sub3(P1, P0), d2v = sub3(Q1, Q0);
+  f3 c1 = f3{P0.x + d1.x * s, P0.y + d1.y * s, P0.z + d1.z * s};
+  f3 c2 = f3{Q0.x + d2v.x * t, Q0.y + d2v.y * t, Q0.z + d2v.z * t};
+  f3 df = sub3(c1, c2);
+  if (!(df.z > 0.0f)) return false;  // the axis must be above the edge
+  d2 = dot3(df, df);
+  return true;
+}
+
+// The up-to-three edges that start at sample (i,j) against the segment interior.
+__device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g, const SegCull& sc, float zcut,
+                                               int i, int j, float& best, int& best_id) {
+  const int mask = segment_candidates(H, g, sc, zcut, i, j);
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
-    if ((k == 0 || k == 2) && i > g.i1) continue;
-    if ((k == 1 || k == 2) && j > g.j1) continue;
-    f3 Q1 = k == 0 ? f3{x1, y0, h10} : (k == 1 ? f3{x0, y1, h01} : f3{x1, y1, h11});
-    if (zcut > fmaxf(Q0.z, Q1.z)) continue;  // edge entirely out of reach below the capsule
-    float s, t;
-    seg_edge_st(g.P0, g.P1, Q0, Q1, s, t);
-    if (!(s > 0.001f && s < 0.999f)) continue;  // the ends belong to the end-sphere slots
-    f3 d1 = sub3(g.P1, g.P0), d2 = sub3(Q1, Q0);
-    f3 c1 = f3{g.P0.x + d1.x * s, g.P0.y + d1.y * s, g.P0.z + d1.z * s};
-    f3 c2 = f3{Q0.x + d2.x * t, Q0.y + d2.y * t, Q0.z + d2.z * t};
-    f3 df = sub3(c1, c2);
-    if (!(df.z > 0.0f)) continue;  // the axis must be above the edge
-    keep_min(dot3(df, df), 3 * (j * H.nx + i) + k, best, best_id);
+    float d2;
+    if (((mask >> k) & 1) && segment_edge_d2(H, g.P0, g.P1, i, j, k, d2))
+      keep_min(d2, 3 * (j * H.nx + i) + k, best, best_id);
   }
 }
 
@@ -503,8 +553,9 @@ __device__ inline ContactOut generate_contact(const Model& M, const float* __res
     return finish_sphere(H, g, M.margin, best, best_id);
   }
   const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
+  const SegCull sc = seg_cull(g);
   for (int j = g.j0; j <= g.j1 + 1; ++j)
-    for (int i = g.i0; i <= g.i1 + 1; ++i) segment_vertex(H, g, zcut, i, j, best, best_id);
+    for (int i = g.i0; i <= g.i1 + 1; ++i) segment_vertex(H, g, sc, zcut, i, j, best, best_id);
   return finish_segment(H, g, M.margin, best, best_id);
 }
 

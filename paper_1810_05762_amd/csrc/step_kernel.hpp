@@ -58,19 +58,25 @@ struct StepArgs {
   long long* dbg;
 };
 
+// Rows (E consecutive floats) per item of the velocity, inverse-inertia and copy arrays.  Odd
+// counts, so that neighbouring items start in different LDS banks when E is 16.
+constexpr int kVS = 7, kCS = 7, kJS = 13;
+
 struct LdsPlan {
-  int pos, vel, iw, nb, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, total;
+  int pos, vel, iw, nb, tq, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
 };
 
 __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch) {
   LdsPlan p;
   int o = 0;
   p.pos = o; o += B * 7 * E;
-  p.vel = o; o += B * 6 * E;
-  p.iw = o; o += B * 6 * E;
+  p.vel = o; o += B * kVS * E;
+  p.iw = o; o += B * kVS * E;
   p.nb = o; o += B * E;
-  p.outj = o; o += J * 12 * E;
-  p.outc = o; o += S * 6 * E;
+  p.tq = o; o += J * 3 * E;
+  o += o & 1;  // the search results kept in the copy arrays are 64-bit words
+  p.outj = o; o += J * kJS * E;
+  p.outc = o; o += S * kCS * E;
   p.tjs = o; o += B * (kMaxBodyJoints + 3);
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
@@ -79,12 +85,13 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
   p.lim = o; o += (D > 0 ? D : 1) * E;
-  p.count = o; o += 4;
+  p.count = o; o += 8;
   p.porg = o; o += 2 * E;
   p.org = o; o += 3 * E;
   p.tslot = o; o += 2 * S;
   p.tbody = o; o += 4 * B;
   p.tin = o; o += 6 * B;
+  p.tjoint = o; o += J * (int)(sizeof(JointTab) / 4);
   p.patch = o; o += with_patch ? E * kPatch * kPatch : 0;
   p.mip = o; o += with_patch ? E * kPatchBlocks * kPatchBlocks : 0;
   p.total = o;
@@ -212,7 +219,7 @@ __device__ __forceinline__ void build_contact_rows(ContactRows& c, const float* 
   float d = Lrec[(s * kRecWords + 3) * E + ee];
   float n[3], rc[3], iwb[6];
   for (int k = 0; k < 3; ++k) { n[k] = Lrec[(s * kRecWords + 4 + k) * E + ee]; rc[k] = Lrec[(s * kRecWords + 7 + k) * E + ee]; }
-  for (int k = 0; k < 6; ++k) iwb[k] = Liw[(body * 6 + k) * E + ee];
+  for (int k = 0; k < 6; ++k) iwb[k] = Liw[(body * kVS + k) * E + ee];
   float nbb = Lnb[body * E + ee] / Lrec[(s * kRecWords + 10) * E + ee];
   float t1[3], t2[3];
   if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
@@ -261,6 +268,12 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
 // EC > 0: envs per workgroup fixed at compile time (LDS offsets become immediates);
 // EC == 0: taken from the launch arguments.  NJ: compile-time bound on the joints one body
 // belongs to (the per-body average reads NJ joint copies without branching).
+// (squared distance, feature id) as one 64-bit word whose unsigned order is the lexicographic
+// order of the pair (squared distances are non-negative, ids non-negative)
+__device__ __forceinline__ unsigned long long pack_best(float d2, int id) {
+  return ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)id;
+}
+
 template <int EC, int NJ>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 #ifdef EXP_TIMING
@@ -291,8 +304,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   int* Llist = reinterpret_cast<int*>(lds + P.list);
   int* Lsurv = reinterpret_cast<int*>(lds + P.surv);
   float* Llam = lds + P.lam;                         // impulses of the contacts beyond one per thread
-  float* Lbest = lds + P.outc;                       // fine-search results; the sweeps reuse this space
-  int* Lbesti = reinterpret_cast<int*>(lds + P.outc) + S * E;
+  // fine search: per queued slot the minimum of (squared distance, feature id) packed in 64 bits,
+  // then the list of candidate edges; both live in the space of the copies the sweeps use
+  unsigned long long* Lbest64 = reinterpret_cast<unsigned long long*>(lds + P.outj);
+  unsigned* Lcand = reinterpret_cast<unsigned*>(lds + P.outj) + 2 * S * E;
+  const int cand_cap = (J * kJS + S * kCS) * E - 2 * S * E;
+  float* Ltq = lds + P.tq;                           // joint torques, [J][3][E]
   float* Lu = lds + P.u;
   float* Lobs = lds + P.obs;
   int* Llim = reinterpret_cast<int*>(lds + P.lim);
@@ -304,6 +321,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   int* Ltslot = reinterpret_cast<int*>(lds + P.tslot);  // slot table: body, kind
   float* Ltbody = lds + P.tbody;                      // body table: radius, half length, axis, 1/mass
   float* Ltin = lds + P.tin;                          // body table: inertia(3), inverse inertia(3)
+  const JointTab* Ltjoint = reinterpret_cast<const JointTab*>(lds + P.tjoint);  // joint table
   const float h = a.h;
 
   // ---- load: body state into registers, clipped actions into LDS
@@ -339,6 +357,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     int c = i / E, ee = i - c * E, env_i = blockIdx.x * E + ee;
     Lorg[i] = env_i < N ? a.origins[3 * env_i + c] : 0.0f;
   }
+  for (int i = tid; i < J * (int)(sizeof(JointTab) / 4); i += kThreads)
+    reinterpret_cast<int*>(lds + P.tjoint)[i] = reinterpret_cast<const int*>(M.joints)[i];
   for (int i = tid; i < S; i += kThreads) { Ltslot[2 * i] = M.slots[i].body; Ltslot[2 * i + 1] = M.slots[i].kind; }
   for (int i = tid; i < B; i += kThreads) {
     Ltbody[4 * i] = M.bodies[i].radius; Ltbody[4 * i + 1] = M.bodies[i].half_len;
@@ -350,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     t[0] = M.bodies[i].n_joint_sides; t[1] = M.bodies[i].slot0; t[2] = M.bodies[i].n_slots;
     for (int k = 0; k < kMaxBodyJoints; ++k) t[3 + k] = M.bodies[i].joint_sides[k];
   }
-  for (int i = tid; i < (J * 12 + S * 6) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
+  for (int i = tid; i < (J * kJS + S * kCS) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
   // contact records start cleared (a step with zero substeps packs "no contact")
   for (int i = tid; i < S * E; i += kThreads) {
     Lreci[(i / E * kRecWords + 0) * E + i % E] = 0;
@@ -403,15 +423,26 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   ContactRows cr;
   bool has_contact = false;  // this thread owns an active contact this substep
 
+  const int tid_o = tid, e_o = e, idx_o = idx;
+  const float h_o = h;
   for (int sub = 0; sub < a.substeps; ++sub) {
+    // The thread's indices and the time step are passed through empty asm statements at the top
+    // of each substep: what is derived from them (LDS addresses, h-scaled constants) is then
+    // recomputed per substep instead of being computed once before the loop and kept alive across
+    // it, which costs registers that the phases below need.
+    int tid = tid_o, e = e_o, idx = idx_o;
+    float h = h_o;
+    asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
+    asm volatile("" : "+s"(h));
+    const int b = idx;
     // ---- A: publish pose and world inverse inertia
-    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; }
+    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
       // velocities are parked in LDS as well: nothing of the body stays in registers while the
       // contact phases run
-      for (int c = 0; c < 3; ++c) { Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c]; }
+      for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
       float R[9], invIb[3];
       quat_to_mat(q, R);
       for (int c = 0; c < 3; ++c) invIb[c] = Ltin[6 * b + 3 + c];
@@ -422,14 +453,14 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       iw[3] = R[3] * R[3] * invIb[0] + R[4] * R[4] * invIb[1] + R[5] * R[5] * invIb[2];
       iw[4] = R[3] * R[6] * invIb[0] + R[4] * R[7] * invIb[1] + R[5] * R[8] * invIb[2];
       iw[5] = R[6] * R[6] * invIb[0] + R[7] * R[7] * invIb[1] + R[8] * R[8] * invIb[2];
-      for (int c = 0; c < 6; ++c) Liw[(b * 6 + c) * E + e] = iw[c];
+      for (int c = 0; c < 6; ++c) Liw[(b * kVS + c) * E + e] = iw[c];
     }
     __syncthreads();
 
     TMARK(1);
     // ---- B: joint torques (stored once per joint; the body applies the sign)
     if (is_joint) {
-      const JointTab& jt = M.joints[idx];
+      const JointTab& jt = Ltjoint[idx];
       float qa[4] = {1, 0, 0, 0};
       if (jt.parent >= 0)
         for (int c = 0; c < 4; ++c) qa[c] = Lpos[(jt.parent * 7 + 3 + c) * E + e];
@@ -443,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         float t = jt.gear[k] * Lu[jt.act[k] * E + e];
         tq[0] += t * ak[0]; tq[1] += t * ak[1]; tq[2] += t * ak[2];
       }
-      for (int c = 0; c < 3; ++c) Loutj[(idx * 12 + c) * E + e] = tq[c];
+      for (int c = 0; c < 3; ++c) Ltq[(idx * 3 + c) * E + e] = tq[c];
     }
     // ---- B1: every slot: plane contact, or reach test against the heightfield copy;
     //          slots that may touch the heightfield (block maxima, then the exact maximum over
@@ -504,28 +535,121 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
                                  p_margin, bx, bq, sl.kind, bo);
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
           slot_range(H, g);
-          float best = INFINITY;
-          int best_id = -1;
           if (pass == 0) {
+            float best = INFINITY;
+            int best_id = -1;
             f3 Pc = sl.kind == 0 ? g.P0 : g.P1;
             const float zcut = Pc.z - g.Rq;
             const int ni = g.i1 - g.i0 + 1, nc = ni * (g.j1 - g.j0 + 1);
             for (int c = gl; c < nc; c += kGroup) sphere_cell(H, Pc, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+#pragma unroll
+            for (int m = kGroup / 2; m >= 1; m >>= 1) {
+              float ob = __shfl_xor(best, m);
+              int oid = __shfl_xor(best_id, m);
+              if (oid >= 0) keep_min(ob, oid, best, best_id);
+            }
+            if (gl == 0) Lbest64[qi] = best_id < 0 ? ~0ull : pack_best(best, best_id);
           } else {
+            // stage 1: the group's lanes split the samples of the box and queue the edges that pass
+            // the cheap reach tests; the segment's end points and the box origin are left in the
+            // slot's (still unused) record for stage 2
+            if (gl == 0) {
+              Lbest64[qi] = ~0ull;
+              Lrec[(s * kRecWords + 1) * E + ee] = g.P0.x; Lrec[(s * kRecWords + 2) * E + ee] = g.P0.y;
+              Lrec[(s * kRecWords + 3) * E + ee] = g.P0.z; Lrec[(s * kRecWords + 4) * E + ee] = g.P1.x;
+              Lrec[(s * kRecWords + 5) * E + ee] = g.P1.y; Lrec[(s * kRecWords + 6) * E + ee] = g.P1.z;
+              Lreci[(s * kRecWords + 7) * E + ee] = g.i0 | (g.j0 << 16);
+              Lreci[(s * kRecWords + 8) * E + ee] = 0;
+            }
             const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
             const int ni = g.i1 - g.i0 + 2, nc = ni * (g.j1 - g.j0 + 2);
-            for (int c = gl; c < nc; c += kGroup) segment_vertex(H, g, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
-          }
+            const SegCull sc = seg_cull(g);
+            for (int c = gl; c < nc; c += kGroup) {
+              const int di = c % ni, dj = c / ni;
+              const int mask = segment_candidates(H, g, sc, zcut, g.i0 + di, g.j0 + dj);
+              // list space for the whole wavefront with one atomic: per-lane counts (0..3) are
+              // summed from two ballots
+              const int n_k = (di < 256 && dj < 256) ? __popc(mask) : 0;
+              const unsigned long long b0 = __ballot(n_k & 1), b1 = __ballot(n_k & 2);
+              if ((b0 | b1) == 0 && mask == 0) continue;
+              int pos = cand_cap;
+              if (b0 | b1) {
+                const int leader = __ffsll((long long)(b0 | b1)) - 1;
+                int base = 0;
+                if ((int)__lane_id() == leader) base = atomicAdd(&Lcount[3], __popcll(b0) + 2 * __popcll(b1));
+                base = __shfl(base, leader);
+                pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b0 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b0, 0u)) +
+                      2 * (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b1 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b1, 0u));
+              }
+              if (mask == 0) continue;
+              if (n_k == 0) pos = cand_cap;  // box too large for the packed index
+              const unsigned cw = (unsigned)qi | ((unsigned)di << 14) | ((unsigned)dj << 22);
 #pragma unroll
-          for (int m = kGroup / 2; m >= 1; m >>= 1) {
-            float ob = __shfl_xor(best, m);
-            int oid = __shfl_xor(best_id, m);
-            if (oid >= 0) keep_min(ob, oid, best, best_id);
+              for (int k = 0; k < 3; ++k)
+                if ((mask >> k) & 1) {
+                  if (pos < cand_cap) Lcand[pos] = cw | ((unsigned)k << 12);
+                  ++pos;
+                }
+              if (pos > cand_cap) {
+                // list full (or box too large for the packed index): the slot is searched again
+                // by the fallback below
+                Lreci[(s * kRecWords + 8) * E + ee] = 1;
+                Lcount[4] = 1;
+              }
+            }
           }
-          if (gl == 0) { Lbest[qi] = best; Lbesti[qi] = best_id; }
         }
         __syncthreads();
+        TMARK(10 + pass);
       }
+      {
+        // stage 2 of the mid-segment search: one queued edge per thread
+        const int n_c = Lcount[3] < cand_cap ? Lcount[3] : cand_cap;
+        for (int t = tid; t < n_c; t += kThreads) {
+          const unsigned cw = Lcand[t];
+          const int qi = cw & 4095, k = (cw >> 12) & 3, di = (cw >> 14) & 255, dj = (cw >> 22) & 255;
+          const int i = Lsurv[qi];
+          const int ee = i % E, s = i / E;
+          const f3 P0 = f3{Lrec[(s * kRecWords + 1) * E + ee], Lrec[(s * kRecWords + 2) * E + ee], Lrec[(s * kRecWords + 3) * E + ee]};
+          const f3 P1 = f3{Lrec[(s * kRecWords + 4) * E + ee], Lrec[(s * kRecWords + 5) * E + ee], Lrec[(s * kRecWords + 6) * E + ee]};
+          const int ij = Lreci[(s * kRecWords + 7) * E + ee];
+          const int ci = (ij & 0xffff) + di, cj = (ij >> 16) + dj;
+          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          float d2;
+          if (segment_edge_d2(H, P0, P1, ci, cj, k, d2)) atomicMin(&Lbest64[qi], pack_best(d2, 3 * (cj * H.nx + ci) + k));
+        }
+        __syncthreads();
+        TMARK(13);
+        if (Lcount[4]) {
+          // rare: some edges did not fit the list; their slots are searched directly
+          for (int sv = grp; sv < n_mid; sv += kThreads / kGroup) {
+            const int qi = S * E - 1 - sv;
+            const int i = Lsurv[qi];
+            const int ee = i % E, s = i / E;
+            if (!Lreci[(s * kRecWords + 8) * E + ee]) continue;
+            const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
+            float bx[3], bq[4], bo[3];
+            for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
+            for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
+            for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+            SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
+                                   p_margin, bx, bq, sl.kind, bo);
+            if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+            slot_range(H, g);
+            const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
+            const int ni = g.i1 - g.i0 + 2, nc = ni * (g.j1 - g.j0 + 2);
+            const SegCull sc = seg_cull(g);
+            float best = INFINITY;
+            int best_id = -1;
+            for (int c = gl; c < nc; c += kGroup) segment_vertex(H, g, sc, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+            if (best_id >= 0) atomicMin(&Lbest64[qi], pack_best(best, best_id));
+          }
+          __syncthreads();
+        }
+      }
+#ifdef EXP_TIMING
+      if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += n_mid; a.dbg[15] += Lcount[3]; }
+#endif
       // ---- B3: one thread per queued slot turns the selected feature into a contact record
       for (int sv = tid; sv < n_end + n_mid; sv += kThreads) {
         const int qi = sv < n_end ? sv : S * E - 1 - (sv - n_end);
@@ -540,11 +664,14 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
                                p_margin, bx, bq, sl.kind, bo);
         if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
         ContactOut co = no_contact();
+        const unsigned long long bw = Lbest64[qi];
+        const float bestd = __uint_as_float((unsigned)(bw >> 32));
+        const int besti = (int)(unsigned)bw;
         if (sl.kind < 2) {
           // a centre underneath the surface overrides the nearest-triangle search
-          if (!underneath_contact(H, g, p_margin, co)) co = finish_sphere(H, g, p_margin, Lbest[qi], Lbesti[qi]);
+          if (!underneath_contact(H, g, p_margin, co)) co = finish_sphere(H, g, p_margin, bestd, besti);
         } else {
-          co = finish_segment(H, g, p_margin, Lbest[qi], Lbesti[qi]);
+          co = finish_segment(H, g, p_margin, bestd, besti);
         }
         if (co.active) {
           store_record(Lrec, Lreci, s, ee, E, co);
@@ -552,8 +679,9 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         }
       }
       __syncthreads();
+      TMARK(12);
       // the search results shared the space of the contact copies: leave finite numbers behind
-      for (int i = tid; i < 2 * S * E; i += kThreads) Lbest[i] = 0.0f;
+      for (int i = tid; i < 2 * S * E; i += kThreads) Loutj[i] = 0.0f;
     }
     __syncthreads();
     TMARK(3);
@@ -568,13 +696,13 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       for (int k = 0; k < my_njs; ++k) {
         const int js = Ltjs[b * (kMaxBodyJoints + 3) + 3 + k];
         const float sg = (js & 1) ? 1.0f : -1.0f;
-        for (int c = 0; c < 3; ++c) tau[c] += sg * Loutj[((js >> 1) * 12 + c) * E + e];
+        for (int c = 0; c < 3; ++c) tau[c] += sg * Ltq[((js >> 1) * 3 + c) * E + e];
       }
       float R[9], qq[4], Ib[3], invIb[3];
       for (int c = 0; c < 4; ++c) qq[c] = Lpos[(b * 7 + 3 + c) * E + e];
       quat_to_mat(qq, R);
       for (int c = 0; c < 3; ++c) { Ib[c] = Ltin[6 * b + c]; invIb[c] = Ltin[6 * b + 3 + c]; }
-      for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * 6 + c) * E + e]; w[c] = Lvel[(b * 6 + 3 + c) * E + e]; }
+      for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * kVS + c) * E + e]; w[c] = Lvel[(b * kVS + 3 + c) * E + e]; }
       v[0] += h * g0; v[1] += h * g1; v[2] += h * g2;
       float wb[3], tb[3];
       mat_t_vec(R, w, wb);
@@ -585,7 +713,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       if (!p_gyro) { gy[0] = gy[1] = gy[2] = 0.0f; }
       for (int c = 0; c < 3; ++c) wb[c] += h * (tb[c] - gy[c]) * invIb[c];
       mat_vec(R, wb, w);
-      for (int c = 0; c < 3; ++c) { Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c]; }
+      for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
     }
     if (a.recs && sub == a.substeps - 1) {
       // export the records of the last substep, [N][S][12] words
@@ -605,20 +733,20 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     // ---- D: row constants
     const int n_active = Lcount[0];
     if (is_joint) {
-      const JointTab& jt = M.joints[idx];
+      const JointTab& jt = Ltjoint[idx];
       const int pa = j_pa, pb = j_pb;
       float xa[3] = {0, 0, 0}, qa[4] = {1, 0, 0, 0}, xb[3], qb[4];
       float iwa[6] = {0, 0, 0, 0, 0, 0}, iwb[6], na = 0.0f, ima = 0.0f;
       if (pa >= 0) {
         for (int c = 0; c < 3; ++c) xa[c] = Lpos[(pa * 7 + c) * E + e];
         for (int c = 0; c < 4; ++c) qa[c] = Lpos[(pa * 7 + 3 + c) * E + e];
-        for (int c = 0; c < 6; ++c) iwa[c] = Liw[(pa * 6 + c) * E + e];
+        for (int c = 0; c < 6; ++c) iwa[c] = Liw[(pa * kVS + c) * E + e];
         na = Lnb[pa * E + e];
         ima = Ltbody[4 * pa + 3];
       }
       for (int c = 0; c < 3; ++c) xb[c] = Lpos[(pb * 7 + c) * E + e];
       for (int c = 0; c < 4; ++c) qb[c] = Lpos[(pb * 7 + 3 + c) * E + e];
-      for (int c = 0; c < 6; ++c) iwb[c] = Liw[(pb * 6 + c) * E + e];
+      for (int c = 0; c < 6; ++c) iwb[c] = Liw[(pb * kVS + c) * E + e];
       const float nbb = Lnb[pb * E + e], imb = Ltbody[4 * pb + 3];
       float Ra[9], Rb[9], t0[3], t1[3];
       quat_to_mat(qa, Ra);
@@ -695,7 +823,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     for (int k = 0; k < NJ; ++k) {
       const bool used = is_body && k < my_njs;
       int js = used ? Ltjs[b * (kMaxBodyJoints + 3) + 3 + k] : 0;
-      gat_off[k] = ((js >> 1) * 12 + (js & 1) * 6) * E + e;
+      gat_off[k] = ((js >> 1) * kJS + (js & 1) * 6) * E + e;
       gat_w[k] = used ? 1.0f : 0.0f;
     }
 #pragma unroll
@@ -721,7 +849,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 #pragma unroll
         for (int k = 0; k < 3; ++k)
 #pragma unroll
-          for (int c = 0; c < 6; ++c) val[NJ + k][c] = Loutc[(gat_slot[k] * 6 + c) * E + e];
+          for (int c = 0; c < 6; ++c) val[NJ + k][c] = Loutc[(gat_slot[k] * kCS + c) * E + e];
         __builtin_amdgcn_sched_group_barrier(0x100, (NJ + 3) * 3, 0);  // the DS reads first
         float acc[6] = {0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -731,7 +859,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         float inb = 1.0f / nbf;
         for (int c = 0; c < 3; ++c) {
           v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
-          Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c];
+          Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c];
         }
       }
     };
@@ -741,8 +869,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           const int pa = j_pa, pb = j_pb;
           float va[3] = {0, 0, 0}, wa[3] = {0, 0, 0}, vb[3], wb[3];
           if (pa >= 0)
-            for (int c = 0; c < 3; ++c) { va[c] = Lvel[(pa * 6 + c) * E + e]; wa[c] = Lvel[(pa * 6 + 3 + c) * E + e]; }
-          for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * 6 + c) * E + e]; wb[c] = Lvel[(pb * 6 + 3 + c) * E + e]; }
+            for (int c = 0; c < 3; ++c) { va[c] = Lvel[(pa * kVS + c) * E + e]; wa[c] = Lvel[(pa * kVS + 3 + c) * E + e]; }
+          for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * kVS + c) * E + e]; wb[c] = Lvel[(pb * kVS + 3 + c) * E + e]; }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
             float jv = (vb[k] - va[k]) + cross_unit_dot(jr.rb, k, wb) - cross_unit_dot(jr.ra, k, wa);
@@ -764,28 +892,24 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
             for (int c = 0; c < 3; ++c) { wa[c] += jr.Za[k][c] * dl; wb[c] += jr.Zb[k][c] * dl; }
           }
           for (int c = 0; c < 3; ++c) {
-            Loutj[(idx * 12 + c) * E + e] = va[c];
-            Loutj[(idx * 12 + 3 + c) * E + e] = wa[c];
-            Loutj[(idx * 12 + 6 + c) * E + e] = vb[c];
-            Loutj[(idx * 12 + 9 + c) * E + e] = wb[c];
+            Loutj[(idx * kJS + c) * E + e] = va[c];
+            Loutj[(idx * kJS + 3 + c) * E + e] = wa[c];
+            Loutj[(idx * kJS + 6 + c) * E + e] = vb[c];
+            Loutj[(idx * kJS + 9 + c) * E + e] = wb[c];
           }
         }
-        TMARK(10);
         __syncthreads();
-        TMARK(11);
         gather();
-        TMARK(12);
         __syncthreads();
-        TMARK(13);
       }
     } else {
       for (int it = 0; it < a.iterations; ++it) {
         if (has_contact) {
           const int ee = cr.slot_e % E, sl = cr.slot_e / E;
           float vv[3], ww[3];
-          for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(cr.body * 6 + k) * E + ee]; ww[k] = Lvel[(cr.body * 6 + 3 + k) * E + ee]; }
+          for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(cr.body * kVS + k) * E + ee]; ww[k] = Lvel[(cr.body * kVS + 3 + k) * E + ee]; }
           relax_contact(cr, p_mu, vv, ww);
-          for (int k = 0; k < 3; ++k) { Loutc[(sl * 6 + k) * E + ee] = vv[k]; Loutc[(sl * 6 + 3 + k) * E + ee] = ww[k]; }
+          for (int k = 0; k < 3; ++k) { Loutc[(sl * kCS + k) * E + ee] = vv[k]; Loutc[(sl * kCS + 3 + k) * E + ee] = ww[k]; }
         }
         for (int k = n_reg + (kThreads - 1 - tid); k < n_active; k += n_reg) {
           // rare: more active contacts in the workgroup than threads; rows rebuilt from the record
@@ -795,10 +919,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           build_contact_rows(c2, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
           for (int r = 0; r < 3; ++r) c2.lam[r] = Llam[3 * (k - n_reg) + r];
           float vv[3], ww[3];
-          for (int r = 0; r < 3; ++r) { vv[r] = Lvel[(body * 6 + r) * E + ee]; ww[r] = Lvel[(body * 6 + 3 + r) * E + ee]; }
+          for (int r = 0; r < 3; ++r) { vv[r] = Lvel[(body * kVS + r) * E + ee]; ww[r] = Lvel[(body * kVS + 3 + r) * E + ee]; }
           relax_contact(c2, p_mu, vv, ww);
           for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = c2.lam[r];
-          for (int r = 0; r < 3; ++r) { Loutc[(sl * 6 + r) * E + ee] = vv[r]; Loutc[(sl * 6 + 3 + r) * E + ee] = ww[r]; }
+          for (int r = 0; r < 3; ++r) { Loutc[(sl * kCS + r) * E + ee] = vv[r]; Loutc[(sl * kCS + 3 + r) * E + ee] = ww[r]; }
         }
         __syncthreads();
         gather();
@@ -845,21 +969,21 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     }
     for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
     for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
-    for (int c = 0; c < 3; ++c) { Lvel[(b * 6 + c) * E + e] = v[c]; Lvel[(b * 6 + 3 + c) * E + e] = w[c]; }
+    for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
   }
   __syncthreads();
 
   // ---- observation vector (Table 2 "Ours"), per joint part
   if (is_joint) {
-    const JointTab& jt = M.joints[idx];
+    const JointTab& jt = Ltjoint[idx];
     const int pa = jt.parent, pb = jt.child;
     float qa[4] = {1, 0, 0, 0}, wa[3] = {0, 0, 0}, qb[4], wb[3];
     if (pa >= 0) {
       for (int c = 0; c < 4; ++c) qa[c] = Lpos[(pa * 7 + 3 + c) * E + e];
-      for (int c = 0; c < 3; ++c) wa[c] = Lvel[(pa * 6 + 3 + c) * E + e];
+      for (int c = 0; c < 3; ++c) wa[c] = Lvel[(pa * kVS + 3 + c) * E + e];
     }
     for (int c = 0; c < 4; ++c) qb[c] = Lpos[(pb * 7 + 3 + c) * E + e];
-    for (int c = 0; c < 3; ++c) wb[c] = Lvel[(pb * 6 + 3 + c) * E + e];
+    for (int c = 0; c < 3; ++c) wb[c] = Lvel[(pb * kVS + 3 + c) * E + e];
     float Ra[9], phi[3];
     quat_to_mat(qa, Ra);
     rel_rotvec(qa, qb, phi);
@@ -885,7 +1009,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     float rx[3], rq[4], rv[3], rw[3];
     for (int c = 0; c < 3; ++c) rx[c] = Lpos[(rb * 7 + c) * E + ee];
     for (int c = 0; c < 4; ++c) rq[c] = Lpos[(rb * 7 + 3 + c) * E + ee];
-    for (int c = 0; c < 3; ++c) { rv[c] = Lvel[(rb * 6 + c) * E + ee]; rw[c] = Lvel[(rb * 6 + 3 + c) * E + ee]; }
+    for (int c = 0; c < 3; ++c) { rv[c] = Lvel[(rb * kVS + c) * E + ee]; rw[c] = Lvel[(rb * kVS + 3 + c) * E + ee]; }
     float ox = a.origins[3 * env_e], oy = a.origins[3 * env_e + 1], oz = a.origins[3 * env_e + 2];
     float height = rx[2];
     if (M.terrain_kind == 1) height = rx[2] + oz - terrain_height(M, a.heights, rx[0] + ox, rx[1] + oy);
