@@ -278,26 +278,36 @@ __device__ __forceinline__ bool slot_reach(const Field& H, SlotGeom& g) {
     const int I0 = (g.i0 - H.pi0) / kMip, I1 = (g.i1 + 1 - H.pi0) / kMip;
     const int J0 = (g.j0 - H.pj0) / kMip, J1 = (g.j1 + 1 - H.pj0) / kMip;
     if (I1 - I0 <= 2 && J1 - J0 <= 2) {
+      {
+        float m[9];
 #pragma unroll
-      for (int dj = 0; dj < 3; ++dj)
+        for (int dj = 0; dj < 3; ++dj)
 #pragma unroll
-        for (int di = 0; di < 3; ++di) {
-          int I = I0 + di < I1 ? I0 + di : I1, J = J0 + dj < J1 ? J0 + dj : J1;
-          hmax = fmaxf(hmax, H.mip[J * nb + I]);
-        }
+          for (int di = 0; di < 3; ++di) {
+            int I = I0 + di < I1 ? I0 + di : I1, J = J0 + dj < J1 ? J0 + dj : J1;
+            m[dj * 3 + di] = H.mip[J * nb + I];
+          }
+        __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);  // the nine reads first, one wait
+#pragma unroll
+        for (int k = 0; k < 9; ++k) hmax = fmaxf(hmax, m[k]);
+      }
       // block maxima say "maybe": take the exact maximum over the samples of the box when it
       // is at most 6 x 6 (all 36 reads are issued together, indices clamped into the box)
       const int ni = g.i1 - g.i0 + 2, nj = g.j1 - g.j0 + 2;
       if (!(zcut > hmax) && ni <= 6 && nj <= 6) {
         const int bi = g.i0 - H.pi0, bj = g.j0 - H.pj0;
         hmax = -INFINITY;
+        float hv[36];
+        int col[6], row[6];
+#pragma unroll
+        for (int d = 0; d < 6; ++d) { col[d] = bi + (d < ni ? d : ni - 1); row[d] = (bj + (d < nj ? d : nj - 1)) * H.ps; }
 #pragma unroll
         for (int dj = 0; dj < 6; ++dj)
 #pragma unroll
-          for (int di = 0; di < 6; ++di) {
-            int pi = bi + (di < ni ? di : ni - 1), pj = bj + (dj < nj ? dj : nj - 1);
-            hmax = fmaxf(hmax, H.patch[pj * H.ps + pi]);
-          }
+          for (int di = 0; di < 6; ++di) hv[dj * 6 + di] = H.patch[row[dj] + col[di]];
+        __builtin_amdgcn_sched_group_barrier(0x100, 36, 0);  // all reads before the first use
+#pragma unroll
+        for (int k = 0; k < 36; ++k) hmax = fmaxf(hmax, hv[k]);
       }
     } else {
       for (int J = J0; J <= J1; ++J)
@@ -342,27 +352,47 @@ __device__ __forceinline__ void keep_min(float d2, int id, float& best, int& bes
   if (d2 < best || (d2 == best && id < best_id)) { best = d2; best_id = id; }
 }
 
-// Both triangles of cell (i,j) against the end sphere centred at P.
-__device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float zcut, int i, int j, float& best,
-                                            int& best_id) {
-  const int ncx = H.nx - 1;
+// Cheap part of the end-sphere search: can a triangle of cell (i,j) be within R of P?  Lower
+// bound of the distance from the horizontal gap to the cell's square and the height of P above
+// the cell's highest corner.
+__device__ __forceinline__ bool sphere_cell_reach(const Field& H, f3 P, float R, int i, int j) {
   float h00, h10, h11, h01;
   field_cell_heights(H, i, j, h00, h10, h11, h01);
-  float zmax = fmaxf(fmaxf(h00, h10), fmaxf(h11, h01));
-  if (zcut > zmax) return;  // whole cell further than r + margin + slack below the sphere
+  const float zmax = fmaxf(fmaxf(h00, h10), fmaxf(h11, h01));
+  const float x0 = H.ox + (float)i * H.cell, x1 = H.ox + (float)(i + 1) * H.cell;
+  const float y0 = H.oy + (float)j * H.cell, y1 = H.oy + (float)(j + 1) * H.cell;
+  const float gx = fmaxf(fmaxf(x0 - P.x, P.x - x1), 0.0f), gy = fmaxf(fmaxf(y0 - P.y, P.y - y1), 0.0f);
+  const float gz = fmaxf(P.z - zmax, 0.0f);
+  return !((gx * gx + gy * gy) + gz * gz > R * R);
+}
+
+// Exact part: triangle t of cell (i,j) against the sphere centre P.  False when back-facing.
+__device__ __forceinline__ bool sphere_tri_d2(const Field& H, f3 P, int i, int j, int t, float& d2) {
+  float h00, h10, h11, h01;
+  field_cell_heights(H, i, j, h00, h10, h11, h01);
   float x0 = H.ox + (float)i * H.cell, x1 = H.ox + (float)(i + 1) * H.cell;
   float y0 = H.oy + (float)j * H.cell, y1 = H.oy + (float)(j + 1) * H.cell;
-  f3 A = f3{x0, y0, h00}, B1 = f3{x1, y0, h10}, C1 = f3{x1, y1, h11}, D1 = f3{x0, y1, h01};
+  f3 A = f3{x0, y0, h00}, C1 = f3{x1, y1, h11};
+  f3 Bv = t == 0 ? f3{x1, y0, h10} : C1, Cv = t == 0 ? C1 : f3{x0, y1, h01};
+  f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
+  float face = dot3(sub3(P, A), nt);
+  if (face < 0.0f) return false;  // back-facing
+  float v, w;
+  tri_closest_vw(P, A, Bv, Cv, v, w);
+  f3 df = sub3(P, tri_point(A, Bv, Cv, v, w));
+  d2 = dot3(df, df);
+  return true;
+}
+
+// Both triangles of cell (i,j) against the end sphere centred at P (reach R = r + margin + slack).
+__device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float R, int i, int j, float& best,
+                                            int& best_id) {
+  const int ncx = H.nx - 1;
+  if (!sphere_cell_reach(H, P, R + kSelSlack, i, j)) return;
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    f3 Bv = t == 0 ? B1 : C1, Cv = t == 0 ? C1 : D1;
-    f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
-    float face = dot3(sub3(P, A), nt);
-    if (face < 0.0f) continue;  // back-facing
-    float v, w;
-    tri_closest_vw(P, A, Bv, Cv, v, w);
-    f3 df = sub3(P, tri_point(A, Bv, Cv, v, w));
-    keep_min(dot3(df, df), 2 * (j * ncx + i) + t, best, best_id);
+    float d2;
+    if (sphere_tri_d2(H, P, i, j, t, d2)) keep_min(d2, 2 * (j * ncx + i) + t, best, best_id);
   }
 }
 
@@ -375,16 +405,33 @@ __device__ __forceinline__ void sphere_cell(const Field& H, f3 P, float zcut, in
 // within R of it has s = along / L^2 in [amin - R L, amax + R L] / L^2, and the edge is out of
 // reach when that part stays more than R above both its ends.
 struct SegCull {
+  f3 P0;                                // first end point (world)
   float dx, dy, dz, L2, RL, R, inv_L2;  // inv_L2 = 0: segment (nearly) vertical, no s interval
+  float zcut;                           // lower end minus the reach
+  int i1, j1;                           // last cell of the box in x and y
 };
-__device__ __forceinline__ SegCull seg_cull(const SlotGeom& g) {
+__device__ __forceinline__ SegCull seg_cull_from(f3 P0, f3 P1, float Rq, float RL, float inv_L2, int i1, int j1) {
   SegCull c;
-  c.dx = g.P1.x - g.P0.x; c.dy = g.P1.y - g.P0.y; c.dz = g.P1.z - g.P0.z;
+  c.P0 = P0;
+  c.dx = P1.x - P0.x; c.dy = P1.y - P0.y; c.dz = P1.z - P0.z;
   c.L2 = c.dx * c.dx + c.dy * c.dy;
-  c.R = g.Rq + kSelSlack;
-  c.RL = c.R * sqrtf(c.L2);
-  c.inv_L2 = c.L2 > 1e-8f ? 1.0f / c.L2 : 0.0f;
+  c.R = Rq + kSelSlack;
+  c.RL = RL; c.inv_L2 = inv_L2;
+  c.zcut = (P0.z < P1.z ? P0.z : P1.z) - Rq;
+  c.i1 = i1; c.j1 = j1;
   return c;
+}
+// the two per-slot constants worth keeping: R L and 1 / L^2
+__device__ __forceinline__ void seg_cull_consts(const SlotGeom& g, float& RL, float& inv_L2) {
+  const float dx = g.P1.x - g.P0.x, dy = g.P1.y - g.P0.y;
+  const float L2 = dx * dx + dy * dy;
+  RL = (g.Rq + kSelSlack) * sqrtf(L2);
+  inv_L2 = L2 > 1e-8f ? 1.0f / L2 : 0.0f;
+}
+__device__ __forceinline__ SegCull seg_cull(const SlotGeom& g) {
+  float RL, inv_L2;
+  seg_cull_consts(g, RL, inv_L2);
+  return seg_cull_from(g.P0, g.P1, g.Rq, RL, inv_L2, g.i1, g.j1);
 }
 
 // Cheap part of the mid-segment search at sample (i,j): bit k of the result is set when edge k
@@ -392,10 +439,9 @@ __device__ __forceinline__ SegCull seg_cull(const SlotGeom& g) {
 // segment.  The three edges lie in the square of cell (i,j), so one test of that square (cross
 // and along intervals of its corners, height of the reachable part of the segment above its
 // highest corner) serves all three.
-__device__ __forceinline__ int segment_candidates(const Field& H, const SlotGeom& g, const SegCull& sc, float zcut,
-                                                  int i, int j) {
+__device__ __forceinline__ int segment_candidates(const Field& H, const SegCull& sc, int i, int j) {
   const float x0 = H.ox + (float)i * H.cell, y0 = H.oy + (float)j * H.cell;
-  const float rx0 = x0 - g.P0.x, ry0 = y0 - g.P0.y;
+  const float rx0 = x0 - sc.P0.x, ry0 = y0 - sc.P0.y;
   const float c0 = sc.dx * ry0 - sc.dy * rx0, a0 = sc.dx * rx0 + sc.dy * ry0;
   // a step of one cell along +x changes (cross, along) by (-se, ce), along +y by (ce, se)
   const float ce = sc.dx * H.cell, se = sc.dy * H.cell;
@@ -418,16 +464,16 @@ __device__ __forceinline__ int segment_candidates(const Field& H, const SlotGeom
     }
   }
   const float zq = fmaxf(fmaxf(h00, h10), fmaxf(h01, h11));
-  if (zcut > zq) return 0;  // the whole square is out of reach below the capsule
+  if (sc.zcut > zq) return 0;  // the whole square is out of reach below the capsule
   if (sc.inv_L2 > 0.0f) {
     const float s_lo = fmaxf((amin - lim) * sc.inv_L2 - 1e-4f, 0.0f);
     const float s_hi = fminf((amax + lim) * sc.inv_L2 + 1e-4f, 1.0f);
-    const float zs = g.P0.z + sc.dz * (sc.dz >= 0.0f ? s_lo : s_hi);
+    const float zs = sc.P0.z + sc.dz * (sc.dz >= 0.0f ? s_lo : s_hi);
     if (zs - sc.R > zq) return 0;
   }
   int mask = 7;
-  if (i > g.i1) mask &= 2;   // edges 0 and 2 leave the box in x
-  if (j > g.j1) mask &= 1;   // edges 1 and 2 leave the box in y
+  if (i > sc.i1) mask &= 2;   // edges 0 and 2 leave the box in x
+  if (j > sc.j1) mask &= 1;   // edges 1 and 2 leave the box in y
   return mask;
 }
 
@@ -450,9 +496,9 @@ __device__ __forceinline__ bool segment_edge_d2(const Field& H, f3 P0, f3 P1, in
 }
 
 // The up-to-three edges that start at sample (i,j) against the segment interior.
-__device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g, const SegCull& sc, float zcut,
-                                               int i, int j, float& best, int& best_id) {
-  const int mask = segment_candidates(H, g, sc, zcut, i, j);
+__device__ __forceinline__ void segment_vertex(const Field& H, const SlotGeom& g, const SegCull& sc, int i, int j,
+                                               float& best, int& best_id) {
+  const int mask = segment_candidates(H, sc, i, j);
 #pragma unroll
   for (int k = 0; k < 3; ++k) {
     float d2;
@@ -547,15 +593,13 @@ __device__ inline ContactOut generate_contact(const Model& M, const float* __res
     ContactOut out = no_contact();
     if (underneath_contact(H, g, M.margin, out)) return out;
     f3 P = slot_kind == 0 ? g.P0 : g.P1;
-    const float zcut = P.z - g.Rq;
     for (int j = g.j0; j <= g.j1; ++j)
-      for (int i = g.i0; i <= g.i1; ++i) sphere_cell(H, P, zcut, i, j, best, best_id);
+      for (int i = g.i0; i <= g.i1; ++i) sphere_cell(H, P, g.Rq, i, j, best, best_id);
     return finish_sphere(H, g, M.margin, best, best_id);
   }
-  const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
   const SegCull sc = seg_cull(g);
   for (int j = g.j0; j <= g.j1 + 1; ++j)
-    for (int i = g.i0; i <= g.i1 + 1; ++i) segment_vertex(H, g, sc, zcut, i, j, best, best_id);
+    for (int i = g.i0; i <= g.i1 + 1; ++i) segment_vertex(H, g, sc, i, j, best, best_id);
   return finish_segment(H, g, M.margin, best, best_id);
 }
 

@@ -274,6 +274,28 @@ __device__ __forceinline__ unsigned long long pack_best(float d2, int id) {
   return ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned)id;
 }
 
+// Number of set bits of a 64-bit lane mask below the calling lane.
+__device__ __forceinline__ int lanes_below(unsigned long long m) {
+  return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+}
+// Reserves n (0..31) consecutive entries of a list for each active lane with one atomic per
+// wavefront; every active lane has to call it.  Returns the lane's first index.
+__device__ __forceinline__ int wave_alloc(int n, int* counter) {
+  int before = 0, total = 0;
+#pragma unroll
+  for (int bit = 0; bit < 5; ++bit) {
+    const unsigned long long bm = __ballot((n >> bit) & 1);
+    before += lanes_below(bm) << bit;
+    total += __popcll(bm) << bit;
+  }
+  int base = 0;
+  if (total > 0) {
+    if (lanes_below(__ballot(1)) == 0) base = atomicAdd(counter, total);
+    base = __builtin_amdgcn_readfirstlane(base);
+  }
+  return base + before;
+}
+
 template <int EC, int NJ>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 #ifdef EXP_TIMING
@@ -290,7 +312,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const bool is_body = idx < B && env_ok;
   const bool is_joint = idx < J && env_ok;
   const int obs_dim = 11 + 3 * D + F;
-  const bool use_patch = M.terrain_kind == 1 && M.nx >= kPatch && M.ny >= kPatch;
+  // model scalars the loops below use, read once (before the kernel's first store, so they come
+  // through the scalar cache and stay in scalar registers)
+  const int m_terrain = M.terrain_kind, m_contacts = M.contacts;
+  const Field H0 = make_field(M, a.heights, a.coarse);
+  const bool use_patch = m_terrain == 1 && H0.nx >= kPatch && H0.ny >= kPatch;
   const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0);
   float* Lpos = lds + P.pos;
   float* Lvel = lds + P.vel;
@@ -307,8 +333,13 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   // fine search: per queued slot the minimum of (squared distance, feature id) packed in 64 bits,
   // then the list of candidate edges; both live in the space of the copies the sweeps use
   unsigned long long* Lbest64 = reinterpret_cast<unsigned long long*>(lds + P.outj);
-  unsigned* Lcand = reinterpret_cast<unsigned*>(lds + P.outj) + 2 * S * E;
-  const int cand_cap = (J * kJS + S * kCS) * E - 2 * S * E;
+  float* Lgeo = lds + P.outj + 2 * S * E;           // per queued slot: reach, and R L, 1/L^2 of a segment
+  unsigned* Lcand = reinterpret_cast<unsigned*>(lds + P.outj) + 5 * S * E;
+  const int cand_cap = (J * kJS + S * kCS) * E - 5 * S * E;
+  // work units of the fine search (8 cells of one queued slot each): end spheres in the first
+  // third of the list, mid-segments in the rest.  The space holds the observations at the end.
+  unsigned* Lunit = reinterpret_cast<unsigned*>(lds + P.obs);
+  const int unit_cap = (11 + 3 * D + F) * E, unit_cap_e = unit_cap / 3;
   float* Ltq = lds + P.tq;                           // joint torques, [J][3][E]
   float* Lu = lds + P.u;
   float* Lobs = lds + P.obs;
@@ -436,7 +467,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     asm volatile("" : "+s"(h));
     const int b = idx;
     // ---- A: publish pose and world inverse inertia
-    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; }
+    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; Lcount[5] = 0; Lcount[6] = 0; }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
@@ -476,15 +507,19 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       }
       for (int c = 0; c < 3; ++c) Ltq[(idx * 3 + c) * E + e] = tq[c];
     }
-    // ---- B1: every slot: plane contact, or reach test against the heightfield copy;
-    //          slots that may touch the heightfield (block maxima, then the exact maximum over
-    //          the box) are queued for the fine search: end spheres from the front of the
-    //          queue, mid-segments from the back
-    for (int i = tid; i < S * E; i += kThreads) {
+    // ---- B1: every slot: plane contact, or reach test against the heightfield copy.  A slot
+    //          that may touch the heightfield (block maxima, then the exact maximum over its box)
+    //          is queued (end spheres from the front of the queue, mid-segments from the back), its
+    //          world-space geometry is left in its still unused record, and its box is cut into
+    //          work units of 8 cells (samples for a mid-segment).
+    //          Slots go to the threads from the top of the workgroup down: a second round, if any,
+    //          then runs on the last wavefronts while the first ones hold the joint threads.
+    for (int i = kThreads - 1 - tid; i < S * E; i += kThreads) {
       int ee = i % E, s = i / E;
       int env_i = blockIdx.x * E + ee;
       ContactOut co = no_contact();
-      if (env_i < N && M.contacts) {
+      int nu_e = 0, nu_m = 0, qi = 0;
+      if (env_i < N && m_contacts) {
         const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
         float bx[3], bq[4], bo[3];
         for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
@@ -492,16 +527,45 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
         SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
                                p_margin, bx, bq, sl.kind, bo);
-        if (M.terrain_kind == 0) {
+        if (m_terrain == 0) {
           co = plane_contact(g, p_margin);
         } else {
-          Field H = make_field(M, a.heights, a.coarse);
+          Field H = H0;
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
           if (slot_reach(H, g)) {
-            if (sl.kind < 2) Lsurv[atomicAdd(&Lcount[1], 1)] = i;
-            else Lsurv[S * E - 1 - atomicAdd(&Lcount[2], 1)] = i;
+            const bool mid = sl.kind == 2;
+            qi = mid ? S * E - 1 - atomicAdd(&Lcount[2], 1) : atomicAdd(&Lcount[1], 1);
+            Lsurv[qi] = i;
+            Lbest64[qi] = ~0ull;
+            const int ni = g.i1 - g.i0 + (mid ? 2 : 1), nj = g.j1 - g.j0 + (mid ? 2 : 1);
+            const bool fits = ni <= 15 && nj <= 15 && g.i0 < 4096 && g.j0 < 4096;  // packed box below
+            const f3 Pa = sl.kind == 1 ? g.P1 : g.P0;
+            Lrec[(s * kRecWords + 1) * E + ee] = Pa.x; Lrec[(s * kRecWords + 2) * E + ee] = Pa.y;
+            Lrec[(s * kRecWords + 3) * E + ee] = Pa.z;
+            Lreci[(s * kRecWords + 7) * E + ee] = g.i0 | (g.j0 << 12) | (ni << 24) | (nj << 28);
+            Lreci[(s * kRecWords + 8) * E + ee] = fits ? 0 : 1;   // 1: search this slot the slow way
+            Lgeo[3 * qi] = g.Rq;
+            if (mid) {
+              Lrec[(s * kRecWords + 4) * E + ee] = g.P1.x; Lrec[(s * kRecWords + 5) * E + ee] = g.P1.y;
+              Lrec[(s * kRecWords + 6) * E + ee] = g.P1.z;
+              float RL, inv_L2;
+              seg_cull_consts(g, RL, inv_L2);
+              Lgeo[3 * qi + 1] = RL; Lgeo[3 * qi + 2] = inv_L2;
+            }
+            if (!fits) Lcount[4] = 1;
+            else if (mid) nu_m = (ni * nj + 7) >> 3;
+            else nu_e = (ni * nj + 7) >> 3;
           }
         }
+      }
+      if (m_terrain == 1) {
+        // list space for the units of the whole wavefront, one atomic per kind
+        const int ue = wave_alloc(nu_e, &Lcount[5]), um = wave_alloc(nu_m, &Lcount[6]);
+        const int nu = nu_e + nu_m, u0 = nu_e ? ue : um, cap = nu_e ? unit_cap_e : unit_cap - unit_cap_e;
+        unsigned* U = Lunit + (nu_e ? 0 : unit_cap_e);
+        for (int u = 0; u < nu; ++u)
+          if (u0 + u < cap) U[u0 + u] = (unsigned)qi | ((unsigned)u << 12);
+        if (nu > 0 && u0 + nu > cap) { Lreci[(s * kRecWords + 8) * E + ee] = 1; Lcount[4] = 1; }
       }
       if (co.active) {
         store_record(Lrec, Lreci, s, ee, E, co);
@@ -512,118 +576,83 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       }
     }
     TMARK(2);
-    if (M.terrain_kind == 1) {
+    if (m_terrain == 1) {
       __syncthreads();
-      // ---- B2: fine search, kGroup lanes per queued slot; lanes split the cells (or samples)
-      //          of the reach box and the group keeps the lexicographic minimum of (d2, id).
-      //          The two kinds of slot run in separate loops so a wavefront follows one path.
+      // ---- B2: fine search in two stages.  Stage 1: kGroup lanes per work unit, one cell per
+      //          lane: a cheap reach test decides which triangles (end sphere) or edges
+      //          (mid-segment) of the cell become candidates.  Stage 2: one candidate per thread:
+      //          exact distance, minimum of (d2, id) per slot with a 64-bit LDS atomic.
       const int grp = tid / kGroup, gl = tid % kGroup;
-      Field H = make_field(M, a.heights, a.coarse);
+      Field H = H0;
       const int n_end = Lcount[1], n_mid = Lcount[2];
       for (int pass = 0; pass < 2; ++pass) {
-        const int n_q = pass == 0 ? n_end : n_mid;
-        for (int sv = grp; sv < n_q; sv += kThreads / kGroup) {
-          const int qi = pass == 0 ? sv : S * E - 1 - sv;
+        const int cap = pass == 0 ? unit_cap_e : unit_cap - unit_cap_e;
+        const int n_u = Lcount[5 + pass] < cap ? Lcount[5 + pass] : cap;
+        const unsigned* U = Lunit + (pass == 0 ? 0 : unit_cap_e);
+        for (int x = grp; x < n_u; x += kThreads / kGroup) {
+          const unsigned uw = U[x];
+          const int qi = uw & 4095, c = (int)(uw >> 12) * 8 + gl;
           const int i = Lsurv[qi];
           const int ee = i % E, s = i / E;
-          const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
-          float bx[3], bq[4], bo[3];
-          for (int c = 0; c < 3; ++c) bx[c] = Lpos[(sl.body * 7 + c) * E + ee];
-          for (int c = 0; c < 4; ++c) bq[c] = Lpos[(sl.body * 7 + 3 + c) * E + ee];
-          for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
-          SlotGeom g = slot_geom(Ltbody[4 * sl.body], Ltbody[4 * sl.body + 1], __float_as_int(Ltbody[4 * sl.body + 2]),
-                                 p_margin, bx, bq, sl.kind, bo);
+          const unsigned box = (unsigned)Lreci[(s * kRecWords + 7) * E + ee];
+          const int i0 = box & 4095, j0 = (box >> 12) & 4095, ni = (box >> 24) & 15, nj = box >> 28;
+          // c / ni for small non-negative integers: the quotient of (c + 0.5) / ni is at least
+          // 0.5 / 15 away from an integer, far more than the error of the reciprocal
+          const int dj = (int)(((float)c + 0.5f) * __builtin_amdgcn_rcpf((float)ni)), di = c - dj * ni;
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
-          slot_range(H, g);
+          const f3 Pa = f3{Lrec[(s * kRecWords + 1) * E + ee], Lrec[(s * kRecWords + 2) * E + ee], Lrec[(s * kRecWords + 3) * E + ee]};
+          const float Rq = Lgeo[3 * qi];
+          int mask = 0;
           if (pass == 0) {
-            float best = INFINITY;
-            int best_id = -1;
-            f3 Pc = sl.kind == 0 ? g.P0 : g.P1;
-            const float zcut = Pc.z - g.Rq;
-            const int ni = g.i1 - g.i0 + 1, nc = ni * (g.j1 - g.j0 + 1);
-            for (int c = gl; c < nc; c += kGroup) sphere_cell(H, Pc, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
-#pragma unroll
-            for (int m = kGroup / 2; m >= 1; m >>= 1) {
-              float ob = __shfl_xor(best, m);
-              int oid = __shfl_xor(best_id, m);
-              if (oid >= 0) keep_min(ob, oid, best, best_id);
-            }
-            if (gl == 0) Lbest64[qi] = best_id < 0 ? ~0ull : pack_best(best, best_id);
+            if (c < ni * nj && sphere_cell_reach(H, Pa, Rq + kSelSlack, i0 + di, j0 + dj)) mask = 3;
           } else {
-            // stage 1: the group's lanes split the samples of the box and queue the edges that pass
-            // the cheap reach tests; the segment's end points and the box origin are left in the
-            // slot's (still unused) record for stage 2
-            if (gl == 0) {
-              Lbest64[qi] = ~0ull;
-              Lrec[(s * kRecWords + 1) * E + ee] = g.P0.x; Lrec[(s * kRecWords + 2) * E + ee] = g.P0.y;
-              Lrec[(s * kRecWords + 3) * E + ee] = g.P0.z; Lrec[(s * kRecWords + 4) * E + ee] = g.P1.x;
-              Lrec[(s * kRecWords + 5) * E + ee] = g.P1.y; Lrec[(s * kRecWords + 6) * E + ee] = g.P1.z;
-              Lreci[(s * kRecWords + 7) * E + ee] = g.i0 | (g.j0 << 16);
-              Lreci[(s * kRecWords + 8) * E + ee] = 0;
-            }
-            const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
-            const int ni = g.i1 - g.i0 + 2, nc = ni * (g.j1 - g.j0 + 2);
-            const SegCull sc = seg_cull(g);
-            for (int c = gl; c < nc; c += kGroup) {
-              const int di = c % ni, dj = c / ni;
-              const int mask = segment_candidates(H, g, sc, zcut, g.i0 + di, g.j0 + dj);
-              // list space for the whole wavefront with one atomic: per-lane counts (0..3) are
-              // summed from two ballots
-              const int n_k = (di < 256 && dj < 256) ? __popc(mask) : 0;
-              const unsigned long long b0 = __ballot(n_k & 1), b1 = __ballot(n_k & 2);
-              if ((b0 | b1) == 0 && mask == 0) continue;
-              int pos = cand_cap;
-              if (b0 | b1) {
-                const int leader = __ffsll((long long)(b0 | b1)) - 1;
-                int base = 0;
-                if ((int)__lane_id() == leader) base = atomicAdd(&Lcount[3], __popcll(b0) + 2 * __popcll(b1));
-                base = __shfl(base, leader);
-                pos = base + (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b0 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b0, 0u)) +
-                      2 * (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b1 >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)b1, 0u));
-              }
-              if (mask == 0) continue;
-              if (n_k == 0) pos = cand_cap;  // box too large for the packed index
-              const unsigned cw = (unsigned)qi | ((unsigned)di << 14) | ((unsigned)dj << 22);
+            const f3 Pb = f3{Lrec[(s * kRecWords + 4) * E + ee], Lrec[(s * kRecWords + 5) * E + ee], Lrec[(s * kRecWords + 6) * E + ee]};
+            const SegCull sc = seg_cull_from(Pa, Pb, Rq, Lgeo[3 * qi + 1], Lgeo[3 * qi + 2], i0 + ni - 2, j0 + nj - 2);
+            if (c < ni * nj) mask = segment_candidates(H, sc, i0 + di, j0 + dj);
+          }
+          int pos = wave_alloc(__popc(mask), &Lcount[3]);
+          const unsigned cw = (unsigned)qi | ((unsigned)di << 14) | ((unsigned)dj << 18) | ((unsigned)pass << 22);
 #pragma unroll
-              for (int k = 0; k < 3; ++k)
-                if ((mask >> k) & 1) {
-                  if (pos < cand_cap) Lcand[pos] = cw | ((unsigned)k << 12);
-                  ++pos;
-                }
-              if (pos > cand_cap) {
-                // list full (or box too large for the packed index): the slot is searched again
-                // by the fallback below
-                Lreci[(s * kRecWords + 8) * E + ee] = 1;
-                Lcount[4] = 1;
-              }
+          for (int k = 0; k < 3; ++k)
+            if ((mask >> k) & 1) {
+              if (pos < cand_cap) Lcand[pos] = cw | ((unsigned)k << 12);
+              ++pos;
             }
+          if (mask != 0 && pos > cand_cap) {
+            // candidate list full: the slot is searched again by the fallback below
+            Lreci[(s * kRecWords + 8) * E + ee] = 1;
+            Lcount[4] = 1;
           }
         }
-        __syncthreads();
         TMARK(10 + pass);
       }
+      __syncthreads();
       {
-        // stage 2 of the mid-segment search: one queued edge per thread
         const int n_c = Lcount[3] < cand_cap ? Lcount[3] : cand_cap;
         for (int t = tid; t < n_c; t += kThreads) {
           const unsigned cw = Lcand[t];
-          const int qi = cw & 4095, k = (cw >> 12) & 3, di = (cw >> 14) & 255, dj = (cw >> 22) & 255;
+          const int qi = cw & 4095, k = (cw >> 12) & 3, di = (cw >> 14) & 15, dj = (cw >> 18) & 15;
           const int i = Lsurv[qi];
           const int ee = i % E, s = i / E;
-          const f3 P0 = f3{Lrec[(s * kRecWords + 1) * E + ee], Lrec[(s * kRecWords + 2) * E + ee], Lrec[(s * kRecWords + 3) * E + ee]};
-          const f3 P1 = f3{Lrec[(s * kRecWords + 4) * E + ee], Lrec[(s * kRecWords + 5) * E + ee], Lrec[(s * kRecWords + 6) * E + ee]};
-          const int ij = Lreci[(s * kRecWords + 7) * E + ee];
-          const int ci = (ij & 0xffff) + di, cj = (ij >> 16) + dj;
+          const unsigned box = (unsigned)Lreci[(s * kRecWords + 7) * E + ee];
+          const int ci = (int)(box & 4095) + di, cj = (int)((box >> 12) & 4095) + dj;
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          const f3 Pa = f3{Lrec[(s * kRecWords + 1) * E + ee], Lrec[(s * kRecWords + 2) * E + ee], Lrec[(s * kRecWords + 3) * E + ee]};
           float d2;
-          if (segment_edge_d2(H, P0, P1, ci, cj, k, d2)) atomicMin(&Lbest64[qi], pack_best(d2, 3 * (cj * H.nx + ci) + k));
+          if (((cw >> 22) & 1) == 0) {
+            if (sphere_tri_d2(H, Pa, ci, cj, k, d2)) atomicMin(&Lbest64[qi], pack_best(d2, 2 * (cj * (H.nx - 1) + ci) + k));
+          } else {
+            const f3 Pb = f3{Lrec[(s * kRecWords + 4) * E + ee], Lrec[(s * kRecWords + 5) * E + ee], Lrec[(s * kRecWords + 6) * E + ee]};
+            if (segment_edge_d2(H, Pa, Pb, ci, cj, k, d2)) atomicMin(&Lbest64[qi], pack_best(d2, 3 * (cj * H.nx + ci) + k));
+          }
         }
         __syncthreads();
         TMARK(13);
         if (Lcount[4]) {
-          // rare: some edges did not fit the list; their slots are searched directly
-          for (int sv = grp; sv < n_mid; sv += kThreads / kGroup) {
-            const int qi = S * E - 1 - sv;
+          // rare: a box too large for the packed indices, or a full list: those slots are searched
+          // directly, kGroup lanes per slot
+          for (int sv = grp; sv < n_end + n_mid; sv += kThreads / kGroup) {
+            const int qi = sv < n_end ? sv : S * E - 1 - (sv - n_end);
             const int i = Lsurv[qi];
             const int ee = i % E, s = i / E;
             if (!Lreci[(s * kRecWords + 8) * E + ee]) continue;
@@ -636,23 +665,30 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
                                    p_margin, bx, bq, sl.kind, bo);
             if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
             slot_range(H, g);
-            const float zcut = (g.P0.z < g.P1.z ? g.P0.z : g.P1.z) - g.Rq;
-            const int ni = g.i1 - g.i0 + 2, nc = ni * (g.j1 - g.j0 + 2);
-            const SegCull sc = seg_cull(g);
             float best = INFINITY;
             int best_id = -1;
-            for (int c = gl; c < nc; c += kGroup) segment_vertex(H, g, sc, zcut, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+            if (sl.kind < 2) {
+              const f3 Pc = sl.kind == 0 ? g.P0 : g.P1;
+              const int ni = g.i1 - g.i0 + 1, nc = ni * (g.j1 - g.j0 + 1);
+              for (int c = gl; c < nc; c += kGroup) sphere_cell(H, Pc, g.Rq, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+            } else {
+              const int ni = g.i1 - g.i0 + 2, nc = ni * (g.j1 - g.j0 + 2);
+              const SegCull sc = seg_cull(g);
+              for (int c = gl; c < nc; c += kGroup) segment_vertex(H, g, sc, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
+            }
             if (best_id >= 0) atomicMin(&Lbest64[qi], pack_best(best, best_id));
           }
           __syncthreads();
         }
       }
 #ifdef EXP_TIMING
-      if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += n_mid; a.dbg[15] += Lcount[3]; }
+      if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += Lcount[5] + Lcount[6]; a.dbg[15] += Lcount[3]; }
 #endif
       // ---- B3: one thread per queued slot turns the selected feature into a contact record
-      for (int sv = tid; sv < n_end + n_mid; sv += kThreads) {
-        const int qi = sv < n_end ? sv : S * E - 1 - (sv - n_end);
+      //          (end spheres on the lower half of the workgroup, mid-segments on the upper half,
+      //          so that a wavefront follows one path)
+      for (int sv = tid & (kThreads / 2 - 1); sv < (tid < kThreads / 2 ? n_end : n_mid); sv += kThreads / 2) {
+        const int qi = tid < kThreads / 2 ? sv : S * E - 1 - sv;
         const int i = Lsurv[qi];
         const int ee = i % E, s = i / E;
         const SlotTab sl{Ltslot[2 * s], Ltslot[2 * s + 1]};
@@ -681,7 +717,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       __syncthreads();
       TMARK(12);
       // the search results shared the space of the contact copies: leave finite numbers behind
-      for (int i = tid; i < 2 * S * E; i += kThreads) Loutj[i] = 0.0f;
+      for (int i = tid; i < 5 * S * E; i += kThreads) Loutj[i] = 0.0f;
     }
     __syncthreads();
     TMARK(3);
