@@ -52,7 +52,14 @@ struct Model {
   BodyTab bodies[kMaxBodies];
   JointTab joints[kMaxJoints];
   SlotTab slots[kMaxSlots];
+  // The tables above in the order and layout the step kernel keeps them in LDS (one contiguous
+  // copy at kernel start): per body {joint-side count, slot0, slot count, joint sides[8]}, per
+  // slot {body, kind}, per body {radius, half length, axis, 1/mass}, per body {inertia[3],
+  // inverse inertia[3]}, then the joint table as it is.
+  int32_t table_words;
+  int32_t table_image[kMaxBodies * (kMaxBodyJoints + 3) + 2 * kMaxSlots + 10 * kMaxBodies + kMaxJoints * 32];
 };
+static_assert(sizeof(JointTab) == 32 * 4, "joint table entry is 32 words");
 
 // Contact record as kept in LDS / exported (matches sim_contact_rec_t: 12 words).
 constexpr int kRecWords = 12;

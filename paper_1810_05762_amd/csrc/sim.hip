@@ -162,6 +162,26 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   m->D = D;
   for (int b = 0; b < m->B; ++b)
     if (m->bodies[b].n_joint_sides > m->max_joint_sides) m->max_joint_sides = m->bodies[b].n_joint_sides;
+  {
+    // LDS image of the tables (see Model::table_image)
+    int32_t* w = m->table_image;
+    auto put_f = [&](float f) { memcpy(w++, &f, 4); };
+    for (int b = 0; b < m->B; ++b) {
+      *w++ = m->bodies[b].n_joint_sides; *w++ = m->bodies[b].slot0; *w++ = m->bodies[b].n_slots;
+      for (int k = 0; k < kMaxBodyJoints; ++k) *w++ = m->bodies[b].joint_sides[k];
+    }
+    for (int i = 0; i < m->S; ++i) { *w++ = m->slots[i].body; *w++ = m->slots[i].kind; }
+    for (int b = 0; b < m->B; ++b) {
+      put_f(m->bodies[b].radius); put_f(m->bodies[b].half_len); *w++ = m->bodies[b].axis; put_f(m->bodies[b].inv_mass);
+    }
+    for (int b = 0; b < m->B; ++b) {
+      for (int c = 0; c < 3; ++c) put_f(m->bodies[b].inertia[c]);
+      for (int c = 0; c < 3; ++c) put_f(m->bodies[b].inv_inertia[c]);
+    }
+    memcpy(w, m->joints, (size_t)m->J * sizeof(JointTab));
+    w += m->J * (int)(sizeof(JointTab) / 4);
+    m->table_words = (int)(w - m->table_image);
+  }
   m->terrain_kind = d->terrain_kind;
   m->nx = d->hf_nx; m->ny = d->hf_ny;
   m->cnx = d->terrain_kind == 1 ? (d->hf_nx - 1 + kCoarse - 1) / kCoarse : 0;

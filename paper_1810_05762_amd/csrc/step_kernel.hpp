@@ -77,7 +77,6 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   o += o & 1;  // the search results kept in the copy arrays are 64-bit words
   p.outj = o; o += J * kJS * E;
   p.outc = o; o += S * kCS * E;
-  p.tjs = o; o += B * (kMaxBodyJoints + 3);
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
   p.surv = o; o += S * E;
@@ -88,6 +87,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.count = o; o += 8;
   p.porg = o; o += 2 * E;
   p.org = o; o += 3 * E;
+  p.tjs = o; o += B * (kMaxBodyJoints + 3);  // tjs .. tjoint: one block, copied from Model::table_image
   p.tslot = o; o += 2 * S;
   p.tbody = o; o += 4 * B;
   p.tin = o; o += 6 * B;
@@ -388,19 +388,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     int c = i / E, ee = i - c * E, env_i = blockIdx.x * E + ee;
     Lorg[i] = env_i < N ? a.origins[3 * env_i + c] : 0.0f;
   }
-  for (int i = tid; i < J * (int)(sizeof(JointTab) / 4); i += kThreads)
-    reinterpret_cast<int*>(lds + P.tjoint)[i] = reinterpret_cast<const int*>(M.joints)[i];
-  for (int i = tid; i < S; i += kThreads) { Ltslot[2 * i] = M.slots[i].body; Ltslot[2 * i + 1] = M.slots[i].kind; }
-  for (int i = tid; i < B; i += kThreads) {
-    Ltbody[4 * i] = M.bodies[i].radius; Ltbody[4 * i + 1] = M.bodies[i].half_len;
-    Ltbody[4 * i + 2] = __int_as_float(M.bodies[i].axis); Ltbody[4 * i + 3] = M.bodies[i].inv_mass;
-    for (int c = 0; c < 3; ++c) { Ltin[6 * i + c] = M.bodies[i].inertia[c]; Ltin[6 * i + 3 + c] = M.bodies[i].inv_inertia[c]; }
-  }
-  for (int i = tid; i < B; i += kThreads) {
-    int* t = Ltjs + i * (kMaxBodyJoints + 3);
-    t[0] = M.bodies[i].n_joint_sides; t[1] = M.bodies[i].slot0; t[2] = M.bodies[i].n_slots;
-    for (int k = 0; k < kMaxBodyJoints; ++k) t[3 + k] = M.bodies[i].joint_sides[k];
-  }
+  for (int i = tid; i < M.table_words; i += kThreads) reinterpret_cast<int*>(lds + P.tjs)[i] = M.table_image[i];
   for (int i = tid; i < (J * kJS + S * kCS) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
   // contact records start cleared (a step with zero substeps packs "no contact")
   for (int i = tid; i < S * E; i += kThreads) {
@@ -428,18 +416,41 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       Lporg[2 * tid] = pi0; Lporg[2 * tid + 1] = pj0;
     }
     __syncthreads();
-    for (int i = tid; i < E * kPatch * kPatch; i += kThreads) {
-      int ee = i / (kPatch * kPatch), r = i - ee * (kPatch * kPatch), pj = r / kPatch, pi = r - pj * kPatch;
-      Lpatch[i] = a.heights[(Lporg[2 * ee + 1] + pj) * M.nx + Lporg[2 * ee] + pi];
+    // thirteen samples per thread in flight at a time (the reads come from L2, one at a time each
+    // would cost its full latency)
+    for (int i0 = tid; i0 < E * kPatch * kPatch; i0 += 13 * kThreads) {
+      float hv[13];
+#pragma unroll
+      for (int k = 0; k < 13; ++k) {
+        const int i = i0 + k * kThreads;
+        hv[k] = 0.0f;
+        if (i < E * kPatch * kPatch) {
+          int ee = i / (kPatch * kPatch), r = i - ee * (kPatch * kPatch), pj = r / kPatch, pi = r - pj * kPatch;
+          hv[k] = a.heights[(Lporg[2 * ee + 1] + pj) * H0.nx + Lporg[2 * ee] + pi];
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 13; ++k)
+        if (i0 + k * kThreads < E * kPatch * kPatch) Lpatch[i0 + k * kThreads] = hv[k];
     }
     __syncthreads();
     for (int i = tid; i < E * kPatchBlocks * kPatchBlocks; i += kThreads) {
       int ee = i / (kPatchBlocks * kPatchBlocks), r = i - ee * (kPatchBlocks * kPatchBlocks);
       int bj = r / kPatchBlocks, bi = r - bj * kPatchBlocks;
+      // (kMip+1)^2 samples, indices clamped into the copy, all reads issued before the first use
+      float hv[(kMip + 1) * (kMip + 1)];
+#pragma unroll
+      for (int dj = 0; dj <= kMip; ++dj)
+#pragma unroll
+        for (int di = 0; di <= kMip; ++di) {
+          const int pj = bj * kMip + dj < kPatch ? bj * kMip + dj : kPatch - 1;
+          const int pi = bi * kMip + di < kPatch ? bi * kMip + di : kPatch - 1;
+          hv[dj * (kMip + 1) + di] = Lpatch[ee * (kPatch * kPatch) + pj * kPatch + pi];
+        }
+      __builtin_amdgcn_sched_group_barrier(0x100, (kMip + 1) * (kMip + 1), 0);
       float hm = -INFINITY;
-      for (int pj = bj * kMip; pj <= bj * kMip + kMip && pj < kPatch; ++pj)
-        for (int pi = bi * kMip; pi <= bi * kMip + kMip && pi < kPatch; ++pi)
-          hm = fmaxf(hm, Lpatch[ee * (kPatch * kPatch) + pj * kPatch + pi]);
+#pragma unroll
+      for (int k = 0; k < (kMip + 1) * (kMip + 1); ++k) hm = fmaxf(hm, hv[k]);
       Lmip[i] = hm;
     }
   }
