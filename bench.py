@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload configuration (3 = headline)")
     ap.add_argument("--envs-per-block", type=int, default=0)
+    ap.add_argument("--num-envs", type=int, default=0, help="override the number of envs (scaling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -69,7 +70,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     dev = torch.device("cuda:0")
-    scene, cfg = scenes.config_scene(args.config)
+    scene, cfg = scenes.config_scene(args.config, num_envs=args.num_envs or None)
     N, rob = scene.num_envs, scene.robot
     sim = P.Sim(scene, device=dev)
     if args.envs_per_block:
@@ -116,6 +117,10 @@ def main():
     fl = flops_per_env_step(rob.n_bodies, rob.n_joints, sim.S, sub, its, active, blocks_per_body)
     bA, bB, bC = bytes_per_env_step(rob.n_bodies, rob.n_joints, sim.S, rob.n_dofs, sim.obs_dim, sub, its, active)
     achieved_tflops = fl * N / (kern_ms * 1e-3) / 1e12
+    # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
+    # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.5 MB
+    # read + 4.1 MB written (summary under profiles/); other sizes were not measured
+    traffic = 12.6e6 if (args.config == 3 and N == 4096) else None
     peak_tflops = 157.3
     value = N * args.steps / elapsed
     out = {
@@ -123,13 +128,13 @@ def main():
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg["name"], "num_envs": N, "robot": rob.name, "bodies": rob.n_bodies,
+        "config": {"workload": cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}", "num_envs": N, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
                    "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
                    "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 2},
         "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,
-                     "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": traffic,
                      "flops_per_env_step": fl, "kernel_ms": kern_ms},
         "hbm_roofline": {
             "peak_GBps": 8000.0, "kernel_ms": kern_ms,
