@@ -224,3 +224,36 @@ def make_single(radius=0.1, seg_len=0.0, axis=0, pos=(0.0, 0.0, 1.0), mass=1.0):
     bld = _Builder("single")
     bld.body("body", radius, seg_len, axis, pos, mass=mass)
     return bld.build(root_body=0, feet=(0,), term_height=-1e9, alive_bonus=0.0)
+
+
+def make_star(n_legs=6, hub_radius=0.2, seg_len=0.3, radius=0.05, height=0.6, gear=5.0):
+    """Sphere hub with ``n_legs`` horizontal capsules hinged to it about z: the hub belongs to
+    ``n_legs`` joints (more than any body of the ant or the humanoid).  Legs point along +-x / +-y
+    in turn, staggered in height so that they do not coincide."""
+    bld = _Builder("star")
+    hub = bld.body("hub", hub_radius, 0.0, 0, (0.0, 0.0, height), mass=2.0)
+    dirs = [(1, 0), (0, 1), (-1, 0), (0, -1)]
+    for k in range(n_legs):
+        dx, dy = dirs[k % 4]
+        z = height + 0.08 * (k // 4) - 0.04 * ((k // 4) % 2)
+        a = np.array([dx * hub_radius, dy * hub_radius, z])
+        c = a + np.array([dx, dy, 0.0]) * (seg_len / 2.0)
+        leg = bld.body(f"leg{k}", radius, seg_len, 0 if dx else 1, tuple(c), mass=0.3)
+        bld.joint(hub, leg, tuple(a), [((0.0, 0.0, 1.0), -0.6, 0.6)], gear)
+    return bld.build(root_body=0, feet=(), term_height=-1e9, alive_bonus=0.0)
+
+
+def make_raft(n_links=13, seg_len=0.25, radius=0.05, clearance=0.01, gear=2.0):
+    """Free chain of capsules lying along x just above the ground: every end sphere is within
+    the contact margin from the first substep on (many simultaneous contacts per env)."""
+    bld = _Builder("raft")
+    prev = -1
+    x = 0.0
+    for k in range(n_links):
+        c = (x + seg_len / 2.0, 0.0, radius + clearance)
+        b = bld.body(f"link{k}", radius, seg_len, 0, c, mass=0.4)
+        if prev >= 0:
+            bld.joint(prev, b, (x, 0.0, radius + clearance), [((0.0, 1.0, 0.0), -0.5, 0.5)], gear)
+        prev = b
+        x += seg_len
+    return bld.build(root_body=n_links // 2, feet=(0, n_links - 1), term_height=-1e9, alive_bonus=0.0)
