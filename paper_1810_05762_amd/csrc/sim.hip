@@ -207,7 +207,11 @@ static int default_envs_per_block(const Model& m, int N) {
   if (lim > 16) lim = 16;
   int want = N / 256;  // keep at least one workgroup per compute unit when N allows
   if (want < 1) want = 1;
-  return want < lim ? want : lim;
+  int E = want < lim ? want : lim;
+  // and the workgroup's LDS arrays have to fit
+  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
+  while (E > 1 && (size_t)make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch).total * sizeof(float) > 160 * 1024) --E;
+  return E;
 }
 
 // ----------------------------------------------------------------- kernels

@@ -278,12 +278,13 @@ __device__ __forceinline__ unsigned long long pack_best(float d2, int id) {
 __device__ __forceinline__ int lanes_below(unsigned long long m) {
   return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
 }
-// Reserves n (0..31) consecutive entries of a list for each active lane with one atomic per
-// wavefront; every active lane has to call it.  Returns the lane's first index.
+// Reserves n (0 .. 2^kBits - 1) consecutive entries of a list for each active lane with one
+// atomic per wavefront; every active lane has to call it.  Returns the lane's first index.
+template <int kBits>
 __device__ __forceinline__ int wave_alloc(int n, int* counter) {
   int before = 0, total = 0;
 #pragma unroll
-  for (int bit = 0; bit < 5; ++bit) {
+  for (int bit = 0; bit < kBits; ++bit) {
     const unsigned long long bm = __ballot((n >> bit) & 1);
     before += lanes_below(bm) << bit;
     total += __popcll(bm) << bit;
@@ -478,7 +479,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     asm volatile("" : "+s"(h));
     const int b = idx;
     // ---- A: publish pose and world inverse inertia
-    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; Lcount[5] = 0; Lcount[6] = 0; }
+    if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; Lcount[5] = 0; Lcount[6] = 0; Lcount[7] = 0; }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
@@ -525,7 +526,43 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     //          work units of 8 cells (samples for a mid-segment).
     //          Slots go to the threads from the top of the workgroup down: a second round, if any,
     //          then runs on the last wavefronts while the first ones hold the joint threads.
-    for (int i = kThreads - 1 - tid; i < S * E; i += kThreads) {
+    int n_b1 = S * E;            // slots the per-slot pass visits
+    unsigned* Lslots = Lcand;    // heightfield: list of the slots of the bodies near the ground
+    if (m_terrain == 1) {
+      // ---- B1a: one thread per body: reach test of the whole capsule (box of its segment);
+      //           the slots of a body that passes are listed for the per-slot pass, the others
+      //           are inactive.  A slot can only pass its own test if its body passes this one.
+      for (int i = tid; i < B * E; i += kThreads) {
+        const int ee = i % E, bb = i / E;
+        const int env_i = blockIdx.x * E + ee;
+        const int s0 = Ltjs[bb * (kMaxBodyJoints + 3) + 1], ns = Ltjs[bb * (kMaxBodyJoints + 3) + 2];
+        bool near = false;
+        if (env_i < N && m_contacts) {
+          float bx[3], bq[4], bo[3];
+          for (int c = 0; c < 3; ++c) bx[c] = Lpos[(bb * 7 + c) * E + ee];
+          for (int c = 0; c < 4; ++c) bq[c] = Lpos[(bb * 7 + 3 + c) * E + ee];
+          for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+          SlotGeom g = slot_geom(Ltbody[4 * bb], Ltbody[4 * bb + 1], __float_as_int(Ltbody[4 * bb + 2]), p_margin, bx, bq,
+                                 2, bo);
+          Field H = H0;
+          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          near = slot_reach(H, g);
+        }
+        const int pos = wave_alloc<2>(near ? ns : 0, &Lcount[7]);
+        for (int k = 0; k < ns; ++k) {
+          if (near) Lslots[pos + k] = (unsigned)((s0 + k) * E + ee);
+          else {
+            Lreci[((s0 + k) * kRecWords + 0) * E + ee] = 0;
+            Lrec[((s0 + k) * kRecWords + 10) * E + ee] = 0.0f;
+          }
+        }
+      }
+      __syncthreads();
+      TMARK(24);
+      n_b1 = Lcount[7];
+    }
+    for (int x = kThreads - 1 - tid; x < n_b1; x += kThreads) {
+      const int i = m_terrain == 1 ? (int)Lslots[x] : x;
       int ee = i % E, s = i / E;
       int env_i = blockIdx.x * E + ee;
       ContactOut co = no_contact();
@@ -571,7 +608,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       }
       if (m_terrain == 1) {
         // list space for the units of the whole wavefront, one atomic per kind
-        const int ue = wave_alloc(nu_e, &Lcount[5]), um = wave_alloc(nu_m, &Lcount[6]);
+        const int ue = wave_alloc<5>(nu_e, &Lcount[5]), um = wave_alloc<5>(nu_m, &Lcount[6]);
         const int nu = nu_e + nu_m, u0 = nu_e ? ue : um, cap = nu_e ? unit_cap_e : unit_cap - unit_cap_e;
         unsigned* U = Lunit + (nu_e ? 0 : unit_cap_e);
         for (int u = 0; u < nu; ++u)
@@ -589,6 +626,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     TMARK(2);
     if (m_terrain == 1) {
       __syncthreads();
+      TMARK(25);
       // ---- B2: fine search in two stages.  Stage 1: kGroup lanes per work unit, one cell per
       //          lane: a cheap reach test decides which triangles (end sphere) or edges
       //          (mid-segment) of the cell become candidates.  Stage 2: one candidate per thread:
@@ -621,7 +659,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
             const SegCull sc = seg_cull_from(Pa, Pb, Rq, Lgeo[3 * qi + 1], Lgeo[3 * qi + 2], i0 + ni - 2, j0 + nj - 2);
             if (c < ni * nj) mask = segment_candidates(H, sc, i0 + di, j0 + dj);
           }
-          int pos = wave_alloc(__popc(mask), &Lcount[3]);
+          int pos = wave_alloc<2>(__popc(mask), &Lcount[3]);
           const unsigned cw = (unsigned)qi | ((unsigned)di << 14) | ((unsigned)dj << 18) | ((unsigned)pass << 22);
 #pragma unroll
           for (int k = 0; k < 3; ++k)
