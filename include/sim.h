@@ -145,6 +145,14 @@ int sim_reset(sim_t* sim, const uint8_t* env_mask_dev, uint64_t seed, void* stre
 int sim_step(sim_t* sim, const float* actions_dev, float dt, int substeps, int iterations,
              void* stream);
 
+/* sim_step followed by sim_get_obs in one kernel launch: the step's observation, reward and
+ * done flag (Table 2 "Ours", Eq. 1-3, Section 4.1) are also written to the caller's arrays as
+ * they are packed.  Same arguments, limits and errors as the two calls; any of the three
+ * output pointers may be NULL. */
+int sim_step_obs(sim_t* sim, const float* actions_dev, float dt, int substeps, int iterations,
+                 float* obs_dev /*[N][obs_dim]*/, float* reward_dev /*[N]*/, uint8_t* done_dev /*[N]*/,
+                 void* stream);
+
 /* Copies what the last sim_step packed (or, before any step, the values of the current
  * state) into caller arrays; any of the three pointers may be NULL. */
 int sim_get_obs(sim_t* sim, float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream);

@@ -57,6 +57,7 @@ _SYMBOLS = {
     "sim_obs_dim": [C.c_void_p], "sim_act_dim": [C.c_void_p],
     "sim_reset": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
     "sim_step": [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int, C.c_void_p],
+    "sim_step_obs": [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_obs": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_set_targets": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_state": [C.c_void_p, C.c_void_p, C.c_void_p],
@@ -169,6 +170,11 @@ def sim_step(h, actions_ptr, dt, substeps, iterations, stream):
     return _chk(lib().sim_step(h, actions_ptr, float(dt), int(substeps), int(iterations), stream))
 
 
+def sim_step_obs(h, actions_ptr, dt, substeps, iterations, obs_ptr, reward_ptr, done_ptr, stream):
+    return _chk(lib().sim_step_obs(h, actions_ptr, float(dt), int(substeps), int(iterations), obs_ptr, reward_ptr,
+                                   done_ptr, stream))
+
+
 def sim_get_obs(h, obs_ptr, reward_ptr, done_ptr, stream):
     return _chk(lib().sim_get_obs(h, obs_ptr, reward_ptr, done_ptr, stream))
 
@@ -264,6 +270,14 @@ class Sim:
         if a is not None and tuple(a.shape) != (self.N, self.act_dim):
             raise ValueError(f"actions must be [{self.N}][{self.act_dim}]")
         sim_step(self.h, None if a is None else a.data_ptr(), dt, substeps, iterations, self._stream())
+
+    def step_obs(self, actions, dt, substeps, iterations):
+        a = None if actions is None else self._dev(actions, self.torch.float32)
+        if a is not None and tuple(a.shape) != (self.N, self.act_dim):
+            raise ValueError(f"actions must be [{self.N}][{self.act_dim}]")
+        sim_step_obs(self.h, None if a is None else a.data_ptr(), dt, substeps, iterations, self.obs.data_ptr(),
+                     self.reward.data_ptr(), self.done.data_ptr(), self._stream())
+        return self.obs, self.reward, self.done
 
     def get_obs(self):
         sim_get_obs(self.h, self.obs.data_ptr(), self.reward.data_ptr(), self.done.data_ptr(), self._stream())

@@ -348,7 +348,8 @@ __global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t
 
 // ---------------------------------------------------------------- launches
 static int launch_step(sim* s, const float* actions, float h, int substeps, int iterations, int count_step,
-                       hipStream_t st) {
+                       hipStream_t st, float* obs_out = nullptr, float* reward_out = nullptr,
+                       uint8_t* done_out = nullptr) {
   const Model& m = s->host_model;
   StepArgs a;
   a.M = reinterpret_cast<const Model*>(s->ws + s->lay.model);
@@ -365,6 +366,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.recs = (s->record && substeps > 0) ? reinterpret_cast<int32_t*>(s->ws + s->lay.recs) : nullptr;
   a.N = s->N; a.E = s->E; a.substeps = substeps; a.iterations = iterations; a.count_step = count_step;
   a.h = h;
+  a.obs_out = obs_out; a.reward_out = reward_out; a.done_out = done_out;
 #ifdef EXP_TIMING
   a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
 #else
@@ -515,6 +517,16 @@ extern "C" int sim_step(sim_t* s, const float* actions_dev, float dt, int subste
   if (substeps < 1) return fail(SIM_ERR_ARG, "substeps must be >= 1 (got %d)", substeps);
   if (iterations < 0) return fail(SIM_ERR_ARG, "iterations must be >= 0 (got %d)", iterations);
   return launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int sim_step_obs(sim_t* s, const float* actions_dev, float dt, int substeps, int iterations,
+                            float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  if (!(dt > 0.0f) || !std::isfinite(dt)) return fail(SIM_ERR_ARG, "dt must be finite and > 0");
+  if (substeps < 1) return fail(SIM_ERR_ARG, "substeps must be >= 1 (got %d)", substeps);
+  if (iterations < 0) return fail(SIM_ERR_ARG, "iterations must be >= 0 (got %d)", iterations);
+  return launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, static_cast<hipStream_t>(stream),
+                     obs_dev, reward_dev, done_dev);
 }
 
 extern "C" int sim_get_obs(sim_t* s, float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream) {

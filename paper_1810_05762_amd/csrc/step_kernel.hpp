@@ -55,6 +55,9 @@ struct StepArgs {
   int32_t* recs;         // [N][S][12] or null
   int N, E, substeps, iterations, count_step;
   float h;
+  float* obs_out;        // optional caller copies of obs / reward / done (sim_step_obs), else null
+  float* reward_out;
+  uint8_t* done_out;
   long long* dbg;
 };
 
@@ -1136,15 +1139,23 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     float r_stand = cvert > 0.93f ? 1.0f : 0.0f;
     int steps = a.steps[env_e] + (a.count_step ? 1 : 0);
     a.steps[env_e] = steps;
-    a.reward[env_e] = M.alive_bonus + speed + 0.5f * r_head + 0.05f * r_stand - 4.0f * l1 - 0.5f * l2 -
+    const float rew = M.alive_bonus + speed + 0.5f * r_head + 0.05f * r_stand - 4.0f * l1 - 0.5f * l2 -
                       0.2f * (float)n_lim - (float)n_feet;
-    a.done[env_e] = (height < M.term_height || steps >= M.max_steps) ? 1 : 0;
+    const uint8_t dn = (height < M.term_height || steps >= M.max_steps) ? 1 : 0;
+    a.reward[env_e] = rew;
+    a.done[env_e] = dn;
+    if (a.reward_out) a.reward_out[env_e] = rew;
+    if (a.done_out) a.done_out[env_e] = dn;
   }
   __syncthreads();
   {
     const int env0 = blockIdx.x * E;
     const int n_here = min(E, N - env0);
-    for (int i = tid; i < n_here * obs_dim; i += kThreads) a.obs[(size_t)env0 * obs_dim + i] = Lobs[i];
+    for (int i = tid; i < n_here * obs_dim; i += kThreads) {
+      const float o = Lobs[i];
+      a.obs[(size_t)env0 * obs_dim + i] = o;
+      if (a.obs_out) a.obs_out[(size_t)env0 * obs_dim + i] = o;
+    }
   }
   TMARK(9);
 }

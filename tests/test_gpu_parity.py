@@ -239,6 +239,25 @@ def test_results_do_not_depend_on_launch_shape_or_neighbours_and_are_determinist
     sim.close(); full.close()
 
 
+def test_step_obs_equals_step_followed_by_get_obs():
+    P = _P()
+    sc, cfg = scenes.config_scene(3, num_envs=75)
+    dt = float(np.float32(cfg["dt"]))
+    a, b = P.Sim(sc), P.Sim(sc)
+    a.reset(3); b.reset(3)
+    for s in range(25):
+        act = scenes.actions_for_step(7, s, 75, 21)
+        a.step(act, dt, 4, 20)
+        oa = [t.cpu().numpy().copy() for t in a.get_obs()]
+        ob = [t.cpu().numpy().copy() for t in b.step_obs(act, dt, 4, 20)]
+        assert all(np.array_equal(x, y) for x, y in zip(oa, ob)), s
+    assert np.array_equal(a.get_state().cpu().numpy(), b.get_state().cpu().numpy())
+    # the library's own copy is filled as well
+    ob2 = [t.cpu().numpy().copy() for t in b.get_obs()]
+    assert all(np.array_equal(x, y) for x, y in zip(ob, ob2))
+    a.close(); b.close()
+
+
 def test_state_roundtrip_checkpoint_resume():
     P = _P()
     sc, cfg = scenes.config_scene(2, num_envs=70)
