@@ -171,6 +171,22 @@ def main():
         out["cpu_baseline"] = {"value": n_s * n_steps / el, "unit": "env-steps/s", "cores": cores, "kind": "oracle",
                                "sample": f"{n_s} envs x {n_steps} steps of the same workload "
                                          f"(plain fp64 C oracle, OpenMP over envs)"}
+        # the same oracle on one thread (the paper's CPU comparison is single-core), 16 envs, about 3 s
+        n_1 = min(N, 16)
+        one_scene, _ = scenes.config_scene(args.config, num_envs=n_1)
+        one_scene.env_origins = scene.env_origins[:n_1].copy()
+        ref1 = oracle.OracleSim(one_scene, threads=1)
+        ref1.set_state(sim.get_state().cpu().numpy()[:n_1].astype(np.float64))
+        t0 = time.perf_counter()
+        n1_steps = 0
+        while True:
+            ref1.step(acts[n1_steps % 16][:n_1], dt, sub, its)
+            n1_steps += 1
+            el1 = time.perf_counter() - t0
+            if el1 > 3.0 or n1_steps >= 200:
+                break
+        out["cpu_baseline"]["one_thread_value"] = n_1 * n1_steps / el1
+        out["cpu_baseline"]["one_thread_sample"] = f"{n_1} envs x {n1_steps} steps"
     sim.close()
     print(json.dumps(out))
 
