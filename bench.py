@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload configuration (3 = headline)")
     ap.add_argument("--envs-per-block", type=int, default=0)
     ap.add_argument("--num-envs", type=int, default=0, help="override the number of envs (scaling runs)")
+    ap.add_argument("--height-map", action="store_true", help="append the 15 x 11 height map to the observation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -71,6 +72,8 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     scene, cfg = scenes.config_scene(args.config, num_envs=args.num_envs or None)
+    if args.height_map:
+        scene.params.height_map = 1
     N, rob = scene.num_envs, scene.robot
     sim = P.Sim(scene, device=dev)
     if args.envs_per_block:
@@ -122,7 +125,7 @@ def main():
     # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
     # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.5 MB
     # read + 4.1 MB written (summary under profiles/); other sizes were not measured
-    traffic = 12.6e6 if (args.config == 3 and N == 4096) else None
+    traffic = 12.6e6 if (args.config == 3 and N == 4096 and not args.height_map) else None
     peak_tflops = 157.3
     value = N * args.steps / elapsed
     out = {
@@ -130,7 +133,8 @@ def main():
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}", "num_envs": N, "robot": rob.name, "bodies": rob.n_bodies,
+        "config": {"workload": (cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else ""),
+                   "num_envs": N, "obs_dim": sim.obs_dim, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
                    "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
@@ -153,6 +157,7 @@ def main():
         import oracle
         n_s = min(N, 256)
         sub_scene, _ = scenes.config_scene(args.config, num_envs=n_s)
+        sub_scene.params.height_map = scene.params.height_map
         sub_scene.env_origins = scene.env_origins[:n_s].copy()
         cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
         cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
@@ -174,6 +179,7 @@ def main():
         # the same oracle on one thread (the paper's CPU comparison is single-core), 16 envs, about 3 s
         n_1 = min(N, 16)
         one_scene, _ = scenes.config_scene(args.config, num_envs=n_1)
+        one_scene.params.height_map = scene.params.height_map
         one_scene.env_origins = scene.env_origins[:n_1].copy()
         ref1 = oracle.OracleSim(one_scene, threads=1)
         ref1.set_state(sim.get_state().cpu().numpy()[:n_1].astype(np.float64))

@@ -97,6 +97,8 @@ typedef struct sim_desc {
   double reset_noise;             /* amplitude of the uniform reset perturbation */
   int32_t gyroscopic;             /* 1 = explicit gyroscopic torque */
   int32_t contacts;               /* 0 disables contact generation */
+  int32_t height_map;             /* 1 appends the 15 x 11 terrain height map that follows the centre of mass
+                                     (Section 4.1, complex-terrain task) to the observation: 165 more floats */
 } sim_desc_t;
 
 /* One contact slot of one env.  Slots are static: for each body in order, a

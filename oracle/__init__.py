@@ -44,6 +44,7 @@ class _Desc(C.Structure):
         ("lin_damping", C.c_double), ("ang_damping", C.c_double), ("max_ang_vel", C.c_double),
         ("reset_noise", C.c_double),
         ("gyroscopic", C.c_int32), ("contacts", C.c_int32), ("max_episode_steps", C.c_int32),
+        ("height_map", C.c_int32),
     ]
 
 
@@ -143,6 +144,7 @@ class OracleSim:
         d.max_depen_vel, d.lin_damping, d.ang_damping = p.max_depen_vel, p.lin_damping, p.ang_damping
         d.max_ang_vel, d.reset_noise = p.max_ang_vel, p.reset_noise
         d.gyroscopic, d.contacts, d.max_episode_steps = p.gyroscopic, p.contacts, p.max_episode_steps
+        d.height_map = int(getattr(p, "height_map", 0))
         self.N, self.B, self.J, self.D = scene.num_envs, r.n_bodies, r.n_joints, r.n_dofs
         self._h = L.oracle_create(C.byref(d), self.N)
         if not self._h:

@@ -111,7 +111,7 @@ typedef struct {
   float* heights;
   v3 g;
   double mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
-  int gyro, contacts, max_steps;
+  int gyro, contacts, max_steps, height_map;
 } model;
 
 typedef struct {
@@ -762,6 +762,38 @@ static double terrain_height_at(const model* m, double wx, double wy) {
   return h00 + fx * (h11 - h01) + fy * (h01 - h00);
 }
 
+/* Height map of the complex-terrain task (Section 4.1): a 15 x 11 rectangular grid of terrain
+ * heights that follows the robot's centre of mass, denser near the robot.  The paper gives the
+ * size only; this reading: the grid is aligned with the root body's heading (yaw), row i runs
+ * along the heading at offset s(i - 4), column j across it at offset s(j - 5) (positive to the
+ * left), with s(k) = sign(k) 0.15 (1.3^|k| - 1) / 0.3 metres (0, 0.15, 0.35, 0.60, ... : 0.93 m
+ * behind to 6.4 m ahead, 1.36 m to either side); each entry is the terrain height under the
+ * sample minus the height of the centre of mass (0 for the plane); samples beyond the field read
+ * its nearest border cell.  Entries follow the other observations, row by row. */
+#define HM_ROWS 15
+#define HM_COLS 11
+static double hm_offset(int k) {
+  int a = k < 0 ? -k : k;
+  double s = 0.15 * (pow(1.3, a) - 1.0) / 0.3;
+  return k < 0 ? -s : s;
+}
+static void pack_height_map(const model* m, const env_state* e, double* out) {
+  v3 com = V(0, 0, 0);
+  double mt = 0;
+  for (int b = 0; b < m->B; ++b) { com = vadd(com, vscale(e->x[b], m->mass[b])); mt += m->mass[b]; }
+  com = vadd(vscale(com, 1.0 / mt), e->origin);
+  quat q = e->q[m->root];
+  double yaw = atan2(2 * (q.w * q.z + q.x * q.y), 1 - 2 * (q.y * q.y + q.z * q.z));
+  double c = cos(yaw), s = sin(yaw);
+  for (int i = 0; i < HM_ROWS; ++i)
+    for (int j = 0; j < HM_COLS; ++j) {
+      double f = hm_offset(i - 4), l = hm_offset(j - 5);
+      double wx = com.x + c * f - s * l, wy = com.y + s * f + c * l;
+      double hz = m->terrain_kind == 0 ? 0.0 : terrain_height_at(m, wx, wy);
+      out[i * HM_COLS + j] = hz - com.z;
+    }
+}
+
 static void pack_obs(const model* m, const env_state* e, double* obs, double* reward, uint8_t* done) {
   int D = m->D, rb = m->root, o = 0;
   quat q = e->q[rb];
@@ -806,6 +838,7 @@ static void pack_obs(const model* m, const env_state* e, double* obs, double* re
     obs[11 + 3 * D + f] = flag;
     n_feet += flag;
   }
+  if (m->height_map) pack_height_map(m, e, obs + 11 + 3 * D + m->F);
   /* reward, Eq. (1)-(3) */
   double tn = sqrt(tx * tx + ty * ty);
   double S = tn > 0 ? (e->v[rb].x * tx + e->v[rb].y * ty) / tn : 0.0;
@@ -872,7 +905,7 @@ oracle_sim* oracle_create(const oracle_desc* d, int32_t N) {
   m->mu = d->mu; m->margin = d->margin; m->beta_j = d->beta_joint; m->beta_c = d->beta_contact;
   m->v_depen = d->max_depen_vel; m->c_lin = d->lin_damping; m->c_ang = d->ang_damping;
   m->w_max = d->max_ang_vel; m->reset_noise = d->reset_noise;
-  m->gyro = d->gyroscopic; m->contacts = d->contacts; m->max_steps = d->max_episode_steps;
+  m->gyro = d->gyroscopic; m->contacts = d->contacts; m->max_steps = d->max_episode_steps; m->height_map = d->height_map;
   o->N = N; o->threads = 1;
   o->env = (env_state*)calloc((size_t)N, sizeof(env_state));
   for (int e = 0; e < N; ++e) {
@@ -890,7 +923,7 @@ void oracle_destroy(oracle_sim* o) {
   free(o->m.heights); free(o->env); free(o);
 }
 int32_t oracle_n_slots(const oracle_sim* o) { return o->m.S; }
-int32_t oracle_obs_dim(const oracle_sim* o) { return 11 + 3 * o->m.D + o->m.F; }
+int32_t oracle_obs_dim(const oracle_sim* o) { return 11 + 3 * o->m.D + o->m.F + (o->m.height_map ? HM_ROWS * HM_COLS : 0); }
 void oracle_set_threads(oracle_sim* o, int32_t n) { o->threads = n < 1 ? 1 : n; }
 int32_t oracle_get_threads(const oracle_sim* o) { return o->threads; }
 

@@ -49,6 +49,7 @@ typedef struct oracle_desc {
   double gravity[3], mu, margin, beta_joint, beta_contact, max_depen_vel;
   double lin_damping, ang_damping, max_ang_vel, reset_noise;
   int32_t gyroscopic, contacts, max_episode_steps;
+  int32_t height_map;      /* 1: observation carries the 15 x 11 height map (Section 4.1, complex terrain) */
 } oracle_desc;
 
 typedef struct oracle_contact {

@@ -42,6 +42,7 @@ class SimDesc(C.Structure):
         ("beta_joint", C.c_double), ("beta_contact", C.c_double), ("max_depen_vel", C.c_double),
         ("lin_damping", C.c_double), ("ang_damping", C.c_double), ("max_ang_vel", C.c_double),
         ("reset_noise", C.c_double), ("gyroscopic", C.c_int32), ("contacts", C.c_int32),
+        ("height_map", C.c_int32),
     ]
 
 
@@ -141,6 +142,7 @@ def make_desc(scene):
     d.max_depen_vel, d.lin_damping, d.ang_damping = p.max_depen_vel, p.lin_damping, p.ang_damping
     d.max_ang_vel, d.reset_noise = p.max_ang_vel, p.reset_noise
     d.gyroscopic, d.contacts = p.gyroscopic, p.contacts
+    d.height_map = int(getattr(p, "height_map", 0))
     return d, [bodies, joints, heights, origins]
 
 

@@ -13,6 +13,7 @@ constexpr int kMaxDofs = 32;
 constexpr int kMaxFeet = 4;
 constexpr int kMaxSlots = 3 * kMaxBodies;
 constexpr int kMaxBodyJoints = 8;  // joint sides touching one body
+constexpr int kHmRows = 15, kHmCols = 11;  // height-map observation
 constexpr int kCoarse = 8;         // cells per side of a coarse max-height block
 
 struct BodyTab {
@@ -49,6 +50,10 @@ struct Model {
   float term_height, alive_bonus;
   int32_t max_steps, gyro, contacts;
   int32_t max_joint_sides;  // largest n_joint_sides over the bodies
+  // height-map observation: 0 = off; sample offsets along / across the heading, metres
+  int32_t height_map;
+  float hm_fwd[kHmRows], hm_lat[kHmCols];
+  float body_mass_frac[kMaxBodies];  // mass of each body over the total (centre of mass)
   BodyTab bodies[kMaxBodies];
   JointTab joints[kMaxJoints];
   SlotTab slots[kMaxSlots];

@@ -198,6 +198,25 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   m->reset_noise = (float)d->reset_noise;
   m->term_height = (float)d->term_height; m->alive_bonus = (float)d->alive_bonus;
   m->max_steps = d->max_episode_steps; m->gyro = d->gyroscopic; m->contacts = d->contacts;
+  // Height map of the complex-terrain task (Section 4.1: 15 x 11, follows the centre of mass,
+  // denser near the robot).  Offsets along and across the heading: s(k) = sign(k) 0.15 (1.3^|k| - 1) / 0.3
+  // for k = -4..10 (rows) and k = -5..5 (columns).
+  m->height_map = d->height_map ? 1 : 0;
+  for (int i = 0; i < kHmRows; ++i) {
+    int k = i - 4, ak = k < 0 ? -k : k;
+    double sft = 0.15 * (std::pow(1.3, (double)ak) - 1.0) / 0.3;
+    m->hm_fwd[i] = (float)(k < 0 ? -sft : sft);
+  }
+  for (int j = 0; j < kHmCols; ++j) {
+    int k = j - 5, ak = k < 0 ? -k : k;
+    double sft = 0.15 * (std::pow(1.3, (double)ak) - 1.0) / 0.3;
+    m->hm_lat[j] = (float)(k < 0 ? -sft : sft);
+  }
+  {
+    double mt = 0.0;
+    for (int b = 0; b < m->B; ++b) mt += d->bodies[b].mass;
+    for (int b = 0; b < m->B; ++b) m->body_mass_frac[b] = (float)(d->bodies[b].mass / mt);
+  }
   return SIM_OK;
 }
 
@@ -402,7 +421,7 @@ extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t*
   if (rc) return rc;
   if (!out_bytes) return fail(SIM_ERR_ARG, "out_bytes is NULL");
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
-  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F, num_envs, nh, (size_t)m.cnx * m.cny).total;
+  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0), num_envs, nh, (size_t)m.cnx * m.cny).total;
   return SIM_OK;
 }
 
@@ -417,7 +436,7 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
   const Model& m = s->host_model;
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
   s->N = num_envs;
-  s->obs_dim = 11 + 3 * m.D + m.F;
+  s->obs_dim = 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0);
   s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny);
   s->record = 0; s->recs_valid = 0;
   s->E = default_envs_per_block(m, num_envs);

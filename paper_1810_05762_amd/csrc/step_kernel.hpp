@@ -315,7 +315,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const bool env_ok = env < N;
   const bool is_body = idx < B && env_ok;
   const bool is_joint = idx < J && env_ok;
-  const int obs_dim = 11 + 3 * D + F;
+  const int obs_dim = 11 + 3 * D + F;                                      // staged in LDS
+  const int obs_row = obs_dim + (M.height_map ? kHmRows * kHmCols : 0);   // row of the caller's array
   // model scalars the loops below use, read once (before the kernel's first store, so they come
   // through the scalar cache and stay in scalar registers)
   const int m_terrain = M.terrain_kind, m_contacts = M.contacts;
@@ -1153,8 +1154,42 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     const int n_here = min(E, N - env0);
     for (int i = tid; i < n_here * obs_dim; i += kThreads) {
       const float o = Lobs[i];
-      a.obs[(size_t)env0 * obs_dim + i] = o;
-      if (a.obs_out) a.obs_out[(size_t)env0 * obs_dim + i] = o;
+      const int ee = i / obs_dim, k = i - ee * obs_dim;
+      a.obs[(size_t)(env0 + ee) * obs_row + k] = o;
+      if (a.obs_out) a.obs_out[(size_t)(env0 + ee) * obs_row + k] = o;
+    }
+    if (M.height_map) {
+      // Height map (Section 4.1, complex-terrain task): terrain height under a 15 x 11 grid that
+      // follows the centre of mass and is aligned with the root's heading, minus the height of
+      // the centre of mass; written straight to the output rows (it is not staged in LDS).
+      // Centre and heading per env first (in the space of the sweep copies, free by now).
+      float* Lhm = Loutj;   // [5][E]: centre x,y,z (world), cos, sin of the yaw
+      if (tid < n_here) {
+        const int ee = tid;
+        float cx = 0.0f, cy = 0.0f, cz = 0.0f;
+        for (int bb = 0; bb < B; ++bb) {
+          const float mf = M.body_mass_frac[bb];
+          cx += mf * Lpos[(bb * 7 + 0) * E + ee]; cy += mf * Lpos[(bb * 7 + 1) * E + ee]; cz += mf * Lpos[(bb * 7 + 2) * E + ee];
+        }
+        const int rbb = M.root;
+        const float qw = Lpos[(rbb * 7 + 3) * E + ee], qx = Lpos[(rbb * 7 + 4) * E + ee];
+        const float qy = Lpos[(rbb * 7 + 5) * E + ee], qz = Lpos[(rbb * 7 + 6) * E + ee];
+        const float yaw = atan2f(2.0f * (qw * qz + qx * qy), 1.0f - 2.0f * (qy * qy + qz * qz));
+        Lhm[0 * E + ee] = cx + a.origins[3 * (env0 + ee)];
+        Lhm[1 * E + ee] = cy + a.origins[3 * (env0 + ee) + 1];
+        Lhm[2 * E + ee] = cz + a.origins[3 * (env0 + ee) + 2];
+        Lhm[3 * E + ee] = cosf(yaw); Lhm[4 * E + ee] = sinf(yaw);
+      }
+      __syncthreads();
+      constexpr int kHm = kHmRows * kHmCols;
+      for (int i = tid; i < n_here * kHm; i += kThreads) {
+        const int ee = i / kHm, k = i - ee * kHm, hi = k / kHmCols, hj = k - hi * kHmCols;
+        const float fw = M.hm_fwd[hi], lt = M.hm_lat[hj], c = Lhm[3 * E + ee], sn = Lhm[4 * E + ee];
+        const float wx = Lhm[0 * E + ee] + (c * fw - sn * lt), wy = Lhm[1 * E + ee] + (sn * fw + c * lt);
+        const float hz = terrain_height(M, a.heights, wx, wy) - Lhm[2 * E + ee];
+        a.obs[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
+        if (a.obs_out) a.obs_out[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
+      }
     }
   }
   TMARK(9);

@@ -29,6 +29,7 @@ class SimParams:
     contacts: int = 1
     reset_noise: float = 0.05
     max_episode_steps: int = 1000
+    height_map: int = 0            # 1: append the 15 x 11 terrain height map to the observation
 
 
 @dataclass

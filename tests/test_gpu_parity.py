@@ -345,3 +345,27 @@ def test_full_size_headline_config_sampled_envs_match_oracle():
     assert np.isfinite(g).all()
     np.testing.assert_allclose(np.linalg.norm(g[:, :, 3:7], axis=2), 1.0, atol=1e-5)
     sim.close()
+
+
+def test_height_map_observation_parity():
+    """Configuration 3 with the 15 x 11 height map appended to the observation (241 numbers)."""
+    P = _P()
+    sc, cfg = scenes.config_scene(3, num_envs=77)
+    sc.params.height_map = 1
+    dt = float(np.float32(cfg["dt"]))
+    sim = P.Sim(sc); sim.reset(cfg["seed"])
+    ref = oracle.OracleSim(sc, threads=8)
+    assert sim.obs_dim == ref.obs_dim == 76 + 165
+    for s in range(45):
+        act = scenes.actions_for_step(cfg["seed"], s, 77, 21)
+        obs, rew, done = sim.step_obs(act, dt, cfg["substeps"], cfg["iterations"])
+        if s % 11 == 0:
+            ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))
+            o_ref, _, _ = ref.get_obs()
+            hm_g, hm_o = obs.cpu().numpy()[:, 76:], o_ref[:, 76:]
+            # fp32 interpolation of heights of a few metres at coordinates of tens of metres
+            assert np.abs(hm_g - hm_o).max() < 2e-4, (s, np.abs(hm_g - hm_o).max())
+            assert np.ptp(hm_o, axis=1).min() > 0.01      # the terrain under the grid is not flat
+            # the library's own copy (sim_get_obs) carries the same rows
+            assert np.array_equal(sim.get_obs()[0].cpu().numpy(), obs.cpu().numpy())
+    sim.close()
