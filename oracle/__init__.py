@@ -90,6 +90,10 @@ def _load():
     L.oracle_set_trace.argtypes = [vp, C.c_int32, C.c_void_p, C.c_int32]
     L.oracle_trace_count.argtypes = [vp]
     L.oracle_joint_angles.argtypes = [vp, dp]
+    L.oracle_set_task.argtypes = [vp, C.c_void_p]
+    L.oracle_get_task_state.argtypes = [vp, ip, dp]
+    L.oracle_set_task_state.argtypes = [vp, ip, dp]
+    L.oracle_get_last_push.argtypes = [vp, dp]
     L.oracle_uniform.restype = C.c_double
     L.oracle_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
     _lib = L
@@ -106,6 +110,13 @@ def _dp(a):
 
 def _ip(a):
     return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+class _Task(C.Structure):
+    _fields_ = [("enabled", C.c_int32), ("fall_grace_frames", C.c_int32), ("target_period", C.c_int32),
+                ("push_min_frames", C.c_int32), ("push_max_frames", C.c_int32), ("auto_reset", C.c_int32),
+                ("target_reach", C.c_double), ("target_radius", C.c_double),
+                ("push_min_newton", C.c_double), ("push_max_newton", C.c_double), ("seed", C.c_uint64)]
 
 
 class OracleSim:
@@ -178,6 +189,32 @@ class OracleSim:
     def set_targets(self, xy):
         t = np.ascontiguousarray(xy, dtype=np.float64).reshape(self.N, 2)
         self._L.oracle_set_targets(self._h, _dp(t))
+
+    def set_task(self, task):
+        """task: scenes.TaskParams or None (off).  Initialises the per-env task state."""
+        if task is None:
+            self._L.oracle_set_task(self._h, None)
+            return
+        t = _Task()
+        for name, _ in _Task._fields_:
+            setattr(t, name, getattr(task, name))
+        self._L.oracle_set_task(self._h, C.addressof(t))
+
+    def get_task_state(self):
+        c = np.zeros((self.N, 4), np.int32)
+        t = np.zeros((self.N, 2), np.float64)
+        self._L.oracle_get_task_state(self._h, _ip(c), _dp(t))
+        return c, t
+
+    def set_task_state(self, counters, targets):
+        c = np.ascontiguousarray(counters, dtype=np.int32).reshape(self.N, 4)
+        t = np.ascontiguousarray(targets, dtype=np.float64).reshape(self.N, 2)
+        self._L.oracle_set_task_state(self._h, _ip(c), _dp(t))
+
+    def get_last_push(self):
+        p = np.zeros((self.N, 3), np.float64)
+        self._L.oracle_get_last_push(self._h, _dp(p))
+        return p
 
     def set_step_count(self, counts):
         c = np.ascontiguousarray(np.broadcast_to(np.asarray(counts, np.int32), (self.N,)))

@@ -27,6 +27,7 @@
 #define MAXJ 32
 #define MAXS 96
 #define MAXD 64
+#define MAXOBS (11 + 3 * MAXD + 8 + 15 * 11)
 
 typedef struct { double x, y, z; } v3;
 typedef struct { double w, x, y, z; } quat;
@@ -122,10 +123,17 @@ typedef struct {
   double u[MAXD]; /* clipped actions of the last step */
   int steps;
   oracle_contact con[MAXS];
+  /* task logic (Section 4.1) */
+  int fall_frames, target_age, next_push, episode;
+  v3 push;                 /* external force on the root body during the current step */
+  int has_store;           /* obs/reward/done of the last step kept (task mode packs at step end) */
+  double obs_store[MAXOBS], rew_store;
+  uint8_t done_store;
 } env_state;
 
 struct oracle_sim {
   model m;
+  oracle_task task;
   int N, threads;
   env_state* env;
   int trace_env, trace_cap, trace_n;
@@ -540,6 +548,8 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
         if (m->jp[j] >= 0) tau[m->jp[j]] = vsub(tau[m->jp[j]], vscale(ak, t));
       }
     }
+    /* external push on the root body (Section 4.1, perturbations): constant over the step */
+    e->v[m->root] = vadd(e->v[m->root], vscale(e->push, h / m->mass[m->root]));
     for (int b = 0; b < B; ++b) {
       e->v[b] = vadd(e->v[b], vscale(m->g, h));
       v3 wb = mrot_t(R[b], e->w[b]), tb = mrot_t(R[b], tau[b]), I = m->inertia[b];
@@ -942,12 +952,9 @@ double oracle_uniform(uint64_t seed, uint64_t env, uint64_t idx) {
 /* Reset (Section 4.1, initial state perturbed slightly): rest pose translated by
  * uniform noise, common linear velocity noise, every hinge angle perturbed and
  * clipped to its limits; bodies placed parents-first through the joint list. */
-void oracle_reset(oracle_sim* o, const uint8_t* mask, uint64_t seed) {
-  const model* m = &o->m;
+static void reset_env(const model* m, env_state* e, int ei, uint64_t seed) {
   double a = m->reset_noise;
-  for (int ei = 0; ei < o->N; ++ei) {
-    if (mask && !mask[ei]) continue;
-    env_state* e = &o->env[ei];
+  {
     v3 off, vel;
     off = V(a * (2 * oracle_uniform(seed, ei, 0) - 1), a * (2 * oracle_uniform(seed, ei, 1) - 1),
             a * (2 * oracle_uniform(seed, ei, 2) - 1));
@@ -978,6 +985,98 @@ void oracle_reset(oracle_sim* o, const uint8_t* mask, uint64_t seed) {
     e->steps = 0;
     for (int d = 0; d < m->D; ++d) e->u[d] = 0;
     for (int s = 0; s < MAXS; ++s) clear_contact(&e->con[s]);
+    e->push = V(0, 0, 0);
+    e->has_store = 0;
+  }
+}
+void oracle_reset(oracle_sim* o, const uint8_t* mask, uint64_t seed) {
+  for (int ei = 0; ei < o->N; ++ei) {
+    if (mask && !mask[ei]) continue;
+    reset_env(&o->m, &o->env[ei], ei, seed);
+  }
+}
+
+/* ---- task logic (Section 4.1): draws are keyed by (seed, episode, env, frame, k) ---- */
+static double task_u(const oracle_task* t, int env, int episode, int frame, int k) {
+  return oracle_uniform(t->seed + (uint64_t)episode * 0x9E3779B97F4A7C15ULL, (uint64_t)env,
+                        (uint64_t)(1024 + 8 * frame + k));
+}
+static int task_interval(const oracle_task* t, int env, int episode, int frame) {
+  int span = t->push_max_frames - t->push_min_frames + 1;
+  int d = t->push_min_frames + (int)floor(task_u(t, env, episode, frame, 2) * span);
+  return d > t->push_max_frames ? t->push_max_frames : d;
+}
+static void task_draw_target(const oracle_task* t, const model* m, env_state* e, int env, int frame) {
+  double r = t->target_radius * sqrt(task_u(t, env, e->episode, frame, 3));
+  double phi = 2.0 * 3.14159265358979323846 * task_u(t, env, e->episode, frame, 4);
+  e->target[0] = e->x[m->root].x + r * cos(phi);
+  e->target[1] = e->x[m->root].y + r * sin(phi);
+  e->target_age = 0;
+}
+static void task_begin_episode(const oracle_task* t, const model* m, env_state* e, int env) {
+  e->fall_frames = 0; e->target_age = 0;
+  e->next_push = t->push_max_frames > 0 ? task_interval(t, env, e->episode, 0) : -1;
+  if (t->target_period > 0) task_draw_target(t, m, e, env, 0);
+}
+void oracle_set_task(oracle_sim* o, const oracle_task* task) {
+  if (!task || !task->enabled) { memset(&o->task, 0, sizeof(o->task)); for (int e = 0; e < o->N; ++e) { o->env[e].push = V(0, 0, 0); o->env[e].has_store = 0; } return; }
+  o->task = *task;
+  for (int e = 0; e < o->N; ++e) {
+    o->env[e].episode = 0;
+    o->env[e].push = V(0, 0, 0);
+    o->env[e].has_store = 0;
+    task_begin_episode(&o->task, &o->m, &o->env[e], e);
+  }
+}
+void oracle_get_task_state(const oracle_sim* o, int32_t* c, double* t) {
+  for (int e = 0; e < o->N; ++e) {
+    const env_state* E = &o->env[e];
+    c[4 * e] = E->fall_frames; c[4 * e + 1] = E->target_age; c[4 * e + 2] = E->next_push; c[4 * e + 3] = E->episode;
+    t[2 * e] = E->target[0]; t[2 * e + 1] = E->target[1];
+  }
+}
+void oracle_set_task_state(oracle_sim* o, const int32_t* c, const double* t) {
+  for (int e = 0; e < o->N; ++e) {
+    env_state* E = &o->env[e];
+    E->fall_frames = c[4 * e]; E->target_age = c[4 * e + 1]; E->next_push = c[4 * e + 2]; E->episode = c[4 * e + 3];
+    E->target[0] = t[2 * e]; E->target[1] = t[2 * e + 1];
+  }
+}
+void oracle_get_last_push(const oracle_sim* o, double* p) {
+  for (int e = 0; e < o->N; ++e) { p[3 * e] = o->env[e].push.x; p[3 * e + 1] = o->env[e].push.y; p[3 * e + 2] = o->env[e].push.z; }
+}
+/* before the substeps of a frame: is this the frame of a push? */
+static void task_before_step(const oracle_task* t, env_state* e, int env) {
+  e->push = V(0, 0, 0);
+  if (t->push_max_frames > 0 && e->steps == e->next_push) {
+    int f = e->steps;
+    double mag = t->push_min_newton + (t->push_max_newton - t->push_min_newton) * task_u(t, env, e->episode, f, 0);
+    double phi = 2.0 * 3.14159265358979323846 * task_u(t, env, e->episode, f, 1);
+    e->push = V(mag * cos(phi), mag * sin(phi), 0.0);
+    e->next_push = f + task_interval(t, env, e->episode, f);
+  }
+}
+/* after the substeps (steps already counted): pack, termination with grace, target, auto-reset */
+static void task_after_step(const oracle_task* t, const model* m, env_state* e, int env) {
+  uint8_t dn;
+  pack_obs(m, e, e->obs_store, &e->rew_store, &dn);
+  int below = e->obs_store[0] < m->term_height;
+  e->fall_frames = below ? e->fall_frames + 1 : 0;
+  e->done_store = (e->fall_frames > t->fall_grace_frames || e->steps >= m->max_steps) ? 1 : 0;
+  e->has_store = 1;
+  if (t->target_period > 0) {
+    e->target_age += 1;
+    double dx = e->target[0] - e->x[m->root].x, dy = e->target[1] - e->x[m->root].y;
+    if (e->target_age >= t->target_period || sqrt(dx * dx + dy * dy) < t->target_reach)
+      task_draw_target(t, m, e, env, e->steps);
+  }
+  if (e->done_store && t->auto_reset) {
+    e->episode += 1;
+    reset_env(m, e, env, t->seed + (uint64_t)e->episode * 0x9E3779B97F4A7C15ULL);
+    task_begin_episode(t, m, e, env);
+    double r; uint8_t d2;
+    pack_obs(m, e, e->obs_store, &r, &d2);   /* first observation of the new episode */
+    e->has_store = 1;
   }
 }
 
@@ -990,6 +1089,7 @@ void oracle_set_state(oracle_sim* o, const double* st) {
       E->x[b] = V(s[0], s[1], s[2]);
       E->q[b].w = s[3]; E->q[b].x = s[4]; E->q[b].y = s[5]; E->q[b].z = s[6];
       E->v[b] = V(s[7], s[8], s[9]); E->w[b] = V(s[10], s[11], s[12]);
+      E->has_store = 0;
     }
 }
 void oracle_get_state(const oracle_sim* o, double* st) {
@@ -1036,16 +1136,26 @@ void oracle_step(oracle_sim* o, const double* actions, double dt, int32_t subste
 #endif
   for (int e = 0; e < o->N; ++e) {
     int tr = (e == o->trace_env);
+    if (o->task.enabled) task_before_step(&o->task, &o->env[e], e);
     for (int s = 0; s < substeps; ++s)
       substep(&o->m, &o->env[e], h, iterations, ORACLE_PH_ALL, tr ? o->trace : NULL, &o->trace_n,
               o->trace_cap);
     o->env[e].steps++;
+    if (o->task.enabled) task_after_step(&o->task, &o->m, &o->env[e], e);
   }
 }
 
 void oracle_get_obs(const oracle_sim* o, double* obs, double* reward, uint8_t* done) {
   int od = oracle_obs_dim(o);
-  for (int e = 0; e < o->N; ++e) pack_obs(&o->m, &o->env[e], obs + (size_t)e * od, &reward[e], &done[e]);
+  for (int e = 0; e < o->N; ++e) {
+    const env_state* E = &o->env[e];
+    if (o->task.enabled && E->has_store) {
+      memcpy(obs + (size_t)e * od, E->obs_store, sizeof(double) * od);
+      reward[e] = E->rew_store; done[e] = E->done_store;
+    } else {
+      pack_obs(&o->m, E, obs + (size_t)e * od, &reward[e], &done[e]);
+    }
+  }
 }
 void oracle_get_contacts(const oracle_sim* o, oracle_contact* recs) {
   for (int e = 0; e < o->N; ++e) memcpy(recs + (size_t)e * o->m.S, o->env[e].con, o->m.S * sizeof(oracle_contact));

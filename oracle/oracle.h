@@ -52,6 +52,24 @@ typedef struct oracle_desc {
   int32_t height_map;      /* 1: observation carries the 15 x 11 height map (Section 4.1, complex terrain) */
 } oracle_desc;
 
+/* Task logic around the step (Section 4.1).  All off when `enabled` is 0.
+ *  - fall_grace_frames: an env terminates when its root has been below term_height for more than
+ *    this many consecutive frames (0: at once, as for Ant / Humanoid; 160 for the flagrun tasks);
+ *  - target_period / target_reach / target_radius: the flagrun target is re-drawn uniformly in the
+ *    disc of target_radius around the root every target_period frames, or as soon as the root is
+ *    within target_reach of it (200 frames, 1 m, 100 m); period 0 keeps the targets as set;
+ *  - push_*: every push_min..push_max frames (uniform integer; 200..300) a horizontal force of
+ *    uniform magnitude push_min..push_max newton and uniform direction acts on the root body for
+ *    one frame; push_max_frames 0 disables pushes;
+ *  - auto_reset: an env that is done is reset at once (reset recipe, new episode seed); the
+ *    observation returned for it is the first one of the new episode, reward and done are those
+ *    of the step that ended the old one. */
+typedef struct oracle_task {
+  int32_t enabled, fall_grace_frames, target_period, push_min_frames, push_max_frames, auto_reset;
+  double target_reach, target_radius, push_min_newton, push_max_newton;
+  uint64_t seed;
+} oracle_task;
+
 typedef struct oracle_contact {
   int32_t active; /* 0/1 */
   int32_t kind;   /* -1 none, 0 plane, 1 triangle closest point, 2 triangle underneath, 3 edge (mid-segment) */
@@ -85,6 +103,16 @@ void oracle_set_state(oracle_sim*, const double* state);
 void oracle_get_state(const oracle_sim*, double* state);
 void oracle_set_targets(oracle_sim*, const double* target_xy /*[N][2] env-local*/);
 void oracle_set_step_count(oracle_sim*, const int32_t* counts /*[N]*/);
+/* Switches the task logic on (or off with NULL / enabled 0) and initialises the per-env task
+ * state from the current body state: episode 0, counters 0, first push time and (period > 0)
+ * first target drawn. */
+void oracle_set_task(oracle_sim*, const oracle_task* task);
+/* per-env task state: counters[N][4] = frames below threshold, target age, frame of the next
+ * push (-1 none), episode index; targets[N][2] env-local */
+void oracle_get_task_state(const oracle_sim*, int32_t* counters, double* targets);
+void oracle_set_task_state(oracle_sim*, const int32_t* counters, const double* targets);
+/* force (N) that acted on the root body during the last step, [N][3] */
+void oracle_get_last_push(const oracle_sim*, double* push);
 
 /* phase mask for oracle_step_phases */
 #define ORACLE_PH_CONTACTS 1

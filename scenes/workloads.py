@@ -33,6 +33,23 @@ class SimParams:
 
 
 @dataclass
+class TaskParams:
+    """Task logic around the step (Section 4.1 of the paper); the defaults are the flagrun tasks'
+    numbers.  "A few newtons" is read as 1 to 5 N."""
+    enabled: int = 1
+    fall_grace_frames: int = 160
+    target_period: int = 200
+    push_min_frames: int = 200
+    push_max_frames: int = 300
+    auto_reset: int = 1
+    target_reach: float = 1.0
+    target_radius: float = 100.0
+    push_min_newton: float = 1.0
+    push_max_newton: float = 5.0
+    seed: int = 0
+
+
+@dataclass
 class Scene:
     robot: Robot
     terrain: Terrain
