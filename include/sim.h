@@ -101,6 +101,28 @@ typedef struct sim_desc {
                                      (Section 4.1, complex-terrain task) to the observation: 165 more floats */
 } sim_desc_t;
 
+/* Task logic around the step (Section 4.1 of the paper).  The numbers in brackets are the
+ * paper's for the flagrun tasks.
+ *  - fall_grace_frames: an env is done when its root has been below term_height for more than
+ *    this many consecutive frames [160; 0 for Ant / Humanoid: done at once];
+ *  - target_period, target_reach, target_radius: the per-env target is re-drawn uniformly in the
+ *    disc of target_radius [100 m] around the root every target_period frames [200], or as soon as
+ *    the root is within target_reach [1 m] of it; period 0 keeps the targets as they are set;
+ *  - push_min_frames..push_max_frames [200..300]: uniform integer number of frames between two
+ *    pushes; a push is a horizontal force of uniform magnitude push_min_newton..push_max_newton
+ *    ["a few newtons"] and uniform direction on the root body for one frame; push_max_frames 0
+ *    disables pushes;
+ *  - auto_reset: an env that is done starts its next episode inside the same call (reset recipe
+ *    seeded by seed and the env's episode index); the observation delivered for it is the first
+ *    one of the new episode, reward and done are those of the step that ended the old one.
+ * Every draw comes from the counter-based generator of sim_reset keyed by (seed, episode, env,
+ * frame), so a run is reproducible and independent of the launch shape. */
+typedef struct sim_task_desc {
+  int32_t enabled, fall_grace_frames, target_period, push_min_frames, push_max_frames, auto_reset;
+  double target_reach, target_radius, push_min_newton, push_max_newton;
+  uint64_t seed;
+} sim_task_desc_t;
+
 /* One contact slot of one env.  Slots are static: for each body in order, a
  * capsule owns slot "end -" and "end +" (plus "mid-segment" on a heightfield),
  * a sphere owns one.  kind: -1 none, 0 plane, 1 closest point of triangle
@@ -162,6 +184,18 @@ int sim_get_obs(sim_t* sim, float* obs_dev, float* reward_dev, uint8_t* done_dev
 /* Per-env target position, env-local xy, [N][2] (Section 4.1 flagrun targets; the plain
  * running tasks keep the default (1000, 0), i.e. "forwards"). */
 int sim_set_targets(sim_t* sim, const float* target_xy_dev, void* stream);
+
+/* Switches the task logic on (task->enabled != 0) or off (NULL or enabled == 0) for the following
+ * sim_step / sim_step_obs calls and starts episode 0 of every env from the current body state
+ * (counters cleared, first push time and, with target_period > 0, first target drawn).  With
+ * auto_reset a step takes three kernel launches instead of one.  SIM_ERR_ARG on inconsistent
+ * numbers. */
+int sim_set_task(sim_t* sim, const sim_task_desc_t* task, void* stream);
+/* Per-env task state: counters [N][4] = frames below the threshold, target age, frame of the
+ * next push (-1: none), episode index; targets [N][2] env-local; push [N][3] = force on the root
+ * during the last step.  Any output pointer may be NULL. */
+int sim_get_task_state(sim_t* sim, int32_t* counters_dev, float* targets_dev, float* push_dev, void* stream);
+int sim_set_task_state(sim_t* sim, const int32_t* counters_dev, const float* targets_dev, void* stream);
 
 /* Parity / checkpoint interface (not on the timed path). */
 int sim_get_state(sim_t* sim, float* state_dev, void* stream);

@@ -985,7 +985,6 @@ static void reset_env(const model* m, env_state* e, int ei, uint64_t seed) {
     e->steps = 0;
     for (int d = 0; d < m->D; ++d) e->u[d] = 0;
     for (int s = 0; s < MAXS; ++s) clear_contact(&e->con[s]);
-    e->push = V(0, 0, 0);
     e->has_store = 0;
   }
 }

@@ -46,6 +46,13 @@ class SimDesc(C.Structure):
     ]
 
 
+class TaskDesc(C.Structure):
+    _fields_ = [("enabled", C.c_int32), ("fall_grace_frames", C.c_int32), ("target_period", C.c_int32),
+                ("push_min_frames", C.c_int32), ("push_max_frames", C.c_int32), ("auto_reset", C.c_int32),
+                ("target_reach", C.c_double), ("target_radius", C.c_double),
+                ("push_min_newton", C.c_double), ("push_max_newton", C.c_double), ("seed", C.c_uint64)]
+
+
 CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.int32),
                           ("d", np.float32), ("n", np.float32, 3), ("rc", np.float32, 3),
                           ("w", np.float32), ("pad", np.int32)])
@@ -60,6 +67,9 @@ _SYMBOLS = {
     "sim_step": [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int, C.c_void_p],
     "sim_step_obs": [C.c_void_p, C.c_void_p, C.c_float, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_obs": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_set_task": [C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_get_task_state": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_set_task_state": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_set_targets": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_state": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_set_state": [C.c_void_p, C.c_void_p, C.c_void_p],
@@ -177,6 +187,24 @@ def sim_step_obs(h, actions_ptr, dt, substeps, iterations, obs_ptr, reward_ptr, 
                                    done_ptr, stream))
 
 
+def sim_set_task(h, task, stream):
+    """task: an object with the fields of sim_task_desc_t (e.g. scenes.TaskParams) or None."""
+    if task is None:
+        return _chk(lib().sim_set_task(h, None, stream))
+    t = TaskDesc()
+    for name, _ in TaskDesc._fields_:
+        setattr(t, name, getattr(task, name))
+    return _chk(lib().sim_set_task(h, C.addressof(t), stream))
+
+
+def sim_get_task_state(h, counters_ptr, targets_ptr, push_ptr, stream):
+    return _chk(lib().sim_get_task_state(h, counters_ptr, targets_ptr, push_ptr, stream))
+
+
+def sim_set_task_state(h, counters_ptr, targets_ptr, stream):
+    return _chk(lib().sim_set_task_state(h, counters_ptr, targets_ptr, stream))
+
+
 def sim_get_obs(h, obs_ptr, reward_ptr, done_ptr, stream):
     return _chk(lib().sim_get_obs(h, obs_ptr, reward_ptr, done_ptr, stream))
 
@@ -280,6 +308,22 @@ class Sim:
         sim_step_obs(self.h, None if a is None else a.data_ptr(), dt, substeps, iterations, self.obs.data_ptr(),
                      self.reward.data_ptr(), self.done.data_ptr(), self._stream())
         return self.obs, self.reward, self.done
+
+    def set_task(self, task):
+        sim_set_task(self.h, task, self._stream())
+
+    def get_task_state(self):
+        t = self.torch
+        c = t.empty(self.N, 4, dtype=t.int32, device=self.device)
+        tg = t.empty(self.N, 2, dtype=t.float32, device=self.device)
+        p = t.empty(self.N, 3, dtype=t.float32, device=self.device)
+        sim_get_task_state(self.h, c.data_ptr(), tg.data_ptr(), p.data_ptr(), self._stream())
+        return c, tg, p
+
+    def set_task_state(self, counters, targets):
+        c = self._dev(np.asarray(counters, np.int32).reshape(self.N, 4), self.torch.int32)
+        tg = self._dev(np.asarray(targets, np.float32).reshape(self.N, 2), self.torch.float32)
+        sim_set_task_state(self.h, c.data_ptr(), tg.data_ptr(), self._stream())
 
     def get_obs(self):
         sim_get_obs(self.h, self.obs.data_ptr(), self.reward.data_ptr(), self.done.data_ptr(), self._stream())

@@ -66,6 +66,14 @@ struct Model {
 };
 static_assert(sizeof(JointTab) == 32 * 4, "joint table entry is 32 words");
 
+// Task logic around the step (Section 4.1), as set by sim_set_task; passed to the kernels by value.
+struct TaskParams {
+  int32_t enabled, grace, period, push_min_f, push_max_f, auto_reset;
+  float reach, radius, push_min_n, push_max_n;
+  uint64_t seed;
+};
+constexpr uint64_t kEpisodeStride = 0x9E3779B97F4A7C15ULL;  // seed of episode k = seed + k * this
+
 // Contact record as kept in LDS / exported (matches sim_contact_rec_t: 12 words).
 constexpr int kRecWords = 12;
 

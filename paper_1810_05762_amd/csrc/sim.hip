@@ -41,7 +41,7 @@ extern "C" const char* sim_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ layout
 struct Layout {
-  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, flag, total;
+  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, reset_flag, push, flag, total;
 };
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -59,6 +59,9 @@ static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, si
   L.reward = o; o = align_up(o + (size_t)N * sizeof(float));
   L.done = o; o = align_up(o + (size_t)N);
   L.recs = o; o = align_up(o + (size_t)N * S * sizeof(sim_contact_rec_t));
+  L.task_i = o; o = align_up(o + (size_t)N * 4 * sizeof(int32_t));
+  L.reset_flag = o; o = align_up(o + (size_t)N);
+  L.push = o; o = align_up(o + (size_t)N * 3 * sizeof(float));
   L.flag = o; o = align_up(o + 256);
   L.total = o;
   return L;
@@ -71,6 +74,7 @@ struct sim {
   int N, obs_dim, E;
   int record;
   int recs_valid;
+  TaskParams task;
 };
 
 // ------------------------------------------------------- description -> Model
@@ -293,24 +297,10 @@ __global__ void gen_contacts_kernel(const Model* Mp, const float* __restrict__ h
   r[10] = __float_as_int(c.w); r[11] = 0;
 }
 
-// counter-based uniform draw: one 64-bit mixing finaliser per (seed, env, index)
-__device__ inline float reset_uniform(uint64_t seed, uint64_t env, uint64_t idx) {
-  uint64_t z = seed + env * 0x632BE59BD9B4E019ULL + idx * 0xD1B54A32D192ED03ULL;
-  z += 0x9E3779B97F4A7C15ULL;
-  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
-  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
-  z ^= z >> 31;
-  return (float)(z >> 40) * (1.0f / 16777216.0f);
-}
-
 // Seeded reset (Section 4.1: initial state perturbed slightly).  One thread per env;
 // bodies are placed parents-first through the joint list.
-__global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t* __restrict__ steps,
-                             const uint8_t* __restrict__ mask, uint64_t seed, int N) {
-  const Model& M = *Mp;
-  int env = blockIdx.x * blockDim.x + threadIdx.x;
-  if (env >= N) return;
-  if (mask && !mask[env]) return;
+__device__ void reset_one_env(const Model& M, float* __restrict__ state, int32_t* __restrict__ steps, int env,
+                              uint64_t seed, int N, float root_xy[2]) {
   const float a = M.reset_noise;
   float off[3], vel[3];
   for (int c = 0; c < 3; ++c) {
@@ -363,19 +353,65 @@ __global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t
     for (int c = 0; c < 3; ++c) { st[(7 + c) * fs] = vel[c]; st[(10 + c) * fs] = 0.0f; }
   }
   steps[env] = 0;
+  root_xy[0] = X[M.root][0]; root_xy[1] = X[M.root][1];
+}
+
+__global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t* __restrict__ steps,
+                             const uint8_t* __restrict__ mask, uint64_t seed, int N) {
+  int env = blockIdx.x * blockDim.x + threadIdx.x;
+  if (env >= N) return;
+  if (mask && !mask[env]) return;
+  float rxy[2];
+  reset_one_env(*Mp, state, steps, env, seed, N, rxy);
+}
+
+// Start of an episode for the task logic (Section 4.1): counters cleared, first push time and
+// (flagrun) first target drawn around the root.
+__device__ void task_begin_episode(const TaskParams& t, int32_t* __restrict__ task_i, float* __restrict__ targets,
+                                   int env, int episode, float rx, float ry) {
+  task_i[4 * env + 0] = 0; task_i[4 * env + 1] = 0;
+  task_i[4 * env + 2] = t.push_max_f > 0 ? task_interval(t, env, episode, 0) : -1;
+  task_i[4 * env + 3] = episode;
+  if (t.period > 0) task_draw_target(t, env, episode, 0, rx, ry, targets + 2 * env);
+}
+
+// sim_set_task: episode 0 for every env, from the current body state
+__global__ void task_init_kernel(const Model* Mp, const float* __restrict__ state, int32_t* __restrict__ task_i,
+                                 float* __restrict__ targets, float* __restrict__ push,
+                                 uint8_t* __restrict__ reset_flag, TaskParams t, int N) {
+  int env = blockIdx.x * blockDim.x + threadIdx.x;
+  if (env >= N) return;
+  const Model& M = *Mp;
+  const size_t fs = (size_t)M.B * N;
+  const float rx = state[0 * fs + (size_t)M.root * N + env], ry = state[1 * fs + (size_t)M.root * N + env];
+  task_begin_episode(t, task_i, targets, env, 0, rx, ry);
+  push[3 * env] = push[3 * env + 1] = push[3 * env + 2] = 0.0f;
+  reset_flag[env] = 0;
+}
+
+// after a step: envs whose episode ended start the next one (reset recipe, seed of that episode)
+__global__ void task_reset_kernel(const Model* Mp, float* __restrict__ state, int32_t* __restrict__ steps,
+                                  int32_t* __restrict__ task_i, float* __restrict__ targets,
+                                  const uint8_t* __restrict__ reset_flag, TaskParams t, int N) {
+  int env = blockIdx.x * blockDim.x + threadIdx.x;
+  if (env >= N || !reset_flag[env]) return;
+  const int episode = task_i[4 * env + 3] + 1;
+  float rxy[2];
+  reset_one_env(*Mp, state, steps, env, t.seed + (uint64_t)episode * kEpisodeStride, N, rxy);
+  task_begin_episode(t, task_i, targets, env, episode, rxy[0], rxy[1]);
 }
 
 // ---------------------------------------------------------------- launches
 static int launch_step(sim* s, const float* actions, float h, int substeps, int iterations, int count_step,
                        hipStream_t st, float* obs_out = nullptr, float* reward_out = nullptr,
-                       uint8_t* done_out = nullptr) {
+                       uint8_t* done_out = nullptr, const uint8_t* repack = nullptr) {
   const Model& m = s->host_model;
   StepArgs a;
   a.M = reinterpret_cast<const Model*>(s->ws + s->lay.model);
   a.heights = reinterpret_cast<const float*>(s->ws + s->lay.heights);
   a.coarse = reinterpret_cast<const float*>(s->ws + s->lay.coarse);
   a.origins = reinterpret_cast<const float*>(s->ws + s->lay.origins);
-  a.targets = reinterpret_cast<const float*>(s->ws + s->lay.targets);
+  a.targets = reinterpret_cast<float*>(s->ws + s->lay.targets);
   a.state = reinterpret_cast<float*>(s->ws + s->lay.state);
   a.steps = reinterpret_cast<int32_t*>(s->ws + s->lay.steps);
   a.actions = actions;
@@ -386,6 +422,11 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.N = s->N; a.E = s->E; a.substeps = substeps; a.iterations = iterations; a.count_step = count_step;
   a.h = h;
   a.obs_out = obs_out; a.reward_out = reward_out; a.done_out = done_out;
+  a.task = s->task;
+  a.task_i = reinterpret_cast<int32_t*>(s->ws + s->lay.task_i);
+  a.reset_flag = reinterpret_cast<uint8_t*>(s->ws + s->lay.reset_flag);
+  a.push = reinterpret_cast<float*>(s->ws + s->lay.push);
+  a.repack = repack;
 #ifdef EXP_TIMING
   a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
 #else
@@ -439,6 +480,7 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
   s->obs_dim = 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0);
   s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny);
   s->record = 0; s->recs_valid = 0;
+  memset(&s->task, 0, sizeof(s->task));
   s->E = default_envs_per_block(m, num_envs);
   if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace must be non-NULL and 256-byte aligned"); }
   if (workspace_bytes < s->lay.total) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, s->lay.total); }
@@ -483,6 +525,9 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
     HIP_TRY_S(hipMemset(s->ws + s->lay.steps, 0, (size_t)num_envs * sizeof(int32_t)));
     HIP_TRY_S(hipMemset(s->ws + s->lay.recs, 0, (size_t)num_envs * m.S * sizeof(sim_contact_rec_t)));
     HIP_TRY_S(hipMemset(s->ws + s->lay.flag, 0, 256));
+    HIP_TRY_S(hipMemset(s->ws + s->lay.task_i, 0, (size_t)num_envs * 4 * sizeof(int32_t)));
+    HIP_TRY_S(hipMemset(s->ws + s->lay.reset_flag, 0, (size_t)num_envs));
+    HIP_TRY_S(hipMemset(s->ws + s->lay.push, 0, (size_t)num_envs * 3 * sizeof(float)));
   }
   rc = launch_step(s, nullptr, 1.0f, 0, 0, 0, nullptr);
   if (rc) return bail(rc);
@@ -530,22 +575,83 @@ extern "C" int sim_reset(sim_t* s, const uint8_t* env_mask_dev, uint64_t seed, v
   return launch_step(s, nullptr, 1.0f, 0, 0, 0, st);
 }
 
-extern "C" int sim_step(sim_t* s, const float* actions_dev, float dt, int substeps, int iterations, void* stream) {
-  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+// One env-step: the fused kernel, then (task logic with auto-reset only) the reset of the envs
+// whose episode ended and a zero-substep launch that re-packs their observation.
+static int step_common(sim* s, const float* actions_dev, float dt, int substeps, int iterations, float* obs_dev,
+                       float* reward_dev, uint8_t* done_dev, hipStream_t st) {
   if (!(dt > 0.0f) || !std::isfinite(dt)) return fail(SIM_ERR_ARG, "dt must be finite and > 0");
   if (substeps < 1) return fail(SIM_ERR_ARG, "substeps must be >= 1 (got %d)", substeps);
   if (iterations < 0) return fail(SIM_ERR_ARG, "iterations must be >= 0 (got %d)", iterations);
-  return launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, static_cast<hipStream_t>(stream));
+  int rc = launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, st, obs_dev, reward_dev, done_dev);
+  if (rc || !(s->task.enabled && s->task.auto_reset)) return rc;
+  const uint8_t* flags = reinterpret_cast<const uint8_t*>(s->ws + s->lay.reset_flag);
+  hipLaunchKernelGGL(task_reset_kernel, dim3(blocks_for(s->N, 64)), dim3(64), 0, st,
+                     reinterpret_cast<const Model*>(s->ws + s->lay.model), reinterpret_cast<float*>(s->ws + s->lay.state),
+                     reinterpret_cast<int32_t*>(s->ws + s->lay.steps), reinterpret_cast<int32_t*>(s->ws + s->lay.task_i),
+                     reinterpret_cast<float*>(s->ws + s->lay.targets), flags, s->task, s->N);
+  HIP_TRY(hipGetLastError());
+  const int keep_recs = s->recs_valid;
+  rc = launch_step(s, nullptr, 1.0f, 0, 0, 0, st, obs_dev, nullptr, nullptr, flags);
+  s->recs_valid = keep_recs;
+  return rc;
+}
+
+extern "C" int sim_step(sim_t* s, const float* actions_dev, float dt, int substeps, int iterations, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  return step_common(s, actions_dev, dt, substeps, iterations, nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int sim_set_task(sim_t* s, const sim_task_desc_t* t, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  memset(&s->task, 0, sizeof(s->task));
+  if (!t || !t->enabled) return SIM_OK;
+  if (t->fall_grace_frames < 0 || t->target_period < 0) return fail(SIM_ERR_ARG, "task: negative frame count");
+  if (t->push_max_frames > 0 && (t->push_min_frames < 1 || t->push_min_frames > t->push_max_frames))
+    return fail(SIM_ERR_ARG, "task: need 1 <= push_min_frames <= push_max_frames");
+  if (!(t->target_radius >= 0) || !(t->target_reach >= 0) || !(t->push_min_newton <= t->push_max_newton))
+    return fail(SIM_ERR_ARG, "task: radius/reach must be >= 0 and push_min_newton <= push_max_newton");
+  TaskParams& p = s->task;
+  p.enabled = 1; p.grace = t->fall_grace_frames; p.period = t->target_period;
+  p.push_min_f = t->push_min_frames; p.push_max_f = t->push_max_frames; p.auto_reset = t->auto_reset ? 1 : 0;
+  p.reach = (float)t->target_reach; p.radius = (float)t->target_radius;
+  p.push_min_n = (float)t->push_min_newton; p.push_max_n = (float)t->push_max_newton; p.seed = t->seed;
+  hipLaunchKernelGGL(task_init_kernel, dim3(blocks_for(s->N, 64)), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const Model*>(s->ws + s->lay.model), reinterpret_cast<const float*>(s->ws + s->lay.state),
+                     reinterpret_cast<int32_t*>(s->ws + s->lay.task_i), reinterpret_cast<float*>(s->ws + s->lay.targets),
+                     reinterpret_cast<float*>(s->ws + s->lay.push), reinterpret_cast<uint8_t*>(s->ws + s->lay.reset_flag),
+                     s->task, s->N);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_get_task_state(sim_t* s, int32_t* counters_dev, float* targets_dev, float* push_dev, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (counters_dev) hipLaunchKernelGGL(copy_i32_kernel, dim3(blocks_for((size_t)s->N * 4)), dim3(256), 0, st,
+                                       reinterpret_cast<const int32_t*>(s->ws + s->lay.task_i), counters_dev, s->N * 4);
+  if (targets_dev) hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for((size_t)s->N * 2)), dim3(256), 0, st,
+                                      reinterpret_cast<const float*>(s->ws + s->lay.targets), targets_dev, s->N * 2);
+  if (push_dev) hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for((size_t)s->N * 3)), dim3(256), 0, st,
+                                   reinterpret_cast<const float*>(s->ws + s->lay.push), push_dev, s->N * 3);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_set_task_state(sim_t* s, const int32_t* counters_dev, const float* targets_dev, void* stream) {
+  if (!s || !counters_dev || !targets_dev) return fail(SIM_ERR_ARG, "sim, counters or targets is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(copy_i32_kernel, dim3(blocks_for((size_t)s->N * 4)), dim3(256), 0, st, counters_dev,
+                     reinterpret_cast<int32_t*>(s->ws + s->lay.task_i), s->N * 4);
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for((size_t)s->N * 2)), dim3(256), 0, st, targets_dev,
+                     reinterpret_cast<float*>(s->ws + s->lay.targets), s->N * 2);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
 }
 
 extern "C" int sim_step_obs(sim_t* s, const float* actions_dev, float dt, int substeps, int iterations,
                             float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
-  if (!(dt > 0.0f) || !std::isfinite(dt)) return fail(SIM_ERR_ARG, "dt must be finite and > 0");
-  if (substeps < 1) return fail(SIM_ERR_ARG, "substeps must be >= 1 (got %d)", substeps);
-  if (iterations < 0) return fail(SIM_ERR_ARG, "iterations must be >= 0 (got %d)", iterations);
-  return launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, static_cast<hipStream_t>(stream),
-                     obs_dev, reward_dev, done_dev);
+  return step_common(s, actions_dev, dt, substeps, iterations, obs_dev, reward_dev, done_dev, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int sim_get_obs(sim_t* s, float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream) {

@@ -45,7 +45,7 @@ struct StepArgs {
   const float* heights;
   const float* coarse;   // block maxima of the heightfield
   const float* origins;  // [N][3]
-  const float* targets;  // [N][2]
+  float* targets;  // [N][2]
   float* state;          // [13][B][N]
   int32_t* steps;        // [N]
   const float* actions;  // [N][D] or null
@@ -58,6 +58,11 @@ struct StepArgs {
   float* obs_out;        // optional caller copies of obs / reward / done (sim_step_obs), else null
   float* reward_out;
   uint8_t* done_out;
+  TaskParams task;       // task logic (enabled = 0: off)
+  int32_t* task_i;       // [N][4]: frames below the threshold, target age, frame of the next push, episode
+  uint8_t* reset_flag;   // [N]: set when the env finished its episode and is to be reset
+  float* push;           // [N][3]: force on the root body during this step
+  const uint8_t* repack; // non-null: only re-pack the observation of the flagged envs (zero substeps)
   long long* dbg;
 };
 
@@ -66,7 +71,7 @@ struct StepArgs {
 constexpr int kVS = 7, kCS = 7, kJS = 13;
 
 struct LdsPlan {
-  int pos, vel, iw, nb, tq, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
+  int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
 };
 
 __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch) {
@@ -77,6 +82,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.iw = o; o += B * kVS * E;
   p.nb = o; o += B * E;
   p.tq = o; o += J * 3 * E;
+  p.push = o; o += 3 * E;
   o += o & 1;  // the search results kept in the copy arrays are 64-bit words
   p.outj = o; o += J * kJS * E;
   p.outc = o; o += S * kCS * E;
@@ -271,6 +277,33 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
 // EC > 0: envs per workgroup fixed at compile time (LDS offsets become immediates);
 // EC == 0: taken from the launch arguments.  NJ: compile-time bound on the joints one body
 // belongs to (the per-body average reads NJ joint copies without branching).
+// counter-based uniform draw: one 64-bit mixing finaliser per (seed, env, index)
+__device__ inline float reset_uniform(uint64_t seed, uint64_t env, uint64_t idx) {
+  uint64_t z = seed + env * 0x632BE59BD9B4E019ULL + idx * 0xD1B54A32D192ED03ULL;
+  z += 0x9E3779B97F4A7C15ULL;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+  z ^= z >> 31;
+  return (float)(z >> 40) * (1.0f / 16777216.0f);
+}
+// draws of the task logic, keyed by (seed, episode, env, frame, k): k = 0 push magnitude,
+// 1 push direction, 2 frames to the next push, 3 target distance, 4 target direction
+__device__ inline float task_u(const TaskParams& t, int env, int episode, int frame, int k) {
+  return reset_uniform(t.seed + (uint64_t)episode * kEpisodeStride, (uint64_t)env, (uint64_t)(1024 + 8 * frame + k));
+}
+__device__ inline int task_interval(const TaskParams& t, int env, int episode, int frame) {
+  const int span = t.push_max_f - t.push_min_f + 1;
+  const int d = t.push_min_f + (int)floorf(task_u(t, env, episode, frame, 2) * (float)span);
+  return d > t.push_max_f ? t.push_max_f : d;
+}
+__device__ inline void task_draw_target(const TaskParams& t, int env, int episode, int frame, float rx, float ry,
+                                        float* target_xy) {
+  const float r = t.radius * sqrtf(task_u(t, env, episode, frame, 3));
+  const float phi = 6.283185307179586f * task_u(t, env, episode, frame, 4);
+  target_xy[0] = rx + r * cosf(phi);
+  target_xy[1] = ry + r * sinf(phi);
+}
+
 // (squared distance, feature id) as one 64-bit word whose unsigned order is the lexicographic
 // order of the pair (squared distances are non-negative, ids non-negative)
 __device__ __forceinline__ unsigned long long pack_best(float d2, int id) {
@@ -346,6 +379,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   unsigned* Lunit = reinterpret_cast<unsigned*>(lds + P.obs);
   const int unit_cap = (11 + 3 * D + F) * E, unit_cap_e = unit_cap / 3;
   float* Ltq = lds + P.tq;                           // joint torques, [J][3][E]
+  float* Lpush = lds + P.push;                       // external force on the root body, [3][E]
   float* Lu = lds + P.u;
   float* Lobs = lds + P.obs;
   int* Llim = reinterpret_cast<int*>(lds + P.lim);
@@ -360,6 +394,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const JointTab* Ltjoint = reinterpret_cast<const JointTab*>(lds + P.tjoint);  // joint table
   const float h = a.h;
 
+  // re-packing launch: a workgroup none of whose envs is flagged has nothing to do
+  if (a.repack) {
+    const int env_t = blockIdx.x * E + (tid < E ? tid : 0);
+    if (!__syncthreads_or(tid < E && env_t < N && a.repack[env_t])) return;
+  }
   // ---- load: body state into registers, clipped actions into LDS
   float x[3] = {0, 0, 0}, q[4] = {1, 0, 0, 0}, v[3] = {0, 0, 0}, w[3] = {0, 0, 0};
   int my_slot0 = 0, my_nslots = 0, my_njs = 0;
@@ -393,6 +432,22 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     int c = i / E, ee = i - c * E, env_i = blockIdx.x * E + ee;
     Lorg[i] = env_i < N ? a.origins[3 * env_i + c] : 0.0f;
   }
+  // external pushes (Section 4.1): is this frame the env's next push?
+  if (tid < E) {
+    const int env_t = blockIdx.x * E + tid;
+    float fx = 0.0f, fy = 0.0f;
+    if (a.task.enabled && a.task.push_max_f > 0 && a.count_step && env_t < N) {
+      const int f = a.steps[env_t], ep = a.task_i[4 * env_t + 3];
+      if (f == a.task_i[4 * env_t + 2]) {
+        const float mag = a.task.push_min_n + (a.task.push_max_n - a.task.push_min_n) * task_u(a.task, env_t, ep, f, 0);
+        const float phi = 6.283185307179586f * task_u(a.task, env_t, ep, f, 1);
+        fx = mag * cosf(phi); fy = mag * sinf(phi);
+        a.task_i[4 * env_t + 2] = f + task_interval(a.task, env_t, ep, f);
+      }
+    }
+    Lpush[0 * E + tid] = fx; Lpush[1 * E + tid] = fy; Lpush[2 * E + tid] = 0.0f;
+    if (a.task.enabled && a.count_step && env_t < N) { a.push[3 * env_t] = fx; a.push[3 * env_t + 1] = fy; a.push[3 * env_t + 2] = 0.0f; }
+  }
   for (int i = tid; i < M.table_words; i += kThreads) reinterpret_cast<int*>(lds + P.tjs)[i] = M.table_image[i];
   for (int i = tid; i < (J * kJS + S * kCS) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
   // contact records start cleared (a step with zero substeps packs "no contact")
@@ -405,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 
   // per-env copy of the heightfield samples around the root body (the whole robot stays
   // within it during one step; anything outside falls back to global memory)
-  if (use_patch) {
+  if (use_patch && a.substeps > 0) {   // (a launch without substeps never searches the terrain)
     if (tid < E) {
       int env_e = blockIdx.x * E + tid;
       int pi0 = 0, pj0 = 0;
@@ -792,6 +847,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       quat_to_mat(qq, R);
       for (int c = 0; c < 3; ++c) { Ib[c] = Ltin[6 * b + c]; invIb[c] = Ltin[6 * b + 3 + c]; }
       for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * kVS + c) * E + e]; w[c] = Lvel[(b * kVS + 3 + c) * E + e]; }
+      if (a.task.enabled && b == M.root) {
+        const float him = h * Ltbody[4 * b + 3];
+        v[0] += him * Lpush[0 * E + e]; v[1] += him * Lpush[1 * E + e]; v[2] += him * Lpush[2 * E + e];
+      }
       v[0] += h * g0; v[1] += h * g1; v[2] += h * g2;
       float wb[3], tb[3];
       mat_t_vec(R, w, wb);
@@ -1139,14 +1198,37 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     float cvert = 1.0f - 2.0f * (qx * qx + qy * qy);
     float r_stand = cvert > 0.93f ? 1.0f : 0.0f;
     int steps = a.steps[env_e] + (a.count_step ? 1 : 0);
-    a.steps[env_e] = steps;
+    const bool only_obs = a.repack != nullptr;       // re-packing a freshly reset env: obs only
+    if (!only_obs) a.steps[env_e] = steps;
     const float rew = M.alive_bonus + speed + 0.5f * r_head + 0.05f * r_stand - 4.0f * l1 - 0.5f * l2 -
                       0.2f * (float)n_lim - (float)n_feet;
-    const uint8_t dn = (height < M.term_height || steps >= M.max_steps) ? 1 : 0;
-    a.reward[env_e] = rew;
-    a.done[env_e] = dn;
-    if (a.reward_out) a.reward_out[env_e] = rew;
-    if (a.done_out) a.done_out[env_e] = dn;
+    uint8_t dn = (height < M.term_height || steps >= M.max_steps) ? 1 : 0;
+    if (a.task.enabled && a.count_step) {
+      // Section 4.1: termination only after `grace` consecutive frames below the threshold;
+      // flagrun target re-drawn every `period` frames or when reached; finished envs are flagged
+      // for the reset that follows this launch
+      int fall = a.task_i[4 * env_e + 0], age = a.task_i[4 * env_e + 1];
+      const int ep = a.task_i[4 * env_e + 3];
+      fall = height < M.term_height ? fall + 1 : 0;
+      dn = (fall > a.task.grace || steps >= M.max_steps) ? 1 : 0;
+      if (a.task.period > 0) {
+        age += 1;
+        if (age >= a.task.period || tn < a.task.reach) {
+          float txy[2];
+          task_draw_target(a.task, env_e, ep, steps, rx[0], rx[1], txy);
+          a.targets[2 * env_e] = txy[0]; a.targets[2 * env_e + 1] = txy[1];
+          age = 0;
+        }
+      }
+      a.task_i[4 * env_e + 0] = fall; a.task_i[4 * env_e + 1] = age;
+      a.reset_flag[env_e] = (dn && a.task.auto_reset) ? 1 : 0;
+    }
+    if (!only_obs) {
+      a.reward[env_e] = rew;
+      a.done[env_e] = dn;
+      if (a.reward_out) a.reward_out[env_e] = rew;
+      if (a.done_out) a.done_out[env_e] = dn;
+    }
   }
   __syncthreads();
   {
@@ -1155,6 +1237,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     for (int i = tid; i < n_here * obs_dim; i += kThreads) {
       const float o = Lobs[i];
       const int ee = i / obs_dim, k = i - ee * obs_dim;
+      if (a.repack && !a.repack[env0 + ee]) continue;
       a.obs[(size_t)(env0 + ee) * obs_row + k] = o;
       if (a.obs_out) a.obs_out[(size_t)(env0 + ee) * obs_row + k] = o;
     }
@@ -1184,6 +1267,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       constexpr int kHm = kHmRows * kHmCols;
       for (int i = tid; i < n_here * kHm; i += kThreads) {
         const int ee = i / kHm, k = i - ee * kHm, hi = k / kHmCols, hj = k - hi * kHmCols;
+        if (a.repack && !a.repack[env0 + ee]) continue;
         const float fw = M.hm_fwd[hi], lt = M.hm_lat[hj], c = Lhm[3 * E + ee], sn = Lhm[4 * E + ee];
         const float wx = Lhm[0 * E + ee] + (c * fw - sn * lt), wy = Lhm[1 * E + ee] + (sn * fw + c * lt);
         const float hz = terrain_height(M, a.heights, wx, wy) - Lhm[2 * E + ee];
