@@ -79,6 +79,23 @@ __device__ __forceinline__ void field_cell_heights(const Field& H, int i, int j,
   }
 }
 
+// The same for a sample that may lie on the last row or column: the neighbours that do not exist
+// are replaced by the sample itself (callers do not use them).
+__device__ __forceinline__ void field_cell_heights_clamped(const Field& H, int i, int j, float& h00, float& h10,
+                                                           float& h11, float& h01) {
+  unsigned di = (unsigned)(i - H.pi0), dj = (unsigned)(j - H.pj0);
+  if (di + 1u < (unsigned)H.ps && dj + 1u < (unsigned)H.ps) {
+    const lds_float* p = H.patch + dj * H.ps + di;
+    h00 = p[0]; h10 = p[1]; h01 = p[H.ps]; h11 = p[H.ps + 1];
+  } else {
+    const int ip = i + 1 < H.nx ? i + 1 : i, jp = j + 1 < H.ny ? j + 1 : j;
+    h00 = H.h[j * H.nx + i]; h10 = H.h[j * H.nx + ip]; h01 = H.h[jp * H.nx + i]; h11 = H.h[jp * H.nx + ip];
+  }
+}
+// world x / y of sample column i / row j
+__device__ __forceinline__ float field_x(const Field& H, int i) { float fx = (float)i * H.cell; return H.ox + fx; }
+__device__ __forceinline__ float field_y(const Field& H, int j) { float fy = (float)j * H.cell; return H.oy + fy; }
+
 __device__ __forceinline__ f3 field_vertex(const Field& H, int i, int j) {
   float fx = (float)i * H.cell, fy = (float)j * H.cell;
   return f3{H.ox + fx, H.oy + fy, field_height(H, i, j)};
@@ -332,9 +349,12 @@ __device__ __forceinline__ bool underneath_contact(const Field& H, const SlotGeo
   int i = (int)fi, j = (int)fj;
   float fx = ux - fi, fy = uy - fj;
   int t = (fx >= fy) ? 0 : 1;
-  f3 A = field_vertex(H, i, j);
-  f3 Bv = t == 0 ? field_vertex(H, i + 1, j) : field_vertex(H, i + 1, j + 1);
-  f3 Cv = t == 0 ? field_vertex(H, i + 1, j + 1) : field_vertex(H, i, j + 1);
+  float h00, h10, h11, h01;
+  field_cell_heights(H, i, j, h00, h10, h11, h01);   // the four corners in one go
+  const float x0 = field_x(H, i), x1 = field_x(H, i + 1), y0 = field_y(H, j), y1 = field_y(H, j + 1);
+  f3 A = f3{x0, y0, h00}, C1 = f3{x1, y1, h11};
+  f3 Bv = t == 0 ? f3{x1, y0, h10} : C1;
+  f3 Cv = t == 0 ? C1 : f3{x0, y1, h01};
   f3 nt = cross3(sub3(Bv, A), sub3(Cv, A));
   float face = dot3(sub3(P, A), nt);
   if (!(face < 0.0f)) return false;
@@ -481,8 +501,10 @@ __device__ __forceinline__ int segment_candidates(const Field& H, const SegCull&
 // edge is not admissible (closest point at an end of the segment, or the axis not above it).
 __device__ __forceinline__ bool segment_edge_d2(const Field& H, f3 P0, f3 P1, int i, int j, int k, float& d2) {
   const int i1 = i + (k == 1 ? 0 : 1), j1 = j + (k == 0 ? 0 : 1);
-  f3 Q0 = f3{H.ox + (float)i * H.cell, H.oy + (float)j * H.cell, field_height(H, i, j)};
-  f3 Q1 = f3{H.ox + (float)i1 * H.cell, H.oy + (float)j1 * H.cell, field_height(H, i1, j1)};
+  float h00, h10, h11, h01;
+  field_cell_heights_clamped(H, i, j, h00, h10, h11, h01);
+  f3 Q0 = f3{H.ox + (float)i * H.cell, H.oy + (float)j * H.cell, h00};
+  f3 Q1 = f3{H.ox + (float)i1 * H.cell, H.oy + (float)j1 * H.cell, k == 0 ? h10 : (k == 1 ? h01 : h11)};
   float s, t;
   seg_edge_st(P0, P1, Q0, Q1, s, t);
   if (!(s > 0.001f && s < 0.999f)) return false;  // the ends belong to the end-sphere slots
@@ -520,9 +542,13 @@ __device__ __forceinline__ ContactOut finish_sphere(const Field& H, const SlotGe
   const int ncx = H.nx - 1;
   f3 pl = g.kind == 0 ? g.p0 : g.p1;
   int t = best_id & 1, c = best_id >> 1, i = c % ncx, j = c / ncx;
-  f3 A = sub3(field_vertex(H, i, j), g.org);
-  f3 Bv = sub3(t == 0 ? field_vertex(H, i + 1, j) : field_vertex(H, i + 1, j + 1), g.org);
-  f3 Cv = sub3(t == 0 ? field_vertex(H, i + 1, j + 1) : field_vertex(H, i, j + 1), g.org);
+  float h00, h10, h11, h01;
+  field_cell_heights(H, i, j, h00, h10, h11, h01);
+  const float x0 = field_x(H, i), x1 = field_x(H, i + 1), y0 = field_y(H, j), y1 = field_y(H, j + 1);
+  const f3 C1 = f3{x1, y1, h11};
+  f3 A = sub3(f3{x0, y0, h00}, g.org);
+  f3 Bv = sub3(t == 0 ? f3{x1, y0, h10} : C1, g.org);
+  f3 Cv = sub3(t == 0 ? C1 : f3{x0, y1, h01}, g.org);
   float v, w;
   tri_closest_vw(pl, A, Bv, Cv, v, w);
   f3 df = sub3(pl, tri_point(A, Bv, Cv, v, w));
@@ -552,8 +578,10 @@ __device__ __forceinline__ ContactOut finish_segment(const Field& H, const SlotG
   float d = dist - g.r;
   if (!(d < margin)) return out;
   int k = best_id % 3, vtx = best_id / 3, i = vtx % H.nx, j = vtx / H.nx;
-  f3 Q0 = sub3(field_vertex(H, i, j), g.org);
-  f3 Q1 = sub3(k == 0 ? field_vertex(H, i + 1, j) : (k == 1 ? field_vertex(H, i, j + 1) : field_vertex(H, i + 1, j + 1)),
+  float h00, h10, h11, h01;
+  field_cell_heights_clamped(H, i, j, h00, h10, h11, h01);
+  f3 Q0 = sub3(f3{field_x(H, i), field_y(H, j), h00}, g.org);
+  f3 Q1 = sub3(f3{field_x(H, i + (k == 1 ? 0 : 1)), field_y(H, j + (k == 0 ? 0 : 1)), k == 0 ? h10 : (k == 1 ? h01 : h11)},
                g.org);
   float s, t;
   seg_edge_st(g.p0, g.p1, Q0, Q1, s, t);
