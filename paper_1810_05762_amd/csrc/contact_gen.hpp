@@ -273,7 +273,7 @@ __device__ __forceinline__ bool slot_range(const Field& H, SlotGeom& g) {
 
 // Cells overlapped by the reach box; false when the slot cannot touch the field
 // (box outside the field, or higher than every sample of the coarse blocks under it).
-__device__ __forceinline__ bool slot_reach(const Field& H, SlotGeom& g) {
+__device__ __forceinline__ bool slot_reach(const Field& H, SlotGeom& g, bool exact = true) {
   const int ncx = H.nx - 1, ncy = H.ny - 1;
   float xl, xh, yl, yh, zl;
   if (g.kind < 2) {
@@ -311,7 +311,7 @@ __device__ __forceinline__ bool slot_reach(const Field& H, SlotGeom& g) {
       // block maxima say "maybe": take the exact maximum over the samples of the box when it
       // is at most 6 x 6 (all 36 reads are issued together, indices clamped into the box)
       const int ni = g.i1 - g.i0 + 2, nj = g.j1 - g.j0 + 2;
-      if (!(zcut > hmax) && ni <= 6 && nj <= 6) {
+      if (exact && !(zcut > hmax) && ni <= 6 && nj <= 6) {
         const int bi = g.i0 - H.pi0, bj = g.j0 - H.pj0;
         hmax = -INFINITY;
         float hv[36];

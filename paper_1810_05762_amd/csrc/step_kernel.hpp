@@ -605,7 +605,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
                                  2, bo);
           Field H = H0;
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
-          near = slot_reach(H, g);
+          near = slot_reach(H, g, false);
         }
         const int pos = wave_alloc<2>(near ? ns : 0, &Lcount[7]);
         for (int k = 0; k < ns; ++k) {
