@@ -446,6 +446,9 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   const bool few = m.max_joint_sides <= 4;
   int lrc = (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
             : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
+            : (s->E == 4 && few) ? launch(&step_kernel<4, 4>)
+            : (s->E == 2 && few) ? launch(&step_kernel<2, 4>)
+            : (s->E == 1 && few) ? launch(&step_kernel<1, 4>)
             : few ? launch(&step_kernel<0, 4>) : launch(&step_kernel<0, kMaxBodyJoints>);
   if (lrc) return lrc;
   HIP_TRY(hipGetLastError());
