@@ -368,10 +368,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   int* Llist = reinterpret_cast<int*>(lds + P.list);
   int* Lsurv = reinterpret_cast<int*>(lds + P.surv);
   float* Llam = lds + P.lam;                         // impulses of the contacts beyond one per thread
-  // fine search: per queued slot the minimum of (squared distance, feature id) packed in 64 bits,
+  // fine search: per slot (index s * E + env) the minimum of (squared distance, feature id) packed in 64 bits,
   // then the list of candidate edges; both live in the space of the copies the sweeps use
   unsigned long long* Lbest64 = reinterpret_cast<unsigned long long*>(lds + P.outj);
-  float* Lgeo = lds + P.outj + 2 * S * E;           // per queued slot: reach, and R L, 1/L^2 of a segment
+  float* Lgeo = lds + P.outj + 2 * S * E;           // per slot: reach, and R L, 1/L^2 of a segment
   unsigned* Lcand = reinterpret_cast<unsigned*>(lds + P.outj) + 5 * S * E;
   const int cand_cap = (J * kJS + S * kCS) * E - 5 * S * E;
   // work units of the fine search (8 cells of one queued slot each): end spheres in the first
@@ -643,7 +643,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
             const bool mid = sl.kind == 2;
             qi = mid ? S * E - 1 - atomicAdd(&Lcount[2], 1) : atomicAdd(&Lcount[1], 1);
             Lsurv[qi] = i;
-            Lbest64[qi] = ~0ull;
+            Lbest64[i] = ~0ull;
             const int ni = g.i1 - g.i0 + (mid ? 2 : 1), nj = g.j1 - g.j0 + (mid ? 2 : 1);
             const bool fits = ni <= 15 && nj <= 15 && g.i0 < 4096 && g.j0 < 4096;  // packed box below
             const f3 Pa = sl.kind == 1 ? g.P1 : g.P0;
@@ -651,13 +651,13 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
             Lrec[(s * kRecWords + 3) * E + ee] = Pa.z;
             Lreci[(s * kRecWords + 7) * E + ee] = g.i0 | (g.j0 << 12) | (ni << 24) | (nj << 28);
             Lreci[(s * kRecWords + 8) * E + ee] = fits ? 0 : 1;   // 1: search this slot the slow way
-            Lgeo[3 * qi] = g.Rq;
+            Lgeo[3 * i] = g.Rq;
             if (mid) {
               Lrec[(s * kRecWords + 4) * E + ee] = g.P1.x; Lrec[(s * kRecWords + 5) * E + ee] = g.P1.y;
               Lrec[(s * kRecWords + 6) * E + ee] = g.P1.z;
               float RL, inv_L2;
               seg_cull_consts(g, RL, inv_L2);
-              Lgeo[3 * qi + 1] = RL; Lgeo[3 * qi + 2] = inv_L2;
+              Lgeo[3 * i + 1] = RL; Lgeo[3 * i + 2] = inv_L2;
             }
             if (!fits) Lcount[4] = 1;
             else if (mid) nu_m = (ni * nj + 7) >> 3;
@@ -671,7 +671,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         const int nu = nu_e + nu_m, u0 = nu_e ? ue : um, cap = nu_e ? unit_cap_e : unit_cap - unit_cap_e;
         unsigned* U = Lunit + (nu_e ? 0 : unit_cap_e);
         for (int u = 0; u < nu; ++u)
-          if (u0 + u < cap) U[u0 + u] = (unsigned)qi | ((unsigned)u << 12);
+          if (u0 + u < cap) U[u0 + u] = (unsigned)i | ((unsigned)u << 12);
         if (nu > 0 && u0 + nu > cap) { Lreci[(s * kRecWords + 8) * E + ee] = 1; Lcount[4] = 1; }
       }
       if (co.active) {
@@ -699,8 +699,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         const unsigned* U = Lunit + (pass == 0 ? 0 : unit_cap_e);
         for (int x = grp; x < n_u; x += kThreads / kGroup) {
           const unsigned uw = U[x];
-          const int qi = uw & 4095, c = (int)(uw >> 12) * 8 + gl;
-          const int i = Lsurv[qi];
+          const int i = uw & 4095, c = (int)(uw >> 12) * 8 + gl;   // slot index, cell within the box
           const int ee = i % E, s = i / E;
           const unsigned box = (unsigned)Lreci[(s * kRecWords + 7) * E + ee];
           const int i0 = box & 4095, j0 = (box >> 12) & 4095, ni = (box >> 24) & 15, nj = box >> 28;
@@ -709,17 +708,17 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           const int dj = (int)(((float)c + 0.5f) * __builtin_amdgcn_rcpf((float)ni)), di = c - dj * ni;
           if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
           const f3 Pa = f3{Lrec[(s * kRecWords + 1) * E + ee], Lrec[(s * kRecWords + 2) * E + ee], Lrec[(s * kRecWords + 3) * E + ee]};
-          const float Rq = Lgeo[3 * qi];
+          const float Rq = Lgeo[3 * i];
           int mask = 0;
           if (pass == 0) {
             if (c < ni * nj && sphere_cell_reach(H, Pa, Rq + kSelSlack, i0 + di, j0 + dj)) mask = 3;
           } else {
             const f3 Pb = f3{Lrec[(s * kRecWords + 4) * E + ee], Lrec[(s * kRecWords + 5) * E + ee], Lrec[(s * kRecWords + 6) * E + ee]};
-            const SegCull sc = seg_cull_from(Pa, Pb, Rq, Lgeo[3 * qi + 1], Lgeo[3 * qi + 2], i0 + ni - 2, j0 + nj - 2);
+            const SegCull sc = seg_cull_from(Pa, Pb, Rq, Lgeo[3 * i + 1], Lgeo[3 * i + 2], i0 + ni - 2, j0 + nj - 2);
             if (c < ni * nj) mask = segment_candidates(H, sc, i0 + di, j0 + dj);
           }
           int pos = wave_alloc<2>(__popc(mask), &Lcount[3]);
-          const unsigned cw = (unsigned)qi | ((unsigned)di << 14) | ((unsigned)dj << 18) | ((unsigned)pass << 22);
+          const unsigned cw = (unsigned)i | ((unsigned)di << 14) | ((unsigned)dj << 18) | ((unsigned)pass << 22);
 #pragma unroll
           for (int k = 0; k < 3; ++k)
             if ((mask >> k) & 1) {
@@ -739,8 +738,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         const int n_c = Lcount[3] < cand_cap ? Lcount[3] : cand_cap;
         for (int t = tid; t < n_c; t += kThreads) {
           const unsigned cw = Lcand[t];
-          const int qi = cw & 4095, k = (cw >> 12) & 3, di = (cw >> 14) & 15, dj = (cw >> 18) & 15;
-          const int i = Lsurv[qi];
+          const int i = cw & 4095, k = (cw >> 12) & 3, di = (cw >> 14) & 15, dj = (cw >> 18) & 15;
           const int ee = i % E, s = i / E;
           const unsigned box = (unsigned)Lreci[(s * kRecWords + 7) * E + ee];
           const int ci = (int)(box & 4095) + di, cj = (int)((box >> 12) & 4095) + dj;
@@ -748,10 +746,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           const f3 Pa = f3{Lrec[(s * kRecWords + 1) * E + ee], Lrec[(s * kRecWords + 2) * E + ee], Lrec[(s * kRecWords + 3) * E + ee]};
           float d2;
           if (((cw >> 22) & 1) == 0) {
-            if (sphere_tri_d2(H, Pa, ci, cj, k, d2)) atomicMin(&Lbest64[qi], pack_best(d2, 2 * (cj * (H.nx - 1) + ci) + k));
+            if (sphere_tri_d2(H, Pa, ci, cj, k, d2)) atomicMin(&Lbest64[i], pack_best(d2, 2 * (cj * (H.nx - 1) + ci) + k));
           } else {
             const f3 Pb = f3{Lrec[(s * kRecWords + 4) * E + ee], Lrec[(s * kRecWords + 5) * E + ee], Lrec[(s * kRecWords + 6) * E + ee]};
-            if (segment_edge_d2(H, Pa, Pb, ci, cj, k, d2)) atomicMin(&Lbest64[qi], pack_best(d2, 3 * (cj * H.nx + ci) + k));
+            if (segment_edge_d2(H, Pa, Pb, ci, cj, k, d2)) atomicMin(&Lbest64[i], pack_best(d2, 3 * (cj * H.nx + ci) + k));
           }
         }
         __syncthreads();
@@ -784,7 +782,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
               const SegCull sc = seg_cull(g);
               for (int c = gl; c < nc; c += kGroup) segment_vertex(H, g, sc, g.i0 + c % ni, g.j0 + c / ni, best, best_id);
             }
-            if (best_id >= 0) atomicMin(&Lbest64[qi], pack_best(best, best_id));
+            if (best_id >= 0) atomicMin(&Lbest64[i], pack_best(best, best_id));
           }
           __syncthreads();
         }
@@ -808,7 +806,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
                                p_margin, bx, bq, sl.kind, bo);
         if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
         ContactOut co = no_contact();
-        const unsigned long long bw = Lbest64[qi];
+        const unsigned long long bw = Lbest64[i];
         const float bestd = __uint_as_float((unsigned)(bw >> 32));
         const int besti = (int)(unsigned)bw;
         if (sl.kind < 2) {
