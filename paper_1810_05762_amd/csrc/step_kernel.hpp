@@ -560,23 +560,29 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     __syncthreads();
 
     TMARK(1);
-    // ---- B: joint torques (stored once per joint; the body applies the sign)
-    if (is_joint) {
-      const JointTab& jt = Ltjoint[idx];
-      float qa[4] = {1, 0, 0, 0};
-      if (jt.parent >= 0)
-        for (int c = 0; c < 4; ++c) qa[c] = Lpos[(jt.parent * 7 + 3 + c) * E + e];
-      float Ra[9];
-      quat_to_mat(qa, Ra);
-      float tq[3] = {0, 0, 0};
-      for (int k = 0; k < 3; ++k) {
-        if (jt.mode[k] != 1) continue;
-        float ak[3];
-        mat_vec(Ra, jt.axes[k], ak);
-        float t = jt.gear[k] * Lu[jt.act[k] * E + e];
-        tq[0] += t * ak[0]; tq[1] += t * ak[1]; tq[2] += t * ak[2];
+    // ---- B: joint torques (stored once per joint; the body applies the sign).  They go through
+    //         LDS only, so they are computed by the upper half of the workgroup when the joints fit
+    //         there: the lower half runs the per-body pass below at the same time.
+    {
+      const int tq_base = J * E <= kThreads / 2 ? kThreads / 2 : 0;
+      const int tj = (tid - tq_base) / E, te = (tid - tq_base) % E;
+      if (tid >= tq_base && tj < J && blockIdx.x * E + te < N) {
+        const JointTab& jt = Ltjoint[tj];
+        float qa[4] = {1, 0, 0, 0};
+        if (jt.parent >= 0)
+          for (int c = 0; c < 4; ++c) qa[c] = Lpos[(jt.parent * 7 + 3 + c) * E + te];
+        float Ra[9];
+        quat_to_mat(qa, Ra);
+        float tq[3] = {0, 0, 0};
+        for (int k = 0; k < 3; ++k) {
+          if (jt.mode[k] != 1) continue;
+          float ak[3];
+          mat_vec(Ra, jt.axes[k], ak);
+          float t = jt.gear[k] * Lu[jt.act[k] * E + te];
+          tq[0] += t * ak[0]; tq[1] += t * ak[1]; tq[2] += t * ak[2];
+        }
+        for (int c = 0; c < 3; ++c) Ltq[(tj * 3 + c) * E + te] = tq[c];
       }
-      for (int c = 0; c < 3; ++c) Ltq[(idx * 3 + c) * E + e] = tq[c];
     }
     // ---- B1: every slot: plane contact, or reach test against the heightfield copy.  A slot
     //          that may touch the heightfield (block maxima, then the exact maximum over its box)
