@@ -591,6 +591,37 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     //          work units of 8 cells (samples for a mid-segment).
     //          Slots go to the threads from the top of the workgroup down: a second round, if any,
     //          then runs on the last wavefronts while the first ones hold the joint threads.
+    // forces -> velocities (torques, gravity, push, explicit gyroscopic term): body threads, needs
+    // the joint torques and nothing of the contacts
+    auto forces = [&]() {
+      if (!is_body) return;
+      float tau[3] = {0, 0, 0};
+      for (int k = 0; k < my_njs; ++k) {
+        const int js = Ltjs[b * (kMaxBodyJoints + 3) + 3 + k];
+        const float sg = (js & 1) ? 1.0f : -1.0f;
+        for (int c = 0; c < 3; ++c) tau[c] += sg * Ltq[((js >> 1) * 3 + c) * E + e];
+      }
+      float R[9], qq[4], Ib[3], invIb[3];
+      for (int c = 0; c < 4; ++c) qq[c] = Lpos[(b * 7 + 3 + c) * E + e];
+      quat_to_mat(qq, R);
+      for (int c = 0; c < 3; ++c) { Ib[c] = Ltin[6 * b + c]; invIb[c] = Ltin[6 * b + 3 + c]; }
+      for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * kVS + c) * E + e]; w[c] = Lvel[(b * kVS + 3 + c) * E + e]; }
+      if (a.task.enabled && b == M.root) {
+        const float him = h * Ltbody[4 * b + 3];
+        v[0] += him * Lpush[0 * E + e]; v[1] += him * Lpush[1 * E + e]; v[2] += him * Lpush[2 * E + e];
+      }
+      v[0] += h * g0; v[1] += h * g1; v[2] += h * g2;
+      float wb[3], tb[3];
+      mat_t_vec(R, w, wb);
+      mat_t_vec(R, tau, tb);
+      float Iw[3] = {Ib[0] * wb[0], Ib[1] * wb[1], Ib[2] * wb[2]};
+      float gy[3];
+      cross(wb, Iw, gy);
+      if (!p_gyro) { gy[0] = gy[1] = gy[2] = 0.0f; }
+      for (int c = 0; c < 3; ++c) wb[c] += h * (tb[c] - gy[c]) * invIb[c];
+      mat_vec(R, wb, w);
+      for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
+    };
     int n_b1 = S * E;            // slots the per-slot pass visits
     unsigned* Lslots = Lcand;    // heightfield: list of the slots of the bodies near the ground
     if (m_terrain == 1) {
@@ -625,6 +656,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       __syncthreads();
       TMARK(24);
       n_b1 = Lcount[7];
+      // the lower wavefronts integrate the forces while the upper ones run the per-slot pass
+      forces();
     }
     for (int x = kThreads - 1 - tid; x < n_b1; x += kThreads) {
       const int i = m_terrain == 1 ? (int)Lslots[x] : x;
@@ -834,39 +867,14 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     __syncthreads();
     TMARK(3);
 
-    // ---- C: block count, forces -> velocities
+    // ---- C: block weight sums (and, on the plane, forces -> velocities)
     float nbf = 0.0f;
     if (is_body) {
       nbf = (float)my_njs;
       for (int k = 0; k < my_nslots; ++k) nbf += Lrec[((my_slot0 + k) * kRecWords + 10) * E + e];
       Lnb[b * E + e] = nbf;
-      float tau[3] = {0, 0, 0};
-      for (int k = 0; k < my_njs; ++k) {
-        const int js = Ltjs[b * (kMaxBodyJoints + 3) + 3 + k];
-        const float sg = (js & 1) ? 1.0f : -1.0f;
-        for (int c = 0; c < 3; ++c) tau[c] += sg * Ltq[((js >> 1) * 3 + c) * E + e];
-      }
-      float R[9], qq[4], Ib[3], invIb[3];
-      for (int c = 0; c < 4; ++c) qq[c] = Lpos[(b * 7 + 3 + c) * E + e];
-      quat_to_mat(qq, R);
-      for (int c = 0; c < 3; ++c) { Ib[c] = Ltin[6 * b + c]; invIb[c] = Ltin[6 * b + 3 + c]; }
-      for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * kVS + c) * E + e]; w[c] = Lvel[(b * kVS + 3 + c) * E + e]; }
-      if (a.task.enabled && b == M.root) {
-        const float him = h * Ltbody[4 * b + 3];
-        v[0] += him * Lpush[0 * E + e]; v[1] += him * Lpush[1 * E + e]; v[2] += him * Lpush[2 * E + e];
-      }
-      v[0] += h * g0; v[1] += h * g1; v[2] += h * g2;
-      float wb[3], tb[3];
-      mat_t_vec(R, w, wb);
-      mat_t_vec(R, tau, tb);
-      float Iw[3] = {Ib[0] * wb[0], Ib[1] * wb[1], Ib[2] * wb[2]};
-      float gy[3];
-      cross(wb, Iw, gy);
-      if (!p_gyro) { gy[0] = gy[1] = gy[2] = 0.0f; }
-      for (int c = 0; c < 3; ++c) wb[c] += h * (tb[c] - gy[c]) * invIb[c];
-      mat_vec(R, wb, w);
-      for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
     }
+    if (m_terrain == 0) forces();   // plane: no per-body pass, the torques are complete only now
     if (a.recs && sub == a.substeps - 1) {
       // export the records of the last substep, [N][S][12] words
       for (int i = tid; i < S * E * kRecWords; i += kThreads) {
