@@ -225,8 +225,9 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
 }
 
 static int default_envs_per_block(const Model& m, int N) {
-  int bj = m.B > m.J ? m.B : m.J;
-  int lim = kThreads / bj;
+  // bodies need a thread each, joints two (one per side) plus a wavefront left for contacts
+  int lim = kThreads / m.B;
+  if (m.J > 0 && (kThreads - 64) / (2 * m.J) < lim) lim = (kThreads - 64) / (2 * m.J);
   if (lim > 16) lim = 16;
   int want = N / 256;  // keep at least one workgroup per compute unit when N allows
   if (want < 1) want = 1;
@@ -556,10 +557,9 @@ extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
   const Model& m = s->host_model;
   if (E == 0) { s->E = default_envs_per_block(m, s->N); return SIM_OK; }
-  int bj = m.B > m.J ? m.B : m.J;
-  if (E < 1 || E * bj > kThreads)
-    return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*max(B,J) <= %d)", E, kThreads,
-                kThreads);
+  if (E < 1 || E * m.B > kThreads || 2 * E * m.J > kThreads - 64)
+    return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*B <= %d and 2*E*J <= %d)", E, kThreads,
+                kThreads, kThreads - 64);
   LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, E, (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0);
   if ((size_t)P.total * 4 > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d exceeds LDS", E);
   s->E = E;

@@ -89,7 +89,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
   p.surv = o; o += S * E;
-  p.lam = o; o += 3 * (S * E > kThreads - ((J * E + 63) / 64) * 64 ? S * E - (kThreads - ((J * E + 63) / 64) * 64) : 0);
+  p.lam = o; o += 3 * (S * E > kThreads - ((2 * J * E + 63) / 64) * 64 ? S * E - (kThreads - ((2 * J * E + 63) / 64) * 64) : 0);
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
   p.lim = o; o += (D > 0 ? D : 1) * E;
@@ -189,18 +189,25 @@ __device__ __forceinline__ void store_record(float* Lrec, int* Lreci, int s, int
   Lrec[(s * kRecWords + 10) * E + ee] = co.w;
 }
 
-struct JointRows {
-  // positional rows along world x,y,z
-  float ra[3], rb[3];      // lever arms from each centre to the shared impulse point
-  float Ya[3][3], Yb[3][3];// angular response of parent / child per unit impulse
-  float sa, sb;            // linear response n_a/m_a, n_b/m_b
-  float pbias[3], pmeff[3];
-  // angular rows along the joint axes (sign folded in for upper limits)
-  float ax[3][3];
-  float Za[3][3], Zb[3][3];
-  float abias[3], ameff[3], lam[3];
-  int onesided;            // bit k set: row k is a limit row (impulse >= 0)
+// Rows of one joint as seen from ONE of its two bodies (a joint is relaxed by a pair of
+// neighbouring lanes, one per side; a row's J v is the sum of the two lanes' parts, exchanged
+// with a DPP lane swap, and each lane then updates its own body's copy).  sg = -1 for the
+// parent side, +1 for the child side; all signs are folded into the stored vectors.
+struct SideRows {
+  float sr[3];             // sg * lever arm from the own centre to the shared impulse point
+  float sv;                // sg * n_o / m_o: own linear response per unit impulse
+  float sg;
+  float Y[3][3];           // own angular response per unit impulse of positional row k
+  float pme[3], pnb[3];    // -m_eff and -m_eff * bias of the positional rows (world x, y, z)
+  float sax[3][3];         // sg * joint axis k (sign of an upper limit folded in)
+  float Z[3][3];           // own angular response per unit impulse of angular row k
+  float ame[3], anb[3], lam[3];
+  int onesided;            // bit k set: angular row k is a limit row (impulse >= 0)
 };
+// value of the neighbouring lane (lane ^ 1), one DPP move
+__device__ __forceinline__ float lane_swap1(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true));
+}
 
 struct ContactRows {
   float dir[3][3];   // n, t1, t2
@@ -516,12 +523,15 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   }
 
   TMARK(0);
-  // wavefronts [0, joint_threads/64) hold the joint threads; contact k of a workgroup goes to
-  // thread kThreads-1-k as long as that thread is not in a joint wavefront (n_reg contacts)
-  const int joint_threads = ((J * E + 63) / 64) * 64;
+  // wavefronts [0, joint_threads/64) hold the joint-side threads; contact k of a workgroup goes
+  // to thread kThreads-1-k as long as that thread is not in a joint wavefront (n_reg contacts)
+  const int joint_threads = ((2 * J * E + 63) / 64) * 64;
   const int n_reg = kThreads - joint_threads;
   const bool joint_wave = __builtin_amdgcn_readfirstlane(tid) < joint_threads;
-  JointRows jr;
+  // joint-side role: lanes 2p and 2p+1 are the parent and the child side of pair p = (joint, env)
+  const int js_side = tid & 1, js_e = (tid >> 1) % E, js_j = (tid >> 1) / E;
+  const bool js_on = js_j < J && blockIdx.x * E + js_e < N;
+  SideRows jr;
   ContactRows cr;
   bool has_contact = false;  // this thread owns an active contact this substep
 
@@ -892,53 +902,58 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     TMARK(4);
     // ---- D: row constants
     const int n_active = Lcount[0];
-    if (is_joint) {
-      const JointTab& jt = Ltjoint[idx];
-      const int pa = j_pa, pb = j_pb;
-      float xa[3] = {0, 0, 0}, qa[4] = {1, 0, 0, 0}, xb[3], qb[4];
-      float iwa[6] = {0, 0, 0, 0, 0, 0}, iwb[6], na = 0.0f, ima = 0.0f;
-      if (pa >= 0) {
-        for (int c = 0; c < 3; ++c) xa[c] = Lpos[(pa * 7 + c) * E + e];
-        for (int c = 0; c < 4; ++c) qa[c] = Lpos[(pa * 7 + 3 + c) * E + e];
-        for (int c = 0; c < 6; ++c) iwa[c] = Liw[(pa * kVS + c) * E + e];
-        na = Lnb[pa * E + e];
-        ima = Ltbody[4 * pa + 3];
+    if (js_on) {
+      const JointTab& jt = Ltjoint[js_j];
+      const int e = js_e;
+      const int ob = js_side ? jt.child : jt.parent;     // own body; -1: the static world
+      const bool ghost = ob < 0;
+      const int bo = ghost ? 0 : ob;                     // loads stay unconditional
+      const float sg = js_side ? 1.0f : -1.0f;
+      float xo[3], qo[4], iwo[6];
+      for (int c = 0; c < 3; ++c) xo[c] = Lpos[(bo * 7 + c) * E + e];
+      for (int c = 0; c < 4; ++c) qo[c] = Lpos[(bo * 7 + 3 + c) * E + e];
+      for (int c = 0; c < 6; ++c) iwo[c] = Liw[(bo * kVS + c) * E + e];
+      float no = Lnb[bo * E + e], imo = Ltbody[4 * bo + 3];
+      if (ghost) {
+        for (int c = 0; c < 3; ++c) xo[c] = 0.0f;
+        qo[0] = 1.0f; qo[1] = qo[2] = qo[3] = 0.0f;
+        for (int c = 0; c < 6; ++c) iwo[c] = 0.0f;
+        no = 0.0f; imo = 0.0f;
       }
-      for (int c = 0; c < 3; ++c) xb[c] = Lpos[(pb * 7 + c) * E + e];
-      for (int c = 0; c < 4; ++c) qb[c] = Lpos[(pb * 7 + 3 + c) * E + e];
-      for (int c = 0; c < 6; ++c) iwb[c] = Liw[(pb * kVS + c) * E + e];
-      const float nbb = Lnb[pb * E + e], imb = Ltbody[4 * pb + 3];
-      float Ra[9], Rb[9], t0[3], t1[3];
-      quat_to_mat(qa, Ra);
-      quat_to_mat(qb, Rb);
-      mat_vec(Ra, jt.la, t0);
-      mat_vec(Rb, jt.lb, t1);
-      float C[3];
+      // anchors: own one here, the other side's through the lane swap
+      float Ro[9], lo[3], t0[3], pw[3], C[3], r[3];
+      quat_to_mat(qo, Ro);
+      for (int c = 0; c < 3; ++c) lo[c] = js_side ? jt.lb[c] : jt.la[c];
+      mat_vec(Ro, lo, t0);
       for (int c = 0; c < 3; ++c) {
-        float pa_c = xa[c] + t0[c], pb_c = xb[c] + t1[c];
-        C[c] = pb_c - pa_c;
-        float mid = 0.5f * (pa_c + pb_c);
-        jr.ra[c] = mid - xa[c];
-        jr.rb[c] = mid - xb[c];
+        pw[c] = xo[c] + t0[c];
+        const float po = lane_swap1(pw[c]);
+        C[c] = sg * (pw[c] - po);                        // child anchor minus parent anchor
+        r[c] = 0.5f * (pw[c] + po) - xo[c];              // impulses act at the midpoint
+        jr.sr[c] = sg * r[c];
       }
-      jr.sa = na * ima; jr.sb = nbb * imb;
+      jr.sg = sg;
+      jr.sv = sg * no * imo;
       const float bh = p_beta_j / h;
       for (int k = 0; k < 3; ++k) {
-        float ca[3], cb[3], ya[3], yb[3];
-        cross_unit(jr.ra, k, ca);
-        cross_unit(jr.rb, k, cb);
-        sym_vec(iwa, ca, ya);
-        sym_vec(iwb, cb, yb);
-        float keff = na * (ima + dot(ca, ya)) + nbb * (imb + dot(cb, yb));
-        jr.pmeff[k] = keff > 0.0f ? 1.0f / keff : 0.0f;
-        jr.pbias[k] = bh * C[k];
-        for (int c = 0; c < 3; ++c) { jr.Ya[k][c] = -na * ya[c]; jr.Yb[k][c] = nbb * yb[c]; }
+        float cr[3], y[3];
+        cross_unit(r, k, cr);
+        sym_vec(iwo, cr, y);
+        const float kp = no * (imo + dot(cr, y));
+        const float keff = kp + lane_swap1(kp);
+        jr.pme[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
+        jr.pnb[k] = jr.pme[k] * (bh * C[k]);
+        for (int c = 0; c < 3; ++c) jr.Y[k][c] = sg * no * y[c];
       }
-      float phi[3];
+      // joint angles from both orientations; axes live in the parent frame
+      float qx[4], qa[4], qb[4], Ra[9], phi[3];
+      for (int c = 0; c < 4; ++c) qx[c] = lane_swap1(qo[c]);
+      for (int c = 0; c < 4; ++c) { qa[c] = js_side ? qx[c] : qo[c]; qb[c] = js_side ? qo[c] : qx[c]; }
+      quat_to_mat(qa, Ra);
       rel_rotvec(qa, qb, phi);
       jr.onesided = 0;
       for (int k = 0; k < 3; ++k) {
-        float ak[3], za[3], zb[3];
+        float ak[3], z[3];
         mat_vec(Ra, jt.axes[k], ak);
         float th = dot(jt.axes[k], phi);
         float sgn = 1.0f, bias;
@@ -951,13 +966,13 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           jr.onesided |= 1 << k;
         }
         for (int c = 0; c < 3; ++c) ak[c] *= sgn;
-        sym_vec(iwa, ak, za);
-        sym_vec(iwb, ak, zb);
-        float keff = na * dot(ak, za) + nbb * dot(ak, zb);
-        jr.ameff[k] = keff > 0.0f ? 1.0f / keff : 0.0f;
-        jr.abias[k] = bias;
+        sym_vec(iwo, ak, z);
+        const float kp = no * dot(ak, z);
+        const float keff = kp + lane_swap1(kp);
+        jr.ame[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
+        jr.anb[k] = jr.ame[k] * bias;
         jr.lam[k] = 0.0f;
-        for (int c = 0; c < 3; ++c) { jr.ax[k][c] = ak[c]; jr.Za[k][c] = -na * za[c]; jr.Zb[k][c] = nbb * zb[c]; }
+        for (int c = 0; c < 3; ++c) { jr.sax[k][c] = sg * ak[c]; jr.Z[k][c] = sg * no * z[c]; }
       }
     }
     // contact k of the workgroup's list goes to thread kThreads-1-k (the joint threads sit at
@@ -1025,38 +1040,39 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     };
     if (joint_wave) {
       for (int it = 0; it < a.iterations; ++it) {
-        if (is_joint) {
-          const int pa = j_pa, pb = j_pb;
-          float va[3] = {0, 0, 0}, wa[3] = {0, 0, 0}, vb[3], wb[3];
-          if (pa >= 0)
-            for (int c = 0; c < 3; ++c) { va[c] = Lvel[(pa * kVS + c) * E + e]; wa[c] = Lvel[(pa * kVS + 3 + c) * E + e]; }
-          for (int c = 0; c < 3; ++c) { vb[c] = Lvel[(pb * kVS + c) * E + e]; wb[c] = Lvel[(pb * kVS + 3 + c) * E + e]; }
+        if (js_on) {
+          const JointTab& jt = Ltjoint[js_j];
+          const int e = js_e;
+          const int ob = js_side ? jt.child : jt.parent;
+          const int bo = ob < 0 ? 0 : ob;
+          const float live = ob < 0 ? 0.0f : 1.0f;       // the world does not move
+          float vo[3], wo[3];
+          for (int c = 0; c < 3; ++c) { vo[c] = live * Lvel[(bo * kVS + c) * E + e]; wo[c] = live * Lvel[(bo * kVS + 3 + c) * E + e]; }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
-            float jv = (vb[k] - va[k]) + cross_unit_dot(jr.rb, k, wb) - cross_unit_dot(jr.ra, k, wa);
-            float dl = -jr.pmeff[k] * (jv + jr.pbias[k]);
-            va[k] -= jr.sa * dl;
-            vb[k] += jr.sb * dl;
-            for (int c = 0; c < 3; ++c) { wa[c] += jr.Ya[k][c] * dl; wb[c] += jr.Yb[k][c] * dl; }
+            const float part = jr.sg * vo[k] + cross_unit_dot(jr.sr, k, wo);
+            const float jv = part + lane_swap1(part);
+            const float dl = jv * jr.pme[k] + jr.pnb[k];
+            vo[k] += jr.sv * dl;
+            for (int c = 0; c < 3; ++c) wo[c] += jr.Y[k][c] * dl;
           }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
-            float dw[3] = {wb[0] - wa[0], wb[1] - wa[1], wb[2] - wa[2]};
-            float jv = dot(jr.ax[k], dw);
-            float dl = -jr.ameff[k] * (jv + jr.abias[k]);
+            const float part = dot(jr.sax[k], wo);
+            const float jv = part + lane_swap1(part);
+            float dl = jv * jr.ame[k] + jr.anb[k];
             if (jr.onesided & (1 << k)) {
               float ln = fmaxf(jr.lam[k] + dl, 0.0f);
               dl = ln - jr.lam[k];
               jr.lam[k] = ln;
             }
-            for (int c = 0; c < 3; ++c) { wa[c] += jr.Za[k][c] * dl; wb[c] += jr.Zb[k][c] * dl; }
+            for (int c = 0; c < 3; ++c) wo[c] += jr.Z[k][c] * dl;
           }
-          for (int c = 0; c < 3; ++c) {
-            Loutj[(idx * kJS + c) * E + e] = va[c];
-            Loutj[(idx * kJS + 3 + c) * E + e] = wa[c];
-            Loutj[(idx * kJS + 6 + c) * E + e] = vb[c];
-            Loutj[(idx * kJS + 9 + c) * E + e] = wb[c];
-          }
+          if (ob >= 0)
+            for (int c = 0; c < 3; ++c) {
+              Loutj[(js_j * kJS + js_side * 6 + c) * E + e] = vo[c];
+              Loutj[(js_j * kJS + js_side * 6 + 3 + c) * E + e] = wo[c];
+            }
         }
         __syncthreads();
         gather();
