@@ -990,53 +990,70 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     }
 
     TMARK(5);
-    // the copies this body averages: NJ joint sides (unused entries point at joint 0's copy
-    // with weight 0) and its three contact slots (weight 0 when inactive)
+    // The per-body average is split over two threads when the workgroup has room: thread (e, b)
+    // takes the linear half of body b's velocity, thread (e, B + b) the angular half (a wavefront
+    // issues one instruction every five to six cycles however many others share its SIMD, so two
+    // short threads beat one long one).  The copies a body averages: NJ joint sides (unused
+    // entries point at joint 0's copy with weight 0) and its three contact slots (weight 0 when
+    // inactive).
+    const bool g_split = 2 * B * E <= kThreads;
+    const int g_half = (g_split && idx >= B) ? 1 : 0;
+    const int g_b = idx - g_half * B;
+    const bool g_on = env_ok && g_b < B && idx < (g_split ? 2 * B : B);
+    float g_inb = 0.0f;
     int gat_off[NJ], gat_slot[3];
     float gat_w[NJ + 3];
+    {
+      const int* tb = Ltjs + (g_on ? g_b : 0) * (kMaxBodyJoints + 3);
+      const int g_njs = tb[0], g_slot0 = tb[1], g_nslots = tb[2];
+      const float g_nbf = g_on ? Lnb[g_b * E + e] : 0.0f;
+      g_inb = g_nbf > 0.0f ? 1.0f / g_nbf : 0.0f;
 #pragma unroll
-    for (int k = 0; k < NJ; ++k) {
-      const bool used = is_body && k < my_njs;
-      int js = used ? Ltjs[b * (kMaxBodyJoints + 3) + 3 + k] : 0;
-      gat_off[k] = ((js >> 1) * kJS + (js & 1) * 6) * E + e;
-      gat_w[k] = used ? 1.0f : 0.0f;
-    }
+      for (int k = 0; k < NJ; ++k) {
+        const bool used = g_on && k < g_njs;
+        int js = used ? tb[3 + k] : 0;
+        gat_off[k] = ((js >> 1) * kJS + (js & 1) * 6) * E + e;
+        gat_w[k] = used ? 1.0f : 0.0f;
+      }
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      const bool used = is_body && k < my_nslots;
-      gat_slot[k] = my_slot0 + (used ? k : 0);
-      gat_w[NJ + k] = used ? Lrec[((my_slot0 + k) * kRecWords + 10) * E + e] : 0.0f;
+      for (int k = 0; k < 3; ++k) {
+        const bool used = g_on && k < g_nslots;
+        gat_slot[k] = (g_slot0 + (used ? k : 0)) * kCS * E + e;
+        gat_w[NJ + k] = used ? Lrec[((g_slot0 + k) * kRecWords + 10) * E + e] : 0.0f;
+      }
     }
     // ---- S: sweeps
     // Wavefronts that hold joint threads run only the joint rows, the others only the contact
     // rows (a wave-uniform branch, so neither path carries the other's registers); both paths
     // execute the same two barriers per sweep.
-    auto gather = [&]() {
-      if (is_body && nbf > 0.0f) {
+    // one half (0 linear, 1 angular) of the average of body g_b
+    auto gather_half = [&](int hsel) {
+      if (g_on && g_inb > 0.0f) {
         // every load is unconditional: unused entries read a valid location and enter the sum
         // with weight 0 (the copy arrays only ever hold finite numbers); all reads are issued
         // before the first use so their LDS latency is paid once
-        float val[NJ + 3][6];
+        const int ho = hsel * 3 * E;
+        float val[NJ + 3][3];
 #pragma unroll
         for (int k = 0; k < NJ; ++k)
 #pragma unroll
-          for (int c = 0; c < 6; ++c) val[k][c] = Loutj[gat_off[k] + c * E];
+          for (int c = 0; c < 3; ++c) val[k][c] = Loutj[gat_off[k] + ho + c * E];
 #pragma unroll
         for (int k = 0; k < 3; ++k)
 #pragma unroll
-          for (int c = 0; c < 6; ++c) val[NJ + k][c] = Loutc[(gat_slot[k] * kCS + c) * E + e];
-        __builtin_amdgcn_sched_group_barrier(0x100, (NJ + 3) * 3, 0);  // the DS reads first
-        float acc[6] = {0, 0, 0, 0, 0, 0};
+          for (int c = 0; c < 3; ++c) val[NJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
+        __builtin_amdgcn_sched_group_barrier(0x100, (NJ + 3) * 2, 0);  // the DS reads first
+        float acc[3] = {0, 0, 0};
 #pragma unroll
         for (int k = 0; k < NJ + 3; ++k)
 #pragma unroll
-          for (int c = 0; c < 6; ++c) acc[c] += gat_w[k] * val[k][c];
-        float inb = 1.0f / nbf;
-        for (int c = 0; c < 3; ++c) {
-          v[c] = acc[c] * inb; w[c] = acc[3 + c] * inb;
-          Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c];
-        }
+          for (int c = 0; c < 3; ++c) acc[c] += gat_w[k] * val[k][c];
+        for (int c = 0; c < 3; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = acc[c] * g_inb;
       }
+    };
+    auto gather = [&]() {
+      gather_half(g_half);
+      if (!g_split) gather_half(1);
     };
     if (joint_wave) {
       for (int it = 0; it < a.iterations; ++it) {
@@ -1112,6 +1129,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       // the pose was parked in LDS during the sweeps (unchanged since phase A)
       for (int c = 0; c < 3; ++c) x[c] = Lpos[(b * 7 + c) * E + e];
       for (int c = 0; c < 4; ++c) q[c] = Lpos[(b * 7 + 3 + c) * E + e];
+      // the solved velocities were left in LDS by the threads that averaged them
+      for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * kVS + c) * E + e]; w[c] = Lvel[(b * kVS + 3 + c) * E + e]; }
       float dl = 1.0f / (1.0f + h * p_clin), da = 1.0f / (1.0f + h * p_cang);
       for (int c = 0; c < 3; ++c) { v[c] *= dl; w[c] *= da; }
       float wn = sqrtf(dot(w, w));
