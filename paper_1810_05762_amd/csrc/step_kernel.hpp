@@ -425,8 +425,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const float p_mu = M.mu, p_margin = M.margin, p_beta_j = M.beta_j, p_beta_c = M.beta_c;
   const float p_vdepen = M.v_depen, p_clin = M.c_lin, p_cang = M.c_ang, p_wmax = M.w_max;
   const int p_gyro = M.gyro;
-  int j_pa = -1, j_pb = 0;
-  if (is_joint) { j_pa = M.joints[idx].parent; j_pb = M.joints[idx].child; }
   for (int i = tid; i < E * D; i += kThreads) {
     int ee = i / D, d = i - ee * D;
     int env_i = blockIdx.x * E + ee;
