@@ -209,6 +209,10 @@ int sim_generate_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, vo
 /* Synchronises `stream` and scans the state: SIM_ERR_NONFINITE if any value is NaN/Inf. */
 int sim_check(sim_t* sim, void* stream);
 
+/* Launch shape of sim_step as it stands: threads and envs per workgroup, dynamic LDS bytes per
+ * workgroup (grid = ceil(num_envs / envs_per_block)).  Any output pointer may be NULL. */
+int sim_launch_info(const sim_t* sim, int32_t* threads_per_block, int32_t* envs_per_block, size_t* lds_bytes);
+
 /* Launch shape of sim_step: envs per workgroup (0 = library default). */
 int sim_set_envs_per_block(sim_t* sim, int envs_per_block);
 

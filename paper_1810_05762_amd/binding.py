@@ -78,6 +78,7 @@ _SYMBOLS = {
     "sim_get_contacts": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_generate_contacts": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_check": [C.c_void_p, C.c_void_p],
+    "sim_launch_info": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_size_t)],
     "sim_set_envs_per_block": [C.c_void_p, C.c_int],
     "sim_last_error": [],
 }
@@ -241,6 +242,12 @@ def sim_check(h, stream):
     return _chk(lib().sim_check(h, stream))
 
 
+def sim_launch_info(h):
+    t, e, l = C.c_int32(0), C.c_int32(0), C.c_size_t(0)
+    _chk(lib().sim_launch_info(h, C.byref(t), C.byref(e), C.byref(l)))
+    return {"threads_per_block": t.value, "envs_per_block": e.value, "lds_bytes": l.value}
+
+
 def sim_set_envs_per_block(h, e):
     return _chk(lib().sim_set_envs_per_block(h, int(e)))
 
@@ -366,6 +373,9 @@ class Sim:
 
     def check(self):
         sim_check(self.h, self._stream())
+
+    def launch_info(self):
+        return sim_launch_info(self.h)
 
     def set_envs_per_block(self, e):
         sim_set_envs_per_block(self.h, e)

@@ -553,6 +553,16 @@ extern "C" int sim_num_slots(const sim_t* s) { return s ? s->host_model.S : fail
 extern "C" int sim_obs_dim(const sim_t* s) { return s ? s->obs_dim : fail(SIM_ERR_ARG, "sim is NULL"); }
 extern "C" int sim_act_dim(const sim_t* s) { return s ? s->host_model.D : fail(SIM_ERR_ARG, "sim is NULL"); }
 
+extern "C" int sim_launch_info(const sim_t* s, int32_t* threads_per_block, int32_t* envs_per_block, size_t* lds_bytes) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  const Model& m = s->host_model;
+  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
+  if (threads_per_block) *threads_per_block = kThreads;
+  if (envs_per_block) *envs_per_block = s->E;
+  if (lds_bytes) *lds_bytes = (size_t)make_plan(m.B, m.J, m.S, m.D, m.F, s->E, with_patch).total * sizeof(float);
+  return SIM_OK;
+}
+
 extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
   const Model& m = s->host_model;
