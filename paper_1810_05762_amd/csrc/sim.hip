@@ -428,7 +428,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.reset_flag = reinterpret_cast<uint8_t*>(s->ws + s->lay.reset_flag);
   a.push = reinterpret_cast<float*>(s->ws + s->lay.push);
   a.repack = repack;
-#ifdef EXP_TIMING
+#ifdef SIM_PHASE_TIMING
   a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
 #else
   a.dbg = nullptr;

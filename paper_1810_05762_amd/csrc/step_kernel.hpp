@@ -63,7 +63,7 @@ struct StepArgs {
   uint8_t* reset_flag;   // [N]: set when the env finished its episode and is to be reset
   float* push;           // [N][3]: force on the root body during this step
   const uint8_t* repack; // non-null: only re-pack the observation of the flagged envs (zero substeps)
-  long long* dbg;
+  long long* dbg;        // phase-timing slots (diagnostic build only)
 };
 
 // Rows (E consecutive floats) per item of the velocity, inverse-inertia and copy arrays.  Odd
@@ -219,7 +219,10 @@ struct ContactRows {
   int body;
 };
 
-#ifdef EXP_TIMING
+// Phase timing (diagnostic build, -DSIM_PHASE_TIMING): thread 0 of workgroup 7 adds the cycles
+// since the previous mark to slot k of a small buffer in the workspace (phase_timing.py reads it).
+// Each mark costs a few hundred cycles itself, so marks are kept out of the sweep loop.
+#ifdef SIM_PHASE_TIMING
 #define TMARK(k) do { if (tid == 0 && blockIdx.x == 7) { long long _t = clock64(); a.dbg[k] += _t - t_last; t_last = _t; } } while (0)
 #else
 #define TMARK(k) do { } while (0)
@@ -342,7 +345,7 @@ __device__ __forceinline__ int wave_alloc(int n, int* counter) {
 
 template <int EC, int NJ>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
-#ifdef EXP_TIMING
+#ifdef SIM_PHASE_TIMING
   long long t_last = clock64();
 #endif
   extern __shared__ float lds[];
@@ -834,7 +837,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           __syncthreads();
         }
       }
-#ifdef EXP_TIMING
+#ifdef SIM_PHASE_TIMING
       if (tid == 0 && blockIdx.x == 7) { a.dbg[14] += Lcount[5] + Lcount[6]; a.dbg[15] += Lcount[3]; }
 #endif
       // ---- B3: one thread per queued slot turns the selected feature into a contact record
