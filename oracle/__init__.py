@@ -45,6 +45,7 @@ class _Desc(C.Structure):
         ("reset_noise", C.c_double),
         ("gyroscopic", C.c_int32), ("contacts", C.c_int32), ("max_episode_steps", C.c_int32),
         ("height_map", C.c_int32),
+        ("n_collide_pairs", C.c_int32), ("collide_pairs", _i), ("group_size", C.c_int32),
     ]
 
 
@@ -53,6 +54,10 @@ class Contact(C.Structure):
                 ("d", C.c_double), ("n", C.c_double * 3), ("rc", C.c_double * 3), ("w", C.c_double)]
 
 
+PAIR_CONTACT_DTYPE = np.dtype([("env_a", np.int32), ("body_a", np.int32), ("env_b", np.int32),
+                               ("body_b", np.int32), ("s", np.float32), ("t", np.float32),
+                               ("d", np.float64), ("n", np.float64, 3), ("ra", np.float64, 3),
+                               ("rb", np.float64, 3), ("w", np.float64)])
 CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.int32), ("pad", np.int32),
                           ("d", np.float64), ("n", np.float64, 3), ("rc", np.float64, 3),
                           ("w", np.float64)])
@@ -94,6 +99,11 @@ def _load():
     L.oracle_get_task_state.argtypes = [vp, ip, dp]
     L.oracle_set_task_state.argtypes = [vp, ip, dp]
     L.oracle_get_last_push.argtypes = [vp, dp]
+    L.oracle_get_pair_contacts.argtypes = [vp, C.c_void_p, C.c_int32]
+    L.oracle_generate_pair_contacts.argtypes = [vp, C.c_void_p, C.c_int32]
+    fp = C.POINTER(C.c_float)
+    L.oracle_segment_segment_f32.restype = C.c_float
+    L.oracle_segment_segment_f32.argtypes = [fp, fp, fp, fp, fp, fp]
     L.oracle_uniform.restype = C.c_double
     L.oracle_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64]
     _lib = L
@@ -102,6 +112,15 @@ def _load():
 
 def uniform(seed, env, idx):
     return float(_load().oracle_uniform(seed, env, idx))
+
+
+def segment_segment_f32(P0, P1, Q0, Q1):
+    """(d2, s, t) of the oracle's single-precision segment-segment closest points."""
+    a = [np.ascontiguousarray(x, dtype=np.float32) for x in (P0, P1, Q0, Q1)]
+    s, t = C.c_float(), C.c_float()
+    fp = C.POINTER(C.c_float)
+    d2 = _load().oracle_segment_segment_f32(*[x.ctypes.data_as(fp) for x in a], C.byref(s), C.byref(t))
+    return float(d2), float(s.value), float(t.value)
 
 
 def _dp(a):
@@ -136,6 +155,7 @@ class OracleSim:
             feet=i32(np.array(list(r.feet) + [0], dtype=np.int32)),
             heights=np.ascontiguousarray(t.heights, dtype=np.float32),
             env_origins=f64(scene.env_origins),
+            pairs=i32(r.collide_pairs if getattr(p, "self_collide", 0) else np.zeros((0, 2), np.int32)),
         )
         self._keep = keep
         d = _Desc()
@@ -156,6 +176,9 @@ class OracleSim:
         d.max_ang_vel, d.reset_noise = p.max_ang_vel, p.reset_noise
         d.gyroscopic, d.contacts, d.max_episode_steps = p.gyroscopic, p.contacts, p.max_episode_steps
         d.height_map = int(getattr(p, "height_map", 0))
+        d.n_collide_pairs = int(keep["pairs"].shape[0])
+        d.collide_pairs = _ip(keep["pairs"]) if d.n_collide_pairs else None
+        d.group_size = int(getattr(p, "group_size", 1))
         self.N, self.B, self.J, self.D = scene.num_envs, r.n_bodies, r.n_joints, r.n_dofs
         self._h = L.oracle_create(C.byref(d), self.N)
         if not self._h:
@@ -250,6 +273,17 @@ class OracleSim:
         rec = np.zeros((self.N, self.S), CONTACT_DTYPE)
         self._L.oracle_generate_contacts(self._h, 1 if brute else 0, rec.ctypes.data)
         return rec
+
+    def get_pair_contacts(self, cap=4096):
+        """Capsule-capsule contacts of the last substep (all groups, in order)."""
+        rec = np.zeros(cap, PAIR_CONTACT_DTYPE)
+        n = self._L.oracle_get_pair_contacts(self._h, rec.ctypes.data, cap)
+        return rec[:min(n, cap)].copy()
+
+    def generate_pair_contacts(self, cap=4096):
+        rec = np.zeros(cap, PAIR_CONTACT_DTYPE)
+        n = self._L.oracle_generate_pair_contacts(self._h, rec.ctypes.data, cap)
+        return rec[:min(n, cap)].copy()
 
     def start_trace(self, env=0, cap=4096):
         self._trace = np.zeros(cap, TRACE_DTYPE)

@@ -28,6 +28,9 @@
 #define MAXS 96
 #define MAXD 64
 #define MAXOBS (11 + 3 * MAXD + 8 + 15 * 11)
+#define MAXG 16                       /* agents of one interaction group */
+#define MAXP (MAXB * (MAXB - 1) / 2)  /* body pairs of one agent that may collide */
+#define MAXPC 512                     /* capsule-capsule contacts of one group */
 
 typedef struct { double x, y, z; } v3;
 typedef struct { double w, x, y, z; } quat;
@@ -113,6 +116,10 @@ typedef struct {
   v3 g;
   double mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
   int gyro, contacts, max_steps, height_map;
+  /* capsule-capsule collisions (Section 3.1: contacts among bodies; Section 4.1: inter-agent
+   * collisions): body pairs of one agent that may touch, and the number of consecutive agents
+   * that share one interaction group (1: agents do not see each other) */
+  int NP, pair_a[MAXP], pair_b[MAXP], G;
 } model;
 
 typedef struct {
@@ -136,6 +143,8 @@ struct oracle_sim {
   oracle_task task;
   int N, threads;
   env_state* env;
+  oracle_pair_contact* pcon; /* [groups][MAXPC] capsule-capsule contacts of the last substep */
+  int* pcon_n;               /* [groups] */
   int trace_env, trace_cap, trace_n;
   oracle_sweep_trace* trace;
 };
@@ -524,116 +533,255 @@ static void joint_theta(const model* m, const env_state* e, int j, double th[3])
   for (int k = 0; k < 3; ++k) th[k] = vdot(m->jaxes[j][k], phi);
 }
 
-static void substep(const model* m, env_state* e, double h, int iterations, int phases,
+/* closest points of two segments in single precision, one rounding per written operation */
+static float segseg_f32(f3 P0, f3 P1, f3 Q0, f3 Q1, float* s_out, float* t_out) {
+  const float tiny = 1e-12f;
+  f3 d1 = fsub(P1, P0), d2 = fsub(Q1, Q0), r = fsub(P0, Q0);
+  float a = fdot(d1, d1), e = fdot(d2, d2), f = fdot(d2, r), c = fdot(d1, r), b = fdot(d1, d2);
+  float s, t;
+  if (a <= tiny && e <= tiny) { s = 0.0f; t = 0.0f; }
+  else if (a <= tiny) { s = 0.0f; t = clamp01f(f / e); }
+  else if (e <= tiny) { t = 0.0f; s = clamp01f(-c / a); }
+  else {
+    float ae = a * e, bb = b * b;
+    float den = ae - bb, floor_ = 1e-6f * ae;
+    if (den > floor_) { float bf = b * f, ce = c * e; float num = bf - ce; s = clamp01f(num / den); }
+    else s = 0.5f; /* parallel: any point of the overlap is closest; start from the middle */
+    float bs = b * s;
+    float tn = bs + f;
+    t = tn / e;
+    if (t < 0.0f) { t = 0.0f; s = clamp01f(-c / a); }
+    else if (t > 1.0f) { t = 1.0f; float bc = b - c; s = clamp01f(bc / a); }
+  }
+  float ux = d1.x * s, uy = d1.y * s, uz = d1.z * s;
+  float wx = d2.x * t, wy = d2.y * t, wz = d2.z * t;
+  f3 cp = F3(P0.x + ux, P0.y + uy, P0.z + uz), cq = F3(Q0.x + wx, Q0.y + wy, Q0.z + wz);
+  f3 df = fsub(cp, cq);
+  *s_out = s; *t_out = t;
+  return fdot(df, df);
+}
+
+float oracle_segment_segment_f32(const float* P0, const float* P1, const float* Q0, const float* Q1,
+                                 float* s, float* t) {
+  return segseg_f32(F3(P0[0], P0[1], P0[2]), F3(P1[0], P1[1], P1[2]), F3(Q0[0], Q0[1], Q0[2]),
+                    F3(Q1[0], Q1[1], Q1[2]), s, t);
+}
+
+/* One candidate pair of capsules: body ba of agent A against body bb of agent B (the same agent
+ * for self-collision).  The decision is taken in single precision in the frame of agent A; the
+ * geometry of an accepted contact is then built in double precision from the segment parameters
+ * the decision found. */
+static int pair_contact(const model* m, const env_state* A, int ea, int ba, const env_state* Bv, int eb, int bb,
+                        oracle_pair_contact* c) {
+  f3 p0, p1, q0, q1;
+  body_ends_f32(m, A, ba, 0, &p0, &p1);
+  body_ends_f32(m, Bv, bb, 0, &q0, &q1);
+  float ox = (float)Bv->origin.x - (float)A->origin.x, oy = (float)Bv->origin.y - (float)A->origin.y,
+        oz = (float)Bv->origin.z - (float)A->origin.z;
+  q0 = F3(q0.x + ox, q0.y + oy, q0.z + oz);
+  q1 = F3(q1.x + ox, q1.y + oy, q1.z + oz);
+  float s, t;
+  float d2 = segseg_f32(p0, p1, q0, q1, &s, &t);
+  float rr = (float)m->radius[ba] + (float)m->radius[bb];
+  float lim = rr + (float)m->margin;
+  if (!(d2 < lim * lim)) return 0;
+  v3 RA[3], RB[3];
+  qmat(A->q[ba], RA); qmat(Bv->q[bb], RB);
+  v3 ha = vscale(RA[m->axis[ba]], m->half_len[ba]), hb = vscale(RB[m->axis[bb]], m->half_len[bb]);
+  v3 xa = vadd(A->x[ba], A->origin), xb = vadd(Bv->x[bb], Bv->origin);
+  v3 cp = vadd(vsub(xa, ha), vscale(ha, 2.0 * (double)s));
+  v3 cq = vadd(vsub(xb, hb), vscale(hb, 2.0 * (double)t));
+  v3 df = vsub(cp, cq);
+  double dist = vnorm(df);
+  v3 n = dist < 1e-9 ? V(0, 0, 1) : vscale(df, 1.0 / dist);
+  c->env_a = ea; c->body_a = ba; c->env_b = eb; c->body_b = bb; c->s = s; c->t = t;
+  c->d = dist - m->radius[ba] - m->radius[bb];
+  c->n[0] = n.x; c->n[1] = n.y; c->n[2] = n.z;
+  /* one contact point for both bodies, midway between the two surface points, so that the pair
+   * of opposite impulses carries no net torque */
+  v3 sa = vsub(cp, vscale(n, m->radius[ba])), sb = vadd(cq, vscale(n, m->radius[bb]));
+  v3 pm = vscale(vadd(sa, sb), 0.5);
+  v3 ra = vsub(pm, xa), rb = vsub(pm, xb);
+  c->ra[0] = ra.x; c->ra[1] = ra.y; c->ra[2] = ra.z;
+  c->rb[0] = rb.x; c->rb[1] = rb.y; c->rb[2] = rb.z;
+  c->w = block_weight(m, c->d, 1.0);
+  return 1;
+}
+
+/* capsule-capsule contacts of one interaction group from the positions at substep start:
+ * agent by agent its own listed body pairs, then every body pair with each later agent */
+static int generate_pair_contacts(const model* m, env_state* envs, int e0, int G, oracle_pair_contact* out) {
+  int n = 0;
+  if (!m->contacts) return 0;
+  for (int ga = 0; ga < G; ++ga) {
+    for (int p = 0; p < m->NP && n < MAXPC; ++p)
+      n += pair_contact(m, &envs[ga], e0 + ga, m->pair_a[p], &envs[ga], e0 + ga, m->pair_b[p], &out[n]);
+    for (int gb = ga + 1; gb < G; ++gb)
+      for (int ba = 0; ba < m->B; ++ba)
+        for (int bb = 0; bb < m->B && n < MAXPC; ++bb)
+          n += pair_contact(m, &envs[ga], e0 + ga, ba, &envs[gb], e0 + gb, bb, &out[n]);
+  }
+  return n;
+}
+
+/* One substep of an interaction group of G agents (envs[0..G), global indices e0..).  Forces,
+ * terrain contacts and integration are per agent; the solve couples the agents of the group
+ * through the capsule-capsule contacts.  Bodies are numbered g*B + b inside the group. */
+static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_contact* pcon, int* pcon_n,
+                    double h, int iterations, int phases,
                     oracle_sweep_trace* trace, int* trace_n, int trace_cap) {
   const int B = m->B, J = m->J, S = m->S;
-  v3 R[MAXB][3];
+  static _Thread_local v3 R[MAXG * MAXB][3];
   /* 1. contacts from positions at substep start */
-  if (phases & ORACLE_PH_CONTACTS) generate_contacts(m, e, 0, e->con);
-  for (int b = 0; b < B; ++b) qmat(e->q[b], R[b]);
+  if (phases & ORACLE_PH_CONTACTS) {
+    for (int g = 0; g < G; ++g) generate_contacts(m, &envs[g], 0, envs[g].con);
+    *pcon_n = (m->NP > 0 || G > 1) ? generate_pair_contacts(m, envs, e0, G, pcon) : 0;
+  }
+  for (int g = 0; g < G; ++g)
+    for (int b = 0; b < B; ++b) qmat(envs[g].q[b], R[g * B + b]);
 
   /* 2. forces -> velocities: gravity, joint torques (+ on child, - on parent),
    *    explicit gyroscopic term in the body frame */
   if (phases & ORACLE_PH_FORCES) {
-    v3 tau[MAXB];
-    for (int b = 0; b < B; ++b) tau[b] = V(0, 0, 0);
-    for (int j = 0; j < J; ++j) {
-      v3 Ra[3], xa; quat qa;
-      joint_frames(m, e, j, Ra, &xa, &qa);
-      for (int k = 0; k < 3; ++k) {
-        if (m->jmode[j][k] != 1) continue;
-        v3 ak = mrot(Ra, m->jaxes[j][k]);
-        double t = m->jgear[j][k] * e->u[m->jact[j][k]];
-        tau[m->jc[j]] = vadd(tau[m->jc[j]], vscale(ak, t));
-        if (m->jp[j] >= 0) tau[m->jp[j]] = vsub(tau[m->jp[j]], vscale(ak, t));
+    for (int g = 0; g < G; ++g) {
+      env_state* e = &envs[g];
+      v3 tau[MAXB];
+      for (int b = 0; b < B; ++b) tau[b] = V(0, 0, 0);
+      for (int j = 0; j < J; ++j) {
+        v3 Ra[3], xa; quat qa;
+        joint_frames(m, e, j, Ra, &xa, &qa);
+        for (int k = 0; k < 3; ++k) {
+          if (m->jmode[j][k] != 1) continue;
+          v3 ak = mrot(Ra, m->jaxes[j][k]);
+          double t = m->jgear[j][k] * e->u[m->jact[j][k]];
+          tau[m->jc[j]] = vadd(tau[m->jc[j]], vscale(ak, t));
+          if (m->jp[j] >= 0) tau[m->jp[j]] = vsub(tau[m->jp[j]], vscale(ak, t));
+        }
       }
-    }
-    /* external push on the root body (Section 4.1, perturbations): constant over the step */
-    e->v[m->root] = vadd(e->v[m->root], vscale(e->push, h / m->mass[m->root]));
-    for (int b = 0; b < B; ++b) {
-      e->v[b] = vadd(e->v[b], vscale(m->g, h));
-      v3 wb = mrot_t(R[b], e->w[b]), tb = mrot_t(R[b], tau[b]), I = m->inertia[b];
-      v3 Iw = V(I.x * wb.x, I.y * wb.y, I.z * wb.z);
-      v3 rhs = m->gyro ? vsub(tb, vcross(wb, Iw)) : tb;
-      wb = vadd(wb, V(h * rhs.x / I.x, h * rhs.y / I.y, h * rhs.z / I.z));
-      e->w[b] = mrot(R[b], wb);
+      /* external push on the root body (Section 4.1, perturbations): constant over the step */
+      e->v[m->root] = vadd(e->v[m->root], vscale(e->push, h / m->mass[m->root]));
+      for (int b = 0; b < B; ++b) {
+        const v3* Rb = R[g * B + b];
+        e->v[b] = vadd(e->v[b], vscale(m->g, h));
+        v3 wb = mrot_t(Rb, e->w[b]), tb = mrot_t(Rb, tau[b]), I = m->inertia[b];
+        v3 Iw = V(I.x * wb.x, I.y * wb.y, I.z * wb.z);
+        v3 rhs = m->gyro ? vsub(tb, vcross(wb, Iw)) : tb;
+        wb = vadd(wb, V(h * rhs.x / I.x, h * rhs.y / I.y, h * rhs.z / I.z));
+        e->w[b] = mrot(Rb, wb);
+      }
     }
   }
 
   if (phases & ORACLE_PH_SOLVE) {
-    /* 3. row setup.  A *block* is one joint (6 rows: 3 positional, 3 angular)
-     * or one active contact slot (3 rows: normal, two tangents).  Mass
-     * splitting: body i is shared out among its blocks in proportion to block
-     * weights (1 for a joint; for a contact the record's weight, which rises
-     * from 0 at the margin, so a slot that has just become active changes
-     * nothing).  W[i] is the weight sum; inside block c body i acts with
-     * its inverse mass scaled by W[i] / w_c. */
-    static _Thread_local row_t rows[MAXROWS];
+    /* 3. row setup.  A *block* is one joint (6 rows: 3 positional, 3 angular),
+     * one active terrain contact slot or one capsule-capsule contact (3 rows:
+     * normal, two tangents).  Mass splitting: body i is shared out among its
+     * blocks in proportion to block weights (1 for a joint; for a contact the
+     * record's weight, which rises from 0 at the margin, so a contact that has
+     * just become active changes nothing).  W[i] is the weight sum; inside
+     * block c body i acts with its inverse mass scaled by W[i] / w_c. */
+    static _Thread_local row_t* rows = NULL;
+    if (!rows) rows = (row_t*)malloc(sizeof(row_t) * (MAXG * MAXROWS + 3 * MAXPC));
+    static _Thread_local v3 vel[MAXG * MAXB], om[MAXG * MAXB], v0[MAXG * MAXB], w0[MAXG * MAXB], pl[MAXG * MAXB],
+        pa[MAXG * MAXB];
+    static _Thread_local double W[MAXG * MAXB], wslot[MAXG * MAXS];
     int nrows = 0;
-    double W[MAXB], wslot[MAXS];
-    for (int b = 0; b < B; ++b) W[b] = m->body_joint_count[b];
-    for (int s = 0; s < S; ++s) {
-      wslot[s] = 0;
-      if (!e->con[s].active) continue;
-      wslot[s] = e->con[s].w;
-      W[m->slots[s].body] += wslot[s];
+    const int npc = *pcon_n;
+    for (int g = 0; g < G; ++g) {
+      for (int b = 0; b < B; ++b) W[g * B + b] = m->body_joint_count[b];
+      for (int s = 0; s < S; ++s) {
+        wslot[g * S + s] = 0;
+        if (!envs[g].con[s].active) continue;
+        wslot[g * S + s] = envs[g].con[s].w;
+        W[g * B + m->slots[s].body] += envs[g].con[s].w;
+      }
+    }
+    for (int k = 0; k < npc; ++k) {
+      W[(pcon[k].env_a - e0) * B + pcon[k].body_a] += pcon[k].w;
+      W[(pcon[k].env_b - e0) * B + pcon[k].body_b] += pcon[k].w;
     }
     double pos_err_max = 0;
-    for (int j = 0; j < J; ++j) {
-      int a = m->jp[j], b = m->jc[j];
-      v3 Ra[3], xa; quat qa;
-      joint_frames(m, e, j, Ra, &xa, &qa);
-      v3 pa = vadd(xa, mrot(Ra, m->la[j])), pb = vadd(e->x[b], mrot(R[b], m->lb[j]));
-      v3 C = vsub(pb, pa), mid = vscale(vadd(pa, pb), 0.5);
-      v3 ra = vsub(mid, xa), rb = vsub(mid, e->x[b]);
-      double cn = vnorm(C);
-      if (cn > pos_err_max) pos_err_max = cn;
-      double th[3];
-      joint_theta(m, e, j, th);
-      for (int k = 0; k < 6; ++k) {
-        row_t* r = &rows[nrows++];
-        r->a = a; r->b = b; r->slot = -1; r->lambda = 0;
-        r->sca = a >= 0 ? W[a] : 0.0; r->scb = W[b];
-        if (k < 3) {
-          v3 ex = V(k == 0, k == 1, k == 2);
-          r->jla = vscale(ex, -1); r->jaa = vscale(vcross(ra, ex), -1);
-          r->jlb = ex; r->jab = vcross(rb, ex);
-          r->bias = m->beta_j / h * vget(C, k);
-          r->type = 0;
-        } else {
-          int kk = k - 3;
-          v3 ak = mrot(Ra, m->jaxes[j][kk]);
-          r->jla = V(0, 0, 0); r->jlb = V(0, 0, 0);
-          if (m->jmode[j][kk] == 0) {
-            r->jaa = vscale(ak, -1); r->jab = ak;
-            r->bias = m->beta_j / h * th[kk];
+    for (int g = 0; g < G; ++g) {
+      const env_state* e = &envs[g];
+      const int f0 = g * B;
+      for (int j = 0; j < J; ++j) {
+        int a = m->jp[j], b = m->jc[j];
+        v3 Ra[3], xa; quat qa;
+        joint_frames(m, e, j, Ra, &xa, &qa);
+        v3 pa_ = vadd(xa, mrot(Ra, m->la[j])), pb = vadd(e->x[b], mrot(R[f0 + b], m->lb[j]));
+        v3 C = vsub(pb, pa_), mid = vscale(vadd(pa_, pb), 0.5);
+        v3 ra = vsub(mid, xa), rb = vsub(mid, e->x[b]);
+        double cn = vnorm(C);
+        if (cn > pos_err_max) pos_err_max = cn;
+        double th[3];
+        joint_theta(m, e, j, th);
+        for (int k = 0; k < 6; ++k) {
+          row_t* r = &rows[nrows++];
+          r->a = a >= 0 ? f0 + a : -1; r->b = f0 + b; r->slot = -1; r->lambda = 0;
+          r->sca = a >= 0 ? W[f0 + a] : 0.0; r->scb = W[f0 + b];
+          if (k < 3) {
+            v3 ex = V(k == 0, k == 1, k == 2);
+            r->jla = vscale(ex, -1); r->jaa = vscale(vcross(ra, ex), -1);
+            r->jlb = ex; r->jab = vcross(rb, ex);
+            r->bias = m->beta_j / h * vget(C, k);
             r->type = 0;
           } else {
-            double glo = th[kk] - m->jlo[j][kk], ghi = m->jhi[j][kk] - th[kk], g;
-            if (glo < ghi) { g = glo; r->jaa = vscale(ak, -1); r->jab = ak; }
-            else { g = ghi; r->jaa = ak; r->jab = vscale(ak, -1); }
-            r->bias = g >= 0 ? g / h : m->beta_j * g / h;
-            r->type = 1;
+            int kk = k - 3;
+            v3 ak = mrot(Ra, m->jaxes[j][kk]);
+            r->jla = V(0, 0, 0); r->jlb = V(0, 0, 0);
+            if (m->jmode[j][kk] == 0) {
+              r->jaa = vscale(ak, -1); r->jab = ak;
+              r->bias = m->beta_j / h * th[kk];
+              r->type = 0;
+            } else {
+              double glo = th[kk] - m->jlo[j][kk], ghi = m->jhi[j][kk] - th[kk], gg;
+              if (glo < ghi) { gg = glo; r->jaa = vscale(ak, -1); r->jab = ak; }
+              else { gg = ghi; r->jaa = ak; r->jab = vscale(ak, -1); }
+              r->bias = gg >= 0 ? gg / h : m->beta_j * gg / h;
+              r->type = 1;
+            }
           }
         }
       }
+      for (int s = 0; s < S; ++s) {
+        const oracle_contact* c = &e->con[s];
+        if (!c->active) continue;
+        int b = m->slots[s].body;
+        v3 n = V(c->n[0], c->n[1], c->n[2]), rc = V(c->rc[0], c->rc[1], c->rc[2]);
+        /* tangent basis; the branch is decided in single precision like the contact selection */
+        v3 t1 = (fabsf((float)n.x) < 0.57735f) ? vcross(n, V(1, 0, 0)) : vcross(n, V(0, 1, 0));
+        t1 = vscale(t1, 1.0 / vnorm(t1));
+        v3 t2 = vcross(n, t1);
+        v3 dirs[3] = {n, t1, t2};
+        for (int k = 0; k < 3; ++k) {
+          row_t* r = &rows[nrows++];
+          r->a = -1; r->b = f0 + b; r->slot = s; r->lambda = 0;
+          r->sca = 0.0; r->scb = W[f0 + b] / wslot[g * S + s];
+          r->jla = V(0, 0, 0); r->jaa = V(0, 0, 0);
+          r->jlb = dirs[k]; r->jab = vcross(rc, dirs[k]);
+          if (k == 0) {
+            double bias = c->d >= 0 ? c->d / h : m->beta_c * c->d / h;
+            if (c->d < 0 && bias < -m->v_depen) bias = -m->v_depen;
+            r->bias = bias; r->type = 1;
+          } else { r->bias = 0; r->type = 2; }
+        }
+      }
     }
-    for (int s = 0; s < S; ++s) {
-      const oracle_contact* c = &e->con[s];
-      if (!c->active) continue;
-      int b = m->slots[s].body;
-      v3 n = V(c->n[0], c->n[1], c->n[2]), rc = V(c->rc[0], c->rc[1], c->rc[2]);
-      /* tangent basis; the branch is decided in single precision like the contact selection */
+    /* capsule-capsule contacts: the same three rows between two bodies, +J on body A, -J on B */
+    for (int q = 0; q < npc; ++q) {
+      const oracle_pair_contact* c = &pcon[q];
+      int fa = (c->env_a - e0) * B + c->body_a, fb = (c->env_b - e0) * B + c->body_b;
+      v3 n = V(c->n[0], c->n[1], c->n[2]), ra = V(c->ra[0], c->ra[1], c->ra[2]), rb = V(c->rb[0], c->rb[1], c->rb[2]);
       v3 t1 = (fabsf((float)n.x) < 0.57735f) ? vcross(n, V(1, 0, 0)) : vcross(n, V(0, 1, 0));
       t1 = vscale(t1, 1.0 / vnorm(t1));
       v3 t2 = vcross(n, t1);
       v3 dirs[3] = {n, t1, t2};
       for (int k = 0; k < 3; ++k) {
         row_t* r = &rows[nrows++];
-        r->a = -1; r->b = b; r->slot = s; r->lambda = 0;
-        r->sca = 0.0; r->scb = W[b] / wslot[s];
-        r->jla = V(0, 0, 0); r->jaa = V(0, 0, 0);
-        r->jlb = dirs[k]; r->jab = vcross(rc, dirs[k]);
+        r->a = fb; r->b = fa; r->slot = S + q; r->lambda = 0;
+        r->sca = W[fb] / c->w; r->scb = W[fa] / c->w;
+        r->jlb = dirs[k]; r->jab = vcross(ra, dirs[k]);
+        r->jla = vscale(dirs[k], -1); r->jaa = vscale(vcross(rb, dirs[k]), -1);
         if (k == 0) {
           double bias = c->d >= 0 ? c->d / h : m->beta_c * c->d / h;
           if (c->d < 0 && bias < -m->v_depen) bias = -m->v_depen;
@@ -645,20 +793,22 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
       row_t* r = &rows[i];
       double k = 0;
       if (r->a >= 0)
-        k += r->sca * (vdot(r->jla, r->jla) / m->mass[r->a] +
-                         vdot(r->jaa, inv_inertia_apply(R[r->a], m->inertia[r->a], r->jaa)));
+        k += r->sca * (vdot(r->jla, r->jla) / m->mass[r->a % B] +
+                         vdot(r->jaa, inv_inertia_apply(R[r->a], m->inertia[r->a % B], r->jaa)));
       if (r->b >= 0)
-        k += r->scb * (vdot(r->jlb, r->jlb) / m->mass[r->b] +
-                         vdot(r->jab, inv_inertia_apply(R[r->b], m->inertia[r->b], r->jab)));
+        k += r->scb * (vdot(r->jlb, r->jlb) / m->mass[r->b % B] +
+                         vdot(r->jab, inv_inertia_apply(R[r->b], m->inertia[r->b % B], r->jab)));
       r->meff = k > 0 ? 1.0 / k : 0.0;
     }
+    for (int g = 0; g < G; ++g)
+      for (int b = 0; b < B; ++b) { vel[g * B + b] = envs[g].v[b]; om[g * B + b] = envs[g].w[b]; }
 
     /* 4. projected-Jacobi sweeps over blocks: every block starts from the same
      * velocity snapshot; inside a block the rows are relaxed one after another
      * on the block's private copy of its bodies (inverse mass scaled as above). */
+    const int NB = G * B;
     for (int it = 0; it < iterations; ++it) {
-      v3 v0[MAXB], w0[MAXB], pl[MAXB], pa[MAXB];
-      for (int b = 0; b < B; ++b) { v0[b] = e->v[b]; w0[b] = e->w[b]; pl[b] = V(0, 0, 0); pa[b] = V(0, 0, 0); }
+      for (int b = 0; b < NB; ++b) { v0[b] = vel[b]; w0[b] = om[b]; pl[b] = V(0, 0, 0); pa[b] = V(0, 0, 0); }
       double sq = 0, mx = 0, viol = 0, cone = -INFINITY; int nbil = 0;
       /* diagnostics are taken on the snapshot, before any block is relaxed */
       for (int i = 0; i < nrows; ++i) {
@@ -700,13 +850,13 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
             row_t* rr = &rows[i + k + t];
             rr->lambda += dl[t];
             if (a >= 0) {
-              va = vadd(va, vscale(rr->jla, rr->sca * dl[t] / m->mass[a]));
-              wa = vadd(wa, vscale(inv_inertia_apply(R[a], m->inertia[a], rr->jaa), rr->sca * dl[t]));
+              va = vadd(va, vscale(rr->jla, rr->sca * dl[t] / m->mass[a % B]));
+              wa = vadd(wa, vscale(inv_inertia_apply(R[a], m->inertia[a % B], rr->jaa), rr->sca * dl[t]));
               pl[a] = vadd(pl[a], vscale(rr->jla, dl[t]));
               pa[a] = vadd(pa[a], vscale(rr->jaa, dl[t]));
             }
-            vb = vadd(vb, vscale(rr->jlb, rr->scb * dl[t] / m->mass[b]));
-            wb = vadd(wb, vscale(inv_inertia_apply(R[b], m->inertia[b], rr->jab), rr->scb * dl[t]));
+            vb = vadd(vb, vscale(rr->jlb, rr->scb * dl[t] / m->mass[b % B]));
+            wb = vadd(wb, vscale(inv_inertia_apply(R[b], m->inertia[b % B], rr->jab), rr->scb * dl[t]));
             pl[b] = vadd(pl[b], vscale(rr->jlb, dl[t]));
             pa[b] = vadd(pa[b], vscale(rr->jab, dl[t]));
           }
@@ -716,9 +866,9 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
       }
       /* every body receives the plain sum of the impulses of its blocks
        * (accumulated above in ascending block order) */
-      for (int b = 0; b < B; ++b) {
-        e->v[b] = vadd(e->v[b], vscale(pl[b], 1.0 / m->mass[b]));
-        e->w[b] = vadd(e->w[b], inv_inertia_apply(R[b], m->inertia[b], pa[b]));
+      for (int b = 0; b < NB; ++b) {
+        vel[b] = vadd(vel[b], vscale(pl[b], 1.0 / m->mass[b % B]));
+        om[b] = vadd(om[b], inv_inertia_apply(R[b], m->inertia[b % B], pa[b]));
       }
       if (trace && *trace_n < trace_cap) {
         oracle_sweep_trace* t = &trace[(*trace_n)++];
@@ -733,21 +883,26 @@ static void substep(const model* m, env_state* e, double h, int iterations, int 
         t->cone_excess = cone;
       }
     }
+    for (int g = 0; g < G; ++g)
+      for (int b = 0; b < B; ++b) { envs[g].v[b] = vel[g * B + b]; envs[g].w[b] = om[g * B + b]; }
   }
 
   /* 5. damping, angular-velocity cap, position integration */
   if (phases & ORACLE_PH_INTEGRATE) {
-    for (int b = 0; b < B; ++b) {
-      e->v[b] = vscale(e->v[b], 1.0 / (1.0 + h * m->c_lin));
-      e->w[b] = vscale(e->w[b], 1.0 / (1.0 + h * m->c_ang));
-      double wn = vnorm(e->w[b]);
-      if (wn > m->w_max) e->w[b] = vscale(e->w[b], m->w_max / wn);
-      e->x[b] = vadd(e->x[b], vscale(e->v[b], h));
-      quat wq = {0, e->w[b].x, e->w[b].y, e->w[b].z};
-      quat dq = qmul(wq, e->q[b]);
-      quat qn = {e->q[b].w + 0.5 * h * dq.w, e->q[b].x + 0.5 * h * dq.x, e->q[b].y + 0.5 * h * dq.y,
-                 e->q[b].z + 0.5 * h * dq.z};
-      e->q[b] = qnormalize(qn);
+    for (int g = 0; g < G; ++g) {
+      env_state* e = &envs[g];
+      for (int b = 0; b < B; ++b) {
+        e->v[b] = vscale(e->v[b], 1.0 / (1.0 + h * m->c_lin));
+        e->w[b] = vscale(e->w[b], 1.0 / (1.0 + h * m->c_ang));
+        double wn = vnorm(e->w[b]);
+        if (wn > m->w_max) e->w[b] = vscale(e->w[b], m->w_max / wn);
+        e->x[b] = vadd(e->x[b], vscale(e->v[b], h));
+        quat wq = {0, e->w[b].x, e->w[b].y, e->w[b].z};
+        quat dq = qmul(wq, e->q[b]);
+        quat qn = {e->q[b].w + 0.5 * h * dq.w, e->q[b].x + 0.5 * h * dq.x, e->q[b].y + 0.5 * h * dq.y,
+                   e->q[b].z + 0.5 * h * dq.z};
+        e->q[b] = qnormalize(qn);
+      }
     }
   }
 }
@@ -916,8 +1071,16 @@ oracle_sim* oracle_create(const oracle_desc* d, int32_t N) {
   m->v_depen = d->max_depen_vel; m->c_lin = d->lin_damping; m->c_ang = d->ang_damping;
   m->w_max = d->max_ang_vel; m->reset_noise = d->reset_noise;
   m->gyro = d->gyroscopic; m->contacts = d->contacts; m->max_steps = d->max_episode_steps; m->height_map = d->height_map;
+  m->NP = 0;
+  for (int p = 0; p < d->n_collide_pairs && p < MAXP; ++p) {
+    m->pair_a[m->NP] = d->collide_pairs[2 * p]; m->pair_b[m->NP] = d->collide_pairs[2 * p + 1]; m->NP++;
+  }
+  m->G = d->group_size < 1 ? 1 : (d->group_size > MAXG ? MAXG : d->group_size);
   o->N = N; o->threads = 1;
   o->env = (env_state*)calloc((size_t)N, sizeof(env_state));
+  int groups = (N + m->G - 1) / m->G;
+  o->pcon = (oracle_pair_contact*)calloc((size_t)groups * MAXPC, sizeof(oracle_pair_contact));
+  o->pcon_n = (int*)calloc((size_t)groups, sizeof(int));
   for (int e = 0; e < N; ++e) {
     o->env[e].origin = V(d->env_origins[3 * e], d->env_origins[3 * e + 1], d->env_origins[3 * e + 2]);
     o->env[e].target[0] = 1000.0; o->env[e].target[1] = 0.0;
@@ -930,7 +1093,7 @@ oracle_sim* oracle_create(const oracle_desc* d, int32_t N) {
 
 void oracle_destroy(oracle_sim* o) {
   if (!o) return;
-  free(o->m.heights); free(o->env); free(o);
+  free(o->m.heights); free(o->env); free(o->pcon); free(o->pcon_n); free(o);
 }
 int32_t oracle_n_slots(const oracle_sim* o) { return o->m.S; }
 int32_t oracle_obs_dim(const oracle_sim* o) { return 11 + 3 * o->m.D + o->m.F + (o->m.height_map ? HM_ROWS * HM_COLS : 0); }
@@ -1119,29 +1282,64 @@ static void load_actions(oracle_sim* o, const double* actions) {
     }
 }
 
+/* agents [e0, e0 + G) of interaction group gi */
+static int group_span(const oracle_sim* o, int gi, int* e0) {
+  *e0 = gi * o->m.G;
+  return *e0 + o->m.G <= o->N ? o->m.G : o->N - *e0;
+}
+
 void oracle_substep_phases(oracle_sim* o, const double* actions, double h, int32_t iterations, int32_t phases) {
   load_actions(o, actions);
-  for (int e = 0; e < o->N; ++e) {
-    int tr = (e == o->trace_env);
-    substep(&o->m, &o->env[e], h, iterations, phases, tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
+  int groups = (o->N + o->m.G - 1) / o->m.G;
+  for (int gi = 0; gi < groups; ++gi) {
+    int e0, G = group_span(o, gi, &e0);
+    int tr = (o->trace_env >= e0 && o->trace_env < e0 + G);
+    substep(&o->m, &o->env[e0], e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations, phases,
+            tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
   }
 }
 
 void oracle_step(oracle_sim* o, const double* actions, double dt, int32_t substeps, int32_t iterations) {
   load_actions(o, actions);
   double h = dt / substeps;
+  int groups = (o->N + o->m.G - 1) / o->m.G;
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static) num_threads(o->threads)
 #endif
-  for (int e = 0; e < o->N; ++e) {
-    int tr = (e == o->trace_env);
-    if (o->task.enabled) task_before_step(&o->task, &o->env[e], e);
+  for (int gi = 0; gi < groups; ++gi) {
+    int e0, G = group_span(o, gi, &e0);
+    int tr = (o->trace_env >= e0 && o->trace_env < e0 + G);
+    if (o->task.enabled)
+      for (int e = e0; e < e0 + G; ++e) task_before_step(&o->task, &o->env[e], e);
     for (int s = 0; s < substeps; ++s)
-      substep(&o->m, &o->env[e], h, iterations, ORACLE_PH_ALL, tr ? o->trace : NULL, &o->trace_n,
-              o->trace_cap);
-    o->env[e].steps++;
-    if (o->task.enabled) task_after_step(&o->task, &o->m, &o->env[e], e);
+      substep(&o->m, &o->env[e0], e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations,
+              ORACLE_PH_ALL, tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
+    for (int e = e0; e < e0 + G; ++e) {
+      o->env[e].steps++;
+      if (o->task.enabled) task_after_step(&o->task, &o->m, &o->env[e], e);
+    }
   }
+}
+
+int32_t oracle_get_pair_contacts(const oracle_sim* o, oracle_pair_contact* out, int32_t cap) {
+  int n = 0, groups = (o->N + o->m.G - 1) / o->m.G;
+  for (int gi = 0; gi < groups; ++gi)
+    for (int k = 0; k < o->pcon_n[gi]; ++k, ++n)
+      if (n < cap) out[n] = o->pcon[(size_t)gi * MAXPC + k];
+  return n;
+}
+
+int32_t oracle_generate_pair_contacts(oracle_sim* o, oracle_pair_contact* out, int32_t cap) {
+  int n = 0, groups = (o->N + o->m.G - 1) / o->m.G;
+  oracle_pair_contact* tmp = (oracle_pair_contact*)malloc(sizeof(oracle_pair_contact) * MAXPC);
+  for (int gi = 0; gi < groups; ++gi) {
+    int e0, G = group_span(o, gi, &e0);
+    int k = generate_pair_contacts(&o->m, &o->env[e0], e0, G, tmp);
+    for (int i = 0; i < k; ++i, ++n)
+      if (n < cap) out[n] = tmp[i];
+  }
+  free(tmp);
+  return n;
 }
 
 void oracle_get_obs(const oracle_sim* o, double* obs, double* reward, uint8_t* done) {

@@ -50,6 +50,15 @@ typedef struct oracle_desc {
   double lin_damping, ang_damping, max_ang_vel, reset_noise;
   int32_t gyroscopic, contacts, max_episode_steps;
   int32_t height_map;      /* 1: observation carries the 15 x 11 height map (Section 4.1, complex terrain) */
+  /* Capsule-capsule collisions (Section 3.1: contacts among bodies; Section 4.1: inter-agent
+   * collisions).  collide_pairs lists the body pairs of one agent that may touch (bodies joined
+   * by a joint or overlapping in the rest pose are left out by whoever builds the list).
+   * group_size consecutive agents form one interaction group: every body of an agent may touch
+   * every body of another agent of its group; groups never interact.  0 or 1: no inter-agent
+   * contacts. */
+  int32_t n_collide_pairs;
+  const int32_t* collide_pairs; /* [n_collide_pairs][2] */
+  int32_t group_size;
 } oracle_desc;
 
 /* Task logic around the step (Section 4.1).  All off when `enabled` is 0.
@@ -78,6 +87,17 @@ typedef struct oracle_contact {
   double d, n[3], rc[3];
   double w;       /* share of the body this contact block gets in the mass splitting, (0,1] */
 } oracle_contact;
+
+/* One capsule-capsule contact.  Body A = (env_a, body_a), body B = (env_b, body_b); s, t are the
+ * single-precision parameters of the closest points on the two segments (0 at the -l end, 1 at
+ * the +l end); n points from B to A; ra / rb are the contact point (midway between the closest
+ * points of the two surfaces) relative to the respective body centre; d is the surface distance. */
+typedef struct oracle_pair_contact {
+  int32_t env_a, body_a, env_b, body_b;
+  float s, t;
+  double d, n[3], ra[3], rb[3];
+  double w;       /* mass-splitting share on both bodies, as for terrain contacts */
+} oracle_pair_contact;
 
 /* per-sweep diagnostics of one env (used by the invariant pins) */
 typedef struct oracle_sweep_trace {
@@ -132,6 +152,15 @@ void oracle_get_obs(const oracle_sim*, double* obs /*[N][obs_dim]*/, double* rew
 void oracle_get_contacts(const oracle_sim*, oracle_contact* recs);
 /* contact generation alone on the current state; brute != 0 scans every triangle/edge */
 void oracle_generate_contacts(oracle_sim*, int32_t brute, oracle_contact* recs);
+/* capsule-capsule contacts of the last substep, all groups in order; returns their number
+ * (at most cap are written) */
+int32_t oracle_get_pair_contacts(const oracle_sim*, oracle_pair_contact* out, int32_t cap);
+/* the same from the current state, without stepping */
+int32_t oracle_generate_pair_contacts(oracle_sim*, oracle_pair_contact* out, int32_t cap);
+/* single-precision closest points of two segments P0P1, Q0Q1 (fixed operation order): writes the
+ * parameters and returns the squared distance; exposed so it can be pinned */
+float oracle_segment_segment_f32(const float* P0, const float* P1, const float* Q0, const float* Q1,
+                                 float* s, float* t);
 /* trace env `env`: buf receives one record per sweep of subsequent steps, up to cap */
 void oracle_set_trace(oracle_sim*, int32_t env, oracle_sweep_trace* buf, int32_t cap);
 int32_t oracle_trace_count(const oracle_sim*);

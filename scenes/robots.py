@@ -80,6 +80,35 @@ class Robot:
     def obs_dim(self):
         return 11 + 3 * self.n_dofs + len(self.feet)
 
+    @property
+    def collide_pairs(self):
+        """int32 [P, 2]: body pairs that may touch when self-collision is on (collision_pairs)."""
+        return collision_pairs(self)
+
+
+def collision_pairs(robot, clearance=0.03, samples=33):
+    """Body pairs of one robot that may collide with each other: all pairs that no joint connects
+    and whose capsules are more than `clearance` apart in the rest pose (capsules that touch or
+    overlap by construction, such as neighbours along a limb, are filtered out).  The rest-pose
+    gap is taken from `samples` points along each segment.  Returns int32 [P, 2], first < second."""
+    B = robot.n_bodies
+    joined = {(min(int(a), int(b)), max(int(a), int(b))) for a, b in zip(robot.j_parent, robot.j_child)}
+    u = np.linspace(-1.0, 1.0, samples)
+    pts = []
+    for b in range(B):
+        ax = np.zeros(3)
+        ax[int(robot.axis[b])] = robot.half_len[b]
+        pts.append(robot.rest_pos[b][None, :] + u[:, None] * ax[None, :])
+    out = []
+    for a in range(B):
+        for b in range(a + 1, B):
+            if (a, b) in joined:
+                continue
+            d = np.linalg.norm(pts[a][:, None, :] - pts[b][None, :, :], axis=2).min()
+            if d - robot.radius[a] - robot.radius[b] > clearance:
+                out.append((a, b))
+    return np.array(out, np.int32).reshape(-1, 2)
+
 
 class _Builder:
     def __init__(self, name):
@@ -223,6 +252,14 @@ def make_single(radius=0.1, seg_len=0.0, axis=0, pos=(0.0, 0.0, 1.0), mass=1.0):
     """One free body (sphere if seg_len == 0, else a capsule), no joints."""
     bld = _Builder("single")
     bld.body("body", radius, seg_len, axis, pos, mass=mass)
+    return bld.build(root_body=0, feet=(0,), term_height=-1e9, alive_bonus=0.0)
+
+
+def make_loose(bodies):
+    """Free bodies without joints: ``bodies`` is a list of (radius, seg_len, axis, pos, mass)."""
+    bld = _Builder("loose")
+    for k, (r, L, ax, pos, m) in enumerate(bodies):
+        bld.body(f"body{k}", r, L, ax, pos, mass=m)
     return bld.build(root_body=0, feet=(0,), term_height=-1e9, alive_bonus=0.0)
 
 

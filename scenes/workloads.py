@@ -30,6 +30,8 @@ class SimParams:
     reset_noise: float = 0.05
     max_episode_steps: int = 1000
     height_map: int = 0            # 1: append the 15 x 11 terrain height map to the observation
+    self_collide: int = 0          # 1: capsules of one robot collide (pairs: robots.collision_pairs)
+    group_size: int = 1            # agents per interaction group (inter-agent collisions inside it)
 
 
 @dataclass
@@ -83,8 +85,29 @@ def env_field_origins(terrain, num_envs, seed, border=4.0, clear_radius=0.5):
     return o.astype(np.float32).astype(np.float64)
 
 
-def make_scene(robot, terrain, num_envs, seed=0, params=None, name=""):
-    if terrain.kind == PLANE:
+def env_group_origins(terrain, num_envs, group_size, spacing, seed):
+    """Origins for interacting agents: consecutive `group_size` agents stand on a small square
+    grid `spacing` apart (Section 4.1: the initial spacing sets how often agents collide); the
+    groups themselves are placed like non-interacting envs."""
+    n_groups = (num_envs + group_size - 1) // group_size
+    base = env_grid_origins(n_groups, spacing=50.0) if terrain.kind == PLANE else env_field_origins(
+        terrain, n_groups, seed, border=8.0)
+    side = int(np.ceil(np.sqrt(group_size)))
+    o = np.zeros((num_envs, 3), np.float64)
+    for e in range(num_envs):
+        g, k = divmod(e, group_size)
+        o[e, 0] = base[g, 0] + ((k % side) - 0.5 * (side - 1)) * spacing
+        o[e, 1] = base[g, 1] + ((k // side) - 0.5 * (side - 1)) * spacing
+        o[e, 2] = 0.0 if terrain.kind == PLANE else terrain_height_max_near(terrain, o[e, 0], o[e, 1], 0.5)
+    return o.astype(np.float32).astype(np.float64)
+
+
+def make_scene(robot, terrain, num_envs, seed=0, params=None, name="", spacing=None):
+    """`spacing` (with params.group_size > 1) places the agents of a group that far apart."""
+    params = params or SimParams()
+    if params.group_size > 1 and spacing is not None:
+        origins = env_group_origins(terrain, num_envs, params.group_size, spacing, seed)
+    elif terrain.kind == PLANE:
         origins = env_grid_origins(num_envs)
     else:
         origins = env_field_origins(terrain, num_envs, seed)

@@ -1,0 +1,202 @@
+"""Pins for the oracle's capsule-capsule contacts (Section 3.1: contacts among bodies as
+unilateral constraints with Coulomb friction, restitution 0; Section 4.1: inter-agent
+collisions): closest points against brute force and closed forms, perfectly inelastic
+collisions, momentum conservation of an isolated pair, self- against inter-agent path,
+a resting stack."""
+import numpy as np
+import pytest
+
+import oracle
+import scenes
+from helpers import free_params, single_scene, linear_momentum, angular_momentum
+
+
+def _brute_d2(P0, P1, Q0, Q1, n=401):
+    u = np.linspace(0.0, 1.0, n)
+    a = P0[None, :] + u[:, None] * (P1 - P0)[None, :]
+    b = Q0[None, :] + u[:, None] * (Q1 - Q0)[None, :]
+    return ((a[:, None, :] - b[None, :, :]) ** 2).sum(2).min()
+
+
+def test_segment_segment_against_dense_sampling():
+    rng = np.random.default_rng(5)
+    for k in range(300):
+        P0, P1, Q0, Q1 = (rng.uniform(-1, 1, 3).astype(np.float32).astype(np.float64) for _ in range(4))
+        if k % 7 == 0:
+            Q1 = Q0 + (P1 - P0) * rng.uniform(0.3, 2.0)      # parallel
+        if k % 11 == 0:
+            P1 = P0.copy()                                   # a sphere
+        d2, s, t = oracle.segment_segment_f32(P0, P1, Q0, Q1)
+        assert 0.0 <= s <= 1.0 and 0.0 <= t <= 1.0
+        # the reported parameters give the reported distance ...
+        cp, cq = P0 + s * (P1 - P0), Q0 + t * (Q1 - Q0)
+        assert abs(((cp - cq) ** 2).sum() - d2) < 1e-5
+        # ... and no sampled pair of points is closer (sampling error of a 401 x 401 grid)
+        ref = _brute_d2(P0, P1, Q0, Q1)
+        assert d2 <= ref + 1e-5
+        assert d2 >= ref - 0.02
+
+
+def test_segment_segment_closed_forms():
+    # crossing segments touch
+    d2, s, t = oracle.segment_segment_f32([-1, 0, 0], [1, 0, 0], [0, -1, 0], [0, 1, 0])
+    assert d2 == 0.0 and s == 0.5 and t == 0.5
+    # skew segments: distance along the common normal
+    d2, s, t = oracle.segment_segment_f32([-1, 0, 0], [1, 0, 0], [0.5, -1, 0.25], [0.5, 3, 0.25])
+    assert d2 == pytest.approx(0.0625, rel=1e-6) and s == pytest.approx(0.75) and t == pytest.approx(0.25)
+    # end point against end point
+    d2, s, t = oracle.segment_segment_f32([0, 0, 0], [1, 0, 0], [2, 1, 0], [3, 1, 0])
+    assert d2 == pytest.approx(2.0) and s == 1.0 and t == 0.0
+    # point against segment interior (textbook point-line distance)
+    d2, s, t = oracle.segment_segment_f32([0.25, 2, 0], [0.25, 2, 0], [0, 0, 0], [1, 0, 0])
+    assert d2 == pytest.approx(4.0) and t == pytest.approx(0.25)
+    # swapping the segments swaps the parameters
+    a = oracle.segment_segment_f32([0, 0, 0], [1, 0.2, 0], [0.3, 1, 0.1], [0.9, 0.4, -0.3])
+    b = oracle.segment_segment_f32([0.3, 1, 0.1], [0.9, 0.4, -0.3], [0, 0, 0], [1, 0.2, 0])
+    assert a[0] == pytest.approx(b[0], rel=1e-5) and a[1] == pytest.approx(b[2], abs=1e-5)
+
+
+def _two_spheres(m0, m1, gap=0.05, r=0.1, group=False):
+    """Two free spheres on the x axis far above the ground, no gravity."""
+    p = free_params(gravity=(0.0, 0.0, 0.0), self_collide=1)
+    if not group:
+        rob = scenes.make_loose([(r, 0.0, 0, (0.0, 0.0, 5.0), m0), (r, 0.0, 0, (2 * r + gap, 0.0, 5.0), m1)])
+        return rob, single_scene(rob, params=p)
+    assert m0 == m1
+    p.self_collide, p.group_size = 0, 2
+    rob = scenes.make_single(radius=r, pos=(0.0, 0.0, 5.0), mass=m0)
+    sc = single_scene(rob, params=p, num_envs=2)
+    sc.env_origins[1, 0] = 2 * r + gap
+    return rob, sc
+
+
+@pytest.mark.parametrize("m0,m1", [(1.0, 1.0), (1.0, 3.0), (5.0, 0.5)])
+def test_head_on_collision_is_perfectly_inelastic(m0, m1):
+    """Restitution 0: after the impact both spheres move with the centre-of-mass velocity and the
+    surfaces touch; before it (gap larger than what one substep closes) nothing changes."""
+    rob, sc = _two_spheres(m0, m1)
+    o = oracle.OracleSim(sc)
+    st = scenes.rest_state(rob)
+    st[0, 0, 7], st[0, 1, 7] = 1.0, -0.5
+    o.set_state(st)
+    vcm = (m0 * 1.0 - m1 * 0.5) / (m0 + m1)
+    h = 1.0 / 240.0
+    o.substep_phases(None, h, 4)               # gap 0.05 > 1.5 * h: speculative row inactive
+    s = o.get_state()
+    assert s[0, 0, 7] == pytest.approx(1.0, abs=1e-12) and s[0, 1, 7] == pytest.approx(-0.5, abs=1e-12)
+    for _ in range(40):
+        o.substep_phases(None, h, 4)
+    s = o.get_state()
+    assert s[0, 0, 7] == pytest.approx(vcm, abs=1e-9) and s[0, 1, 7] == pytest.approx(vcm, abs=1e-9)
+    assert s[0, 1, 0] - s[0, 0, 0] - 0.2 == pytest.approx(0.0, abs=1e-9)
+    assert np.abs(s[0, :, 8:13]).max() < 1e-12
+    pc = o.get_pair_contacts()
+    assert len(pc) == 1 and (pc[0]["body_a"], pc[0]["body_b"]) == (0, 1)
+    assert np.allclose(pc[0]["n"], [-1.0, 0.0, 0.0]) and pc[0]["d"] == pytest.approx(0.0, abs=1e-9)
+
+
+def test_isolated_pair_conserves_linear_and_angular_momentum():
+    """Off-centre capsule hits with friction: the contact impulses are internal forces."""
+    rng = np.random.default_rng(11)
+    p = free_params(gravity=(0.0, 0.0, 0.0), self_collide=1, gyroscopic=0)
+    hits = 0
+    for trial in range(40):
+        rob = scenes.make_loose([(0.08, 0.5, 0, (0.0, 0.0, 5.0), 1.3), (0.05, 0.4, 1, (0.1, 0.05, 6.0), 0.7)])
+        sc = single_scene(rob, params=p)
+        st = scenes.rest_state(rob)
+        st[0, 1, 2] = 5.14
+        q = rng.normal(size=(2, 4)) * 0.3 + np.array([1.0, 0, 0, 0])
+        st[0, :, 3:7] = q / np.linalg.norm(q, axis=1, keepdims=True)
+        st[0, :, 7:13] = rng.normal(size=(2, 6)) * np.array([0.5, 0.5, 0.5, 2, 2, 2])
+        st[0, 1, 9] -= 4.0
+        o = oracle.OracleSim(sc)
+        o.set_state(st)
+        P0, L0 = linear_momentum(rob, st[0]), angular_momentum(rob, st[0])
+        o.substep_phases(None, 1.0 / 240.0, 30, oracle.PH_CONTACTS | oracle.PH_FORCES | oracle.PH_SOLVE)
+        s1 = o.get_state()
+        pc = o.get_pair_contacts()
+        if len(pc) == 0 or np.abs(s1[0, :, 7:13] - st[0, :, 7:13]).max() < 1e-2:
+            continue                                    # no record, or a speculative row that stayed idle
+        hits += 1
+        assert np.allclose(linear_momentum(rob, s1[0]), P0, atol=1e-12)
+        assert np.allclose(angular_momentum(rob, s1[0]), L0, atol=1e-12)
+        # the relative normal velocity at the contact satisfies the speculative bound
+        c = pc[0]
+        va = s1[0, 0, 7:10] + np.cross(s1[0, 0, 10:13], c["ra"])
+        vb = s1[0, 1, 7:10] + np.cross(s1[0, 1, 10:13], c["rb"])
+        bound = -c["d"] * 240.0 if c["d"] >= 0 else 0.0
+        assert c["n"] @ (va - vb) >= bound - 1e-6
+    assert hits >= 10
+
+
+def test_contact_geometry_of_two_capsules():
+    """Crossed capsules one above the other: closed-form distance, normal and contact points
+    (to the single precision of the segment parameters)."""
+    rob = scenes.make_loose([(0.08, 0.6, 0, (0.0, 0.0, 5.0), 1.0), (0.05, 0.4, 1, (0.1, -0.05, 6.0), 1.0)])
+    sc = single_scene(rob, params=free_params(gravity=(0.0, 0.0, 0.0), self_collide=1))
+    o = oracle.OracleSim(sc)
+    st = scenes.rest_state(rob)
+    st[0, 1, 2] = 5.14
+    o.set_state(st)
+    pc = o.generate_pair_contacts()
+    assert len(pc) == 1
+    c = pc[0]
+    assert c["d"] == pytest.approx(0.14 - 0.13, abs=2e-6)
+    assert np.allclose(c["n"], [0, 0, -1.0], atol=2e-6)          # from B (above) to A
+    # one contact point, midway between the top of A and the bottom of B at the crossing
+    assert np.allclose(c["ra"], [0.1, 0.0, 0.085], atol=2e-6)
+    assert np.allclose(c["rb"], [0.0, 0.05, -0.055], atol=2e-6)
+    assert c["s"] == pytest.approx((0.1 + 0.3) / 0.6, abs=1e-6) and c["t"] == pytest.approx(0.25 / 0.4 * 1.0, abs=1e-6)
+    # outside the margin: no record
+    st[0, 1, 2] += 0.011
+    o.set_state(st)
+    assert len(o.generate_pair_contacts()) == 0
+
+
+def test_inter_agent_contact_equals_self_contact_of_the_merged_robot():
+    """Two one-sphere agents of one interaction group behave exactly like one robot made of the
+    same two free spheres with self-collision on."""
+    rob2, sc2 = _two_spheres(1.0, 1.0)
+    rob1, scg = _two_spheres(1.0, 1.0, group=True)
+    a, b = oracle.OracleSim(sc2), oracle.OracleSim(scg)
+    st = scenes.rest_state(rob2)
+    st[0, 0, 7:10], st[0, 1, 7:10] = (1.0, 0.2, 0.0), (-0.5, 0.0, 0.1)
+    a.set_state(st)
+    sg = np.zeros((2, 1, 13))
+    sg[:, 0] = st[0]
+    sg[1, 0, 0] -= scg.env_origins[1, 0]
+    b.set_state(sg)
+    for _ in range(30):
+        a.substep_phases(None, 1.0 / 240.0, 6)
+        b.substep_phases(None, 1.0 / 240.0, 6)
+    sa, sb = a.get_state(), b.get_state()
+    sb[1, 0, 0] += scg.env_origins[1, 0]
+    assert np.allclose(sa[0], sb[:, 0], atol=1e-12)
+    assert len(b.get_pair_contacts()) == 1
+    # agents of different groups never see each other
+    scg.params.group_size = 1
+    c = oracle.OracleSim(scg)
+    c.set_state(sg)
+    for _ in range(30):
+        c.substep_phases(None, 1.0 / 240.0, 6)
+    assert len(c.get_pair_contacts()) == 0
+    assert c.get_state()[0, 0, 7] == pytest.approx(1.0)
+
+
+def test_sphere_resting_on_a_grounded_sphere_stays_put():
+    """Stack under gravity: ground contact and sphere-sphere contact share the lower body; after
+    settling both spheres are at rest with touching surfaces."""
+    r = 0.1
+    rob = scenes.make_loose([(r, 0.0, 0, (0.0, 0.0, r), 2.0), (r, 0.0, 0, (0.0, 0.0, 1.0), 1.0)])
+    sc = single_scene(rob, params=free_params(self_collide=1))
+    o = oracle.OracleSim(sc)
+    st = scenes.rest_state(rob)
+    st[0, 1, 2] = 3 * r + 0.002
+    o.set_state(st)
+    for _ in range(240):
+        o.step(None, 1.0 / 60.0, 4, 20)
+    s = o.get_state()
+    assert np.abs(s[0, :, 7:10]).max() < 2e-3
+    assert s[0, 0, 2] == pytest.approx(r, abs=2e-3)
+    assert s[0, 1, 2] - s[0, 0, 2] == pytest.approx(2 * r, abs=2e-3)
+    assert np.abs(s[0, :, 0:2]).max() < 1e-6
