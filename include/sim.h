@@ -99,6 +99,19 @@ typedef struct sim_desc {
   int32_t contacts;               /* 0 disables contact generation */
   int32_t height_map;             /* 1 appends the 15 x 11 terrain height map that follows the centre of mass
                                      (Section 4.1, complex-terrain task) to the observation: 165 more floats */
+  /* Capsule-capsule collisions (Section 3.1: contacts among bodies are detected speculatively;
+   * Section 4.1: inter-agent collisions of the flagrun tasks).  collide_pairs: body pairs of one
+   * agent that may touch each other (host, [n_collide_pairs][2], first < second, at most
+   * SIM_MAX_BODIES * (SIM_MAX_BODIES - 1) / 2; leave out bodies that a joint connects or that
+   * overlap by construction); 0 pairs = no self-collision.  group_size consecutive agents form
+   * one interaction group: every body of an agent may touch every body of the other agents of
+   * its group, groups never interact (their env_origins say where the agents stand); 0 or 1 =
+   * agents do not see each other, at most SIM_MAX_GROUP.  A group is simulated by one workgroup,
+   * which holds at most SIM_PAIR_CAP capsule-capsule contacts per substep (see
+   * sim_get_pair_contacts). */
+  int32_t n_collide_pairs;
+  const int32_t* collide_pairs;
+  int32_t group_size;
 } sim_desc_t;
 
 /* Task logic around the step (Section 4.1 of the paper).  The numbers in brackets are the
@@ -140,6 +153,16 @@ typedef struct sim_contact_rec {
                   fades towards the segment ends.  0 when inactive. */
   int32_t pad;
 } sim_contact_rec_t;
+
+/* One capsule-capsule contact of the last substep.  Body A = (env_a, body_a), B = (env_b, body_b);
+ * s, t: parameters of the closest points on the two segments (0 at the -half_len end, 1 at the
+ * other); d: gap between the surfaces; w: share in the mass splitting, as for terrain contacts. */
+typedef struct sim_pair_contact_rec {
+  int32_t env_a, body_a, env_b, body_b;
+  float s, t, d, w;
+} sim_pair_contact_rec_t;
+#define SIM_MAX_GROUP 16
+#define SIM_PAIR_CAP 96
 
 /* Bytes of device workspace sim_create needs for this description (256-byte aligned base). */
 int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t* out_bytes);
@@ -206,6 +229,14 @@ int sim_record_contacts(sim_t* sim, int enable);
 int sim_get_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
 /* Contact generation alone on the current state, straight into recs_dev. */
 int sim_generate_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
+/* Capsule-capsule contacts of the last substep of the last sim_step (recording enabled): up to
+ * `cap` records into recs_dev, workgroup by workgroup, each workgroup's in a fixed order; the total
+ * number goes to count_dev[0] and count_dev[1] receives the number of contacts that were dropped
+ * since sim_create because a workgroup found more than SIM_PAIR_CAP in one substep (results are
+ * not to be trusted once this is non-zero).  SIM_ERR_ARG if the description had neither collide
+ * pairs nor groups. */
+int sim_get_pair_contacts(sim_t* sim, sim_pair_contact_rec_t* recs_dev, int32_t cap, int32_t* count_dev /*[2]*/,
+                          void* stream);
 /* Synchronises `stream` and scans the state: SIM_ERR_NONFINITE if any value is NaN/Inf. */
 int sim_check(sim_t* sim, void* stream);
 

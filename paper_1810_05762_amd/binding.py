@@ -43,6 +43,7 @@ class SimDesc(C.Structure):
         ("lin_damping", C.c_double), ("ang_damping", C.c_double), ("max_ang_vel", C.c_double),
         ("reset_noise", C.c_double), ("gyroscopic", C.c_int32), ("contacts", C.c_int32),
         ("height_map", C.c_int32),
+        ("n_collide_pairs", C.c_int32), ("collide_pairs", C.POINTER(C.c_int32)), ("group_size", C.c_int32),
     ]
 
 
@@ -53,6 +54,9 @@ class TaskDesc(C.Structure):
                 ("push_min_newton", C.c_double), ("push_max_newton", C.c_double), ("seed", C.c_uint64)]
 
 
+PAIR_CONTACT_DTYPE = np.dtype([("env_a", np.int32), ("body_a", np.int32), ("env_b", np.int32),
+                               ("body_b", np.int32), ("s", np.float32), ("t", np.float32),
+                               ("d", np.float32), ("w", np.float32)])
 CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.int32),
                           ("d", np.float32), ("n", np.float32, 3), ("rc", np.float32, 3),
                           ("w", np.float32), ("pad", np.int32)])
@@ -77,6 +81,7 @@ _SYMBOLS = {
     "sim_record_contacts": [C.c_void_p, C.c_int],
     "sim_get_contacts": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_generate_contacts": [C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_get_pair_contacts": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
     "sim_check": [C.c_void_p, C.c_void_p],
     "sim_launch_info": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_size_t)],
     "sim_set_envs_per_block": [C.c_void_p, C.c_int],
@@ -154,7 +159,11 @@ def make_desc(scene):
     d.max_ang_vel, d.reset_noise = p.max_ang_vel, p.reset_noise
     d.gyroscopic, d.contacts = p.gyroscopic, p.contacts
     d.height_map = int(getattr(p, "height_map", 0))
-    return d, [bodies, joints, heights, origins]
+    pairs = np.ascontiguousarray(r.collide_pairs if getattr(p, "self_collide", 0) else np.zeros((0, 2)), dtype=np.int32)
+    d.n_collide_pairs = int(pairs.shape[0])
+    d.collide_pairs = pairs.ctypes.data_as(C.POINTER(C.c_int32)) if d.n_collide_pairs else None
+    d.group_size = int(getattr(p, "group_size", 1))
+    return d, [bodies, joints, heights, origins, pairs]
 
 
 # ---- plain functions, one per C entry point (pointers are ints / torch data_ptr) ----
@@ -236,6 +245,10 @@ def sim_get_contacts(h, recs_ptr, stream):
 
 def sim_generate_contacts(h, recs_ptr, stream):
     return _chk(lib().sim_generate_contacts(h, recs_ptr, stream))
+
+
+def sim_get_pair_contacts(h, recs_ptr, cap, count_ptr, stream):
+    return _chk(lib().sim_get_pair_contacts(h, recs_ptr, int(cap), count_ptr, stream))
 
 
 def sim_check(h, stream):
@@ -370,6 +383,14 @@ class Sim:
 
     def generate_contacts(self):
         return self._recs(sim_generate_contacts)
+
+    def get_pair_contacts(self, cap=4096):
+        """(records, dropped): capsule-capsule contacts of the last substep of the last step."""
+        buf = self.torch.zeros(cap * PAIR_CONTACT_DTYPE.itemsize, dtype=self.torch.uint8, device=self.device)
+        cnt = self.torch.zeros(2, dtype=self.torch.int32, device=self.device)
+        sim_get_pair_contacts(self.h, buf.data_ptr(), cap, cnt.data_ptr(), self._stream())
+        n, dropped = (int(v) for v in cnt.cpu().numpy())
+        return buf.cpu().numpy().view(PAIR_CONTACT_DTYPE)[:min(n, cap)].copy(), dropped
 
     def check(self):
         sim_check(self.h, self._stream())

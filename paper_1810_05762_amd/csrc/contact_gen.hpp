@@ -195,6 +195,51 @@ __device__ __forceinline__ void seg_edge_st(f3 P0, f3 P1, f3 Q0, f3 Q1, float& s
   }
 }
 
+// Closest points of two capsule segments P0->P1 and Q0->Q1 (either may have zero length):
+// writes the parameters and returns the squared distance.  Decides which capsule pairs are
+// in contact (Section 3.1: contacts among bodies; Section 4.1: inter-agent collisions), so
+// it follows the fixed operation order of this file.  Parallel segments start from the
+// middle of the first one.
+__device__ __forceinline__ float segment_segment(f3 P0, f3 P1, f3 Q0, f3 Q1, float& s, float& t) {
+  const float tiny = 1e-12f;
+  f3 d1 = sub3(P1, P0), d2 = sub3(Q1, Q0), r = sub3(P0, Q0);
+  float a = dot3(d1, d1), e = dot3(d2, d2), f = dot3(d2, r), c = dot3(d1, r), b = dot3(d1, d2);
+  if (a <= tiny && e <= tiny) { s = 0.0f; t = 0.0f; }
+  else if (a <= tiny) { s = 0.0f; t = clamp01(f / e); }
+  else if (e <= tiny) { t = 0.0f; s = clamp01(-c / a); }
+  else {
+    float ae = a * e, bb = b * b;
+    float den = ae - bb, floor_ = 1e-6f * ae;
+    if (den > floor_) { float bf = b * f, ce = c * e; float num = bf - ce; s = clamp01(num / den); }
+    else s = 0.5f;
+    float bs = b * s;
+    float tn = bs + f;
+    t = tn / e;
+    if (t < 0.0f) { t = 0.0f; s = clamp01(-c / a); }
+    else if (t > 1.0f) { t = 1.0f; float bc = b - c; s = clamp01(bc / a); }
+  }
+  float ux = d1.x * s, uy = d1.y * s, uz = d1.z * s;
+  float wx = d2.x * t, wy = d2.y * t, wz = d2.z * t;
+  f3 cp = f3{P0.x + ux, P0.y + uy, P0.z + uz}, cq = f3{Q0.x + wx, Q0.y + wy, Q0.z + wz};
+  f3 df = sub3(cp, cq);
+  return dot3(df, df);
+}
+
+// Are two capsules within the contact margin?  Segment end points env-local, the second
+// capsule's shifted by `off` (its env origin minus the first one's).  Returns the segment
+// parameters of the closest points and the gap between the surfaces.
+__device__ __forceinline__ bool pair_in_contact(f3 p0, f3 p1, f3 q0, f3 q1, const float off[3], float rad_a,
+                                                float rad_b, float margin, float& s, float& t, float& gap) {
+  q0 = f3{q0.x + off[0], q0.y + off[1], q0.z + off[2]};
+  q1 = f3{q1.x + off[0], q1.y + off[1], q1.z + off[2]};
+  const float d2 = segment_segment(p0, p1, q0, q1, s, t);
+  const float rr = rad_a + rad_b;
+  const float lim = rr + margin;
+  if (!(d2 < lim * lim)) return false;
+  gap = (sqrtf(d2) - rad_a) - rad_b;
+  return true;
+}
+
 // End points of a body's segment: env-local (p0,p1) from the state, in the same
 // operation order the selection is specified in.
 __device__ __forceinline__ void body_ends(const float x[3], const float q[4], float half_len, int axis,

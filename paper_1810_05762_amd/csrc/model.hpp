@@ -15,6 +15,11 @@ constexpr int kMaxSlots = 3 * kMaxBodies;
 constexpr int kMaxBodyJoints = 8;  // joint sides touching one body
 constexpr int kHmRows = 15, kHmCols = 11;  // height-map observation
 constexpr int kCoarse = 8;         // cells per side of a coarse max-height block
+constexpr int kMaxPairs = kMaxBodies * (kMaxBodies - 1) / 2;  // body pairs of one agent
+constexpr int kMaxGroup = 16;      // agents of one interaction group
+constexpr int kMaxAgentPairs = kMaxGroup * (kMaxGroup - 1) / 2;
+constexpr int kPairCap = 96;       // capsule-capsule contacts one workgroup holds per substep
+constexpr int kPairWords = 6;      // queue entry: key, body refs, s, t, weight, distance
 
 struct BodyTab {
   float radius, half_len, inv_mass;
@@ -54,6 +59,12 @@ struct Model {
   int32_t height_map;
   float hm_fwd[kHmRows], hm_lat[kHmCols];
   float body_mass_frac[kMaxBodies];  // mass of each body over the total (centre of mass)
+  // Capsule-capsule collisions (Section 3.1: contacts among bodies; Section 4.1: inter-agent
+  // collisions): body pairs of one agent that may touch, and the interaction groups (group
+  // consecutive agents see each other; agent_pair_*[k] are the members of the k-th pair of a group).
+  int32_t n_pairs, group, n_agent_pairs;
+  uint8_t pair_a[kMaxPairs], pair_b[kMaxPairs];
+  uint8_t agent_pair_a[kMaxAgentPairs], agent_pair_b[kMaxAgentPairs];
   BodyTab bodies[kMaxBodies];
   JointTab joints[kMaxJoints];
   SlotTab slots[kMaxSlots];

@@ -21,6 +21,7 @@ static_assert(SIM_MAX_BODIES == kMaxBodies && SIM_MAX_JOINTS == kMaxJoints && SI
                   SIM_MAX_FEET == kMaxFeet,
               "public limits and table sizes must agree");
 static_assert(sizeof(sim_contact_rec_t) == kRecWords * 4, "contact record is 12 words");
+static_assert(sizeof(sim_pair_contact_rec_t) == 32 && SIM_PAIR_CAP == kPairCap && SIM_MAX_GROUP == kMaxGroup, "pair contact records");
 
 // ------------------------------------------------------------------ errors
 static thread_local char g_err[512] = "";
@@ -41,11 +42,11 @@ extern "C" const char* sim_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ layout
 struct Layout {
-  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, reset_flag, push, flag, total;
+  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, reset_flag, push, flag, pair_recs, pair_count, total;
 };
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, size_t n_coarse) {
+static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, size_t n_coarse, int pairs) {
   Layout L;
   size_t o = 0;
   L.model = o; o = align_up(o + sizeof(Model));
@@ -63,6 +64,9 @@ static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, si
   L.reset_flag = o; o = align_up(o + (size_t)N);
   L.push = o; o = align_up(o + (size_t)N * 3 * sizeof(float));
   L.flag = o; o = align_up(o + 256);
+  // capsule-capsule contact records: one workgroup may hold as few as one env
+  L.pair_recs = o; o = align_up(o + (pairs ? (size_t)N * kPairCap * sizeof(sim_pair_contact_rec_t) : 0));
+  L.pair_count = o; o = align_up(o + (pairs ? (size_t)N * sizeof(int32_t) : 0));
   L.total = o;
   return L;
 }
@@ -74,6 +78,7 @@ struct sim {
   int N, obs_dim, E;
   int record;
   int recs_valid;
+  int pair_grid;   // workgroups of the launch that wrote the capsule-capsule records
   TaskParams task;
 };
 
@@ -216,12 +221,41 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
     double sft = 0.15 * (std::pow(1.3, (double)ak) - 1.0) / 0.3;
     m->hm_lat[j] = (float)(k < 0 ? -sft : sft);
   }
+  // capsule-capsule collisions
+  if (d->n_collide_pairs < 0 || d->n_collide_pairs > kMaxPairs) return fail(SIM_ERR_ARG, "n_collide_pairs %d outside 0..%d", d->n_collide_pairs, kMaxPairs);
+  if (d->n_collide_pairs > 0 && !d->collide_pairs) return fail(SIM_ERR_ARG, "collide_pairs is NULL");
+  m->n_pairs = d->n_collide_pairs;
+  for (int p = 0; p < m->n_pairs; ++p) {
+    const int a = d->collide_pairs[2 * p], b = d->collide_pairs[2 * p + 1];
+    if (a < 0 || b <= a || b >= m->B) return fail(SIM_ERR_ARG, "collide pair %d: need 0 <= first < second < n_bodies", p);
+    m->pair_a[p] = (uint8_t)a; m->pair_b[p] = (uint8_t)b;
+  }
+  if (d->group_size < 0 || d->group_size > kMaxGroup) return fail(SIM_ERR_ARG, "group_size %d outside 0..%d", d->group_size, kMaxGroup);
+  m->group = d->group_size > 1 ? d->group_size : 1;
+  m->n_agent_pairs = 0;
+  for (int a = 0; a < m->group; ++a)
+    for (int b = a + 1; b < m->group; ++b) {
+      m->agent_pair_a[m->n_agent_pairs] = (uint8_t)a; m->agent_pair_b[m->n_agent_pairs] = (uint8_t)b;
+      ++m->n_agent_pairs;
+    }
+  if (m->group > 1) {
+    // the whole group has to fit one workgroup
+    if (m->group * m->B > kThreads || (m->J > 0 && 2 * m->group * m->J > kThreads - 64))
+      return fail(SIM_ERR_ARG, "group_size %d does not fit one workgroup for this robot", m->group);
+  }
   {
     double mt = 0.0;
     for (int b = 0; b < m->B; ++b) mt += d->bodies[b].mass;
     for (int b = 0; b < m->B; ++b) m->body_mass_frac[b] = (float)(d->bodies[b].mass / mt);
   }
   return SIM_OK;
+}
+
+// does this model generate capsule-capsule contacts, and with which group size (0: no)
+static int pairs_of(const Model& m) { return (m.n_pairs > 0 || m.group > 1) ? (m.group > 1 ? m.group : 1) : 0; }
+static LdsPlan plan_for(const Model& m, int E) {
+  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
+  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m));
 }
 
 static int default_envs_per_block(const Model& m, int N) {
@@ -232,9 +266,12 @@ static int default_envs_per_block(const Model& m, int N) {
   int want = N / 256;  // keep at least one workgroup per compute unit when N allows
   if (want < 1) want = 1;
   int E = want < lim ? want : lim;
+  // a workgroup holds whole interaction groups
+  const int G = m.group > 1 ? m.group : 1;
+  if (E < G) E = G;
+  E -= E % G;
   // and the workgroup's LDS arrays have to fit
-  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
-  while (E > 1 && (size_t)make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch).total * sizeof(float) > 160 * 1024) --E;
+  while (E > G && (size_t)plan_for(m, E).total * sizeof(float) > 160 * 1024) E -= G;
   return E;
 }
 
@@ -428,13 +465,16 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.reset_flag = reinterpret_cast<uint8_t*>(s->ws + s->lay.reset_flag);
   a.push = reinterpret_cast<float*>(s->ws + s->lay.push);
   a.repack = repack;
+  const int pairs = pairs_of(m);
+  a.pair_recs = (pairs && s->record && substeps > 0) ? reinterpret_cast<int32_t*>(s->ws + s->lay.pair_recs) : nullptr;
+  a.pair_count = reinterpret_cast<int32_t*>(s->ws + s->lay.pair_count);
+  a.pair_dropped = reinterpret_cast<int32_t*>(s->ws + s->lay.flag) + 1;
 #ifdef SIM_PHASE_TIMING
   a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
 #else
   a.dbg = nullptr;
 #endif
-  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
-  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, s->E, with_patch);
+  LdsPlan P = plan_for(m, s->E);
   size_t lds_bytes = (size_t)P.total * sizeof(float);
   if (lds_bytes > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d needs %zu bytes of LDS (limit 160 KiB)", s->E, lds_bytes);
   int grid = (s->N + s->E - 1) / s->E;
@@ -445,7 +485,8 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
     return SIM_OK;
   };
   const bool few = m.max_joint_sides <= 4;
-  int lrc = (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
+  int lrc = pairs ? (few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
+            : (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
             : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
             : (s->E == 4 && few) ? launch(&step_kernel<4, 4>)
             : (s->E == 2 && few) ? launch(&step_kernel<2, 4>)
@@ -454,6 +495,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   if (lrc) return lrc;
   HIP_TRY(hipGetLastError());
   if (a.recs) s->recs_valid = 1;
+  if (a.pair_recs) s->pair_grid = grid;
   return SIM_OK;
 }
 
@@ -466,7 +508,7 @@ extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t*
   if (rc) return rc;
   if (!out_bytes) return fail(SIM_ERR_ARG, "out_bytes is NULL");
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
-  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0), num_envs, nh, (size_t)m.cnx * m.cny).total;
+  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0), num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m)).total;
   return SIM_OK;
 }
 
@@ -482,8 +524,8 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
   s->N = num_envs;
   s->obs_dim = 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0);
-  s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny);
-  s->record = 0; s->recs_valid = 0;
+  s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m));
+  s->record = 0; s->recs_valid = 0; s->pair_grid = 0;
   memset(&s->task, 0, sizeof(s->task));
   s->E = default_envs_per_block(m, num_envs);
   if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace must be non-NULL and 256-byte aligned"); }
@@ -556,10 +598,9 @@ extern "C" int sim_act_dim(const sim_t* s) { return s ? s->host_model.D : fail(S
 extern "C" int sim_launch_info(const sim_t* s, int32_t* threads_per_block, int32_t* envs_per_block, size_t* lds_bytes) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
   const Model& m = s->host_model;
-  const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
   if (threads_per_block) *threads_per_block = kThreads;
   if (envs_per_block) *envs_per_block = s->E;
-  if (lds_bytes) *lds_bytes = (size_t)make_plan(m.B, m.J, m.S, m.D, m.F, s->E, with_patch).total * sizeof(float);
+  if (lds_bytes) *lds_bytes = (size_t)plan_for(m, s->E).total * sizeof(float);
   return SIM_OK;
 }
 
@@ -570,7 +611,8 @@ extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
   if (E < 1 || E * m.B > kThreads || 2 * E * m.J > kThreads - 64)
     return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*B <= %d and 2*E*J <= %d)", E, kThreads,
                 kThreads, kThreads - 64);
-  LdsPlan P = make_plan(m.B, m.J, m.S, m.D, m.F, E, (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0);
+  if (m.group > 1 && E % m.group) return fail(SIM_ERR_ARG, "envs_per_block %d is not a multiple of the group size %d", E, m.group);
+  LdsPlan P = plan_for(m, E);
   if ((size_t)P.total * 4 > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d exceeds LDS", E);
   s->E = E;
   return SIM_OK;
@@ -729,6 +771,49 @@ extern "C" int sim_get_contacts(sim_t* s, sim_contact_rec_t* recs_dev, void* str
   hipLaunchKernelGGL(copy_i32_kernel, dim3(blocks_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
                      reinterpret_cast<const int32_t*>(s->ws + s->lay.recs), reinterpret_cast<int32_t*>(recs_dev),
                      (int)n);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+// Packs the per-workgroup capsule-capsule records into one list (one block; workgroup order).
+__global__ void gather_pair_recs_kernel(const int32_t* __restrict__ recs, const int32_t* __restrict__ count, int grid,
+                                        const int32_t* __restrict__ dropped, int32_t* __restrict__ out, int cap,
+                                        int32_t* __restrict__ out_count) {
+  __shared__ int scan[1024];
+  __shared__ int base;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (int g0 = 0; g0 < grid; g0 += 1024) {
+    const int g = g0 + threadIdx.x;
+    const int c = g < grid ? count[g] : 0;
+    scan[threadIdx.x] = c;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      scan[threadIdx.x] += v;
+      __syncthreads();
+    }
+    const int first = base + scan[threadIdx.x] - c;
+    for (int k = 0; k < c; ++k)
+      if (first + k < cap)
+        for (int w = 0; w < 8; ++w) out[(size_t)(first + k) * 8 + w] = recs[((size_t)g * kPairCap + k) * 8 + w];
+    __syncthreads();
+    if (threadIdx.x == 1023) base += scan[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) { out_count[0] = base; out_count[1] = dropped[0]; }
+}
+
+extern "C" int sim_get_pair_contacts(sim_t* s, sim_pair_contact_rec_t* recs_dev, int32_t cap, int32_t* count_dev, void* stream) {
+  if (!s || !count_dev || (cap > 0 && !recs_dev)) return fail(SIM_ERR_ARG, "sim, recs or count is NULL");
+  if (!pairs_of(s->host_model)) return fail(SIM_ERR_ARG, "the description has neither collide pairs nor interaction groups");
+  if (!s->recs_valid || !s->pair_grid) return fail(SIM_ERR_ARG, "no contact records: call sim_record_contacts(sim, 1) before sim_step");
+  hipLaunchKernelGGL(gather_pair_recs_kernel, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const int32_t*>(s->ws + s->lay.pair_recs),
+                     reinterpret_cast<const int32_t*>(s->ws + s->lay.pair_count), s->pair_grid,
+                     reinterpret_cast<const int32_t*>(s->ws + s->lay.flag) + 1, reinterpret_cast<int32_t*>(recs_dev),
+                     cap < 0 ? 0 : cap, count_dev);
   HIP_TRY(hipGetLastError());
   return SIM_OK;
 }

@@ -64,6 +64,9 @@ struct StepArgs {
   float* push;           // [N][3]: force on the root body during this step
   const uint8_t* repack; // non-null: only re-pack the observation of the flagged envs (zero substeps)
   long long* dbg;        // phase-timing slots (diagnostic build only)
+  int32_t* pair_recs;    // [grid][kPairCap][8] capsule-capsule contacts of the last substep, or null
+  int32_t* pair_count;   // [grid] their number per workgroup
+  int32_t* pair_dropped; // [1] contacts dropped because a workgroup found more than kPairCap
 };
 
 // Rows (E consecutive floats) per item of the velocity, inverse-inertia and copy arrays.  Odd
@@ -72,9 +75,11 @@ constexpr int kVS = 7, kCS = 7, kJS = 13;
 
 struct LdsPlan {
   int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
+  int pq, po, pnear, pbs, pcount;  // capsule-capsule contacts (only with pairs != 0)
 };
 
-__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch) {
+// pairs: 0 = no capsule-capsule contacts, else the interaction group size (1 = self-collision only)
+__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch, int pairs = 0) {
   LdsPlan p;
   int o = 0;
   p.pos = o; o += B * 7 * E;
@@ -103,6 +108,11 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.tjoint = o; o += J * (int)(sizeof(JointTab) / 4);
   p.patch = o; o += with_patch ? E * kPatch * kPatch : 0;
   p.mip = o; o += with_patch ? E * kPatchBlocks * kPatchBlocks : 0;
+  p.pq = o; o += pairs ? kPairCap * kPairWords : 0;   // sorted queue of the substep's contacts
+  p.po = o; o += pairs ? kPairCap * 12 : 0;           // velocity copies of their two bodies
+  p.pnear = o; o += pairs ? (E * pairs) / 2 + 1 : 0;  // agent pairs whose bounding spheres overlap
+  p.pbs = o; o += pairs ? E : 0;                      // bounding radius of every agent about its root
+  p.pcount = o; o += pairs ? 4 : 0;
   p.total = o;
   return p;
 }
@@ -284,6 +294,109 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
   }
 }
 
+// Rows of one capsule-capsule contact (Section 3.1: contacts among bodies; Section 4.1:
+// inter-agent collisions): normal and two tangents between body A (+J) and body B (-J), one
+// contact point for both (midway between the closest surface points, so the pair of opposite
+// impulses carries no net torque).
+struct PairRows {
+  float dir[3][3];              // n (from B to A), t1, t2
+  float angA[3][3], angB[3][3]; // lever arm x dir on either body
+  float YA[3][3], YB[3][3];     // angular responses
+  float lsA, lsB;               // linear responses
+  float meff[3], bias, lam[3];
+  int offA, offB;               // position of the bodies' velocity rows in LDS: body * kVS * E + env
+};
+
+// Builds the rows of queue entry k from the poses, the segment parameters (s, t) the contact
+// search found, the bodies' world inverse inertia and weight sums.
+__device__ __forceinline__ void build_pair_rows(PairRows& c, const float* Lpq, const float* Lpos, const float* Liw,
+                                                const float* Lnb, const float* Lorg, const float* Ltbody, int k,
+                                                int E, float h, float beta_c, float v_depen) {
+  const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
+  const int ra = refs & 0xffff, rb = (refs >> 16) & 0xffff;
+  const int ba = ra / E, ea = ra - ba * E, bb = rb / E, eb = rb - bb * E;
+  const float sp = Lpq[k * kPairWords + 2], tp = Lpq[k * kPairWords + 3], wk = Lpq[k * kPairWords + 4];
+  float xa[3], xb[3], qa[4], qb[4], iwa[6], iwb[6];
+  for (int i = 0; i < 3; ++i) {
+    xa[i] = Lpos[(ba * 7 + i) * E + ea];
+    xb[i] = Lpos[(bb * 7 + i) * E + eb] + (Lorg[i * E + eb] - Lorg[i * E + ea]);   // in A's env frame
+  }
+  for (int i = 0; i < 4; ++i) { qa[i] = Lpos[(ba * 7 + 3 + i) * E + ea]; qb[i] = Lpos[(bb * 7 + 3 + i) * E + eb]; }
+  for (int i = 0; i < 6; ++i) { iwa[i] = Liw[(ba * kVS + i) * E + ea]; iwb[i] = Liw[(bb * kVS + i) * E + eb]; }
+  const float radA = Ltbody[4 * ba], hlA = Ltbody[4 * ba + 1], imA = Ltbody[4 * ba + 3];
+  const float radB = Ltbody[4 * bb], hlB = Ltbody[4 * bb + 1], imB = Ltbody[4 * bb + 3];
+  const int axA = __float_as_int(Ltbody[4 * ba + 2]), axB = __float_as_int(Ltbody[4 * bb + 2]);
+  float Ra[9], Rb[9], cp[3], cq[3], df[3];
+  quat_to_mat(qa, Ra);
+  quat_to_mat(qb, Rb);
+  for (int i = 0; i < 3; ++i) {
+    const float ha = Ra[3 * i + axA] * hlA, hb = Rb[3 * i + axB] * hlB;
+    cp[i] = xa[i] - ha + 2.0f * sp * ha;
+    cq[i] = xb[i] - hb + 2.0f * tp * hb;
+    df[i] = cp[i] - cq[i];
+  }
+  const float dist = sqrtf(dot(df, df));
+  float n[3] = {0.0f, 0.0f, 1.0f};
+  if (dist >= 1e-9f) { const float inv = 1.0f / dist; for (int i = 0; i < 3; ++i) n[i] = df[i] * inv; }
+  const float d = dist - radA - radB;
+  float armA[3], armB[3];
+  for (int i = 0; i < 3; ++i) {
+    const float pm = 0.5f * ((cp[i] - n[i] * radA) + (cq[i] + n[i] * radB));
+    armA[i] = pm - xa[i];
+    armB[i] = pm - xb[i];
+  }
+  float t1[3], t2[3];
+  if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
+  else { t1[0] = -n[2]; t1[1] = 0.0f; t1[2] = n[0]; }
+  const float inv = 1.0f / sqrtf(dot(t1, t1));
+  for (int i = 0; i < 3; ++i) t1[i] *= inv;
+  cross(n, t1, t2);
+  for (int i = 0; i < 3; ++i) { c.dir[0][i] = n[i]; c.dir[1][i] = t1[i]; c.dir[2][i] = t2[i]; }
+  const float nbA = Lnb[ba * E + ea] / wk, nbB = Lnb[bb * E + eb] / wk;
+  c.lsA = nbA * imA; c.lsB = nbB * imB;
+  for (int r = 0; r < 3; ++r) {
+    float ya[3], yb[3];
+    cross(armA, c.dir[r], c.angA[r]);
+    cross(armB, c.dir[r], c.angB[r]);
+    sym_vec(iwa, c.angA[r], ya);
+    sym_vec(iwb, c.angB[r], yb);
+    const float keff = nbA * (imA + dot(c.angA[r], ya)) + nbB * (imB + dot(c.angB[r], yb));
+    c.meff[r] = keff > 0.0f ? 1.0f / keff : 0.0f;
+    for (int i = 0; i < 3; ++i) { c.YA[r][i] = nbA * ya[i]; c.YB[r][i] = nbB * yb[i]; }
+    c.lam[r] = 0.0f;
+  }
+  c.bias = d >= 0.0f ? d / h : fmaxf(beta_c * d / h, -v_depen);
+  c.offA = ba * kVS * E + ea;
+  c.offB = bb * kVS * E + eb;
+}
+
+// One sweep of a capsule-capsule block on its private copies of the two bodies' velocities.
+__device__ __forceinline__ void relax_pair(PairRows& c, float mu, float va[3], float wa[3], float vb[3], float wb[3]) {
+  {
+    float jv = dot(c.dir[0], va) - dot(c.dir[0], vb) + dot(c.angA[0], wa) - dot(c.angB[0], wb);
+    float dl = -c.meff[0] * (jv + c.bias);
+    float ln = fmaxf(c.lam[0] + dl, 0.0f);
+    dl = ln - c.lam[0];
+    c.lam[0] = ln;
+    for (int k = 0; k < 3; ++k) {
+      va[k] += c.lsA * c.dir[0][k] * dl; wa[k] += c.YA[0][k] * dl;
+      vb[k] -= c.lsB * c.dir[0][k] * dl; wb[k] -= c.YB[0][k] * dl;
+    }
+  }
+  float jv1 = dot(c.dir[1], va) - dot(c.dir[1], vb) + dot(c.angA[1], wa) - dot(c.angB[1], wb);
+  float jv2 = dot(c.dir[2], va) - dot(c.dir[2], vb) + dot(c.angA[2], wa) - dot(c.angB[2], wb);
+  float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
+  float lim = mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
+  if (nrm > lim) { float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
+  float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
+  c.lam[1] = l1; c.lam[2] = l2;
+  for (int k = 0; k < 3; ++k) {
+    const float lin = c.dir[1][k] * d1 + c.dir[2][k] * d2;
+    va[k] += c.lsA * lin; wa[k] += c.YA[1][k] * d1 + c.YA[2][k] * d2;
+    vb[k] -= c.lsB * lin; wb[k] -= c.YB[1][k] * d1 + c.YB[2][k] * d2;
+  }
+}
+
 // EC > 0: envs per workgroup fixed at compile time (LDS offsets become immediates);
 // EC == 0: taken from the launch arguments.  NJ: compile-time bound on the joints one body
 // belongs to (the per-body average reads NJ joint copies without branching).
@@ -343,7 +456,8 @@ __device__ __forceinline__ int wave_alloc(int n, int* counter) {
   return base + before;
 }
 
-template <int EC, int NJ>
+// PC != 0: capsule-capsule contacts (within an agent and between the agents of a group) compiled in.
+template <int EC, int NJ, int PC = 0>
 __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 #ifdef SIM_PHASE_TIMING
   long long t_last = clock64();
@@ -365,7 +479,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const int m_terrain = M.terrain_kind, m_contacts = M.contacts;
   const Field H0 = make_field(M, a.heights, a.coarse);
   const bool use_patch = m_terrain == 1 && H0.nx >= kPatch && H0.ny >= kPatch;
-  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0);
+  const int m_group = PC ? (M.group > 1 ? M.group : 1) : 1, m_npairs = PC ? M.n_pairs : 0, m_nap = PC ? M.n_agent_pairs : 0;
+  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0);
   float* Lpos = lds + P.pos;
   float* Lvel = lds + P.vel;
   float* Liw = lds + P.iw;
@@ -402,6 +517,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   float* Ltbody = lds + P.tbody;                      // body table: radius, half length, axis, 1/mass
   float* Ltin = lds + P.tin;                          // body table: inertia(3), inverse inertia(3)
   const JointTab* Ltjoint = reinterpret_cast<const JointTab*>(lds + P.tjoint);  // joint table
+  float* Lpq = lds + P.pq;                            // capsule-capsule contacts, kPairWords each, sorted by key
+  float* Lpo = lds + P.po;                            // their velocity copies: A (v, w), B (v, w)
+  int* Lnear = reinterpret_cast<int*>(lds + P.pnear);
+  int* Lbs = reinterpret_cast<int*>(lds + P.pbs);     // bounding radii as float bits (ordered like ints)
+  int* Lpcount = reinterpret_cast<int*>(lds + P.pcount);  // contacts found, near agent pairs
   const float h = a.h;
 
   // re-packing launch: a workgroup none of whose envs is flagged has nothing to do
@@ -534,6 +654,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const bool js_on = js_j < J && blockIdx.x * E + js_e < N;
   SideRows jr;
   ContactRows cr;
+  PairRows pr;
   bool has_contact = false;  // this thread owns an active contact this substep
 
   const int tid_o = tid, e_o = e, idx_o = idx;
@@ -550,6 +671,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     const int b = idx;
     // ---- A: publish pose and world inverse inertia
     if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; Lcount[5] = 0; Lcount[6] = 0; Lcount[7] = 0; }
+    if constexpr (PC != 0) {
+      if (tid < 4) Lpcount[tid] = 0;
+      if (tid < E) Lbs[tid] = 0;
+    }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
       for (int c = 0; c < 4; ++c) Lpos[(b * 7 + 3 + c) * E + e] = q[c];
@@ -878,11 +1003,119 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     __syncthreads();
     TMARK(3);
 
+    // ---- P: capsule-capsule contacts from the poses published in phase A (Section 3.1: contacts
+    //         among bodies; Section 4.1: inter-agent collisions).  Candidates: the listed body pairs
+    //         of every agent, and every body pair of two agents of one group whose bounding spheres
+    //         overlap.  A candidate passes a bounding-sphere test, then the segment-segment test in
+    //         the fixed operation order; hits are queued and the queue is sorted by candidate key, so
+    //         that the order in which the bodies later add up their contacts does not depend on which
+    //         wavefront found what first.
+    int n_pc = 0;
+    if constexpr (PC != 0) {
+      if (m_contacts && (m_npairs > 0 || m_group > 1)) {
+        if (m_group > 1) {
+          if (is_body) {
+            float dx[3];
+            for (int c = 0; c < 3; ++c) dx[c] = Lpos[(b * 7 + c) * E + e] - Lpos[(M.root * 7 + c) * E + e];
+            const float rad = sqrtf(dot(dx, dx)) + Ltbody[4 * b + 1] + Ltbody[4 * b];
+            atomicMax(&Lbs[e], __float_as_int(rad));
+          }
+          __syncthreads();
+          const int n_ap = (E / m_group) * m_nap;
+          for (int t = tid; t < n_ap; t += kThreads) {
+            const int gi = t / m_nap, pi = t - gi * m_nap;
+            const int ea = gi * m_group + M.agent_pair_a[pi], eb = gi * m_group + M.agent_pair_b[pi];
+            bool near = false;
+            if (blockIdx.x * E + eb < N) {   // (ea < eb)
+              float dd = 0.0f;
+              for (int c = 0; c < 3; ++c) {
+                const float dc = (Lpos[(M.root * 7 + c) * E + eb] + Lorg[c * E + eb]) - (Lpos[(M.root * 7 + c) * E + ea] + Lorg[c * E + ea]);
+                dd += dc * dc;
+              }
+              const float rr = __int_as_float(Lbs[ea]) + __int_as_float(Lbs[eb]) + p_margin + 2e-3f;
+              near = dd <= rr * rr;
+            }
+            const int pos = wave_alloc<1>(near ? 1 : 0, &Lpcount[1]);
+            if (near) Lnear[pos] = ea | (eb << 16);
+          }
+          __syncthreads();
+        }
+        float* Ltmp = Lpo;   // unsorted queue; the copies are not in use yet
+        auto test_pair = [&](int ea, int ba, int eb, int bb, unsigned key, bool valid) {
+          bool hit = false;
+          float sp = 0.0f, tp = 0.0f, gap = 0.0f;
+          if (valid) {
+            float xa[3], xb[3], off[3];
+            for (int c = 0; c < 3; ++c) {
+              off[c] = Lorg[c * E + eb] - Lorg[c * E + ea];
+              xa[c] = Lpos[(ba * 7 + c) * E + ea];
+              xb[c] = Lpos[(bb * 7 + c) * E + eb];
+            }
+            const float radA = Ltbody[4 * ba], hlA = Ltbody[4 * ba + 1], radB = Ltbody[4 * bb], hlB = Ltbody[4 * bb + 1];
+            float dd = 0.0f;
+            for (int c = 0; c < 3; ++c) { const float dc = (xb[c] + off[c]) - xa[c]; dd += dc * dc; }
+            const float reach = (radA + hlA) + (radB + hlB) + p_margin + 2e-3f;
+            if (dd <= reach * reach) {
+              float qa[4], qb[4];
+              for (int c = 0; c < 4; ++c) { qa[c] = Lpos[(ba * 7 + 3 + c) * E + ea]; qb[c] = Lpos[(bb * 7 + 3 + c) * E + eb]; }
+              f3 p0, p1, q0, q1;
+              body_ends(xa, qa, hlA, __float_as_int(Ltbody[4 * ba + 2]), p0, p1);
+              body_ends(xb, qb, hlB, __float_as_int(Ltbody[4 * bb + 2]), q0, q1);
+              hit = pair_in_contact(p0, p1, q0, q1, off, radA, radB, p_margin, sp, tp, gap);
+            }
+          }
+          const int pos = wave_alloc<1>(hit ? 1 : 0, &Lpcount[0]);
+          if (hit && pos < kPairCap) {
+            Ltmp[pos * kPairWords + 0] = __uint_as_float(key);
+            Ltmp[pos * kPairWords + 1] = __int_as_float((ba * E + ea) | ((bb * E + eb) << 16));
+            Ltmp[pos * kPairWords + 2] = sp;
+            Ltmp[pos * kPairWords + 3] = tp;
+            Ltmp[pos * kPairWords + 4] = block_weight(p_margin, gap, 1.0f);
+            Ltmp[pos * kPairWords + 5] = gap;
+          }
+        };
+        // the listed pairs of every agent: thread (idx, e) takes pairs idx, idx + stride, ...
+        {
+          const int stride = kThreads / E;
+          if (idx < stride)
+            for (int pp = idx; pp < m_npairs; pp += stride)
+              test_pair(e, M.pair_a[pp], e, M.pair_b[pp], ((unsigned)pp << 12) | (unsigned)e, env_ok);
+        }
+        // agents of one group: 256 lanes per near agent pair, lane = (body of A) * 16 + (body of B)
+        if (m_group > 1) {
+          const int n_near = Lpcount[1];
+          for (int nn = tid >> 8; nn < n_near; nn += kThreads >> 8) {
+            const int cb = tid & 255, ba = cb >> 4, bb = cb & 15;
+            const int pr = Lnear[nn], ea = pr & 0xffff, eb = pr >> 16;
+            test_pair(ea, ba, eb, bb, 0x80000000u | ((unsigned)ea << 20) | ((unsigned)eb << 8) | (unsigned)(ba << 4) | (unsigned)bb,
+                      ba < B && bb < B);
+          }
+        }
+        __syncthreads();
+        const int n_raw = Lpcount[0];
+        n_pc = n_raw < kPairCap ? n_raw : kPairCap;
+        if (tid < n_pc) {
+          const unsigned key = __float_as_uint(Ltmp[tid * kPairWords]);
+          int rank = 0;
+          for (int k = 0; k < n_pc; ++k) rank += __float_as_uint(Ltmp[k * kPairWords]) < key ? 1 : 0;
+          for (int wd = 0; wd < kPairWords; ++wd) Lpq[rank * kPairWords + wd] = Ltmp[tid * kPairWords + wd];
+        }
+        if (tid == 0 && n_raw > kPairCap) atomicAdd(a.pair_dropped, n_raw - kPairCap);
+        __syncthreads();
+      }
+    }
+    const int my_ref = b * E + e;
     // ---- C: block weight sums (and, on the plane, forces -> velocities)
     float nbf = 0.0f;
     if (is_body) {
       nbf = (float)my_njs;
       for (int k = 0; k < my_nslots; ++k) nbf += Lrec[((my_slot0 + k) * kRecWords + 10) * E + e];
+      if constexpr (PC != 0) {
+        for (int k = 0; k < n_pc; ++k) {
+          const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
+          if ((refs & 0xffff) == my_ref || ((refs >> 16) & 0xffff) == my_ref) nbf += Lpq[k * kPairWords + 4];
+        }
+      }
       Lnb[b * E + e] = nbf;
     }
     if (m_terrain == 0) forces();   // plane: no per-body pass, the torques are complete only now
@@ -895,6 +1128,19 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           int word = Lreci[(s * kRecWords + wd) * E + ee];
           if (!Lreci[(s * kRecWords + 0) * E + ee]) word = (wd == 1 || wd == 2) ? -1 : 0;   // inactive: canonical record
           a.recs[((size_t)env_i * S + s) * kRecWords + wd] = word;
+        }
+      }
+    }
+    if constexpr (PC != 0) {
+      if (a.pair_recs && sub == a.substeps - 1) {
+        if (tid == 0) a.pair_count[blockIdx.x] = n_pc;
+        if (tid < n_pc) {
+          const int refs = __float_as_int(Lpq[tid * kPairWords + 1]);
+          const int ra = refs & 0xffff, rb = (refs >> 16) & 0xffff;
+          int32_t* o = a.pair_recs + ((size_t)blockIdx.x * kPairCap + tid) * 8;
+          o[0] = blockIdx.x * E + ra % E; o[1] = ra / E; o[2] = blockIdx.x * E + rb % E; o[3] = rb / E;
+          o[4] = __float_as_int(Lpq[tid * kPairWords + 2]); o[5] = __float_as_int(Lpq[tid * kPairWords + 3]);
+          o[6] = __float_as_int(Lpq[tid * kPairWords + 5]); o[7] = __float_as_int(Lpq[tid * kPairWords + 4]);
         }
       }
     }
@@ -989,6 +1235,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       for (int k = n_reg + tid; k < n_active; k += kThreads)
         for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = 0.0f;
     }
+    // capsule-capsule contact k of the sorted queue goes to thread k
+    if constexpr (PC != 0) {
+      if (tid < n_pc) build_pair_rows(pr, Lpq, Lpos, Liw, Lnb, Lorg, Ltbody, tid, E, h, p_beta_c, p_vdepen);
+    }
 
     TMARK(5);
     // The per-body average is split over two threads when the workgroup has room: thread (e, b)
@@ -1002,6 +1252,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     const int g_b = idx - g_half * B;
     const bool g_on = env_ok && g_b < B && idx < (g_split ? 2 * B : B);
     float g_inb = 0.0f;
+    const int g_ref = g_b * E + e;
     int gat_off[NJ], gat_slot[3];
     float gat_w[NJ + 3];
     {
@@ -1049,7 +1300,35 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         for (int k = 0; k < NJ + 3; ++k)
 #pragma unroll
           for (int c = 0; c < 3; ++c) acc[c] += gat_w[k] * val[k][c];
+        if constexpr (PC != 0) {
+          // capsule-capsule contacts that touch this body, in queue order
+          for (int k = 0; k < n_pc; ++k) {
+            const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
+            const float wk = Lpq[k * kPairWords + 4];
+            if ((refs & 0xffff) == g_ref)
+              for (int c = 0; c < 3; ++c) acc[c] += wk * Lpo[k * 12 + hsel * 3 + c];
+            if (((refs >> 16) & 0xffff) == g_ref)
+              for (int c = 0; c < 3; ++c) acc[c] += wk * Lpo[k * 12 + 6 + hsel * 3 + c];
+          }
+        }
         for (int c = 0; c < 3; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = acc[c] * g_inb;
+      }
+    };
+    // one sweep of this thread's capsule-capsule contact, if it has one
+    auto pair_sweep = [&]() {
+      if constexpr (PC != 0) {
+        if (tid < n_pc) {
+          float va[3], wa[3], vb[3], wb[3];
+          for (int c = 0; c < 3; ++c) {
+            va[c] = Lvel[pr.offA + c * E]; wa[c] = Lvel[pr.offA + (3 + c) * E];
+            vb[c] = Lvel[pr.offB + c * E]; wb[c] = Lvel[pr.offB + (3 + c) * E];
+          }
+          relax_pair(pr, p_mu, va, wa, vb, wb);
+          for (int c = 0; c < 3; ++c) {
+            Lpo[tid * 12 + c] = va[c]; Lpo[tid * 12 + 3 + c] = wa[c];
+            Lpo[tid * 12 + 6 + c] = vb[c]; Lpo[tid * 12 + 9 + c] = wb[c];
+          }
+        }
       }
     };
     auto gather = [&]() {
@@ -1092,6 +1371,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
               Loutj[(js_j * kJS + js_side * 6 + 3 + c) * E + e] = wo[c];
             }
         }
+        pair_sweep();
         __syncthreads();
         gather();
         __syncthreads();
@@ -1118,6 +1398,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
           for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = c2.lam[r];
           for (int r = 0; r < 3; ++r) { Loutc[(sl * kCS + r) * E + ee] = vv[r]; Loutc[(sl * kCS + 3 + r) * E + ee] = ww[r]; }
         }
+        pair_sweep();
         __syncthreads();
         gather();
         __syncthreads();

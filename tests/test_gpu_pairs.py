@@ -1,0 +1,184 @@
+"""GPU parity of the capsule-capsule contacts (within an agent and between the agents of an
+interaction group) against the fp64 oracle: contact sets and segment parameters bit for bit on
+identical fp32 states, free-running states within the same bars as the terrain-only tests."""
+import numpy as np
+import pytest
+
+import oracle
+import scenes
+
+pytestmark = pytest.mark.gpu
+
+TOL_1, TOL_10 = 1e-4, 1e-3
+
+
+def _P():
+    import paper_1810_05762_amd as P
+    return P
+
+
+def rel_err(g, o):
+    out = []
+    for sl in (slice(0, 3), slice(3, 7), slice(7, 10), slice(10, 13)):
+        d = np.abs(g[:, :, sl] - o[:, :, sl]).reshape(g.shape[0], -1).max(1)
+        n = np.maximum(1.0, np.abs(o[:, :, sl]).reshape(g.shape[0], -1).max(1))
+        out.append(d / n)
+    return np.stack(out, 1).max(1)
+
+
+def _key(r):
+    return np.lexsort((r["body_b"], r["env_b"], r["body_a"], r["env_a"]))
+
+
+def assert_same_pair_sets(pg, po):
+    """Same contacts (as sets), same single-precision segment parameters."""
+    assert len(pg) == len(po), (len(pg), len(po))
+    pg, po = pg[_key(pg)], po[_key(po)]
+    for f in ("env_a", "body_a", "env_b", "body_b"):
+        assert np.array_equal(pg[f], po[f]), f
+    assert np.array_equal(pg["s"].view(np.uint32) & 0x7fffffff, po["s"].view(np.uint32) & 0x7fffffff)
+    assert np.array_equal(pg["t"].view(np.uint32) & 0x7fffffff, po["t"].view(np.uint32) & 0x7fffffff)
+    np.testing.assert_allclose(pg["d"], po["d"], atol=2e-6)
+    np.testing.assert_allclose(pg["w"], po["w"], atol=2e-3)   # (margin - d) / (margin / 2) with d to 2e-6
+
+
+def _loose_pairs_scene(n_envs, seed):
+    """Two free capsules per env in random poses, no gravity; axis distance 0.09 .. 0.16 m
+    (radii 0.08 + 0.05: from 4 cm of overlap to 3 cm of clearance; a distance near zero would
+    leave the contact normal undefined)."""
+    from scipy.spatial.transform import Rotation
+    rob = scenes.make_loose([(0.08, 0.5, 0, (0.0, 0.0, 5.0), 1.3), (0.05, 0.4, 1, (0.0, 0.0, 6.0), 0.7)])
+    p = scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1)
+    sc = scenes.make_scene(rob, scenes.make_plane(), n_envs, params=p)
+    rng = np.random.default_rng(seed)
+    st = np.repeat(scenes.rest_state(rob), n_envs, axis=0)
+    for e in range(n_envs):
+        while True:
+            q = rng.normal(size=(2, 4))
+            q /= np.linalg.norm(q, axis=1, keepdims=True)
+            x1 = st[e, 0, 0:3] + rng.normal(size=3) * 0.15
+            ends = []
+            for b, x in ((0, st[e, 0, 0:3]), (1, x1)):
+                ax = Rotation.from_quat([q[b, 1], q[b, 2], q[b, 3], q[b, 0]]).as_matrix()[:, int(rob.axis[b])]
+                ends += [x - rob.half_len[b] * ax, x + rob.half_len[b] * ax]
+            d2, _, _ = oracle.segment_segment_f32(*ends)
+            if 0.09 ** 2 < d2 < 0.16 ** 2:
+                break
+        st[e, :, 3:7] = q
+        st[e, 1, 0:3] = x1
+    st[:, :, 7:13] = rng.normal(size=(n_envs, 2, 6)) * np.array([0.5, 0.5, 0.5, 2, 2, 2])
+    return rob, sc, st.astype(np.float32).astype(np.float64)
+
+
+def test_two_capsules_contact_set_and_one_step_parity():
+    P = _P()
+    n = 203
+    rob, sc, st = _loose_pairs_scene(n, 3)
+    sim, ref = P.Sim(sc), oracle.OracleSim(sc, threads=8)
+    sim.set_state(st); ref.set_state(st)
+    sim.record_contacts(True)
+    h = float(np.float32(1.0 / 240.0))
+    sim.step(None, h, 1, 20); ref.step(None, h, 1, 20)
+    pg, dropped = sim.get_pair_contacts()
+    po = ref.get_pair_contacts()
+    assert dropped == 0
+    assert 40 < len(po) < n                      # some touch, some do not
+    assert_same_pair_sets(pg, po)
+    e = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+    print(f"two capsules: {len(po)} contacts, 1 substep max rel err {e.max():.2e}")
+    assert e.max() <= TOL_1
+    # the contacts did change the motion
+    moved = np.abs(ref.get_state()[:, :, 7:13] - st[:, :, 7:13]).reshape(n, -1).max(1)
+    assert (moved > 1e-2).sum() > 20
+    sim.check(); sim.close()
+
+
+def test_head_on_spheres_match_the_closed_form():
+    """Perfectly inelastic impact: both spheres end with the centre-of-mass velocity."""
+    P = _P()
+    rob = scenes.make_loose([(0.1, 0.0, 0, (0.0, 0.0, 5.0), 1.0), (0.1, 0.0, 0, (0.25, 0.0, 5.0), 3.0)])
+    sc = scenes.make_scene(rob, scenes.make_plane(), 5, params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1))
+    sim = P.Sim(sc)
+    st = np.repeat(scenes.rest_state(rob), 5, axis=0)
+    st[:, 0, 7], st[:, 1, 7] = 1.0, -0.5
+    sim.set_state(st)
+    for _ in range(12):
+        sim.step(None, 1.0 / 60.0, 4, 4)
+    s = sim.get_state().cpu().numpy()
+    vcm = (1.0 * 1.0 - 3.0 * 0.5) / 4.0
+    assert np.allclose(s[:, :, 7], vcm, atol=1e-5)
+    assert np.allclose(s[:, 1, 0] - s[:, 0, 0], 0.2, atol=1e-5)
+    sim.close()
+
+
+def _humanoid_scene(n_envs, group, spacing, terrain="plane", self_collide=1):
+    rob = scenes.make_humanoid()
+    p = scenes.SimParams(self_collide=self_collide, group_size=group)
+    t = scenes.make_plane() if terrain == "plane" else scenes.make_heightfield(seed=1003)
+    return rob, scenes.make_scene(rob, t, n_envs, seed=21, params=p, spacing=spacing if group > 1 else None)
+
+
+@pytest.mark.parametrize("group,terrain,n_envs", [(1, "plane", 37), (4, "plane", 38), (16, "plane", 40), (4, "heightfield", 38)])
+def test_humanoids_with_collisions(group, terrain, n_envs):
+    """Falling humanoids (random actions) with self-collision, in groups standing 0.6 m apart:
+    contact sets of every substep on teacher-forced states, then ten free-running steps."""
+    P = _P()
+    rob, sc = _humanoid_scene(n_envs, group, 0.6, terrain)
+    sim, ref = P.Sim(sc), oracle.OracleSim(sc, threads=8)
+    sim.reset(5)
+    sim.record_contacts(True)
+    dt, sub, its = float(np.float32(1.0 / 60.0)), 4, 20
+    h = dt / sub
+    total = inter = 0
+    for s in range(50):
+        a = scenes.actions_for_step(9, s, n_envs, rob.n_dofs)
+        if s % 5 == 4:
+            # one substep on identical states: sets bit for bit, state to the one-step bar
+            ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))
+            sim.step(a, h, 1, its); ref.step(a, h, 1, its)
+            pg, dropped = sim.get_pair_contacts()
+            po = ref.get_pair_contacts()
+            assert dropped == 0
+            assert_same_pair_sets(pg, po)
+            cg, co = sim.get_contacts(), ref.get_contacts()
+            assert all(np.array_equal(cg[f], co[f]) for f in ("active", "kind", "feat"))
+            e = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+            assert e.max() <= TOL_1, (s, e.max())
+            total += len(po); inter += int((po["env_a"] != po["env_b"]).sum())
+        else:
+            sim.step(a, dt, sub, its)
+    assert total > 20
+    if group > 1:
+        assert inter > 5
+    # free run from a contact-rich state
+    ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))
+    errs = {}
+    for s in range(10):
+        a = scenes.actions_for_step(9, 50 + s, n_envs, rob.n_dofs)
+        sim.step(a, dt, sub, its); ref.step(a, dt, sub, its)
+        if s in (0, 9):
+            errs[s + 1] = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+    print(f"group {group} {terrain}: {total} pair contacts sampled ({inter} between agents); 1 step max {errs[1].max():.2e}, "
+          f"10 steps median {np.median(errs[10]):.2e} p95 {np.quantile(errs[10], .95):.2e} max {errs[10].max():.2e}")
+    assert errs[1].max() <= TOL_1
+    assert np.median(errs[10]) <= TOL_1 and np.quantile(errs[10], 0.9) <= TOL_10
+    sim.check(); sim.close()
+
+
+def test_groups_do_not_interact_across_group_boundaries_and_off_switch_matches_plain_kernel():
+    """With collisions compiled in but nothing close enough to touch, the states equal those of the
+    plain kernel bit for bit (the extra phase changes nothing else)."""
+    P = _P()
+    n = 35
+    rob = scenes.make_humanoid()
+    sc0 = scenes.make_scene(rob, scenes.make_plane(), n, seed=4, params=scenes.SimParams())
+    sc1 = scenes.make_scene(rob, scenes.make_plane(), n, seed=4, params=scenes.SimParams(group_size=4))   # agents 5 m apart
+    a0, a1 = P.Sim(sc0), P.Sim(sc1)
+    a0.reset(3); a1.reset(3)
+    a1.record_contacts(True)
+    for s in range(8):
+        a = scenes.actions_for_step(2, s, n, rob.n_dofs)
+        a0.step(a, 1.0 / 60.0, 4, 20); a1.step(a, 1.0 / 60.0, 4, 20)
+    assert len(a1.get_pair_contacts()[0]) == 0
+    assert np.array_equal(a0.get_state().cpu().numpy(), a1.get_state().cpu().numpy())
+    a0.close(); a1.close()
