@@ -485,7 +485,8 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
     return SIM_OK;
   };
   const bool few = m.max_joint_sides <= 4;
-  int lrc = pairs ? (few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
+  int lrc = pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
+                     : few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
             : (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
             : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
             : (s->E == 4 && few) ? launch(&step_kernel<4, 4>)

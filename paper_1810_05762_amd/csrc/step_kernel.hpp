@@ -109,7 +109,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.patch = o; o += with_patch ? E * kPatch * kPatch : 0;
   p.mip = o; o += with_patch ? E * kPatchBlocks * kPatchBlocks : 0;
   p.pq = o; o += pairs ? kPairCap * kPairWords : 0;   // sorted queue of the substep's contacts
-  p.po = o; o += pairs ? kPairCap * 12 : 0;           // velocity copies of their two bodies
+  p.po = o; o += pairs ? (kPairCap + 1) * 12 : 0;     // weighted velocity copies of their two bodies; the last entry stays zero
   p.pnear = o; o += pairs ? (E * pairs) / 2 + 1 : 0;  // agent pairs whose bounding spheres overlap
   p.pbs = o; o += pairs ? E : 0;                      // bounding radius of every agent about its root
   p.pcount = o; o += pairs ? 4 : 0;
@@ -295,36 +295,41 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
 }
 
 // Rows of one capsule-capsule contact (Section 3.1: contacts among bodies; Section 4.1:
-// inter-agent collisions): normal and two tangents between body A (+J) and body B (-J), one
-// contact point for both (midway between the closest surface points, so the pair of opposite
-// impulses carries no net torque).
-struct PairRows {
-  float dir[3][3];              // n (from B to A), t1, t2
-  float angA[3][3], angB[3][3]; // lever arm x dir on either body
-  float YA[3][3], YB[3][3];     // angular responses
-  float lsA, lsB;               // linear responses
+// inter-agent collisions) as seen from ONE of its two bodies: normal and two tangents between
+// body A (+J) and body B (-J), one contact point for both (midway between the closest surface
+// points, so the pair of opposite impulses carries no net torque).  Like a joint, a contact is
+// relaxed by two neighbouring lanes, one per body; a row's J v is the sum of the two lanes'
+// parts, both lanes compute the same impulse and each updates its own body's copy.  All signs
+// (+1 for A, -1 for B) are folded into the stored vectors.
+struct PairSide {
+  float sd[3][3];    // sg * (n, t1, t2); n points from B to A
+  float sa[3][3];    // sg * (lever arm x direction)
+  float Y[3][3];     // own angular response per unit impulse
+  float ls;          // own linear response per unit impulse along sd
   float meff[3], bias, lam[3];
-  int offA, offB;               // position of the bodies' velocity rows in LDS: body * kVS * E + env
+  float wk;          // the block's weight: copies are published multiplied by it
+  int off;           // own body's velocity rows in LDS: body * kVS * E + env
 };
 
-// Builds the rows of queue entry k from the poses, the segment parameters (s, t) the contact
-// search found, the bodies' world inverse inertia and weight sums.
-__device__ __forceinline__ void build_pair_rows(PairRows& c, const float* Lpq, const float* Lpos, const float* Liw,
-                                                const float* Lnb, const float* Lorg, const float* Ltbody, int k,
-                                                int E, float h, float beta_c, float v_depen) {
+// Builds side `side` (0: body A, 1: body B) of queue entry k from the poses, the segment
+// parameters (s, t) the contact search found, the body's world inverse inertia and weight sum.
+// Both lanes evaluate the same geometry with the same operations.
+__device__ __forceinline__ void build_pair_side(PairSide& c, int side, const float* Lpq, const float* Lpos,
+                                                const float* Liw, const float* Lnb, const float* Lorg,
+                                                const float* Ltbody, int k, int E, float h, float beta_c,
+                                                float v_depen) {
   const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
   const int ra = refs & 0xffff, rb = (refs >> 16) & 0xffff;
   const int ba = ra / E, ea = ra - ba * E, bb = rb / E, eb = rb - bb * E;
   const float sp = Lpq[k * kPairWords + 2], tp = Lpq[k * kPairWords + 3], wk = Lpq[k * kPairWords + 4];
-  float xa[3], xb[3], qa[4], qb[4], iwa[6], iwb[6];
+  float xa[3], xb[3], qa[4], qb[4];
   for (int i = 0; i < 3; ++i) {
     xa[i] = Lpos[(ba * 7 + i) * E + ea];
     xb[i] = Lpos[(bb * 7 + i) * E + eb] + (Lorg[i * E + eb] - Lorg[i * E + ea]);   // in A's env frame
   }
   for (int i = 0; i < 4; ++i) { qa[i] = Lpos[(ba * 7 + 3 + i) * E + ea]; qb[i] = Lpos[(bb * 7 + 3 + i) * E + eb]; }
-  for (int i = 0; i < 6; ++i) { iwa[i] = Liw[(ba * kVS + i) * E + ea]; iwb[i] = Liw[(bb * kVS + i) * E + eb]; }
-  const float radA = Ltbody[4 * ba], hlA = Ltbody[4 * ba + 1], imA = Ltbody[4 * ba + 3];
-  const float radB = Ltbody[4 * bb], hlB = Ltbody[4 * bb + 1], imB = Ltbody[4 * bb + 3];
+  const float radA = Ltbody[4 * ba], hlA = Ltbody[4 * ba + 1];
+  const float radB = Ltbody[4 * bb], hlB = Ltbody[4 * bb + 1];
   const int axA = __float_as_int(Ltbody[4 * ba + 2]), axB = __float_as_int(Ltbody[4 * bb + 2]);
   float Ra[9], Rb[9], cp[3], cq[3], df[3];
   quat_to_mat(qa, Ra);
@@ -339,61 +344,61 @@ __device__ __forceinline__ void build_pair_rows(PairRows& c, const float* Lpq, c
   float n[3] = {0.0f, 0.0f, 1.0f};
   if (dist >= 1e-9f) { const float inv = 1.0f / dist; for (int i = 0; i < 3; ++i) n[i] = df[i] * inv; }
   const float d = dist - radA - radB;
-  float armA[3], armB[3];
+  // own body
+  const int bo = side ? bb : ba, eo = side ? eb : ea;
+  const float sg = side ? -1.0f : 1.0f;
+  float arm[3], iwo[6];
   for (int i = 0; i < 3; ++i) {
     const float pm = 0.5f * ((cp[i] - n[i] * radA) + (cq[i] + n[i] * radB));
-    armA[i] = pm - xa[i];
-    armB[i] = pm - xb[i];
+    arm[i] = pm - (side ? xb[i] : xa[i]);
   }
+  for (int i = 0; i < 6; ++i) iwo[i] = Liw[(bo * kVS + i) * E + eo];
+  const float imo = Ltbody[4 * bo + 3];
+  const float nbo = Lnb[bo * E + eo] / wk;
   float t1[3], t2[3];
   if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
   else { t1[0] = -n[2]; t1[1] = 0.0f; t1[2] = n[0]; }
   const float inv = 1.0f / sqrtf(dot(t1, t1));
   for (int i = 0; i < 3; ++i) t1[i] *= inv;
   cross(n, t1, t2);
-  for (int i = 0; i < 3; ++i) { c.dir[0][i] = n[i]; c.dir[1][i] = t1[i]; c.dir[2][i] = t2[i]; }
-  const float nbA = Lnb[ba * E + ea] / wk, nbB = Lnb[bb * E + eb] / wk;
-  c.lsA = nbA * imA; c.lsB = nbB * imB;
+  for (int i = 0; i < 3; ++i) { c.sd[0][i] = sg * n[i]; c.sd[1][i] = sg * t1[i]; c.sd[2][i] = sg * t2[i]; }
+  c.ls = nbo * imo;
   for (int r = 0; r < 3; ++r) {
-    float ya[3], yb[3];
-    cross(armA, c.dir[r], c.angA[r]);
-    cross(armB, c.dir[r], c.angB[r]);
-    sym_vec(iwa, c.angA[r], ya);
-    sym_vec(iwb, c.angB[r], yb);
-    const float keff = nbA * (imA + dot(c.angA[r], ya)) + nbB * (imB + dot(c.angB[r], yb));
+    float y[3];
+    cross(arm, c.sd[r], c.sa[r]);
+    sym_vec(iwo, c.sa[r], y);
+    const float kp = nbo * (imo + dot(c.sa[r], y));
+    const float keff = kp + lane_swap1(kp);
     c.meff[r] = keff > 0.0f ? 1.0f / keff : 0.0f;
-    for (int i = 0; i < 3; ++i) { c.YA[r][i] = nbA * ya[i]; c.YB[r][i] = nbB * yb[i]; }
+    for (int i = 0; i < 3; ++i) c.Y[r][i] = nbo * y[i];
     c.lam[r] = 0.0f;
   }
   c.bias = d >= 0.0f ? d / h : fmaxf(beta_c * d / h, -v_depen);
-  c.offA = ba * kVS * E + ea;
-  c.offB = bb * kVS * E + eb;
+  c.wk = wk;
+  c.off = bo * kVS * E + eo;
 }
 
-// One sweep of a capsule-capsule block on its private copies of the two bodies' velocities.
-__device__ __forceinline__ void relax_pair(PairRows& c, float mu, float va[3], float wa[3], float vb[3], float wb[3]) {
+// One sweep of one side of a capsule-capsule block on its private copy of the own body's velocity.
+__device__ __forceinline__ void relax_pair_side(PairSide& c, float mu, float v[3], float w[3]) {
   {
-    float jv = dot(c.dir[0], va) - dot(c.dir[0], vb) + dot(c.angA[0], wa) - dot(c.angB[0], wb);
+    const float part = dot(c.sd[0], v) + dot(c.sa[0], w);
+    const float jv = part + lane_swap1(part);
     float dl = -c.meff[0] * (jv + c.bias);
-    float ln = fmaxf(c.lam[0] + dl, 0.0f);
+    const float ln = fmaxf(c.lam[0] + dl, 0.0f);
     dl = ln - c.lam[0];
     c.lam[0] = ln;
-    for (int k = 0; k < 3; ++k) {
-      va[k] += c.lsA * c.dir[0][k] * dl; wa[k] += c.YA[0][k] * dl;
-      vb[k] -= c.lsB * c.dir[0][k] * dl; wb[k] -= c.YB[0][k] * dl;
-    }
+    for (int k = 0; k < 3; ++k) { v[k] += c.ls * c.sd[0][k] * dl; w[k] += c.Y[0][k] * dl; }
   }
-  float jv1 = dot(c.dir[1], va) - dot(c.dir[1], vb) + dot(c.angA[1], wa) - dot(c.angB[1], wb);
-  float jv2 = dot(c.dir[2], va) - dot(c.dir[2], vb) + dot(c.angA[2], wa) - dot(c.angB[2], wb);
+  const float p1 = dot(c.sd[1], v) + dot(c.sa[1], w), p2 = dot(c.sd[2], v) + dot(c.sa[2], w);
+  const float jv1 = p1 + lane_swap1(p1), jv2 = p2 + lane_swap1(p2);
   float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
-  float lim = mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
-  if (nrm > lim) { float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
-  float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
+  const float lim = mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
+  if (nrm > lim) { const float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
+  const float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
   c.lam[1] = l1; c.lam[2] = l2;
   for (int k = 0; k < 3; ++k) {
-    const float lin = c.dir[1][k] * d1 + c.dir[2][k] * d2;
-    va[k] += c.lsA * lin; wa[k] += c.YA[1][k] * d1 + c.YA[2][k] * d2;
-    vb[k] -= c.lsB * lin; wb[k] -= c.YB[1][k] * d1 + c.YB[2][k] * d2;
+    v[k] += c.ls * (c.sd[1][k] * d1 + c.sd[2][k] * d2);
+    w[k] += c.Y[1][k] * d1 + c.Y[2][k] * d2;
   }
 }
 
@@ -518,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   float* Ltin = lds + P.tin;                          // body table: inertia(3), inverse inertia(3)
   const JointTab* Ltjoint = reinterpret_cast<const JointTab*>(lds + P.tjoint);  // joint table
   float* Lpq = lds + P.pq;                            // capsule-capsule contacts, kPairWords each, sorted by key
-  float* Lpo = lds + P.po;                            // their velocity copies: A (v, w), B (v, w)
+  float* Lpo = lds + P.po;                            // their copies times the block weight: A (v, w), B (v, w)
   int* Lnear = reinterpret_cast<int*>(lds + P.pnear);
   int* Lbs = reinterpret_cast<int*>(lds + P.pbs);     // bounding radii as float bits (ordered like ints)
   int* Lpcount = reinterpret_cast<int*>(lds + P.pcount);  // contacts found, near agent pairs
@@ -578,6 +583,9 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   }
   for (int i = tid; i < M.table_words; i += kThreads) reinterpret_cast<int*>(lds + P.tjs)[i] = M.table_image[i];
   for (int i = tid; i < (J * kJS + S * kCS) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
+  if constexpr (PC != 0) {
+    if (tid < 12) Lpo[kPairCap * 12 + tid] = 0.0f;   // the entry unused list slots point at
+  }
   // contact records start cleared (a step with zero substeps packs "no contact")
   for (int i = tid; i < S * E; i += kThreads) {
     Lreci[(i / E * kRecWords + 0) * E + i % E] = 0;
@@ -652,10 +660,6 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   // joint-side role: lanes 2p and 2p+1 are the parent and the child side of pair p = (joint, env)
   const int js_side = tid & 1, js_e = (tid >> 1) % E, js_j = (tid >> 1) / E;
   const bool js_on = js_j < J && blockIdx.x * E + js_e < N;
-  SideRows jr;
-  ContactRows cr;
-  PairRows pr;
-  bool has_contact = false;  // this thread owns an active contact this substep
 
   const int tid_o = tid, e_o = e, idx_o = idx;
   const float h_o = h;
@@ -664,6 +668,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     // of each substep: what is derived from them (LDS addresses, h-scaled constants) is then
     // recomputed per substep instead of being computed once before the loop and kept alive across
     // it, which costs registers that the phases below need.
+    // row constants of this substep (declared here: nothing of them is carried into the next one)
+    SideRows jr;
+    ContactRows cr;
+    PairSide pr;
+    bool has_contact = false;  // this thread owns an active contact this substep
     int tid = tid_o, e = e_o, idx = idx_o;
     float h = h_o;
     asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
@@ -1104,18 +1113,47 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         __syncthreads();
       }
     }
-    const int my_ref = b * E + e;
+    TMARK(16);
+    // The per-body average is split over two threads when the workgroup has room: thread (e, b)
+    // takes the linear half of body b's velocity, thread (e, B + b) the angular half (a wavefront
+    // issues one instruction every five to six cycles however many others share its SIMD, so two
+    // short threads beat one long one).
+    const bool g_split = 2 * B * E <= kThreads;
+    const int g_half = (g_split && idx >= B) ? 1 : 0;
+    const int g_b = idx - g_half * B;
+    const bool g_on = env_ok && g_b < B && idx < (g_split ? 2 * B : B);
+    const int g_ref = g_b * E + e;
+    // capsule-capsule contacts of body g_b: where their (weighted) copies will be (up to kPairList
+    // of them; a body with more walks the queue in every sweep), and the sum of their weights
+    constexpr int kPairList = 6;
+    int gp_off[kPairList];
+#pragma unroll
+    for (int j = 0; j < kPairList; ++j) gp_off[j] = kPairCap * 12;
+    bool gp_many = false;
+    float gp_wsum = 0.0f;
+    if constexpr (PC != 0) {
+      if (g_on) {
+        int cnt = 0;
+        for (int k = 0; k < n_pc; ++k) {
+          const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
+          const bool ma = (refs & 0xffff) == g_ref, mb = ((refs >> 16) & 0xffff) == g_ref;
+          if (ma || mb) {
+            const int off = k * 12 + (mb ? 6 : 0);
+#pragma unroll
+            for (int j = 0; j < kPairList; ++j) gp_off[j] = cnt == j ? off : gp_off[j];
+            gp_wsum += Lpq[k * kPairWords + 4];
+            ++cnt;
+          }
+        }
+        gp_many = cnt > kPairList;
+      }
+    }
     // ---- C: block weight sums (and, on the plane, forces -> velocities)
     float nbf = 0.0f;
     if (is_body) {
       nbf = (float)my_njs;
       for (int k = 0; k < my_nslots; ++k) nbf += Lrec[((my_slot0 + k) * kRecWords + 10) * E + e];
-      if constexpr (PC != 0) {
-        for (int k = 0; k < n_pc; ++k) {
-          const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
-          if ((refs & 0xffff) == my_ref || ((refs >> 16) & 0xffff) == my_ref) nbf += Lpq[k * kPairWords + 4];
-        }
-      }
+      nbf += gp_wsum;   // (a body thread is the linear-half thread of its own body)
       Lnb[b * E + e] = nbf;
     }
     if (m_terrain == 0) forces();   // plane: no per-body pass, the torques are complete only now
@@ -1149,7 +1187,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     TMARK(4);
     // ---- D: row constants
     const int n_active = Lcount[0];
-    if (js_on) {
+    // (with the capsule-capsule contacts compiled in, the joint rows and the contact rows are
+    // built inside the wavefront-uniform branches that use them, so that the two sets of
+    // registers are never alive together)
+    auto build_joint_side = [&]() {
+     if (js_on) {
       const JointTab& jt = Ltjoint[js_j];
       const int e = js_e;
       const int ob = js_side ? jt.child : jt.parent;     // own body; -1: the static world
@@ -1221,10 +1263,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         jr.lam[k] = 0.0f;
         for (int c = 0; c < 3; ++c) { jr.sax[k][c] = sg * ak[c]; jr.Z[k][c] = sg * no * z[c]; }
       }
-    }
+     }
+    };
     // contact k of the workgroup's list goes to thread kThreads-1-k (the joint threads sit at
     // the low end); contacts beyond one per thread start from zero impulse in LDS
-    {
+    auto build_contact = [&]() {
       const int li = kThreads - 1 - tid;
       has_contact = li < n_active && li < n_reg;
       if (has_contact) {
@@ -1232,27 +1275,29 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
         build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
       }
-      for (int k = n_reg + tid; k < n_active; k += kThreads)
-        for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = 0.0f;
+    };
+    // capsule-capsule contact k of the sorted queue goes to two neighbouring lanes (body A, body B).
+    // The contact lanes start right above the joint wavefronts (whose registers are busy with the
+    // joint rows) and go up; what does not fit there goes below, into the joint wavefronts.
+    const int pk_up = (kThreads - joint_threads) >> 1;
+    const int pk = tid >= joint_threads ? (tid - joint_threads) >> 1 : pk_up + ((joint_threads - 1 - tid) >> 1);
+    const bool has_pair = PC != 0 && pk < n_pc;
+    auto build_pair = [&]() {
+      if constexpr (PC != 0) {
+        if (has_pair) build_pair_side(pr, tid & 1, Lpq, Lpos, Liw, Lnb, Lorg, Ltbody, pk, E, h, p_beta_c, p_vdepen);
+      }
+    };
+    if constexpr (PC == 0) {
+      build_joint_side();
+      build_contact();
     }
-    // capsule-capsule contact k of the sorted queue goes to thread k
-    if constexpr (PC != 0) {
-      if (tid < n_pc) build_pair_rows(pr, Lpq, Lpos, Liw, Lnb, Lorg, Ltbody, tid, E, h, p_beta_c, p_vdepen);
-    }
+    for (int k = n_reg + tid; k < n_active; k += kThreads)
+      for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = 0.0f;
 
     TMARK(5);
-    // The per-body average is split over two threads when the workgroup has room: thread (e, b)
-    // takes the linear half of body b's velocity, thread (e, B + b) the angular half (a wavefront
-    // issues one instruction every five to six cycles however many others share its SIMD, so two
-    // short threads beat one long one).  The copies a body averages: NJ joint sides (unused
-    // entries point at joint 0's copy with weight 0) and its three contact slots (weight 0 when
-    // inactive).
-    const bool g_split = 2 * B * E <= kThreads;
-    const int g_half = (g_split && idx >= B) ? 1 : 0;
-    const int g_b = idx - g_half * B;
-    const bool g_on = env_ok && g_b < B && idx < (g_split ? 2 * B : B);
+    // The copies a body averages: NJ joint sides (unused entries point at joint 0's copy with
+    // weight 0) and its three contact slots (weight 0 when inactive).
     float g_inb = 0.0f;
-    const int g_ref = g_b * E + e;
     int gat_off[NJ], gat_slot[3];
     float gat_w[NJ + 3];
     {
@@ -1301,33 +1346,42 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
 #pragma unroll
           for (int c = 0; c < 3; ++c) acc[c] += gat_w[k] * val[k][c];
         if constexpr (PC != 0) {
-          // capsule-capsule contacts that touch this body, in queue order
-          for (int k = 0; k < n_pc; ++k) {
-            const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
-            const float wk = Lpq[k * kPairWords + 4];
-            if ((refs & 0xffff) == g_ref)
-              for (int c = 0; c < 3; ++c) acc[c] += wk * Lpo[k * 12 + hsel * 3 + c];
-            if (((refs >> 16) & 0xffff) == g_ref)
-              for (int c = 0; c < 3; ++c) acc[c] += wk * Lpo[k * 12 + 6 + hsel * 3 + c];
+          if (n_pc > 0) {
+            if (gp_many) {
+              // more contacts on this body than the list holds: walk the queue
+              for (int k = 0; k < n_pc; ++k) {
+                const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
+                if ((refs & 0xffff) == g_ref)
+                  for (int c = 0; c < 3; ++c) acc[c] += Lpo[k * 12 + hsel * 3 + c];
+                if (((refs >> 16) & 0xffff) == g_ref)
+                  for (int c = 0; c < 3; ++c) acc[c] += Lpo[k * 12 + 6 + hsel * 3 + c];
+              }
+            } else {
+              // the (weighted) copies of the listed contacts; unused entries point at zeros
+              float pv[kPairList][3];
+#pragma unroll
+              for (int j = 0; j < kPairList; ++j)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) pv[j][c] = Lpo[gp_off[j] + hsel * 3 + c];
+#pragma unroll
+              for (int j = 0; j < kPairList; ++j)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) acc[c] += pv[j][c];
+            }
           }
         }
         for (int c = 0; c < 3; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = acc[c] * g_inb;
       }
     };
-    // one sweep of this thread's capsule-capsule contact, if it has one
+    // one sweep of this thread's side of a capsule-capsule contact, if it has one
     auto pair_sweep = [&]() {
       if constexpr (PC != 0) {
-        if (tid < n_pc) {
-          float va[3], wa[3], vb[3], wb[3];
-          for (int c = 0; c < 3; ++c) {
-            va[c] = Lvel[pr.offA + c * E]; wa[c] = Lvel[pr.offA + (3 + c) * E];
-            vb[c] = Lvel[pr.offB + c * E]; wb[c] = Lvel[pr.offB + (3 + c) * E];
-          }
-          relax_pair(pr, p_mu, va, wa, vb, wb);
-          for (int c = 0; c < 3; ++c) {
-            Lpo[tid * 12 + c] = va[c]; Lpo[tid * 12 + 3 + c] = wa[c];
-            Lpo[tid * 12 + 6 + c] = vb[c]; Lpo[tid * 12 + 9 + c] = wb[c];
-          }
+        if (has_pair) {
+          float vo[3], wo[3];
+          for (int c = 0; c < 3; ++c) { vo[c] = Lvel[pr.off + c * E]; wo[c] = Lvel[pr.off + (3 + c) * E]; }
+          relax_pair_side(pr, p_mu, vo, wo);
+          const int po = (2 * pk + (tid & 1)) * 6;
+          for (int c = 0; c < 3; ++c) { Lpo[po + c] = pr.wk * vo[c]; Lpo[po + 3 + c] = pr.wk * wo[c]; }
         }
       }
     };
@@ -1336,6 +1390,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       if (!g_split) gather_half(1);
     };
     if (joint_wave) {
+      if constexpr (PC != 0) { build_joint_side(); build_pair(); }
       for (int it = 0; it < a.iterations; ++it) {
         if (js_on) {
           const JointTab& jt = Ltjoint[js_j];
@@ -1377,6 +1432,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         __syncthreads();
       }
     } else {
+      if constexpr (PC != 0) { build_contact(); build_pair(); }
       for (int it = 0; it < a.iterations; ++it) {
         if (has_contact) {
           const int ee = cr.slot_e % E, sl = cr.slot_e / E;
