@@ -7,6 +7,7 @@ import numpy as np
 
 from . import build as _build
 
+SIM_PAIR_CAP = 96
 SIM_MAX_FEET = 4
 _LIB = None
 

@@ -182,3 +182,66 @@ def test_groups_do_not_interact_across_group_boundaries_and_off_switch_matches_p
     assert len(a1.get_pair_contacts()[0]) == 0
     assert np.array_equal(a0.get_state().cpu().numpy(), a1.get_state().cpu().numpy())
     a0.close(); a1.close()
+
+
+def test_parallel_and_degenerate_capsule_pairs():
+    """Parallel capsules (the search starts from the middle of the first segment), a sphere
+    against a capsule and a sphere against a sphere, side by side and touching."""
+    P = _P()
+    rob = scenes.make_loose([(0.05, 0.4, 0, (0.0, 0.0, 5.0), 1.0), (0.05, 0.3, 0, (0.05, 0.0, 6.0), 1.0),
+                             (0.06, 0.0, 0, (0.0, 1.0, 5.0), 0.5), (0.04, 0.0, 0, (0.0, 1.0, 6.0), 0.8),
+                             (0.05, 0.4, 2, (1.0, 0.0, 5.0), 1.0), (0.07, 0.0, 0, (1.0, 0.0, 6.0), 0.6)])
+    sc = scenes.make_scene(rob, scenes.make_plane(), 19, params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1))
+    st = np.repeat(scenes.rest_state(rob), 19, axis=0)
+    st[:, 1, 2] = 5.0 + 0.095          # parallel to body 0, 5 mm of overlap
+    st[:, 3, 2] = 5.0 + 0.105          # sphere on sphere, 5 mm of clearance
+    st[:, 5, 2] = 5.0 + 0.2 + 0.125    # sphere on the end of an upright capsule, 5 mm of clearance
+    st[:, 1, 9], st[:, 3, 9], st[:, 5, 9] = -0.5, -2.0, -2.5
+    sim, ref = P.Sim(sc), oracle.OracleSim(sc, threads=4)
+    sim.set_state(st); ref.set_state(st)
+    sim.record_contacts(True)
+    h = float(np.float32(1.0 / 240.0))
+    for k in range(6):
+        ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))    # identical states every substep
+        sim.step(None, h, 1, 10); ref.step(None, h, 1, 10)
+        pg, dropped = sim.get_pair_contacts()
+        po = ref.get_pair_contacts()
+        assert dropped == 0 and len(po) == 3 * 19
+        assert_same_pair_sets(pg, po)
+        if k == 0:
+            assert np.all(po["s"][po["body_a"] == 0] == 0.5)      # exactly parallel: middle of the first segment
+        e = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+        assert e.max() <= TOL_1
+    assert set(zip(po["body_a"].tolist(), po["body_b"].tolist())) == {(0, 1), (2, 3), (4, 5)}
+    sim.check(); sim.close()
+
+
+def test_more_contacts_than_a_workgroup_holds_are_counted_as_dropped():
+    """Sixteen overlapping spheres in one env: 120 touching pairs against room for 96."""
+    P = _P()
+    rng = np.random.default_rng(2)
+    rob = scenes.make_loose([(0.1, 0.0, 0, (3.0 * k, 0.0, 5.0), 1.0) for k in range(16)])
+    sc = scenes.make_scene(rob, scenes.make_plane(), 3, params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1))
+    assert len(rob.collide_pairs) == 120
+    st = np.repeat(scenes.rest_state(rob), 3, axis=0)
+    st[:, :, 0:3] = np.array([0.0, 0.0, 5.0]) + rng.normal(size=(3, 16, 3)) * 0.02
+    sim = P.Sim(sc)
+    assert sim.launch_info()["envs_per_block"] == 1
+    sim.set_state(st)
+    sim.record_contacts(True)
+    sim.step(None, 1.0 / 240.0, 1, 4)
+    pg, dropped = sim.get_pair_contacts()
+    assert len(pg) == 3 * P.binding.SIM_PAIR_CAP and dropped == 3 * (120 - P.binding.SIM_PAIR_CAP)
+    sim.check(); sim.close()
+
+
+def test_envs_per_block_must_hold_whole_groups():
+    P = _P()
+    rob, sc = _humanoid_scene(24, 4, 1.0)
+    sim = P.Sim(sc)
+    assert sim.launch_info()["envs_per_block"] % 4 == 0
+    with pytest.raises(P.SimError):
+        sim.set_envs_per_block(6)
+    sim.set_envs_per_block(8)
+    sim.step(None, 1.0 / 60.0, 2, 4)
+    sim.check(); sim.close()

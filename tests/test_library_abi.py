@@ -51,6 +51,36 @@ def test_workspace_size_and_description_validation_need_no_gpu():
         P.sim_workspace_bytes(d3, 10)
 
 
+def test_collision_description_validation_needs_no_gpu():
+    import ctypes as C
+    import numpy as np
+    import paper_1810_05762_amd as P
+    rob = scenes.make_humanoid()
+    sc = scenes.make_scene(rob, scenes.make_plane(), 64, params=scenes.SimParams(self_collide=1, group_size=4), spacing=1.0)
+    d, keep = P.make_desc(sc)
+    assert d.n_collide_pairs == len(rob.collide_pairs) > 0 and d.group_size == 4
+    plain, _k = P.make_desc(scenes.make_scene(rob, scenes.make_plane(), 64))
+    assert P.sim_workspace_bytes(d, 64) > P.sim_workspace_bytes(plain, 64)   # room for the contact records
+    # the list never names two bodies that a joint connects
+    joined = {(min(a, b), max(a, b)) for a, b in zip(rob.j_parent, rob.j_child)}
+    assert not joined & {tuple(p) for p in rob.collide_pairs.tolist()}
+    for field, value in (("group_size", 17), ("group_size", -1), ("n_collide_pairs", 500)):
+        d2, keep2 = P.make_desc(sc)
+        setattr(d2, field, value)
+        with pytest.raises(P.SimError):
+            P.sim_workspace_bytes(d2, 64)
+    for bad in ((3, 3), (5, 2), (0, 13), (-1, 2)):
+        d2, keep2 = P.make_desc(sc)
+        arr = np.array([bad], np.int32)
+        d2.n_collide_pairs, d2.collide_pairs = 1, arr.ctypes.data_as(C.POINTER(C.c_int32))
+        with pytest.raises(P.SimError):
+            P.sim_workspace_bytes(d2, 64)
+    d2, keep2 = P.make_desc(sc)
+    d2.collide_pairs = None
+    with pytest.raises(P.SimError):
+        P.sim_workspace_bytes(d2, 64)
+
+
 def test_product_package_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_1810_05762_amd")
     for dirpath, _, files in os.walk(pkg):
