@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--envs-per-block", type=int, default=0)
     ap.add_argument("--num-envs", type=int, default=0, help="override the number of envs (scaling runs)")
     ap.add_argument("--height-map", action="store_true", help="append the 15 x 11 height map to the observation")
+    ap.add_argument("--self-collide", action="store_true", help="capsules of one robot collide with each other")
+    ap.add_argument("--group-size", type=int, default=1, help="agents per interaction group (inter-agent collisions)")
+    ap.add_argument("--spacing", type=float, default=1.5, help="distance between the agents of a group, metres")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -74,6 +77,13 @@ def main():
     scene, cfg = scenes.config_scene(args.config, num_envs=args.num_envs or None)
     if args.height_map:
         scene.params.height_map = 1
+    collide = args.self_collide or args.group_size > 1
+    if collide:
+        # the same robots, terrain and stepping parameters with capsule-capsule collisions on
+        scene.params.self_collide = 1 if args.self_collide else 0
+        scene.params.group_size = args.group_size
+        scene = scenes.make_scene(scene.robot, scene.terrain, scene.num_envs, seed=cfg["seed"], params=scene.params,
+                                  name=cfg["name"], spacing=args.spacing if args.group_size > 1 else None)
     N, rob = scene.num_envs, scene.robot
     sim = P.Sim(scene, device=dev)
     if args.envs_per_block:
@@ -125,7 +135,18 @@ def main():
     # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
     # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.6 MB
     # read + 5.3 MB written (summary under profiles/); other sizes were not measured
-    traffic = 14.0e6 if (args.config == 3 and N == 4096 and not args.height_map) else None
+    traffic = 14.0e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide) else None
+    pair_info = {}
+    if collide:
+        sim.record_contacts(True)
+        one_step(0)
+        pc, dropped = sim.get_pair_contacts(cap=64 * N)
+        sim.record_contacts(False)
+        pair_info = {"self_collide": int(args.self_collide), "group_size": args.group_size,
+                     "spacing_m": args.spacing if args.group_size > 1 else None,
+                     "capsule_contacts_per_env": round(len(pc) / N, 3),
+                     "capsule_contacts_between_agents_per_env": round(float((pc["env_a"] != pc["env_b"]).sum()) / N, 3),
+                     "capsule_contacts_dropped": dropped}
     peak_tflops = 157.3
     value = N * args.steps / elapsed
     out = {
@@ -133,13 +154,14 @@ def main():
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": (cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else ""),
+        "config": {"workload": (cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")
+                               + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else ""),
                    "num_envs": N, "obs_dim": sim.obs_dim, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
                    "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
                    "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 1,
-                   **sim.launch_info()},
+                   **sim.launch_info(), **pair_info},
         "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,
                      "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": traffic,
                      "flops_per_env_step": fl, "kernel_ms": kern_ms},
@@ -158,7 +180,7 @@ def main():
         import oracle
         n_s = min(N, 256)
         sub_scene, _ = scenes.config_scene(args.config, num_envs=n_s)
-        sub_scene.params.height_map = scene.params.height_map
+        sub_scene.params = scene.params
         sub_scene.env_origins = scene.env_origins[:n_s].copy()
         cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
         cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
@@ -180,7 +202,7 @@ def main():
         # the same oracle on one thread (the paper's CPU comparison is single-core), 16 envs, about 3 s
         n_1 = min(N, 16)
         one_scene, _ = scenes.config_scene(args.config, num_envs=n_1)
-        one_scene.params.height_map = scene.params.height_map
+        one_scene.params = scene.params
         one_scene.env_origins = scene.env_origins[:n_1].copy()
         ref1 = oracle.OracleSim(one_scene, threads=1)
         ref1.set_state(sim.get_state().cpu().numpy()[:n_1].astype(np.float64))
