@@ -63,10 +63,10 @@ static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, si
   L.task_i = o; o = align_up(o + (size_t)N * 4 * sizeof(int32_t));
   L.reset_flag = o; o = align_up(o + (size_t)N);
   L.push = o; o = align_up(o + (size_t)N * 3 * sizeof(float));
-  L.flag = o; o = align_up(o + 256);
   // capsule-capsule contact records: one workgroup may hold as few as one env
   L.pair_recs = o; o = align_up(o + (pairs ? (size_t)N * kPairCap * sizeof(sim_pair_contact_rec_t) : 0));
   L.pair_count = o; o = align_up(o + (pairs ? (size_t)N * sizeof(int32_t) : 0));
+  L.flag = o; o = align_up(o + 256);   // (last: the diagnostic build keeps its counters here)
   L.total = o;
   return L;
 }

@@ -1,6 +1,7 @@
 """Where the step kernel's time goes: cycle counters around its phases.
 
     python3 paper_1810_05762_amd/phase_timing.py [--config 3] [--steps 20]
+                                                 [--self-collide] [--group-size G --spacing S]
 
 Builds the diagnostic variant of the library (-DSIM_PHASE_TIMING), runs the benchmark's workload
 (60 settle steps, then `steps` measured ones) and prints, per env-step, the cycles thread 0 of one
@@ -27,6 +28,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--self-collide", action="store_true")
+    ap.add_argument("--group-size", type=int, default=1)
+    ap.add_argument("--spacing", type=float, default=1.5)
     args = ap.parse_args()
     import torch
     import scenes
@@ -35,6 +39,10 @@ def main():
     import paper_1810_05762_amd as P
 
     sc, cfg = scenes.config_scene(args.config)
+    if args.self_collide or args.group_size > 1:
+        sc.params.self_collide, sc.params.group_size = int(args.self_collide), args.group_size
+        sc = scenes.make_scene(sc.robot, sc.terrain, sc.num_envs, seed=cfg["seed"], params=sc.params, name=cfg["name"],
+                               spacing=args.spacing if args.group_size > 1 else None)
     N, D = sc.num_envs, sc.robot.n_dofs
     sim = P.Sim(sc)
     if cfg["fallen"]:
