@@ -1190,9 +1190,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     // (with the capsule-capsule contacts compiled in, the joint rows and the contact rows are
     // built inside the wavefront-uniform branches that use them, so that the two sets of
     // registers are never alive together)
+    // (With the capsule-capsule contacts compiled in, every lane of the wavefronts concerned builds
+    // rows, the idle ones from a clamped index: a value assigned on every path is not carried from
+    // one substep into the next in registers, as a conditionally assigned one is.)
     auto build_joint_side = [&]() {
-     if (js_on) {
-      const JointTab& jt = Ltjoint[js_j];
+     {
+      const JointTab& jt = Ltjoint[js_j < J ? js_j : J - 1];
       const int e = js_e;
       const int ob = js_side ? jt.child : jt.parent;     // own body; -1: the static world
       const bool ghost = ob < 0;
@@ -1270,10 +1273,12 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     auto build_contact = [&]() {
       const int li = kThreads - 1 - tid;
       has_contact = li < n_active && li < n_reg;
-      if (has_contact) {
-        const int i = Llist[li];
+      if (n_active > 0) {
+        const int i = Llist[li < n_active ? li : n_active - 1];
         const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
         build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
+      } else {
+        cr = ContactRows{};
       }
     };
     // capsule-capsule contact k of the sorted queue goes to two neighbouring lanes (body A, body B).
@@ -1284,13 +1289,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     const bool has_pair = PC != 0 && pk < n_pc;
     auto build_pair = [&]() {
       if constexpr (PC != 0) {
-        if (has_pair) build_pair_side(pr, tid & 1, Lpq, Lpos, Liw, Lnb, Lorg, Ltbody, pk, E, h, p_beta_c, p_vdepen);
+        if (n_pc > 0) build_pair_side(pr, tid & 1, Lpq, Lpos, Liw, Lnb, Lorg, Ltbody, pk < n_pc ? pk : n_pc - 1, E, h, p_beta_c, p_vdepen);
+        else pr = PairSide{};
       }
     };
-    if constexpr (PC == 0) {
-      build_joint_side();
-      build_contact();
-    }
     for (int k = n_reg + tid; k < n_active; k += kThreads)
       for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = 0.0f;
 
@@ -1390,7 +1392,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       if (!g_split) gather_half(1);
     };
     if (joint_wave) {
-      if constexpr (PC != 0) { build_joint_side(); build_pair(); }
+      build_joint_side();
+      build_pair();
       for (int it = 0; it < a.iterations; ++it) {
         if (js_on) {
           const JointTab& jt = Ltjoint[js_j];
@@ -1432,7 +1435,8 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
         __syncthreads();
       }
     } else {
-      if constexpr (PC != 0) { build_contact(); build_pair(); }
+      build_contact();
+      build_pair();
       for (int it = 0; it < a.iterations; ++it) {
         if (has_contact) {
           const int ee = cr.slot_e % E, sl = cr.slot_e / E;

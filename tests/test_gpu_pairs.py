@@ -165,9 +165,10 @@ def test_humanoids_with_collisions(group, terrain, n_envs):
     sim.check(); sim.close()
 
 
-def test_groups_do_not_interact_across_group_boundaries_and_off_switch_matches_plain_kernel():
+def test_distant_groups_do_not_interact_and_variant_matches_plain_kernel():
     """With collisions compiled in but nothing close enough to touch, the states equal those of the
-    plain kernel bit for bit (the extra phase changes nothing else)."""
+    plain kernel up to rounding (two instantiations of the kernel: the compiler may contract
+    multiply-adds differently; the extra phase changes nothing else)."""
     P = _P()
     n = 35
     rob = scenes.make_humanoid()
@@ -180,7 +181,8 @@ def test_groups_do_not_interact_across_group_boundaries_and_off_switch_matches_p
         a = scenes.actions_for_step(2, s, n, rob.n_dofs)
         a0.step(a, 1.0 / 60.0, 4, 20); a1.step(a, 1.0 / 60.0, 4, 20)
     assert len(a1.get_pair_contacts()[0]) == 0
-    assert np.array_equal(a0.get_state().cpu().numpy(), a1.get_state().cpu().numpy())
+    e = rel_err(a1.get_state().cpu().numpy().astype(np.float64), a0.get_state().cpu().numpy().astype(np.float64))
+    assert e.max() <= TOL_1
     a0.close(); a1.close()
 
 
