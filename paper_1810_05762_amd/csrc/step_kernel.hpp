@@ -664,10 +664,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const int tid_o = tid, e_o = e, idx_o = idx;
   const float h_o = h;
   for (int sub = 0; sub < a.substeps; ++sub) {
-    // The thread's indices and the time step are passed through empty asm statements at the top
-    // of each substep: what is derived from them (LDS addresses, h-scaled constants) is then
-    // recomputed per substep instead of being computed once before the loop and kept alive across
-    // it, which costs registers that the phases below need.
+    // In the collision variant the thread's indices and the time step are passed through empty asm
+    // statements at the top of each substep: what is derived from them (LDS addresses, h-scaled
+    // constants) is then recomputed per substep instead of being computed once before the loop and
+    // kept alive across it, which costs registers that variant does not have.  The plain variants
+    // have them to spare and let the compiler hoist.
     // row constants of this substep (declared here: nothing of them is carried into the next one)
     SideRows jr;
     ContactRows cr;
@@ -675,8 +676,10 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     bool has_contact = false;  // this thread owns an active contact this substep
     int tid = tid_o, e = e_o, idx = idx_o;
     float h = h_o;
-    asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
-    asm volatile("" : "+s"(h));
+    if constexpr (PC != 0) {
+      asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
+      asm volatile("" : "+s"(h));
+    }
     const int b = idx;
     // ---- A: publish pose and world inverse inertia
     if (tid == 0) { Lcount[0] = 0; Lcount[1] = 0; Lcount[2] = 0; Lcount[3] = 0; Lcount[4] = 0; Lcount[5] = 0; Lcount[6] = 0; Lcount[7] = 0; }
