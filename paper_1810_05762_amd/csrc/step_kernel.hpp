@@ -35,7 +35,7 @@
 
 namespace sim355 {
 
-constexpr int kThreads = 512;
+constexpr int kThreads = 768;
 constexpr int kGroup = 8;  // lanes that share the fine terrain search of one slot
 constexpr int kPatch = 28; // samples per side of the per-env heightfield copy kept in LDS
 constexpr int kPatchBlocks = (kPatch + kMip - 1) / kMip;
@@ -676,7 +676,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     bool has_contact = false;  // this thread owns an active contact this substep
     int tid = tid_o, e = e_o, idx = idx_o;
     float h = h_o;
-    if constexpr (PC != 0) {
+    {
       asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
       asm volatile("" : "+s"(h));
     }
@@ -980,7 +980,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
       // ---- B3: one thread per queued slot turns the selected feature into a contact record
       //          (end spheres on the lower half of the workgroup, mid-segments on the upper half,
       //          so that a wavefront follows one path)
-      for (int sv = tid & (kThreads / 2 - 1); sv < (tid < kThreads / 2 ? n_end : n_mid); sv += kThreads / 2) {
+      for (int sv = tid < kThreads / 2 ? tid : tid - kThreads / 2; sv < (tid < kThreads / 2 ? n_end : n_mid); sv += kThreads / 2) {
         const int qi = tid < kThreads / 2 ? sv : S * E - 1 - sv;
         const int i = Lsurv[qi];
         const int ee = i % E, s = i / E;
