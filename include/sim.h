@@ -129,7 +129,7 @@ typedef struct sim_desc {
  *    seeded by seed and the env's episode index); the observation delivered for it is the first
  *    one of the new episode, reward and done are those of the step that ended the old one.
  * Every draw comes from the counter-based generator of sim_reset keyed by (seed, episode, env,
- * frame), so a run is reproducible and independent of the launch shape. */
+ * frame), so they are reproducible and do not depend on the launch shape. */
 typedef struct sim_task_desc {
   int32_t enabled, fall_grace_frames, target_period, push_min_frames, push_max_frames, auto_reset;
   double target_reach, target_radius, push_min_newton, push_max_newton;
@@ -244,7 +244,9 @@ int sim_check(sim_t* sim, void* stream);
  * workgroup (grid = ceil(num_envs / envs_per_block)).  Any output pointer may be NULL. */
 int sim_launch_info(const sim_t* sim, int32_t* threads_per_block, int32_t* envs_per_block, size_t* lds_bytes);
 
-/* Launch shape of sim_step: envs per workgroup (0 = library default). */
+/* Launch shape of sim_step: envs per workgroup (0 = library default).  Results are bit-reproducible
+ * for a given launch shape, and contact sets are the same for all; the continuous state of two
+ * launch shapes agrees to rounding (they run different instantiations of the kernel). */
 int sim_set_envs_per_block(sim_t* sim, int envs_per_block);
 
 /* Message for the last error on the calling thread (never NULL). */

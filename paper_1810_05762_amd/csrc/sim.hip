@@ -253,9 +253,15 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
 
 // does this model generate capsule-capsule contacts, and with which group size (0: no)
 static int pairs_of(const Model& m) { return (m.n_pairs > 0 || m.group > 1) ? (m.group > 1 ? m.group : 1) : 0; }
+// Threads per workgroup of the step launch: the wide workgroup pays off for full workgroups on the
+// heightfield (more lanes for the contact search); small batches and the collision variant (which
+// needs the registers) keep the narrow one.
+static int threads_for(const Model& m, int E) {
+  return (E == 16 && m.terrain_kind == 1 && m.max_joint_sides <= 4 && !pairs_of(m)) ? kThreadsWide : kThreads;
+}
 static LdsPlan plan_for(const Model& m, int E) {
   const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
-  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m));
+  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m), threads_for(m, E));
 }
 
 static int default_envs_per_block(const Model& m, int N) {
@@ -478,15 +484,17 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   size_t lds_bytes = (size_t)P.total * sizeof(float);
   if (lds_bytes > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d needs %zu bytes of LDS (limit 160 KiB)", s->E, lds_bytes);
   int grid = (s->N + s->E - 1) / s->E;
+  const int threads = threads_for(m, s->E);
   auto launch = [&](auto kern) -> int {
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes));
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds_bytes, st, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds_bytes, st, a);
     return SIM_OK;
   };
   const bool few = m.max_joint_sides <= 4;
   int lrc = pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
                      : few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
+            : threads == kThreadsWide ? launch(&step_kernel<16, 4, 0, kThreadsWide>)
             : (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
             : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
             : (s->E == 4 && few) ? launch(&step_kernel<4, 4>)
@@ -599,7 +607,7 @@ extern "C" int sim_act_dim(const sim_t* s) { return s ? s->host_model.D : fail(S
 extern "C" int sim_launch_info(const sim_t* s, int32_t* threads_per_block, int32_t* envs_per_block, size_t* lds_bytes) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
   const Model& m = s->host_model;
-  if (threads_per_block) *threads_per_block = kThreads;
+  if (threads_per_block) *threads_per_block = threads_for(m, s->E);
   if (envs_per_block) *envs_per_block = s->E;
   if (lds_bytes) *lds_bytes = (size_t)plan_for(m, s->E).total * sizeof(float);
   return SIM_OK;

@@ -35,7 +35,8 @@
 
 namespace sim355 {
 
-constexpr int kThreads = 768;
+constexpr int kThreads = 512;       // threads per workgroup every shape fits (host-side limits)
+constexpr int kThreadsWide = 768;   // the wider workgroup the big heightfield batches are run with
 constexpr int kGroup = 8;  // lanes that share the fine terrain search of one slot
 constexpr int kPatch = 28; // samples per side of the per-env heightfield copy kept in LDS
 constexpr int kPatchBlocks = (kPatch + kMip - 1) / kMip;
@@ -79,7 +80,8 @@ struct LdsPlan {
 };
 
 // pairs: 0 = no capsule-capsule contacts, else the interaction group size (1 = self-collision only)
-__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch, int pairs = 0) {
+__host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch, int pairs = 0,
+                                             int threads = kThreads) {
   LdsPlan p;
   int o = 0;
   p.pos = o; o += B * 7 * E;
@@ -94,7 +96,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
   p.surv = o; o += S * E;
-  p.lam = o; o += 3 * (S * E > kThreads - ((2 * J * E + 63) / 64) * 64 ? S * E - (kThreads - ((2 * J * E + 63) / 64) * 64) : 0);
+  p.lam = o; o += 3 * (S * E > threads - ((2 * J * E + 63) / 64) * 64 ? S * E - (threads - ((2 * J * E + 63) / 64) * 64) : 0);
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
   p.lim = o; o += (D > 0 ? D : 1) * E;
@@ -462,8 +464,10 @@ __device__ __forceinline__ int wave_alloc(int n, int* counter) {
 }
 
 // PC != 0: capsule-capsule contacts (within an agent and between the agents of a group) compiled in.
-template <int EC, int NJ, int PC = 0>
-__global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
+// NT: threads per workgroup.
+template <int EC, int NJ, int PC = 0, int NT = kThreads>
+__global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
+  constexpr int kThreads = NT;   // (shadows the namespace-scope default inside the kernel)
 #ifdef SIM_PHASE_TIMING
   long long t_last = clock64();
 #endif
@@ -485,7 +489,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const Field H0 = make_field(M, a.heights, a.coarse);
   const bool use_patch = m_terrain == 1 && H0.nx >= kPatch && H0.ny >= kPatch;
   const int m_group = PC ? (M.group > 1 ? M.group : 1) : 1, m_npairs = PC ? M.n_pairs : 0, m_nap = PC ? M.n_agent_pairs : 0;
-  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0);
+  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0, NT);
   float* Lpos = lds + P.pos;
   float* Lvel = lds + P.vel;
   float* Liw = lds + P.iw;
@@ -664,11 +668,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
   const int tid_o = tid, e_o = e, idx_o = idx;
   const float h_o = h;
   for (int sub = 0; sub < a.substeps; ++sub) {
-    // In the collision variant the thread's indices and the time step are passed through empty asm
-    // statements at the top of each substep: what is derived from them (LDS addresses, h-scaled
+    // In the variants that are short of registers (capsule-capsule collisions, or the wide workgroup
+    // with its 170 VGPRs per thread) the thread's indices and the time step are passed through empty
+    // asm statements at the top of each substep: what is derived from them (LDS addresses, h-scaled
     // constants) is then recomputed per substep instead of being computed once before the loop and
-    // kept alive across it, which costs registers that variant does not have.  The plain variants
-    // have them to spare and let the compiler hoist.
+    // kept alive across it.  The others have registers to spare and let the compiler hoist.
     // row constants of this substep (declared here: nothing of them is carried into the next one)
     SideRows jr;
     ContactRows cr;
@@ -676,7 +680,7 @@ __global__ __launch_bounds__(kThreads) void step_kernel(StepArgs a) {
     bool has_contact = false;  // this thread owns an active contact this substep
     int tid = tid_o, e = e_o, idx = idx_o;
     float h = h_o;
-    {
+    if constexpr (PC != 0 || NT > 512) {
       asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
       asm volatile("" : "+s"(h));
     }
