@@ -30,6 +30,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "contact_gen.hpp"
 #include "model.hpp"
 
@@ -1121,14 +1123,16 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       }
     }
     TMARK(16);
-    // The per-body average is split over two threads when the workgroup has room: thread (e, b)
-    // takes the linear half of body b's velocity, thread (e, B + b) the angular half (a wavefront
-    // issues one instruction every five to six cycles however many others share its SIMD, so two
-    // short threads beat one long one).
-    const bool g_split = 2 * B * E <= kThreads;
-    const int g_half = (g_split && idx >= B) ? 1 : 0;
+    // The per-body average is split over several threads when the workgroup has room: thread (e, b)
+    // takes the linear half of body b's velocity, thread (e, B + b) the angular half; in the wide
+    // workgroup three threads take two components each (a wavefront issues one instruction every
+    // five to six cycles however many others share its SIMD, so short threads beat a long one).
+    // (the wide workgroup always has room for three threads per body: 3 * 16 bodies * 16 envs)
+    constexpr bool g_three = NT >= 768 && EC == 16;
+    const bool g_split = g_three || 2 * B * E <= kThreads;
+    const int g_half = g_three ? (idx < B ? 0 : (idx < 2 * B ? 1 : 2)) : ((g_split && idx >= B) ? 1 : 0);
     const int g_b = idx - g_half * B;
-    const bool g_on = env_ok && g_b < B && idx < (g_split ? 2 * B : B);
+    const bool g_on = env_ok && g_b < B && idx < (g_three ? 3 * B : (g_split ? 2 * B : B));
     const int g_ref = g_b * E + e;
     // capsule-capsule contacts of body g_b: where their (weighted) copies will be (up to kPairList
     // of them; a body with more walks the queue in every sweep), and the sum of their weights
@@ -1160,7 +1164,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     if (is_body) {
       nbf = (float)my_njs;
       for (int k = 0; k < my_nslots; ++k) nbf += Lrec[((my_slot0 + k) * kRecWords + 10) * E + e];
-      nbf += gp_wsum;   // (a body thread is the linear-half thread of its own body)
+      nbf += gp_wsum;   // (a body thread is the first averaging thread of its own body)
       Lnb[b * E + e] = nbf;
     }
     if (m_terrain == 0) forces();   // plane: no per-body pass, the torques are complete only now
@@ -1332,28 +1336,31 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     // Wavefronts that hold joint threads run only the joint rows, the others only the contact
     // rows (a wave-uniform branch, so neither path carries the other's registers); both paths
     // execute the same two barriers per sweep.
-    // one half (0 linear, 1 angular) of the average of body g_b
-    auto gather_half = [&](int hsel) {
+    // components [c0, c0 + NC) of the average of body g_b (0..2 linear, 3..5 angular velocity)
+    auto gather_part = [&](auto nc_tag, int c0) {
+      constexpr int NC = decltype(nc_tag)::value;
       if (g_on && g_inb > 0.0f) {
         // every load is unconditional: unused entries read a valid location and enter the sum
         // with weight 0 (the copy arrays only ever hold finite numbers); all reads are issued
         // before the first use so their LDS latency is paid once
-        const int ho = hsel * 3 * E;
-        float val[NJ + 3][3];
+        const int ho = c0 * E;
+        float val[NJ + 3][NC];
 #pragma unroll
         for (int k = 0; k < NJ; ++k)
 #pragma unroll
-          for (int c = 0; c < 3; ++c) val[k][c] = Loutj[gat_off[k] + ho + c * E];
+          for (int c = 0; c < NC; ++c) val[k][c] = Loutj[gat_off[k] + ho + c * E];
 #pragma unroll
         for (int k = 0; k < 3; ++k)
 #pragma unroll
-          for (int c = 0; c < 3; ++c) val[NJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
-        __builtin_amdgcn_sched_group_barrier(0x100, (NJ + 3) * 2, 0);  // the DS reads first
-        float acc[3] = {0, 0, 0};
+          for (int c = 0; c < NC; ++c) val[NJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
+        __builtin_amdgcn_sched_group_barrier(0x100, NC == 3 ? (NJ + 3) * 2 : NJ + 3, 0);  // the DS reads first
+        float acc[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
 #pragma unroll
         for (int k = 0; k < NJ + 3; ++k)
 #pragma unroll
-          for (int c = 0; c < 3; ++c) acc[c] += gat_w[k] * val[k][c];
+          for (int c = 0; c < NC; ++c) acc[c] += gat_w[k] * val[k][c];
         if constexpr (PC != 0) {
           if (n_pc > 0) {
             if (gp_many) {
@@ -1361,25 +1368,25 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
               for (int k = 0; k < n_pc; ++k) {
                 const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
                 if ((refs & 0xffff) == g_ref)
-                  for (int c = 0; c < 3; ++c) acc[c] += Lpo[k * 12 + hsel * 3 + c];
+                  for (int c = 0; c < NC; ++c) acc[c] += Lpo[k * 12 + c0 + c];
                 if (((refs >> 16) & 0xffff) == g_ref)
-                  for (int c = 0; c < 3; ++c) acc[c] += Lpo[k * 12 + 6 + hsel * 3 + c];
+                  for (int c = 0; c < NC; ++c) acc[c] += Lpo[k * 12 + 6 + c0 + c];
               }
             } else {
               // the (weighted) copies of the listed contacts; unused entries point at zeros
-              float pv[kPairList][3];
+              float pv[kPairList][NC];
 #pragma unroll
               for (int j = 0; j < kPairList; ++j)
 #pragma unroll
-                for (int c = 0; c < 3; ++c) pv[j][c] = Lpo[gp_off[j] + hsel * 3 + c];
+                for (int c = 0; c < NC; ++c) pv[j][c] = Lpo[gp_off[j] + c0 + c];
 #pragma unroll
               for (int j = 0; j < kPairList; ++j)
 #pragma unroll
-                for (int c = 0; c < 3; ++c) acc[c] += pv[j][c];
+                for (int c = 0; c < NC; ++c) acc[c] += pv[j][c];
             }
           }
         }
-        for (int c = 0; c < 3; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = acc[c] * g_inb;
+        for (int c = 0; c < NC; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = acc[c] * g_inb;
       }
     };
     // one sweep of this thread's side of a capsule-capsule contact, if it has one
@@ -1395,8 +1402,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       }
     };
     auto gather = [&]() {
-      gather_half(g_half);
-      if (!g_split) gather_half(1);
+      if constexpr (g_three) {
+        gather_part(std::integral_constant<int, 2>{}, 2 * g_half);   // two components per thread
+      } else {
+        gather_part(std::integral_constant<int, 3>{}, 3 * g_half);   // linear or angular half
+        if (!g_split) gather_part(std::integral_constant<int, 3>{}, 3);
+      }
     };
     if (joint_wave) {
       build_joint_side();
