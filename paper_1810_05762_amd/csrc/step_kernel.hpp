@@ -543,6 +543,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   // ---- load: body state into registers, clipped actions into LDS
   float x[3] = {0, 0, 0}, q[4] = {1, 0, 0, 0}, v[3] = {0, 0, 0}, w[3] = {0, 0, 0};
   int my_slot0 = 0, my_nslots = 0, my_njs = 0;
+  float root_ox = 0.0f, root_oy = 0.0f;
   const int b = idx;
   if (is_body) {
     const float* st = a.state + (size_t)b * N + env;
@@ -553,6 +554,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     w[0] = st[10 * fs]; w[1] = st[11 * fs]; w[2] = st[12 * fs];
     const BodyTab& bt = M.bodies[b];
     my_slot0 = bt.slot0; my_nslots = bt.n_slots; my_njs = bt.n_joint_sides;
+    if (b == M.root) { root_ox = a.origins[3 * env]; root_oy = a.origins[3 * env + 1]; }   // for the heightfield copy
   }
   // uniform parameters and this thread's joint, read once
   const float g0 = M.g[0], g1 = M.g[1], g2 = M.g[2];
@@ -603,27 +605,23 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   // per-env copy of the heightfield samples around the root body (the whole robot stays
   // within it during one step; anything outside falls back to global memory)
   if (use_patch && a.substeps > 0) {   // (a launch without substeps never searches the terrain)
-    if (tid < E) {
-      int env_e = blockIdx.x * E + tid;
-      int pi0 = 0, pj0 = 0;
-      if (env_e < N) {
-        const size_t fs = (size_t)B * N;
-        float rx = a.state[0 * fs + (size_t)M.root * N + env_e] + a.origins[3 * env_e];
-        float ry = a.state[1 * fs + (size_t)M.root * N + env_e] + a.origins[3 * env_e + 1];
-        float ci = floorf((rx - M.hox) * M.inv_cell), cj = floorf((ry - M.hoy) * M.inv_cell);
-        ci = fminf(fmaxf(ci - (float)(kPatch / 2), 0.0f), (float)(M.nx - kPatch));
-        cj = fminf(fmaxf(cj - (float)(kPatch / 2), 0.0f), (float)(M.ny - kPatch));
-        pi0 = (int)ci; pj0 = (int)cj;
-      }
-      Lporg[2 * tid] = pi0; Lporg[2 * tid + 1] = pj0;
+    // where the copy starts: from the root body's position, which its body thread has just loaded
+    if (is_body && b == M.root) {
+      const float rx = x[0] + root_ox, ry = x[1] + root_oy;
+      float ci = floorf((rx - M.hox) * M.inv_cell), cj = floorf((ry - M.hoy) * M.inv_cell);
+      ci = fminf(fmaxf(ci - (float)(kPatch / 2), 0.0f), (float)(M.nx - kPatch));
+      cj = fminf(fmaxf(cj - (float)(kPatch / 2), 0.0f), (float)(M.ny - kPatch));
+      Lporg[2 * e] = (int)ci; Lporg[2 * e + 1] = (int)cj;
     }
+    if (tid < E && blockIdx.x * E + tid >= N) { Lporg[2 * tid] = 0; Lporg[2 * tid + 1] = 0; }
     __syncthreads();
-    // thirteen samples per thread in flight at a time (the reads come from L2, one at a time each
-    // would cost its full latency)
-    for (int i0 = tid; i0 < E * kPatch * kPatch; i0 += 13 * kThreads) {
-      float hv[13];
+    // many samples per thread in flight at a time (the reads come from L2, one at a time each
+    // would cost its full latency): the wide workgroup fetches the copies of 16 envs in one round
+    constexpr int kInFlight = NT >= 768 ? 17 : 13;
+    for (int i0 = tid; i0 < E * kPatch * kPatch; i0 += kInFlight * kThreads) {
+      float hv[kInFlight];
 #pragma unroll
-      for (int k = 0; k < 13; ++k) {
+      for (int k = 0; k < kInFlight; ++k) {
         const int i = i0 + k * kThreads;
         hv[k] = 0.0f;
         if (i < E * kPatch * kPatch) {
@@ -632,7 +630,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         }
       }
 #pragma unroll
-      for (int k = 0; k < 13; ++k)
+      for (int k = 0; k < kInFlight; ++k)
         if (i0 + k * kThreads < E * kPatch * kPatch) Lpatch[i0 + k * kThreads] = hv[k];
     }
     __syncthreads();
