@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 
 import numpy as np
 
-# ---- algorithmic work per env-step (model stated in the design doc, FMA = 2 flops) ----
+# ---- algorithmic work per env-step (one FMA counts as 2 flops) ----
 F_JOINT_SWEEP = 156.0     # 3 positional rows x 27 + 3 angular rows x 25
 F_CONTACT_SWEEP = 95.0    # normal row 29 + friction pair 66
 F_JOINT_SETUP = 420.0     # two rotation matrices, anchors, 6 effective masses and responses, joint angles

@@ -10,7 +10,7 @@
  * contacts as unilateral constraints, isotropic Coulomb friction, restitution
  * 0, implicit-style velocity-level time stepping.  The paper's Newton/Krylov
  * solver is replaced by a fixed-count projected-Jacobi iteration; where the
- * paper is silent the readings are listed in the design document.
+ * paper is silent a reading is taken and stated where it is used.
  * Observation: Table 2 ("Ours").  Reward: Eq. (1)-(3).  Episode rules: Section
  * 4.1 (fall threshold, 1000-frame cap).
  */
