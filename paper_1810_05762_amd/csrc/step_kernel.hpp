@@ -1022,8 +1022,9 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     // ---- P: capsule-capsule contacts from the poses published in phase A (Section 3.1: contacts
     //         among bodies; Section 4.1: inter-agent collisions).  Candidates: the listed body pairs
     //         of every agent, and every body pair of two agents of one group whose bounding spheres
-    //         overlap.  A candidate passes a bounding-sphere test, then the segment-segment test in
-    //         the fixed operation order; hits are queued and the queue is sorted by candidate key, so
+    //         overlap.  A candidate passes a bounding-sphere test (stage 1, which compacts the
+    //         survivors into a list), then the segment-segment test in the fixed operation order
+    //         (stage 2, one survivor per lane); hits are queued and the queue is sorted by key, so
     //         that the order in which the bodies later add up their contacts does not depend on which
     //         wavefront found what first.
     int n_pc = 0;
@@ -1090,21 +1091,54 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
             Ltmp[pos * kPairWords + 5] = gap;
           }
         };
+        // Stage 1: bounding spheres of the two capsules only; what passes is listed as a packed word
+        // (env and body of A, env and body of B: also the sort key of a hit).  The list lives where
+        // the observations are staged at the end of the step.
+        unsigned* Lc2 = Lunit;
+        auto cull_pair = [&](int ea, int ba, int eb, int bb, bool valid) {
+          bool pass = false;
+          if (valid) {
+            float dd = 0.0f;
+            for (int c = 0; c < 3; ++c) {
+              const float dc = (Lpos[(bb * 7 + c) * E + eb] + (Lorg[c * E + eb] - Lorg[c * E + ea])) - Lpos[(ba * 7 + c) * E + ea];
+              dd += dc * dc;
+            }
+            const float reach = (Ltbody[4 * ba] + Ltbody[4 * ba + 1]) + (Ltbody[4 * bb] + Ltbody[4 * bb + 1]) + p_margin + 2e-3f;
+            pass = dd <= reach * reach;
+          }
+          const int pos = wave_alloc<1>(pass ? 1 : 0, &Lpcount[2]);
+          if (pass) {
+            if (pos < unit_cap) Lc2[pos] = ((unsigned)ea << 20) | ((unsigned)eb << 8) | (unsigned)(ba << 4) | (unsigned)bb;
+            else Lpcount[3] = 1;   // list full: everything is tested the slow way below
+          }
+        };
         // the listed pairs of every agent: thread (idx, e) takes pairs idx, idx + stride, ...
-        {
-          const int stride = kThreads / E;
-          if (idx < stride)
-            for (int pp = idx; pp < m_npairs; pp += stride)
-              test_pair(e, M.pair_a[pp], e, M.pair_b[pp], ((unsigned)pp << 12) | (unsigned)e, env_ok);
-        }
+        const int pair_stride = kThreads / E;
+        if (idx < pair_stride)
+          for (int pp = idx; pp < m_npairs; pp += pair_stride) cull_pair(e, M.pair_a[pp], e, M.pair_b[pp], env_ok);
         // agents of one group: 256 lanes per near agent pair, lane = (body of A) * 16 + (body of B)
-        if (m_group > 1) {
-          const int n_near = Lpcount[1];
+        const int n_near = m_group > 1 ? Lpcount[1] : 0;
+        for (int nn = tid >> 8; nn < n_near; nn += kThreads >> 8) {
+          const int cb = tid & 255, ba = cb >> 4, bb = cb & 15;
+          const int pr = Lnear[nn];
+          cull_pair(pr & 0xffff, ba, pr >> 16, bb, ba < B && bb < B);
+        }
+        __syncthreads();
+        // Stage 2: the segment-segment test, one listed candidate per lane
+        if (!Lpcount[3]) {
+          const int n_c2 = Lpcount[2];
+          for (int c = tid; c < n_c2; c += kThreads) {
+            const unsigned wd = Lc2[c];
+            test_pair((int)(wd >> 20), (int)((wd >> 4) & 15u), (int)((wd >> 8) & 0xfffu), (int)(wd & 15u), wd, true);
+          }
+        } else {
+          if (idx < pair_stride)
+            for (int pp = idx; pp < m_npairs; pp += pair_stride)
+              test_pair(e, M.pair_a[pp], e, M.pair_b[pp], ((unsigned)e << 20) | ((unsigned)e << 8) | (unsigned)(M.pair_a[pp] << 4) | (unsigned)M.pair_b[pp], env_ok);
           for (int nn = tid >> 8; nn < n_near; nn += kThreads >> 8) {
             const int cb = tid & 255, ba = cb >> 4, bb = cb & 15;
             const int pr = Lnear[nn], ea = pr & 0xffff, eb = pr >> 16;
-            test_pair(ea, ba, eb, bb, 0x80000000u | ((unsigned)ea << 20) | ((unsigned)eb << 8) | (unsigned)(ba << 4) | (unsigned)bb,
-                      ba < B && bb < B);
+            test_pair(ea, ba, eb, bb, ((unsigned)ea << 20) | ((unsigned)eb << 8) | (unsigned)(ba << 4) | (unsigned)bb, ba < B && bb < B);
           }
         }
         __syncthreads();
