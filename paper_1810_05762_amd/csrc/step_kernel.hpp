@@ -1177,15 +1177,29 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     if constexpr (PC != 0) {
       if (g_on) {
         int cnt = 0;
-        for (int k = 0; k < n_pc; ++k) {
-          const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
-          const bool ma = (refs & 0xffff) == g_ref, mb = ((refs >> 16) & 0xffff) == g_ref;
-          if (ma || mb) {
-            const int off = k * 12 + (mb ? 6 : 0);
+        // four queue entries per round, their LDS reads issued together (one at a time each read
+        // would cost its full latency)
+        for (int k0 = 0; k0 < n_pc; k0 += 4) {
+          int refs[4];
+          float wq[4];
 #pragma unroll
-            for (int j = 0; j < kPairList; ++j) gp_off[j] = cnt == j ? off : gp_off[j];
-            gp_wsum += Lpq[k * kPairWords + 4];
-            ++cnt;
+          for (int j = 0; j < 4; ++j) {
+            const int k = k0 + j < n_pc ? k0 + j : n_pc - 1;
+            refs[j] = __float_as_int(Lpq[k * kPairWords + 1]);
+            wq[j] = Lpq[k * kPairWords + 4];
+          }
+          __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int k = k0 + j;
+            const bool ma = (refs[j] & 0xffff) == g_ref, mb = ((refs[j] >> 16) & 0xffff) == g_ref;
+            if (k < n_pc && (ma || mb)) {
+              const int off = k * 12 + (mb ? 6 : 0);
+#pragma unroll
+              for (int i = 0; i < kPairList; ++i) gp_off[i] = cnt == i ? off : gp_off[i];
+              gp_wsum += wq[j];
+              ++cnt;
+            }
           }
         }
         gp_many = cnt > kPairList;
