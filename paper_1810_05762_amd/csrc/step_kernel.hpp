@@ -78,7 +78,7 @@ constexpr int kVS = 7, kCS = 7, kJS = 13;
 
 struct LdsPlan {
   int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
-  int pq, po, pnear, pbs, pcount;  // capsule-capsule contacts (only with pairs != 0)
+  int pq, po, pnear, pbs, pcount, pbcnt, pblist;  // capsule-capsule contacts (only with pairs != 0)
 };
 
 // pairs: 0 = no capsule-capsule contacts, else the interaction group size (1 = self-collision only)
@@ -117,6 +117,8 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.pnear = o; o += pairs ? (E * pairs) / 2 + 1 : 0;  // agent pairs whose bounding spheres overlap
   p.pbs = o; o += pairs ? E : 0;                      // bounding radius of every agent about its root
   p.pcount = o; o += pairs ? 4 : 0;
+  p.pbcnt = o; o += pairs ? B * E : 0;                  // per body: how many of them touch it
+  p.pblist = o; o += pairs ? (B * E * 6 + 3) / 4 : 0;  // per body: up to six of them, one byte each
   p.total = o;
   return p;
 }
@@ -533,6 +535,8 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   int* Lnear = reinterpret_cast<int*>(lds + P.pnear);
   int* Lbs = reinterpret_cast<int*>(lds + P.pbs);     // bounding radii as float bits (ordered like ints)
   int* Lpcount = reinterpret_cast<int*>(lds + P.pcount);  // contacts found, near agent pairs
+  int* Lpbcnt = reinterpret_cast<int*>(lds + P.pbcnt);
+  uint8_t* Lpblist = reinterpret_cast<uint8_t*>(lds + P.pblist);
   const float h = a.h;
 
   // re-packing launch: a workgroup none of whose envs is flagged has nothing to do
@@ -690,6 +694,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     if constexpr (PC != 0) {
       if (tid < 4) Lpcount[tid] = 0;
       if (tid < E) Lbs[tid] = 0;
+      for (int i = tid; i < B * E; i += kThreads) Lpbcnt[i] = 0;
     }
     if (is_body) {
       for (int c = 0; c < 3; ++c) Lpos[(b * 7 + c) * E + e] = x[c];
@@ -1152,6 +1157,15 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         }
         if (tid == 0 && n_raw > kPairCap) atomicAdd(a.pair_dropped, n_raw - kPairCap);
         __syncthreads();
+        // every contact enters the lists of its two bodies (the order in which they arrive does not
+        // matter: the averaging threads sort their list)
+        if (tid < 2 * n_pc) {
+          const int refs = __float_as_int(Lpq[(tid >> 1) * kPairWords + 1]);
+          const int ref = (tid & 1) ? (refs >> 16) & 0xffff : refs & 0xffff;
+          const int slot = atomicAdd(&Lpbcnt[ref], 1);
+          if (slot < 6) Lpblist[ref * 6 + slot] = (uint8_t)tid;   // 2 * (queue index) + side
+        }
+        __syncthreads();
       }
     }
     TMARK(16);
@@ -1168,7 +1182,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     const int g_ref = g_b * E + e;
     // capsule-capsule contacts of body g_b: where their (weighted) copies will be (up to kPairList
     // of them; a body with more walks the queue in every sweep), and the sum of their weights
-    constexpr int kPairList = 6;
+    constexpr int kPairList = 6;   // (the list in LDS and the sorting network below are made for six)
     int gp_off[kPairList];
 #pragma unroll
     for (int j = 0; j < kPairList; ++j) gp_off[j] = kPairCap * 12;
@@ -1176,30 +1190,26 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     float gp_wsum = 0.0f;
     if constexpr (PC != 0) {
       if (g_on) {
-        int cnt = 0;
-        // four queue entries per round, their LDS reads issued together (one at a time each read
-        // would cost its full latency)
-        for (int k0 = 0; k0 < n_pc; k0 += 4) {
-          int refs[4];
-          float wq[4];
+        const int cnt = n_pc > 0 ? Lpbcnt[g_ref] : 0;
+        if (cnt > 0 && cnt <= kPairList) {
+          // the body's list (bytes 2 * queue index + side), sorted into queue order
+          int v[kPairList];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int k = k0 + j < n_pc ? k0 + j : n_pc - 1;
-            refs[j] = __float_as_int(Lpq[k * kPairWords + 1]);
-            wq[j] = Lpq[k * kPairWords + 4];
+          for (int j = 0; j < kPairList; ++j) v[j] = j < cnt ? (int)Lpblist[g_ref * 6 + j] : 255;
+          auto cx = [&](int i, int j) { const int lo = min(v[i], v[j]), hi = max(v[i], v[j]); v[i] = lo; v[j] = hi; };
+          cx(0, 5); cx(1, 3); cx(2, 4); cx(1, 2); cx(3, 4); cx(0, 3); cx(2, 5); cx(0, 1); cx(2, 3); cx(4, 5); cx(1, 2); cx(3, 4);
+#pragma unroll
+          for (int j = 0; j < kPairList; ++j) {
+            const bool used = v[j] != 255;
+            gp_off[j] = used ? v[j] * 6 : kPairCap * 12;
+            const float wj = Lpq[(used ? v[j] >> 1 : 0) * kPairWords + 4];
+            gp_wsum += used ? wj : 0.0f;
           }
-          __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int k = k0 + j;
-            const bool ma = (refs[j] & 0xffff) == g_ref, mb = ((refs[j] >> 16) & 0xffff) == g_ref;
-            if (k < n_pc && (ma || mb)) {
-              const int off = k * 12 + (mb ? 6 : 0);
-#pragma unroll
-              for (int i = 0; i < kPairList; ++i) gp_off[i] = cnt == i ? off : gp_off[i];
-              gp_wsum += wq[j];
-              ++cnt;
-            }
+        } else if (cnt > kPairList) {
+          // more than the list holds: the weights by a walk over the queue (as in every sweep)
+          for (int k = 0; k < n_pc; ++k) {
+            const int refs = __float_as_int(Lpq[k * kPairWords + 1]);
+            if ((refs & 0xffff) == g_ref || ((refs >> 16) & 0xffff) == g_ref) gp_wsum += Lpq[k * kPairWords + 4];
           }
         }
         gp_many = cnt > kPairList;
