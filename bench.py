@@ -59,6 +59,7 @@ def main():
     ap.add_argument("--self-collide", action="store_true", help="capsules of one robot collide with each other")
     ap.add_argument("--group-size", type=int, default=1, help="agents per interaction group (inter-agent collisions)")
     ap.add_argument("--spacing", type=float, default=1.5, help="distance between the agents of a group, metres")
+    ap.add_argument("--task", action="store_true", help="task logic of Section 4.1: pushes, flagrun targets, grace period, auto-reset")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -92,6 +93,9 @@ def main():
         sim.set_state(scenes.fallen_states(scene, cfg["seed"]))
     else:
         sim.reset(cfg["seed"])
+    task = scenes.TaskParams(seed=cfg["seed"]) if args.task else None
+    if task is not None:
+        sim.set_task(task)
     dt, sub, its = float(np.float32(cfg["dt"])), cfg["substeps"], cfg["iterations"]
     ring = [torch.as_tensor(scenes.actions_for_step(cfg["seed"], s, N, rob.n_dofs)).to(dev) for s in range(16)]
     obs = torch.empty(N, sim.obs_dim, dtype=torch.float32, device=dev)
@@ -135,7 +139,7 @@ def main():
     # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
     # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 10.7 MB
     # read + 11.6 MB written (summary under profiles/); other sizes were not measured
-    traffic = 22.3e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide) else None
+    traffic = 22.3e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task) else None
     pair_info = {}
     if collide:
         sim.record_contacts(True)
@@ -155,12 +159,13 @@ def main():
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": (cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")
-                               + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else ""),
+                               + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else "")
+                               + ("_task" if args.task else ""),
                    "num_envs": N, "obs_dim": sim.obs_dim, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
                    "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
-                   "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 1,
+                   "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 3 if args.task else 1,
                    **sim.launch_info(), **pair_info},
         "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,
                      "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": traffic,
@@ -186,6 +191,8 @@ def main():
         cores = max(1, min(cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
         ref = oracle.OracleSim(sub_scene, threads=cores)
         ref.set_state(sim.get_state().cpu().numpy()[:n_s].astype(np.float64))
+        if task is not None:
+            ref.set_task(task)
         acts = [ring[k].cpu().numpy()[:n_s] for k in range(16)]
         ref.step(acts[0], dt, sub, its)
         t0 = time.perf_counter()
@@ -206,6 +213,8 @@ def main():
         one_scene.env_origins = scene.env_origins[:n_1].copy()
         ref1 = oracle.OracleSim(one_scene, threads=1)
         ref1.set_state(sim.get_state().cpu().numpy()[:n_1].astype(np.float64))
+        if task is not None:
+            ref1.set_task(task)
         t0 = time.perf_counter()
         n1_steps = 0
         while True:
