@@ -165,7 +165,7 @@ def main():
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
                    "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
-                   "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 3 if args.task else 1,
+                   "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 1,
                    **sim.launch_info(), **pair_info},
         "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,
                      "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": traffic,

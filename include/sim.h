@@ -211,7 +211,9 @@ int sim_set_targets(sim_t* sim, const float* target_xy_dev, void* stream);
 /* Switches the task logic on (task->enabled != 0) or off (NULL or enabled == 0) for the following
  * sim_step / sim_step_obs calls and starts episode 0 of every env from the current body state
  * (counters cleared, first push time and, with target_period > 0, first target drawn).  With
- * auto_reset a step takes three kernel launches instead of one.  SIM_ERR_ARG on inconsistent
+ * auto_reset, an env whose episode ends in a step is put back to a fresh initial state at the end
+ * of that same step (still one kernel launch): the step returns the ended episode's last reward
+ * and done = 1 next to the first observation of the next episode.  SIM_ERR_ARG on inconsistent
  * numbers. */
 int sim_set_task(sim_t* sim, const sim_task_desc_t* task, void* stream);
 /* Per-env task state: counters [N][4] = frames below the threshold, target age, frame of the

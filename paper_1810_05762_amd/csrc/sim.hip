@@ -42,7 +42,7 @@ extern "C" const char* sim_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ layout
 struct Layout {
-  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, reset_flag, push, flag, pair_recs, pair_count, total;
+  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, push, flag, pair_recs, pair_count, total;
 };
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -61,7 +61,6 @@ static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, si
   L.done = o; o = align_up(o + (size_t)N);
   L.recs = o; o = align_up(o + (size_t)N * S * sizeof(sim_contact_rec_t));
   L.task_i = o; o = align_up(o + (size_t)N * 4 * sizeof(int32_t));
-  L.reset_flag = o; o = align_up(o + (size_t)N);
   L.push = o; o = align_up(o + (size_t)N * 3 * sizeof(float));
   // capsule-capsule contact records: one workgroup may hold as few as one env
   L.pair_recs = o; o = align_up(o + (pairs ? (size_t)N * kPairCap * sizeof(sim_pair_contact_rec_t) : 0));
@@ -341,63 +340,25 @@ __global__ void gen_contacts_kernel(const Model* Mp, const float* __restrict__ h
   r[10] = __float_as_int(c.w); r[11] = 0;
 }
 
-// Seeded reset (Section 4.1: initial state perturbed slightly).  One thread per env;
-// bodies are placed parents-first through the joint list.
+// Seeded reset of one env by one thread: the poses are built in local arrays, then stored.
+struct LocalPoses {
+  float x[kMaxBodies][3], q[kMaxBodies][4];
+  __device__ float& X(int b, int c) { return x[b][c]; }
+  __device__ float& Q(int b, int c) { return q[b][c]; }
+};
 __device__ void reset_one_env(const Model& M, float* __restrict__ state, int32_t* __restrict__ steps, int env,
-                              uint64_t seed, int N, float root_xy[2]) {
-  const float a = M.reset_noise;
-  float off[3], vel[3];
-  for (int c = 0; c < 3; ++c) {
-    off[c] = a * (2.0f * reset_uniform(seed, env, c) - 1.0f);
-    vel[c] = a * (2.0f * reset_uniform(seed, env, 3 + c) - 1.0f);
-  }
-  float X[kMaxBodies][3], Q[kMaxBodies][4];
-  for (int b = 0; b < M.B; ++b) {
-    for (int c = 0; c < 3; ++c) X[b][c] = M.bodies[b].rest_pos[c] + off[c];
-    Q[b][0] = 1.0f; Q[b][1] = Q[b][2] = Q[b][3] = 0.0f;
-  }
-  for (int j = 0; j < M.J; ++j) {
-    const JointTab& jt = M.joints[j];
-    float phi[3] = {0, 0, 0};
-    for (int k = 0; k < 3; ++k) {
-      if (jt.mode[k] != 1) continue;
-      float th = a * (2.0f * reset_uniform(seed, env, 8 + 3 * j + k) - 1.0f);
-      th = fminf(fmaxf(th, jt.lo[k]), jt.hi[k]);
-      for (int c = 0; c < 3; ++c) phi[c] += th * jt.axes[k][c];
-    }
-    float ang = sqrtf(dot(phi, phi));
-    float dq[4];
-    if (ang < 1e-12f) { dq[0] = 1.0f; dq[1] = 0.5f * phi[0]; dq[2] = 0.5f * phi[1]; dq[3] = 0.5f * phi[2]; }
-    else { float s = sinf(0.5f * ang) / ang; dq[0] = cosf(0.5f * ang); dq[1] = s * phi[0]; dq[2] = s * phi[1]; dq[3] = s * phi[2]; }
-    float qa[4] = {1, 0, 0, 0}, xa[3] = {0, 0, 0};
-    if (jt.parent >= 0) {
-      for (int c = 0; c < 4; ++c) qa[c] = Q[jt.parent][c];
-      for (int c = 0; c < 3; ++c) xa[c] = X[jt.parent][c];
-    }
-    float qb[4];
-    qb[0] = qa[0] * dq[0] - qa[1] * dq[1] - qa[2] * dq[2] - qa[3] * dq[3];
-    qb[1] = qa[0] * dq[1] + qa[1] * dq[0] + qa[2] * dq[3] - qa[3] * dq[2];
-    qb[2] = qa[0] * dq[2] - qa[1] * dq[3] + qa[2] * dq[0] + qa[3] * dq[1];
-    qb[3] = qa[0] * dq[3] + qa[1] * dq[2] - qa[2] * dq[1] + qa[3] * dq[0];
-    float inv = 1.0f / sqrtf(qb[0] * qb[0] + qb[1] * qb[1] + qb[2] * qb[2] + qb[3] * qb[3]);
-    for (int c = 0; c < 4; ++c) qb[c] *= inv;
-    float Ra[9], Rb[9], t0[3], t1[3];
-    quat_to_mat(qa, Ra);
-    quat_to_mat(qb, Rb);
-    mat_vec(Ra, jt.la, t0);
-    mat_vec(Rb, jt.lb, t1);
-    for (int c = 0; c < 4; ++c) Q[jt.child][c] = qb[c];
-    for (int c = 0; c < 3; ++c) X[jt.child][c] = xa[c] + t0[c] - t1[c];
-  }
+                              uint64_t seed, int N) {
+  LocalPoses P;
+  float vel[3];
+  reset_pose(M, env, seed, P, vel);
   const size_t fs = (size_t)M.B * N;
   for (int b = 0; b < M.B; ++b) {
     float* st = state + (size_t)b * N + env;
-    for (int c = 0; c < 3; ++c) st[c * fs] = X[b][c];
-    for (int c = 0; c < 4; ++c) st[(3 + c) * fs] = Q[b][c];
+    for (int c = 0; c < 3; ++c) st[c * fs] = P.x[b][c];
+    for (int c = 0; c < 4; ++c) st[(3 + c) * fs] = P.q[b][c];
     for (int c = 0; c < 3; ++c) { st[(7 + c) * fs] = vel[c]; st[(10 + c) * fs] = 0.0f; }
   }
   steps[env] = 0;
-  root_xy[0] = X[M.root][0]; root_xy[1] = X[M.root][1];
 }
 
 __global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t* __restrict__ steps,
@@ -405,24 +366,13 @@ __global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t
   int env = blockIdx.x * blockDim.x + threadIdx.x;
   if (env >= N) return;
   if (mask && !mask[env]) return;
-  float rxy[2];
-  reset_one_env(*Mp, state, steps, env, seed, N, rxy);
-}
-
-// Start of an episode for the task logic (Section 4.1): counters cleared, first push time and
-// (flagrun) first target drawn around the root.
-__device__ void task_begin_episode(const TaskParams& t, int32_t* __restrict__ task_i, float* __restrict__ targets,
-                                   int env, int episode, float rx, float ry) {
-  task_i[4 * env + 0] = 0; task_i[4 * env + 1] = 0;
-  task_i[4 * env + 2] = t.push_max_f > 0 ? task_interval(t, env, episode, 0) : -1;
-  task_i[4 * env + 3] = episode;
-  if (t.period > 0) task_draw_target(t, env, episode, 0, rx, ry, targets + 2 * env);
+  reset_one_env(*Mp, state, steps, env, seed, N);
 }
 
 // sim_set_task: episode 0 for every env, from the current body state
 __global__ void task_init_kernel(const Model* Mp, const float* __restrict__ state, int32_t* __restrict__ task_i,
                                  float* __restrict__ targets, float* __restrict__ push,
-                                 uint8_t* __restrict__ reset_flag, TaskParams t, int N) {
+                                 TaskParams t, int N) {
   int env = blockIdx.x * blockDim.x + threadIdx.x;
   if (env >= N) return;
   const Model& M = *Mp;
@@ -430,25 +380,12 @@ __global__ void task_init_kernel(const Model* Mp, const float* __restrict__ stat
   const float rx = state[0 * fs + (size_t)M.root * N + env], ry = state[1 * fs + (size_t)M.root * N + env];
   task_begin_episode(t, task_i, targets, env, 0, rx, ry);
   push[3 * env] = push[3 * env + 1] = push[3 * env + 2] = 0.0f;
-  reset_flag[env] = 0;
-}
-
-// after a step: envs whose episode ended start the next one (reset recipe, seed of that episode)
-__global__ void task_reset_kernel(const Model* Mp, float* __restrict__ state, int32_t* __restrict__ steps,
-                                  int32_t* __restrict__ task_i, float* __restrict__ targets,
-                                  const uint8_t* __restrict__ reset_flag, TaskParams t, int N) {
-  int env = blockIdx.x * blockDim.x + threadIdx.x;
-  if (env >= N || !reset_flag[env]) return;
-  const int episode = task_i[4 * env + 3] + 1;
-  float rxy[2];
-  reset_one_env(*Mp, state, steps, env, t.seed + (uint64_t)episode * kEpisodeStride, N, rxy);
-  task_begin_episode(t, task_i, targets, env, episode, rxy[0], rxy[1]);
 }
 
 // ---------------------------------------------------------------- launches
 static int launch_step(sim* s, const float* actions, float h, int substeps, int iterations, int count_step,
                        hipStream_t st, float* obs_out = nullptr, float* reward_out = nullptr,
-                       uint8_t* done_out = nullptr, const uint8_t* repack = nullptr) {
+                       uint8_t* done_out = nullptr) {
   const Model& m = s->host_model;
   StepArgs a;
   a.M = reinterpret_cast<const Model*>(s->ws + s->lay.model);
@@ -468,9 +405,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.obs_out = obs_out; a.reward_out = reward_out; a.done_out = done_out;
   a.task = s->task;
   a.task_i = reinterpret_cast<int32_t*>(s->ws + s->lay.task_i);
-  a.reset_flag = reinterpret_cast<uint8_t*>(s->ws + s->lay.reset_flag);
   a.push = reinterpret_cast<float*>(s->ws + s->lay.push);
-  a.repack = repack;
   const int pairs = pairs_of(m);
   a.pair_recs = (pairs && s->record && substeps > 0) ? reinterpret_cast<int32_t*>(s->ws + s->lay.pair_recs) : nullptr;
   a.pair_count = reinterpret_cast<int32_t*>(s->ws + s->lay.pair_count);
@@ -581,7 +516,6 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
     HIP_TRY_S(hipMemset(s->ws + s->lay.recs, 0, (size_t)num_envs * m.S * sizeof(sim_contact_rec_t)));
     HIP_TRY_S(hipMemset(s->ws + s->lay.flag, 0, 256));
     HIP_TRY_S(hipMemset(s->ws + s->lay.task_i, 0, (size_t)num_envs * 4 * sizeof(int32_t)));
-    HIP_TRY_S(hipMemset(s->ws + s->lay.reset_flag, 0, (size_t)num_envs));
     HIP_TRY_S(hipMemset(s->ws + s->lay.push, 0, (size_t)num_envs * 3 * sizeof(float)));
   }
   rc = launch_step(s, nullptr, 1.0f, 0, 0, 0, nullptr);
@@ -639,25 +573,14 @@ extern "C" int sim_reset(sim_t* s, const uint8_t* env_mask_dev, uint64_t seed, v
   return launch_step(s, nullptr, 1.0f, 0, 0, 0, st);
 }
 
-// One env-step: the fused kernel, then (task logic with auto-reset only) the reset of the envs
-// whose episode ended and a zero-substep launch that re-packs their observation.
+// One env-step is one launch of the fused kernel (with the task logic's auto-reset, the envs
+// whose episode ended are reset and their observation re-packed at the end of that launch).
 static int step_common(sim* s, const float* actions_dev, float dt, int substeps, int iterations, float* obs_dev,
                        float* reward_dev, uint8_t* done_dev, hipStream_t st) {
   if (!(dt > 0.0f) || !std::isfinite(dt)) return fail(SIM_ERR_ARG, "dt must be finite and > 0");
   if (substeps < 1) return fail(SIM_ERR_ARG, "substeps must be >= 1 (got %d)", substeps);
   if (iterations < 0) return fail(SIM_ERR_ARG, "iterations must be >= 0 (got %d)", iterations);
-  int rc = launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, st, obs_dev, reward_dev, done_dev);
-  if (rc || !(s->task.enabled && s->task.auto_reset)) return rc;
-  const uint8_t* flags = reinterpret_cast<const uint8_t*>(s->ws + s->lay.reset_flag);
-  hipLaunchKernelGGL(task_reset_kernel, dim3(blocks_for(s->N, 64)), dim3(64), 0, st,
-                     reinterpret_cast<const Model*>(s->ws + s->lay.model), reinterpret_cast<float*>(s->ws + s->lay.state),
-                     reinterpret_cast<int32_t*>(s->ws + s->lay.steps), reinterpret_cast<int32_t*>(s->ws + s->lay.task_i),
-                     reinterpret_cast<float*>(s->ws + s->lay.targets), flags, s->task, s->N);
-  HIP_TRY(hipGetLastError());
-  const int keep_recs = s->recs_valid;
-  rc = launch_step(s, nullptr, 1.0f, 0, 0, 0, st, obs_dev, nullptr, nullptr, flags);
-  s->recs_valid = keep_recs;
-  return rc;
+  return launch_step(s, actions_dev, dt / (float)substeps, substeps, iterations, 1, st, obs_dev, reward_dev, done_dev);
 }
 
 extern "C" int sim_step(sim_t* s, const float* actions_dev, float dt, int substeps, int iterations, void* stream) {
@@ -682,8 +605,7 @@ extern "C" int sim_set_task(sim_t* s, const sim_task_desc_t* t, void* stream) {
   hipLaunchKernelGGL(task_init_kernel, dim3(blocks_for(s->N, 64)), dim3(64), 0, static_cast<hipStream_t>(stream),
                      reinterpret_cast<const Model*>(s->ws + s->lay.model), reinterpret_cast<const float*>(s->ws + s->lay.state),
                      reinterpret_cast<int32_t*>(s->ws + s->lay.task_i), reinterpret_cast<float*>(s->ws + s->lay.targets),
-                     reinterpret_cast<float*>(s->ws + s->lay.push), reinterpret_cast<uint8_t*>(s->ws + s->lay.reset_flag),
-                     s->task, s->N);
+                     reinterpret_cast<float*>(s->ws + s->lay.push), s->task, s->N);
   HIP_TRY(hipGetLastError());
   return SIM_OK;
 }

@@ -63,9 +63,7 @@ struct StepArgs {
   uint8_t* done_out;
   TaskParams task;       // task logic (enabled = 0: off)
   int32_t* task_i;       // [N][4]: frames below the threshold, target age, frame of the next push, episode
-  uint8_t* reset_flag;   // [N]: set when the env finished its episode and is to be reset
   float* push;           // [N][3]: force on the root body during this step
-  const uint8_t* repack; // non-null: only re-pack the observation of the flagged envs (zero substeps)
   long long* dbg;        // phase-timing slots (diagnostic build only)
   int32_t* pair_recs;    // [grid][kPairCap][8] capsule-capsule contacts of the last substep, or null
   int32_t* pair_count;   // [grid] their number per workgroup
@@ -438,6 +436,74 @@ __device__ inline void task_draw_target(const TaskParams& t, int env, int episod
   target_xy[1] = ry + r * sinf(phi);
 }
 
+// Seeded reset (Section 4.1: initial state perturbed slightly): the rest pose displaced by a
+// uniform offset, every hinge angle drawn uniformly (clamped to its limits), bodies placed
+// parents-first through the joint list; one common linear velocity, no angular velocity.
+// `P` holds the poses while they are built: P.X(b, c) and P.Q(b, c) are references to position
+// component c and quaternion component c of body b (local arrays for the stand-alone reset
+// kernels, the env's column of the pose array in LDS for the reset at the end of a step).
+template <class Poses>
+__device__ inline void reset_pose(const Model& M, int env, uint64_t seed, Poses& P, float vel[3]) {
+  const float a = M.reset_noise;
+  float off[3];
+  for (int c = 0; c < 3; ++c) {
+    off[c] = a * (2.0f * reset_uniform(seed, env, c) - 1.0f);
+    vel[c] = a * (2.0f * reset_uniform(seed, env, 3 + c) - 1.0f);
+  }
+  for (int b = 0; b < M.B; ++b) {
+    for (int c = 0; c < 3; ++c) P.X(b, c) = M.bodies[b].rest_pos[c] + off[c];
+    P.Q(b, 0) = 1.0f; P.Q(b, 1) = 0.0f; P.Q(b, 2) = 0.0f; P.Q(b, 3) = 0.0f;
+  }
+  for (int j = 0; j < M.J; ++j) {
+    const JointTab& jt = M.joints[j];
+    float phi[3] = {0, 0, 0};
+    for (int k = 0; k < 3; ++k) {
+      if (jt.mode[k] != 1) continue;
+      float th = a * (2.0f * reset_uniform(seed, env, 8 + 3 * j + k) - 1.0f);
+      th = fminf(fmaxf(th, jt.lo[k]), jt.hi[k]);
+      for (int c = 0; c < 3; ++c) phi[c] += th * jt.axes[k][c];
+    }
+    float ang = sqrtf(dot(phi, phi));
+    float dq[4];
+    if (ang < 1e-12f) { dq[0] = 1.0f; dq[1] = 0.5f * phi[0]; dq[2] = 0.5f * phi[1]; dq[3] = 0.5f * phi[2]; }
+    else { float s = sinf(0.5f * ang) / ang; dq[0] = cosf(0.5f * ang); dq[1] = s * phi[0]; dq[2] = s * phi[1]; dq[3] = s * phi[2]; }
+    float qa[4] = {1, 0, 0, 0}, xa[3] = {0, 0, 0};
+    if (jt.parent >= 0) {
+      for (int c = 0; c < 4; ++c) qa[c] = P.Q(jt.parent, c);
+      for (int c = 0; c < 3; ++c) xa[c] = P.X(jt.parent, c);
+    }
+    float qb[4];
+    qb[0] = qa[0] * dq[0] - qa[1] * dq[1] - qa[2] * dq[2] - qa[3] * dq[3];
+    qb[1] = qa[0] * dq[1] + qa[1] * dq[0] + qa[2] * dq[3] - qa[3] * dq[2];
+    qb[2] = qa[0] * dq[2] - qa[1] * dq[3] + qa[2] * dq[0] + qa[3] * dq[1];
+    qb[3] = qa[0] * dq[3] + qa[1] * dq[2] - qa[2] * dq[1] + qa[3] * dq[0];
+    float inv = 1.0f / sqrtf(qb[0] * qb[0] + qb[1] * qb[1] + qb[2] * qb[2] + qb[3] * qb[3]);
+    for (int c = 0; c < 4; ++c) qb[c] *= inv;
+    float Ra[9], Rb[9], t0[3], t1[3];
+    quat_to_mat(qa, Ra);
+    quat_to_mat(qb, Rb);
+    mat_vec(Ra, jt.la, t0);
+    mat_vec(Rb, jt.lb, t1);
+    for (int c = 0; c < 4; ++c) P.Q(jt.child, c) = qb[c];
+    for (int c = 0; c < 3; ++c) P.X(jt.child, c) = xa[c] + t0[c] - t1[c];
+  }
+}
+// Start of an episode for the task logic (Section 4.1): counters cleared, first push time and
+// (flagrun) first target drawn around the root.
+__device__ inline void task_begin_episode(const TaskParams& t, int32_t* __restrict__ task_i, float* __restrict__ targets,
+                                          int env, int episode, float rx, float ry) {
+  task_i[4 * env + 0] = 0; task_i[4 * env + 1] = 0;
+  task_i[4 * env + 2] = t.push_max_f > 0 ? task_interval(t, env, episode, 0) : -1;
+  task_i[4 * env + 3] = episode;
+  if (t.period > 0) task_draw_target(t, env, episode, 0, rx, ry, targets + 2 * env);
+}
+// the env's column of the pose array in LDS ([body][7][E]) as the place reset_pose builds in
+struct LdsPoses {
+  float* Lpos; int E, ee;
+  __device__ float& X(int b, int c) { return Lpos[(b * 7 + c) * E + ee]; }
+  __device__ float& Q(int b, int c) { return Lpos[(b * 7 + 3 + c) * E + ee]; }
+};
+
 // (squared distance, feature id) as one 64-bit word whose unsigned order is the lexicographic
 // order of the pair (squared distances are non-negative, ids non-negative)
 __device__ __forceinline__ unsigned long long pack_best(float d2, int id) {
@@ -539,11 +605,6 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   uint8_t* Lpblist = reinterpret_cast<uint8_t*>(lds + P.pblist);
   const float h = a.h;
 
-  // re-packing launch: a workgroup none of whose envs is flagged has nothing to do
-  if (a.repack) {
-    const int env_t = blockIdx.x * E + (tid < E ? tid : 0);
-    if (!__syncthreads_or(tid < E && env_t < N && a.repack[env_t])) return;
-  }
   // ---- load: body state into registers, clipped actions into LDS
   float x[3] = {0, 0, 0}, q[4] = {1, 0, 0, 0}, v[3] = {0, 0, 0}, w[3] = {0, 0, 0};
   int my_slot0 = 0, my_nslots = 0, my_njs = 0;
@@ -1584,8 +1645,16 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   }
   __syncthreads();
 
+  // The observation is packed once for every env (pass 0).  With the task logic's auto-reset, an
+  // env whose episode ends in pass 0 is put back to a fresh initial state right here, and pass 1
+  // packs the observation of that state for it (no action, no contact), so the caller gets the
+  // finished step's reward and done flag next to the first observation of the next episode.
+  int* Lrst = reinterpret_cast<int*>(Lpush);   // [E]: env was reset in pass 0 (the pushes are no longer read)
+  const bool may_reset = a.task.enabled && a.task.auto_reset && a.count_step;
   // ---- observation vector (Table 2 "Ours"), per joint part
-  if (is_joint) {
+  auto pack_joints = [&](auto pass_c) {
+  constexpr int pass = decltype(pass_c)::value;
+  if (is_joint && (pass == 0 || Lrst[e])) {
     const JointTab& jt = Ltjoint[idx];
     const int pa = jt.parent, pb = jt.child;
     float qa[4] = {1, 0, 0, 0}, wa[3] = {0, 0, 0}, qb[4], wb[3];
@@ -1607,14 +1676,17 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       float th = dot(jt.axes[k], phi);
       Lobs[e * obs_dim + 11 + ai] = th;
       Lobs[e * obs_dim + 11 + D + ai] = dot(ak, dw);
-      Lobs[e * obs_dim + 11 + 2 * D + ai] = Lu[ai * E + e];
+      Lobs[e * obs_dim + 11 + 2 * D + ai] = pass ? 0.0f : Lu[ai * E + e];
       float g = fminf(th - jt.lo[k], jt.hi[k] - th);
       Llim[ai * E + e] = g <= 0.0f ? 1 : 0;
     }
   }
-  __syncthreads();
-  // ---- root part, reward (Eq. 1-3), done (Section 4.1)
-  if (tid < E && (blockIdx.x * E + tid) < N) {
+  };
+  // ---- root part, reward (Eq. 1-3), done (Section 4.1); returns whether the env was reset
+  auto pack_root = [&](auto pass_c) -> bool {
+  constexpr int pass = decltype(pass_c)::value;
+  bool reset_now = false;
+  if (tid < E && (blockIdx.x * E + tid) < N && (pass == 0 || Lrst[tid])) {
     const int ee = tid, env_e = blockIdx.x * E + tid;
     const int rb = M.root;
     float rx[3], rq[4], rv[3], rw[3];
@@ -1643,7 +1715,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       int flag = 0;
       for (int k = 0; k < bt.n_slots; ++k) {
         int s = bt.slot0 + k;
-        if (Lreci[(s * kRecWords + 0) * E + ee] && Lrec[(s * kRecWords + 3) * E + ee] <= 0.005f) flag = 1;
+        if (pass == 0 && Lreci[(s * kRecWords + 0) * E + ee] && Lrec[(s * kRecWords + 3) * E + ee] <= 0.005f) flag = 1;
       }
       o[11 + 3 * D + f] = (float)flag;
       n_feet += flag;
@@ -1661,15 +1733,15 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     float cvert = 1.0f - 2.0f * (qx * qx + qy * qy);
     float r_stand = cvert > 0.93f ? 1.0f : 0.0f;
     int steps = a.steps[env_e] + (a.count_step ? 1 : 0);
-    const bool only_obs = a.repack != nullptr;       // re-packing a freshly reset env: obs only
+    const bool only_obs = pass != 0;                 // re-packing a freshly reset env: obs only
     if (!only_obs) a.steps[env_e] = steps;
     const float rew = M.alive_bonus + speed + 0.5f * r_head + 0.05f * r_stand - 4.0f * l1 - 0.5f * l2 -
                       0.2f * (float)n_lim - (float)n_feet;
     uint8_t dn = (height < M.term_height || steps >= M.max_steps) ? 1 : 0;
-    if (a.task.enabled && a.count_step) {
+    if (a.task.enabled && a.count_step && pass == 0) {
       // Section 4.1: termination only after `grace` consecutive frames below the threshold;
-      // flagrun target re-drawn every `period` frames or when reached; finished envs are flagged
-      // for the reset that follows this launch
+      // flagrun target re-drawn every `period` frames or when reached; finished envs start
+      // their next episode below
       int fall = a.task_i[4 * env_e + 0], age = a.task_i[4 * env_e + 1];
       const int ep = a.task_i[4 * env_e + 3];
       fall = height < M.term_height ? fall + 1 : 0;
@@ -1684,13 +1756,44 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         }
       }
       a.task_i[4 * env_e + 0] = fall; a.task_i[4 * env_e + 1] = age;
-      a.reset_flag[env_e] = (dn && a.task.auto_reset) ? 1 : 0;
+      reset_now = dn && a.task.auto_reset;
     }
     if (!only_obs) {
       a.reward[env_e] = rew;
       a.done[env_e] = dn;
       if (a.reward_out) a.reward_out[env_e] = rew;
       if (a.done_out) a.done_out[env_e] = dn;
+    }
+    if (reset_now) {
+      // next episode: the reset recipe with that episode's seed, built in this env's column of
+      // the pose array (no other thread reads it before the barrier below)
+      const int episode = a.task_i[4 * env_e + 3] + 1;
+      LdsPoses poses{Lpos, E, ee};
+      float v0[3];
+      reset_pose(M, env_e, a.task.seed + (uint64_t)episode * kEpisodeStride, poses, v0);
+      for (int bb = 0; bb < B; ++bb)
+        for (int c = 0; c < 3; ++c) { Lvel[(bb * kVS + c) * E + ee] = v0[c]; Lvel[(bb * kVS + 3 + c) * E + ee] = 0.0f; }
+      a.steps[env_e] = 0;
+      task_begin_episode(a.task, a.task_i, a.targets, env_e, episode, Lpos[(rb * 7 + 0) * E + ee], Lpos[(rb * 7 + 1) * E + ee]);
+    }
+  }
+  return reset_now;
+  };
+  pack_joints(std::integral_constant<int, 0>{});
+  __syncthreads();
+  const bool reset_now = pack_root(std::integral_constant<int, 0>{});
+  if (may_reset) {
+    if (tid < E) Lrst[tid] = reset_now ? 1 : 0;
+    if (__syncthreads_or(reset_now)) {
+      if (is_body && Lrst[e]) {
+        float* st = a.state + (size_t)b * N + env;
+        const size_t fs = (size_t)B * N;
+        for (int c = 0; c < 7; ++c) st[c * fs] = Lpos[(b * 7 + c) * E + e];
+        for (int c = 0; c < 6; ++c) st[(7 + c) * fs] = Lvel[(b * kVS + c) * E + e];
+      }
+      pack_joints(std::integral_constant<int, 1>{});
+      __syncthreads();
+      pack_root(std::integral_constant<int, 1>{});
     }
   }
   __syncthreads();
@@ -1700,7 +1803,6 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     for (int i = tid; i < n_here * obs_dim; i += kThreads) {
       const float o = Lobs[i];
       const int ee = i / obs_dim, k = i - ee * obs_dim;
-      if (a.repack && !a.repack[env0 + ee]) continue;
       a.obs[(size_t)(env0 + ee) * obs_row + k] = o;
       if (a.obs_out) a.obs_out[(size_t)(env0 + ee) * obs_row + k] = o;
     }
@@ -1730,8 +1832,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       constexpr int kHm = kHmRows * kHmCols;
       for (int i = tid; i < n_here * kHm; i += kThreads) {
         const int ee = i / kHm, k = i - ee * kHm, hi = k / kHmCols, hj = k - hi * kHmCols;
-        if (a.repack && !a.repack[env0 + ee]) continue;
-        const float fw = M.hm_fwd[hi], lt = M.hm_lat[hj], c = Lhm[3 * E + ee], sn = Lhm[4 * E + ee];
+          const float fw = M.hm_fwd[hi], lt = M.hm_lat[hj], c = Lhm[3 * E + ee], sn = Lhm[4 * E + ee];
         const float wx = Lhm[0 * E + ee] + (c * fw - sn * lt), wy = Lhm[1 * E + ee] + (sn * fw + c * lt);
         const float hz = terrain_height(M, a.heights, wx, wy) - Lhm[2 * E + ee];
         a.obs[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
