@@ -137,9 +137,9 @@ def main():
     bA, bB, bC = bytes_per_env_step(rob.n_bodies, rob.n_joints, sim.S, rob.n_dofs, sim.obs_dim, sub, its, active)
     achieved_tflops = fl * N / (kern_ms * 1e-3) / 1e12
     # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
-    # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 10.7 MB
-    # read + 11.6 MB written (summary under profiles/); other sizes were not measured
-    traffic = 22.3e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task) else None
+    # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.6 MB
+    # read + 6.9 MB written (summary under profiles/); other sizes were not measured
+    traffic = 15.5e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task) else None
     pair_info = {}
     if collide:
         sim.record_contacts(True)
