@@ -82,6 +82,9 @@ def _load():
     L.oracle_obs_dim.argtypes = [vp]
     L.oracle_set_threads.argtypes = [vp, C.c_int32]
     L.oracle_get_threads.argtypes = [vp]
+    L.oracle_set_warm_start.argtypes = [vp, C.c_double]
+    L.oracle_get_warm.argtypes = [vp, dp, dp]
+    L.oracle_set_warm.argtypes = [vp, dp, dp]
     L.oracle_reset.argtypes = [vp, C.c_void_p, C.c_uint64]
     L.oracle_set_state.argtypes = [vp, dp]
     L.oracle_get_state.argtypes = [vp, dp]
@@ -187,6 +190,7 @@ class OracleSim:
         self.obs_dim = L.oracle_obs_dim(self._h)
         self._trace = None
         L.oracle_set_threads(self._h, int(threads))
+        L.oracle_set_warm_start(self._h, float(getattr(p, "warm_start", 0.0)))
 
     def __del__(self):
         if getattr(self, "_h", None):
@@ -195,6 +199,21 @@ class OracleSim:
 
     def set_threads(self, n):
         self._L.oracle_set_threads(self._h, int(n))
+
+    def set_warm_start(self, share):
+        """Rows start each substep from `share` (0..1) of their impulse at the end of the previous one."""
+        self._L.oracle_set_warm_start(self._h, float(share))
+
+    def set_warm(self, lam_j, lam_s):
+        lj = np.ascontiguousarray(lam_j, np.float64).reshape(self.N, self.J, 6)
+        ls = np.ascontiguousarray(lam_s, np.float64).reshape(self.N, self.S, 3)
+        self._L.oracle_set_warm(self._h, _dp(lj), _dp(ls))
+
+    def get_warm(self):
+        """Impulses kept for the next substep: joints [N][J][6], terrain slots [N][S][3]."""
+        lj = np.zeros((self.N, self.J, 6)); ls = np.zeros((self.N, self.S, 3))
+        self._L.oracle_get_warm(self._h, _dp(lj), _dp(ls))
+        return lj, ls
 
     def reset(self, seed=0, mask=None):
         m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)

@@ -120,6 +120,8 @@ typedef struct {
    * collisions): body pairs of one agent that may touch, and the number of consecutive agents
    * that share one interaction group (1: agents do not see each other) */
   int NP, pair_a[MAXP], pair_b[MAXP], G;
+  /* warm start: share of the previous substep's impulses the rows start from (0: none) */
+  double warm;
 } model;
 
 typedef struct {
@@ -136,7 +138,16 @@ typedef struct {
   int has_store;           /* obs/reward/done of the last step kept (task mode packs at step end) */
   double obs_store[MAXOBS], rew_store;
   uint8_t done_store;
+  /* warm start: impulses at the end of the previous substep; for a limit row also which limit
+   * it stood for (0 lower, 1 upper), for a slot whether it was active */
+  double lam_j[MAXJ][6], lam_s[MAXS][3];
+  int side_j[MAXJ][3], lam_s_on[MAXS];
 } env_state;
+
+static void clear_warm(env_state* e) {
+  memset(e->lam_j, 0, sizeof e->lam_j); memset(e->lam_s, 0, sizeof e->lam_s);
+  memset(e->side_j, 0, sizeof e->side_j); memset(e->lam_s_on, 0, sizeof e->lam_s_on);
+}
 
 struct oracle_sim {
   model m;
@@ -717,7 +728,8 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
         joint_theta(m, e, j, th);
         for (int k = 0; k < 6; ++k) {
           row_t* r = &rows[nrows++];
-          r->a = a >= 0 ? f0 + a : -1; r->b = f0 + b; r->slot = -1; r->lambda = 0;
+          r->a = a >= 0 ? f0 + a : -1; r->b = f0 + b; r->slot = -1;
+          r->lambda = m->warm * e->lam_j[j][k];
           r->sca = a >= 0 ? W[f0 + a] : 0.0; r->scb = W[f0 + b];
           if (k < 3) {
             v3 ex = V(k == 0, k == 1, k == 2);
@@ -735,8 +747,12 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
               r->type = 0;
             } else {
               double glo = th[kk] - m->jlo[j][kk], ghi = m->jhi[j][kk] - th[kk], gg;
-              if (glo < ghi) { gg = glo; r->jaa = vscale(ak, -1); r->jab = ak; }
-              else { gg = ghi; r->jaa = ak; r->jab = vscale(ak, -1); }
+              int side;
+              if (glo < ghi) { gg = glo; r->jaa = vscale(ak, -1); r->jab = ak; side = 0; }
+              else { gg = ghi; r->jaa = ak; r->jab = vscale(ak, -1); side = 1; }
+              /* an impulse kept from the other limit would push the wrong way */
+              if (e->side_j[j][kk] >= 0 && side != e->side_j[j][kk]) r->lambda = 0;
+              envs[g].side_j[j][kk] = side;
               r->bias = gg >= 0 ? gg / h : m->beta_j * gg / h;
               r->type = 1;
             }
@@ -755,7 +771,8 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
         v3 dirs[3] = {n, t1, t2};
         for (int k = 0; k < 3; ++k) {
           row_t* r = &rows[nrows++];
-          r->a = -1; r->b = f0 + b; r->slot = s; r->lambda = 0;
+          r->a = -1; r->b = f0 + b; r->slot = s;
+          r->lambda = e->lam_s_on[s] ? m->warm * e->lam_s[s][k] : 0.0;
           r->sca = 0.0; r->scb = W[f0 + b] / wslot[g * S + s];
           r->jla = V(0, 0, 0); r->jaa = V(0, 0, 0);
           r->jlb = dirs[k]; r->jab = vcross(rc, dirs[k]);
@@ -802,6 +819,19 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
     }
     for (int g = 0; g < G; ++g)
       for (int b = 0; b < B; ++b) { vel[g * B + b] = envs[g].v[b]; om[g * B + b] = envs[g].w[b]; }
+    /* warm start: the impulses the rows start from act on the bodies before the first sweep */
+    if (m->warm > 0) {
+      for (int i = 0; i < nrows; ++i) {
+        const row_t* r = &rows[i];
+        if (r->lambda == 0) continue;
+        if (r->a >= 0) {
+          vel[r->a] = vadd(vel[r->a], vscale(r->jla, r->lambda / m->mass[r->a % B]));
+          om[r->a] = vadd(om[r->a], vscale(inv_inertia_apply(R[r->a], m->inertia[r->a % B], r->jaa), r->lambda));
+        }
+        vel[r->b] = vadd(vel[r->b], vscale(r->jlb, r->lambda / m->mass[r->b % B]));
+        om[r->b] = vadd(om[r->b], vscale(inv_inertia_apply(R[r->b], m->inertia[r->b % B], r->jab), r->lambda));
+      }
+    }
 
     /* 4. projected-Jacobi sweeps over blocks: every block starts from the same
      * velocity snapshot; inside a block the rows are relaxed one after another
@@ -885,6 +915,21 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
     }
     for (int g = 0; g < G; ++g)
       for (int b = 0; b < B; ++b) { envs[g].v[b] = vel[g * B + b]; envs[g].w[b] = om[g * B + b]; }
+    /* impulses kept for the next substep's warm start (terrain slots and joints; a contact
+     * between capsules always starts from zero) */
+    {
+      int i = 0;
+      for (int g = 0; g < G; ++g) {
+        env_state* e = &envs[g];
+        for (int j = 0; j < J; ++j)
+          for (int k = 0; k < 6; ++k) e->lam_j[j][k] = rows[i++].lambda;
+        for (int s = 0; s < S; ++s) {
+          e->lam_s_on[s] = e->con[s].active;
+          if (!e->con[s].active) continue;
+          for (int k = 0; k < 3; ++k) e->lam_s[s][k] = rows[i++].lambda;
+        }
+      }
+    }
   }
 
   /* 5. damping, angular-velocity cap, position integration */
@@ -1149,6 +1194,7 @@ static void reset_env(const model* m, env_state* e, int ei, uint64_t seed) {
     for (int d = 0; d < m->D; ++d) e->u[d] = 0;
     for (int s = 0; s < MAXS; ++s) clear_contact(&e->con[s]);
     e->has_store = 0;
+    clear_warm(e);
   }
 }
 void oracle_reset(oracle_sim* o, const uint8_t* mask, uint64_t seed) {
@@ -1252,7 +1298,33 @@ void oracle_set_state(oracle_sim* o, const double* st) {
       E->q[b].w = s[3]; E->q[b].x = s[4]; E->q[b].y = s[5]; E->q[b].z = s[6];
       E->v[b] = V(s[7], s[8], s[9]); E->w[b] = V(s[10], s[11], s[12]);
       E->has_store = 0;
+      clear_warm(E);
     }
+}
+void oracle_set_warm_start(oracle_sim* o, double share) { o->m.warm = share < 0 ? 0 : (share > 1 ? 1 : share); }
+void oracle_set_warm(oracle_sim* o, const double* lam_j, const double* lam_s) {
+  const int J = o->m.J, S = o->m.S;
+  for (int e = 0; e < o->N; ++e) {
+    env_state* E = &o->env[e];
+    for (int j = 0; j < J; ++j) {
+      for (int k = 0; k < 6; ++k) E->lam_j[j][k] = lam_j[((size_t)e * J + j) * 6 + k];
+      for (int k = 0; k < 3; ++k) E->side_j[j][k] = -1;   /* stands for whichever limit is nearer */
+    }
+    for (int q = 0; q < S; ++q) {
+      E->lam_s_on[q] = 1;
+      for (int k = 0; k < 3; ++k) E->lam_s[q][k] = lam_s[((size_t)e * S + q) * 3 + k];
+    }
+  }
+}
+void oracle_get_warm(const oracle_sim* o, double* lam_j, double* lam_s) {
+  const int J = o->m.J, S = o->m.S;
+  for (int e = 0; e < o->N; ++e) {
+    const env_state* E = &o->env[e];
+    for (int j = 0; j < J; ++j)
+      for (int k = 0; k < 6; ++k) lam_j[((size_t)e * J + j) * 6 + k] = E->lam_j[j][k];
+    for (int q = 0; q < S; ++q)
+      for (int k = 0; k < 3; ++k) lam_s[((size_t)e * S + q) * 3 + k] = E->lam_s_on[q] ? E->lam_s[q][k] : 0.0;
+  }
 }
 void oracle_get_state(const oracle_sim* o, double* st) {
   int B = o->m.B;

@@ -121,6 +121,20 @@ int32_t oracle_get_threads(const oracle_sim*);
 void oracle_reset(oracle_sim*, const uint8_t* env_mask /*NULL=all*/, uint64_t seed);
 void oracle_set_state(oracle_sim*, const double* state);
 void oracle_get_state(const oracle_sim*, double* state);
+/* Warm start (a stiffness gain within the Jacobi scheme, Section 3.1): every joint row and every
+ * terrain contact slot that was active in the previous substep starts from `share` (0..1, 0 =
+ * off, the default) times its impulse at the end of that substep; a limit row only if it stands
+ * for the same limit as then.  These impulses are applied to the bodies before the first sweep.
+ * Reset and oracle_set_state clear what is kept.  With few sweeps the kept impulse acts as an
+ * integrator on the position error, and a share of 1 can then grow without bound (a hanging
+ * chain at 4 sweeps does); 0.8 to 0.9 is the useful range. */
+void oracle_set_warm_start(oracle_sim*, double share);
+/* What is kept for the next substep: joint row impulses [N][J][6] (world x, y, z, then the three
+ * joint axes) and terrain slot impulses [N][S][3] (normal, two tangents; 0 for inactive slots). */
+void oracle_get_warm(const oracle_sim*, double* lam_j, double* lam_s);
+/* Overwrites what is kept (tests inject known impulses); a limit row's value then stands for
+ * whichever limit is the nearer one in the next substep. */
+void oracle_set_warm(oracle_sim*, const double* lam_j, const double* lam_s);
 void oracle_set_targets(oracle_sim*, const double* target_xy /*[N][2] env-local*/);
 void oracle_set_step_count(oracle_sim*, const int32_t* counts /*[N]*/);
 /* Switches the task logic on (or off with NULL / enabled 0) and initialises the per-env task

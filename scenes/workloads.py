@@ -32,6 +32,7 @@ class SimParams:
     height_map: int = 0            # 1: append the 15 x 11 terrain height map to the observation
     self_collide: int = 0          # 1: capsules of one robot collide (pairs: robots.collision_pairs)
     group_size: int = 1            # agents per interaction group (inter-agent collisions inside it)
+    warm_start: float = 0.0        # share (0..1) of the previous substep's impulses the rows start from
 
 
 @dataclass
