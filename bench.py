@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--group-size", type=int, default=1, help="agents per interaction group (inter-agent collisions)")
     ap.add_argument("--spacing", type=float, default=1.5, help="distance between the agents of a group, metres")
     ap.add_argument("--task", action="store_true", help="task logic of Section 4.1: pushes, flagrun targets, grace period, auto-reset")
+    ap.add_argument("--warm-start", type=float, default=0.0, help="share of the last substep's impulses the rows start from (0 = off)")
+    ap.add_argument("--iterations", type=int, default=0, help="override the sweeps per substep (the workload is then named for it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -78,6 +80,10 @@ def main():
     scene, cfg = scenes.config_scene(args.config, num_envs=args.num_envs or None)
     if args.height_map:
         scene.params.height_map = 1
+    if args.warm_start > 0:
+        scene.params.warm_start = args.warm_start
+    if args.iterations > 0:
+        cfg["iterations"] = args.iterations
     collide = args.self_collide or args.group_size > 1
     if collide:
         # the same robots, terrain and stepping parameters with capsule-capsule collisions on
@@ -139,7 +145,7 @@ def main():
     # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
     # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.6 MB
     # read + 6.9 MB written (summary under profiles/); other sizes were not measured
-    traffic = 15.5e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task) else None
+    traffic = 15.5e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task and not args.warm_start and not args.iterations) else None
     pair_info = {}
     if collide:
         sim.record_contacts(True)
@@ -160,7 +166,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": (cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")
                                + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else "")
-                               + ("_task" if args.task else ""),
+                               + ("_task" if args.task else "") + (f"_warm{args.warm_start:g}" if args.warm_start > 0 else "")
+                               + (f"_its{args.iterations}" if args.iterations > 0 else ""),
                    "num_envs": N, "obs_dim": sim.obs_dim, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",

@@ -45,6 +45,7 @@ class SimDesc(C.Structure):
         ("reset_noise", C.c_double), ("gyroscopic", C.c_int32), ("contacts", C.c_int32),
         ("height_map", C.c_int32),
         ("n_collide_pairs", C.c_int32), ("collide_pairs", C.POINTER(C.c_int32)), ("group_size", C.c_int32),
+        ("warm_start", C.c_double),
     ]
 
 
@@ -74,6 +75,7 @@ _SYMBOLS = {
     "sim_get_obs": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_set_task": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_task_state": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_get_kept_impulses": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_set_task_state": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_set_targets": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_state": [C.c_void_p, C.c_void_p, C.c_void_p],
@@ -164,6 +166,7 @@ def make_desc(scene):
     d.n_collide_pairs = int(pairs.shape[0])
     d.collide_pairs = pairs.ctypes.data_as(C.POINTER(C.c_int32)) if d.n_collide_pairs else None
     d.group_size = int(getattr(p, "group_size", 1))
+    d.warm_start = float(getattr(p, "warm_start", 0.0))
     return d, [bodies, joints, heights, origins, pairs]
 
 
@@ -206,6 +209,10 @@ def sim_set_task(h, task, stream):
     for name, _ in TaskDesc._fields_:
         setattr(t, name, getattr(task, name))
     return _chk(lib().sim_set_task(h, C.addressof(t), stream))
+
+
+def sim_get_kept_impulses(h, joint_rows_ptr, slot_rows_ptr, stream):
+    return _chk(lib().sim_get_kept_impulses(h, joint_rows_ptr, slot_rows_ptr, stream))
 
 
 def sim_get_task_state(h, counters_ptr, targets_ptr, push_ptr, stream):
@@ -285,6 +292,7 @@ class Sim:
             self.h = sim_create(self.desc, self.N, self._ws_ptr, nbytes)
         L = lib()
         self.B, self.S = L.sim_num_bodies(self.h), L.sim_num_slots(self.h)
+        self.J = int(scene.robot.n_joints)
         self.obs_dim, self.act_dim = L.sim_obs_dim(self.h), L.sim_act_dim(self.h)
         f32 = dict(dtype=torch.float32, device=self.device)
         self.obs = torch.zeros(self.N, self.obs_dim, **f32)
@@ -332,6 +340,14 @@ class Sim:
 
     def set_task(self, task):
         sim_set_task(self.h, task, self._stream())
+
+    def get_kept_impulses(self):
+        """Warm start: joint row impulses [N][J][6] and terrain slot impulses [N][S][3] kept for the next substep."""
+        t = self.torch
+        lj = t.zeros(self.N, self.J, 6, dtype=t.float32, device=self.device)
+        ls = t.zeros(self.N, self.S, 3, dtype=t.float32, device=self.device)
+        sim_get_kept_impulses(self.h, lj.data_ptr(), ls.data_ptr(), self._stream())
+        return lj, ls
 
     def get_task_state(self):
         t = self.torch

@@ -52,6 +52,7 @@ struct Model {
   float cell, inv_cell, hox, hoy;
   float g[3];
   float mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
+  float warm;   // warm start: share of the last substep's impulses the rows start from (0: none)
   float term_height, alive_bonus;
   int32_t max_steps, gyro, contacts;
   int32_t max_joint_sides;  // largest n_joint_sides over the bodies

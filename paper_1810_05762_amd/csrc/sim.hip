@@ -42,11 +42,11 @@ extern "C" const char* sim_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ layout
 struct Layout {
-  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, push, flag, pair_recs, pair_count, total;
+  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, push, flag, pair_recs, pair_count, lam_j, lam_s, total;
 };
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, size_t n_coarse, int pairs) {
+static Layout make_layout(int B, int J, int S, int obs_dim, int N, size_t n_heights, size_t n_coarse, int pairs, int warm) {
   Layout L;
   size_t o = 0;
   L.model = o; o = align_up(o + sizeof(Model));
@@ -65,6 +65,9 @@ static Layout make_layout(int B, int S, int obs_dim, int N, size_t n_heights, si
   // capsule-capsule contact records: one workgroup may hold as few as one env
   L.pair_recs = o; o = align_up(o + (pairs ? (size_t)N * kPairCap * sizeof(sim_pair_contact_rec_t) : 0));
   L.pair_count = o; o = align_up(o + (pairs ? (size_t)N * sizeof(int32_t) : 0));
+  // warm start: impulses kept from one step to the next, [J*6][N] and [S*3][N]
+  L.lam_j = o; o = align_up(o + (warm ? (size_t)N * J * 6 * sizeof(float) : 0));
+  L.lam_s = o; o = align_up(o + (warm ? (size_t)N * S * 3 * sizeof(float) : 0));
   L.flag = o; o = align_up(o + 256);   // (last: the diagnostic build keeps its counters here)
   L.total = o;
   return L;
@@ -204,6 +207,8 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   m->c_lin = (float)d->lin_damping; m->c_ang = (float)d->ang_damping;
   m->w_max = (float)std::fmin(d->max_ang_vel, 1e30);
   m->reset_noise = (float)d->reset_noise;
+  if (!(d->warm_start >= 0.0 && d->warm_start <= 1.0)) return fail(SIM_ERR_ARG, "warm_start %g outside 0..1", d->warm_start);
+  m->warm = (float)d->warm_start;
   m->term_height = (float)d->term_height; m->alive_bonus = (float)d->alive_bonus;
   m->max_steps = d->max_episode_steps; m->gyro = d->gyroscopic; m->contacts = d->contacts;
   // Height map of the complex-terrain task (Section 4.1: 15 x 11, follows the centre of mass,
@@ -231,6 +236,8 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   }
   if (d->group_size < 0 || d->group_size > kMaxGroup) return fail(SIM_ERR_ARG, "group_size %d outside 0..%d", d->group_size, kMaxGroup);
   m->group = d->group_size > 1 ? d->group_size : 1;
+  if (m->warm > 0.0f && (m->n_pairs > 0 || m->group > 1))
+    return fail(SIM_ERR_ARG, "warm_start is not available together with capsule-capsule collisions");
   m->n_agent_pairs = 0;
   for (int a = 0; a < m->group; ++a)
     for (int b = a + 1; b < m->group; ++b) {
@@ -256,11 +263,11 @@ static int pairs_of(const Model& m) { return (m.n_pairs > 0 || m.group > 1) ? (m
 // heightfield (more lanes for the contact search); small batches and the collision variant (which
 // needs the registers) keep the narrow one.
 static int threads_for(const Model& m, int E) {
-  return (E == 16 && m.terrain_kind == 1 && m.max_joint_sides <= 4 && !pairs_of(m)) ? kThreadsWide : kThreads;
+  return (E == 16 && m.terrain_kind == 1 && m.max_joint_sides <= 4 && !pairs_of(m) && !(m.warm > 0.0f)) ? kThreadsWide : kThreads;
 }
 static LdsPlan plan_for(const Model& m, int E) {
   const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
-  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m), threads_for(m, E));
+  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m), threads_for(m, E), m.warm > 0.0f ? 1 : 0);
 }
 
 static int default_envs_per_block(const Model& m, int N) {
@@ -369,6 +376,26 @@ __global__ void reset_kernel(const Model* Mp, float* __restrict__ state, int32_t
   reset_one_env(*Mp, state, steps, env, seed, N);
 }
 
+// Warm start: what is kept from step to step ([rows][N], rows = 6 per joint or 3 per slot) is
+// dropped for the envs of the mask (NULL: all).
+__global__ void clear_kept_kernel(float* __restrict__ lam, const uint8_t* __restrict__ mask, int rows, int N) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * N) return;
+  if (mask && !mask[i % N]) return;
+  lam[i] = 0.0f;
+}
+// [rows][N] -> [N][rows]; limit rows (bit (r % 6) - 3 of the joint's mask) carry the limit they
+// stood for in their sign, which is dropped here
+__global__ void get_kept_kernel(const float* __restrict__ lam, float* __restrict__ out, int rows, int N,
+                                const Model* Mp, int joints) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)rows * N) return;
+  const int env = (int)(i % N), r = (int)(i / N);
+  float v = lam[i];
+  if (joints && r % 6 >= 3 && Mp->joints[r / 6].mode[r % 6 - 3] == 1) v = fabsf(v);
+  out[(size_t)env * rows + r] = v;
+}
+
 // sim_set_task: episode 0 for every env, from the current body state
 __global__ void task_init_kernel(const Model* Mp, const float* __restrict__ state, int32_t* __restrict__ task_i,
                                  float* __restrict__ targets, float* __restrict__ push,
@@ -409,6 +436,8 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   const int pairs = pairs_of(m);
   a.pair_recs = (pairs && s->record && substeps > 0) ? reinterpret_cast<int32_t*>(s->ws + s->lay.pair_recs) : nullptr;
   a.pair_count = reinterpret_cast<int32_t*>(s->ws + s->lay.pair_count);
+  a.lam_j = reinterpret_cast<float*>(s->ws + s->lay.lam_j);
+  a.lam_s = reinterpret_cast<float*>(s->ws + s->lay.lam_s);
   a.pair_dropped = reinterpret_cast<int32_t*>(s->ws + s->lay.flag) + 1;
 #ifdef SIM_PHASE_TIMING
   a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
@@ -427,7 +456,9 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
     return SIM_OK;
   };
   const bool few = m.max_joint_sides <= 4;
-  int lrc = pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
+  int lrc = m.warm > 0.0f ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 0, kThreads, 1>)
+                             : few ? launch(&step_kernel<0, 4, 0, kThreads, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 1>))
+            : pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
                      : few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
             : threads == kThreadsWide ? launch(&step_kernel<16, 4, 0, kThreadsWide>)
             : (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
@@ -452,7 +483,7 @@ extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t*
   if (rc) return rc;
   if (!out_bytes) return fail(SIM_ERR_ARG, "out_bytes is NULL");
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
-  *out_bytes = make_layout(m.B, m.S, 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0), num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m)).total;
+  *out_bytes = make_layout(m.B, m.J, m.S, 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0), num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m), m.warm > 0.0f).total;
   return SIM_OK;
 }
 
@@ -468,7 +499,7 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
   size_t nh = desc->terrain_kind == 1 ? (size_t)desc->hf_nx * desc->hf_ny : 0;
   s->N = num_envs;
   s->obs_dim = 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0);
-  s->lay = make_layout(m.B, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m));
+  s->lay = make_layout(m.B, m.J, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m), m.warm > 0.0f);
   s->record = 0; s->recs_valid = 0; s->pair_grid = 0;
   memset(&s->task, 0, sizeof(s->task));
   s->E = default_envs_per_block(m, num_envs);
@@ -517,6 +548,10 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
     HIP_TRY_S(hipMemset(s->ws + s->lay.flag, 0, 256));
     HIP_TRY_S(hipMemset(s->ws + s->lay.task_i, 0, (size_t)num_envs * 4 * sizeof(int32_t)));
     HIP_TRY_S(hipMemset(s->ws + s->lay.push, 0, (size_t)num_envs * 3 * sizeof(float)));
+    if (m.warm > 0.0f) {
+      HIP_TRY_S(hipMemset(s->ws + s->lay.lam_j, 0, (size_t)num_envs * m.J * 6 * sizeof(float)));
+      HIP_TRY_S(hipMemset(s->ws + s->lay.lam_s, 0, (size_t)num_envs * m.S * 3 * sizeof(float)));
+    }
   }
   rc = launch_step(s, nullptr, 1.0f, 0, 0, 0, nullptr);
   if (rc) return bail(rc);
@@ -561,6 +596,33 @@ extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
   return SIM_OK;
 }
 
+static int clear_kept(sim* s, const uint8_t* mask, hipStream_t st) {
+  const Model& m = s->host_model;
+  if (!(m.warm > 0.0f)) return SIM_OK;
+  if (m.J > 0) hipLaunchKernelGGL(clear_kept_kernel, dim3(blocks_for((size_t)m.J * 6 * s->N)), dim3(256), 0, st,
+                                  reinterpret_cast<float*>(s->ws + s->lay.lam_j), mask, m.J * 6, s->N);
+  if (m.S > 0) hipLaunchKernelGGL(clear_kept_kernel, dim3(blocks_for((size_t)m.S * 3 * s->N)), dim3(256), 0, st,
+                                  reinterpret_cast<float*>(s->ws + s->lay.lam_s), mask, m.S * 3, s->N);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_get_kept_impulses(sim_t* s, float* joint_rows_dev, float* slot_rows_dev, void* stream) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  const Model& m = s->host_model;
+  if (!(m.warm > 0.0f)) return fail(SIM_ERR_ARG, "the sim was created without warm_start");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Model* dm = reinterpret_cast<const Model*>(s->ws + s->lay.model);
+  if (joint_rows_dev && m.J > 0)
+    hipLaunchKernelGGL(get_kept_kernel, dim3(blocks_for((size_t)m.J * 6 * s->N)), dim3(256), 0, st,
+                       reinterpret_cast<const float*>(s->ws + s->lay.lam_j), joint_rows_dev, m.J * 6, s->N, dm, 1);
+  if (slot_rows_dev && m.S > 0)
+    hipLaunchKernelGGL(get_kept_kernel, dim3(blocks_for((size_t)m.S * 3 * s->N)), dim3(256), 0, st,
+                       reinterpret_cast<const float*>(s->ws + s->lay.lam_s), slot_rows_dev, m.S * 3, s->N, dm, 0);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
 extern "C" int sim_reset(sim_t* s, const uint8_t* env_mask_dev, uint64_t seed, void* stream) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -569,6 +631,8 @@ extern "C" int sim_reset(sim_t* s, const uint8_t* env_mask_dev, uint64_t seed, v
                      reinterpret_cast<float*>(s->ws + s->lay.state),
                      reinterpret_cast<int32_t*>(s->ws + s->lay.steps), env_mask_dev, seed, s->N);
   HIP_TRY(hipGetLastError());
+  int rc = clear_kept(s, env_mask_dev, st);
+  if (rc) return rc;
   s->recs_valid = 0;
   return launch_step(s, nullptr, 1.0f, 0, 0, 0, st);
 }
@@ -676,6 +740,8 @@ extern "C" int sim_set_state(sim_t* s, const float* state_dev, void* stream) {
   hipLaunchKernelGGL(set_state_kernel, dim3(blocks_for(n)), dim3(256), 0, static_cast<hipStream_t>(stream),
                      state_dev, reinterpret_cast<float*>(s->ws + s->lay.state), s->host_model.B, s->N);
   HIP_TRY(hipGetLastError());
+  int rc = clear_kept(s, nullptr, static_cast<hipStream_t>(stream));
+  if (rc) return rc;
   s->recs_valid = 0;
   return launch_step(s, nullptr, 1.0f, 0, 0, 0, static_cast<hipStream_t>(stream));
 }

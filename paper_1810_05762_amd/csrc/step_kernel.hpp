@@ -65,6 +65,8 @@ struct StepArgs {
   int32_t* task_i;       // [N][4]: frames below the threshold, target age, frame of the next push, episode
   float* push;           // [N][3]: force on the root body during this step
   long long* dbg;        // phase-timing slots (diagnostic build only)
+  float* lam_j;          // warm start: [J*6][N] joint row impulses at the end of the last substep
+  float* lam_s;          //             [S*3][N] terrain slot impulses (0 for slots that were inactive)
   int32_t* pair_recs;    // [grid][kPairCap][8] capsule-capsule contacts of the last substep, or null
   int32_t* pair_count;   // [grid] their number per workgroup
   int32_t* pair_dropped; // [1] contacts dropped because a workgroup found more than kPairCap
@@ -77,11 +79,12 @@ constexpr int kVS = 7, kCS = 7, kJS = 13;
 struct LdsPlan {
   int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
   int pq, po, pnear, pbs, pcount, pbcnt, pblist;  // capsule-capsule contacts (only with pairs != 0)
+  int wj, wc;                                     // kept impulses of joints and slots (only with warm != 0)
 };
 
 // pairs: 0 = no capsule-capsule contacts, else the interaction group size (1 = self-collision only)
 __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch, int pairs = 0,
-                                             int threads = kThreads) {
+                                             int threads = kThreads, int warm = 0) {
   LdsPlan p;
   int o = 0;
   p.pos = o; o += B * 7 * E;
@@ -96,7 +99,8 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.rec = o; o += S * kRecWords * E;
   p.list = o; o += S * E;
   p.surv = o; o += S * E;
-  p.lam = o; o += 3 * (S * E > threads - ((2 * J * E + 63) / 64) * 64 ? S * E - (threads - ((2 * J * E + 63) / 64) * 64) : 0);
+  p.lam = o;   // (with the warm start these impulses live in the per-slot array below)
+  o += warm ? 0 : 3 * (S * E > threads - ((2 * J * E + 63) / 64) * 64 ? S * E - (threads - ((2 * J * E + 63) / 64) * 64) : 0);
   p.u = o; o += (D > 0 ? D : 1) * E;
   p.obs = o; o += (11 + 3 * D + F) * E;
   p.lim = o; o += (D > 0 ? D : 1) * E;
@@ -117,6 +121,8 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.pcount = o; o += pairs ? 4 : 0;
   p.pbcnt = o; o += pairs ? B * E : 0;                  // per body: how many of them touch it
   p.pblist = o; o += pairs ? (B * E * 6 + 3) / 4 : 0;  // per body: up to six of them, one byte each
+  p.wj = o; o += warm ? J * 6 * E : 0;
+  p.wc = o; o += warm ? S * 3 * E : 0;
   p.total = o;
   return p;
 }
@@ -217,6 +223,7 @@ struct SideRows {
   float Z[3][3];           // own angular response per unit impulse of angular row k
   float ame[3], anb[3], lam[3];
   int onesided;            // bit k set: angular row k is a limit row (impulse >= 0)
+  int upper;               // bit k set: that limit row stands for the upper limit
 };
 // value of the neighbouring lane (lane ^ 1), one DPP move
 __device__ __forceinline__ float lane_swap1(float x) {
@@ -296,6 +303,12 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
     vv[k] += c.ls * (c.dir[1][k] * d1 + c.dir[2][k] * d2);
     ww[k] += c.Y[1][k] * d1 + c.Y[2][k] * d2;
   }
+}
+
+// Warm start: the block's copy of its body after the impulses the rows start from.
+__device__ __forceinline__ void apply_contact_impulses(const ContactRows& c, float vv[3], float ww[3]) {
+  for (int r = 0; r < 3; ++r)
+    for (int k = 0; k < 3; ++k) { vv[k] += c.ls * c.dir[r][k] * c.lam[r]; ww[k] += c.Y[r][k] * c.lam[r]; }
 }
 
 // Rows of one capsule-capsule contact (Section 3.1: contacts among bodies; Section 4.1:
@@ -535,7 +548,7 @@ __device__ __forceinline__ int wave_alloc(int n, int* counter) {
 
 // PC != 0: capsule-capsule contacts (within an agent and between the agents of a group) compiled in.
 // NT: threads per workgroup.
-template <int EC, int NJ, int PC = 0, int NT = kThreads>
+template <int EC, int NJ, int PC = 0, int NT = kThreads, int WS = 0>
 __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   constexpr int kThreads = NT;   // (shadows the namespace-scope default inside the kernel)
 #ifdef SIM_PHASE_TIMING
@@ -559,7 +572,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   const Field H0 = make_field(M, a.heights, a.coarse);
   const bool use_patch = m_terrain == 1 && H0.nx >= kPatch && H0.ny >= kPatch;
   const int m_group = PC ? (M.group > 1 ? M.group : 1) : 1, m_npairs = PC ? M.n_pairs : 0, m_nap = PC ? M.n_agent_pairs : 0;
-  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0, NT);
+  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0, NT, WS);
   float* Lpos = lds + P.pos;
   float* Lvel = lds + P.vel;
   float* Liw = lds + P.iw;
@@ -603,6 +616,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   int* Lpcount = reinterpret_cast<int*>(lds + P.pcount);  // contacts found, near agent pairs
   int* Lpbcnt = reinterpret_cast<int*>(lds + P.pbcnt);
   uint8_t* Lpblist = reinterpret_cast<uint8_t*>(lds + P.pblist);
+  // Warm start (WS != 0): the impulse every joint row ([J*6][E]; a limit row's carries the limit it
+  // stood for in its sign, minus = upper) and every terrain slot row ([S*3][E]) ended the last
+  // substep with.  Slots that were not active then hold zero.
+  float* Lwj = lds + P.wj;
+  float* Lwc = lds + P.wc;
+  const float p_warm = WS ? M.warm : 0.0f;
   const float h = a.h;
 
   // ---- load: body state into registers, clipped actions into LDS
@@ -656,6 +675,16 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   }
   for (int i = tid; i < M.table_words; i += kThreads) reinterpret_cast<int*>(lds + P.tjs)[i] = M.table_image[i];
   for (int i = tid; i < (J * kJS + S * kCS) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
+  if constexpr (WS != 0) {
+    for (int i = tid; i < J * 6 * E; i += kThreads) {
+      const int env_i = blockIdx.x * E + i % E;
+      Lwj[i] = env_i < N ? a.lam_j[(size_t)(i / E) * N + env_i] : 0.0f;
+    }
+    for (int i = tid; i < S * 3 * E; i += kThreads) {
+      const int env_i = blockIdx.x * E + i % E;
+      Lwc[i] = env_i < N ? a.lam_s[(size_t)(i / E) * N + env_i] : 0.0f;
+    }
+  }
   if constexpr (PC != 0) {
     if (tid < 12) Lpo[kPairCap * 12 + tid] = 0.0f;   // the entry unused list slots point at
   }
@@ -1372,6 +1401,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       quat_to_mat(qa, Ra);
       rel_rotvec(qa, qb, phi);
       jr.onesided = 0;
+      jr.upper = 0;
       for (int k = 0; k < 3; ++k) {
         float ak[3], z[3];
         mat_vec(Ra, jt.axes[k], ak);
@@ -1381,7 +1411,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           bias = bh * th;
         } else {
           float glo = th - jt.lo[k], ghi = jt.hi[k] - th, g;
-          if (glo < ghi) { g = glo; } else { g = ghi; sgn = -1.0f; }
+          if (glo < ghi) { g = glo; } else { g = ghi; sgn = -1.0f; jr.upper |= 1 << k; }
           bias = g >= 0.0f ? g / h : bh * g;
           jr.onesided |= 1 << k;
         }
@@ -1405,6 +1435,8 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const int i = Llist[li < n_active ? li : n_active - 1];
         const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
         build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
+        if constexpr (WS != 0)
+          for (int r = 0; r < 3; ++r) cr.lam[r] = p_warm * Lwc[(sl * 3 + r) * E + ee];
       } else {
         cr = ContactRows{};
       }
@@ -1421,8 +1453,14 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         else pr = PairSide{};
       }
     };
+    // impulses of the contacts beyond one per thread: slot k of a small array, or (warm start) the
+    // contact's own place in the per-slot array, which already holds what was kept
+    auto overflow_lam = [&](int k, int r) -> float& {
+      if constexpr (WS != 0) { const int i = Llist[k]; return Lwc[(i / E * 3 + r) * E + i % E]; }
+      else return Llam[3 * (k - n_reg) + r];
+    };
     for (int k = n_reg + tid; k < n_active; k += kThreads)
-      for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = 0.0f;
+      for (int r = 0; r < 3; ++r) overflow_lam(k, r) = WS ? p_warm * overflow_lam(k, r) : 0.0f;
 
     TMARK(5);
     // The copies a body averages: NJ joint sides (unused entries point at joint 0's copy with
@@ -1526,10 +1564,28 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         if (!g_split) gather_part(std::integral_constant<int, 3>{}, 3);
       }
     };
+    // Warm start: sweep -1 relaxes nothing; every block applies the impulses it starts from (the
+    // kept ones times the share) to its copies, and the average of the copies hands every body
+    // the plain sum of them, as a sweep does with the increments.
     if (joint_wave) {
       build_joint_side();
       build_pair();
-      for (int it = 0; it < a.iterations; ++it) {
+      float acc[3] = {0.0f, 0.0f, 0.0f};   // impulses of the positional rows so far (kept for the next substep)
+      if constexpr (WS != 0) {
+        const int jj = js_j < J ? js_j : J - 1;
+        for (int k = 0; k < 3; ++k) acc[k] = p_warm * Lwj[(jj * 6 + k) * E + js_e];
+        for (int k = 0; k < 3; ++k) {
+          const float kept = Lwj[(jj * 6 + 3 + k) * E + js_e];
+          float l0 = p_warm * kept;
+          if (jr.onesided & (1 << k)) {
+            // kept for the other limit: it would push the wrong way
+            const bool was_upper = __float_as_int(kept) < 0, is_upper = (jr.upper >> k) & 1;
+            l0 = was_upper == is_upper ? fabsf(l0) : 0.0f;
+          }
+          jr.lam[k] = l0;
+        }
+      }
+      for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
         if (js_on) {
           const JointTab& jt = Ltjoint[js_j];
           const int e = js_e;
@@ -1540,21 +1596,34 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           for (int c = 0; c < 3; ++c) { vo[c] = live * Lvel[(bo * kVS + c) * E + e]; wo[c] = live * Lvel[(bo * kVS + 3 + c) * E + e]; }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
-            const float part = jr.sg * vo[k] + cross_unit_dot(jr.sr, k, wo);
-            const float jv = part + lane_swap1(part);
-            const float dl = jv * jr.pme[k] + jr.pnb[k];
+            float dl;
+            if (WS != 0 && it < 0) {
+              dl = acc[k];
+            } else {
+              const float part = jr.sg * vo[k] + cross_unit_dot(jr.sr, k, wo);
+              const float jv = part + lane_swap1(part);
+              dl = jv * jr.pme[k] + jr.pnb[k];
+              if constexpr (WS != 0) acc[k] += dl;
+            }
             vo[k] += jr.sv * dl;
             for (int c = 0; c < 3; ++c) wo[c] += jr.Y[k][c] * dl;
           }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
-            const float part = dot(jr.sax[k], wo);
-            const float jv = part + lane_swap1(part);
-            float dl = jv * jr.ame[k] + jr.anb[k];
-            if (jr.onesided & (1 << k)) {
-              float ln = fmaxf(jr.lam[k] + dl, 0.0f);
-              dl = ln - jr.lam[k];
-              jr.lam[k] = ln;
+            float dl;
+            if (WS != 0 && it < 0) {
+              dl = jr.lam[k];
+            } else {
+              const float part = dot(jr.sax[k], wo);
+              const float jv = part + lane_swap1(part);
+              dl = jv * jr.ame[k] + jr.anb[k];
+              if (jr.onesided & (1 << k)) {
+                float ln = fmaxf(jr.lam[k] + dl, 0.0f);
+                dl = ln - jr.lam[k];
+                jr.lam[k] = ln;
+              } else if constexpr (WS != 0) {
+                jr.lam[k] += dl;
+              }
             }
             for (int c = 0; c < 3; ++c) wo[c] += jr.Z[k][c] * dl;
           }
@@ -1569,15 +1638,32 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         gather();
         __syncthreads();
       }
+      if constexpr (WS != 0) {
+        // (both lanes of a joint hold the same impulses; the two sit in one wavefront, so the
+        // parent side's stores follow both lanes' reads above)
+        if (js_on && js_side == 0) {
+          for (int k = 0; k < 3; ++k) Lwj[(js_j * 6 + k) * E + js_e] = acc[k];
+          for (int k = 0; k < 3; ++k)
+            Lwj[(js_j * 6 + 3 + k) * E + js_e] = ((jr.onesided & jr.upper) >> k) & 1 ? -jr.lam[k] : jr.lam[k];
+        }
+      }
     } else {
+      if constexpr (WS != 0) {
+        // a slot that is not active in this substep hands nothing on to the next one (nobody
+        // reads its entries now; the records are final since the barrier after the contact search)
+        for (int i = tid - joint_threads; i < S * E; i += n_reg)
+          if (!Lreci[(i / E * kRecWords + 0) * E + i % E])
+            for (int r = 0; r < 3; ++r) Lwc[(i / E * 3 + r) * E + i % E] = 0.0f;
+      }
       build_contact();
       build_pair();
-      for (int it = 0; it < a.iterations; ++it) {
+      for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
         if (has_contact) {
           const int ee = cr.slot_e % E, sl = cr.slot_e / E;
           float vv[3], ww[3];
           for (int k = 0; k < 3; ++k) { vv[k] = Lvel[(cr.body * kVS + k) * E + ee]; ww[k] = Lvel[(cr.body * kVS + 3 + k) * E + ee]; }
-          relax_contact(cr, p_mu, vv, ww);
+          if (WS != 0 && it < 0) apply_contact_impulses(cr, vv, ww);
+          else relax_contact(cr, p_mu, vv, ww);
           for (int k = 0; k < 3; ++k) { Loutc[(sl * kCS + k) * E + ee] = vv[k]; Loutc[(sl * kCS + 3 + k) * E + ee] = ww[k]; }
         }
         for (int k = n_reg + (kThreads - 1 - tid); k < n_active; k += n_reg) {
@@ -1586,17 +1672,24 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
           ContactRows c2;
           build_contact_rows(c2, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
-          for (int r = 0; r < 3; ++r) c2.lam[r] = Llam[3 * (k - n_reg) + r];
+          for (int r = 0; r < 3; ++r) c2.lam[r] = overflow_lam(k, r);
           float vv[3], ww[3];
           for (int r = 0; r < 3; ++r) { vv[r] = Lvel[(body * kVS + r) * E + ee]; ww[r] = Lvel[(body * kVS + 3 + r) * E + ee]; }
-          relax_contact(c2, p_mu, vv, ww);
-          for (int r = 0; r < 3; ++r) Llam[3 * (k - n_reg) + r] = c2.lam[r];
+          if (WS != 0 && it < 0) apply_contact_impulses(c2, vv, ww);
+          else relax_contact(c2, p_mu, vv, ww);
+          for (int r = 0; r < 3; ++r) overflow_lam(k, r) = c2.lam[r];
           for (int r = 0; r < 3; ++r) { Loutc[(sl * kCS + r) * E + ee] = vv[r]; Loutc[(sl * kCS + 3 + r) * E + ee] = ww[r]; }
         }
         pair_sweep();
         __syncthreads();
         gather();
         __syncthreads();
+      }
+      if constexpr (WS != 0) {
+        if (has_contact) {
+          const int ee = cr.slot_e % E, sl = cr.slot_e / E;
+          for (int r = 0; r < 3; ++r) Lwc[(sl * 3 + r) * E + ee] = cr.lam[r];
+        }
       }
     }
 
@@ -1797,6 +1890,19 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     }
   }
   __syncthreads();
+  if constexpr (WS != 0) {
+    // the kept impulses go back to the workspace for the next launch; an env that was just reset
+    // starts its episode without any
+    if (a.substeps > 0) {
+      for (int i = tid; i < (J * 6 + S * 3) * E; i += kThreads) {
+        const int ee = i % E, env_i = blockIdx.x * E + ee;
+        if (env_i >= N) continue;
+        const bool fresh = may_reset && Lrst[ee];
+        if (i < J * 6 * E) a.lam_j[(size_t)(i / E) * N + env_i] = fresh ? 0.0f : Lwj[i];
+        else a.lam_s[(size_t)((i - J * 6 * E) / E) * N + env_i] = fresh ? 0.0f : Lwc[i - J * 6 * E];
+      }
+    }
+  }
   {
     const int env0 = blockIdx.x * E;
     const int n_here = min(E, N - env0);

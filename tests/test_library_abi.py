@@ -81,6 +81,25 @@ def test_collision_description_validation_needs_no_gpu():
         P.sim_workspace_bytes(d2, 64)
 
 
+def test_warm_start_description_validation_needs_no_gpu():
+    import paper_1810_05762_amd as P
+    rob = scenes.make_humanoid()
+    plain, _k = P.make_desc(scenes.make_scene(rob, scenes.make_plane(), 64))
+    warm, _k2 = P.make_desc(scenes.make_scene(rob, scenes.make_plane(), 64, params=scenes.SimParams(warm_start=0.8)))
+    assert warm.warm_start == 0.8 and plain.warm_start == 0.0
+    # room for the kept impulses: 6 per joint and 3 per slot, one float each, per env
+    extra = P.sim_workspace_bytes(warm, 64) - P.sim_workspace_bytes(plain, 64)
+    assert extra >= 64 * 4 * (6 * rob.n_joints + 3 * 2 * rob.n_bodies)
+    for bad in (-0.1, 1.5, float("nan")):
+        d, _k3 = P.make_desc(scenes.make_scene(rob, scenes.make_plane(), 64))
+        d.warm_start = bad
+        with pytest.raises(P.SimError):
+            P.sim_workspace_bytes(d, 64)
+    both = scenes.make_scene(rob, scenes.make_plane(), 64, params=scenes.SimParams(self_collide=1, warm_start=0.5))
+    with pytest.raises(P.SimError):
+        P.sim_workspace_bytes(P.make_desc(both)[0], 64)
+
+
 def test_product_package_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_1810_05762_amd")
     for dirpath, _, files in os.walk(pkg):
