@@ -1570,6 +1570,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     if (joint_wave) {
       build_joint_side();
       build_pair();
+      TMARK(17);
       float acc[3] = {0.0f, 0.0f, 0.0f};   // impulses of the positional rows so far (kept for the next substep)
       if constexpr (WS != 0) {
         const int jj = js_j < J ? js_j : J - 1;

@@ -20,7 +20,7 @@ MARKS = [(0, "load state, tables, heightfield patch"), (1, "A publish pose, inve
          (24, "B1a per-body reach pass (+ torques)"), (2, "B1b per-slot pass, own part"),
          (25, "B1b wait for the other wavefronts"), (10, "B2 stage 1, end spheres"),
          (11, "B2 stage 1, mid-segments"), (13, "B2 stage 2, exact distances"), (12, "B3 records"),
-         (3, "clear search space"), (16, "P capsule-capsule contacts"), (4, "C weight sums"), (5, "D row constants"), (6, "S sweeps"),
+         (3, "clear search space"), (16, "P capsule-capsule contacts"), (4, "C weight sums"), (5, "D row constants"), (17, "D joint rows (thread 0's wavefront)"), (6, "S sweeps"),
          (7, "E integrate"), (8, "store state"), (9, "obs / reward / done")]
 
 
