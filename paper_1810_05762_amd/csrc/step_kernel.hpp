@@ -8,19 +8,25 @@
 // consecutive global addresses of the [field][body][env] state arrays.
 // Roles (a thread can hold several):
 //   body thread  (e, b): owns pose and velocity of one body in registers,
-//   joint thread (e, j): owns the six rows of one joint (constants in registers),
+//   joint-side threads  : two neighbouring lanes own the six rows of one joint, one lane per
+//                         body (parent, child); a row's J v is the sum of the two lanes' parts,
 //   contact thread      : owns the three rows of one active contact slot (constants in
 //                         registers); a workgroup's contacts beyond one per thread are
 //                         rebuilt from their LDS record every sweep,
-//   env thread   (e)    : packs root observations, reward and done.
+//   pair-side threads   : (collision variant) two lanes per capsule-capsule contact,
+//   env thread   (e)    : packs root observations, reward and done, applies the task rules.
+// The joint-side threads fill the low wavefronts, the contact threads the high ones, so that a
+// wavefront runs either the joint or the contact branch of a sweep.
 //
 // Per substep (Section 3.1 of the paper: maximal coordinates, torque control,
 // speculative unilateral contacts, isotropic Coulomb friction, restitution 0):
 //   A  body threads publish pose and world inverse inertia
 //   B  contact generation per slot; joint threads turn actions into torques
 //   C  body threads count their blocks, integrate gravity/torque/gyroscopic term
+//   P  (collision variant) capsule-capsule contacts within an agent and within a group
 //   D  joint / contact threads build row constants
-//   S  `iterations` sweeps: every block relaxes its rows one after another on a
+//   S  (warm-start variant: sweep -1 applies the impulses kept from the last substep)
+//      `iterations` sweeps: every block relaxes its rows one after another on a
 //      private copy of its bodies taken from the shared snapshot; a body is
 //      shared out among its blocks by weight (joint 1, contact a ramp from 0 at
 //      the margin to 1 at half the margin) and acts inside block c with inverse
@@ -1344,12 +1350,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     TMARK(4);
     // ---- D: row constants
     const int n_active = Lcount[0];
-    // (with the capsule-capsule contacts compiled in, the joint rows and the contact rows are
-    // built inside the wavefront-uniform branches that use them, so that the two sets of
-    // registers are never alive together)
-    // (With the capsule-capsule contacts compiled in, every lane of the wavefronts concerned builds
-    // rows, the idle ones from a clamped index: a value assigned on every path is not carried from
-    // one substep into the next in registers, as a conditionally assigned one is.)
+    // The joint rows and the contact rows are built inside the wavefront-uniform branches that use
+    // them, so that the two sets of registers are never alive together.  Every lane of the
+    // wavefronts concerned builds rows, the idle ones from a clamped index: a value assigned on
+    // every path is not carried from one substep into the next in registers, as a conditionally
+    // assigned one is.
     auto build_joint_side = [&]() {
      {
       const JointTab& jt = Ltjoint[js_j < J ? js_j : J - 1];
