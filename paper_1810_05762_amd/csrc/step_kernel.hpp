@@ -227,7 +227,10 @@ struct SideRows {
   float pme[3], pnb[3];    // -m_eff and -m_eff * bias of the positional rows (world x, y, z)
   float sax[3][3];         // sg * joint axis k (sign of an upper limit folded in)
   float Z[3][3];           // own angular response per unit impulse of angular row k
-  float ame[3], anb[3], lam[3];
+  float ame[3], anb[3];
+  float nl[3];             // lower bound of the next increment of angular row k: minus the impulse so
+                           // far for a limit row (impulse >= 0), -infinity for a locked axis
+  float lam[3];            // impulses of the angular rows so far (only the warm start keeps them)
   int onesided;            // bit k set: angular row k is a limit row (impulse >= 0)
   int upper;               // bit k set: that limit row stands for the upper limit
 };
@@ -1384,9 +1387,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const float po = lane_swap1(pw[c]);
         C[c] = sg * (pw[c] - po);                        // child anchor minus parent anchor
         r[c] = 0.5f * (pw[c] + po) - xo[c];              // impulses act at the midpoint
-        jr.sr[c] = sg * r[c];
       }
-      jr.sg = sg;
+      // the world's side of a joint adds nothing to J v (whatever velocity its lane reads)
+      const float sgl = ghost ? 0.0f : sg;
+      for (int c = 0; c < 3; ++c) jr.sr[c] = sgl * r[c];
+      jr.sg = sgl;
       jr.sv = sg * no * imo;
       const float bh = p_beta_j / h;
       for (int k = 0; k < 3; ++k) {
@@ -1427,7 +1432,8 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         jr.ame[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
         jr.anb[k] = jr.ame[k] * bias;
         jr.lam[k] = 0.0f;
-        for (int c = 0; c < 3; ++c) { jr.sax[k][c] = sg * ak[c]; jr.Z[k][c] = sg * no * z[c]; }
+        jr.nl[k] = jt.mode[k] == 0 ? -INFINITY : 0.0f;
+        for (int c = 0; c < 3; ++c) { jr.sax[k][c] = sgl * ak[c]; jr.Z[k][c] = sg * no * z[c]; }
       }
      }
     };
@@ -1589,6 +1595,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
             l0 = was_upper == is_upper ? fabsf(l0) : 0.0f;
           }
           jr.lam[k] = l0;
+          if (jr.onesided & (1 << k)) jr.nl[k] = -l0;
         }
       }
       for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
@@ -1597,9 +1604,8 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           const int e = js_e;
           const int ob = js_side ? jt.child : jt.parent;
           const int bo = ob < 0 ? 0 : ob;
-          const float live = ob < 0 ? 0.0f : 1.0f;       // the world does not move
           float vo[3], wo[3];
-          for (int c = 0; c < 3; ++c) { vo[c] = live * Lvel[(bo * kVS + c) * E + e]; wo[c] = live * Lvel[(bo * kVS + 3 + c) * E + e]; }
+          for (int c = 0; c < 3; ++c) { vo[c] = Lvel[(bo * kVS + c) * E + e]; wo[c] = Lvel[(bo * kVS + 3 + c) * E + e]; }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
             float dl;
@@ -1622,14 +1628,10 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
             } else {
               const float part = dot(jr.sax[k], wo);
               const float jv = part + lane_swap1(part);
-              dl = jv * jr.ame[k] + jr.anb[k];
-              if (jr.onesided & (1 << k)) {
-                float ln = fmaxf(jr.lam[k] + dl, 0.0f);
-                dl = ln - jr.lam[k];
-                jr.lam[k] = ln;
-              } else if constexpr (WS != 0) {
-                jr.lam[k] += dl;
-              }
+              // a limit row's impulse stays >= 0: max(lam + dl, 0) - lam = max(dl, -lam)
+              dl = fmaxf(jv * jr.ame[k] + jr.anb[k], jr.nl[k]);
+              jr.nl[k] -= dl;
+              if constexpr (WS != 0) jr.lam[k] += dl;
             }
             for (int c = 0; c < 3; ++c) wo[c] += jr.Z[k][c] * dl;
           }
