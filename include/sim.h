@@ -191,9 +191,11 @@ int sim_num_slots(const sim_t* sim); /* contact slots per env */
 int sim_obs_dim(const sim_t* sim);   /* 11 + 3 * act_dim + n_feet */
 int sim_act_dim(const sim_t* sim);   /* number of actuated hinge DoF */
 
-/* Seeded reset (Section 4.1: initial state perturbed slightly): rest pose shifted by
- * uniform noise, a common linear velocity, every hinge angle perturbed and clipped to its
- * limits.  env_mask_dev: one byte per env, non-zero = reset; NULL = all envs. */
+/* Seeded reset (Section 4.1: positions, velocities, joint angles and joint angular velocities
+ * perturbed slightly): rest pose shifted by uniform noise, a uniform linear velocity of the body
+ * the joint tree hangs from, every hinge angle perturbed (clipped to its limits) and every hinge
+ * given a uniform rate, all of amplitude reset_noise; children are placed and moved so that their
+ * joints are assembled.  env_mask_dev: one byte per env, non-zero = reset; NULL = all envs. */
 int sim_reset(sim_t* sim, const uint8_t* env_mask_dev, uint64_t seed, void* stream);
 
 /* Advances all envs by dt in `substeps` substeps of `iterations` solver sweeps each and

@@ -1185,10 +1185,22 @@ static void reset_env(const model* m, env_state* e, int ei, uint64_t seed) {
       int pa = m->jp[j], b = m->jc[j];
       quat qa; v3 xa, Ra[3], Rb[3];
       joint_frames(m, e, j, Ra, &xa, &qa);
-      (void)pa;
       e->q[b] = qnormalize(qmul(qa, qexp(phi)));
       qmat(e->q[b], Rb);
       e->x[b] = vsub(vadd(xa, mrot(Ra, m->la[j])), mrot(Rb, m->lb[j]));
+      /* joint angular velocities (Section 4.1: perturbed slightly as well): a rate about every
+       * hinge axis; the child turns with the parent plus these rates, and its centre moves so
+       * that the two anchor points share one velocity (the world as a parent stands still) */
+      v3 va = V(0, 0, 0), wa = V(0, 0, 0), wb;
+      if (pa >= 0) { va = e->v[pa]; wa = e->w[pa]; }
+      wb = wa;
+      for (int k = 0; k < 3; ++k) {
+        if (m->jmode[j][k] != 1) continue;
+        double rate = a * (2 * oracle_uniform(seed, ei, 256 + 3 * j + k) - 1);
+        wb = vadd(wb, vscale(mrot(Ra, m->jaxes[j][k]), rate));
+      }
+      e->w[b] = wb;
+      e->v[b] = vsub(vadd(va, vcross(wa, mrot(Ra, m->la[j]))), vcross(wb, mrot(Rb, m->lb[j])));
     }
     e->steps = 0;
     for (int d = 0; d < m->D; ++d) e->u[d] = 0;

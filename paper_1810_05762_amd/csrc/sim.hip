@@ -349,21 +349,22 @@ __global__ void gen_contacts_kernel(const Model* Mp, const float* __restrict__ h
 
 // Seeded reset of one env by one thread: the poses are built in local arrays, then stored.
 struct LocalPoses {
-  float x[kMaxBodies][3], q[kMaxBodies][4];
+  float x[kMaxBodies][3], q[kMaxBodies][4], v[kMaxBodies][3], w[kMaxBodies][3];
   __device__ float& X(int b, int c) { return x[b][c]; }
   __device__ float& Q(int b, int c) { return q[b][c]; }
+  __device__ float& V(int b, int c) { return v[b][c]; }
+  __device__ float& W(int b, int c) { return w[b][c]; }
 };
 __device__ void reset_one_env(const Model& M, float* __restrict__ state, int32_t* __restrict__ steps, int env,
                               uint64_t seed, int N) {
   LocalPoses P;
-  float vel[3];
-  reset_pose(M, env, seed, P, vel);
+  reset_pose(M, env, seed, P);
   const size_t fs = (size_t)M.B * N;
   for (int b = 0; b < M.B; ++b) {
     float* st = state + (size_t)b * N + env;
     for (int c = 0; c < 3; ++c) st[c * fs] = P.x[b][c];
     for (int c = 0; c < 4; ++c) st[(3 + c) * fs] = P.q[b][c];
-    for (int c = 0; c < 3; ++c) { st[(7 + c) * fs] = vel[c]; st[(10 + c) * fs] = 0.0f; }
+    for (int c = 0; c < 3; ++c) { st[(7 + c) * fs] = P.v[b][c]; st[(10 + c) * fs] = P.w[b][c]; }
   }
   steps[env] = 0;
 }

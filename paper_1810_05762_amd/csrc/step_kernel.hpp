@@ -458,16 +458,20 @@ __device__ inline void task_draw_target(const TaskParams& t, int env, int episod
   target_xy[1] = ry + r * sinf(phi);
 }
 
-// Seeded reset (Section 4.1: initial state perturbed slightly): the rest pose displaced by a
-// uniform offset, every hinge angle drawn uniformly (clamped to its limits), bodies placed
-// parents-first through the joint list; one common linear velocity, no angular velocity.
-// `P` holds the poses while they are built: P.X(b, c) and P.Q(b, c) are references to position
-// component c and quaternion component c of body b (local arrays for the stand-alone reset
-// kernels, the env's column of the pose array in LDS for the reset at the end of a step).
+// Seeded reset (Section 4.1: positions, velocities, joint angles and joint angular velocities
+// perturbed slightly): the rest pose displaced by a uniform offset, every hinge angle and every
+// hinge rate drawn uniformly (angles clamped to their limits), bodies placed parents-first
+// through the joint list; the top of the tree gets one uniform linear velocity and no spin, a
+// child turns with its parent plus its hinge rates and moves so that the two anchor points of its
+// joint share one velocity (the world as a parent stands still).
+// `P` holds the state while it is built: P.X(b, c), P.Q(b, c), P.V(b, c), P.W(b, c) are
+// references to component c of position, quaternion, linear and angular velocity of body b (local
+// arrays for the stand-alone reset kernels, the env's columns of the pose and velocity arrays in
+// LDS for the reset at the end of a step).
 template <class Poses>
-__device__ inline void reset_pose(const Model& M, int env, uint64_t seed, Poses& P, float vel[3]) {
+__device__ inline void reset_pose(const Model& M, int env, uint64_t seed, Poses& P) {
   const float a = M.reset_noise;
-  float off[3];
+  float off[3], vel[3];
   for (int c = 0; c < 3; ++c) {
     off[c] = a * (2.0f * reset_uniform(seed, env, c) - 1.0f);
     vel[c] = a * (2.0f * reset_uniform(seed, env, 3 + c) - 1.0f);
@@ -475,6 +479,7 @@ __device__ inline void reset_pose(const Model& M, int env, uint64_t seed, Poses&
   for (int b = 0; b < M.B; ++b) {
     for (int c = 0; c < 3; ++c) P.X(b, c) = M.bodies[b].rest_pos[c] + off[c];
     P.Q(b, 0) = 1.0f; P.Q(b, 1) = 0.0f; P.Q(b, 2) = 0.0f; P.Q(b, 3) = 0.0f;
+    for (int c = 0; c < 3; ++c) { P.V(b, c) = vel[c]; P.W(b, c) = 0.0f; }
   }
   for (int j = 0; j < M.J; ++j) {
     const JointTab& jt = M.joints[j];
@@ -489,10 +494,10 @@ __device__ inline void reset_pose(const Model& M, int env, uint64_t seed, Poses&
     float dq[4];
     if (ang < 1e-12f) { dq[0] = 1.0f; dq[1] = 0.5f * phi[0]; dq[2] = 0.5f * phi[1]; dq[3] = 0.5f * phi[2]; }
     else { float s = sinf(0.5f * ang) / ang; dq[0] = cosf(0.5f * ang); dq[1] = s * phi[0]; dq[2] = s * phi[1]; dq[3] = s * phi[2]; }
-    float qa[4] = {1, 0, 0, 0}, xa[3] = {0, 0, 0};
+    float qa[4] = {1, 0, 0, 0}, xa[3] = {0, 0, 0}, va[3] = {0, 0, 0}, wa[3] = {0, 0, 0};
     if (jt.parent >= 0) {
       for (int c = 0; c < 4; ++c) qa[c] = P.Q(jt.parent, c);
-      for (int c = 0; c < 3; ++c) xa[c] = P.X(jt.parent, c);
+      for (int c = 0; c < 3; ++c) { xa[c] = P.X(jt.parent, c); va[c] = P.V(jt.parent, c); wa[c] = P.W(jt.parent, c); }
     }
     float qb[4];
     qb[0] = qa[0] * dq[0] - qa[1] * dq[1] - qa[2] * dq[2] - qa[3] * dq[3];
@@ -508,6 +513,18 @@ __device__ inline void reset_pose(const Model& M, int env, uint64_t seed, Poses&
     mat_vec(Rb, jt.lb, t1);
     for (int c = 0; c < 4; ++c) P.Q(jt.child, c) = qb[c];
     for (int c = 0; c < 3; ++c) P.X(jt.child, c) = xa[c] + t0[c] - t1[c];
+    float wb[3] = {wa[0], wa[1], wa[2]};
+    for (int k = 0; k < 3; ++k) {
+      if (jt.mode[k] != 1) continue;
+      const float rate = a * (2.0f * reset_uniform(seed, env, 256 + 3 * j + k) - 1.0f);
+      float ak[3];
+      mat_vec(Ra, jt.axes[k], ak);
+      for (int c = 0; c < 3; ++c) wb[c] += rate * ak[c];
+    }
+    float ca[3], cb[3];
+    cross(wa, t0, ca);
+    cross(wb, t1, cb);
+    for (int c = 0; c < 3; ++c) { P.W(jt.child, c) = wb[c]; P.V(jt.child, c) = va[c] + ca[c] - cb[c]; }
   }
 }
 // Start of an episode for the task logic (Section 4.1): counters cleared, first push time and
@@ -521,9 +538,11 @@ __device__ inline void task_begin_episode(const TaskParams& t, int32_t* __restri
 }
 // the env's column of the pose array in LDS ([body][7][E]) as the place reset_pose builds in
 struct LdsPoses {
-  float* Lpos; int E, ee;
+  float* Lpos; float* Lvel; int E, ee;
   __device__ float& X(int b, int c) { return Lpos[(b * 7 + c) * E + ee]; }
   __device__ float& Q(int b, int c) { return Lpos[(b * 7 + 3 + c) * E + ee]; }
+  __device__ float& V(int b, int c) { return Lvel[(b * kVS + c) * E + ee]; }
+  __device__ float& W(int b, int c) { return Lvel[(b * kVS + 3 + c) * E + ee]; }
 };
 
 // (squared distance, feature id) as one 64-bit word whose unsigned order is the lexicographic
@@ -1869,11 +1888,8 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       // next episode: the reset recipe with that episode's seed, built in this env's column of
       // the pose array (no other thread reads it before the barrier below)
       const int episode = a.task_i[4 * env_e + 3] + 1;
-      LdsPoses poses{Lpos, E, ee};
-      float v0[3];
-      reset_pose(M, env_e, a.task.seed + (uint64_t)episode * kEpisodeStride, poses, v0);
-      for (int bb = 0; bb < B; ++bb)
-        for (int c = 0; c < 3; ++c) { Lvel[(bb * kVS + c) * E + ee] = v0[c]; Lvel[(bb * kVS + 3 + c) * E + ee] = 0.0f; }
+      LdsPoses poses{Lpos, Lvel, E, ee};
+      reset_pose(M, env_e, a.task.seed + (uint64_t)episode * kEpisodeStride, poses);
       a.steps[env_e] = 0;
       task_begin_episode(a.task, a.task_i, a.targets, env_e, episode, Lpos[(rb * 7 + 0) * E + ee], Lpos[(rb * 7 + 1) * E + ee]);
     }

@@ -151,10 +151,29 @@ def test_reset_noise_is_seeded_bounded_and_kinematically_consistent():
     assert np.abs(th[:, hinge]).max() <= 0.05 + 1e-12
     assert np.abs(th[:, ~hinge]).max() < 1e-12
     assert (th[:, hinge] >= rob.j_lo[hinge] - 1e-12).all() and (th[:, hinge] <= rob.j_hi[hinge] + 1e-12).all()
-    # anchors coincide: the pose is assembled, so a solve without forces leaves it still
+    # joint angular velocities: one uniform rate per hinge axis, read back by the observation
+    D = rob.n_dofs
+    obs = o.get_obs()[0]
+    want = np.zeros((64, D))
+    for env in range(64):
+        for j in range(rob.n_joints):
+            for k in range(3):
+                if rob.j_mode[j, k] == scenes.HINGE:
+                    want[env, rob.j_act[j, k]] = 0.05 * (2 * oracle.uniform(123, env, 256 + 3 * j + k) - 1)
+    o.reset(123)
+    np.testing.assert_allclose(o.get_obs()[0][:, 11 + D:11 + 2 * D], want, atol=1e-12)
+    assert 0.03 < np.abs(want).max() <= 0.05
+    # the body the joint tree hangs from keeps the common velocity and does not turn
+    top = [b for b in range(rob.n_bodies) if b not in set(rob.j_child)]
+    assert len(top) == 1
+    assert np.abs(a[:, top[0], 10:13]).max() == 0 and 0.03 < np.abs(a[:, top[0], 7:10]).max() <= 0.05
+    # anchors coincide and share one velocity, locked axes do not turn: the state is assembled,
+    # so the bilateral rows see no error and no residual before the first sweep
     o.start_trace(0, 8)
     o.substep_phases(None, 1 / 240, 1, oracle.PH_SOLVE)
     assert o.trace()["pos_err_max"][0] < 1e-12
+    assert o.trace()["bilateral_max"][0] < 1e-12
+    o.reset(124)
     b = o.get_state()
     # masked reset touches only the chosen envs
     mask = np.zeros(64, np.uint8); mask[3] = 1
