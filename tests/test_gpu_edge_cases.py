@@ -153,3 +153,44 @@ def test_candidate_list_overflow_falls_back_to_the_direct_search():
     w = _run(sim, ref, sc, 4, 1 / 60, 4, 20, 10)
     assert w[1] <= 1e-4 and w[10] <= 1e-3, w
     sim.close(); sim2.close()
+
+
+@pytest.mark.parametrize("with_task", [False, True])
+def test_step_captured_in_a_graph_replays_like_eager_launches(with_task):
+    """sim_step_obs allocates nothing, does not synchronise and launches on the caller's stream,
+    so a caller can capture it in a HIP graph (here through torch) and replay it: every replay,
+    with eager work of the same sim in between, must equal the eager step bit for bit."""
+    import torch
+    import paper_1810_05762_amd as P
+    n = 300
+    sc, cfg = scenes.config_scene(3, num_envs=n)
+    dt = float(np.float32(cfg["dt"]))
+    tp = scenes.TaskParams(fall_grace_frames=3, target_period=11, push_min_frames=5, push_max_frames=9, auto_reset=1, seed=4)
+
+    def make():
+        sim = P.Sim(sc); sim.reset(cfg["seed"])
+        if with_task:
+            sim.set_task(tp)
+        return sim
+
+    acts = [torch.as_tensor(scenes.actions_for_step(cfg["seed"], s, n, sc.robot.n_dofs)).cuda() for s in range(30)]
+    eager, graphed = make(), make()
+    abuf = acts[0].clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.step_obs(abuf, dt, cfg["substeps"], cfg["iterations"])
+    # capturing runs nothing
+    assert torch.equal(graphed.get_state(), eager.get_state())
+    resets = 0
+    for k in range(30):
+        abuf.copy_(acts[k])
+        g.replay()
+        torch.cuda.synchronize()
+        eo, er, ed = eager.step_obs(acts[k], dt, cfg["substeps"], cfg["iterations"])
+        assert torch.equal(graphed.obs, eo) and torch.equal(graphed.reward, er) and torch.equal(graphed.done, ed)
+        assert torch.equal(graphed.get_state(), eager.get_state())     # eager launches of the graphed sim between replays
+        resets += int(ed.sum().item())
+    if with_task:
+        assert resets > 0
+    graphed.check(); eager.check()
+    graphed.close(); eager.close()
