@@ -259,11 +259,12 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
 
 // does this model generate capsule-capsule contacts, and with which group size (0: no)
 static int pairs_of(const Model& m) { return (m.n_pairs > 0 || m.group > 1) ? (m.group > 1 ? m.group : 1) : 0; }
-// Threads per workgroup of the step launch: the wide workgroup pays off for full workgroups on the
-// heightfield (more lanes for the contact search); small batches and the collision variant (which
-// needs the registers) keep the narrow one.
+// Threads per workgroup of the step launch: the wide workgroup pays off for full workgroups of 16
+// envs (more lanes for the contact search on the heightfield, a finer split of the velocity
+// average everywhere); small batches and the collision and warm-start variants (which need the
+// registers) keep the narrow one.
 static int threads_for(const Model& m, int E) {
-  return (E == 16 && m.terrain_kind == 1 && m.max_joint_sides <= 4 && !pairs_of(m) && !(m.warm > 0.0f)) ? kThreadsWide : kThreads;
+  return (E == 16 && m.max_joint_sides <= 4 && !pairs_of(m) && !(m.warm > 0.0f)) ? kThreadsWide : kThreads;
 }
 static LdsPlan plan_for(const Model& m, int E) {
   const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;

@@ -215,7 +215,7 @@ def test_reset_matches_oracle_recipe_and_mask():
 def test_results_are_deterministic_and_do_not_depend_on_neighbours_or_narrow_launch_shapes():
     """Bit-equal: two runs in the same launch shape; the narrow-workgroup shapes (8, 5, 1 envs per
     workgroup) among themselves; an env computed alone and among 150.  The wide workgroup that full
-    batches on the heightfield get (16 envs, 768 threads) is another instantiation of the kernel,
+    batches get (16 envs per workgroup, 768 threads) is another instantiation of the kernel,
     whose multiply-adds the compiler may contract differently: it agrees to rounding."""
     P = _P()
     sc, cfg = scenes.config_scene(3, num_envs=150)
