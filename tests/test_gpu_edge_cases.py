@@ -194,3 +194,36 @@ def test_step_captured_in_a_graph_replays_like_eager_launches(with_task):
         assert resets > 0
     graphed.check(); eager.check()
     graphed.close(); eager.close()
+
+
+def _max_size_robot():
+    """The largest robot the library takes: 16 capsules in a chain hung from the world, 16 joints
+    with two hinge axes each (32 actuated degrees of freedom)."""
+    from scenes.robots import _Builder
+    bld = _Builder("max16")
+    seg, r = 0.12, 0.03
+    prev = -1
+    for k in range(16):
+        a = (0.0, 0.0, 1.75 - k * seg)
+        b = bld.body(f"link{k}", r, seg, 2, (0.0, 0.0, 1.75 - (k + 0.5) * seg), mass=0.3)
+        bld.joint(prev, b, a, [((0.0, 1.0, 0.0), -1.0, 1.0), ((1.0, 0.0, 0.0), -0.8, 0.8)], 1.5)
+        prev = b
+    return bld.build(root_body=0, feet=(15,), term_height=-1e9, alive_bonus=0.0)
+
+
+@pytest.mark.parametrize("epb", [None, 14])
+def test_largest_robot_the_library_takes(epb):
+    rob = _max_size_robot()
+    assert (rob.n_bodies, rob.n_joints, rob.n_dofs) == (16, 16, 32)
+    sc = scenes.make_scene(rob, scenes.make_heightfield(seed=1003), 45)
+    sim, ref = _pair(sc)
+    if epb:
+        sim.set_envs_per_block(epb)
+    assert sim.obs_dim == 11 + 3 * 32 + 1 == ref.obs_dim
+    w = _run(sim, ref, sc, 12, 1 / 60, 4, 20, 10, warm=50)     # the chain swings down onto the terrain first
+    assert w[1] <= 1e-4 and w[10] <= 1e-3, w
+    og, rg, dg = (t.cpu().numpy() for t in sim.get_obs())
+    oo, ro, do = ref.get_obs()
+    assert np.abs(og - oo).max() <= 1e-3 * max(1.0, np.abs(oo).max())     # ten free-running steps: the state's bar
+    assert ref.get_contacts()["active"].sum() > 0
+    sim.close()

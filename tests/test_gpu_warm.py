@@ -168,3 +168,27 @@ def test_hanging_chain_keeps_its_static_tension_on_the_gpu():
         sag[share] = z_rest - st[0, -1, 2]
         sim.close()
     assert sag[0.9] == pytest.approx(0.1 * sag[0.0], rel=2e-2)
+
+
+def test_contacts_beyond_one_per_thread_keep_their_impulses_in_place():
+    """13 capsules lying on the ground in each of the 16 envs of one workgroup: 416 active contacts
+    for 128 contact threads; the other 288 are relaxed through the per-slot array of kept impulses
+    itself."""
+    P = _P()
+    sc = scenes.make_scene(scenes.make_raft(n_links=13), scenes.make_plane(), 16, params=scenes.SimParams(warm_start=0.8))
+    sim = P.Sim(sc); sim.set_envs_per_block(16)
+    st = scenes.rest_state(sc.robot, 16)
+    sim.set_state(st)
+    ref = oracle.OracleSim(sc, threads=4); ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))
+    assert sim.launch_info()["threads_per_block"] == 512
+    for s in range(10):
+        a = scenes.actions_for_step(4, s, 16, sc.robot.n_dofs)
+        sim.step(a, 1 / 60, 4, 20); ref.step(a, 1 / 60, 4, 20)
+        if s in (0, 9):
+            e = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state()).max()
+            (gj, gs), (oj, os_) = _kept(sim), ref.get_warm()
+            assert ref.get_contacts()["active"].sum() > 200 and (np.abs(os_[:, :, 0]) > 0).sum() > 30   # far more active contacts than contact threads
+            assert e <= (TOL_1 if s == 0 else TOL_10), (s, e)
+            assert np.abs(gs - os_).max() <= 1e-4 * max(1.0, np.abs(os_).max())
+            assert np.abs(gj - oj).max() <= 1e-4 * max(1.0, np.abs(oj).max())
+    sim.check(); sim.close()

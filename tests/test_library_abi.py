@@ -100,6 +100,26 @@ def test_warm_start_description_validation_needs_no_gpu():
         P.sim_workspace_bytes(P.make_desc(both)[0], 64)
 
 
+def test_robots_beyond_the_size_limits_are_rejected_without_a_gpu():
+    import paper_1810_05762_amd as P
+    from scenes.robots import _Builder
+
+    def chain(n, hinges):
+        bld = _Builder("chain")
+        prev = -1
+        for k in range(n):
+            b = bld.body(f"l{k}", 0.03, 0.1, 2, (0.0, 0.0, 3.0 - (k + 0.5) * 0.1), mass=0.3)
+            bld.joint(prev, b, (0.0, 0.0, 3.0 - k * 0.1), [((0.0, 1.0, 0.0), -1.0, 1.0), ((1.0, 0.0, 0.0), -1.0, 1.0), ((0.0, 0.0, 1.0), -1.0, 1.0)][:hinges], 1.0)
+            prev = b
+        return bld.build(root_body=0, feet=(), term_height=-1e9, alive_bonus=0.0)
+
+    ok = scenes.make_scene(chain(16, 2), scenes.make_plane(), 8)          # 16 bodies, 16 joints, 32 dofs: the limits
+    assert P.sim_workspace_bytes(P.make_desc(ok)[0], 8) > 0
+    for rob in (chain(17, 1), chain(12, 3)):                               # 17 bodies / joints; 36 dofs
+        with pytest.raises(P.SimError):
+            P.sim_workspace_bytes(P.make_desc(scenes.make_scene(rob, scenes.make_plane(), 8))[0], 8)
+
+
 def test_product_package_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_1810_05762_amd")
     for dirpath, _, files in os.walk(pkg):
