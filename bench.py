@@ -145,6 +145,10 @@ def main():
     # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
     # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.6 MB
     # read + 6.9 MB written (summary under profiles/); other sizes were not measured
+    # vector instructions per launch at the headline size (rocprofv3 SQ_INSTS_VALU, same summary):
+    # times 64 lanes, over the kernel time, against what 256 CUs x 4 SIMDs x 16 lanes issue per
+    # clock at 2.4 GHz without packed instructions
+    valu_insts = 43.6e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task and not args.warm_start and not args.iterations) else None
     traffic = 15.5e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task and not args.warm_start and not args.iterations) else None
     pair_info = {}
     if collide:
@@ -176,7 +180,8 @@ def main():
                    **sim.launch_info(), **pair_info},
         "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,
                      "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": traffic,
-                     "flops_per_env_step": fl, "kernel_ms": kern_ms},
+                     "flops_per_env_step": fl, "kernel_ms": kern_ms,
+                     "valu_issue_frac": (valu_insts * 64 / (kern_ms * 1e-3) / (256 * 4 * 16 * 2.4e9)) if valu_insts else None},
         "hbm_roofline": {
             "peak_GBps": 8000.0, "kernel_ms": kern_ms,
             "A_compulsory": {"bytes_per_env_step": bA, "GBps": bA * N / (kern_ms * 1e-3) / 1e9,
