@@ -323,20 +323,27 @@ def test_nonfinite_state_is_detected_by_check():
     sim.close()
 
 
-def test_full_size_headline_config_sampled_envs_match_oracle():
-    """4096 humanoids on the heightfield in the launch shape the benchmark times;
-    64 sampled envs are recomputed one by one by the oracle."""
+@pytest.mark.parametrize("share", [0.0, 0.8])
+def test_full_size_headline_config_sampled_envs_match_oracle(share):
+    """4096 humanoids on the heightfield in the launch shape the benchmark times (`share` > 0: with
+    the warm start, as `bench.py --warm-start` runs it); 64 sampled envs are recomputed one by one
+    by the oracle."""
+    import dataclasses
     P = _P()
     sc, cfg = scenes.config_scene(3)
+    sc.params = dataclasses.replace(sc.params, warm_start=share)
     N = sc.num_envs
     sim = P.Sim(sc)
     sim.reset(cfg["seed"])
     dt = float(np.float32(cfg["dt"]))
     for s in range(40):
         sim.step(scenes.actions_for_step(cfg["seed"], s, N, 21), dt, cfg["substeps"], cfg["iterations"])
+    if share > 0:
+        sim.set_state(sim.get_state())        # both sides start with nothing kept
     pick = np.random.default_rng(0).choice(N, 64, replace=False)
     pick[:2] = (0, N - 1)
     sub, _ = scenes.config_scene(3, num_envs=64)
+    sub.params = dataclasses.replace(sub.params, warm_start=share)
     sub.env_origins = sc.env_origins[pick].copy()
     ref = oracle.OracleSim(sub, threads=8)
     ref.set_state(sim.get_state().cpu().numpy()[pick].astype(np.float64))
