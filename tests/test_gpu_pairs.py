@@ -294,3 +294,40 @@ def test_task_logic_with_interacting_agents():
         steps = np.where(dg == 1, 0, steps + 1).astype(np.int32)
     assert episodes > n // 2 and contacts > 50
     sim.check(); sim.close()
+
+
+def test_full_size_collision_variant_sampled_groups_match_the_oracle():
+    """4096 humanoids on the heightfield in groups of 4 standing 1 m apart, in the launch shape
+    `bench.py --self-collide --group-size 4 --spacing 1.0` times; 16 sampled groups (64 envs) are
+    recomputed by the oracle."""
+    P = _P()
+    n, group = 4096, 4
+    rob, sc = _humanoid_scene(n, group, 1.0, "heightfield")
+    sim = P.Sim(sc)
+    sim.reset(5)
+    sim.record_contacts(True)
+    dt, sub, its = float(np.float32(1.0 / 60.0)), 4, 20
+    for s in range(40):
+        sim.step(scenes.actions_for_step(9, s, n, rob.n_dofs), dt, sub, its)
+    groups = np.random.default_rng(1).choice(n // group, 16, replace=False)
+    groups[:2] = (0, n // group - 1)
+    pick = (groups[:, None] * group + np.arange(group)[None, :]).reshape(-1)
+    _, small = _humanoid_scene(len(pick), group, 1.0, "heightfield")
+    small.env_origins = sc.env_origins[pick].copy()
+    ref = oracle.OracleSim(small, threads=8)
+    ref.set_state(sim.get_state().cpu().numpy()[pick].astype(np.float64))
+    errs = {}
+    for s in range(10):
+        a = scenes.actions_for_step(9, 40 + s, n, rob.n_dofs)
+        sim.step(a, dt, sub, its); ref.step(a[pick], dt, sub, its)
+        if s in (0, 9):
+            errs[s + 1] = np.asarray(rel_err(sim.get_state().cpu().numpy()[pick].astype(np.float64), ref.get_state())).reshape(len(pick), -1).max(1)
+    pg, dropped = sim.get_pair_contacts(cap=400000)
+    info = sim.launch_info()
+    print(f"full size, groups of 4: {len(pg)} capsule contacts in all, 1 step {errs[1].max():.2e}, 10 steps median {np.median(errs[10]):.2e} max {errs[10].max():.2e}")
+    assert info["envs_per_block"] == 16 and dropped == 0 and len(pg) > n // 2
+    assert errs[1].max() <= TOL_1
+    assert np.median(errs[10]) <= TOL_1 and np.quantile(errs[10], 0.9) <= TOL_10
+    g = sim.get_state().cpu().numpy()
+    assert np.isfinite(g).all()
+    sim.check(); sim.close()
