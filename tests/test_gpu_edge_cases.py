@@ -109,7 +109,8 @@ def test_hub_with_six_joints_uses_the_general_kernel():
 
 def test_more_active_contacts_than_contact_threads():
     """13 capsules lying on the ground in each of 16 envs of one workgroup: 416 active end-sphere
-    contacts for 320 contact threads, the rest go through the LDS-resident impulse path."""
+    contacts for the 384 contact threads of the 768-thread workgroup (12 joints x 2 sides x 16 envs
+    take the other 384), the rest go through the LDS-resident impulse path."""
     sc = scenes.make_scene(scenes.make_raft(n_links=13), scenes.make_plane(), 16)
     sim, ref = _pair(sc)
     sim.set_envs_per_block(16)
