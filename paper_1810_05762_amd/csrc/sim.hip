@@ -463,7 +463,6 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
             : pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
                      : few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
             : threads == kThreadsWide ? launch(&step_kernel<16, 4, 0, kThreadsWide>)
-            : (s->E == 16 && few) ? launch(&step_kernel<16, 4>)
             : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
             : (s->E == 4 && few) ? launch(&step_kernel<4, 4>)
             : (s->E == 2 && few) ? launch(&step_kernel<2, 4>)
