@@ -318,7 +318,8 @@ class Sim:
         t = self.torch
         if isinstance(a, t.Tensor):
             return a.to(device=self.device, dtype=dtype).contiguous()
-        return t.as_tensor(np.ascontiguousarray(a), dtype=dtype).to(self.device)
+        # (a copy: torch refuses to wrap arrays that are not writable, e.g. broadcast views)
+        return t.as_tensor(np.array(a, order="C", copy=True), dtype=dtype).to(self.device)
 
     def reset(self, seed=0, mask=None):
         m = None if mask is None else self._dev(mask, self.torch.uint8)

@@ -34,24 +34,5 @@ def build(force=True, verbose=False, extra=()):
     return LIB_PATH
 
 
-TIMING_LIB_PATH = os.path.join(HERE, "libsim355_timing.so")
-
-
-def build_timing():
-    """Diagnostic variant of the library with per-phase cycle counters (see phase_timing.py)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    subprocess.run([hipcc] + HIPCC_FLAGS + ["-DSIM_PHASE_TIMING", "-o", TIMING_LIB_PATH] + SOURCES, check=True)
-    return TIMING_LIB_PATH
-
-
-def build_issue_probe():
-    """Stand-alone microbenchmark of the per-wavefront instruction issue rate (csrc/issue_probe.hip)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = os.path.join(HERE, "issue_probe")
-    subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                    "-o", out, os.path.join(HERE, "csrc", "issue_probe.hip")], check=True)
-    return out
-
-
 if __name__ == "__main__":
     build(force=True, verbose=True)
