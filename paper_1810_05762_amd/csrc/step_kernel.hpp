@@ -250,7 +250,7 @@ struct ContactRows {
 };
 
 // Phase timing (diagnostic build, -DSIM_PHASE_TIMING): thread 0 of workgroup 7 adds the cycles
-// since the previous mark to slot k of a small buffer in the workspace (phase_timing.py reads it).
+// since the previous mark to slot k of a small buffer in the workspace.
 // Each mark costs a few hundred cycles itself, so marks are kept out of the sweep loop.
 #ifdef SIM_PHASE_TIMING
 #define TMARK(k) do { if (tid == 0 && blockIdx.x == 7) { long long _t = clock64(); a.dbg[k] += _t - t_last; t_last = _t; } } while (0)
@@ -893,8 +893,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       float gy[3];
       cross(wb, Iw, gy);
       if (!p_gyro) { gy[0] = gy[1] = gy[2] = 0.0f; }
-      for (int c = 0; c < 3; ++c) wb[c] += h * (tb[c] - gy[c]) * invIb[c];
-      mat_vec(R, wb, w);
+      // only the increment goes back to the world frame (the velocity itself is not rotated
+      // there and back, which would round it six times more)
+      float dwb[3], dww[3];
+      for (int c = 0; c < 3; ++c) dwb[c] = h * (tb[c] - gy[c]) * invIb[c];
+      mat_vec(R, dwb, dww);
+      for (int c = 0; c < 3; ++c) w[c] += dww[c];
       for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
     };
     int n_b1 = S * E;            // slots the per-slot pass visits
@@ -1489,8 +1493,6 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       if constexpr (WS != 0) { const int i = Llist[k]; return Lwc[(i / E * 3 + r) * E + i % E]; }
       else return Llam[3 * (k - n_reg) + r];
     };
-    for (int k = n_reg + tid; k < n_active; k += kThreads)
-      for (int r = 0; r < 3; ++r) overflow_lam(k, r) = WS ? p_warm * overflow_lam(k, r) : 0.0f;
 
     TMARK(5);
     // The copies a body averages: NJ joint sides (unused entries point at joint 0's copy with
@@ -1528,8 +1530,14 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         // every load is unconditional: unused entries read a valid location and enter the sum
         // with weight 0 (the copy arrays only ever hold finite numbers); all reads are issued
         // before the first use so their LDS latency is paid once
+        // The average is taken over the copies' differences from the snapshot, (sum of w_k (copy_k -
+        // v0)) / W added to v0: the differences are small next to the velocity itself, so the sum
+        // rounds at their magnitude and the velocity is rounded once per sweep, where a weighted
+        // sum of the copies themselves would round it once per copy.
         const int ho = c0 * E;
-        float val[NJ + 3][NC];
+        float val[NJ + 3][NC], v0[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) v0[c] = Lvel[(g_b * kVS + c) * E + e + ho];
 #pragma unroll
         for (int k = 0; k < NJ; ++k)
 #pragma unroll
@@ -1538,14 +1546,14 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         for (int k = 0; k < 3; ++k)
 #pragma unroll
           for (int c = 0; c < NC; ++c) val[NJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
-        __builtin_amdgcn_sched_group_barrier(0x100, NC == 3 ? (NJ + 3) * 2 : NJ + 3, 0);  // the DS reads first
+        __builtin_amdgcn_sched_group_barrier(0x100, NC == 3 ? (NJ + 4) * 2 : NJ + 4, 0);  // the DS reads first
         float acc[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
 #pragma unroll
         for (int k = 0; k < NJ + 3; ++k)
 #pragma unroll
-          for (int c = 0; c < NC; ++c) acc[c] += gat_w[k] * val[k][c];
+          for (int c = 0; c < NC; ++c) acc[c] += gat_w[k] * (val[k][c] - v0[c]);
         if constexpr (PC != 0) {
           if (n_pc > 0) {
             if (gp_many) {
@@ -1557,6 +1565,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
                 if (((refs >> 16) & 0xffff) == g_ref)
                   for (int c = 0; c < NC; ++c) acc[c] += Lpo[k * 12 + 6 + c0 + c];
               }
+              for (int c = 0; c < NC; ++c) acc[c] -= gp_wsum * v0[c];   // (their copies come multiplied by the weights)
             } else {
               // the (weighted) copies of the listed contacts; unused entries point at zeros
               float pv[kPairList][NC];
@@ -1568,10 +1577,13 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
               for (int j = 0; j < kPairList; ++j)
 #pragma unroll
                 for (int c = 0; c < NC; ++c) acc[c] += pv[j][c];
+              // (the listed copies come multiplied by their weights: the snapshot's share goes off in one piece)
+#pragma unroll
+              for (int c = 0; c < NC; ++c) acc[c] -= gp_wsum * v0[c];
             }
           }
         }
-        for (int c = 0; c < NC; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = acc[c] * g_inb;
+        for (int c = 0; c < NC; ++c) Lvel[(g_b * kVS + c) * E + e + ho] = v0[c] + acc[c] * g_inb;
       }
     };
     // one sweep of this thread's side of a capsule-capsule contact, if it has one
@@ -1684,6 +1696,10 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       }
       build_contact();
       build_pair();
+      // the starting impulses of the contacts beyond one per thread are set by the thread that
+      // relaxes them in every sweep below (same index mapping), so no other thread's store is read
+      for (int k = n_reg + (kThreads - 1 - tid); k < n_active; k += n_reg)
+        for (int r = 0; r < 3; ++r) overflow_lam(k, r) = WS ? p_warm * overflow_lam(k, r) : 0.0f;
       for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
         if (has_contact) {
           const int ee = cr.slot_e % E, sl = cr.slot_e / E;
