@@ -161,7 +161,9 @@ def test_humanoids_with_collisions(group, terrain, n_envs):
     print(f"group {group} {terrain}: {total} pair contacts sampled ({inter} between agents); 1 step max {errs[1].max():.2e}, "
           f"10 steps median {np.median(errs[10]):.2e} p95 {np.quantile(errs[10], .95):.2e} max {errs[10].max():.2e}")
     assert errs[1].max() <= TOL_1
-    assert np.median(errs[10]) <= TOL_1 and np.quantile(errs[10], 0.9) <= TOL_10
+    # (contact sets are compared on the teacher-forced substeps above; in the free run every env
+    #  has to stay within the ten-step tolerance, whatever its contact sets did)
+    assert np.median(errs[10]) <= TOL_1 and errs[10].max() <= TOL_10
     sim.check(); sim.close()
 
 
@@ -327,7 +329,7 @@ def test_full_size_collision_variant_sampled_groups_match_the_oracle():
     print(f"full size, groups of 4: {len(pg)} capsule contacts in all, 1 step {errs[1].max():.2e}, 10 steps median {np.median(errs[10]):.2e} max {errs[10].max():.2e}")
     assert info["envs_per_block"] == 16 and dropped == 0 and len(pg) > n // 2
     assert errs[1].max() <= TOL_1
-    assert np.median(errs[10]) <= TOL_1 and np.quantile(errs[10], 0.9) <= TOL_10
+    assert np.median(errs[10]) <= TOL_1 and errs[10].max() <= TOL_10       # every sampled env
     g = sim.get_state().cpu().numpy()
     assert np.isfinite(g).all()
     sim.check(); sim.close()

@@ -10,22 +10,12 @@ import scenes
 
 pytestmark = pytest.mark.gpu
 
-TOL_1, TOL_10 = 1e-4, 1e-3
+from helpers import TOL_1, TOL_10, gate_after_10_steps, rel_err4 as rel_err
 
 
 def _P():
     import paper_1810_05762_amd as P
     return P
-
-
-def rel_err(g, o):
-    """[N][4]: error of position, quaternion, linear and angular velocity per env."""
-    out = []
-    for sl in (slice(0, 3), slice(3, 7), slice(7, 10), slice(10, 13)):
-        d = np.abs(g[:, :, sl] - o[:, :, sl]).reshape(g.shape[0], -1).max(1)
-        n = np.maximum(1.0, np.abs(o[:, :, sl]).reshape(g.shape[0], -1).max(1))
-        out.append(d / n)
-    return np.stack(out, 1)
 
 
 def _start(k, n_envs, warm, envs_per_block=None):
@@ -76,27 +66,18 @@ def test_state_parity_after_1_and_10_steps(k, n_envs, warm, epb):
             sim.step(a, h, 1, its)
             ref.step(a, h, 1, its)
             cg, co = sim.get_contacts(), ref.get_contacts()
-            forked |= (cg["active"] != co["active"]).any(1) | (cg["feat"] != co["feat"]).any(1)
+            forked |= np.any([(cg[f] != co[f]).any(1) for f in ("active", "kind", "feat")], axis=0)
         if s in (0, 9):
-            errs[s + 1] = (rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state()).max(1),
-                           forked.copy())
+            errs[s + 1] = (rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state()), forked.copy())
     sim.check()
     (e1, f1), (e10, f10) = errs[1], errs[10]
-    print(f"config {k}: 1 step max {e1[~f1].max():.2e} ({f1.sum()} forked, max {e1.max():.2e}); 10 steps "
-          f"median {np.median(e10):.2e} p95 {np.quantile(e10, .95):.2e} max unforked {e10[~f10].max():.2e} "
-          f"({f10.sum()}/{n_envs} forked, max {e10.max():.2e})")
     assert ref.get_contacts()["active"].sum() > n_envs      # the comparison is contact-rich
-    # 1 step: every env.  10 steps: every env on the plane configs; on the heightfield the bulk
-    # (median and 95th percentile), because a nearest-feature tie at a crease, or plain chaotic
-    # growth of fp32 rounding over 40-80 contact-rich substeps, lets a few percent of the envs
-    # drift past 1e-3 (the oracle does the same against a copy of itself whose state is rounded
-    # to fp32 every substep, see test_oracle_sensitivity.py).
+    # 1 step: every env, forked or not
+    print(f"config {k}: 1 step max {e1.max():.2e} ({f1.sum()} forked)")
     assert e1.max() <= TOL_1
-    assert np.median(e10) <= TOL_1 and np.quantile(e10, 0.95) <= TOL_10
-    if sc.terrain.kind == scenes.PLANE:
-        assert e10.max() <= TOL_10
-    else:
-        assert (e10 > TOL_10).mean() <= 0.05
+    # 10 steps: every env whose contact sets never differed within 1e-3; the others reported
+    gate_after_10_steps(e10, f10, many_impacts=cfg["fallen"], label=f"config {k}: ")
+    assert np.median(e10.max(1)) <= TOL_1
     sim.close()
 
 
@@ -357,10 +338,10 @@ def test_full_size_headline_config_sampled_envs_match_oracle(share):
     g = sim.get_state().cpu().numpy().astype(np.float64)
     e10 = rel_err(g[pick], ref.get_state()).max(1)
     print(f"full size: 1 step {e1:.2e}, 10 steps median {np.median(e10):.2e} max {e10.max():.2e}")
-    # one step: every sampled env; ten steps: the gate of the heightfield configurations above
-    # (contact-rich substeps amplify fp32 rounding chaotically in a few envs)
+    # whole steps in the benchmark's launch shape: contact sets are not compared per substep here,
+    # so every sampled env has to stay within the tolerances, forked or not
     assert e1 <= TOL_1
-    assert np.median(e10) <= TOL_1 and np.quantile(e10, 0.95) <= TOL_10 and (e10 > TOL_10).mean() <= 0.05
+    assert e10.max() <= TOL_10 and np.median(e10) <= TOL_1
     # properties that hold at any size
     assert np.isfinite(g).all()
     np.testing.assert_allclose(np.linalg.norm(g[:, :, 3:7], axis=2), 1.0, atol=1e-5)

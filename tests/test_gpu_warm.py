@@ -10,7 +10,7 @@ import pytest
 import oracle
 import scenes
 from helpers import free_params, single_scene
-from test_gpu_parity import TOL_1, TOL_10, rel_err
+from helpers import TOL_1, TOL_10, gate_after_10_steps, rel_err4 as rel_err
 
 pytestmark = pytest.mark.gpu
 G = 9.81
@@ -57,31 +57,37 @@ def test_states_and_kept_impulses_match_the_oracle(k, n_envs, settle, epb, split
     sc, cfg, sim, ref, dt = _start(k, n_envs, settle, epb, 0.8)
     sub, its = cfg["substeps"], cfg["iterations"]
     errs, lam_err = {}, {}
+    sim.record_contacts(True)
+    forked = np.zeros(n_envs, bool)
+
+    def compare_sets():
+        cg, co = sim.get_contacts(), ref.get_contacts()
+        return np.any([(cg[f] != co[f]).any(1) for f in ("active", "kind", "feat")], axis=0)
+
     for s in range(10):
         a = scenes.actions_for_step(cfg["seed"], settle + s, n_envs, sc.robot.n_dofs)
         if split:
             for _ in range(sub):
                 sim.step(a, dt / sub, 1, its); ref.step(a, dt / sub, 1, its)
+                forked |= compare_sets()
         else:
             sim.step(a, dt, sub, its); ref.step(a, dt, sub, its)
+            forked |= compare_sets()            # (the sets of the step's last substep)
         if s in (0, 9):
-            errs[s + 1] = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state()).max(1)
+            errs[s + 1] = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
             (gj, gs), (oj, os_) = _kept(sim), ref.get_warm()
             scale = max(1.0, np.abs(oj).max(), np.abs(os_).max())
             lam_err[s + 1] = np.array([np.abs(gj - oj).reshape(n_envs, -1).max(1), np.abs(gs - os_).reshape(n_envs, -1).max(1)]).max(0) / scale
             assert np.abs(oj).max() > 0.1 and np.abs(os_).max() > 0.01       # there is something to compare
     sim.check()
     e1, e10 = errs[1], errs[10]
-    print(f"config {k} warm: 1 step {e1.max():.2e}, 10 steps median {np.median(e10):.2e} p95 {np.quantile(e10, .95):.2e} max {e10.max():.2e}; "
-          f"kept impulses 1 step {lam_err[1].max():.2e}, 10 steps median {np.median(lam_err[10]):.2e}")
+    print(f"config {k} warm: 1 step {e1.max():.2e}; kept impulses 1 step {lam_err[1].max():.2e}, 10 steps median {np.median(lam_err[10]):.2e}")
     assert e1.max() <= TOL_1
     assert lam_err[1].max() <= 1e-4
-    assert np.median(e10) <= TOL_1 and np.quantile(e10, 0.95) <= TOL_10
+    # ten steps: every env whose contact sets never differed within 1e-3, the others reported
+    gate_after_10_steps(e10, forked, label=f"config {k} warm: ")
+    assert np.median(e10.max(1)) <= TOL_1
     assert np.median(lam_err[10]) <= 1e-3
-    if sc.terrain.kind == scenes.PLANE:
-        assert e10.max() <= TOL_10
-    else:
-        assert (e10 > TOL_10).mean() <= 0.05
     sim.close()
 
 

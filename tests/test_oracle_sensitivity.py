@@ -47,3 +47,79 @@ def test_fp32_state_storage_alone_spreads_trajectories(k, warm):
     assert e1.max() < 1e-4
     assert np.median(e10) < 1e-4
     assert e10.max() > 20 * np.median(e1)
+
+
+def test_a_closing_speculative_contact_turns_a_position_difference_into_velocity_over_h():
+    """Section 3.1, speculative contacts: a contact whose gap d would close within the substep
+    leaves the body the approach speed d / h exactly (restitution 0).  Two spheres that differ by
+    delta in height therefore differ by delta / h in velocity after the impact substep: the step map
+    multiplies position differences by 1 / h (480 per second in the configuration with 8 substeps)."""
+    from helpers import free_params, single_scene
+    h, r, d, delta, v0 = 1.0 / 120.0, 0.1, 0.010, 1e-6, -2.0
+    out = []
+    for gap in (d, d + delta):
+        sc = single_scene(scenes.make_single(radius=r, pos=(0.0, 0.0, r + gap)), params=free_params(gravity=(0.0, 0.0, 0.0)))
+        o = oracle.OracleSim(sc)
+        st = scenes.rest_state(sc.robot, 1)
+        st[0, 0, 9] = v0
+        o.set_state(st)
+        o.step(None, h, 1, 4)
+        out.append(o.get_state()[0, 0, 9])
+    assert out[0] == pytest.approx(-d / h, rel=1e-12)
+    assert out[1] - out[0] == pytest.approx(-delta / h, rel=1e-6)
+
+
+def _single_precision_twin(tmp_path):
+    """The oracle with every `double` turned into `float` (sources rewritten by text substitution
+    and compiled into a scratch directory): what a straightforward fp32 implementation of exactly
+    the oracle's formulas computes."""
+    import importlib.util
+    import os
+    import re
+    import sys
+    src = os.path.dirname(oracle.__file__)
+    dst = tmp_path / "oracle_f32"
+    dst.mkdir()
+    for f in ("oracle.c", "oracle.h", "__init__.py"):
+        t = open(os.path.join(src, f)).read()
+        t = re.sub(r"\bdouble\b", "float", t).replace("c_double", "c_float").replace("np.float64", "np.float32")
+        (dst / f).write_text(t)
+    spec = importlib.util.spec_from_file_location("oracle_f32", str(dst / "__init__.py"))
+    mod = importlib.util.module_from_spec(spec)
+    sys.modules["oracle_f32"] = mod
+    spec.loader.exec_module(mod)
+    mod.build(force=True)
+    return mod
+
+
+def test_plain_single_precision_twin_of_the_oracle_leaves_1e_3_on_fallen_humanoids(tmp_path):
+    """How close can single precision stay to the oracle on the 8 x 32 fallen-humanoid workload?
+    A twin of the oracle that computes everything in fp32 drifts beyond 1e-3 in ten steps in some
+    envs whose contact sets never differ from the oracle's: the bar the HIP path is held to there
+    (tests/helpers.py, gate_after_10_steps) cannot be 'every env within 1e-3' for any fp32 code
+    that is not more careful than the formulas as written.  Its median stays near 1e-4."""
+    f32 = _single_precision_twin(tmp_path)
+    N, k, warm = 203, 4, 30
+    sc, cfg = scenes.config_scene(k, num_envs=N)
+    a, b = oracle.OracleSim(sc, threads=8), f32.OracleSim(sc, threads=8)
+    a.set_state(scenes.fallen_states(sc, cfg["seed"]))
+    sub, its = cfg["substeps"], cfg["iterations"]
+    for s in range(warm):
+        a.step(scenes.actions_for_step(cfg["seed"], s, N, sc.robot.n_dofs), cfg["dt"], sub, its)
+    s0 = a.get_state().astype(np.float32)
+    a.set_state(s0.astype(np.float64)); b.set_state(s0)
+    h = float(np.float32(cfg["dt"])) / sub
+    forked = np.zeros(N, bool)
+    for s in range(10):
+        act = scenes.actions_for_step(cfg["seed"], warm + s, N, sc.robot.n_dofs)
+        for _ in range(sub):
+            a.step(act, h, 1, its); b.step(act.astype(np.float32), h, 1, its)
+            ca, cb = a.get_contacts(), b.get_contacts()
+            forked |= np.any([(ca[f] != cb[f]).any(1) for f in ("active", "kind", "feat")], axis=0)
+    e10 = _rel_err(b.get_state().astype(np.float64), a.get_state())
+    same = ~forked
+    print(f"fp32 twin, config 4: median {np.median(e10):.2e}; {same.sum()} envs with identical contact sets, "
+          f"max {e10[same].max():.2e}, {int((e10[same] > 1e-3).sum())} beyond 1e-3")
+    assert same.sum() > 50
+    assert e10[same].max() > 1e-3
+    assert np.median(e10) < 5e-4
