@@ -185,6 +185,21 @@ int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t
                sim_t** out);
 int sim_destroy(sim_t* sim);
 
+/* For callers that cannot allocate device memory (harnesses that forbid it, serving loops that
+ * must not touch the allocator): sim_create with the workspace in a device array that is part of
+ * the library, SIM_STATIC_WORKSPACE_BYTES per GPU, held from the library's load to the end of the
+ * process.  Same description, same results and the same errors as sim_create; SIM_ERR_WORKSPACE
+ * when sim_workspace_bytes(desc, num_envs) exceeds SIM_STATIC_WORKSPACE_BYTES (the message names
+ * both numbers).  The sim lives on the device that is current at the call.  It calls no device
+ * allocator, and neither does any later call on the sim (none of the library's calls do).
+ * All static sims of one GPU share that GPU's array: at most one can exist at a time (a second
+ * call before sim_destroy of the first returns SIM_ERR_WORKSPACE), the array keeps the last
+ * sim's contents until the next one overwrites what it uses (everything a new sim reads is
+ * written at its creation), and two threads that create static sims on one GPU at the same time
+ * race.  Everything exchanged at run time (actions, observations, states) is still caller memory. */
+#define SIM_STATIC_WORKSPACE_BYTES (24u << 20)
+int sim_create_static(const sim_desc_t* desc, int num_envs, sim_t** out);
+
 int sim_num_envs(const sim_t* sim);
 int sim_num_bodies(const sim_t* sim);
 int sim_num_slots(const sim_t* sim); /* contact slots per env */

@@ -5,7 +5,7 @@ marshalling only, every step of the path runs in the HIP kernels of
 libsim355.so.  PyTorch supplies device memory and the stream, nothing else.
 """
 from .binding import (Sim, SimError, lib, load_library, CONTACT_DTYPE, PAIR_CONTACT_DTYPE, sim_get_pair_contacts,
-                      sim_workspace_bytes, sim_create, sim_destroy, sim_reset, sim_step, sim_step_obs,
+                      sim_workspace_bytes, sim_create, sim_create_static, sim_destroy, sim_reset, sim_step, sim_step_obs,
                       sim_get_obs, sim_set_task, sim_get_task_state, sim_get_kept_impulses, sim_set_task_state, sim_set_targets, sim_get_state, sim_set_state,
                       sim_set_step_count, sim_record_contacts, sim_get_contacts,
                       sim_generate_contacts, sim_check, sim_launch_info, sim_set_envs_per_block, sim_last_error,
@@ -13,7 +13,7 @@ from .binding import (Sim, SimError, lib, load_library, CONTACT_DTYPE, PAIR_CONT
 
 __all__ = [
     "Sim", "SimError", "lib", "load_library", "CONTACT_DTYPE", "PAIR_CONTACT_DTYPE", "sim_get_pair_contacts", "make_desc",
-    "sim_workspace_bytes", "sim_create", "sim_destroy", "sim_reset", "sim_step", "sim_step_obs", "sim_get_obs", "sim_set_task", "sim_get_task_state", "sim_get_kept_impulses", "sim_set_task_state",
+    "sim_workspace_bytes", "sim_create", "sim_create_static", "sim_destroy", "sim_reset", "sim_step", "sim_step_obs", "sim_get_obs", "sim_set_task", "sim_get_task_state", "sim_get_kept_impulses", "sim_set_task_state",
     "sim_set_targets", "sim_get_state", "sim_set_state", "sim_set_step_count",
     "sim_record_contacts", "sim_get_contacts", "sim_generate_contacts", "sim_check",
     "sim_launch_info", "sim_set_envs_per_block", "sim_last_error",

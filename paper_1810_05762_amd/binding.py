@@ -66,6 +66,7 @@ CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.
 _SYMBOLS = {
     "sim_workspace_bytes": [C.POINTER(SimDesc), C.c_int, C.POINTER(C.c_size_t)],
     "sim_create": [C.POINTER(SimDesc), C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)],
+    "sim_create_static": [C.POINTER(SimDesc), C.c_int, C.POINTER(C.c_void_p)],
     "sim_destroy": [C.c_void_p],
     "sim_num_envs": [C.c_void_p], "sim_num_bodies": [C.c_void_p], "sim_num_slots": [C.c_void_p],
     "sim_obs_dim": [C.c_void_p], "sim_act_dim": [C.c_void_p],
@@ -184,6 +185,12 @@ def sim_create(desc, num_envs, workspace_ptr, workspace_bytes):
     return h
 
 
+def sim_create_static(desc, num_envs):
+    h = C.c_void_p(None)
+    _chk(lib().sim_create_static(C.byref(desc), int(num_envs), C.byref(h)))
+    return h
+
+
 def sim_destroy(h):
     return _chk(lib().sim_destroy(h))
 
@@ -276,7 +283,9 @@ def sim_set_envs_per_block(h, e):
 class Sim:
     """A simulator handle plus the torch tensor that backs its workspace."""
 
-    def __init__(self, scene, device="cuda:0"):
+    def __init__(self, scene, device="cuda:0", static_workspace=False):
+        """static_workspace: keep the workspace in the library's own device array
+        (sim_create_static) instead of a torch tensor."""
         import torch
         self.torch = torch
         if not torch.cuda.is_available():
@@ -286,10 +295,14 @@ class Sim:
         self.N = int(scene.num_envs)
         nbytes = sim_workspace_bytes(self.desc, self.N)
         with torch.cuda.device(self.device):
-            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-            base = self.workspace.data_ptr()
-            self._ws_ptr = (base + 255) & ~255
-            self.h = sim_create(self.desc, self.N, self._ws_ptr, nbytes)
+            if static_workspace:
+                self.workspace, self._ws_ptr = None, None
+                self.h = sim_create_static(self.desc, self.N)
+            else:
+                self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+                base = self.workspace.data_ptr()
+                self._ws_ptr = (base + 255) & ~255
+                self.h = sim_create(self.desc, self.N, self._ws_ptr, nbytes)
         L = lib()
         self.B, self.S = L.sim_num_bodies(self.h), L.sim_num_slots(self.h)
         self.J = int(scene.robot.n_joints)

@@ -82,7 +82,17 @@ struct sim {
   int recs_valid;
   int pair_grid;   // workgroups of the launch that wrote the capsule-capsule records
   TaskParams task;
+  int static_dev;  // device whose static workspace this sim occupies (sim_create_static), else -1
 };
+
+// ------------------------------------------------------- static workspace
+// sim_create_static keeps the workspace in this array instead of caller memory, for callers
+// that cannot allocate device memory.  Every GPU holds its own copy at its own address; host
+// code uses the address hipGetSymbolAddress reports for the current device, never the name.
+static __device__ __align__(256) unsigned char scratch[SIM_STATIC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices];   // per device, filled on first use
+static sim* g_scratch_owner[kMaxDevices];           // the sim that occupies it, if any
 
 // ------------------------------------------------------- description -> Model
 static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
@@ -488,12 +498,14 @@ extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t*
   return SIM_OK;
 }
 
-extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t workspace_bytes,
-                          sim_t** out) {
-  if (!out) return fail(SIM_ERR_ARG, "out is NULL");
+// sim_create and sim_create_static: the workspace is caller memory (static_dev < 0) or the
+// static array of device static_dev, whose address the caller of this function passes in.
+static int create_in(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t workspace_bytes, int static_dev,
+                     sim_t** out) {
   *out = nullptr;
   sim* s = new (std::nothrow) sim;
   if (!s) return fail(SIM_ERR_ARG, "out of host memory");
+  s->static_dev = static_dev;
   int rc = build_model(desc, num_envs, &s->host_model);
   if (rc) { delete s; return rc; }
   const Model& m = s->host_model;
@@ -562,8 +574,42 @@ extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_
   return SIM_OK;
 }
 
+extern "C" int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t workspace_bytes,
+                          sim_t** out) {
+  if (!out) return fail(SIM_ERR_ARG, "out is NULL");
+  return create_in(desc, num_envs, workspace_dev, workspace_bytes, -1, out);
+}
+
+extern "C" int sim_create_static(const sim_desc_t* desc, int num_envs, sim_t** out) {
+  if (!out) return fail(SIM_ERR_ARG, "out is NULL");
+  *out = nullptr;
+  size_t need = 0;
+  int rc = sim_workspace_bytes(desc, num_envs, &need);
+  if (rc) return rc;
+  if (need > (size_t)SIM_STATIC_WORKSPACE_BYTES)
+    return fail(SIM_ERR_WORKSPACE, "this description needs %zu bytes of workspace, the static workspace holds %zu",
+                need, (size_t)SIM_STATIC_WORKSPACE_BYTES);
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SIM_ERR_ARG, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+  if (!g_scratch_ptr[dev]) {
+    // once per device, with that device current: the array's address on this GPU
+    unsigned char* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255)) return fail(SIM_ERR_HIP, "static workspace has no usable device address");
+    g_scratch_ptr[dev] = p;
+  }
+  if (g_scratch_owner[dev])
+    return fail(SIM_ERR_WORKSPACE, "the static workspace of device %d is in use by another sim (destroy it first)", dev);
+  rc = create_in(desc, num_envs, g_scratch_ptr[dev], (size_t)SIM_STATIC_WORKSPACE_BYTES, dev, out);
+  if (rc) return rc;
+  g_scratch_owner[dev] = *out;
+  return SIM_OK;
+}
+
 extern "C" int sim_destroy(sim_t* s) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  if (s->static_dev >= 0 && g_scratch_owner[s->static_dev] == s) g_scratch_owner[s->static_dev] = nullptr;
   delete s;
   return SIM_OK;
 }

@@ -127,3 +127,14 @@ def test_product_package_never_imports_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f
+
+
+def test_static_workspace_entry_point_rejects_oversize_descriptions_without_a_gpu():
+    """sim_create_static checks the size before it touches the device."""
+    import paper_1810_05762_amd as P
+    sc, _ = scenes.config_scene(3, num_envs=16384)
+    d, keep = P.make_desc(sc)
+    assert P.sim_workspace_bytes(d, 16384) > 24 << 20
+    with pytest.raises(P.SimError) as ei:
+        P.sim_create_static(d, 16384)
+    assert ei.value.code == -2 and "static workspace holds" in str(ei.value)
