@@ -54,7 +54,7 @@ def rel_err4(g, o):
     return np.stack(out, 1)
 
 
-def gate_after_10_steps(e10q, forked, many_impacts=False, label=""):
+def gate_after_10_steps(e10q, forked, many_impacts=False, label="", sets_seen_every_substep=True):
     """The 10-step state gate, split by whether the two sides ever disagreed on a contact set.
 
     e10q [N][4] from rel_err4; forked [N] bool: in some substep the HIP path and the oracle
@@ -67,6 +67,9 @@ def gate_after_10_steps(e10q, forked, many_impacts=False, label=""):
            velocity difference delta / h (its bias is gap / h), so a body that hits the ground in
            the last substeps shows 480 times its position error in its velocity
            (tests/test_oracle_sensitivity.py shows the oracle doing this against copies of itself).
+           Without sets_seen_every_substep (whole env-steps in one launch: only the sets of each
+           step's last substep can be compared, so some forks go unseen) one env in a hundred may
+           lie between 1e-3 and 5e-3.
       (ii) envs that forked follow another branch of a discontinuous map: reported, and bounded
            coarsely (nine in ten within 1e-3, all within 1e-2), the spread the oracle shows
            against its own fp32-stored copy in test_oracle_sensitivity.py.
@@ -84,6 +87,9 @@ def gate_after_10_steps(e10q, forked, many_impacts=False, label=""):
     if many_impacts:
         ev = e10q[same, 2:].max(1)
         assert (ev <= TOL_10).mean() >= 0.97 and ev.max() <= 5e-3, line
+    elif not sets_seen_every_substep:
+        ev = e10q[same, 2:].max(1)
+        assert (ev <= TOL_10).mean() >= 0.99 and ev.max() <= 5e-3, line
     else:
         assert e10q[same, 2:].max() <= TOL_10, line
     if forked.any():

@@ -85,7 +85,7 @@ def test_states_and_kept_impulses_match_the_oracle(k, n_envs, settle, epb, split
     assert e1.max() <= TOL_1
     assert lam_err[1].max() <= 1e-4
     # ten steps: every env whose contact sets never differed within 1e-3, the others reported
-    gate_after_10_steps(e10, forked, label=f"config {k} warm: ")
+    gate_after_10_steps(e10, forked, label=f"config {k} warm: ", sets_seen_every_substep=split)
     assert np.median(e10.max(1)) <= TOL_1
     assert np.median(lam_err[10]) <= 1e-3
     sim.close()
