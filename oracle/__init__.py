@@ -85,6 +85,7 @@ def _load():
     L.oracle_set_warm_start.argtypes = [vp, C.c_double]
     L.oracle_get_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm.argtypes = [vp, dp, dp]
+    L.oracle_set_warm_flags.argtypes = [vp, ip, ip]
     L.oracle_reset.argtypes = [vp, C.c_void_p, C.c_uint64]
     L.oracle_set_state.argtypes = [vp, dp]
     L.oracle_get_state.argtypes = [vp, dp]
@@ -208,6 +209,13 @@ class OracleSim:
         lj = np.ascontiguousarray(lam_j, np.float64).reshape(self.N, self.J, 6)
         ls = np.ascontiguousarray(lam_s, np.float64).reshape(self.N, self.S, 3)
         self._L.oracle_set_warm(self._h, _dp(lj), _dp(ls))
+
+    def set_warm_flags(self, limit_side, slot_was_active):
+        """Bookkeeping of the kept impulses: which limit a hinge row's stood for ([N][J][3]: 0 lower,
+        1 upper, -1 whichever is nearer now) and whether a slot was active in the previous substep."""
+        sd = np.ascontiguousarray(limit_side, np.int32).reshape(self.N, self.J, 3)
+        on = np.ascontiguousarray(slot_was_active, np.int32).reshape(self.N, self.S)
+        self._L.oracle_set_warm_flags(self._h, _ip(sd), _ip(on))
 
     def get_warm(self):
         """Impulses kept for the next substep: joints [N][J][6], terrain slots [N][S][3]."""

@@ -1328,6 +1328,15 @@ void oracle_set_warm(oracle_sim* o, const double* lam_j, const double* lam_s) {
     }
   }
 }
+void oracle_set_warm_flags(oracle_sim* o, const int32_t* limit_side, const int32_t* slot_was_active) {
+  const int J = o->m.J, S = o->m.S;
+  for (int e = 0; e < o->N; ++e) {
+    env_state* E = &o->env[e];
+    for (int j = 0; j < J; ++j)
+      for (int k = 0; k < 3; ++k) E->side_j[j][k] = limit_side[((size_t)e * J + j) * 3 + k];
+    for (int q = 0; q < S; ++q) E->lam_s_on[q] = slot_was_active[(size_t)e * S + q] ? 1 : 0;
+  }
+}
 void oracle_get_warm(const oracle_sim* o, double* lam_j, double* lam_s) {
   const int J = o->m.J, S = o->m.S;
   for (int e = 0; e < o->N; ++e) {

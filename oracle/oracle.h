@@ -9,6 +9,13 @@
  * reward of Eq. (1)-(3).  It shares no code with the HIP library and must only
  * be used by tests, the smoke check and the benchmark's CPU-baseline leg.
  *
+ * Every function of it is pinned by a closed form, an invariant, a brute-force
+ * search or a value the paper prints (tests/test_oracle_*.py).  Parity unpinned:
+ * the two odd multipliers that spread (env, index) over the generator's seeds
+ * (any pair of odd constants would do; only the generator itself is pinned, to
+ * its published outputs), and anything about gait quality or learning curves,
+ * for which the paper gives no number.
+ *
  * All arrays are host memory.  State interchange: state[N][B][13] =
  * position(3), quaternion(w,x,y,z), linear velocity(3), angular velocity(3),
  * positions env-local, velocities world-frame.
@@ -135,6 +142,10 @@ void oracle_get_warm(const oracle_sim*, double* lam_j, double* lam_s);
 /* Overwrites what is kept (tests inject known impulses); a limit row's value then stands for
  * whichever limit is the nearer one in the next substep. */
 void oracle_set_warm(oracle_sim*, const double* lam_j, const double* lam_s);
+/* What the kept impulses stood for (after oracle_set_warm): limit_side [N][J][3], 0 = the lower
+ * limit, 1 = the upper limit, -1 = whichever limit is nearer now; slot_was_active [N][S], 0 = the
+ * slot was not active in the previous substep.  Sets bookkeeping only, no arithmetic. */
+void oracle_set_warm_flags(oracle_sim*, const int32_t* limit_side, const int32_t* slot_was_active);
 void oracle_set_targets(oracle_sim*, const double* target_xy /*[N][2] env-local*/);
 void oracle_set_step_count(oracle_sim*, const int32_t* counts /*[N]*/);
 /* Switches the task logic on (or off with NULL / enabled 0) and initialises the per-env task
