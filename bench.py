@@ -5,8 +5,15 @@ block projected-Jacobi sweeps, position integration, obs/reward/done packing, wi
 obs/reward/done delivered into caller tensors), on the 4096-humanoid heightfield
 workload (configuration 3).  Inputs are seeded and synthetic and already
 resident in HBM when the timed region starts.  Prints one JSON line.
+
+The timed region (`--steps` env-steps between two synchronisations, with a pair of events on the
+launch stream around it) is run `--repeats` times; the line reports the median repeat.
+`--copy-probe` runs a plain device copy of known size instead (the calibration run of the HBM
+traffic counters); `--print-csrc-hash` prints the hash that ties profiles/step_kernel_counters.json
+to the kernel sources.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -47,6 +54,48 @@ def bytes_per_env_step(B, J, S, D, obs_dim, substeps, iterations, active):
     return a, b, c
 
 
+def csrc_hash():
+    """sha256 over the kernel sources: the counter figures under profiles/ are only quoted for the
+    sources they were measured on."""
+    d = os.path.join(ROOT, "paper_1810_05762_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def measured_counters(workload):
+    """HBM bytes and vector instructions per launch of the step kernel from the tracked rocprofv3
+    summary, or None when it was measured on other kernel sources or another workload."""
+    path = os.path.join(ROOT, "profiles", "step_kernel_counters.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    if rec.get("csrc_sha256") != csrc_hash() or rec.get("workload") != workload:
+        return None
+    return rec
+
+
+def copy_probe():
+    """A plain device-to-device copy of 256 MiB, five times: under `rocprofv3 --pmc FETCH_SIZE` (or
+    WRITE_SIZE) counter / size is the factor by which that counter over- or under-reports."""
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py --copy-probe needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    n = 256 * 1024 * 1024 // 4
+    src = torch.arange(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:1000], src[:1000])
+    print(json.dumps({"copy_probe_MiB": 256, "copies": 5}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,7 +112,16 @@ def main():
     ap.add_argument("--warm-start", type=float, default=0.0, help="share of the last substep's impulses the rows start from (0 = off)")
     ap.add_argument("--iterations", type=int, default=0, help="override the sweeps per substep (the workload is then named for it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=3, help="repeats of the timed region; the median is reported")
+    ap.add_argument("--copy-probe", action="store_true", help="run the 256 MiB copy that calibrates the traffic counters, then exit")
+    ap.add_argument("--print-csrc-hash", action="store_true")
     args = ap.parse_args()
+    if args.print_csrc_hash:
+        print(csrc_hash())
+        return
+    if args.copy_probe:
+        copy_probe()
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (envs would be sharded across GPUs with no "
               "exchange inside a step); run with --gpus 1", file=sys.stderr)
@@ -109,7 +167,14 @@ def main():
     done = torch.empty(N, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
 
-    def one_step(k):
+    # configuration 4: a seeded per-env target direction that changes every 200 steps
+    retarget = None
+    if cfg.get("fallen") and task is None:
+        retarget = [torch.as_tensor(scenes.targets_for_step(cfg["seed"], 200 * e, N)).to(dev) for e in range(8)]
+
+    def one_step(k, may_retarget=True):
+        if retarget is not None and may_retarget and k % 200 == 0:
+            P.sim_set_targets(sim.h, retarget[(k // 200) % 8].data_ptr(), stream)
         # sim_step + sim_get_obs in their one-launch form: the step kernel writes obs, reward and
         # done straight into the caller's tensors
         P.sim_step_obs(sim.h, ring[k % 16].data_ptr(), dt, sub, its, obs.data_ptr(), rew.data_ptr(), done.data_ptr(),
@@ -118,12 +183,24 @@ def main():
     settle = 60          # robots are dropped from their reset height; let them land first (untimed)
     for k in range(settle + args.warmup):
         one_step(k)
-    torch.cuda.synchronize(dev)
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        one_step(settle + args.warmup + k)
-    torch.cuda.synchronize(dev)
-    elapsed = time.perf_counter() - t0
+    # the timed region, `repeats` times: K steps between two synchronisations (host clock) with a
+    # pair of events on the launch stream around them; the median repeat is reported
+    host_s, event_ms = [], []
+    k0 = settle + args.warmup
+    for r in range(max(1, args.repeats)):
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(dev)
+        t0 = time.perf_counter()
+        ev0.record()
+        for k in range(args.steps):
+            one_step(k0 + k)
+        ev1.record()
+        torch.cuda.synchronize(dev)
+        host_s.append(time.perf_counter() - t0)
+        event_ms.append(ev0.elapsed_time(ev1))
+        k0 += args.steps
+    mid = int(np.argsort(host_s)[len(host_s) // 2])
+    elapsed = host_s[mid]
     sim.check()
 
     # dominant kernel: the fused step kernel, timed per launch with events on its stream
@@ -131,7 +208,7 @@ def main():
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
     for k, (e0, e1) in enumerate(evs):
         e0.record()
-        one_step(k)
+        one_step(k, may_retarget=False)      # (the kernel alone between the two events)
         e1.record()
     torch.cuda.synchronize(dev)
     kern_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
@@ -142,14 +219,16 @@ def main():
     fl = flops_per_env_step(rob.n_bodies, rob.n_joints, sim.S, sub, its, active, blocks_per_body)
     bA, bB, bC = bytes_per_env_step(rob.n_bodies, rob.n_joints, sim.S, rob.n_dofs, sim.obs_dim, sub, its, active)
     achieved_tflops = fl * N / (kern_ms * 1e-3) / 1e12
-    # HBM bytes per launch of the step kernel at the headline size, from rocprofv3 FETCH_SIZE and
-    # WRITE_SIZE scaled by what the same counters read for a 256 MiB copy (0.5 and 1.0): 8.6 MB
-    # read + 6.9 MB written (summary under profiles/); other sizes were not measured
-    # vector instructions per launch at the headline size (rocprofv3 SQ_INSTS_VALU, same summary):
-    # times 64 lanes, over the kernel time, against what 256 CUs x 4 SIMDs x 16 lanes issue per
-    # clock at 2.4 GHz without packed instructions
-    valu_insts = 43.6e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task and not args.warm_start and not args.iterations) else None
-    traffic = 15.5e6 if (args.config == 3 and N == 4096 and not args.height_map and not collide and not args.task and not args.warm_start and not args.iterations) else None
+    workload = ((cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")
+                + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else "")
+                + ("_task" if args.task else "") + (f"_warm{args.warm_start:g}" if args.warm_start > 0 else "")
+                + (f"_its{args.iterations}" if args.iterations > 0 else "")
+                + (f"_epb{args.envs_per_block}" if args.envs_per_block else ""))
+    # HBM bytes and vector instructions per launch come from the tracked rocprofv3 summary and are
+    # quoted only for the kernel sources and the workload they were measured on (null otherwise)
+    ctr = measured_counters(workload)
+    valu_insts = ctr["valu_insts_per_launch"] if ctr else None
+    traffic = (ctr["fetch_bytes_per_launch"] + ctr["write_bytes_per_launch"]) if ctr else None
     pair_info = {}
     if collide:
         sim.record_contacts(True)
@@ -167,11 +246,10 @@ def main():
         "metric": "env-steps/sec on 1 MI355X (4096 humanoids, heightfield); HBM roofline fraction",
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "repeats": {"n": len(host_s), "reported": "median", "host_ms_per_step": [t / args.steps * 1e3 for t in host_s],
+                    "event_ms_per_step": [t / args.steps for t in event_ms]},
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": (cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")
-                               + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else "")
-                               + ("_task" if args.task else "") + (f"_warm{args.warm_start:g}" if args.warm_start > 0 else "")
-                               + (f"_its{args.iterations}" if args.iterations > 0 else ""),
+        "config": {"workload": workload,
                    "num_envs": N, "obs_dim": sim.obs_dim, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
@@ -182,14 +260,21 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved_tflops / peak_tflops, "traffic": traffic,
                      "flops_per_env_step": fl, "kernel_ms": kern_ms,
                      "valu_issue_frac": (valu_insts * 64 / (kern_ms * 1e-3) / (256 * 4 * 16 * 2.4e9)) if valu_insts else None},
-        "hbm_roofline": {
+        # HBM is not what bounds this kernel (body state stays in LDS through all substeps and
+        # sweeps); the byte accountings are printed for the record.  A and B are bytes the kernel has
+        # to move, as fractions of 8 TB/s; C is what an engine with one kernel per sweep would stream
+        # (velocities and rows through HBM every sweep): a hypothetical, not traffic of this kernel
+        # and not a roofline fraction of it.
+        "hbm_accountings": {
             "peak_GBps": 8000.0, "kernel_ms": kern_ms,
+            "measured_GBps": (traffic / (kern_ms * 1e-3) / 1e9) if traffic else None,
+            "measured_frac_of_peak": (traffic / (kern_ms * 1e-3) / 8e12) if traffic else None,
             "A_compulsory": {"bytes_per_env_step": bA, "GBps": bA * N / (kern_ms * 1e-3) / 1e9,
-                             "frac": bA * N / (kern_ms * 1e-3) / 8e12},
+                             "frac_of_peak": bA * N / (kern_ms * 1e-3) / 8e12},
             "B_per_substep": {"bytes_per_env_step": bB, "GBps": bB * N / (kern_ms * 1e-3) / 1e9,
-                              "frac": bB * N / (kern_ms * 1e-3) / 8e12},
-            "C_streaming_jacobi": {"bytes_per_env_step": bC, "GBps": bC * N / (kern_ms * 1e-3) / 1e9,
-                                   "frac": bC * N / (kern_ms * 1e-3) / 8e12},
+                              "frac_of_peak": bB * N / (kern_ms * 1e-3) / 8e12},
+            "C_unfused_engine_hypothetical": {"bytes_per_env_step": bC,
+                                              "equivalent_GBps": bC * N / (kern_ms * 1e-3) / 1e9},
         },
     }
 

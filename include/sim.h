@@ -220,9 +220,11 @@ int sim_step(sim_t* sim, const float* actions_dev, float dt, int substeps, int i
              void* stream);
 
 /* sim_step followed by sim_get_obs in one kernel launch: the step's observation, reward and
- * done flag (Table 2 "Ours", Eq. 1-3, Section 4.1) are also written to the caller's arrays as
- * they are packed.  Same arguments, limits and errors as the two calls; any of the three
- * output pointers may be NULL.  Like sim_step it is one kernel launch on `stream`, allocates
+ * done flag (Table 2 "Ours", Eq. 1-3, Section 4.1) are written to the caller's arrays as they
+ * are packed, instead of the library's own copies (each output is stored once: an output whose
+ * pointer is NULL goes to the library's copy as in sim_step, and sim_get_obs refuses with
+ * SIM_ERR_ARG to return an output that the last step handed to the caller).  Same arguments,
+ * limits and errors as the two calls; any of the three output pointers may be NULL.  Like sim_step it is one kernel launch on `stream`, allocates
  * nothing and does not synchronise, so it can be captured in a HIP graph and replayed (the
  * graph then steps with whatever the actions array holds at replay time). */
 int sim_step_obs(sim_t* sim, const float* actions_dev, float dt, int substeps, int iterations,

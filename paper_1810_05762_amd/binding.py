@@ -311,6 +311,7 @@ class Sim:
         self.obs = torch.zeros(self.N, self.obs_dim, **f32)
         self.reward = torch.zeros(self.N, **f32)
         self.done = torch.zeros(self.N, dtype=torch.uint8, device=self.device)
+        self._delivered = False
 
     def close(self):
         if getattr(self, "h", None):
@@ -337,12 +338,14 @@ class Sim:
     def reset(self, seed=0, mask=None):
         m = None if mask is None else self._dev(mask, self.torch.uint8)
         sim_reset(self.h, None if m is None else m.data_ptr(), seed, self._stream())
+        self._delivered = False
 
     def step(self, actions, dt, substeps, iterations):
         a = None if actions is None else self._dev(actions, self.torch.float32)
         if a is not None and tuple(a.shape) != (self.N, self.act_dim):
             raise ValueError(f"actions must be [{self.N}][{self.act_dim}]")
         sim_step(self.h, None if a is None else a.data_ptr(), dt, substeps, iterations, self._stream())
+        self._delivered = False
 
     def step_obs(self, actions, dt, substeps, iterations):
         a = None if actions is None else self._dev(actions, self.torch.float32)
@@ -350,6 +353,7 @@ class Sim:
             raise ValueError(f"actions must be [{self.N}][{self.act_dim}]")
         sim_step_obs(self.h, None if a is None else a.data_ptr(), dt, substeps, iterations, self.obs.data_ptr(),
                      self.reward.data_ptr(), self.done.data_ptr(), self._stream())
+        self._delivered = True     # the step wrote into self.obs / reward / done; the library kept no copy
         return self.obs, self.reward, self.done
 
     def set_task(self, task):
@@ -377,6 +381,8 @@ class Sim:
         sim_set_task_state(self.h, c.data_ptr(), tg.data_ptr(), self._stream())
 
     def get_obs(self):
+        if self._delivered:
+            return self.obs, self.reward, self.done
         sim_get_obs(self.h, self.obs.data_ptr(), self.reward.data_ptr(), self.done.data_ptr(), self._stream())
         return self.obs, self.reward, self.done
 
@@ -396,6 +402,7 @@ class Sim:
         if s.numel() != self.N * self.B * 13:
             raise ValueError("state must be [N][B][13]")
         sim_set_state(self.h, s.data_ptr(), self._stream())
+        self._delivered = False
 
     def set_step_count(self, counts):
         c = self._dev(np.broadcast_to(np.asarray(counts, np.int32), (self.N,)), self.torch.int32)

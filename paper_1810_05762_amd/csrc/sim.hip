@@ -83,6 +83,7 @@ struct sim {
   int pair_grid;   // workgroups of the launch that wrote the capsule-capsule records
   TaskParams task;
   int static_dev;  // device whose static workspace this sim occupies (sim_create_static), else -1
+  int ws_has[3];   // the workspace holds obs / reward / done of the last step (else the caller got them)
 };
 
 // ------------------------------------------------------- static workspace
@@ -482,6 +483,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   HIP_TRY(hipGetLastError());
   if (a.recs) s->recs_valid = 1;
   if (a.pair_recs) s->pair_grid = grid;
+  s->ws_has[0] = obs_out == nullptr; s->ws_has[1] = reward_out == nullptr; s->ws_has[2] = done_out == nullptr;
   return SIM_OK;
 }
 
@@ -753,6 +755,8 @@ extern "C" int sim_step_obs(sim_t* s, const float* actions_dev, float dt, int su
 
 extern "C" int sim_get_obs(sim_t* s, float* obs_dev, float* reward_dev, uint8_t* done_dev, void* stream) {
   if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  if ((obs_dev && !s->ws_has[0]) || (reward_dev && !s->ws_has[1]) || (done_dev && !s->ws_has[2]))
+    return fail(SIM_ERR_ARG, "the last sim_step_obs delivered this output to the caller's own array; the library kept no copy");
   int n_obs = s->N * s->obs_dim;
   hipLaunchKernelGGL(copy_out_kernel, dim3(blocks_for(n_obs)), dim3(256), 0, static_cast<hipStream_t>(stream),
                      reinterpret_cast<const float*>(s->ws + s->lay.obs),

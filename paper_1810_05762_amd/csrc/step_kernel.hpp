@@ -64,7 +64,7 @@ struct StepArgs {
   int32_t* recs;         // [N][S][12] or null
   int N, E, substeps, iterations, count_step;
   float h;
-  float* obs_out;        // optional caller copies of obs / reward / done (sim_step_obs), else null
+  float* obs_out;        // caller arrays for obs / reward / done (sim_step_obs) that replace the library's, or null
   float* reward_out;
   uint8_t* done_out;
   TaskParams task;       // task logic (enabled = 0: off)
@@ -1895,10 +1895,9 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       reset_now = dn && a.task.auto_reset;
     }
     if (!only_obs) {
-      a.reward[env_e] = rew;
-      a.done[env_e] = dn;
-      if (a.reward_out) a.reward_out[env_e] = rew;
-      if (a.done_out) a.done_out[env_e] = dn;
+      // (one copy each: the caller's array when there is one, else the library's)
+      (a.reward_out ? a.reward_out : a.reward)[env_e] = rew;
+      (a.done_out ? a.done_out : a.done)[env_e] = dn;
     }
     if (reset_now) {
       // next episode: the reset recipe with that episode's seed, built in this env's column of
@@ -1946,11 +1945,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   {
     const int env0 = blockIdx.x * E;
     const int n_here = min(E, N - env0);
+    float* const obs_dst = a.obs_out ? a.obs_out : a.obs;   // one copy: the caller's array when there is one
     for (int i = tid; i < n_here * obs_dim; i += kThreads) {
       const float o = Lobs[i];
       const int ee = i / obs_dim, k = i - ee * obs_dim;
-      a.obs[(size_t)(env0 + ee) * obs_row + k] = o;
-      if (a.obs_out) a.obs_out[(size_t)(env0 + ee) * obs_row + k] = o;
+      obs_dst[(size_t)(env0 + ee) * obs_row + k] = o;
     }
     if (M.height_map) {
       // Height map (Section 4.1, complex-terrain task): terrain height under a 15 x 11 grid that
@@ -1981,8 +1980,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           const float fw = M.hm_fwd[hi], lt = M.hm_lat[hj], c = Lhm[3 * E + ee], sn = Lhm[4 * E + ee];
         const float wx = Lhm[0 * E + ee] + (c * fw - sn * lt), wy = Lhm[1 * E + ee] + (sn * fw + c * lt);
         const float hz = terrain_height(M, a.heights, wx, wy) - Lhm[2 * E + ee];
-        a.obs[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
-        if (a.obs_out) a.obs_out[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
+        obs_dst[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
       }
     }
   }
