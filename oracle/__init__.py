@@ -83,6 +83,7 @@ def _load():
     L.oracle_set_threads.argtypes = [vp, C.c_int32]
     L.oracle_get_threads.argtypes = [vp]
     L.oracle_set_warm_start.argtypes = [vp, C.c_double]
+    L.oracle_set_solver.argtypes = [vp, C.c_int32, C.c_int32, C.c_double]
     L.oracle_get_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm_flags.argtypes = [vp, ip, ip]
@@ -192,6 +193,8 @@ class OracleSim:
         self._trace = None
         L.oracle_set_threads(self._h, int(threads))
         L.oracle_set_warm_start(self._h, float(getattr(p, "warm_start", 0.0)))
+        L.oracle_set_solver(self._h, int(getattr(p, "solver", 0)), int(getattr(p, "krylov_iters", 8)),
+                            float(getattr(p, "newton_reg", 0.0)))
 
     def __del__(self):
         if getattr(self, "_h", None):
@@ -204,6 +207,11 @@ class OracleSim:
     def set_warm_start(self, share):
         """Rows start each substep from `share` (0..1) of their impulse at the end of the previous one."""
         self._L.oracle_set_warm_start(self._h, float(share))
+
+    def set_solver(self, kind, krylov_iters=8, reg=0.0):
+        """kind 0: block projected Jacobi; 1: non-smooth Newton with `krylov_iters` conjugate-residual
+        iterations per Newton iteration (the `iterations` of step() then count Newton iterations)."""
+        self._L.oracle_set_solver(self._h, int(kind), int(krylov_iters), float(reg))
 
     def set_warm(self, lam_j, lam_s):
         lj = np.ascontiguousarray(lam_j, np.float64).reshape(self.N, self.J, 6)

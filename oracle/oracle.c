@@ -31,6 +31,7 @@
 #define MAXG 16                       /* agents of one interaction group */
 #define MAXP (MAXB * (MAXB - 1) / 2)  /* body pairs of one agent that may collide */
 #define MAXPC 512                     /* capsule-capsule contacts of one group */
+#define FRICTION_EPS 1e-3             /* m/s: smoothing of the friction law in the Newton solver */
 
 typedef struct { double x, y, z; } v3;
 typedef struct { double w, x, y, z; } quat;
@@ -122,6 +123,12 @@ typedef struct {
   int NP, pair_a[MAXP], pair_b[MAXP], G;
   /* warm start: share of the previous substep's impulses the rows start from (0: none) */
   double warm;
+  /* solver of the rows: 0 = block projected Jacobi with mass splitting (`iterations` sweeps);
+   * 1 = non-smooth Newton with a conjugate-residual inner solve, the paper's own choice
+   * (Section 3.1): `iterations` Newton iterations of `krylov_iters` inner iterations each;
+   * newton_reg: relative compliance added to the diagonal of J M^-1 J^T */
+  int solver, krylov_iters;
+  double newton_reg;
 } model;
 
 typedef struct {
@@ -635,6 +642,160 @@ static int generate_pair_contacts(const model* m, env_state* envs, int e0, int G
   return n;
 }
 
+/* ------------------------------------------- non-smooth Newton / Krylov solve */
+
+/* (dv, dw)[body] = M^-1 J^T x: every body receives the plain sum of its rows' impulses in
+ * ascending row order, then its inverse mass and world inverse inertia */
+static void rows_to_bodies(const model* m, const row_t* rows, int nrows, const double* x, v3 (*R)[3], int NB,
+                           v3* dv, v3* dw) {
+  const int B = m->B;
+  for (int b = 0; b < NB; ++b) { dv[b] = V(0, 0, 0); dw[b] = V(0, 0, 0); }
+  for (int i = 0; i < nrows; ++i) {
+    const row_t* r = &rows[i];
+    if (r->a >= 0) { dv[r->a] = vadd(dv[r->a], vscale(r->jla, x[i])); dw[r->a] = vadd(dw[r->a], vscale(r->jaa, x[i])); }
+    dv[r->b] = vadd(dv[r->b], vscale(r->jlb, x[i])); dw[r->b] = vadd(dw[r->b], vscale(r->jab, x[i]));
+  }
+  for (int b = 0; b < NB; ++b) {
+    dv[b] = vscale(dv[b], 1.0 / m->mass[b % B]);
+    dw[b] = inv_inertia_apply(R[b], m->inertia[b % B], dw[b]);
+  }
+}
+
+/* y = (J M^-1 J^T + reg D) x on the rows with on[i] != 0 (x is zero elsewhere), 0 on the others */
+static void delassus_apply(const model* m, const row_t* rows, int nrows, const double* diag, const int* on,
+                           const double* x, v3 (*R)[3], int NB, v3* dv, v3* dw, double* y) {
+  rows_to_bodies(m, rows, nrows, x, R, NB, dv, dw);
+  for (int i = 0; i < nrows; ++i)
+    y[i] = (!on || on[i]) ? row_jv(&rows[i], dv, dw) + m->newton_reg * diag[i] * x[i] : 0.0;
+}
+
+/* The paper's solver (Section 3.1): a non-smooth Newton method on the complementarity form of
+ * the rows, each Newton iteration solved by a Krylov method with a fixed number of iterations.
+ * The paper gives no formulas; this reading:
+ *   unknowns lambda; velocities u = v* + M^-1 J^T lambda; row residual s = J u + bias.
+ *   bilateral rows:  s = 0.
+ *   one-sided rows:  phi = min(lambda, s / D) = 0 (minimum map, D = diagonal of J M^-1 J^T).
+ *   friction pair t of a contact with normal impulse lambda_n: the smooth isotropic Coulomb law
+ *       lambda_t = -mu lambda_n s_t / sqrt(|s_t|^2 + eps^2)   (Section 3.1: "smooth isotropic").
+ * A Newton iteration linearises with the branch every row is on: bilateral rows and one-sided
+ * rows with lambda - s/D > 0 ask for s = 0 after the update, one-sided rows on the other branch
+ * return to lambda = 0; a friction pair enters as a damper s_t + c lambda_t = 0 whose compliance
+ * c = |s_t|_eps / (mu lambda_n) is taken from the current iterate (a pair without normal impulse
+ * returns to zero), which keeps the linear system symmetric positive semi-definite.  It is solved
+ * from zero by `krylov_iters` iterations of the conjugate-residual method with diagonal
+ * preconditioning (matrix-free: J M^-1 J^T is applied through the bodies).  After the update
+ * one-sided impulses are clipped at zero and friction pairs onto the disc mu lambda_n, so an
+ * inexact inner solve never leaves the feasible set. */
+static void newton_solve(const model* m, row_t* rows, int nrows, v3 (*R)[3], int NB, v3* vel, v3* om, int outer,
+                         oracle_sweep_trace* trace, int* trace_n, int trace_cap, double pos_err_max) {
+  static _Thread_local double *lam = NULL, *diag, *sres, *known, *rhs, *x, *z, *p, *q, *az, *tmp, *comp, *pd;
+  static _Thread_local int* on;
+  static _Thread_local v3 dv[MAXG * MAXB], dw[MAXG * MAXB], u[MAXG * MAXB], uw[MAXG * MAXB];
+  const int cap = MAXG * MAXROWS + 3 * MAXPC;
+  if (!lam) {
+    lam = (double*)malloc(sizeof(double) * cap * 13);
+    diag = lam + cap; sres = diag + cap; known = sres + cap; rhs = known + cap; x = rhs + cap; z = x + cap;
+    p = z + cap; q = p + cap; az = q + cap; tmp = az + cap; comp = tmp + cap; pd = comp + cap;
+    on = (int*)malloc(sizeof(int) * cap);
+  }
+  const int B = m->B;
+  for (int i = 0; i < nrows; ++i) {
+    const row_t* r = &rows[i];
+    double k = 0;
+    if (r->a >= 0) k += vdot(r->jla, r->jla) / m->mass[r->a % B] + vdot(r->jaa, inv_inertia_apply(R[r->a], m->inertia[r->a % B], r->jaa));
+    k += vdot(r->jlb, r->jlb) / m->mass[r->b % B] + vdot(r->jab, inv_inertia_apply(R[r->b], m->inertia[r->b % B], r->jab));
+    diag[i] = k;
+    lam[i] = r->lambda;   /* 0, or the warm-start share of what was kept */
+  }
+  for (int it = 0; it <= outer; ++it) {
+    /* velocities of the current iterate, from scratch */
+    rows_to_bodies(m, rows, nrows, lam, R, NB, dv, dw);
+    for (int b = 0; b < NB; ++b) { u[b] = vadd(vel[b], dv[b]); uw[b] = vadd(om[b], dw[b]); }
+    if (it == outer) break;
+    double sq = 0, mx = 0, viol = 0; int nbil = 0;
+    for (int i = 0; i < nrows; ++i) {
+      sres[i] = row_jv(&rows[i], u, uw) + rows[i].bias;
+      if (rows[i].type == 0) { sq += sres[i] * sres[i]; nbil++; if (fabs(sres[i]) > mx) mx = fabs(sres[i]); }
+      if (rows[i].type == 1 && -sres[i] > viol) viol = -sres[i];
+    }
+    if (trace && *trace_n < trace_cap) {
+      oracle_sweep_trace* t = &trace[(*trace_n)++];
+      t->bilateral_rms = nbil ? sqrt(sq / nbil) : 0; t->bilateral_max = mx; t->onesided_viol = viol;
+      t->pos_err_max = pos_err_max; t->cone_excess = 0;
+      double sl = 0;
+      for (int r = 0; r < nrows; ++r) if (rows[r].slot >= 0 && rows[r].type == 1) sl += lam[r];
+      t->sum_lambda_n = sl;
+    }
+    /* branch of every row */
+    for (int i = 0; i < nrows; ++i) {
+      const row_t* r = &rows[i];
+      known[i] = 0; comp[i] = 0;
+      if (r->type == 0) on[i] = 1;
+      else if (r->type == 1) {
+        on[i] = diag[i] > 0 && (lam[i] - sres[i] / diag[i] > 0);
+        if (!on[i]) known[i] = -lam[i];
+      } else {
+        /* friction pair (i, i+1); its normal row is the one before the pair.  Smooth isotropic
+         * Coulomb law: lambda_t = -mu lambda_n s_t / |s_t|_eps, i.e. the pair is a damper whose
+         * compliance c = |s_t|_eps / (mu lambda_n) comes from the current iterate; with c known the
+         * pair's two rows read s_t + c lambda_t = 0, which keeps the system symmetric.  Without
+         * normal impulse there is no friction. */
+        int n = i - 1;
+        double rad = m->mu * lam[n];
+        if (rad > 0) {
+          double sn = sqrt(sres[i] * sres[i] + sres[i + 1] * sres[i + 1] + FRICTION_EPS * FRICTION_EPS);
+          on[i] = on[i + 1] = 1;
+          comp[i] = comp[i + 1] = sn / rad;
+        } else {
+          on[i] = on[i + 1] = 0;
+          known[i] = -lam[i]; known[i + 1] = -lam[i + 1];
+        }
+        ++i;
+      }
+    }
+    /* right-hand side of the rows on the "s" branch: -s - c lambda - (A known); the operator of
+     * the inner solve is A + reg D + c on those rows, its preconditioner that operator's diagonal */
+    delassus_apply(m, rows, nrows, diag, NULL, known, R, NB, dv, dw, tmp);
+    for (int i = 0; i < nrows; ++i) {
+      rhs[i] = on[i] ? -sres[i] - comp[i] * lam[i] - (tmp[i] - m->newton_reg * diag[i] * known[i]) : 0.0;
+      pd[i] = diag[i] * (1.0 + m->newton_reg) + comp[i];
+      if (!(pd[i] > 0)) on[i] = 0;
+    }
+    /* preconditioned conjugate residuals from x = 0 (stops early once the residual has dropped by
+     * twelve orders of magnitude, where the recurrences would divide rounding noise) */
+    double gamma = 0;
+    for (int i = 0; i < nrows; ++i) { x[i] = 0; z[i] = on[i] ? rhs[i] / pd[i] : 0.0; p[i] = z[i]; }
+    delassus_apply(m, rows, nrows, diag, on, z, R, NB, dv, dw, az);
+    for (int i = 0; i < nrows; ++i) { az[i] += comp[i] * z[i]; q[i] = az[i]; gamma += z[i] * az[i]; }
+    const double gamma0 = gamma;
+    for (int k = 0; k < m->krylov_iters; ++k) {
+      double den = 0;
+      for (int i = 0; i < nrows; ++i) if (on[i]) den += q[i] * q[i] / pd[i];
+      if (!(den > 0) || !(gamma > 1e-24 * gamma0)) break;
+      double alpha = gamma / den;
+      for (int i = 0; i < nrows; ++i) if (on[i]) { x[i] += alpha * p[i]; z[i] -= alpha * q[i] / pd[i]; }
+      delassus_apply(m, rows, nrows, diag, on, z, R, NB, dv, dw, az);
+      double gn = 0;
+      for (int i = 0; i < nrows; ++i) { az[i] += comp[i] * z[i]; gn += z[i] * az[i]; }
+      double beta = gn / gamma;
+      for (int i = 0; i < nrows; ++i) { p[i] = z[i] + beta * p[i]; q[i] = az[i] + beta * q[i]; }
+      gamma = gn;
+    }
+    /* update, then back into the feasible set */
+    for (int i = 0; i < nrows; ++i) lam[i] += on[i] ? x[i] : known[i];
+    for (int i = 0; i < nrows; ++i) {
+      if (rows[i].type == 1 && lam[i] < 0) lam[i] = 0;
+      if (rows[i].type == 2) {
+        double rad = m->mu * lam[i - 1], nrm = sqrt(lam[i] * lam[i] + lam[i + 1] * lam[i + 1]);
+        if (nrm > rad) { double sc = nrm > 0 ? rad / nrm : 0; lam[i] *= sc; lam[i + 1] *= sc; }
+        ++i;
+      }
+    }
+  }
+  for (int b = 0; b < NB; ++b) { vel[b] = u[b]; om[b] = uw[b]; }
+  for (int i = 0; i < nrows; ++i) rows[i].lambda = lam[i];
+}
+
 /* One substep of an interaction group of G agents (envs[0..G), global indices e0..).  Forces,
  * terrain contacts and integration are per agent; the solve couples the agents of the group
  * through the capsule-capsule contacts.  Bodies are numbered g*B + b inside the group. */
@@ -819,6 +980,10 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
     }
     for (int g = 0; g < G; ++g)
       for (int b = 0; b < B; ++b) { vel[g * B + b] = envs[g].v[b]; om[g * B + b] = envs[g].w[b]; }
+    const int NB = G * B;
+    if (m->solver == 1) {
+      newton_solve(m, rows, nrows, R, NB, vel, om, iterations, trace, trace_n, trace_cap, pos_err_max);
+    } else {
     /* warm start: the impulses the rows start from act on the bodies before the first sweep */
     if (m->warm > 0) {
       for (int i = 0; i < nrows; ++i) {
@@ -836,7 +1001,6 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
     /* 4. projected-Jacobi sweeps over blocks: every block starts from the same
      * velocity snapshot; inside a block the rows are relaxed one after another
      * on the block's private copy of its bodies (inverse mass scaled as above). */
-    const int NB = G * B;
     for (int it = 0; it < iterations; ++it) {
       for (int b = 0; b < NB; ++b) { v0[b] = vel[b]; w0[b] = om[b]; pl[b] = V(0, 0, 0); pa[b] = V(0, 0, 0); }
       double sq = 0, mx = 0, viol = 0, cone = -INFINITY; int nbil = 0;
@@ -913,6 +1077,7 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
         t->cone_excess = cone;
       }
     }
+    }   /* solver */
     for (int g = 0; g < G; ++g)
       for (int b = 0; b < B; ++b) { envs[g].v[b] = vel[g * B + b]; envs[g].w[b] = om[g * B + b]; }
     /* impulses kept for the next substep's warm start (terrain slots and joints; a contact
@@ -1312,6 +1477,11 @@ void oracle_set_state(oracle_sim* o, const double* st) {
       E->has_store = 0;
       clear_warm(E);
     }
+}
+void oracle_set_solver(oracle_sim* o, int32_t kind, int32_t krylov_iters, double reg) {
+  o->m.solver = kind == 1 ? 1 : 0;
+  o->m.krylov_iters = krylov_iters < 0 ? 0 : krylov_iters;
+  o->m.newton_reg = reg < 0 ? 0 : reg;
 }
 void oracle_set_warm_start(oracle_sim* o, double share) { o->m.warm = share < 0 ? 0 : (share > 1 ? 1 : share); }
 void oracle_set_warm(oracle_sim* o, const double* lam_j, const double* lam_s) {

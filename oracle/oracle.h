@@ -136,6 +136,12 @@ void oracle_get_state(const oracle_sim*, double* state);
  * integrator on the position error, and a share of 1 can then grow without bound (a hanging
  * chain at 4 sweeps does); 0.8 to 0.9 is the useful range. */
 void oracle_set_warm_start(oracle_sim*, double share);
+/* Solver of the rows.  kind 0 (default): block projected Jacobi, `iterations` of oracle_step are
+ * sweeps.  kind 1: the paper's solver (Section 3.1), a non-smooth Newton method with a Krylov
+ * inner solve: `iterations` of oracle_step are Newton iterations per substep, each solved by
+ * `krylov_iters` preconditioned conjugate-residual iterations on J M^-1 J^T (+ reg times its
+ * diagonal); same rows, biases and friction law as kind 0, no mass splitting. */
+void oracle_set_solver(oracle_sim*, int32_t kind, int32_t krylov_iters, double reg);
 /* What is kept for the next substep: joint row impulses [N][J][6] (world x, y, z, then the three
  * joint axes) and terrain slot impulses [N][S][3] (normal, two tangents; 0 for inactive slots). */
 void oracle_get_warm(const oracle_sim*, double* lam_j, double* lam_s);
