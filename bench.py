@@ -111,6 +111,9 @@ def main():
     ap.add_argument("--task", action="store_true", help="task logic of Section 4.1: pushes, flagrun targets, grace period, auto-reset")
     ap.add_argument("--warm-start", type=float, default=0.0, help="share of the last substep's impulses the rows start from (0 = off)")
     ap.add_argument("--iterations", type=int, default=0, help="override the sweeps per substep (the workload is then named for it)")
+    ap.add_argument("--solver", choices=("jacobi", "newton"), default="jacobi",
+                    help="newton: the paper's non-smooth Newton / Krylov solver, 3 Newton iterations of --krylov inner iterations per substep")
+    ap.add_argument("--krylov", type=int, default=8, help="conjugate-residual iterations per Newton iteration (--solver newton)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--repeats", type=int, default=3, help="repeats of the timed region; the median is reported")
     ap.add_argument("--copy-probe", action="store_true", help="run the 256 MiB copy that calibrates the traffic counters, then exit")
@@ -140,6 +143,9 @@ def main():
         scene.params.height_map = 1
     if args.warm_start > 0:
         scene.params.warm_start = args.warm_start
+    if args.solver == "newton":
+        scene.params.solver, scene.params.krylov_iters = 1, args.krylov
+        cfg["iterations"] = 3          # Newton iterations per substep
     if args.iterations > 0:
         cfg["iterations"] = args.iterations
     collide = args.self_collide or args.group_size > 1
@@ -223,6 +229,7 @@ def main():
                 + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else "")
                 + ("_task" if args.task else "") + (f"_warm{args.warm_start:g}" if args.warm_start > 0 else "")
                 + (f"_its{args.iterations}" if args.iterations > 0 else "")
+                + (f"_newton{cfg['iterations']}x{args.krylov}" if args.solver == "newton" else "")
                 + (f"_epb{args.envs_per_block}" if args.envs_per_block else ""))
     # HBM bytes and vector instructions per launch come from the tracked rocprofv3 summary and are
     # quoted only for the kernel sources and the workload they were measured on (null otherwise)
@@ -253,7 +260,7 @@ def main():
                    "num_envs": N, "obs_dim": sim.obs_dim, "robot": rob.name, "bodies": rob.n_bodies,
                    "joints": rob.n_joints, "dofs": rob.n_dofs, "contact_slots": sim.S,
                    "terrain": "heightfield 256x256 x 0.1 m" if scene.terrain.kind else "plane",
-                   "dt": cfg["dt"], "substeps": sub, "iterations": its, "settle_steps": settle,
+                   "dt": cfg["dt"], "substeps": sub, "iterations": its, "solver": args.solver, "settle_steps": settle,
                    "mean_active_contacts_per_env": round(active, 3), "kernel_launches_per_step": 1,
                    **sim.launch_info(), **pair_info},
         "roofline": {"bound": "alu", "kernel": "step_kernel", "achieved": achieved_tflops, "peak": peak_tflops,

@@ -126,7 +126,8 @@ typedef struct {
   /* solver of the rows: 0 = block projected Jacobi with mass splitting (`iterations` sweeps);
    * 1 = non-smooth Newton with a conjugate-residual inner solve, the paper's own choice
    * (Section 3.1): `iterations` Newton iterations of `krylov_iters` inner iterations each;
-   * newton_reg: relative compliance added to the diagonal of J M^-1 J^T */
+   * newton_reg: damping of the Newton step, this share of the diagonal of J M^-1 J^T is added to the
+   * operator that the increments are solved with (the fixed point does not depend on it) */
   int solver, krylov_iters;
   double newton_reg;
 } model;
@@ -762,7 +763,7 @@ static void newton_solve(const model* m, row_t* rows, int nrows, v3 (*R)[3], int
       if (!(pd[i] > 0)) on[i] = 0;
     }
     /* preconditioned conjugate residuals from x = 0 (stops early once the residual has dropped by
-     * twelve orders of magnitude, where the recurrences would divide rounding noise) */
+     * twelve orders of magnitude in this measure, where the recurrences would divide rounding noise) */
     double gamma = 0;
     for (int i = 0; i < nrows; ++i) { x[i] = 0; z[i] = on[i] ? rhs[i] / pd[i] : 0.0; p[i] = z[i]; }
     delassus_apply(m, rows, nrows, diag, on, z, R, NB, dv, dw, az);
@@ -771,7 +772,7 @@ static void newton_solve(const model* m, row_t* rows, int nrows, v3 (*R)[3], int
     for (int k = 0; k < m->krylov_iters; ++k) {
       double den = 0;
       for (int i = 0; i < nrows; ++i) if (on[i]) den += q[i] * q[i] / pd[i];
-      if (!(den > 0) || !(gamma > 1e-24 * gamma0)) break;
+      if (!(den > 0) || !(gamma > 1e-12 * gamma0)) break;
       double alpha = gamma / den;
       for (int i = 0; i < nrows; ++i) if (on[i]) { x[i] += alpha * p[i]; z[i] -= alpha * q[i] / pd[i]; }
       delassus_apply(m, rows, nrows, diag, on, z, R, NB, dv, dw, az);

@@ -140,7 +140,7 @@ void oracle_set_warm_start(oracle_sim*, double share);
  * sweeps.  kind 1: the paper's solver (Section 3.1), a non-smooth Newton method with a Krylov
  * inner solve: `iterations` of oracle_step are Newton iterations per substep, each solved by
  * `krylov_iters` preconditioned conjugate-residual iterations on J M^-1 J^T (+ reg times its
- * diagonal); same rows, biases and friction law as kind 0, no mass splitting. */
+ * diagonal: a damping of the Newton step that leaves the fixed point where it is); same rows, biases and friction law as kind 0, no mass splitting. */
 void oracle_set_solver(oracle_sim*, int32_t kind, int32_t krylov_iters, double reg);
 /* What is kept for the next substep: joint row impulses [N][J][6] (world x, y, z, then the three
  * joint axes) and terrain slot impulses [N][S][3] (normal, two tangents; 0 for inactive slots). */

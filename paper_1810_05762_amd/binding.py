@@ -46,6 +46,7 @@ class SimDesc(C.Structure):
         ("height_map", C.c_int32),
         ("n_collide_pairs", C.c_int32), ("collide_pairs", C.POINTER(C.c_int32)), ("group_size", C.c_int32),
         ("warm_start", C.c_double),
+        ("solver", C.c_int32), ("krylov_iterations", C.c_int32), ("newton_reg", C.c_double),
     ]
 
 
@@ -168,6 +169,9 @@ def make_desc(scene):
     d.collide_pairs = pairs.ctypes.data_as(C.POINTER(C.c_int32)) if d.n_collide_pairs else None
     d.group_size = int(getattr(p, "group_size", 1))
     d.warm_start = float(getattr(p, "warm_start", 0.0))
+    d.solver = int(getattr(p, "solver", 0))
+    d.krylov_iterations = int(getattr(p, "krylov_iters", 8))
+    d.newton_reg = float(getattr(p, "newton_reg", 0.0))
     return d, [bodies, joints, heights, origins, pairs]
 
 

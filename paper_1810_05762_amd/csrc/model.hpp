@@ -53,6 +53,10 @@ struct Model {
   float g[3];
   float mu, margin, beta_j, beta_c, v_depen, c_lin, c_ang, w_max, reset_noise;
   float warm;   // warm start: share of the last substep's impulses the rows start from (0: none)
+  // solver of the rows: 0 block projected Jacobi; 1 non-smooth Newton with `krylov` conjugate-residual
+  // iterations per Newton iteration; newton_reg times the operator's diagonal damps the Newton step
+  int32_t solver, krylov;
+  float newton_reg;
   float term_height, alive_bonus;
   int32_t max_steps, gyro, contacts;
   int32_t max_joint_sides;  // largest n_joint_sides over the bodies

@@ -220,6 +220,11 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   m->reset_noise = (float)d->reset_noise;
   if (!(d->warm_start >= 0.0 && d->warm_start <= 1.0)) return fail(SIM_ERR_ARG, "warm_start %g outside 0..1", d->warm_start);
   m->warm = (float)d->warm_start;
+  if (d->solver != 0 && d->solver != 1) return fail(SIM_ERR_ARG, "solver must be 0 (Jacobi) or 1 (Newton / Krylov)");
+  if (d->solver == 1 && (d->krylov_iterations < 1 || d->krylov_iterations > 64)) return fail(SIM_ERR_ARG, "krylov_iterations %d outside 1..64", d->krylov_iterations);
+  if (d->solver == 1 && !(d->newton_reg >= 0.0 && d->newton_reg <= 1.0)) return fail(SIM_ERR_ARG, "newton_reg outside 0..1");
+  m->solver = d->solver; m->krylov = d->solver == 1 ? d->krylov_iterations : 0; m->newton_reg = (float)d->newton_reg;
+  if (m->solver == 1 && m->warm > 0.0f) return fail(SIM_ERR_ARG, "the Newton solver is not available together with the warm start");
   m->term_height = (float)d->term_height; m->alive_bonus = (float)d->alive_bonus;
   m->max_steps = d->max_episode_steps; m->gyro = d->gyroscopic; m->contacts = d->contacts;
   // Height map of the complex-terrain task (Section 4.1: 15 x 11, follows the centre of mass,
@@ -249,6 +254,8 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   m->group = d->group_size > 1 ? d->group_size : 1;
   if (m->warm > 0.0f && (m->n_pairs > 0 || m->group > 1))
     return fail(SIM_ERR_ARG, "warm_start is not available together with capsule-capsule collisions");
+  if (m->solver == 1 && (m->n_pairs > 0 || m->group > 1))
+    return fail(SIM_ERR_ARG, "the Newton solver is not available together with capsule-capsule collisions");
   m->n_agent_pairs = 0;
   for (int a = 0; a < m->group; ++a)
     for (int b = a + 1; b < m->group; ++b) {
@@ -275,11 +282,17 @@ static int pairs_of(const Model& m) { return (m.n_pairs > 0 || m.group > 1) ? (m
 // average everywhere); small batches and the collision and warm-start variants (which need the
 // registers) keep the narrow one.
 static int threads_for(const Model& m, int E) {
-  return (E == 16 && m.max_joint_sides <= 4 && !pairs_of(m) && !(m.warm > 0.0f)) ? kThreadsWide : kThreads;
+  return (E == 16 && m.max_joint_sides <= 4 && !pairs_of(m) && !(m.warm > 0.0f) && m.solver == 0) ? kThreadsWide : kThreads;
 }
 static LdsPlan plan_for(const Model& m, int E) {
   const int with_patch = (m.terrain_kind == 1 && m.nx >= kPatch && m.ny >= kPatch) ? 1 : 0;
-  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m), threads_for(m, E), m.warm > 0.0f ? 1 : 0);
+  return make_plan(m.B, m.J, m.S, m.D, m.F, E, with_patch, pairs_of(m), threads_for(m, E), m.warm > 0.0f ? 1 : 0, m.solver);
+}
+// The Newton solver keeps every row's vectors in registers, one contact per thread: every slot of
+// every env of the workgroup needs a contact thread of its own next to the joint wavefronts.
+static bool newton_fits(const Model& m, int E) {
+  const int joint_threads = ((2 * m.J * E + 63) / 64) * 64;
+  return E <= 8 && m.S * E <= kThreads - joint_threads && 2 * m.B * E <= kThreads;
 }
 
 static int default_envs_per_block(const Model& m, int N) {
@@ -287,6 +300,10 @@ static int default_envs_per_block(const Model& m, int N) {
   int lim = kThreads / m.B;
   if (m.J > 0 && (kThreads - 64) / (2 * m.J) < lim) lim = (kThreads - 64) / (2 * m.J);
   if (lim > 16) lim = 16;
+  if (m.solver == 1) {
+    if (lim > 8) lim = 8;
+    while (lim > 1 && !newton_fits(m, lim)) --lim;
+  }
   int want = N / 256;  // keep at least one workgroup per compute unit when N allows
   if (want < 1) want = 1;
   int E = want < lim ? want : lim;
@@ -469,7 +486,11 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
     return SIM_OK;
   };
   const bool few = m.max_joint_sides <= 4;
-  int lrc = m.warm > 0.0f ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 0, kThreads, 1>)
+  if (m.solver == 1 && !newton_fits(m, s->E))
+    return fail(SIM_ERR_ARG, "this robot does not fit the Newton solver's workgroup (a contact thread per slot)");
+  int lrc = m.solver == 1 ? ((s->E == 8 && few) ? launch(&step_kernel<8, 4, 0, kThreads, 0, 1>)
+                             : few ? launch(&step_kernel<0, 4, 0, kThreads, 0, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 0, 1>))
+            : m.warm > 0.0f ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 0, kThreads, 1>)
                              : few ? launch(&step_kernel<0, 4, 0, kThreads, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 1>))
             : pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
                      : few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
@@ -639,6 +660,8 @@ extern "C" int sim_set_envs_per_block(sim_t* s, int E) {
     return fail(SIM_ERR_ARG, "envs_per_block %d does not fit %d threads (need E*B <= %d and 2*E*J <= %d)", E, kThreads,
                 kThreads, kThreads - 64);
   if (m.group > 1 && E % m.group) return fail(SIM_ERR_ARG, "envs_per_block %d is not a multiple of the group size %d", E, m.group);
+  if (m.solver == 1 && !newton_fits(m, E))
+    return fail(SIM_ERR_ARG, "envs_per_block %d: the Newton solver needs a contact thread per slot (at most 8 envs per workgroup)", E);
   LdsPlan P = plan_for(m, E);
   if ((size_t)P.total * 4 > 160 * 1024) return fail(SIM_ERR_ARG, "envs_per_block %d exceeds LDS", E);
   s->E = E;

@@ -86,11 +86,12 @@ struct LdsPlan {
   int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
   int pq, po, pnear, pbs, pcount, pbcnt, pblist;  // capsule-capsule contacts (only with pairs != 0)
   int wj, wc;                                     // kept impulses of joints and slots (only with warm != 0)
+  int nu, nred, nsum;                             // Newton solver: body vectors, reduction entries, totals
 };
 
 // pairs: 0 = no capsule-capsule contacts, else the interaction group size (1 = self-collision only)
 __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, int E, int with_patch, int pairs = 0,
-                                             int threads = kThreads, int warm = 0) {
+                                             int threads = kThreads, int warm = 0, int newton = 0) {
   LdsPlan p;
   int o = 0;
   p.pos = o; o += B * 7 * E;
@@ -129,6 +130,9 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.pblist = o; o += pairs ? (B * E * 6 + 3) / 4 : 0;  // per body: up to six of them, one byte each
   p.wj = o; o += warm ? J * 6 * E : 0;
   p.wc = o; o += warm ? S * 3 * E : 0;
+  p.nu = o; o += newton ? B * kVS * E : 0;
+  p.nred = o; o += newton ? 3 * (J + S) * E : 0;
+  p.nsum = o; o += newton ? 3 * E : 0;
   p.total = o;
   return p;
 }
@@ -231,6 +235,8 @@ struct SideRows {
   float nl[3];             // lower bound of the next increment of angular row k: minus the impulse so
                            // far for a limit row (impulse >= 0), -infinity for a locked axis
   float lam[3];            // impulses of the angular rows so far (only the warm start keeps them)
+  float pD[3], pb[3];      // (Newton solver) diagonal of J M^-1 J^T and bias of the positional rows
+  float aD[3], ab[3];      //                 and of the angular rows
   int onesided;            // bit k set: angular row k is a limit row (impulse >= 0)
   int upper;               // bit k set: that limit row stands for the upper limit
 };
@@ -245,6 +251,7 @@ struct ContactRows {
   float Y[3][3];     // angular response
   float ls;          // linear response n_b / m
   float meff[3], bias, lam[3];
+  float D[3];        // (Newton solver) diagonal of J M^-1 J^T
   int slot_e;        // slot * E + e
   int body;
 };
@@ -262,7 +269,7 @@ struct ContactRows {
 // body's world inverse inertia, weight sum and inverse mass.
 __device__ __forceinline__ void build_contact_rows(ContactRows& c, const float* Lrec, const float* Liw,
                                                    const float* Lnb, int s, int ee, int E, int body, float imb,
-                                                   float h, float beta_c, float v_depen) {
+                                                   float h, float beta_c, float v_depen, bool whole_body = false) {
   c.body = body;
   c.slot_e = s * E + ee;
   float d = Lrec[(s * kRecWords + 3) * E + ee];
@@ -270,6 +277,7 @@ __device__ __forceinline__ void build_contact_rows(ContactRows& c, const float* 
   for (int k = 0; k < 3; ++k) { n[k] = Lrec[(s * kRecWords + 4 + k) * E + ee]; rc[k] = Lrec[(s * kRecWords + 7 + k) * E + ee]; }
   for (int k = 0; k < 6; ++k) iwb[k] = Liw[(body * kVS + k) * E + ee];
   float nbb = Lnb[body * E + ee] / Lrec[(s * kRecWords + 10) * E + ee];
+  if (whole_body) nbb = 1.0f;   // (the Newton solver does not split the body among its blocks)
   float t1[3], t2[3];
   if (fabsf(n[0]) < 0.57735f) { t1[0] = 0.0f; t1[1] = n[2]; t1[2] = -n[1]; }
   else { t1[0] = -n[2]; t1[1] = 0.0f; t1[2] = n[0]; }
@@ -284,6 +292,7 @@ __device__ __forceinline__ void build_contact_rows(ContactRows& c, const float* 
     sym_vec(iwb, c.ang[r], y);
     float keff = nbb * (imb + dot(c.ang[r], y));
     c.meff[r] = keff > 0.0f ? 1.0f / keff : 0.0f;
+    c.D[r] = keff;
     for (int k = 0; k < 3; ++k) c.Y[r][k] = nbb * y[k];
     c.lam[r] = 0.0f;
   }
@@ -576,7 +585,9 @@ __device__ __forceinline__ int wave_alloc(int n, int* counter) {
 
 // PC != 0: capsule-capsule contacts (within an agent and between the agents of a group) compiled in.
 // NT: threads per workgroup.
-template <int EC, int NJ, int PC = 0, int NT = kThreads, int WS = 0>
+// NS != 0: the rows are solved by the non-smooth Newton / conjugate-residual solver instead of
+// the Jacobi sweeps (at most 8 envs per workgroup, every slot has a contact thread of its own).
+template <int EC, int NJ, int PC = 0, int NT = kThreads, int WS = 0, int NS = 0>
 __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   constexpr int kThreads = NT;   // (shadows the namespace-scope default inside the kernel)
 #ifdef SIM_PHASE_TIMING
@@ -600,7 +611,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   const Field H0 = make_field(M, a.heights, a.coarse);
   const bool use_patch = m_terrain == 1 && H0.nx >= kPatch && H0.ny >= kPatch;
   const int m_group = PC ? (M.group > 1 ? M.group : 1) : 1, m_npairs = PC ? M.n_pairs : 0, m_nap = PC ? M.n_agent_pairs : 0;
-  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0, NT, WS);
+  const LdsPlan P = make_plan(B, J, S, D, F, E, use_patch ? 1 : 0, PC ? m_group : 0, NT, WS, NS);
   float* Lpos = lds + P.pos;
   float* Lvel = lds + P.vel;
   float* Liw = lds + P.iw;
@@ -1393,7 +1404,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       for (int c = 0; c < 3; ++c) xo[c] = Lpos[(bo * 7 + c) * E + e];
       for (int c = 0; c < 4; ++c) qo[c] = Lpos[(bo * 7 + 3 + c) * E + e];
       for (int c = 0; c < 6; ++c) iwo[c] = Liw[(bo * kVS + c) * E + e];
-      float no = Lnb[bo * E + e], imo = Ltbody[4 * bo + 3];
+      float no = NS ? 1.0f : Lnb[bo * E + e], imo = Ltbody[4 * bo + 3];   // (Newton: no mass splitting)
       if (ghost) {
         for (int c = 0; c < 3; ++c) xo[c] = 0.0f;
         qo[0] = 1.0f; qo[1] = qo[2] = qo[3] = 0.0f;
@@ -1425,6 +1436,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const float keff = kp + lane_swap1(kp);
         jr.pme[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
         jr.pnb[k] = jr.pme[k] * (bh * C[k]);
+        jr.pD[k] = keff; jr.pb[k] = bh * C[k];
         for (int c = 0; c < 3; ++c) jr.Y[k][c] = sg * no * y[c];
       }
       // joint angles from both orientations; axes live in the parent frame
@@ -1454,6 +1466,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const float keff = kp + lane_swap1(kp);
         jr.ame[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
         jr.anb[k] = jr.ame[k] * bias;
+        jr.aD[k] = keff; jr.ab[k] = bias;
         jr.lam[k] = 0.0f;
         jr.nl[k] = jt.mode[k] == 0 ? -INFINITY : 0.0f;
         for (int c = 0; c < 3; ++c) { jr.sax[k][c] = sgl * ak[c]; jr.Z[k][c] = sg * no * z[c]; }
@@ -1468,7 +1481,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       if (n_active > 0) {
         const int i = Llist[li < n_active ? li : n_active - 1];
         const int ee = i % E, sl = i / E, body = Ltslot[2 * sl];
-        build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen);
+        build_contact_rows(cr, Lrec, Liw, Lnb, sl, ee, E, body, Ltbody[4 * body + 3], h, p_beta_c, p_vdepen, NS != 0);
         if constexpr (WS != 0)
           for (int r = 0; r < 3; ++r) cr.lam[r] = p_warm * Lwc[(sl * 3 + r) * E + ee];
       } else {
@@ -1517,6 +1530,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const bool used = g_on && k < g_nslots;
         gat_slot[k] = (g_slot0 + (used ? k : 0)) * kCS * E + e;
         gat_w[NJ + k] = used ? Lrec[((g_slot0 + k) * kRecWords + 10) * E + e] : 0.0f;
+        if constexpr (NS != 0) gat_w[NJ + k] = (used && Lreci[((g_slot0 + k) * kRecWords + 0) * E + e]) ? 1.0f : 0.0f;
       }
     }
     // ---- S: sweeps
@@ -1609,6 +1623,231 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     // Warm start: sweep -1 relaxes nothing; every block applies the impulses it starts from (the
     // kept ones times the share) to its copies, and the average of the copies hands every body
     // the plain sum of them, as a sweep does with the increments.
+    if constexpr (NS != 0) {
+      // ---- S (Newton): the paper's solver (Section 3.1), a non-smooth Newton method whose every
+      // iteration is solved by a fixed number of preconditioned conjugate-residual iterations.
+      // Unknowns: the impulses lambda of all rows; u = v* + M^-1 J^T lambda; residual s = J u + bias.
+      // Bilateral rows ask for s = 0; one-sided rows for min(lambda, s / D) = 0 (D the diagonal of
+      // J M^-1 J^T); a friction pair follows the smooth isotropic Coulomb law lambda_t = -mu lambda_n
+      // s_t / |s_t|_eps, which enters an iteration as a damper s_t + c lambda_t = 0 with the
+      // compliance c = |s_t|_eps / (mu lambda_n) of the current iterate.  The operator is applied
+      // through the bodies in the two phases of a Jacobi sweep: every block writes the velocity
+      // change its rows' impulses give its bodies (scatter), a barrier, every body adds up its
+      // blocks' contributions (gather), a barrier, every row takes J times the result.  Every row's
+      // vectors stay in the registers of its lane (both lanes of a joint hold the same values).
+      // Dot products over the rows of an env: every block leaves its partial sum in an LDS entry of
+      // its own, one thread per env adds them up in block order, so the result does not depend on
+      // which wavefront ran first.
+      float* LU = lds + P.nu;        // [B][kVS][E]: M^-1 J^T x (plus v* when asked for)
+      float* Lred = lds + P.nred;    // [3][J + S][E]: partial sums of the blocks
+      float* Lsum = lds + P.nsum;    // [3][E]: their totals
+      const int nblk = J + S;
+      const float p_reg = M.newton_reg;
+      const int n_kry = M.krylov;
+      constexpr float kFrictionEps = 1e-3f;   // m/s
+      const bool jrole = joint_wave;
+      if (jrole) build_joint_side(); else build_contact();
+      for (int i = tid; i < 3 * nblk * E; i += kThreads) Lred[i] = 0.0f;   // inactive slots contribute nothing
+      const int nr = jrole ? 6 : 3;
+      const bool active = jrole ? js_on : has_contact;      // this lane holds rows
+      // The row constants of either role in one array, so that the two roles share registers:
+      //   joint side: K[0..2] lever arm, K[3] linear response, K[4] sign, K[5..13] angular response of
+      //               the positional rows, K[14..22] the three axes, K[23..31] their angular response;
+      //   contact:    K[0..8] directions n, t1, t2, K[9..17] lever x direction, K[18..26] angular
+      //               response, K[27] linear response.
+      float K[32], Dg[6], bs[6];
+      int ones = 0, c_body = 0, c_slot_e = 0;
+      if (jrole) {
+        for (int k = 0; k < 3; ++k) {
+          K[k] = jr.sr[k];
+          for (int c = 0; c < 3; ++c) { K[5 + 3 * k + c] = jr.Y[k][c]; K[14 + 3 * k + c] = jr.sax[k][c]; K[23 + 3 * k + c] = jr.Z[k][c]; }
+          Dg[k] = jr.pD[k]; bs[k] = jr.pb[k]; Dg[3 + k] = jr.aD[k]; bs[3 + k] = jr.ab[k];
+        }
+        K[3] = jr.sv; K[4] = jr.sg;
+        ones = jr.onesided;
+      } else {
+        for (int r = 0; r < 3; ++r) {
+          for (int c = 0; c < 3; ++c) { K[3 * r + c] = cr.dir[r][c]; K[9 + 3 * r + c] = cr.ang[r][c]; K[18 + 3 * r + c] = cr.Y[r][c]; }
+          Dg[r] = cr.D[r]; bs[r] = r == 0 ? cr.bias : 0.0f; Dg[3 + r] = 0.0f; bs[3 + r] = 0.0f;
+        }
+        K[27] = cr.ls; K[28] = K[29] = K[30] = K[31] = 0.0f;
+        c_body = cr.body; c_slot_e = cr.slot_e;
+      }
+      const int my_e = jrole ? js_e : (c_slot_e % E);
+      const int my_blk = jrole ? (js_j < J ? js_j : 0) : J + c_slot_e / E;
+      const bool writes_partial = jrole ? (js_on && js_side == 0) : has_contact;
+      const int j_ob = jrole ? (js_side ? Ltjoint[js_j < J ? js_j : 0].child : Ltjoint[js_j < J ? js_j : 0].parent) : 0;
+      const int j_bo = j_ob < 0 ? 0 : j_ob;
+      // the velocity change of the lane's own body from the impulses xv of its rows -> its copy
+      auto scatter = [&](const float* xv) {
+        if (jrole) {
+          if (js_on && j_ob >= 0) {
+            float dw[3] = {0.0f, 0.0f, 0.0f};
+            for (int k = 0; k < 3; ++k)
+              for (int c = 0; c < 3; ++c) dw[c] += K[5 + 3 * k + c] * xv[k] + K[23 + 3 * k + c] * xv[3 + k];
+            for (int c = 0; c < 3; ++c) {
+              Loutj[(js_j * kJS + js_side * 6 + c) * E + js_e] = K[3] * xv[c];
+              Loutj[(js_j * kJS + js_side * 6 + 3 + c) * E + js_e] = dw[c];
+            }
+          }
+        } else if (has_contact) {
+          const int ee = c_slot_e % E, sl = c_slot_e / E;
+          float dv[3] = {0.0f, 0.0f, 0.0f}, dw[3] = {0.0f, 0.0f, 0.0f};
+          for (int r = 0; r < 3; ++r)
+            for (int c = 0; c < 3; ++c) { dv[c] += K[27] * K[3 * r + c] * xv[r]; dw[c] += K[18 + 3 * r + c] * xv[r]; }
+          for (int c = 0; c < 3; ++c) { Loutc[(sl * kCS + c) * E + ee] = dv[c]; Loutc[(sl * kCS + 3 + c) * E + ee] = dw[c]; }
+        }
+      };
+      // every body: the plain sum of its blocks' contributions (in static order), on top of the
+      // velocities the solve started from when `with_base`
+      auto gather_sum = [&](bool with_base, float* dst) {
+        if (!g_on) return;
+        auto part = [&](int c0, int nc) {
+          for (int c = c0; c < c0 + nc; ++c) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int k = 0; k < NJ; ++k) acc += gat_w[k] * Loutj[gat_off[k] + c * E];
+#pragma unroll
+            for (int k = 0; k < 3; ++k) acc += gat_w[NJ + k] * Loutc[gat_slot[k] + c * E];
+            const float base = with_base ? Lvel[(g_b * kVS + c) * E + e] : 0.0f;
+            dst[(g_b * kVS + c) * E + e] = base + acc;
+          }
+        };
+        if (g_split) part(3 * g_half, 3); else part(0, 6);
+      };
+      // y = J (body vectors in src) for the lane's rows
+      auto rows_of = [&](const float* src, float* y) {
+        const int bo = jrole ? j_bo : c_body, ee = my_e;
+        float uv[3], uw[3];
+        for (int c = 0; c < 3; ++c) { uv[c] = src[(bo * kVS + c) * E + ee]; uw[c] = src[(bo * kVS + 3 + c) * E + ee]; }
+        if (jrole) {
+#pragma unroll
+          for (int k = 0; k < 3; ++k) {
+            const float p0 = K[4] * uv[k] + cross_unit_dot(K, k, uw);
+            y[k] = p0 + lane_swap1(p0);
+            const float p1 = K[14 + 3 * k] * uw[0] + K[15 + 3 * k] * uw[1] + K[16 + 3 * k] * uw[2];
+            y[3 + k] = p1 + lane_swap1(p1);
+          }
+        } else {
+          for (int r = 0; r < 3; ++r) {
+            y[r] = (K[3 * r] * uv[0] + K[3 * r + 1] * uv[1] + K[3 * r + 2] * uv[2]) +
+                   (K[9 + 3 * r] * uw[0] + K[10 + 3 * r] * uw[1] + K[11 + 3 * r] * uw[2]);
+            y[3 + r] = 0.0f;
+          }
+        }
+      };
+      // totals over the rows of the lane's env of up to three products
+      auto reduce3 = [&](float pa, float pb, float pc, float& ta, float& tb, float& tc) {
+        if (writes_partial) {
+          Lred[(0 * nblk + my_blk) * E + my_e] = pa; Lred[(1 * nblk + my_blk) * E + my_e] = pb; Lred[(2 * nblk + my_blk) * E + my_e] = pc;
+        }
+        __syncthreads();
+        if (tid < 3 * E) {
+          const int qd = tid / E, ee = tid - qd * E;
+          float sm = 0.0f;
+          for (int k = 0; k < nblk; ++k) sm += Lred[(qd * nblk + k) * E + ee];
+          Lsum[qd * E + ee] = sm;
+        }
+        __syncthreads();
+        ta = Lsum[0 * E + my_e]; tb = Lsum[1 * E + my_e]; tc = Lsum[2 * E + my_e];
+      };
+      float lam[6] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      for (int it = 0; it < a.iterations; ++it) {
+        float sres[6], known[6], cp[6], pd[6], tmp[6];
+        int on = 0;
+        // residual of the current iterate
+        scatter(lam);
+        __syncthreads();
+        gather_sum(true, LU);
+        __syncthreads();
+        rows_of(LU, sres);
+        for (int k = 0; k < 6; ++k) { sres[k] += bs[k]; known[k] = 0.0f; cp[k] = 0.0f; }
+        // the branch every row is on
+        if (jrole) {
+          on = 7;
+          for (int k = 0; k < 3; ++k) {
+            const bool one = (ones >> k) & 1;
+            const bool s_branch = !one || (Dg[3 + k] > 0.0f && lam[3 + k] - sres[3 + k] / Dg[3 + k] > 0.0f);
+            if (s_branch) on |= 8 << k; else known[3 + k] = -lam[3 + k];
+          }
+        } else {
+          if (Dg[0] > 0.0f && lam[0] - sres[0] / Dg[0] > 0.0f) on |= 1; else known[0] = -lam[0];
+          const float rad = p_mu * lam[0];
+          if (rad > 0.0f) {
+            on |= 6;
+            cp[1] = cp[2] = sqrtf(sres[1] * sres[1] + sres[2] * sres[2] + kFrictionEps * kFrictionEps) / rad;
+          } else { known[1] = -lam[1]; known[2] = -lam[2]; }
+        }
+        for (int k = 0; k < 6; ++k) {
+          pd[k] = Dg[k] * (1.0f + p_reg) + cp[k];
+          if (!(pd[k] > 0.0f) || k >= nr || !active) on &= ~(1 << k);
+        }
+        // right-hand side of the rows on the "s" branch: -s - c lambda - A known
+        scatter(known);
+        __syncthreads();
+        gather_sum(false, LU);
+        __syncthreads();
+        rows_of(LU, tmp);
+        float x[6], z[6], pv[6], q[6], az[6];
+        for (int k = 0; k < 6; ++k) {
+          const bool o = (on >> k) & 1;
+          const float rhs = o ? -sres[k] - cp[k] * lam[k] - tmp[k] : 0.0f;
+          x[k] = 0.0f; z[k] = o ? rhs / pd[k] : 0.0f; pv[k] = z[k];
+        }
+        // (A + reg D + c) z on the rows of the "s" branch
+        auto apply_hat = [&](const float* xv, float* y) {
+          scatter(xv);
+          __syncthreads();
+          gather_sum(false, LU);
+          __syncthreads();
+          rows_of(LU, y);
+          for (int k = 0; k < 6; ++k) y[k] = ((on >> k) & 1) ? y[k] + (p_reg * Dg[k] + cp[k]) * xv[k] : 0.0f;
+        };
+        apply_hat(z, az);
+        float gamma, den, unused;
+        {
+          float pa = 0.0f, pb = 0.0f;
+          for (int k = 0; k < 6; ++k) { q[k] = az[k]; pa += z[k] * az[k]; if ((on >> k) & 1) pb += az[k] * az[k] / pd[k]; }
+          reduce3(pa, pb, 0.0f, gamma, den, unused);
+        }
+        const float gamma0 = gamma;
+        bool done = false;
+        for (int kk = 0; kk < n_kry; ++kk) {
+          done = done || !(den > 0.0f) || !(gamma > 1e-12f * gamma0);
+          const float alpha = done ? 0.0f : gamma / den;
+          for (int k = 0; k < 6; ++k)
+            if ((on >> k) & 1) { x[k] += alpha * pv[k]; z[k] -= alpha * q[k] / pd[k]; }
+          if (kk == n_kry - 1) break;       // (the last iteration's operator product would not be used)
+          apply_hat(z, az);
+          float pa = 0.0f, pb = 0.0f, pc = 0.0f, ta, tb, tc;
+          for (int k = 0; k < 6; ++k) {
+            pa += z[k] * az[k];
+            if ((on >> k) & 1) { pb += az[k] * az[k] / pd[k]; pc += az[k] * q[k] / pd[k]; }
+          }
+          reduce3(pa, pb, pc, ta, tb, tc);
+          if (!done) {
+            const float beta = ta / gamma;
+            for (int k = 0; k < 6; ++k) { pv[k] = z[k] + beta * pv[k]; q[k] = az[k] + beta * q[k]; }
+            den = tb + 2.0f * beta * tc + beta * beta * den;     // q . q / pd of the new q
+            gamma = ta;
+          }
+        }
+        // update, then back into the feasible set
+        for (int k = 0; k < 6; ++k) lam[k] += ((on >> k) & 1) ? x[k] : known[k];
+        if (jrole) {
+          for (int k = 0; k < 3; ++k) if ((ones >> k) & 1) lam[3 + k] = fmaxf(lam[3 + k], 0.0f);
+        } else {
+          lam[0] = fmaxf(lam[0], 0.0f);
+          const float rad = p_mu * lam[0], nrm = sqrtf(lam[1] * lam[1] + lam[2] * lam[2]);
+          if (nrm > rad) { const float sc = nrm > 0.0f ? rad / nrm : 0.0f; lam[1] *= sc; lam[2] *= sc; }
+        }
+      }
+      // the solved velocities: v* + M^-1 J^T lambda
+      scatter(lam);
+      __syncthreads();
+      gather_sum(true, Lvel);
+      __syncthreads();
+    } else
     if (joint_wave) {
       build_joint_side();
       build_pair();

@@ -35,7 +35,7 @@ class SimParams:
     warm_start: float = 0.0        # share (0..1) of the previous substep's impulses the rows start from
     solver: int = 0                # 0: block projected Jacobi; 1: non-smooth Newton with a Krylov inner solve
     krylov_iters: int = 8          # conjugate-residual iterations per Newton iteration (solver 1)
-    newton_reg: float = 0.0        # relative compliance on the diagonal of J M^-1 J^T (solver 1)
+    newton_reg: float = 0.1        # damping of the Newton step: this share of the operator's diagonal is added to it (solver 1)
 
 
 @dataclass

@@ -17,7 +17,7 @@ SOLVE_ONLY = oracle.PH_CONTACTS | oracle.PH_SOLVE
 
 def newton(krylov=8, **kw):
     p = free_params(**kw)
-    p.solver, p.krylov_iters = 1, krylov
+    p.solver, p.krylov_iters, p.newton_reg = 1, krylov, 0.0     # (undamped Newton steps: the closed forms are met exactly)
     return p
 
 
