@@ -42,6 +42,21 @@ def flops_per_env_step(B, J, S, substeps, iterations, active, blocks_per_body):
     return substeps * (iterations * sweep + setup)
 
 
+# Newton / Krylov solver: one application of J M^-1 J^T through the bodies
+F_JOINT_APPLY = 162.0     # both sides: velocity change from 6 impulses (39 flops a side), 6 row products (42 a side)
+F_CONTACT_APPLY = 80.0    # velocity change from 3 impulses, 3 row products
+F_ROW_VECTOR = 14.0       # per row and inner iteration: the four vector updates and three partial dot products
+
+
+def flops_per_env_step_newton(B, J, S, substeps, newton_its, krylov, active, blocks_per_body):
+    apply_ = J * F_JOINT_APPLY + active * F_CONTACT_APPLY + B * 12.0 * blocks_per_body
+    rows = 6 * J + 3 * active
+    per_newton = (krylov + 2) * apply_ + krylov * rows * F_ROW_VECTOR + rows * 20.0
+    setup = (J * F_JOINT_SETUP + active * F_CONTACT_SETUP + B * F_BODY_SUBSTEP
+             + S * F_SLOT_REJECT + active * F_SLOT_NARROW)
+    return substeps * (newton_its * per_newton + apply_ + setup)
+
+
 def bytes_per_env_step(B, J, S, D, obs_dim, substeps, iterations, active):
     """HBM byte accountings: A compulsory (state in+out, actions, obs, reward, done);
     B state and slot records streamed once per substep; C every sweep streams velocities
@@ -222,7 +237,10 @@ def main():
     active = float(con["active"].sum()) / N
     blocks_per_body = (2.0 * rob.n_joints + active) / rob.n_bodies
 
-    fl = flops_per_env_step(rob.n_bodies, rob.n_joints, sim.S, sub, its, active, blocks_per_body)
+    if args.solver == "newton":
+        fl = flops_per_env_step_newton(rob.n_bodies, rob.n_joints, sim.S, sub, its, args.krylov, active, blocks_per_body)
+    else:
+        fl = flops_per_env_step(rob.n_bodies, rob.n_joints, sim.S, sub, its, active, blocks_per_body)
     bA, bB, bC = bytes_per_env_step(rob.n_bodies, rob.n_joints, sim.S, rob.n_dofs, sim.obs_dim, sub, its, active)
     achieved_tflops = fl * N / (kern_ms * 1e-3) / 1e12
     workload = ((cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")

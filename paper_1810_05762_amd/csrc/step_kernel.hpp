@@ -86,7 +86,7 @@ struct LdsPlan {
   int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
   int pq, po, pnear, pbs, pcount, pbcnt, pblist;  // capsule-capsule contacts (only with pairs != 0)
   int wj, wc;                                     // kept impulses of joints and slots (only with warm != 0)
-  int nu, nred, nsum;                             // Newton solver: body vectors, reduction entries, totals
+  int nu, nred, nsum;                             // Newton solver: body vectors, reduction entries, partial sums
 };
 
 // pairs: 0 = no capsule-capsule contacts, else the interaction group size (1 = self-collision only)
@@ -132,7 +132,7 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.wc = o; o += warm ? S * 3 * E : 0;
   p.nu = o; o += newton ? B * kVS * E : 0;
   p.nred = o; o += newton ? 3 * (J + S) * E : 0;
-  p.nsum = o; o += newton ? 3 * E : 0;
+  p.nsum = o; o += newton ? 3 * 8 * E : 0;
   p.total = o;
   return p;
 }
@@ -813,7 +813,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     bool has_contact = false;  // this thread owns an active contact this substep
     int tid = tid_o, e = e_o, idx = idx_o;
     float h = h_o;
-    if constexpr (PC != 0 || NT > 512) {
+    if constexpr (PC != 0 || NT > 512 || NS != 0) {
       asm volatile("" : "+v"(tid), "+v"(e), "+v"(idx));
       asm volatile("" : "+s"(h));
     }
@@ -1640,11 +1640,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       // which wavefront ran first.
       float* LU = lds + P.nu;        // [B][kVS][E]: M^-1 J^T x (plus v* when asked for)
       float* Lred = lds + P.nred;    // [3][J + S][E]: partial sums of the blocks
-      float* Lsum = lds + P.nsum;    // [3][E]: their totals
+      float* Lsum = lds + P.nsum;    // [3][8][E]: sums over an eighth of the blocks each
       const int nblk = J + S;
       const float p_reg = M.newton_reg;
       const int n_kry = M.krylov;
       constexpr float kFrictionEps = 1e-3f;   // m/s
+      constexpr int kRedParts = 4;            // (J + S <= 64 blocks: at most sixteen per part)
       const bool jrole = joint_wave;
       if (jrole) build_joint_side(); else build_contact();
       for (int i = tid; i < 3 * nblk * E; i += kThreads) Lred[i] = 0.0f;   // inactive slots contribute nothing
@@ -1700,20 +1701,29 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       };
       // every body: the plain sum of its blocks' contributions (in static order), on top of the
       // velocities the solve started from when `with_base`
+      // (two threads per body, linear and angular half: the host only picks launch shapes where
+      //  2 B E threads exist; all reads are issued before the first use)
       auto gather_sum = [&](bool with_base, float* dst) {
         if (!g_on) return;
-        auto part = [&](int c0, int nc) {
-          for (int c = c0; c < c0 + nc; ++c) {
-            float acc = 0.0f;
+        const int ho = 3 * g_half * E;
+        float val[NJ + 3][3], base[3];
 #pragma unroll
-            for (int k = 0; k < NJ; ++k) acc += gat_w[k] * Loutj[gat_off[k] + c * E];
+        for (int c = 0; c < 3; ++c) base[c] = with_base ? Lvel[(g_b * kVS + c) * E + e + ho] : 0.0f;
 #pragma unroll
-            for (int k = 0; k < 3; ++k) acc += gat_w[NJ + k] * Loutc[gat_slot[k] + c * E];
-            const float base = with_base ? Lvel[(g_b * kVS + c) * E + e] : 0.0f;
-            dst[(g_b * kVS + c) * E + e] = base + acc;
-          }
-        };
-        if (g_split) part(3 * g_half, 3); else part(0, 6);
+        for (int k = 0; k < NJ; ++k)
+#pragma unroll
+          for (int c = 0; c < 3; ++c) val[k][c] = Loutj[gat_off[k] + ho + c * E];
+#pragma unroll
+        for (int k = 0; k < 3; ++k)
+#pragma unroll
+          for (int c = 0; c < 3; ++c) val[NJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+          float acc = 0.0f;
+#pragma unroll
+          for (int k = 0; k < NJ + 3; ++k) acc += gat_w[k] * val[k][c];
+          dst[(g_b * kVS + c) * E + e + ho] = base[c] + acc;
+        }
       };
       // y = J (body vectors in src) for the lane's rows
       auto rows_of = [&](const float* src, float* y) {
@@ -1737,23 +1747,39 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         }
       };
       // totals over the rows of the lane's env of up to three products
+      // (indices of the adding threads, worked out once)
+      const bool red_on = tid < 3 * kRedParts * E;
+      const int red_q = tid / (kRedParts * E), red_r = tid - red_q * (kRedParts * E), red_part = red_r / E, red_e = red_r - red_part * E;
+      const int red_per = (nblk + kRedParts - 1) / kRedParts;
+      const int red_src = (red_q * nblk + red_part * red_per) * E + red_e, red_n = min(red_per, nblk - red_part * red_per);
+      const int red_dst = (red_q * kRedParts + red_part) * E + red_e;
       auto reduce3 = [&](float pa, float pb, float pc, float& ta, float& tb, float& tc) {
         if (writes_partial) {
           Lred[(0 * nblk + my_blk) * E + my_e] = pa; Lred[(1 * nblk + my_blk) * E + my_e] = pb; Lred[(2 * nblk + my_blk) * E + my_e] = pc;
         }
         __syncthreads();
-        if (tid < 3 * E) {
-          const int qd = tid / E, ee = tid - qd * E;
+        // four threads per product and env add up a quarter of the blocks each (reads issued together)
+        if (red_on) {
+          float vals[16];
+#pragma unroll
+          for (int k = 0; k < 16; ++k) vals[k] = k < red_n ? Lred[red_src + k * E] : 0.0f;
           float sm = 0.0f;
-          for (int k = 0; k < nblk; ++k) sm += Lred[(qd * nblk + k) * E + ee];
-          Lsum[qd * E + ee] = sm;
+#pragma unroll
+          for (int k = 0; k < 16; ++k) sm += vals[k];
+          Lsum[red_dst] = sm;
         }
         __syncthreads();
-        ta = Lsum[0 * E + my_e]; tb = Lsum[1 * E + my_e]; tc = Lsum[2 * E + my_e];
+        // every lane adds the four partial sums of its env, in order
+        float vals[3 * kRedParts];
+#pragma unroll
+        for (int k = 0; k < 3 * kRedParts; ++k) vals[k] = Lsum[k * E + my_e];
+        ta = (vals[0] + vals[1]) + (vals[2] + vals[3]);
+        tb = (vals[4] + vals[5]) + (vals[6] + vals[7]);
+        tc = (vals[8] + vals[9]) + (vals[10] + vals[11]);
       };
       float lam[6] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
       for (int it = 0; it < a.iterations; ++it) {
-        float sres[6], known[6], cp[6], pd[6], tmp[6];
+        float sres[6], known[6], cp[6], ipd[6], tmp[6];
         int on = 0;
         // residual of the current iterate
         scatter(lam);
@@ -1778,9 +1804,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
             cp[1] = cp[2] = sqrtf(sres[1] * sres[1] + sres[2] * sres[2] + kFrictionEps * kFrictionEps) / rad;
           } else { known[1] = -lam[1]; known[2] = -lam[2]; }
         }
+        // (ipd: inverse of the preconditioner's diagonal on the rows of the "s" branch, 0 elsewhere)
         for (int k = 0; k < 6; ++k) {
-          pd[k] = Dg[k] * (1.0f + p_reg) + cp[k];
-          if (!(pd[k] > 0.0f) || k >= nr || !active) on &= ~(1 << k);
+          const float pdk = Dg[k] * (1.0f + p_reg) + cp[k];
+          if (!(pdk > 0.0f) || k >= nr || !active) on &= ~(1 << k);
+          ipd[k] = ((on >> k) & 1) ? 1.0f / pdk : 0.0f;
         }
         // right-hand side of the rows on the "s" branch: -s - c lambda - A known
         scatter(known);
@@ -1792,7 +1820,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         for (int k = 0; k < 6; ++k) {
           const bool o = (on >> k) & 1;
           const float rhs = o ? -sres[k] - cp[k] * lam[k] - tmp[k] : 0.0f;
-          x[k] = 0.0f; z[k] = o ? rhs / pd[k] : 0.0f; pv[k] = z[k];
+          x[k] = 0.0f; z[k] = rhs * ipd[k]; pv[k] = z[k];
         }
         // (A + reg D + c) z on the rows of the "s" branch
         auto apply_hat = [&](const float* xv, float* y) {
@@ -1807,7 +1835,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         float gamma, den, unused;
         {
           float pa = 0.0f, pb = 0.0f;
-          for (int k = 0; k < 6; ++k) { q[k] = az[k]; pa += z[k] * az[k]; if ((on >> k) & 1) pb += az[k] * az[k] / pd[k]; }
+          for (int k = 0; k < 6; ++k) { q[k] = az[k]; pa += z[k] * az[k]; pb += az[k] * az[k] * ipd[k]; }
           reduce3(pa, pb, 0.0f, gamma, den, unused);
         }
         const float gamma0 = gamma;
@@ -1815,14 +1843,13 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         for (int kk = 0; kk < n_kry; ++kk) {
           done = done || !(den > 0.0f) || !(gamma > 1e-12f * gamma0);
           const float alpha = done ? 0.0f : gamma / den;
-          for (int k = 0; k < 6; ++k)
-            if ((on >> k) & 1) { x[k] += alpha * pv[k]; z[k] -= alpha * q[k] / pd[k]; }
+          for (int k = 0; k < 6; ++k) { x[k] += alpha * pv[k]; z[k] -= alpha * q[k] * ipd[k]; }   // (all zero off the "s" branch)
           if (kk == n_kry - 1) break;       // (the last iteration's operator product would not be used)
           apply_hat(z, az);
           float pa = 0.0f, pb = 0.0f, pc = 0.0f, ta, tb, tc;
           for (int k = 0; k < 6; ++k) {
             pa += z[k] * az[k];
-            if ((on >> k) & 1) { pb += az[k] * az[k] / pd[k]; pc += az[k] * q[k] / pd[k]; }
+            pb += az[k] * az[k] * ipd[k]; pc += az[k] * q[k] * ipd[k];
           }
           reduce3(pa, pb, pc, ta, tb, tc);
           if (!done) {
