@@ -282,10 +282,16 @@ int sim_get_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* s
 int sim_generate_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
 /* Capsule-capsule contacts of the last substep of the last sim_step (recording enabled): up to
  * `cap` records into recs_dev, workgroup by workgroup, each workgroup's in a fixed order; the total
- * number goes to count_dev[0] and count_dev[1] receives the number of contacts that were dropped
- * since sim_create because a workgroup found more than SIM_PAIR_CAP in one substep (results are
- * not to be trusted once this is non-zero).  SIM_ERR_ARG if the description had neither collide
- * pairs nor groups. */
+ * number goes to count_dev[0] and count_dev[1] receives the number of contacts that were left out
+ * since sim_create because a workgroup found more than SIM_PAIR_CAP in one substep.  What stays
+ * then is fixed: the SIM_PAIR_CAP contacts of the workgroup's agents with the smallest gap d
+ * (single precision; equal gaps: the smaller key (agent of A within the workgroup, agent of B,
+ * body_a, body_b)), whatever order they were found in, so a run is reproducible and equals a
+ * reference that applies the same bound to blocks of envs_per_block agents; the contacts left
+ * out are the most distant ones, which speculative contacts (Section 3.1) mostly keep idle.
+ * (This holds up to the number of contacts a workgroup can list at all, at least 256; past that,
+ * the ones listed first take part in the choice.)  SIM_ERR_ARG if the description had neither
+ * collide pairs nor groups. */
 int sim_get_pair_contacts(sim_t* sim, sim_pair_contact_rec_t* recs_dev, int32_t cap, int32_t* count_dev /*[2]*/,
                           void* stream);
 /* Synchronises `stream` and scans the state: SIM_ERR_NONFINITE if any value is NaN/Inf. */

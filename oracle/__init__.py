@@ -57,7 +57,8 @@ class Contact(C.Structure):
 PAIR_CONTACT_DTYPE = np.dtype([("env_a", np.int32), ("body_a", np.int32), ("env_b", np.int32),
                                ("body_b", np.int32), ("s", np.float32), ("t", np.float32),
                                ("d", np.float64), ("n", np.float64, 3), ("ra", np.float64, 3),
-                               ("rb", np.float64, 3), ("w", np.float64)])
+                               ("rb", np.float64, 3), ("w", np.float64), ("gap32", np.float32),
+                               ("pad", np.int32)])
 CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.int32), ("pad", np.int32),
                           ("d", np.float64), ("n", np.float64, 3), ("rc", np.float64, 3),
                           ("w", np.float64)])
@@ -84,6 +85,8 @@ def _load():
     L.oracle_get_threads.argtypes = [vp]
     L.oracle_set_warm_start.argtypes = [vp, C.c_double]
     L.oracle_set_solver.argtypes = [vp, C.c_int32, C.c_int32, C.c_double]
+    L.oracle_set_pair_cap.argtypes = [vp, C.c_int32, C.c_int32]
+    L.oracle_set_pair_cap.restype = C.c_int64
     L.oracle_get_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm_flags.argtypes = [vp, ip, ip]
@@ -212,6 +215,12 @@ class OracleSim:
         """kind 0: block projected Jacobi; 1: non-smooth Newton with `krylov_iters` conjugate-residual
         iterations per Newton iteration (the `iterations` of step() then count Newton iterations)."""
         self._L.oracle_set_solver(self._h, int(kind), int(krylov_iters), float(reg))
+
+    def set_pair_cap(self, cap, envs_per_unit):
+        """Bounded contact store: every block of `envs_per_unit` consecutive agents keeps at most
+        `cap` capsule-capsule contacts per substep, those with the smallest (single-precision gap,
+        key).  cap <= 0 lifts the bound.  Returns the number removed since the last call."""
+        return int(self._L.oracle_set_pair_cap(self._h, int(cap), int(envs_per_unit)))
 
     def set_warm(self, lam_j, lam_s):
         lj = np.ascontiguousarray(lam_j, np.float64).reshape(self.N, self.J, 6)

@@ -164,6 +164,8 @@ struct oracle_sim {
   env_state* env;
   oracle_pair_contact* pcon; /* [groups][MAXPC] capsule-capsule contacts of the last substep */
   int* pcon_n;               /* [groups] */
+  int pair_cap, pair_unit;   /* bounded contact store: at most pair_cap per pair_unit agents (0: none) */
+  long long pair_removed;
   int trace_env, trace_cap, trace_n;
   oracle_sweep_trace* trace;
 };
@@ -604,6 +606,8 @@ static int pair_contact(const model* m, const env_state* A, int ea, int ba, cons
   float rr = (float)m->radius[ba] + (float)m->radius[bb];
   float lim = rr + (float)m->margin;
   if (!(d2 < lim * lim)) return 0;
+  c->gap32 = (sqrtf(d2) - (float)m->radius[ba]) - (float)m->radius[bb];
+  c->pad_ = 0;
   v3 RA[3], RB[3];
   qmat(A->q[ba], RA); qmat(Bv->q[bb], RB);
   v3 ha = vscale(RA[m->axis[ba]], m->half_len[ba]), hb = vscale(RB[m->axis[bb]], m->half_len[bb]);
@@ -1552,37 +1556,104 @@ static int group_span(const oracle_sim* o, int gi, int* e0) {
   return *e0 + o->m.G <= o->N ? o->m.G : o->N - *e0;
 }
 
+/* ---- bounded contact store: the `cap` contacts with the smallest (gap32, key) of a block stay */
+typedef struct { uint64_t word; int group, index; } cap_entry;
+static int cap_entry_cmp(const void* a, const void* b) {
+  uint64_t x = ((const cap_entry*)a)->word, y = ((const cap_entry*)b)->word;
+  return x < y ? -1 : (x > y ? 1 : 0);
+}
+static uint64_t cap_word(const oracle_pair_contact* c, int unit_e0) {
+  uint32_t gb;
+  memcpy(&gb, &c->gap32, 4);
+  uint32_t ordered = (gb & 0x80000000u) ? ~gb : (gb | 0x80000000u); /* unsigned order = order of the floats */
+  uint32_t key = ((uint32_t)(c->env_a - unit_e0) << 20) | ((uint32_t)(c->env_b - unit_e0) << 8) |
+                 ((uint32_t)c->body_a << 4) | (uint32_t)c->body_b;
+  return ((uint64_t)ordered << 32) | key;
+}
+/* groups [g0, g1) form one block; their lists keep their order, minus what does not fit */
+static int trim_pair_contacts(oracle_sim* o, int g0, int g1) {
+  int total = 0;
+  for (int gi = g0; gi < g1; ++gi) total += o->pcon_n[gi];
+  if (total <= o->pair_cap) return 0;
+  cap_entry* ent = (cap_entry*)malloc(sizeof(cap_entry) * (size_t)total);
+  int n = 0, unit_e0 = g0 * o->m.G;
+  for (int gi = g0; gi < g1; ++gi)
+    for (int k = 0; k < o->pcon_n[gi]; ++k, ++n) {
+      ent[n].word = cap_word(&o->pcon[(size_t)gi * MAXPC + k], unit_e0); ent[n].group = gi; ent[n].index = k;
+    }
+  qsort(ent, (size_t)total, sizeof(cap_entry), cap_entry_cmp);
+  uint64_t last_kept = ent[o->pair_cap - 1].word;
+  free(ent);
+  for (int gi = g0; gi < g1; ++gi) {
+    oracle_pair_contact* list = o->pcon + (size_t)gi * MAXPC;
+    int kept = 0;
+    for (int k = 0; k < o->pcon_n[gi]; ++k)
+      if (cap_word(&list[k], unit_e0) <= last_kept) list[kept++] = list[k];
+    o->pcon_n[gi] = kept;
+  }
+  return total - o->pair_cap;
+}
+static int groups_per_unit(const oracle_sim* o) {
+  int groups = (o->N + o->m.G - 1) / o->m.G;
+  if (o->pair_cap <= 0) return 1;
+  int gpu = o->pair_unit / o->m.G;
+  return gpu < 1 ? 1 : (gpu > groups ? groups : gpu);
+}
+/* one substep of the groups [g0, g1): with a bounded store all of them find their contacts
+ * first, the block is trimmed, then each group goes on */
+static long long substep_groups(oracle_sim* o, int g0, int g1, double h, int iterations, int phases) {
+  long long removed = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    int ph = phases & (pass == 0 ? ORACLE_PH_CONTACTS : ~ORACLE_PH_CONTACTS);
+    if (o->pair_cap <= 0) ph = pass == 0 ? phases : 0;   /* no bound: each group in one go */
+    if (ph)
+      for (int gi = g0; gi < g1; ++gi) {
+        int e0, G = group_span(o, gi, &e0);
+        int tr = (o->trace_env >= e0 && o->trace_env < e0 + G);
+        substep(&o->m, &o->env[e0], e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations, ph,
+                tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
+      }
+    if (pass == 0 && (phases & ORACLE_PH_CONTACTS) && o->pair_cap > 0) removed += trim_pair_contacts(o, g0, g1);
+  }
+  return removed;
+}
+
 void oracle_substep_phases(oracle_sim* o, const double* actions, double h, int32_t iterations, int32_t phases) {
   load_actions(o, actions);
-  int groups = (o->N + o->m.G - 1) / o->m.G;
-  for (int gi = 0; gi < groups; ++gi) {
-    int e0, G = group_span(o, gi, &e0);
-    int tr = (o->trace_env >= e0 && o->trace_env < e0 + G);
-    substep(&o->m, &o->env[e0], e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations, phases,
-            tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
-  }
+  int groups = (o->N + o->m.G - 1) / o->m.G, gpu = groups_per_unit(o);
+  for (int g0 = 0; g0 < groups; g0 += gpu)
+    o->pair_removed += substep_groups(o, g0, g0 + gpu < groups ? g0 + gpu : groups, h, iterations, phases);
 }
 
 void oracle_step(oracle_sim* o, const double* actions, double dt, int32_t substeps, int32_t iterations) {
   load_actions(o, actions);
   double h = dt / substeps;
-  int groups = (o->N + o->m.G - 1) / o->m.G;
+  int groups = (o->N + o->m.G - 1) / o->m.G, gpu = groups_per_unit(o);
+  int units = (groups + gpu - 1) / gpu;
+  long long removed = 0;
 #ifdef _OPENMP
-#pragma omp parallel for schedule(static) num_threads(o->threads)
+#pragma omp parallel for schedule(static) num_threads(o->threads) reduction(+ : removed)
 #endif
-  for (int gi = 0; gi < groups; ++gi) {
-    int e0, G = group_span(o, gi, &e0);
-    int tr = (o->trace_env >= e0 && o->trace_env < e0 + G);
+  for (int u = 0; u < units; ++u) {
+    int g0 = u * gpu, g1 = g0 + gpu < groups ? g0 + gpu : groups;
+    int e_lo = g0 * o->m.G, e_hi = g1 * o->m.G < o->N ? g1 * o->m.G : o->N;
     if (o->task.enabled)
-      for (int e = e0; e < e0 + G; ++e) task_before_step(&o->task, &o->env[e], e);
-    for (int s = 0; s < substeps; ++s)
-      substep(&o->m, &o->env[e0], e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations,
-              ORACLE_PH_ALL, tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
-    for (int e = e0; e < e0 + G; ++e) {
+      for (int e = e_lo; e < e_hi; ++e) task_before_step(&o->task, &o->env[e], e);
+    for (int s = 0; s < substeps; ++s) removed += substep_groups(o, g0, g1, h, iterations, ORACLE_PH_ALL);
+    for (int e = e_lo; e < e_hi; ++e) {
       o->env[e].steps++;
       if (o->task.enabled) task_after_step(&o->task, &o->m, &o->env[e], e);
     }
   }
+  o->pair_removed += removed;
+}
+
+int64_t oracle_set_pair_cap(oracle_sim* o, int32_t cap, int32_t envs_per_unit) {
+  long long r = o->pair_removed;
+  o->pair_removed = 0;
+  o->pair_cap = cap > 0 ? cap : 0;
+  o->pair_unit = envs_per_unit > 0 ? envs_per_unit : o->m.G;
+  return r;
 }
 
 int32_t oracle_get_pair_contacts(const oracle_sim* o, oracle_pair_contact* out, int32_t cap) {

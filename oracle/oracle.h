@@ -104,6 +104,8 @@ typedef struct oracle_pair_contact {
   float s, t;
   double d, n[3], ra[3], rb[3];
   double w;       /* mass-splitting share on both bodies, as for terrain contacts */
+  float gap32;    /* the surface distance as the single-precision decision sees it: (sqrt(d2) - r_a) - r_b */
+  int32_t pad_;
 } oracle_pair_contact;
 
 /* per-sweep diagnostics of one env (used by the invariant pins) */
@@ -188,6 +190,13 @@ void oracle_generate_contacts(oracle_sim*, int32_t brute, oracle_contact* recs);
 int32_t oracle_get_pair_contacts(const oracle_sim*, oracle_pair_contact* out, int32_t cap);
 /* the same from the current state, without stepping */
 int32_t oracle_generate_pair_contacts(oracle_sim*, oracle_pair_contact* out, int32_t cap);
+/* A bounded contact store (Section 3.1 fixes no size; a device that keeps a block of agents'
+ * contacts in on-chip memory has one): consecutive blocks of `envs_per_unit` agents (a multiple of
+ * the group size) keep at most `cap` capsule-capsule contacts per substep, those with the smallest
+ * (gap32, key) in that order, key = (agent of A in the block << 20) | (agent of B in the block << 8)
+ * | (body of A << 4) | body of B.  cap <= 0: no bound (the default).  Returns the number of
+ * contacts removed since the last call. */
+int64_t oracle_set_pair_cap(oracle_sim*, int32_t cap, int32_t envs_per_unit);
 /* single-precision closest points of two segments P0P1, Q0Q1 (fixed operation order): writes the
  * parameters and returns the squared distance; exposed so it can be pinned */
 float oracle_segment_segment_f32(const float* P0, const float* P1, const float* Q0, const float* Q1,

@@ -81,10 +81,12 @@ struct StepArgs {
 // Rows (E consecutive floats) per item of the velocity, inverse-inertia and copy arrays.  Odd
 // counts, so that neighbouring items start in different LDS banks when E is 16.
 constexpr int kVS = 7, kCS = 7, kJS = 13;
+constexpr int kPairHitMin = 256;   // (gap, key) words a workgroup keeps at least
 
 struct LdsPlan {
   int pos, vel, iw, nb, tq, push, outj, outc, tjs, rec, list, surv, lam, u, obs, lim, count, patch, mip, porg, org, tslot, tbody, tin, tjoint, total;
   int pq, po, pnear, pbs, pcount, pbcnt, pblist;  // capsule-capsule contacts (only with pairs != 0)
+  int phit, hit_cap;                              // their (gap, key) words: offset (64-bit aligned) and capacity
   int wj, wc;                                     // kept impulses of joints and slots (only with warm != 0)
   int nu, nred, nsum;                             // Newton solver: body vectors, reduction entries, partial sums
 };
@@ -128,6 +130,16 @@ __host__ __device__ inline LdsPlan make_plan(int B, int J, int S, int D, int F, 
   p.pcount = o; o += pairs ? 4 : 0;
   p.pbcnt = o; o += pairs ? B * E : 0;                  // per body: how many of them touch it
   p.pblist = o; o += pairs ? (B * E * 6 + 3) / 4 : 0;  // per body: up to six of them, one byte each
+  // one 64-bit (gap, key) word per capsule-capsule contact found, for the choice of those that stay
+  // when a workgroup finds more than it holds: in the space of the terrain search's candidate list
+  // (idle by then) where that holds kPairHitMin words, else in a region of their own
+  p.hit_cap = ((J * kJS + S * kCS) * E - 5 * S * E - 2) / 2;
+  p.phit = p.outj + ((5 * S * E + 1) & ~1);
+  if (pairs && p.hit_cap < kPairHitMin) {
+    o += o & 1;
+    p.phit = o; o += 2 * kPairHitMin;
+    p.hit_cap = kPairHitMin;
+  }
   p.wj = o; o += warm ? J * 6 * E : 0;
   p.wc = o; o += warm ? S * 3 * E : 0;
   p.nu = o; o += newton ? B * kVS * E : 0;
@@ -1196,37 +1208,49 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           __syncthreads();
         }
         float* Ltmp = Lpo;   // unsorted queue; the copies are not in use yet
-        auto test_pair = [&](int ea, int ba, int eb, int bb, unsigned key, bool valid) {
-          bool hit = false;
-          float sp = 0.0f, tp = 0.0f, gap = 0.0f;
-          if (valid) {
-            float xa[3], xb[3], off[3];
-            for (int c = 0; c < 3; ++c) {
-              off[c] = Lorg[c * E + eb] - Lorg[c * E + ea];
-              xa[c] = Lpos[(ba * 7 + c) * E + ea];
-              xb[c] = Lpos[(bb * 7 + c) * E + eb];
-            }
-            const float radA = Ltbody[4 * ba], hlA = Ltbody[4 * ba + 1], radB = Ltbody[4 * bb], hlB = Ltbody[4 * bb + 1];
-            float dd = 0.0f;
-            for (int c = 0; c < 3; ++c) { const float dc = (xb[c] + off[c]) - xa[c]; dd += dc * dc; }
-            const float reach = (radA + hlA) + (radB + hlB) + p_margin + 2e-3f;
-            if (dd <= reach * reach) {
-              float qa[4], qb[4];
-              for (int c = 0; c < 4; ++c) { qa[c] = Lpos[(ba * 7 + 3 + c) * E + ea]; qb[c] = Lpos[(bb * 7 + 3 + c) * E + eb]; }
-              f3 p0, p1, q0, q1;
-              body_ends(xa, qa, hlA, __float_as_int(Ltbody[4 * ba + 2]), p0, p1);
-              body_ends(xb, qb, hlB, __float_as_int(Ltbody[4 * bb + 2]), q0, q1);
-              hit = pair_in_contact(p0, p1, q0, q1, off, radA, radB, p_margin, sp, tp, gap);
-            }
+        // Every hit also leaves (gap, key) as one 64-bit word whose unsigned order is that of the
+        // pair: when a workgroup finds more than it can hold, the kPairCap contacts with the smallest
+        // gap stay (ties: smaller key), whichever wavefront found what first.  Where they live:
+        // see make_plan (cleared again below, since the sweeps' copies share the space).
+        unsigned long long* Lhit = reinterpret_cast<unsigned long long*>(lds + P.phit);
+        const int hit_cap = P.hit_cap;
+        // the segment-segment test of one candidate pair from the poses of phase A
+        auto eval_pair = [&](int ea, int ba, int eb, int bb, float& sp, float& tp, float& gap) -> bool {
+          float xa[3], xb[3], off[3];
+          for (int c = 0; c < 3; ++c) {
+            off[c] = Lorg[c * E + eb] - Lorg[c * E + ea];
+            xa[c] = Lpos[(ba * 7 + c) * E + ea];
+            xb[c] = Lpos[(bb * 7 + c) * E + eb];
           }
+          const float radA = Ltbody[4 * ba], hlA = Ltbody[4 * ba + 1], radB = Ltbody[4 * bb], hlB = Ltbody[4 * bb + 1];
+          float dd = 0.0f;
+          for (int c = 0; c < 3; ++c) { const float dc = (xb[c] + off[c]) - xa[c]; dd += dc * dc; }
+          const float reach = (radA + hlA) + (radB + hlB) + p_margin + 2e-3f;
+          if (!(dd <= reach * reach)) return false;
+          float qa[4], qb[4];
+          for (int c = 0; c < 4; ++c) { qa[c] = Lpos[(ba * 7 + 3 + c) * E + ea]; qb[c] = Lpos[(bb * 7 + 3 + c) * E + eb]; }
+          f3 p0, p1, q0, q1;
+          body_ends(xa, qa, hlA, __float_as_int(Ltbody[4 * ba + 2]), p0, p1);
+          body_ends(xb, qb, hlB, __float_as_int(Ltbody[4 * bb + 2]), q0, q1);
+          return pair_in_contact(p0, p1, q0, q1, off, radA, radB, p_margin, sp, tp, gap);
+        };
+        auto store_hit = [&](int pos, int ea, int ba, int eb, int bb, unsigned key, float sp, float tp, float gap) {
+          Ltmp[pos * kPairWords + 0] = __uint_as_float(key);
+          Ltmp[pos * kPairWords + 1] = __int_as_float((ba * E + ea) | ((bb * E + eb) << 16));
+          Ltmp[pos * kPairWords + 2] = sp;
+          Ltmp[pos * kPairWords + 3] = tp;
+          Ltmp[pos * kPairWords + 4] = block_weight(p_margin, gap, 1.0f);
+          Ltmp[pos * kPairWords + 5] = gap;
+        };
+        auto test_pair = [&](int ea, int ba, int eb, int bb, unsigned key, bool valid) {
+          float sp = 0.0f, tp = 0.0f, gap = 0.0f;
+          const bool hit = valid && eval_pair(ea, ba, eb, bb, sp, tp, gap);
           const int pos = wave_alloc<1>(hit ? 1 : 0, &Lpcount[0]);
-          if (hit && pos < kPairCap) {
-            Ltmp[pos * kPairWords + 0] = __uint_as_float(key);
-            Ltmp[pos * kPairWords + 1] = __int_as_float((ba * E + ea) | ((bb * E + eb) << 16));
-            Ltmp[pos * kPairWords + 2] = sp;
-            Ltmp[pos * kPairWords + 3] = tp;
-            Ltmp[pos * kPairWords + 4] = block_weight(p_margin, gap, 1.0f);
-            Ltmp[pos * kPairWords + 5] = gap;
+          if (hit && pos < kPairCap) store_hit(pos, ea, ba, eb, bb, key, sp, tp, gap);
+          if (hit && pos < hit_cap) {
+            const unsigned gb = __float_as_uint(gap);
+            const unsigned ordered = (gb & 0x80000000u) ? ~gb : (gb | 0x80000000u);   // unsigned order = float order
+            Lhit[pos] = ((unsigned long long)ordered << 32) | key;
           }
         };
         // Stage 1: bounding spheres of the two capsules only; what passes is listed as a packed word
@@ -1282,6 +1306,25 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         __syncthreads();
         const int n_raw = Lpcount[0];
         n_pc = n_raw < kPairCap ? n_raw : kPairCap;
+        const int n_hit = n_raw < hit_cap ? n_raw : hit_cap;
+        if (n_raw > kPairCap) {
+          // more than the workgroup holds: the kPairCap smallest (gap, key) words stay; each is
+          // found by its rank among all words and its contact worked out again from its key
+          for (int i = tid; i < n_hit; i += kThreads) {
+            const unsigned long long wi = Lhit[i];
+            int rank = 0;
+            for (int k = 0; k < n_hit; ++k) rank += Lhit[k] < wi ? 1 : 0;
+            if (rank < kPairCap) {
+              const unsigned key = (unsigned)wi;
+              const int ea = (int)(key >> 20), eb = (int)((key >> 8) & 0xfffu), ba = (int)((key >> 4) & 15u), bb = (int)(key & 15u);
+              float sp = 0.0f, tp = 0.0f, gap = 0.0f;
+              eval_pair(ea, ba, eb, bb, sp, tp, gap);
+              store_hit(rank, ea, ba, eb, bb, key, sp, tp, gap);
+            }
+          }
+          __syncthreads();
+        }
+        for (int i = tid; i < 2 * n_hit; i += kThreads) reinterpret_cast<float*>(Lhit)[i] = 0.0f;   // finite numbers for the sweeps' copies
         if (tid < n_pc) {
           const unsigned key = __float_as_uint(Ltmp[tid * kPairWords]);
           int rank = 0;

@@ -220,22 +220,39 @@ def test_parallel_and_degenerate_capsule_pairs():
     sim.check(); sim.close()
 
 
-def test_more_contacts_than_a_workgroup_holds_are_counted_as_dropped():
-    """Sixteen overlapping spheres in one env: 120 touching pairs against room for 96."""
+@pytest.mark.parametrize("E", [1, 2])
+def test_more_contacts_than_a_workgroup_holds_keeps_the_closest(E):
+    """Sixteen overlapping spheres per env: 120 touching pairs each against room for 96 per
+    workgroup (of one env, and of two: 240 against 96, the key's env fields in play).  The 96 with
+    the smallest (single-precision gap, key) stay, the same ones as in the oracle with the same
+    bound, whichever wavefront found which pair first; the step then agrees to the one-step bar."""
     P = _P()
     rng = np.random.default_rng(2)
     rob = scenes.make_loose([(0.1, 0.0, 0, (3.0 * k, 0.0, 5.0), 1.0) for k in range(16)])
-    sc = scenes.make_scene(rob, scenes.make_plane(), 3, params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1))
+    n = 3 * E
+    sc = scenes.make_scene(rob, scenes.make_plane(), n, params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1))
     assert len(rob.collide_pairs) == 120
-    st = np.repeat(scenes.rest_state(rob), 3, axis=0)
-    st[:, :, 0:3] = np.array([0.0, 0.0, 5.0]) + rng.normal(size=(3, 16, 3)) * 0.02
-    sim = P.Sim(sc)
-    assert sim.launch_info()["envs_per_block"] == 1
-    sim.set_state(st)
+    st = np.repeat(scenes.rest_state(rob), n, axis=0)
+    st[:, :, 0:3] = np.array([0.0, 0.0, 5.0]) + rng.normal(size=(n, 16, 3)) * 0.02
+    st = st.astype(np.float32).astype(np.float64)
+    cap = P.binding.SIM_PAIR_CAP
+    sim, ref = P.Sim(sc), oracle.OracleSim(sc, threads=1)
+    sim.set_envs_per_block(E)
+    assert sim.launch_info()["envs_per_block"] == E
+    ref.set_pair_cap(cap, E)
+    sim.set_state(st); ref.set_state(st)
     sim.record_contacts(True)
-    sim.step(None, 1.0 / 240.0, 1, 4)
-    pg, dropped = sim.get_pair_contacts()
-    assert len(pg) == 3 * P.binding.SIM_PAIR_CAP and dropped == 3 * (120 - P.binding.SIM_PAIR_CAP)
+    h = float(np.float32(1.0 / 240.0))
+    for rep in range(2):   # twice: the second substep starts from what the first left in the workgroup's memory
+        sim.step(None, h, 1, 4); ref.step(None, h, 1, 4)
+        pg, dropped = sim.get_pair_contacts()
+        po = ref.get_pair_contacts()
+        assert len(pg) == 3 * cap and dropped == (rep + 1) * 3 * (120 * E - cap)
+        assert_same_pair_sets(pg, po)
+        e = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+        assert e.max() <= TOL_1, e.max()
+        ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))
+    assert ref.set_pair_cap(0, 1) == 2 * 3 * (120 * E - cap)
     sim.check(); sim.close()
 
 

@@ -200,3 +200,73 @@ def test_sphere_resting_on_a_grounded_sphere_stays_put():
     assert s[0, 0, 2] == pytest.approx(r, abs=2e-3)
     assert s[0, 1, 2] - s[0, 0, 2] == pytest.approx(2 * r, abs=2e-3)
     assert np.abs(s[0, :, 0:2]).max() < 1e-6
+
+
+def _sphere_cluster(n_envs, seed):
+    rob = scenes.make_loose([(0.1, 0.0, 0, (3.0 * k, 0.0, 5.0), 1.0) for k in range(16)])
+    sc = scenes.make_scene(rob, scenes.make_plane(), n_envs,
+                           params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1))
+    rng = np.random.default_rng(seed)
+    st = np.repeat(scenes.rest_state(rob), n_envs, axis=0)
+    st[:, :, 0:3] = np.array([0.0, 0.0, 5.0]) + rng.normal(size=(n_envs, 16, 3)) * 0.02
+    return rob, sc, st.astype(np.float32).astype(np.float64)
+
+
+def test_bounded_contact_store_keeps_the_closest_contacts_of_a_block():
+    """Sixteen overlapping spheres per agent, 120 touching pairs each.  With room for 50 contacts
+    per block of two agents, each block keeps exactly the 50 with the smallest centre distance
+    (worked out here from the positions in double precision; the distances on either side of the
+    cut are far enough apart for single precision to order them the same way), in the order the unbounded list has them; a
+    bound that is not reached changes nothing."""
+    rob, sc, st = _sphere_cluster(4, 5)
+    h = 1.0 / 240.0
+    free = oracle.OracleSim(sc, threads=1)
+    free.set_state(st); free.step(None, h, 1, 3)
+    all_c = free.get_pair_contacts()
+    assert len(all_c) == 4 * 120
+    # closed form for spheres: gap = |x_a - x_b| - 2 r
+    x = st[:, :, 0:3]
+    gap = np.linalg.norm(x[all_c["env_a"], all_c["body_a"]] - x[all_c["env_b"], all_c["body_b"]], axis=1) - 0.2
+    np.testing.assert_allclose(all_c["d"], gap, atol=1e-12)
+    np.testing.assert_allclose(all_c["gap32"], gap, atol=1e-6)
+    keep = np.zeros(len(all_c), bool)
+    for blk in range(2):
+        idx = np.flatnonzero(all_c["env_a"] // 2 == blk)
+        srt = idx[np.argsort(gap[idx])]
+        assert gap[srt[50]] - gap[srt[49]] > 1e-6   # the cut falls where single precision orders as double does
+        keep[srt[:50]] = True
+    capped = oracle.OracleSim(sc, threads=1)
+    capped.set_pair_cap(50, 2)
+    capped.set_state(st); capped.step(None, h, 1, 3)
+    kept = capped.get_pair_contacts()
+    assert len(kept) == 100
+    for f in ("env_a", "body_a", "env_b", "body_b"):
+        assert np.array_equal(kept[f], all_c[f][keep]), f
+    assert capped.set_pair_cap(0, 1) == 4 * 120 - 100
+    assert np.abs(capped.get_state() - free.get_state()).max() > 1e-6   # fewer contacts, another step
+    # a bound that is not reached: bit for bit the unbounded step, also in several threads
+    roomy = oracle.OracleSim(sc, threads=4)
+    roomy.set_pair_cap(240, 2)
+    roomy.set_state(st); roomy.step(None, h, 1, 3)
+    assert np.array_equal(roomy.get_state(), free.get_state())
+    assert roomy.set_pair_cap(0, 1) == 0
+
+
+def test_bounded_contact_store_breaks_equal_gaps_by_the_smaller_key():
+    """Four spheres at the corners of a square of side 0.15 touch along the four sides with exactly
+    equal gaps (the diagonals, 0.212 apart against 0.2 + the 0.01 margin, do not): room for two keeps the two pairs with the
+    smallest (agent, agent, body, body) keys, (0,1) and (0,2)."""
+    rob = scenes.make_loose([(0.1, 0.0, 0, (3.0 * k, 0.0, 5.0), 1.0) for k in range(4)])
+    sc = scenes.make_scene(rob, scenes.make_plane(), 1,
+                           params=scenes.SimParams(gravity=(0.0, 0.0, 0.0), self_collide=1, contact_margin=0.01))
+    st = scenes.rest_state(rob)
+    st[0, :, 0:3] = np.array([[0.0, 0.0, 5.0], [0.15, 0.0, 5.0], [0.0, 0.15, 5.0], [0.15, 0.15, 5.0]])
+    ref = oracle.OracleSim(sc, threads=1)
+    ref.set_state(st)
+    c = ref.generate_pair_contacts()
+    assert sorted(zip(c["body_a"].tolist(), c["body_b"].tolist())) == [(0, 1), (0, 2), (1, 3), (2, 3)]
+    assert len(set(c["gap32"].tolist())) == 1
+    ref.set_pair_cap(2, 1)
+    ref.step(None, 1.0 / 240.0, 1, 2)
+    k = ref.get_pair_contacts()
+    assert list(zip(k["body_a"].tolist(), k["body_b"].tolist())) == [(0, 1), (0, 2)]
