@@ -119,16 +119,17 @@ typedef struct sim_desc {
    * are applied to the bodies before the first sweep.  What is kept survives from one sim_step
    * to the next and is cleared for an env by its reset and for all by sim_set_state.  About 0.8
    * halves the sweeps needed for the same penetration; with few sweeps values near 1 can build
-   * up without bound (the kept impulse integrates the position error).  Not available together
-   * with capsule-capsule collisions (SIM_ERR_ARG). */
+   * up without bound (the kept impulse integrates the position error).  Capsule-capsule contacts
+   * (whose identity changes from substep to substep) keep nothing: with collisions switched on
+   * they start every substep from zero next to warm joints and terrain slots. */
   double warm_start;
   /* Solver of the rows (Section 3.1).  0: block projected Jacobi with mass splitting; the
    * `iterations` of sim_step are sweeps per substep.  1: the paper's own choice, a non-smooth
    * Newton method (minimum map for one-sided rows, smooth isotropic Coulomb friction) whose every
    * iteration is solved by krylov_iterations preconditioned conjugate-residual iterations on
    * J M^-1 J^T (+ newton_reg times its diagonal, a damping of the Newton step that does not move
-   * the solution; 0.1 keeps single and double precision on the same branches); the `iterations` of sim_step are then Newton
-   * iterations per substep (3 with 8 inner iterations is a sensible start).  It solves the joints
+   * the solution; 0.1 keeps single and double precision on the same branches); the `iterations` of
+   * sim_step are then Newton iterations per substep (3 with 8 inner iterations is a sensible start).  It solves the joints
    * far more stiffly per unit of work where loads are carried (a hanging chain does not sag), costs
    * about 2.5 times a 20-sweep step, runs at most 8 envs per workgroup, and is not available together
    * with the warm start or capsule-capsule collisions (SIM_ERR_ARG). */

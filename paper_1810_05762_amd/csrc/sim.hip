@@ -252,8 +252,6 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   }
   if (d->group_size < 0 || d->group_size > kMaxGroup) return fail(SIM_ERR_ARG, "group_size %d outside 0..%d", d->group_size, kMaxGroup);
   m->group = d->group_size > 1 ? d->group_size : 1;
-  if (m->warm > 0.0f && (m->n_pairs > 0 || m->group > 1))
-    return fail(SIM_ERR_ARG, "warm_start is not available together with capsule-capsule collisions");
   if (m->solver == 1 && (m->n_pairs > 0 || m->group > 1))
     return fail(SIM_ERR_ARG, "the Newton solver is not available together with capsule-capsule collisions");
   m->n_agent_pairs = 0;
@@ -490,6 +488,8 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
     return fail(SIM_ERR_ARG, "this robot does not fit the Newton solver's workgroup (a contact thread per slot)");
   int lrc = m.solver == 1 ? ((s->E == 8 && few) ? launch(&step_kernel<8, 4, 0, kThreads, 0, 1>)
                              : few ? launch(&step_kernel<0, 4, 0, kThreads, 0, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 0, 1>))
+            : (m.warm > 0.0f && pairs) ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1, kThreads, 1>)
+                             : few ? launch(&step_kernel<0, 4, 1, kThreads, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1, kThreads, 1>))
             : m.warm > 0.0f ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 0, kThreads, 1>)
                              : few ? launch(&step_kernel<0, 4, 0, kThreads, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 1>))
             : pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)

@@ -1644,12 +1644,14 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       }
     };
     // one sweep of this thread's side of a capsule-capsule contact, if it has one
-    auto pair_sweep = [&]() {
+    // (a capsule-capsule contact starts every substep without impulses: in the warm start's
+    // sweep -1 its copies are the bodies' velocities as they are)
+    auto pair_sweep = [&](bool relax) {
       if constexpr (PC != 0) {
         if (has_pair) {
           float vo[3], wo[3];
           for (int c = 0; c < 3; ++c) { vo[c] = Lvel[pr.off + c * E]; wo[c] = Lvel[pr.off + (3 + c) * E]; }
-          relax_pair_side(pr, p_mu, vo, wo);
+          if (relax) relax_pair_side(pr, p_mu, vo, wo);
           const int po = (2 * pk + (tid & 1)) * 6;
           for (int c = 0; c < 3; ++c) { Lpo[po + c] = pr.wk * vo[c]; Lpo[po + 3 + c] = pr.wk * wo[c]; }
         }
@@ -1981,7 +1983,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
               Loutj[(js_j * kJS + js_side * 6 + 3 + c) * E + e] = wo[c];
             }
         }
-        pair_sweep();
+        pair_sweep(!(WS != 0 && it < 0));
         __syncthreads();
         gather();
         __syncthreads();
@@ -2032,7 +2034,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           for (int r = 0; r < 3; ++r) overflow_lam(k, r) = c2.lam[r];
           for (int r = 0; r < 3; ++r) { Loutc[(sl * kCS + r) * E + ee] = vv[r]; Loutc[(sl * kCS + 3 + r) * E + ee] = ww[r]; }
         }
-        pair_sweep();
+        pair_sweep(!(WS != 0 && it < 0));
         __syncthreads();
         gather();
         __syncthreads();

@@ -167,6 +167,68 @@ def test_humanoids_with_collisions(group, terrain, n_envs):
     sim.check(); sim.close()
 
 
+@pytest.mark.parametrize("group,terrain,n_envs", [(4, "plane", 38), (1, "heightfield", 37), (16, "plane", 40)])
+def test_humanoids_with_collisions_and_warm_start(group, terrain, n_envs):
+    """Collisions and the warm start together (capsule-capsule contacts start every substep without
+    impulses, joints and terrain slots from 0.8 of what they ended the last one with): substeps on
+    identical states with identical kept impulses agree in contact sets, state and kept impulses;
+    then ten free-running steps."""
+    import dataclasses
+    P = _P()
+    rob, sc = _humanoid_scene(n_envs, group, 0.6, terrain)
+    sc.params = dataclasses.replace(sc.params, warm_start=0.8)
+    sim, ref = P.Sim(sc), oracle.OracleSim(sc, threads=8)
+    sim.reset(5)
+    sim.record_contacts(True)
+    dt, sub, its = float(np.float32(1.0 / 60.0)), 4, 20
+    h = dt / sub
+
+    def kept():
+        lj, ls = sim.get_kept_impulses()
+        return lj.cpu().numpy().astype(np.float64), ls.cpu().numpy().astype(np.float64)
+
+    def sync_ref():
+        # same fp32 state, nothing kept on either side (set_state clears it)
+        st = sim.get_state()
+        sim.set_state(st)
+        ref.set_state(st.cpu().numpy().astype(np.float64))
+
+    total = 0
+    for s in range(40):
+        a = scenes.actions_for_step(9, s, n_envs, rob.n_dofs)
+        if s % 5 == 4:
+            # two substeps from identical states: the second one starts from kept impulses
+            sync_ref()
+            for rep in range(2):
+                sim.step(a, h, 1, its); ref.step(a, h, 1, its)
+                pg, dropped = sim.get_pair_contacts()
+                po = ref.get_pair_contacts()
+                assert dropped == 0
+                if rep == 0:
+                    assert_same_pair_sets(pg, po)   # (identical states only before the first substep)
+                total += len(po)
+            e = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+            assert e.max() <= TOL_1, (s, e.max())
+            (gj, gs), (oj, os_) = kept(), ref.get_warm()
+            scale = max(1.0, np.abs(oj).max(), np.abs(os_).max())
+            assert max(np.abs(gj - oj).max(), np.abs(gs - os_).max()) / scale <= 1e-4
+        else:
+            sim.step(a, dt, sub, its)
+    assert total > 20
+    sync_ref()
+    errs = {}
+    for s in range(10):
+        a = scenes.actions_for_step(9, 40 + s, n_envs, rob.n_dofs)
+        sim.step(a, dt, sub, its); ref.step(a, dt, sub, its)
+        if s in (0, 9):
+            errs[s + 1] = rel_err(sim.get_state().cpu().numpy().astype(np.float64), ref.get_state())
+    print(f"warm, group {group} {terrain}: {total} pair contacts sampled; 1 step max {errs[1].max():.2e}, "
+          f"10 steps median {np.median(errs[10]):.2e} p95 {np.quantile(errs[10], .95):.2e} max {errs[10].max():.2e}")
+    assert errs[1].max() <= TOL_1
+    assert np.median(errs[10]) <= TOL_1 and errs[10].max() <= TOL_10
+    sim.check(); sim.close()
+
+
 def test_distant_groups_do_not_interact_and_variant_matches_plain_kernel():
     """With collisions compiled in but nothing close enough to touch, the states equal those of the
     plain kernel up to rounding (two instantiations of the kernel: the compiler may contract

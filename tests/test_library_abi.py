@@ -95,9 +95,10 @@ def test_warm_start_description_validation_needs_no_gpu():
         d.warm_start = bad
         with pytest.raises(P.SimError):
             P.sim_workspace_bytes(d, 64)
+    # together with collisions: accepted, the same room for the kept impulses on top
     both = scenes.make_scene(rob, scenes.make_plane(), 64, params=scenes.SimParams(self_collide=1, warm_start=0.5))
-    with pytest.raises(P.SimError):
-        P.sim_workspace_bytes(P.make_desc(both)[0], 64)
+    coll = scenes.make_scene(rob, scenes.make_plane(), 64, params=scenes.SimParams(self_collide=1))
+    assert P.sim_workspace_bytes(P.make_desc(both)[0], 64) - P.sim_workspace_bytes(P.make_desc(coll)[0], 64) == extra
 
 
 def test_robots_beyond_the_size_limits_are_rejected_without_a_gpu():
