@@ -295,6 +295,35 @@ int sim_generate_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, vo
  * collide pairs nor groups. */
 int sim_get_pair_contacts(sim_t* sim, sim_pair_contact_rec_t* recs_dev, int32_t cap, int32_t* count_dev /*[2]*/,
                           void* stream);
+/* Interaction groups chosen from where the agents are (Section 3.1, last paragraph: all agents
+ * are simulated in one shared scene; Section 4.1: the agents of the flagrun tasks collide with
+ * each other).  At creation agent k stands at place k and group_size consecutive places form a
+ * group, so agents that walk away from their group mates stop meeting anybody.  These calls
+ * re-assign the places; everything the caller sees (states, actions, observations, records)
+ * stays indexed by agent.  All need group_size > 1 (SIM_ERR_ARG otherwise).
+ *
+ * sim_regroup: a uniform grid of `cell` metres over the ground plane; an agent's cell is that of
+ *   its root body's world position; agents are ordered along the Z-order curve of the cells (cell
+ *   index floor(p / cell) + 32768 per axis, clamped to 16 bits, x in the even bits; equal cells:
+ *   by agent number).  Inside windows of (64 / group_size) * group_size consecutive agents of that
+ *   order the groups are then grown by who is within `reach` metres of whom (root bodies): the
+ *   first free agent of a window starts a group, which takes, while it has room, the first free
+ *   agent within reach of any of its members, else the first free agent.  The places are handed
+ *   out group by group.  `reach` is about twice an agent's radius of action, `cell` a few times
+ *   that.  Call it every few steps: the cost is one pass over all pairs of agents (quadratic, no
+ *   scratch memory), a fraction of a step up to some ten thousand agents.  Agents close to each
+ *   other that still end up in different groups (their group was full, a window border runs
+ *   between them) do not collide; sim_count_near_pairs says how many such pairs there are.
+ * sim_set_groups: place_env_dev[N] (device) names the agent at every place, any permutation of
+ *   0 .. N-1 (checked; SIM_ERR_ARG if it is none; synchronises `stream`); NULL puts every agent
+ *   back at the place of its own number.
+ * sim_get_groups: the current place_env into place_env_dev[N] (device).
+ * sim_count_near_pairs: counts_dev[0] = agent pairs whose root bodies are within `reach` metres,
+ *   counts_dev[1] = those of them that the current groups keep apart (device, two int64). */
+int sim_regroup(sim_t* sim, float cell, float reach, void* stream);
+int sim_set_groups(sim_t* sim, const int32_t* place_env_dev, void* stream);
+int sim_get_groups(sim_t* sim, int32_t* place_env_dev, void* stream);
+int sim_count_near_pairs(sim_t* sim, float reach, int64_t* counts_dev /*[2]*/, void* stream);
 /* Synchronises `stream` and scans the state: SIM_ERR_NONFINITE if any value is NaN/Inf. */
 int sim_check(sim_t* sim, void* stream);
 

@@ -87,6 +87,11 @@ def _load():
     L.oracle_set_solver.argtypes = [vp, C.c_int32, C.c_int32, C.c_double]
     L.oracle_set_pair_cap.argtypes = [vp, C.c_int32, C.c_int32]
     L.oracle_set_pair_cap.restype = C.c_int64
+    L.oracle_regroup.argtypes = [vp, C.c_double, C.c_double]
+    L.oracle_set_groups.argtypes = [vp, ip]
+    L.oracle_set_groups.restype = C.c_int32
+    L.oracle_get_groups.argtypes = [vp, ip]
+    L.oracle_count_near_pairs.argtypes = [vp, C.c_double, C.c_void_p]
     L.oracle_get_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm.argtypes = [vp, dp, dp]
     L.oracle_set_warm_flags.argtypes = [vp, ip, ip]
@@ -221,6 +226,32 @@ class OracleSim:
         `cap` capsule-capsule contacts per substep, those with the smallest (single-precision gap,
         key).  cap <= 0 lifts the bound.  Returns the number removed since the last call."""
         return int(self._L.oracle_set_pair_cap(self._h, int(cap), int(envs_per_unit)))
+
+    def regroup(self, cell, reach):
+        """Interaction groups from the agents' positions: order along the Z-order curve of a grid
+        of `cell` metres; inside windows of that order, groups of agents within `reach` of each other."""
+        self._L.oracle_regroup(self._h, float(cell), float(reach))
+
+    def set_groups(self, place_env):
+        """place_env[N]: a permutation of the agents, groups are consecutive places (None: identity)."""
+        if place_env is None:
+            rc = self._L.oracle_set_groups(self._h, None)
+        else:
+            pe = np.ascontiguousarray(place_env, np.int32).reshape(self.N)
+            rc = self._L.oracle_set_groups(self._h, pe.ctypes.data_as(C.POINTER(C.c_int32)))
+        if rc != 0:
+            raise ValueError("place_env is not a permutation of the agents")
+
+    def get_groups(self):
+        pe = np.zeros(self.N, np.int32)
+        self._L.oracle_get_groups(self._h, pe.ctypes.data_as(C.POINTER(C.c_int32)))
+        return pe
+
+    def count_near_pairs(self, reach):
+        """(agent pairs whose roots are within `reach`, those of them in different groups)"""
+        c = np.zeros(2, np.int64)
+        self._L.oracle_count_near_pairs(self._h, float(reach), c.ctypes.data)
+        return int(c[0]), int(c[1])
 
     def set_warm(self, lam_j, lam_s):
         lj = np.ascontiguousarray(lam_j, np.float64).reshape(self.N, self.J, 6)

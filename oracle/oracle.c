@@ -166,6 +166,11 @@ struct oracle_sim {
   int* pcon_n;               /* [groups] */
   int pair_cap, pair_unit;   /* bounded contact store: at most pair_cap per pair_unit agents (0: none) */
   long long pair_removed;
+  /* interaction groups over places: place p holds agent place_env[p]; group gi = places
+   * [gi G, gi G + G).  Identity until oracle_set_groups / oracle_regroup change it.  Inside a
+   * substep agents are numbered by place (also in the contacts kept in pcon). */
+  int* place_env;
+  int regrouped;
   int trace_env, trace_cap, trace_n;
   oracle_sweep_trace* trace;
 };
@@ -1296,6 +1301,9 @@ oracle_sim* oracle_create(const oracle_desc* d, int32_t N) {
   int groups = (N + m->G - 1) / m->G;
   o->pcon = (oracle_pair_contact*)calloc((size_t)groups * MAXPC, sizeof(oracle_pair_contact));
   o->pcon_n = (int*)calloc((size_t)groups, sizeof(int));
+  o->place_env = (int*)malloc(sizeof(int) * (size_t)N);
+  for (int p = 0; p < N; ++p) o->place_env[p] = p;
+  o->regrouped = 0;
   for (int e = 0; e < N; ++e) {
     o->env[e].origin = V(d->env_origins[3 * e], d->env_origins[3 * e + 1], d->env_origins[3 * e + 2]);
     o->env[e].target[0] = 1000.0; o->env[e].target[1] = 0.0;
@@ -1308,7 +1316,7 @@ oracle_sim* oracle_create(const oracle_desc* d, int32_t N) {
 
 void oracle_destroy(oracle_sim* o) {
   if (!o) return;
-  free(o->m.heights); free(o->env); free(o->pcon); free(o->pcon_n); free(o);
+  free(o->m.heights); free(o->env); free(o->pcon); free(o->pcon_n); free(o->place_env); free(o);
 }
 int32_t oracle_n_slots(const oracle_sim* o) { return o->m.S; }
 int32_t oracle_obs_dim(const oracle_sim* o) { return 11 + 3 * o->m.D + o->m.F + (o->m.height_map ? HM_ROWS * HM_COLS : 0); }
@@ -1609,9 +1617,20 @@ static long long substep_groups(oracle_sim* o, int g0, int g1, double h, int ite
     if (ph)
       for (int gi = g0; gi < g1; ++gi) {
         int e0, G = group_span(o, gi, &e0);
-        int tr = (o->trace_env >= e0 && o->trace_env < e0 + G);
-        substep(&o->m, &o->env[e0], e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations, ph,
+        int tr = 0;
+        for (int g = 0; g < G; ++g) tr |= (o->place_env[e0 + g] == o->trace_env);
+        env_state* members = &o->env[e0];
+        if (o->regrouped) {
+          /* the members of the group side by side for the substep, then back to their own places */
+          members = (env_state*)malloc(sizeof(env_state) * (size_t)G);
+          for (int g = 0; g < G; ++g) members[g] = o->env[o->place_env[e0 + g]];
+        }
+        substep(&o->m, members, e0, G, o->pcon + (size_t)gi * MAXPC, &o->pcon_n[gi], h, iterations, ph,
                 tr ? o->trace : NULL, &o->trace_n, o->trace_cap);
+        if (o->regrouped) {
+          for (int g = 0; g < G; ++g) o->env[o->place_env[e0 + g]] = members[g];
+          free(members);
+        }
       }
     if (pass == 0 && (phases & ORACLE_PH_CONTACTS) && o->pair_cap > 0) removed += trim_pair_contacts(o, g0, g1);
   }
@@ -1636,11 +1655,12 @@ void oracle_step(oracle_sim* o, const double* actions, double dt, int32_t subste
 #endif
   for (int u = 0; u < units; ++u) {
     int g0 = u * gpu, g1 = g0 + gpu < groups ? g0 + gpu : groups;
-    int e_lo = g0 * o->m.G, e_hi = g1 * o->m.G < o->N ? g1 * o->m.G : o->N;
+    int p_lo = g0 * o->m.G, p_hi = g1 * o->m.G < o->N ? g1 * o->m.G : o->N;
     if (o->task.enabled)
-      for (int e = e_lo; e < e_hi; ++e) task_before_step(&o->task, &o->env[e], e);
+      for (int p = p_lo; p < p_hi; ++p) { int e = o->place_env[p]; task_before_step(&o->task, &o->env[e], e); }
     for (int s = 0; s < substeps; ++s) removed += substep_groups(o, g0, g1, h, iterations, ORACLE_PH_ALL);
-    for (int e = e_lo; e < e_hi; ++e) {
+    for (int p = p_lo; p < p_hi; ++p) {
+      int e = o->place_env[p];
       o->env[e].steps++;
       if (o->task.enabled) task_after_step(&o->task, &o->m, &o->env[e], e);
     }
@@ -1656,11 +1676,16 @@ int64_t oracle_set_pair_cap(oracle_sim* o, int32_t cap, int32_t envs_per_unit) {
   return r;
 }
 
+/* a contact as the caller sees it: agents by their own numbers, not by place */
+static oracle_pair_contact by_agent(const oracle_sim* o, oracle_pair_contact c) {
+  c.env_a = o->place_env[c.env_a]; c.env_b = o->place_env[c.env_b];
+  return c;
+}
 int32_t oracle_get_pair_contacts(const oracle_sim* o, oracle_pair_contact* out, int32_t cap) {
   int n = 0, groups = (o->N + o->m.G - 1) / o->m.G;
   for (int gi = 0; gi < groups; ++gi)
     for (int k = 0; k < o->pcon_n[gi]; ++k, ++n)
-      if (n < cap) out[n] = o->pcon[(size_t)gi * MAXPC + k];
+      if (n < cap) out[n] = by_agent(o, o->pcon[(size_t)gi * MAXPC + k]);
   return n;
 }
 
@@ -1669,12 +1694,135 @@ int32_t oracle_generate_pair_contacts(oracle_sim* o, oracle_pair_contact* out, i
   oracle_pair_contact* tmp = (oracle_pair_contact*)malloc(sizeof(oracle_pair_contact) * MAXPC);
   for (int gi = 0; gi < groups; ++gi) {
     int e0, G = group_span(o, gi, &e0);
-    int k = generate_pair_contacts(&o->m, &o->env[e0], e0, G, tmp);
+    env_state* members = (env_state*)malloc(sizeof(env_state) * (size_t)G);
+    for (int g = 0; g < G; ++g) members[g] = o->env[o->place_env[e0 + g]];
+    int k = generate_pair_contacts(&o->m, members, e0, G, tmp);
+    free(members);
     for (int i = 0; i < k; ++i, ++n)
-      if (n < cap) out[n] = tmp[i];
+      if (n < cap) out[n] = by_agent(o, tmp[i]);
   }
   free(tmp);
   return n;
+}
+
+/* ---- interaction groups chosen from where the agents are (Section 3.1: all agents share one
+ * scene; Section 4.1: the agents of the flagrun tasks collide with each other).  A uniform grid
+ * of `cell` metres over the ground plane; an agent's cell is that of its root body's world
+ * position; agents are ordered along the Z-order curve of the cells (ties: agent number), and
+ * every G consecutive agents of that order form a group.  All decisions in single precision. */
+static uint32_t spread_bits16(uint32_t v) {
+  v &= 0xffffu;
+  v = (v | (v << 8)) & 0x00ff00ffu;
+  v = (v | (v << 4)) & 0x0f0f0f0fu;
+  v = (v | (v << 2)) & 0x33333333u;
+  v = (v | (v << 1)) & 0x55555555u;
+  return v;
+}
+static uint32_t cell_coord(float p, float cell) {
+  float c = floorf(p / cell);
+  if (!(c >= -32768.0f)) c = -32768.0f;   /* (also catches NaN) */
+  if (c > 32767.0f) c = 32767.0f;
+  return (uint32_t)((int)c + 32768);
+}
+typedef struct { uint64_t word; } order_entry;
+static int order_entry_cmp(const void* a, const void* b) {
+  uint64_t x = ((const order_entry*)a)->word, y = ((const order_entry*)b)->word;
+  return x < y ? -1 : (x > y ? 1 : 0);
+}
+static void root_world_f32(const oracle_sim* o, int e, float p[3]) {
+  const env_state* E = &o->env[e];
+  const v3 x = E->x[o->m.root];
+  p[0] = (float)x.x + (float)E->origin.x; p[1] = (float)x.y + (float)E->origin.y; p[2] = (float)x.z + (float)E->origin.z;
+}
+/* counts[0]: agent pairs whose roots are within `reach`; counts[1]: those of them that the
+ * current groups keep apart (they cannot collide) */
+void oracle_count_near_pairs(const oracle_sim* o, double reach, int64_t* counts) {
+  const int N = o->N, G = o->m.G;
+  int* place_of = (int*)malloc(sizeof(int) * (size_t)N);
+  float* P = (float*)malloc(sizeof(float) * 3 * (size_t)N);
+  for (int p = 0; p < N; ++p) place_of[o->place_env[p]] = p;
+  for (int e = 0; e < N; ++e) root_world_f32(o, e, P + 3 * e);
+  const float r = (float)reach, r2 = r * r;
+  counts[0] = counts[1] = 0;
+  for (int i = 0; i < N; ++i)
+    for (int j = i + 1; j < N; ++j) {
+      float dx = P[3 * i] - P[3 * j], dy = P[3 * i + 1] - P[3 * j + 1], dz = P[3 * i + 2] - P[3 * j + 2];
+      float d2 = (dx * dx + dy * dy) + dz * dz;
+      if (d2 <= r2) { counts[0]++; if (place_of[i] / G != place_of[j] / G) counts[1]++; }
+    }
+  free(P); free(place_of);
+}
+void oracle_regroup(oracle_sim* o, double cell, double reach) {
+  const int N = o->N, G = o->m.G;
+  const float cs = (float)cell, r = (float)reach, r2 = r * r;
+  order_entry* ent = (order_entry*)malloc(sizeof(order_entry) * (size_t)N);
+  for (int e = 0; e < N; ++e) {
+    float p[3];
+    root_world_f32(o, e, p);
+    uint32_t key = spread_bits16(cell_coord(p[0], cs)) | (spread_bits16(cell_coord(p[1], cs)) << 1);
+    ent[e].word = ((uint64_t)key << 32) | (uint32_t)e;
+  }
+  qsort(ent, (size_t)N, sizeof(order_entry), order_entry_cmp);
+  /* second pass: inside windows of W consecutive agents of that order (whole groups, at most 64)
+   * the groups are grown by who is within reach of whom: the first free agent starts a group,
+   * which then takes, while it has room, the first free agent within reach of any member, or the
+   * first free agent if there is none */
+  const int W = (64 / G) * G;
+  for (int w0 = 0; w0 < N; w0 += W) {
+    const int n = N - w0 < W ? N - w0 : W;
+    int agent[64], taken[64];
+    float P[64][3];
+    for (int k = 0; k < n; ++k) { agent[k] = (int)(uint32_t)ent[w0 + k].word; taken[k] = 0; root_world_f32(o, agent[k], P[k]); }
+    int out = 0;
+    while (out < n) {
+      int members[MAXG], cnt = 0;
+      for (int k = 0; k < n; ++k) if (!taken[k]) { members[cnt++] = k; taken[k] = 1; break; }
+      while (cnt < G && out + cnt < n) {
+        int nx = -1;
+        for (int k = 0; k < n && nx < 0; ++k) {
+          if (taken[k]) continue;
+          for (int q = 0; q < cnt; ++q) {
+            const float* a = P[k]; const float* b = P[members[q]];
+            float dx = a[0] - b[0], dy = a[1] - b[1], dz = a[2] - b[2];
+            float d2 = (dx * dx + dy * dy) + dz * dz;
+            if (d2 <= r2) { nx = k; break; }
+          }
+        }
+        for (int k = 0; k < n && nx < 0; ++k) if (!taken[k]) nx = k;
+        members[cnt++] = nx; taken[nx] = 1;
+      }
+      for (int q = 0; q < cnt; ++q) o->place_env[w0 + out + q] = agent[members[q]];
+      out += cnt;
+    }
+  }
+  o->regrouped = 1;
+  free(ent);
+  memset(o->pcon_n, 0, sizeof(int) * (size_t)((N + G - 1) / G));
+}
+/* place_env[N]: a permutation of the agents (NULL: agents in their own order); returns 0, or -1
+ * if it is none */
+int32_t oracle_set_groups(oracle_sim* o, const int32_t* place_env) {
+  const int N = o->N;
+  if (place_env) {
+    uint8_t* seen = (uint8_t*)calloc((size_t)N, 1);
+    int ok = 1;
+    for (int p = 0; p < N && ok; ++p) {
+      if (place_env[p] < 0 || place_env[p] >= N || seen[place_env[p]]) ok = 0;
+      else seen[place_env[p]] = 1;
+    }
+    free(seen);
+    if (!ok) return -1;
+  }
+  o->regrouped = 0;
+  for (int p = 0; p < N; ++p) {
+    o->place_env[p] = place_env ? place_env[p] : p;
+    if (o->place_env[p] != p) o->regrouped = 1;
+  }
+  memset(o->pcon_n, 0, sizeof(int) * (size_t)((N + o->m.G - 1) / o->m.G));
+  return 0;
+}
+void oracle_get_groups(const oracle_sim* o, int32_t* place_env) {
+  for (int p = 0; p < o->N; ++p) place_env[p] = o->place_env[p];
 }
 
 void oracle_get_obs(const oracle_sim* o, double* obs, double* reward, uint8_t* done) {

@@ -197,6 +197,23 @@ int32_t oracle_generate_pair_contacts(oracle_sim*, oracle_pair_contact* out, int
  * | (body of A << 4) | body of B.  cap <= 0: no bound (the default).  Returns the number of
  * contacts removed since the last call. */
 int64_t oracle_set_pair_cap(oracle_sim*, int32_t cap, int32_t envs_per_unit);
+/* Interaction groups chosen from where the agents are (Section 3.1: all agents share one scene;
+ * Section 4.1: the agents of the flagrun tasks collide with each other).  Groups are G consecutive
+ * *places*; place p holds agent place_env[p] (at creation: agent p).  oracle_regroup orders the
+ * agents along the Z-order curve of a uniform grid of `cell` metres over the ground plane (an
+ * agent's cell is that of its root body's world position, cell index floor(p / cell) + 32768
+ * clamped to 16 bits per axis, x in the even bits; ties by agent number); then, inside windows of
+ * (64 / G) G consecutive agents of that order, groups are grown by who is within `reach` of whom
+ * (root bodies): the first free agent of the window starts a group, which takes, while it has
+ * room, the first free agent within reach of any member, else the first free agent.  The places
+ * are handed out group by group.  oracle_set_groups takes any permutation (NULL: agents in their
+ * own order; returns -1 if it is none).  oracle_count_near_pairs: counts[0] = agent pairs whose
+ * root bodies are within `reach`, counts[1] = those of them in different groups.  All of these
+ * decide in single precision (positions rounded to float before the origin is added). */
+void oracle_regroup(oracle_sim*, double cell, double reach);
+int32_t oracle_set_groups(oracle_sim*, const int32_t* place_env);
+void oracle_get_groups(const oracle_sim*, int32_t* place_env);
+void oracle_count_near_pairs(const oracle_sim*, double reach, int64_t* counts);
 /* single-precision closest points of two segments P0P1, Q0Q1 (fixed operation order): writes the
  * parameters and returns the squared distance; exposed so it can be pinned */
 float oracle_segment_segment_f32(const float* P0, const float* P1, const float* Q0, const float* Q1,

@@ -87,6 +87,10 @@ _SYMBOLS = {
     "sim_get_contacts": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_generate_contacts": [C.c_void_p, C.c_void_p, C.c_void_p],
     "sim_get_pair_contacts": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
+    "sim_regroup": [C.c_void_p, C.c_float, C.c_float, C.c_void_p],
+    "sim_set_groups": [C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_get_groups": [C.c_void_p, C.c_void_p, C.c_void_p],
+    "sim_count_near_pairs": [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p],
     "sim_check": [C.c_void_p, C.c_void_p],
     "sim_launch_info": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_size_t)],
     "sim_set_envs_per_block": [C.c_void_p, C.c_int],
@@ -270,6 +274,22 @@ def sim_get_pair_contacts(h, recs_ptr, cap, count_ptr, stream):
     return _chk(lib().sim_get_pair_contacts(h, recs_ptr, int(cap), count_ptr, stream))
 
 
+def sim_regroup(h, cell, reach, stream):
+    return _chk(lib().sim_regroup(h, float(cell), float(reach), stream))
+
+
+def sim_set_groups(h, place_env_ptr, stream):
+    return _chk(lib().sim_set_groups(h, place_env_ptr, stream))
+
+
+def sim_get_groups(h, place_env_ptr, stream):
+    return _chk(lib().sim_get_groups(h, place_env_ptr, stream))
+
+
+def sim_count_near_pairs(h, reach, counts_ptr, stream):
+    return _chk(lib().sim_count_near_pairs(h, float(reach), counts_ptr, stream))
+
+
 def sim_check(h, stream):
     return _chk(lib().sim_check(h, stream))
 
@@ -433,6 +453,30 @@ class Sim:
         sim_get_pair_contacts(self.h, buf.data_ptr(), cap, cnt.data_ptr(), self._stream())
         n, dropped = (int(v) for v in cnt.cpu().numpy())
         return buf.cpu().numpy().view(PAIR_CONTACT_DTYPE)[:min(n, cap)].copy(), dropped
+
+    def regroup(self, cell, reach):
+        """Interaction groups from the agents' positions: order along the Z-order curve of a grid of
+        `cell` metres, then groups of agents within `reach` of each other inside windows of that order."""
+        sim_regroup(self.h, cell, reach, self._stream())
+
+    def set_groups(self, place_env):
+        """place_env[N]: the agent at every place (a permutation); None: every agent at its own."""
+        if place_env is None:
+            sim_set_groups(self.h, None, self._stream())
+            return
+        pe = self.torch.as_tensor(np.array(place_env, np.int32, copy=True)).to(self.device)
+        sim_set_groups(self.h, pe.data_ptr(), self._stream())
+
+    def get_groups(self):
+        pe = self.torch.zeros(self.N, dtype=self.torch.int32, device=self.device)
+        sim_get_groups(self.h, pe.data_ptr(), self._stream())
+        return pe.cpu().numpy()
+
+    def count_near_pairs(self, reach):
+        """(agent pairs whose roots are within `reach`, those of them in different groups)"""
+        c = self.torch.zeros(2, dtype=self.torch.int64, device=self.device)
+        sim_count_near_pairs(self.h, reach, c.data_ptr(), self._stream())
+        return tuple(int(v) for v in c.cpu().numpy())
 
     def check(self):
         sim_check(self.h, self._stream())

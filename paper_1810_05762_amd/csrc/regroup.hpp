@@ -1,0 +1,181 @@
+// Interaction groups chosen from where the agents are (Section 3.1: all agents share one scene;
+// Section 4.1: the agents of the flagrun tasks collide with each other).
+//
+// A uniform grid over the ground plane; an agent's cell is that of its root body's world position;
+// the agents are ordered along the Z-order curve of the cells (ties: agent number), which puts
+// agents that stand close together mostly close together in the order; windows of up to 64
+// consecutive agents of that order are then split into groups by who is within reach of whom.
+// The places of the launch (a workgroup holds consecutive places, a group consecutive places of a
+// workgroup) are handed out in the resulting order.
+// Every decision is taken in single precision with the operation order written out, so that a
+// reference in plain C reaches the same order bit for bit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sim355 {
+
+#pragma clang fp contract(off)
+
+__device__ __forceinline__ uint32_t spread_bits16(uint32_t v) {
+  v &= 0xffffu;
+  v = (v | (v << 8)) & 0x00ff00ffu;
+  v = (v | (v << 4)) & 0x0f0f0f0fu;
+  v = (v | (v << 2)) & 0x33333333u;
+  v = (v | (v << 1)) & 0x55555555u;
+  return v;
+}
+
+// cell index along one axis, moved into 0 .. 65535 (clamped; NaN goes to 0)
+__device__ __forceinline__ uint32_t cell_coord(float p, float cell) {
+  float c = floorf(p / cell);
+  if (!(c >= -32768.0f)) c = -32768.0f;
+  if (c > 32767.0f) c = 32767.0f;
+  return (uint32_t)((int)c + 32768);
+}
+
+// world position of agent i's root body; state is [13][B][N], origins [N][3]
+__device__ __forceinline__ void root_world(const float* __restrict__ state, const float* __restrict__ origins, int B, int N,
+                                           int root, int i, float p[3]) {
+  for (int c = 0; c < 3; ++c) p[c] = state[((size_t)c * B + root) * N + i] + origins[3 * i + c];
+}
+
+// words[i] = (Z-order key of agent i's cell) << 32 | i
+__global__ void order_words_kernel(const float* __restrict__ state, const float* __restrict__ origins, int B, int N, int root,
+                                   float cell, unsigned long long* __restrict__ words) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  float p[3];
+  root_world(state, origins, B, N, root, i, p);
+  const uint32_t key = spread_bits16(cell_coord(p[0], cell)) | (spread_bits16(cell_coord(p[1], cell)) << 1);
+  words[i] = ((unsigned long long)key << 32) | (unsigned)i;
+}
+
+// place_env[rank of words[i] among all words] = i.  The words are distinct (they end in the agent
+// number), so the ranks are a permutation.  Quadratic in N on purpose: no scratch memory, a
+// result that does not depend on scheduling, and a few milliseconds at 65536 agents.
+__global__ void rank_places_kernel(const unsigned long long* __restrict__ words, int N, int32_t* __restrict__ place_env) {
+  __shared__ unsigned long long tile[256];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const unsigned long long mine = i < N ? words[i] : ~0ull;
+  int rank = 0;
+  for (int j0 = 0; j0 < N; j0 += 256) {
+    const int j = j0 + threadIdx.x;
+    tile[threadIdx.x] = j < N ? words[j] : ~0ull;
+    __syncthreads();
+    const int n_here = min(256, N - j0);
+    for (int k = 0; k < n_here; ++k) rank += tile[k] < mine ? 1 : 0;
+    __syncthreads();
+  }
+  if (i < N) place_env[rank] = i;
+}
+
+// Second pass: the agents of a window of W consecutive places (W a multiple of the group size G, at
+// most 64; one wavefront per window) are put into groups by who is close to whom rather than by
+// their order along the curve.  Two agents are neighbours if their root bodies are within `reach`.
+// Groups are grown one after another: the first agent of the window not yet in a group starts
+// one; as long as the group has room it takes the first agent (in window order) that is a
+// neighbour of any of its members and still free, or, if there is none, the first free agent.
+// place_env holds the order along the curve on entry and the final places on return; a window
+// only touches its own places.
+__global__ void cluster_windows_kernel(const float* __restrict__ state, const float* __restrict__ origins, int B, int N,
+                                       int root, int G, int W, float reach, int32_t* __restrict__ place_env) {
+  __shared__ float wp[3][64];
+  __shared__ unsigned long long adj[64];
+  __shared__ int agent_of[64], pick[64];
+  const int lane = threadIdx.x, w0 = blockIdx.x * W;
+  const int n = min(W, N - w0);
+  float p[3] = {0.0f, 0.0f, 0.0f};
+  if (lane < n) {
+    agent_of[lane] = place_env[w0 + lane];
+    root_world(state, origins, B, N, root, agent_of[lane], p);
+  }
+  wp[0][lane] = p[0]; wp[1][lane] = p[1]; wp[2][lane] = p[2];
+  __syncthreads();
+  const float r2 = reach * reach;
+  unsigned long long mine = 0ull;
+  if (lane < n)
+    for (int k = 0; k < n; ++k) {
+      const float dx = p[0] - wp[0][k], dy = p[1] - wp[1][k], dz = p[2] - wp[2][k];
+      const float d2 = (dx * dx + dy * dy) + dz * dz;
+      if (k != lane && d2 <= r2) mine |= 1ull << k;
+    }
+  adj[lane] = mine;
+  __syncthreads();
+  if (lane == 0) {
+    unsigned long long free_mask = n == 64 ? ~0ull : ((1ull << n) - 1ull);
+    int out = 0;
+    while (free_mask) {
+      const int seed = __ffsll((long long)free_mask) - 1;
+      free_mask &= ~(1ull << seed);
+      unsigned long long frontier = adj[seed] & free_mask;
+      pick[out++] = seed;
+      for (int cnt = 1; cnt < G && free_mask; ++cnt) {
+        const int nx = __ffsll((long long)(frontier ? frontier : free_mask)) - 1;
+        free_mask &= ~(1ull << nx);
+        frontier = (frontier | adj[nx]) & free_mask;
+        pick[out++] = nx;
+      }
+    }
+  }
+  __syncthreads();
+  if (lane < n) place_env[w0 + lane] = agent_of[pick[lane]];
+}
+
+// place_of[place_env[p]] = p (place_env null: the identity)
+__global__ void invert_places_kernel(const int32_t* __restrict__ place_env, int N, int32_t* __restrict__ place_of) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < N) place_of[place_env ? place_env[p] : p] = p;
+}
+
+// counts[0] += agent pairs whose root bodies are within `reach`; counts[1] += those of them whose
+// places lie in different groups of G
+__global__ void near_pairs_kernel(const float* __restrict__ state, const float* __restrict__ origins, int B, int N, int root,
+                                  const int32_t* __restrict__ place_of, int G, float reach,
+                                  unsigned long long* __restrict__ counts) {
+  __shared__ float tp[3][256];
+  __shared__ int tg[256];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  float p[3] = {0.0f, 0.0f, 0.0f};
+  int gi = -1;
+  if (i < N) { root_world(state, origins, B, N, root, i, p); gi = place_of[i] / G; }
+  const float r2 = reach * reach;
+  unsigned near = 0, split = 0;
+  for (int j0 = blockIdx.x * 256; j0 < N; j0 += 256) {   // (pairs i < j only: tiles from the thread's own on)
+    const int j = j0 + threadIdx.x;
+    float q[3] = {0.0f, 0.0f, 0.0f};
+    if (j < N) root_world(state, origins, B, N, root, j, q);
+    tp[0][threadIdx.x] = q[0]; tp[1][threadIdx.x] = q[1]; tp[2][threadIdx.x] = q[2];
+    tg[threadIdx.x] = j < N ? place_of[j] / G : -1;
+    __syncthreads();
+    const int n_here = min(256, N - j0);
+    if (i < N)
+      for (int k = 0; k < n_here; ++k) {
+        if (j0 + k <= i) continue;
+        const float dx = p[0] - tp[0][k], dy = p[1] - tp[1][k], dz = p[2] - tp[2][k];
+        const float d2 = (dx * dx + dy * dy) + dz * dz;
+        if (d2 <= r2) { near += 1; split += tg[k] != gi ? 1 : 0; }
+      }
+    __syncthreads();
+  }
+  if (near) atomicAdd(&counts[0], (unsigned long long)near);
+  if (split) atomicAdd(&counts[1], (unsigned long long)split);
+}
+
+// is place_env a permutation of 0 .. N-1?  seen[] starts at zero; flag[0] becomes 1 if not
+__global__ void check_places_kernel(const int32_t* __restrict__ place_env, int N, int32_t* __restrict__ seen, int* __restrict__ flag) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= N) return;
+  const int e = place_env[p];
+  if (e < 0 || e >= N) { flag[0] = 1; return; }
+  if (atomicAdd(&seen[e], 1) != 0) flag[0] = 1;
+}
+
+__global__ void fill_words_kernel(int32_t* __restrict__ dst, size_t n, int32_t value) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = value;
+}
+
+#pragma clang fp contract(fast)
+
+}  // namespace sim355

@@ -14,6 +14,7 @@
 #include "contact_gen.hpp"
 #include "model.hpp"
 #include "step_kernel.hpp"
+#include "regroup.hpp"
 
 using namespace sim355;
 
@@ -42,7 +43,7 @@ extern "C" const char* sim_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------ layout
 struct Layout {
-  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, push, flag, pair_recs, pair_count, lam_j, lam_s, total;
+  size_t model, heights, coarse, origins, targets, state, steps, obs, reward, done, recs, task_i, push, flag, pair_recs, pair_count, lam_j, lam_s, place_env, grp_words, grp_counts, total;
 };
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -68,6 +69,10 @@ static Layout make_layout(int B, int J, int S, int obs_dim, int N, size_t n_heig
   // warm start: impulses kept from one step to the next, [J*6][N] and [S*3][N]
   L.lam_j = o; o = align_up(o + (warm ? (size_t)N * J * 6 * sizeof(float) : 0));
   L.lam_s = o; o = align_up(o + (warm ? (size_t)N * S * 3 * sizeof(float) : 0));
+  // interaction groups chosen from positions: agent at every place, sort words / inverse map, counters
+  L.place_env = o; o = align_up(o + (pairs > 1 ? (size_t)N * sizeof(int32_t) : 0));
+  L.grp_words = o; o = align_up(o + (pairs > 1 ? (size_t)N * sizeof(unsigned long long) : 0));
+  L.grp_counts = o; o = align_up(o + (pairs > 1 ? 256 : 0));
   L.flag = o; o = align_up(o + 256);   // (last: the diagnostic build keeps its counters here)
   L.total = o;
   return L;
@@ -84,6 +89,7 @@ struct sim {
   TaskParams task;
   int static_dev;  // device whose static workspace this sim occupies (sim_create_static), else -1
   int ws_has[3];   // the workspace holds obs / reward / done of the last step (else the caller got them)
+  int regrouped;   // the places of the launch hold the agents in the order of lay.place_env (else in their own)
 };
 
 // ------------------------------------------------------- static workspace
@@ -467,6 +473,7 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   a.lam_j = reinterpret_cast<float*>(s->ws + s->lay.lam_j);
   a.lam_s = reinterpret_cast<float*>(s->ws + s->lay.lam_s);
   a.pair_dropped = reinterpret_cast<int32_t*>(s->ws + s->lay.flag) + 1;
+  a.place_env = s->regrouped ? reinterpret_cast<const int32_t*>(s->ws + s->lay.place_env) : nullptr;
 #ifdef SIM_PHASE_TIMING
   a.dbg = reinterpret_cast<long long*>(s->ws + s->lay.flag) + 1;
 #else
@@ -536,7 +543,7 @@ static int create_in(const sim_desc_t* desc, int num_envs, void* workspace_dev, 
   s->N = num_envs;
   s->obs_dim = 11 + 3 * m.D + m.F + (m.height_map ? kHmRows * kHmCols : 0);
   s->lay = make_layout(m.B, m.J, m.S, s->obs_dim, num_envs, nh, (size_t)m.cnx * m.cny, pairs_of(m), m.warm > 0.0f);
-  s->record = 0; s->recs_valid = 0; s->pair_grid = 0;
+  s->record = 0; s->recs_valid = 0; s->pair_grid = 0; s->regrouped = 0;
   memset(&s->task, 0, sizeof(s->task));
   s->E = default_envs_per_block(m, num_envs);
   if (!workspace_dev || ((uintptr_t)workspace_dev & 255)) { delete s; return fail(SIM_ERR_WORKSPACE, "workspace must be non-NULL and 256-byte aligned"); }
@@ -885,6 +892,90 @@ extern "C" int sim_get_pair_contacts(sim_t* s, sim_pair_contact_rec_t* recs_dev,
                      reinterpret_cast<const int32_t*>(s->ws + s->lay.pair_count), s->pair_grid,
                      reinterpret_cast<const int32_t*>(s->ws + s->lay.flag) + 1, reinterpret_cast<int32_t*>(recs_dev),
                      cap < 0 ? 0 : cap, count_dev);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+// ---- interaction groups chosen from positions
+static int need_groups(const sim* s) {
+  if (!s) return fail(SIM_ERR_ARG, "sim is NULL");
+  if (s->host_model.group <= 1) return fail(SIM_ERR_ARG, "the description has no interaction groups (group_size <= 1)");
+  return SIM_OK;
+}
+
+extern "C" int sim_regroup(sim_t* s, float cell, float reach, void* stream) {
+  if (int rc = need_groups(s)) return rc;
+  if (!(cell > 0.0f) || !(cell <= 3.0e38f)) return fail(SIM_ERR_ARG, "cell must be positive and finite");
+  if (!(reach >= 0.0f) || !(reach <= 1.0e18f)) return fail(SIM_ERR_ARG, "reach must be non-negative and finite");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Model& m = s->host_model;
+  auto* words = reinterpret_cast<unsigned long long*>(s->ws + s->lay.grp_words);
+  hipLaunchKernelGGL(order_words_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st,
+                     reinterpret_cast<const float*>(s->ws + s->lay.state),
+                     reinterpret_cast<const float*>(s->ws + s->lay.origins), m.B, s->N, m.root, cell, words);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(rank_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, words, s->N,
+                     reinterpret_cast<int32_t*>(s->ws + s->lay.place_env));
+  HIP_TRY(hipGetLastError());
+  const int W = (64 / m.group) * m.group;   // window of the second pass: whole groups, one wavefront
+  hipLaunchKernelGGL(cluster_windows_kernel, dim3((s->N + W - 1) / W), dim3(64), 0, st,
+                     reinterpret_cast<const float*>(s->ws + s->lay.state),
+                     reinterpret_cast<const float*>(s->ws + s->lay.origins), m.B, s->N, m.root, m.group, W, reach,
+                     reinterpret_cast<int32_t*>(s->ws + s->lay.place_env));
+  HIP_TRY(hipGetLastError());
+  s->regrouped = 1;
+  s->recs_valid = 0;
+  return SIM_OK;
+}
+
+extern "C" int sim_set_groups(sim_t* s, const int32_t* place_env_dev, void* stream) {
+  if (int rc = need_groups(s)) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  s->recs_valid = 0;
+  if (!place_env_dev) { s->regrouped = 0; return SIM_OK; }
+  // checked before it is taken over: a wrong entry would send a workgroup outside the arrays
+  int32_t* seen = reinterpret_cast<int32_t*>(s->ws + s->lay.grp_words);
+  int* flag = reinterpret_cast<int*>(s->ws + s->lay.grp_counts);
+  int host_flag = 0;
+  hipLaunchKernelGGL(fill_words_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, seen, (size_t)s->N, 0);
+  hipLaunchKernelGGL(fill_words_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<int32_t*>(flag), (size_t)1, 0);
+  hipLaunchKernelGGL(check_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, place_env_dev, s->N, seen, flag);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipMemcpyAsync(&host_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (host_flag) return fail(SIM_ERR_ARG, "place_env is not a permutation of the agents 0 .. %d", s->N - 1);
+  HIP_TRY(hipMemcpyAsync(s->ws + s->lay.place_env, place_env_dev, (size_t)s->N * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
+  s->regrouped = 1;
+  return SIM_OK;
+}
+
+extern "C" int sim_get_groups(sim_t* s, int32_t* place_env_dev, void* stream) {
+  if (int rc = need_groups(s)) return rc;
+  if (!place_env_dev) return fail(SIM_ERR_ARG, "place_env is NULL");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // (through the inverse twice: one kernel covers both the stored order and the identity)
+  int32_t* tmp = reinterpret_cast<int32_t*>(s->ws + s->lay.grp_words);
+  const int32_t* pe = s->regrouped ? reinterpret_cast<const int32_t*>(s->ws + s->lay.place_env) : nullptr;
+  hipLaunchKernelGGL(invert_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, pe, s->N, tmp);
+  hipLaunchKernelGGL(invert_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, tmp, s->N, place_env_dev);
+  HIP_TRY(hipGetLastError());
+  return SIM_OK;
+}
+
+extern "C" int sim_count_near_pairs(sim_t* s, float reach, int64_t* counts_dev, void* stream) {
+  if (int rc = need_groups(s)) return rc;
+  if (!counts_dev) return fail(SIM_ERR_ARG, "counts is NULL");
+  if (!(reach >= 0.0f) || !(reach <= 1.0e18f)) return fail(SIM_ERR_ARG, "reach must be non-negative and finite");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Model& m = s->host_model;
+  int32_t* place_of = reinterpret_cast<int32_t*>(s->ws + s->lay.grp_words);
+  const int32_t* pe = s->regrouped ? reinterpret_cast<const int32_t*>(s->ws + s->lay.place_env) : nullptr;
+  hipLaunchKernelGGL(invert_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, pe, s->N, place_of);
+  hipLaunchKernelGGL(fill_words_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<int32_t*>(counts_dev), (size_t)4, 0);
+  hipLaunchKernelGGL(near_pairs_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st,
+                     reinterpret_cast<const float*>(s->ws + s->lay.state),
+                     reinterpret_cast<const float*>(s->ws + s->lay.origins), m.B, s->N, m.root, place_of, m.group, reach,
+                     reinterpret_cast<unsigned long long*>(counts_dev));
   HIP_TRY(hipGetLastError());
   return SIM_OK;
 }

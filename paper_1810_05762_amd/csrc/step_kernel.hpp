@@ -76,6 +76,7 @@ struct StepArgs {
   int32_t* pair_recs;    // [grid][kPairCap][8] capsule-capsule contacts of the last substep, or null
   int32_t* pair_count;   // [grid] their number per workgroup
   int32_t* pair_dropped; // [1] contacts dropped because a workgroup found more than kPairCap
+  const int32_t* place_env;  // [N] agent standing at every place of the launch, or null: agent = place
 };
 
 // Rows (E consecutive floats) per item of the velocity, inverse-inertia and copy arrays.  Odd
@@ -611,8 +612,16 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   const int E = EC > 0 ? EC : a.E, N = a.N;
   const int tid = threadIdx.x;
   const int e = tid % E, idx = tid / E;
-  const int env = blockIdx.x * E + e;
+  const int env = blockIdx.x * E + e;   // the thread's place in the launch: a workgroup holds E consecutive places
   const bool env_ok = env < N;
+  // Which agent stands at a place: the agent of the same number, unless the interaction groups were
+  // chosen from the agents' positions (capsule-capsule variants only).  Everything in global memory
+  // is indexed by agent, everything in LDS by the place within the workgroup.
+  auto agent_at = [&](int place) -> int {
+    if constexpr (PC != 0) { if (a.place_env && place < N) return a.place_env[place]; }
+    return place;
+  };
+  const int agent = agent_at(env);
   const bool is_body = idx < B && env_ok;
   const bool is_joint = idx < J && env_ok;
   const int obs_dim = 11 + 3 * D + F;                                      // staged in LDS
@@ -681,7 +690,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   float root_ox = 0.0f, root_oy = 0.0f;
   const int b = idx;
   if (is_body) {
-    const float* st = a.state + (size_t)b * N + env;
+    const float* st = a.state + (size_t)b * N + agent;
     const size_t fs = (size_t)B * N;
     x[0] = st[0 * fs]; x[1] = st[1 * fs]; x[2] = st[2 * fs];
     q[0] = st[3 * fs]; q[1] = st[4 * fs]; q[2] = st[5 * fs]; q[3] = st[6 * fs];
@@ -689,7 +698,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     w[0] = st[10 * fs]; w[1] = st[11 * fs]; w[2] = st[12 * fs];
     const BodyTab& bt = M.bodies[b];
     my_slot0 = bt.slot0; my_nslots = bt.n_slots; my_njs = bt.n_joint_sides;
-    if (b == M.root) { root_ox = a.origins[3 * env]; root_oy = a.origins[3 * env + 1]; }   // for the heightfield copy
+    if (b == M.root) { root_ox = a.origins[3 * agent]; root_oy = a.origins[3 * agent + 1]; }   // for the heightfield copy
   }
   // uniform parameters and this thread's joint, read once
   const float g0 = M.g[0], g1 = M.g[1], g2 = M.g[2];
@@ -700,19 +709,20 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     int ee = i / D, d = i - ee * D;
     int env_i = blockIdx.x * E + ee;
     float uu = 0.0f;
-    if (env_i < N && a.actions) uu = a.actions[(size_t)env_i * D + d];
+    if (env_i < N && a.actions) uu = a.actions[(size_t)agent_at(env_i) * D + d];
     Lu[d * E + ee] = fminf(fmaxf(uu, -1.0f), 1.0f);
   }
   // small copies of what the per-slot code looks up all the time
   for (int i = tid; i < 3 * E; i += kThreads) {
     int c = i / E, ee = i - c * E, env_i = blockIdx.x * E + ee;
-    Lorg[i] = env_i < N ? a.origins[3 * env_i + c] : 0.0f;
+    Lorg[i] = env_i < N ? a.origins[3 * agent_at(env_i) + c] : 0.0f;
   }
   // external pushes (Section 4.1): is this frame the env's next push?
   if (tid < E) {
-    const int env_t = blockIdx.x * E + tid;
+    const bool env_t_ok = blockIdx.x * E + tid < N;
+    const int env_t = agent_at(blockIdx.x * E + tid);
     float fx = 0.0f, fy = 0.0f;
-    if (a.task.enabled && a.task.push_max_f > 0 && a.count_step && env_t < N) {
+    if (a.task.enabled && a.task.push_max_f > 0 && a.count_step && env_t_ok) {
       const int f = a.steps[env_t], ep = a.task_i[4 * env_t + 3];
       if (f == a.task_i[4 * env_t + 2]) {
         const float mag = a.task.push_min_n + (a.task.push_max_n - a.task.push_min_n) * task_u(a.task, env_t, ep, f, 0);
@@ -722,18 +732,18 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       }
     }
     Lpush[0 * E + tid] = fx; Lpush[1 * E + tid] = fy; Lpush[2 * E + tid] = 0.0f;
-    if (a.task.enabled && a.count_step && env_t < N) { a.push[3 * env_t] = fx; a.push[3 * env_t + 1] = fy; a.push[3 * env_t + 2] = 0.0f; }
+    if (a.task.enabled && a.count_step && env_t_ok) { a.push[3 * env_t] = fx; a.push[3 * env_t + 1] = fy; a.push[3 * env_t + 2] = 0.0f; }
   }
   for (int i = tid; i < M.table_words; i += kThreads) reinterpret_cast<int*>(lds + P.tjs)[i] = M.table_image[i];
   for (int i = tid; i < (J * kJS + S * kCS) * E; i += kThreads) Loutj[i] = 0.0f;  // copies may be read (weight 0) before they are written
   if constexpr (WS != 0) {
     for (int i = tid; i < J * 6 * E; i += kThreads) {
       const int env_i = blockIdx.x * E + i % E;
-      Lwj[i] = env_i < N ? a.lam_j[(size_t)(i / E) * N + env_i] : 0.0f;
+      Lwj[i] = env_i < N ? a.lam_j[(size_t)(i / E) * N + agent_at(env_i)] : 0.0f;
     }
     for (int i = tid; i < S * 3 * E; i += kThreads) {
       const int env_i = blockIdx.x * E + i % E;
-      Lwc[i] = env_i < N ? a.lam_s[(size_t)(i / E) * N + env_i] : 0.0f;
+      Lwc[i] = env_i < N ? a.lam_s[(size_t)(i / E) * N + agent_at(env_i)] : 0.0f;
     }
   }
   if constexpr (PC != 0) {
@@ -1408,7 +1418,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         if (env_i < N) {
           int word = Lreci[(s * kRecWords + wd) * E + ee];
           if (!Lreci[(s * kRecWords + 0) * E + ee]) word = (wd == 1 || wd == 2) ? -1 : 0;   // inactive: canonical record
-          a.recs[((size_t)env_i * S + s) * kRecWords + wd] = word;
+          a.recs[((size_t)agent_at(env_i) * S + s) * kRecWords + wd] = word;
         }
       }
     }
@@ -1419,7 +1429,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           const int refs = __float_as_int(Lpq[tid * kPairWords + 1]);
           const int ra = refs & 0xffff, rb = (refs >> 16) & 0xffff;
           int32_t* o = a.pair_recs + ((size_t)blockIdx.x * kPairCap + tid) * 8;
-          o[0] = blockIdx.x * E + ra % E; o[1] = ra / E; o[2] = blockIdx.x * E + rb % E; o[3] = rb / E;
+          o[0] = agent_at(blockIdx.x * E + ra % E); o[1] = ra / E; o[2] = agent_at(blockIdx.x * E + rb % E); o[3] = rb / E;
           o[4] = __float_as_int(Lpq[tid * kPairWords + 2]); o[5] = __float_as_int(Lpq[tid * kPairWords + 3]);
           o[6] = __float_as_int(Lpq[tid * kPairWords + 5]); o[7] = __float_as_int(Lpq[tid * kPairWords + 4]);
         }
@@ -2078,7 +2088,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   __syncthreads();
   TMARK(8);
   if (is_body) {
-    float* st = a.state + (size_t)b * N + env;
+    float* st = a.state + (size_t)b * N + agent;
     const size_t fs = (size_t)B * N;
     if (a.substeps > 0) {
       st[0 * fs] = x[0]; st[1 * fs] = x[1]; st[2 * fs] = x[2];
@@ -2134,7 +2144,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
   constexpr int pass = decltype(pass_c)::value;
   bool reset_now = false;
   if (tid < E && (blockIdx.x * E + tid) < N && (pass == 0 || Lrst[tid])) {
-    const int ee = tid, env_e = blockIdx.x * E + tid;
+    const int ee = tid, env_e = agent_at(blockIdx.x * E + tid);
     const int rb = M.root;
     float rx[3], rq[4], rv[3], rw[3];
     for (int c = 0; c < 3; ++c) rx[c] = Lpos[(rb * 7 + c) * E + ee];
@@ -2229,7 +2239,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     if (tid < E) Lrst[tid] = reset_now ? 1 : 0;
     if (__syncthreads_or(reset_now)) {
       if (is_body && Lrst[e]) {
-        float* st = a.state + (size_t)b * N + env;
+        float* st = a.state + (size_t)b * N + agent;
         const size_t fs = (size_t)B * N;
         for (int c = 0; c < 7; ++c) st[c * fs] = Lpos[(b * 7 + c) * E + e];
         for (int c = 0; c < 6; ++c) st[(7 + c) * fs] = Lvel[(b * kVS + c) * E + e];
@@ -2248,8 +2258,9 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const int ee = i % E, env_i = blockIdx.x * E + ee;
         if (env_i >= N) continue;
         const bool fresh = may_reset && Lrst[ee];
-        if (i < J * 6 * E) a.lam_j[(size_t)(i / E) * N + env_i] = fresh ? 0.0f : Lwj[i];
-        else a.lam_s[(size_t)((i - J * 6 * E) / E) * N + env_i] = fresh ? 0.0f : Lwc[i - J * 6 * E];
+        const int ag = agent_at(env_i);
+        if (i < J * 6 * E) a.lam_j[(size_t)(i / E) * N + ag] = fresh ? 0.0f : Lwj[i];
+        else a.lam_s[(size_t)((i - J * 6 * E) / E) * N + ag] = fresh ? 0.0f : Lwc[i - J * 6 * E];
       }
     }
   }
@@ -2260,7 +2271,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     for (int i = tid; i < n_here * obs_dim; i += kThreads) {
       const float o = Lobs[i];
       const int ee = i / obs_dim, k = i - ee * obs_dim;
-      obs_dst[(size_t)(env0 + ee) * obs_row + k] = o;
+      obs_dst[(size_t)agent_at(env0 + ee) * obs_row + k] = o;
     }
     if (M.height_map) {
       // Height map (Section 4.1, complex-terrain task): terrain height under a 15 x 11 grid that
@@ -2279,9 +2290,10 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         const float qw = Lpos[(rbb * 7 + 3) * E + ee], qx = Lpos[(rbb * 7 + 4) * E + ee];
         const float qy = Lpos[(rbb * 7 + 5) * E + ee], qz = Lpos[(rbb * 7 + 6) * E + ee];
         const float yaw = atan2f(2.0f * (qw * qz + qx * qy), 1.0f - 2.0f * (qy * qy + qz * qz));
-        Lhm[0 * E + ee] = cx + a.origins[3 * (env0 + ee)];
-        Lhm[1 * E + ee] = cy + a.origins[3 * (env0 + ee) + 1];
-        Lhm[2 * E + ee] = cz + a.origins[3 * (env0 + ee) + 2];
+        const int ag = agent_at(env0 + ee);
+        Lhm[0 * E + ee] = cx + a.origins[3 * ag];
+        Lhm[1 * E + ee] = cy + a.origins[3 * ag + 1];
+        Lhm[2 * E + ee] = cz + a.origins[3 * ag + 2];
         Lhm[3 * E + ee] = cosf(yaw); Lhm[4 * E + ee] = sinf(yaw);
       }
       __syncthreads();
@@ -2291,7 +2303,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           const float fw = M.hm_fwd[hi], lt = M.hm_lat[hj], c = Lhm[3 * E + ee], sn = Lhm[4 * E + ee];
         const float wx = Lhm[0 * E + ee] + (c * fw - sn * lt), wy = Lhm[1 * E + ee] + (sn * fw + c * lt);
         const float hz = terrain_height(M, a.heights, wx, wy) - Lhm[2 * E + ee];
-        obs_dst[(size_t)(env0 + ee) * obs_row + obs_dim + k] = hz;
+        obs_dst[(size_t)agent_at(env0 + ee) * obs_row + obs_dim + k] = hz;
       }
     }
   }

@@ -270,3 +270,128 @@ def test_bounded_contact_store_breaks_equal_gaps_by_the_smaller_key():
     ref.step(None, 1.0 / 240.0, 1, 2)
     k = ref.get_pair_contacts()
     assert list(zip(k["body_a"].tolist(), k["body_b"].tolist())) == [(0, 1), (0, 2)]
+
+
+# ---- interaction groups chosen from positions (agents that wander meet their actual neighbours)
+
+def _sphere_agents(n, origins, group):
+    p = free_params(gravity=(0.0, 0.0, 0.0), self_collide=0)
+    p.group_size = group
+    rob = scenes.make_single(radius=0.1, pos=(0.0, 0.0, 5.0), mass=1.0)
+    sc = single_scene(rob, params=p, num_envs=n)
+    sc.env_origins[:] = np.asarray(origins, np.float64)
+    return rob, sc
+
+
+def test_agents_grouped_by_hand_equal_the_merged_robot_whatever_their_numbers():
+    """Agents 0 and 3 of four, put into one group by a permutation, behave exactly like one robot
+    made of the same two free spheres with self-collision on (and like agents 0 and 1 of the
+    consecutive grouping); agents 1 and 2, far away, form the other group.  In their own order
+    (0,1 | 2,3) agents 0 and 3 pass through each other."""
+    rob2, sc2 = _two_spheres(1.0, 1.0)
+    org = [(0.0, 0.0, 0.0), (40.0, 0.0, 0.0), (80.0, 0.0, 0.0), (0.25, 0.0, 0.0)]
+    rob1, sc4 = _sphere_agents(4, org, 2)
+    a, b, c = oracle.OracleSim(sc2), oracle.OracleSim(sc4), oracle.OracleSim(sc4)
+    st = scenes.rest_state(rob2)
+    st[0, 0, 7:10], st[0, 1, 7:10] = (1.0, 0.2, 0.0), (-0.5, 0.0, 0.1)
+    a.set_state(st)
+    s4 = np.repeat(scenes.rest_state(rob1), 4, axis=0)
+    s4[0, 0, 7:10], s4[3, 0, 7:10] = st[0, 0, 7:10], st[0, 1, 7:10]
+    s4[1, 0, 7:10] = (0.0, 0.3, 0.0)   # a bystander that just drifts
+    b.set_state(s4); c.set_state(s4)
+    b.set_groups([0, 3, 2, 1])
+    assert b.get_groups().tolist() == [0, 3, 2, 1]
+    for _ in range(30):
+        a.substep_phases(None, 1.0 / 240.0, 6)
+        b.step(None, 1.0 / 240.0, 1, 6)
+        c.step(None, 1.0 / 240.0, 1, 6)
+    sa, sb, sc_ = a.get_state(), b.get_state(), c.get_state()
+    sb[3, 0, 0] += 0.25
+    assert np.allclose(sa[0, 0], sb[0, 0], atol=1e-12) and np.allclose(sa[0, 1], sb[3, 0], atol=1e-12)
+    pc = b.get_pair_contacts()
+    assert len(pc) == 1 and (pc["env_a"][0], pc["env_b"][0]) == (0, 3)    # reported by agent number
+    assert sb[1, 0, 8] == pytest.approx(0.3) and sb[1, 0, 1] == pytest.approx(0.3 * 30 / 240.0)
+    # their own order: nobody meets anybody
+    assert len(c.get_pair_contacts()) == 0 and sc_[0, 0, 7] == pytest.approx(1.0)
+    # not a permutation
+    with pytest.raises(ValueError):
+        b.set_groups([0, 0, 1, 2])
+    # back to their own order
+    b.set_groups(None)
+    assert b.get_groups().tolist() == [0, 1, 2, 3]
+
+
+def test_regrouping_orders_the_agents_along_the_z_curve_of_their_cells():
+    """Worked by hand on a 2 m grid: agents at cells (x,y) = (1,0) (0,0) (1,1) (0,1) (0,0) (3,2),
+    all in the positive quadrant (cell index + 32768 keeps the order).  Z-order interleaves the
+    bits with x lowest: (0,0) < (1,0) < (0,1) < (1,1) < ... < (3,2); the two agents of cell (0,0)
+    keep their numbers' order.  (Reach 0: nobody is anybody's neighbour, the groups are
+    consecutive agents of the order.)"""
+    org = [(3.0, 0.5, 0.0), (0.5, 1.9, 0.0), (2.1, 3.9, 0.0), (1.99, 2.0, 0.0), (0.0, 0.0, 0.0), (7.5, 4.5, 0.0)]
+    rob, sc = _sphere_agents(6, org, 2)
+    o = oracle.OracleSim(sc)
+    o.set_state(np.repeat(scenes.rest_state(rob), 6, axis=0))
+    o.regroup(2.0, 0.0)
+    assert o.get_groups().tolist() == [1, 4, 0, 3, 2, 5]
+    # the position counts, not the origin: agent 5 moved to cell (0,0)
+    st = o.get_state()
+    st[5, 0, 0:2] = (-7.0, -4.0)
+    o.set_state(st)
+    o.regroup(2.0, 0.0)
+    assert o.get_groups().tolist() == [1, 4, 5, 0, 3, 2]
+    # negative coordinates come before positive ones on each axis (floor, not truncation)
+    st[5, 0, 0:2] = (-7.6, -4.0)     # x = -0.1: cell (-1, 0)
+    o.set_state(st)
+    o.regroup(2.0, 0.0)
+    assert o.get_groups().tolist()[0] == 5
+
+
+def test_regrouping_puts_wandering_neighbours_into_one_group():
+    """Sixty-four agents numbered at random over a field in tight clumps of four, 30 m between
+    clumps.  In their own order almost every close pair is split between groups; after regrouping
+    with cells larger than a clump and smaller than the clump distance every clump that does not
+    straddle a cell border is one group (counted by brute force here), and a step then finds
+    contacts between clump mates only."""
+    rng = np.random.default_rng(11)
+    centres = np.stack(np.meshgrid(np.arange(4) * 30.0 + 7.0, np.arange(4) * 30.0 + 9.0), -1).reshape(16, 2)
+    pts = np.repeat(centres, 4, axis=0) + np.tile(np.array([[0, 0], [0.19, 0], [0, 0.19], [0.19, 0.19]]), (16, 1))
+    perm = rng.permutation(64)
+    org = np.zeros((64, 3)); org[perm, 0:2] = pts          # agent perm[k] stands at point k
+    rob, sc = _sphere_agents(64, org, 4)
+    o = oracle.OracleSim(sc)
+    o.set_state(np.repeat(scenes.rest_state(rob), 64, axis=0))
+    near, split = o.count_near_pairs(0.5)
+    assert near == 16 * 6 and split > 80
+    o.regroup(8.0, 0.5)
+    groups = o.get_groups().reshape(16, 4)
+    clump_of = np.empty(64, int); clump_of[perm] = np.arange(64) // 4
+    assert all(len(set(clump_of[g])) == 1 for g in groups)
+    assert o.count_near_pairs(0.5) == (96, 0)
+    o.step(None, 1.0 / 240.0, 1, 4)
+    pc = o.get_pair_contacts()
+    assert len(pc) == 16 * 4    # the four sides of each square touch (0.19 < 0.2), the diagonals do not
+    assert np.array_equal(clump_of[pc["env_a"]], clump_of[pc["env_b"]])
+
+
+def test_regrouping_grows_groups_from_neighbours_inside_a_window():
+    """Eight agents in one cell (one window), groups of 2, reach 1 m.  Along x: agents 0..7 at
+    0, 10, 0.5, 10.4, 20, 30, 20.9, 0.9.  Order in the cell: by number.  Agent 0 starts the first
+    group and takes its first free neighbour, 2 (0.5 m; 7 at 0.9 m comes later in the order);
+    agent 1 takes 3; agent 4 takes 6; agent 5 has no neighbour and takes the first free agent, 7
+    (whose neighbours 0 and 2 are gone)."""
+    xs = [0.0, 10.0, 0.5, 10.4, 20.0, 30.0, 20.9, 0.9]
+    rob, sc = _sphere_agents(8, [(x, 1.0, 0.0) for x in xs], 2)
+    o = oracle.OracleSim(sc)
+    o.set_state(np.repeat(scenes.rest_state(rob), 8, axis=0))
+    o.regroup(100.0, 1.0)
+    assert o.get_groups().tolist() == [0, 2, 1, 3, 4, 6, 5, 7]
+    assert o.count_near_pairs(1.0) == (5, 2)     # 0-2, 0-7, 2-7, 1-3, 4-6; apart: 0-7, 2-7
+    # groups of 4: a group keeps growing through the neighbours of its members: 0, 2, 7 (a
+    # neighbour of both), then, nobody within reach being left, the first free agent, 1; agent 3
+    # starts the second group, has no free neighbour and takes 4, then 4's neighbour 6, then 5
+    sc.params.group_size = 4
+    o4 = oracle.OracleSim(sc)
+    o4.set_state(np.repeat(scenes.rest_state(rob), 8, axis=0))
+    o4.regroup(100.0, 1.0)
+    assert o4.get_groups().tolist() == [0, 2, 7, 1, 3, 4, 6, 5]
+    assert o4.count_near_pairs(1.0) == (5, 1)    # only 1-3 stay apart
