@@ -123,6 +123,10 @@ def main():
     ap.add_argument("--self-collide", action="store_true", help="capsules of one robot collide with each other")
     ap.add_argument("--group-size", type=int, default=1, help="agents per interaction group (inter-agent collisions)")
     ap.add_argument("--spacing", type=float, default=1.5, help="distance between the agents of a group, metres")
+    ap.add_argument("--crowd", type=float, default=0.0,
+                    help="with --group-size: all agents share one scene at this many agents per square metre, numbered "
+                         "in no spatial order; the groups are then chosen from the positions (see --regroup-every)")
+    ap.add_argument("--regroup-every", type=int, default=10, help="steps between two sim_regroup calls (--crowd)")
     ap.add_argument("--task", action="store_true", help="task logic of Section 4.1: pushes, flagrun targets, grace period, auto-reset")
     ap.add_argument("--warm-start", type=float, default=0.0, help="share of the last substep's impulses the rows start from (0 = off)")
     ap.add_argument("--iterations", type=int, default=0, help="override the sweeps per substep (the workload is then named for it)")
@@ -170,6 +174,21 @@ def main():
         scene.params.group_size = args.group_size
         scene = scenes.make_scene(scene.robot, scene.terrain, scene.num_envs, seed=cfg["seed"], params=scene.params,
                                   name=cfg["name"], spacing=args.spacing if args.group_size > 1 else None)
+    crowd = args.crowd > 0 and args.group_size > 1
+    if crowd:
+        # one shared scene: on the heightfield the crowd stands in the middle of the field, every agent
+        # lifted onto the terrain under it
+        hf = scene.terrain.kind != 0
+        side = float(np.sqrt(scene.num_envs / args.crowd))
+        if hf and side > min(scene.terrain.extent) - 4.0:
+            print(f"bench.py: a crowd of {scene.num_envs} at {args.crowd}/m2 needs {side:.0f} m, the heightfield has "
+                  f"{min(scene.terrain.extent):.1f} m; use fewer agents (--num-envs) or a plane configuration", file=sys.stderr)
+            sys.exit(2)
+        base = tuple(np.asarray(scene.terrain.origin[:2]) + 0.5 * (np.asarray(scene.terrain.extent) - side)) if hf else (0.0, 0.0)
+        org = scenes.crowd_origins(scene.num_envs, args.crowd, cfg["seed"], base=base)
+        if hf:
+            org[:, 2] = [scenes.terrain_height_max_near(scene.terrain, x, y, 0.5) for x, y in org[:, 0:2]]
+        scene.env_origins = org.astype(np.float32).astype(np.float64)
     N, rob = scene.num_envs, scene.robot
     sim = P.Sim(scene, device=dev)
     if args.envs_per_block:
@@ -193,9 +212,13 @@ def main():
     if cfg.get("fallen") and task is None:
         retarget = [torch.as_tensor(scenes.targets_for_step(cfg["seed"], 200 * e, N)).to(dev) for e in range(8)]
 
+    regroup_cell, regroup_reach = 2.4, 1.2     # metres: root bodies of two touching humanoids are at most about this far apart
+
     def one_step(k, may_retarget=True):
         if retarget is not None and may_retarget and k % 200 == 0:
             P.sim_set_targets(sim.h, retarget[(k // 200) % 8].data_ptr(), stream)
+        if crowd and may_retarget and k % args.regroup_every == 0:
+            P.sim_regroup(sim.h, regroup_cell, regroup_reach, stream)
         # sim_step + sim_get_obs in their one-launch form: the step kernel writes obs, reward and
         # done straight into the caller's tensors
         P.sim_step_obs(sim.h, ring[k % 16].data_ptr(), dt, sub, its, obs.data_ptr(), rew.data_ptr(), done.data_ptr(),
@@ -245,7 +268,7 @@ def main():
     achieved_tflops = fl * N / (kern_ms * 1e-3) / 1e12
     workload = ((cfg["name"] if not args.num_envs else f"{cfg['name']}_n{N}") + ("_heightmap" if args.height_map else "")
                 + ("_selfcollide" if args.self_collide else "") + (f"_group{args.group_size}" if args.group_size > 1 else "")
-                + ("_task" if args.task else "") + (f"_warm{args.warm_start:g}" if args.warm_start > 0 else "")
+                + (f"_crowd{args.crowd:g}" if crowd else "") + ("_task" if args.task else "") + (f"_warm{args.warm_start:g}" if args.warm_start > 0 else "")
                 + (f"_its{args.iterations}" if args.iterations > 0 else "")
                 + (f"_newton{cfg['iterations']}x{args.krylov}" if args.solver == "newton" else "")
                 + (f"_epb{args.envs_per_block}" if args.envs_per_block else ""))
@@ -265,6 +288,24 @@ def main():
                      "capsule_contacts_per_env": round(len(pc) / N, 3),
                      "capsule_contacts_between_agents_per_env": round(float((pc["env_a"] != pc["env_b"]).sum()) / N, 3),
                      "capsule_contacts_dropped": dropped}
+        if crowd:
+            # how well the groups chosen from the positions cover the agents that are close to each other
+            near_now = sim.count_near_pairs(regroup_reach)
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(20):
+                P.sim_regroup(sim.h, regroup_cell, regroup_reach, stream)
+            ev1.record()
+            torch.cuda.synchronize(dev)
+            near_re = sim.count_near_pairs(regroup_reach)
+            sim.set_groups(None)
+            near_own = sim.count_near_pairs(regroup_reach)
+            pair_info.update({"crowd_agents_per_m2": args.crowd, "regroup_every_steps": args.regroup_every,
+                              "regroup_cell_m": regroup_cell, "regroup_reach_m": regroup_reach,
+                              "regroup_ms": ev0.elapsed_time(ev1) / 20,
+                              "agent_pairs_within_reach": near_now[0],
+                              "of_them_in_different_groups": {"as_stepped": near_now[1], "just_regrouped": near_re[1],
+                                                              "in_number_order": near_own[1]}})
     peak_tflops = 157.3
     value = N * args.steps / elapsed
     out = {

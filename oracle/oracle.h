@@ -200,12 +200,15 @@ int64_t oracle_set_pair_cap(oracle_sim*, int32_t cap, int32_t envs_per_unit);
 /* Interaction groups chosen from where the agents are (Section 3.1: all agents share one scene;
  * Section 4.1: the agents of the flagrun tasks collide with each other).  Groups are G consecutive
  * *places*; place p holds agent place_env[p] (at creation: agent p).  oracle_regroup orders the
- * agents along the Z-order curve of a uniform grid of `cell` metres over the ground plane (an
- * agent's cell is that of its root body's world position, cell index floor(p / cell) + 32768
- * clamped to 16 bits per axis, x in the even bits; ties by agent number); then, inside windows of
- * (64 / G) G consecutive agents of that order, groups are grown by who is within `reach` of whom
- * (root bodies): the first free agent of the window starts a group, which takes, while it has
- * room, the first free agent within reach of any member, else the first free agent.  The places
+ * agents along the Hilbert curve (order 16) through the cells of a uniform grid of `cell` metres
+ * over the ground plane (an agent's cell is that of its root body's world position, cell index
+ * floor(p / cell) + 32768 clamped to 16 bits per axis; ties by agent number); then, inside windows
+ * of (256 / G) G consecutive agents of that order, agents whose root bodies are within `reach`
+ * of each other are put together: in window order every free agent with a free neighbour starts
+ * a cluster that takes, up to G members, the first free neighbour of any member; the clusters
+ * are laid out one after another, one that does not fit into the group being filled moves on to
+ * the next group and the gap is closed with agents that have no free neighbour (else with the
+ * cluster's first members); the remaining agents come last.  The places
  * are handed out group by group.  oracle_set_groups takes any permutation (NULL: agents in their
  * own order; returns -1 if it is none).  oracle_count_near_pairs: counts[0] = agent pairs whose
  * root bodies are within `reach`, counts[1] = those of them in different groups.  All of these

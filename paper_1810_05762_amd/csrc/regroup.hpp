@@ -2,8 +2,8 @@
 // Section 4.1: the agents of the flagrun tasks collide with each other).
 //
 // A uniform grid over the ground plane; an agent's cell is that of its root body's world position;
-// the agents are ordered along the Z-order curve of the cells (ties: agent number), which puts
-// agents that stand close together mostly close together in the order; windows of up to 64
+// the agents are ordered along the Hilbert curve through the cells (ties: agent number), which puts
+// agents that stand close together mostly close together in the order; windows of up to 256
 // consecutive agents of that order are then split into groups by who is within reach of whom.
 // The places of the launch (a workgroup holds consecutive places, a group consecutive places of a
 // workgroup) are handed out in the resulting order.
@@ -17,13 +17,22 @@ namespace sim355 {
 
 #pragma clang fp contract(off)
 
-__device__ __forceinline__ uint32_t spread_bits16(uint32_t v) {
-  v &= 0xffffu;
-  v = (v | (v << 8)) & 0x00ff00ffu;
-  v = (v | (v << 4)) & 0x0f0f0f0fu;
-  v = (v | (v << 2)) & 0x33333333u;
-  v = (v | (v << 1)) & 0x55555555u;
-  return v;
+// Position of cell (x, y), 16 bits each, along the Hilbert curve of order 16 (Hilbert 1891; the
+// usual bit-by-bit form): from the top bit down, the quadrant (rx, ry) adds ((3 rx) xor ry) times
+// the quadrant's size, and the coordinates inside it are reflected and exchanged so that the curve
+// of the next level starts where this one enters the quadrant.
+__device__ __forceinline__ uint32_t hilbert_index16(uint32_t x, uint32_t y) {
+  uint32_t d = 0;
+  for (uint32_t s = 32768u; s > 0; s >>= 1) {
+    const uint32_t rx = (x & s) ? 1u : 0u, ry = (y & s) ? 1u : 0u;
+    d += s * s * ((3u * rx) ^ ry);
+    x &= s - 1u; y &= s - 1u;          // inside the quadrant
+    if (ry == 0u) {
+      if (rx == 1u) { x = (s - 1u) - x; y = (s - 1u) - y; }
+      const uint32_t t = x; x = y; y = t;
+    }
+  }
+  return d;
 }
 
 // cell index along one axis, moved into 0 .. 65535 (clamped; NaN goes to 0)
@@ -40,14 +49,14 @@ __device__ __forceinline__ void root_world(const float* __restrict__ state, cons
   for (int c = 0; c < 3; ++c) p[c] = state[((size_t)c * B + root) * N + i] + origins[3 * i + c];
 }
 
-// words[i] = (Z-order key of agent i's cell) << 32 | i
+// words[i] = (position of agent i's cell along the curve) << 32 | i
 __global__ void order_words_kernel(const float* __restrict__ state, const float* __restrict__ origins, int B, int N, int root,
                                    float cell, unsigned long long* __restrict__ words) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
   float p[3];
   root_world(state, origins, B, N, root, i, p);
-  const uint32_t key = spread_bits16(cell_coord(p[0], cell)) | (spread_bits16(cell_coord(p[1], cell)) << 1);
+  const uint32_t key = hilbert_index16(cell_coord(p[0], cell), cell_coord(p[1], cell));
   words[i] = ((unsigned long long)key << 32) | (unsigned)i;
 }
 
@@ -71,18 +80,25 @@ __global__ void rank_places_kernel(const unsigned long long* __restrict__ words,
 }
 
 // Second pass: the agents of a window of W consecutive places (W a multiple of the group size G, at
-// most 64; one wavefront per window) are put into groups by who is close to whom rather than by
+// most 256; one workgroup per window) are put into groups by who is close to whom rather than by
 // their order along the curve.  Two agents are neighbours if their root bodies are within `reach`.
-// Groups are grown one after another: the first agent of the window not yet in a group starts
-// one; as long as the group has room it takes the first agent (in window order) that is a
-// neighbour of any of its members and still free, or, if there is none, the first free agent.
+//  1. Clusters: in window order, every agent that is still free and has a free neighbour starts a
+//     cluster, which takes, while it has fewer than G members, the first free agent (in window
+//     order) that is a neighbour of any of its members.  What stays free has no free neighbour.
+//  2. Packing: the clusters are laid out one after another; a cluster that does not fit into the
+//     group being filled goes to the next one, and the gap is closed with free agents (in window
+//     order) or, when they have run out, with the first members of that cluster.  The remaining
+//     free agents follow.  Groups are every G consecutive agents of this layout.
 // place_env holds the order along the curve on entry and the final places on return; a window
 // only touches its own places.
+constexpr int kWindow = 256;
 __global__ void cluster_windows_kernel(const float* __restrict__ state, const float* __restrict__ origins, int B, int N,
                                        int root, int G, int W, float reach, int32_t* __restrict__ place_env) {
-  __shared__ float wp[3][64];
-  __shared__ unsigned long long adj[64];
-  __shared__ int agent_of[64], pick[64];
+  __shared__ float wp[3][kWindow];
+  __shared__ unsigned long long adj[kWindow][4];
+  __shared__ unsigned long long free_mask[4], frontier[4];
+  __shared__ int agent_of[kWindow];
+  __shared__ short seq[kWindow], csize[kWindow / 2], pick[kWindow];
   const int lane = threadIdx.x, w0 = blockIdx.x * W;
   const int n = min(W, N - w0);
   float p[3] = {0.0f, 0.0f, 0.0f};
@@ -93,30 +109,67 @@ __global__ void cluster_windows_kernel(const float* __restrict__ state, const fl
   wp[0][lane] = p[0]; wp[1][lane] = p[1]; wp[2][lane] = p[2];
   __syncthreads();
   const float r2 = reach * reach;
-  unsigned long long mine = 0ull;
+  unsigned long long mine[4] = {0ull, 0ull, 0ull, 0ull};
   if (lane < n)
     for (int k = 0; k < n; ++k) {
       const float dx = p[0] - wp[0][k], dy = p[1] - wp[1][k], dz = p[2] - wp[2][k];
       const float d2 = (dx * dx + dy * dy) + dz * dz;
-      if (k != lane && d2 <= r2) mine |= 1ull << k;
+      if (k != lane && d2 <= r2) mine[k >> 6] |= 1ull << (k & 63);
     }
-  adj[lane] = mine;
+  for (int w = 0; w < 4; ++w) adj[lane][w] = mine[w];
   __syncthreads();
   if (lane == 0) {
-    unsigned long long free_mask = n == 64 ? ~0ull : ((1ull << n) - 1ull);
-    int out = 0;
-    while (free_mask) {
-      const int seed = __ffsll((long long)free_mask) - 1;
-      free_mask &= ~(1ull << seed);
-      unsigned long long frontier = adj[seed] & free_mask;
-      pick[out++] = seed;
-      for (int cnt = 1; cnt < G && free_mask; ++cnt) {
-        const int nx = __ffsll((long long)(frontier ? frontier : free_mask)) - 1;
-        free_mask &= ~(1ull << nx);
-        frontier = (frontier | adj[nx]) & free_mask;
-        pick[out++] = nx;
-      }
+    for (int w = 0; w < 4; ++w) {
+      const int lo = 64 * w;
+      free_mask[w] = n >= lo + 64 ? ~0ull : (n > lo ? (1ull << (n - lo)) - 1ull : 0ull);
     }
+    auto first_of = [&](const unsigned long long* m) -> int {
+      for (int w = 0; w < 4; ++w) if (m[w]) return 64 * w + __ffsll((long long)m[w]) - 1;
+      return -1;
+    };
+    // 1. clusters
+    int n_seq = 0, n_cl = 0;
+    for (int seed = 0; seed < n; ++seed) {
+      if (!((free_mask[seed >> 6] >> (seed & 63)) & 1ull)) continue;
+      unsigned long long any = 0ull;
+      for (int w = 0; w < 4; ++w) { frontier[w] = adj[seed][w] & free_mask[w]; any |= frontier[w]; }
+      if (!any) continue;
+      free_mask[seed >> 6] &= ~(1ull << (seed & 63));
+      seq[n_seq++] = (short)seed;
+      int cnt = 1;
+      while (cnt < G) {
+        const int nx = first_of(frontier);
+        if (nx < 0) break;
+        free_mask[nx >> 6] &= ~(1ull << (nx & 63));
+        seq[n_seq++] = (short)nx;
+        ++cnt;
+        for (int w = 0; w < 4; ++w) frontier[w] = (frontier[w] | adj[nx][w]) & free_mask[w];
+      }
+      csize[n_cl++] = (short)cnt;
+    }
+    // 2. packing
+    auto next_single = [&]() -> int {
+      const int sgl = first_of(free_mask);
+      if (sgl >= 0) free_mask[sgl >> 6] &= ~(1ull << (sgl & 63));
+      return sgl;
+    };
+    int out = 0, pos = 0, filled = 0;
+    for (int c = 0; c < n_cl; ++c) {
+      int sz = csize[c];
+      if (filled + sz > G) {
+        while (filled < G) {
+          const int sgl = next_single();
+          if (sgl < 0) break;
+          pick[out++] = (short)sgl; ++filled;
+        }
+        for (; filled < G; ++filled, --sz) pick[out++] = seq[pos++];
+        filled = 0;
+      }
+      for (int t = 0; t < sz; ++t) pick[out++] = seq[pos++];
+      filled += sz;
+      if (filled == G) filled = 0;
+    }
+    for (int sgl = next_single(); sgl >= 0; sgl = next_single()) pick[out++] = (short)sgl;
   }
   __syncthreads();
   if (lane < n) place_env[w0 + lane] = agent_of[pick[lane]];

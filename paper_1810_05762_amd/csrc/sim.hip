@@ -917,8 +917,8 @@ extern "C" int sim_regroup(sim_t* s, float cell, float reach, void* stream) {
   hipLaunchKernelGGL(rank_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, words, s->N,
                      reinterpret_cast<int32_t*>(s->ws + s->lay.place_env));
   HIP_TRY(hipGetLastError());
-  const int W = (64 / m.group) * m.group;   // window of the second pass: whole groups, one wavefront
-  hipLaunchKernelGGL(cluster_windows_kernel, dim3((s->N + W - 1) / W), dim3(64), 0, st,
+  const int W = (kWindow / m.group) * m.group;   // window of the second pass: whole groups, one workgroup
+  hipLaunchKernelGGL(cluster_windows_kernel, dim3((s->N + W - 1) / W), dim3(kWindow), 0, st,
                      reinterpret_cast<const float*>(s->ws + s->lay.state),
                      reinterpret_cast<const float*>(s->ws + s->lay.origins), m.B, s->N, m.root, m.group, W, reach,
                      reinterpret_cast<int32_t*>(s->ws + s->lay.place_env));

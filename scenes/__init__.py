@@ -13,7 +13,7 @@ from .robots import (Robot, make_ant, make_humanoid, make_chain, make_single, ma
                      capsule_mass_inertia, collision_pairs, LOCK, HINGE)
 from .terrain import (Terrain, make_plane, make_heightfield, make_flat_heightfield,
                       make_tilted_heightfield, terrain_height_max_near, PLANE, HEIGHTFIELD)
-from .workloads import (Scene, SimParams, TaskParams, make_scene, config_scene, CONFIGS,
+from .workloads import (Scene, SimParams, TaskParams, make_scene, config_scene, crowd_origins, CONFIGS,
                         actions_for_step, targets_for_step, fallen_states, rest_state,
                         posed_state, env_grid_origins)
 
@@ -22,7 +22,7 @@ __all__ = [
     "capsule_mass_inertia", "collision_pairs",
     "LOCK", "HINGE", "Terrain", "make_plane", "make_heightfield", "make_flat_heightfield",
     "make_tilted_heightfield", "terrain_height_max_near", "PLANE", "HEIGHTFIELD",
-    "Scene", "SimParams", "TaskParams", "make_scene", "config_scene", "CONFIGS",
+    "Scene", "SimParams", "TaskParams", "make_scene", "config_scene", "crowd_origins", "CONFIGS",
     "actions_for_step", "targets_for_step", "fallen_states", "rest_state", "posed_state",
     "env_grid_origins",
 ]

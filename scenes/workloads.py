@@ -106,6 +106,23 @@ def env_group_origins(terrain, num_envs, group_size, spacing, seed):
     return o.astype(np.float32).astype(np.float64)
 
 
+def crowd_origins(num_envs, density, seed, min_dist=0.5, base=(0.0, 0.0)):
+    """Origins for agents that share one scene (Section 3.1, last paragraph): a square with
+    `density` agents per square metre, one agent per cell of a jittered grid (no two closer than
+    about min_dist), numbered in no spatial order, so that consecutive numbers are mostly far
+    apart.  z = 0 (the caller lifts them onto a heightfield)."""
+    rng = np.random.Generator(np.random.Philox(key=int(seed) + 991))
+    side = float(np.sqrt(num_envs / density))
+    k = int(np.ceil(np.sqrt(num_envs)))
+    cell = side / k
+    idx = rng.permutation(k * k)[:num_envs]
+    jit = max(cell - min_dist, 0.0)
+    o = np.zeros((num_envs, 3), np.float64)
+    o[:, 0] = base[0] + (idx % k + 0.5) * cell + rng.uniform(-0.5, 0.5, num_envs) * jit
+    o[:, 1] = base[1] + (idx // k + 0.5) * cell + rng.uniform(-0.5, 0.5, num_envs) * jit
+    return o.astype(np.float32).astype(np.float64)
+
+
 def make_scene(robot, terrain, num_envs, seed=0, params=None, name="", spacing=None):
     """`spacing` (with params.group_size > 1) places the agents of a group that far apart."""
     params = params or SimParams()

@@ -321,29 +321,46 @@ def test_agents_grouped_by_hand_equal_the_merged_robot_whatever_their_numbers():
     assert b.get_groups().tolist() == [0, 1, 2, 3]
 
 
-def test_regrouping_orders_the_agents_along_the_z_curve_of_their_cells():
-    """Worked by hand on a 2 m grid: agents at cells (x,y) = (1,0) (0,0) (1,1) (0,1) (0,0) (3,2),
-    all in the positive quadrant (cell index + 32768 keeps the order).  Z-order interleaves the
-    bits with x lowest: (0,0) < (1,0) < (0,1) < (1,1) < ... < (3,2); the two agents of cell (0,0)
-    keep their numbers' order.  (Reach 0: nobody is anybody's neighbour, the groups are
-    consecutive agents of the order.)"""
-    org = [(3.0, 0.5, 0.0), (0.5, 1.9, 0.0), (2.1, 3.9, 0.0), (1.99, 2.0, 0.0), (0.0, 0.0, 0.0), (7.5, 4.5, 0.0)]
-    rob, sc = _sphere_agents(6, org, 2)
+def test_regrouping_orders_the_agents_along_the_hilbert_curve_of_their_cells():
+    """What defines the curve: it visits every cell of an aligned 2^k x 2^k block once, and
+    consecutive cells share an edge.  One agent per cell of the 8 x 8 block of 2 m cells whose
+    corner is (16 m, -32 m) (negative coordinates included), numbered at random, reach 0 (nobody
+    is anybody's neighbour: the groups are consecutive agents of the order).  A second agent in
+    one of the cells comes right after the first one (equal cells: by agent number)."""
+    rng = np.random.default_rng(4)
+    cells = np.stack(np.meshgrid(np.arange(8), np.arange(8)), -1).reshape(64, 2)
+    num = rng.permutation(64)
+    org = np.zeros((65, 3))
+    org[num, 0:2] = cells * 2.0 + np.array([16.0, -32.0]) + rng.uniform(0.05, 1.95, size=(64, 2))
+    org[64, 0:2] = np.floor(org[num[20], 0:2] / 2.0) * 2.0 + 1.0   # in the cell of agent num[20], not on top of it
+    rob, sc = _sphere_agents(65, org, 2)
     o = oracle.OracleSim(sc)
-    o.set_state(np.repeat(scenes.rest_state(rob), 6, axis=0))
+    o.set_state(np.repeat(scenes.rest_state(rob), 65, axis=0))
     o.regroup(2.0, 0.0)
-    assert o.get_groups().tolist() == [1, 4, 0, 3, 2, 5]
-    # the position counts, not the origin: agent 5 moved to cell (0,0)
+    order = o.get_groups()
+    assert sorted(order.tolist()) == list(range(65))
+    k = order.tolist().index(64)
+    assert order[k - 1] == num[20]
+    walk = np.floor(org[np.delete(order, k), 0:2] / 2.0).astype(int)
+    assert len({tuple(c) for c in walk}) == 64
+    assert np.all(np.abs(np.diff(walk, axis=0)).sum(1) == 1)
+    # the position counts, not the origin: every agent moved by one block along x walks through
+    # the neighbouring block the same way (edge by edge; the block itself may be turned)
     st = o.get_state()
-    st[5, 0, 0:2] = (-7.0, -4.0)
+    st[:, 0, 0] += 16.0
     o.set_state(st)
     o.regroup(2.0, 0.0)
-    assert o.get_groups().tolist() == [1, 4, 5, 0, 3, 2]
-    # negative coordinates come before positive ones on each axis (floor, not truncation)
-    st[5, 0, 0:2] = (-7.6, -4.0)     # x = -0.1: cell (-1, 0)
-    o.set_state(st)
-    o.regroup(2.0, 0.0)
-    assert o.get_groups().tolist()[0] == 5
+    order2 = o.get_groups()
+    walk2 = np.floor((org[order2[order2 != 64], 0:2] + np.array([16.0, 0.0])) / 2.0).astype(int)
+    assert walk2[:, 0].min() == 16 and len({tuple(c) for c in walk2}) == 64
+    assert np.all(np.abs(np.diff(walk2, axis=0)).sum(1) == 1)
+    # floor, not truncation: an agent at x = -0.1 lies in cell -1, not in cell 0 with the one at +0.1
+    rob2, sc2 = _sphere_agents(3, [(0.1, 0.5, 0.0), (-0.1, 0.5, 0.0), (0.3, 0.5, 0.0)], 2)
+    o2 = oracle.OracleSim(sc2)
+    o2.set_state(np.repeat(scenes.rest_state(rob2), 3, axis=0))
+    o2.regroup(2.0, 0.0)
+    g = o2.get_groups().tolist()
+    assert abs(g.index(0) - g.index(2)) == 1 and g.index(1) in (0, 2)
 
 
 def test_regrouping_puts_wandering_neighbours_into_one_group():
@@ -374,11 +391,14 @@ def test_regrouping_puts_wandering_neighbours_into_one_group():
 
 
 def test_regrouping_grows_groups_from_neighbours_inside_a_window():
-    """Eight agents in one cell (one window), groups of 2, reach 1 m.  Along x: agents 0..7 at
-    0, 10, 0.5, 10.4, 20, 30, 20.9, 0.9.  Order in the cell: by number.  Agent 0 starts the first
-    group and takes its first free neighbour, 2 (0.5 m; 7 at 0.9 m comes later in the order);
-    agent 1 takes 3; agent 4 takes 6; agent 5 has no neighbour and takes the first free agent, 7
-    (whose neighbours 0 and 2 are gone)."""
+    """Eight agents in one cell (one window), reach 1 m.  Along x: agents 0..7 at
+    0, 10, 0.5, 10.4, 20, 30, 20.9, 0.9 (order inside the cell: by number).
+    Groups of 2.  Clusters: 0 takes its first free neighbour 2 (7, also within reach, comes later
+    in the order) and is full; 1 takes 3; 4 takes 6; 5 and 7 have no free neighbour.  Layout:
+    [0 2] [1 3] [4 6] then the free agents [5 7].
+    Groups of 4.  Clusters: {0, 2, 7} (7 is a neighbour of both), {1, 3}, {4, 6}.  Layout: 0 2 7,
+    then {1, 3} does not fit any more: the gap is closed with the free agent 5, [0 2 7 5]; then
+    [1 3 4 6]."""
     xs = [0.0, 10.0, 0.5, 10.4, 20.0, 30.0, 20.9, 0.9]
     rob, sc = _sphere_agents(8, [(x, 1.0, 0.0) for x in xs], 2)
     o = oracle.OracleSim(sc)
@@ -386,12 +406,23 @@ def test_regrouping_grows_groups_from_neighbours_inside_a_window():
     o.regroup(100.0, 1.0)
     assert o.get_groups().tolist() == [0, 2, 1, 3, 4, 6, 5, 7]
     assert o.count_near_pairs(1.0) == (5, 2)     # 0-2, 0-7, 2-7, 1-3, 4-6; apart: 0-7, 2-7
-    # groups of 4: a group keeps growing through the neighbours of its members: 0, 2, 7 (a
-    # neighbour of both), then, nobody within reach being left, the first free agent, 1; agent 3
-    # starts the second group, has no free neighbour and takes 4, then 4's neighbour 6, then 5
     sc.params.group_size = 4
     o4 = oracle.OracleSim(sc)
     o4.set_state(np.repeat(scenes.rest_state(rob), 8, axis=0))
     o4.regroup(100.0, 1.0)
-    assert o4.get_groups().tolist() == [0, 2, 7, 1, 3, 4, 6, 5]
-    assert o4.count_near_pairs(1.0) == (5, 1)    # only 1-3 stay apart
+    assert o4.get_groups().tolist() == [0, 2, 7, 5, 1, 3, 4, 6]
+    assert o4.count_near_pairs(1.0) == (5, 0)
+    # Agents 0..4 in a row 0.9 m apart plus a far pair 5, 6, groups of 4: clusters {0,1,2,3}
+    # (full; 4's only neighbour 3 is taken, so 4 stays free) and {5, 6}.  Layout [0 1 2 3] [5 6 4]
+    rob7, sc7 = _sphere_agents(7, [(0.9 * k, 1.0, 0.0) for k in range(5)] + [(50.0, 1.0, 0.0), (50.5, 1.0, 0.0)], 4)
+    o7 = oracle.OracleSim(sc7)
+    o7.set_state(np.repeat(scenes.rest_state(rob7), 7, axis=0))
+    o7.regroup(1000.0, 1.0)
+    assert o7.get_groups().tolist() == [0, 1, 2, 3, 5, 6, 4]
+    # groups of 3 on the same row: clusters {0,1,2}, {3,4}, {5,6}; {5,6} does not fit behind {3,4},
+    # no free agent: its first member closes the gap: [0 1 2] [3 4 5] [6]
+    sc7.params.group_size = 3
+    o3 = oracle.OracleSim(sc7)
+    o3.set_state(np.repeat(scenes.rest_state(rob7), 7, axis=0))
+    o3.regroup(1000.0, 1.0)
+    assert o3.get_groups().tolist() == [0, 1, 2, 3, 4, 5, 6]
