@@ -131,7 +131,7 @@ typedef struct sim_desc {
    * the solution; 0.1 keeps single and double precision on the same branches); the `iterations` of
    * sim_step are then Newton iterations per substep (3 with 8 inner iterations is a sensible start).  It solves the joints
    * far more stiffly per unit of work where loads are carried (a hanging chain does not sag), costs
-   * about 2.5 times a 20-sweep step, runs at most 8 envs per workgroup, and is not available together
+   * about 3.3 times a 20-sweep step, runs at most 8 envs per workgroup, and is not available together
    * with the warm start or capsule-capsule collisions (SIM_ERR_ARG). */
   int32_t solver;
   int32_t krylov_iterations;

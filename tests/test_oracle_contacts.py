@@ -244,3 +244,32 @@ def test_plane_contact_record_closed_form():
     assert c[1]["active"] == 1 and c[0]["active"] == 0
     np.testing.assert_allclose(c[1]["n"], (0, 0, 1))
     np.testing.assert_allclose(c[1]["rc"], (0.2 * np.cos(ang), 0, -0.2 * np.sin(ang) - 0.05), atol=1e-12)
+
+
+def test_outside_the_heightfield_there_is_no_terrain():
+    """Reading of this build (the border is not extended outwards): a sphere 1 cm above a flat
+    field of height 0.2 m touches it while its centre is over the field, touches the border edge
+    / corner while it is within reach of it, and touches nothing beyond: it keeps falling."""
+    t = scenes.make_flat_heightfield(nx=12, ny=12, cell=0.1)          # extent 1.1 x 1.1 m
+    t.heights[:] = 0.2
+    r = 0.05
+    rob = scenes.make_single(radius=r, pos=(0.0, 0.0, 0.0), mass=1.0)
+    xs = [0.5, 1.09, 1.1 + 0.03, 1.1 + r + 0.03, 3.0, -0.03, -(r + 0.03), -2.0]
+    sc = single_scene(rob, t, params=free_params(), num_envs=len(xs))
+    sc.env_origins[:] = 0.0
+    st = np.zeros((len(xs), 1, 13))
+    st[:, 0, 0], st[:, 0, 1], st[:, 0, 2], st[:, 0, 3] = xs, 0.55, 0.2 + r + 0.01, 1.0
+    o = oracle.OracleSim(sc)
+    o.set_state(st)
+    con = o.generate_contacts(False)
+    active = con["active"][:, 0].astype(bool)
+    assert active.tolist() == [True, True, True, False, False, True, False, False]
+    assert np.array_equal(active, o.generate_contacts(True)["active"][:, 0].astype(bool))
+    # over the field: the face under it, 1 cm away; beyond the border but within reach: the border edge
+    assert con["d"][0, 0] == pytest.approx(0.01, abs=1e-6) and con["n"][0, 0] == pytest.approx([0, 0, 1], abs=1e-6)
+    assert con["d"][2, 0] == pytest.approx(np.hypot(0.03, r + 0.01) - r, abs=1e-6) and con["n"][2, 0, 0] > 0.3
+    for _ in range(30):
+        o.step(None, 1.0 / 60.0, 2, 8)
+    z = o.get_state()[:, 0, 2]
+    # over the field it rests; beyond the border it falls (also after rolling off the border edge)
+    assert np.all(z[:2] > 0.2 + r - 2e-3) and np.all(z[2:] < 0.0)
