@@ -188,15 +188,23 @@ typedef struct sim_pair_contact_rec {
 #define SIM_MAX_GROUP 16
 #define SIM_PAIR_CAP 96
 
-/* Bytes of device workspace sim_create needs for this description (256-byte aligned base). */
+/* Bytes of device workspace sim_create needs for this description (256-byte aligned base).
+ * (Section 3.1, last paragraph: all robots are held by one simulation; the workspace is that
+ * simulation's memory: tables, heightfield, body state of all envs, staging of the outputs.)
+ * Host call, no GPU work.  SIM_ERR_ARG on an inconsistent description (same checks as sim_create). */
 int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t* out_bytes);
 
-/* Builds the static tables from `desc` (copied; the caller may free it afterwards),
- * uploads them and the heightfield into `workspace_dev` and puts every env in its
- * unperturbed rest pose.  Synchronous.  SIM_ERR_ARG on an inconsistent description,
+/* One simulation holding num_envs robots (Section 3.1, last paragraph; the many-environments-
+ * per-GPU framing of Section 3).  Builds the static tables from `desc` (copied; the caller may
+ * free it afterwards), uploads them and the heightfield into `workspace_dev` (device memory the
+ * caller owns and keeps alive until sim_destroy) and puts every env in its unperturbed rest
+ * pose.  Synchronous.  SIM_ERR_ARG on an inconsistent description,
  * SIM_ERR_WORKSPACE if workspace_bytes < sim_workspace_bytes(). */
 int sim_create(const sim_desc_t* desc, int num_envs, void* workspace_dev, size_t workspace_bytes,
                sim_t** out);
+/* Ends the simulation: frees the host object (the workspace stays the caller's; a static
+ * workspace becomes free for the next sim_create_static).  No passage of the paper; NULL is
+ * SIM_ERR_ARG. */
 int sim_destroy(sim_t* sim);
 
 /* For callers that cannot allocate device memory (harnesses that forbid it, serving loops that
@@ -214,6 +222,8 @@ int sim_destroy(sim_t* sim);
 #define SIM_STATIC_WORKSPACE_BYTES (24u << 20)
 int sim_create_static(const sim_desc_t* desc, int num_envs, sim_t** out);
 
+/* Sizes of the simulation (host calls, -1 for a NULL sim): what a caller needs to size the
+ * arrays below.  Observation layout: Table 2, column "Ours" (Section 4.1). */
 int sim_num_envs(const sim_t* sim);
 int sim_num_bodies(const sim_t* sim);
 int sim_num_slots(const sim_t* sim); /* contact slots per env */
@@ -272,14 +282,23 @@ int sim_get_kept_impulses(sim_t* sim, float* joint_rows_dev, float* slot_rows_de
 int sim_get_task_state(sim_t* sim, int32_t* counters_dev, float* targets_dev, float* push_dev, void* stream);
 int sim_set_task_state(sim_t* sim, const int32_t* counters_dev, const float* targets_dev, void* stream);
 
-/* Parity / checkpoint interface (not on the timed path). */
+/* Parity / checkpoint interface (not on the timed path; no passage of the paper defines it: it
+ * exposes the maximal-coordinate state of Section 3.1 so that a run can be compared, saved and
+ * resumed).  State: [N][n_bodies][13] floats per body = position (env-local), unit quaternion
+ * (w, x, y, z; body to world), linear velocity, angular velocity (world frame), device memory.
+ * sim_set_state also clears what the warm start keeps and invalidates recorded contacts;
+ * neither call synchronises.  sim_set_step_count: frame counter of every env ([N], device), the
+ * one the 1000-frame episode limit of Section 4.1 counts. */
 int sim_get_state(sim_t* sim, float* state_dev, void* stream);
 int sim_set_state(sim_t* sim, const float* state_dev, void* stream);
 int sim_set_step_count(sim_t* sim, const int32_t* counts_dev, void* stream);
-/* When enabled, sim_step also stores the contact records of its last substep. */
+/* Terrain contacts (Section 3.1: contacts are detected speculatively, i.e. within a margin before
+ * they touch).  sim_record_contacts (host flag): when enabled, sim_step also stores the contact
+ * records of its last substep, one sim_contact_rec_t per slot, which sim_get_contacts copies to
+ * recs_dev (SIM_ERR_ARG if nothing was recorded since the state last changed). */
 int sim_record_contacts(sim_t* sim, int enable);
 int sim_get_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
-/* Contact generation alone on the current state, straight into recs_dev. */
+/* The same contact generation alone, on the current state, straight into recs_dev (no step). */
 int sim_generate_contacts(sim_t* sim, sim_contact_rec_t* recs_dev /*[N][S]*/, void* stream);
 /* Capsule-capsule contacts of the last substep of the last sim_step (recording enabled): up to
  * `cap` records into recs_dev, workgroup by workgroup, each workgroup's in a fixed order; the total
@@ -327,19 +346,23 @@ int sim_regroup(sim_t* sim, float cell, float reach, void* stream);
 int sim_set_groups(sim_t* sim, const int32_t* place_env_dev, void* stream);
 int sim_get_groups(sim_t* sim, int32_t* place_env_dev, void* stream);
 int sim_count_near_pairs(sim_t* sim, float reach, int64_t* counts_dev /*[2]*/, void* stream);
-/* Synchronises `stream` and scans the state: SIM_ERR_NONFINITE if any value is NaN/Inf. */
+/* Health check of a run (no passage of the paper).  Synchronises `stream` and scans the state:
+ * SIM_ERR_NONFINITE if any value is NaN/Inf. */
 int sim_check(sim_t* sim, void* stream);
 
-/* Launch shape of sim_step as it stands: threads and envs per workgroup, dynamic LDS bytes per
+/* Launch shape (no passage of the paper; the paper's engine is a different design).  sim_launch_info:
+ * the launch shape of sim_step as it stands: threads and envs per workgroup, dynamic LDS bytes per
  * workgroup (grid = ceil(num_envs / envs_per_block)).  Any output pointer may be NULL. */
 int sim_launch_info(const sim_t* sim, int32_t* threads_per_block, int32_t* envs_per_block, size_t* lds_bytes);
 
-/* Launch shape of sim_step: envs per workgroup (0 = library default).  Results are bit-reproducible
+/* sim_set_envs_per_block: envs per workgroup of sim_step (0 = library default; a multiple of
+ * group_size; SIM_ERR_ARG if the workgroup's arrays would not fit).  Results are bit-reproducible
  * for a given launch shape, and contact sets are the same for all; the continuous state of two
  * launch shapes agrees to rounding (they run different instantiations of the kernel). */
 int sim_set_envs_per_block(sim_t* sim, int envs_per_block);
 
-/* Message for the last error on the calling thread (never NULL). */
+/* Error reporting (no passage of the paper): message for the last error on the calling thread
+ * (never NULL; owned by the library, valid until the thread's next failing call). */
 const char* sim_last_error(void);
 
 #ifdef __cplusplus
