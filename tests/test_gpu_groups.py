@@ -28,8 +28,10 @@ def _crowd_scene(n, group, side, terrain="plane", seed=3, warm=0.0, min_dist=0.5
     t = scenes.make_plane() if terrain == "plane" else scenes.make_heightfield(seed=1003)
     sc = scenes.make_scene(rob, t, n, seed=21, params=p)
     rng = np.random.default_rng(seed)
-    pts = []
+    pts, tries = [], 0
     while len(pts) < n:
+        tries += 1
+        assert tries < 5000 * n, "the square is too small for that many agents"
         c = rng.uniform(0.0, side, size=2)
         if all(np.hypot(*(c - q)) >= min_dist for q in pts):
             pts.append(c)
@@ -210,3 +212,40 @@ def test_group_calls_check_their_arguments():
     with pytest.raises(P.SimError):
         lone.regroup(1.0, 1.0)
     lone.close()
+
+
+def test_regrouping_and_step_captured_in_one_graph_replay_like_eager_calls():
+    """sim_regroup enqueues kernels only (no allocation, no clearing call, no synchronisation), so
+    it can be captured in a HIP graph together with the step that follows it: every replay, with
+    eager calls on the same sim in between, equals the eager pair of calls bit for bit, places
+    included."""
+    import torch
+    P = _P()
+    n = 96
+    rob, sc = _crowd_scene(n, 4, 9.0, warm=0.8)
+
+    def make():
+        sim = P.Sim(sc); sim.reset(7)
+        return sim
+
+    dt = float(np.float32(1.0 / 60.0))
+    acts = [torch.as_tensor(scenes.actions_for_step(5, s, n, rob.n_dofs)).cuda() for s in range(12)]
+    eager, graphed = make(), make()
+    abuf = acts[0].clone()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.regroup(1.5, 1.2)
+        graphed.step_obs(abuf, dt, 4, 20)
+    assert torch.equal(graphed.get_state(), eager.get_state())      # capturing runs nothing
+    for k in range(12):
+        abuf.copy_(acts[k])
+        g.replay()
+        torch.cuda.synchronize()
+        eager.regroup(1.5, 1.2)
+        eo, er, ed = eager.step_obs(acts[k], dt, 4, 20)
+        assert torch.equal(graphed.obs, eo) and torch.equal(graphed.reward, er) and torch.equal(graphed.done, ed), k
+        assert torch.equal(graphed.get_state(), eager.get_state())
+        assert np.array_equal(graphed.get_groups(), eager.get_groups())
+    assert not np.array_equal(eager.get_groups(), np.arange(n))
+    graphed.check(); eager.check()
+    graphed.close(); eager.close()
