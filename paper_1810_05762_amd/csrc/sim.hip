@@ -317,6 +317,9 @@ static int default_envs_per_block(const Model& m, int N) {
   E -= E % G;
   // and the workgroup's LDS arrays have to fit
   while (E > G && (size_t)plan_for(m, E).total * sizeof(float) > 160 * 1024) E -= G;
+  // the collision variants are compiled for 16 and 8 envs per workgroup (any other number runs the
+  // general form, which is much slower): 8 rather than an odd number in between
+  if (pairs_of(m) && E > 8 && E < 16 && 8 % G == 0) E = 8;
   return E;
 }
 
@@ -496,10 +499,12 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   int lrc = m.solver == 1 ? ((s->E == 8 && few) ? launch(&step_kernel<8, 4, 0, kThreads, 0, 1>)
                              : few ? launch(&step_kernel<0, 4, 0, kThreads, 0, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 0, 1>))
             : (m.warm > 0.0f && pairs) ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1, kThreads, 1>)
+                             : (s->E == 8 && few) ? launch(&step_kernel<8, 4, 1, kThreads, 1>)
                              : few ? launch(&step_kernel<0, 4, 1, kThreads, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1, kThreads, 1>))
             : m.warm > 0.0f ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 0, kThreads, 1>)
                              : few ? launch(&step_kernel<0, 4, 0, kThreads, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 1>))
             : pairs ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1>)
+                     : (s->E == 8 && few) ? launch(&step_kernel<8, 4, 1>)
                      : few ? launch(&step_kernel<0, 4, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 1>))
             : threads == kThreadsWide ? launch(&step_kernel<16, 4, 0, kThreadsWide>)
             : (s->E == 8 && few) ? launch(&step_kernel<8, 4>)
