@@ -8,9 +8,13 @@
  *
  * Paper basis (Section 3.1): maximal coordinates, torque control, speculative
  * contacts as unilateral constraints, isotropic Coulomb friction, restitution
- * 0, implicit-style velocity-level time stepping.  The paper's Newton/Krylov
- * solver is replaced by a fixed-count projected-Jacobi iteration; where the
- * paper is silent a reading is taken and stated where it is used.
+ * 0, implicit-style velocity-level time stepping.  Two solvers for the same
+ * rows: a fixed-count block projected-Jacobi iteration (the default), and the
+ * paper's own choice, a non-smooth Newton method with a conjugate-residual
+ * inner solve; where the paper is silent a reading is taken and stated where
+ * it is used.  Agents of one interaction group collide capsule against
+ * capsule; the groups are consecutive places that any permutation of the
+ * agents, or a grouping from their positions, can fill.
  * Observation: Table 2 ("Ours").  Reward: Eq. (1)-(3).  Episode rules: Section
  * 4.1 (fall threshold, 1000-frame cap).
  */

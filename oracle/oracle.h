@@ -5,8 +5,9 @@
  * (maximal coordinates, torque actuation, speculative unilateral contacts with
  * isotropic Coulomb friction mu, restitution 0, implicit-style velocity
  * stepping: Section 3.1 of the paper) with a fixed-count projected-Jacobi
- * solve, followed by the observation vector of Table 2 ("Ours" column) and the
- * reward of Eq. (1)-(3).  It shares no code with the HIP library and must only
+ * solve (or the paper's non-smooth Newton / Krylov solver as the second
+ * solver), followed by the observation vector of Table 2 ("Ours" column) and
+ * the reward of Eq. (1)-(3).  It shares no code with the HIP library and must only
  * be used by tests, the smoke check and the benchmark's CPU-baseline leg.
  *
  * Every function of it is pinned by a closed form, an invariant, a brute-force
