@@ -188,6 +188,25 @@ typedef struct sim_pair_contact_rec {
 #define SIM_MAX_GROUP 16
 #define SIM_PAIR_CAP 96
 
+/* Built-in descriptions (host calls, no GPU work), so that a C caller needs no table generator:
+ * sim_default_params fills every scalar parameter of *desc with the values of the benchmark
+ * configurations (gravity (0, 0, -9.81), mu 1 as in Section 3.1, margin 2 cm, feedback factors
+ * 0.2, recovery speed 2 m/s, no damping, angular velocity cap 64 rad/s, reset noise 0.05,
+ * gyroscopic term and contacts on, 1000-frame episodes as in Section 4.1, plane terrain, no height
+ * map, no collisions among bodies, no warm start, Jacobi solver) and clears its pointers.
+ * sim_builtin_robot points desc->bodies / joints at tables inside the library (valid until the
+ * library is unloaded; do not free) and sets the counts, root, feet, fall threshold and alive
+ * bonus: SIM_ROBOT_ANT (9 bodies, 8 joints, 8 actuated hinges) or SIM_ROBOT_HUMANOID (13
+ * capsules, 12 joints, 21 actuated hinges), the stick figures of the benchmark configurations
+ * (Section 4.1 names the Ant and Humanoid tasks; the dimensions are this build's own).  The
+ * caller still supplies terrain, env_origins and, if wanted, collide_pairs.  SIM_ERR_ARG for a
+ * NULL desc or an unknown kind.  (This is the "robot kind" of a description; custom tables are
+ * simply the caller's own bodies / joints.) */
+#define SIM_ROBOT_ANT 1
+#define SIM_ROBOT_HUMANOID 2
+int sim_default_params(sim_desc_t* desc);
+int sim_builtin_robot(int32_t robot_kind, sim_desc_t* desc);
+
 /* Bytes of device workspace sim_create needs for this description (256-byte aligned base).
  * (Section 3.1, last paragraph: all robots are held by one simulation; the workspace is that
  * simulation's memory: tables, heightfield, body state of all envs, staging of the outputs.)

@@ -65,6 +65,8 @@ CONTACT_DTYPE = np.dtype([("active", np.int32), ("kind", np.int32), ("feat", np.
                           ("w", np.float32), ("pad", np.int32)])
 
 _SYMBOLS = {
+    "sim_default_params": [C.POINTER(SimDesc)],
+    "sim_builtin_robot": [C.c_int32, C.POINTER(SimDesc)],
     "sim_workspace_bytes": [C.POINTER(SimDesc), C.c_int, C.POINTER(C.c_size_t)],
     "sim_create": [C.POINTER(SimDesc), C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)],
     "sim_create_static": [C.POINTER(SimDesc), C.c_int, C.POINTER(C.c_void_p)],
@@ -127,6 +129,23 @@ def _chk(rc):
     if rc < 0:
         raise SimError(rc, sim_last_error())
     return rc
+
+
+SIM_ROBOT_ANT, SIM_ROBOT_HUMANOID = 1, 2
+
+
+def sim_default_params():
+    """A SimDesc with the library's default parameters and no robot, terrain or origins."""
+    d = SimDesc()
+    _chk(lib().sim_default_params(C.byref(d)))
+    return d
+
+
+def sim_builtin_robot(kind, desc=None):
+    """Points desc (a fresh default one if None) at the library's built-in robot tables."""
+    d = sim_default_params() if desc is None else desc
+    _chk(lib().sim_builtin_robot(int(kind), C.byref(d)))
+    return d
 
 
 def make_desc(scene):

@@ -15,6 +15,7 @@
 #include "model.hpp"
 #include "step_kernel.hpp"
 #include "regroup.hpp"
+#include "builtin_robots.hpp"
 
 using namespace sim355;
 
@@ -523,6 +524,29 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
 static inline int blocks_for(size_t n, int t = 256) { return (int)((n + t - 1) / t); }
 
 // -------------------------------------------------------------------- ABI
+extern "C" int sim_default_params(sim_desc_t* d) {
+  if (!d) return fail(SIM_ERR_ARG, "desc is NULL");
+  memset(d, 0, sizeof *d);
+  d->max_episode_steps = 1000;
+  d->gravity[2] = -9.81;
+  d->mu = 1.0; d->contact_margin = 0.02; d->beta_joint = 0.2; d->beta_contact = 0.2; d->max_depen_vel = 2.0;
+  d->max_ang_vel = 64.0; d->reset_noise = 0.05; d->gyroscopic = 1; d->contacts = 1;
+  d->group_size = 1; d->krylov_iterations = 8; d->newton_reg = 0.1;
+  return SIM_OK;
+}
+
+extern "C" int sim_builtin_robot(int32_t robot_kind, sim_desc_t* d) {
+  if (!d) return fail(SIM_ERR_ARG, "desc is NULL");
+  const BuiltinRobot* r = builtin_robot(robot_kind);
+  if (!r) return fail(SIM_ERR_ARG, "robot_kind %d: 1 = ant, 2 = humanoid", robot_kind);
+  d->n_bodies = r->n_bodies; d->n_joints = r->n_joints;
+  d->bodies = r->bodies; d->joints = r->joints;
+  d->root_body = r->root; d->n_feet = r->n_feet;
+  for (int k = 0; k < SIM_MAX_FEET; ++k) d->foot_bodies[k] = k < r->n_feet ? r->feet[k] : 0;
+  d->term_height = r->term_height; d->alive_bonus = r->alive_bonus;
+  return SIM_OK;
+}
+
 extern "C" int sim_workspace_bytes(const sim_desc_t* desc, int num_envs, size_t* out_bytes) {
   Model m;
   int rc = build_model(desc, num_envs, &m);

@@ -228,3 +228,36 @@ def test_largest_robot_the_library_takes(epb):
     assert np.abs(og - oo).max() <= 1e-3 * max(1.0, np.abs(oo).max())     # ten free-running steps: the state's bar
     assert ref.get_contacts()["active"].sum() > 0
     sim.close()
+
+
+@pytest.mark.parametrize("kind,maker", [(1, "make_ant"), (2, "make_humanoid")])
+def test_sim_from_the_built_in_description_equals_the_sim_from_the_input_recipe(kind, maker):
+    """A sim created through the C interface alone (default parameters, built-in robot tables,
+    the caller adds only where the envs stand) steps bit for bit like the one whose description
+    the input module builds."""
+    import torch
+    import paper_1810_05762_amd as P
+    n = 40
+    rob = getattr(scenes, maker)()
+    sc = scenes.make_scene(rob, scenes.make_plane(), n)
+    ref = P.Sim(sc)
+    d = P.sim_builtin_robot(kind)
+    org = np.ascontiguousarray(sc.env_origins, np.float64)
+    d.env_origins = org.ctypes.data_as(type(d.env_origins))
+    nbytes = P.sim_workspace_bytes(d, n)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+    h = P.sim_create(d, n, (ws.data_ptr() + 255) & ~255, nbytes)
+    stream = torch.cuda.current_stream().cuda_stream
+    P.sim_reset(h, None, 5, stream)
+    ref.reset(5)
+    st = torch.empty(n, rob.n_bodies, 13, dtype=torch.float32, device="cuda")
+    for s in range(6):
+        a = torch.as_tensor(scenes.actions_for_step(3, s, n, rob.n_dofs)).cuda()
+        P.sim_step(h, a.data_ptr(), 1.0 / 60.0, 4, 20, stream)
+        ref.step(a, 1.0 / 60.0, 4, 20)
+    P.sim_get_state(h, st.data_ptr(), stream)
+    assert torch.equal(st, ref.get_state())
+    assert P.lib().sim_act_dim(h) == rob.n_dofs
+    torch.cuda.synchronize()
+    P.sim_destroy(h)
+    ref.close()

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import scenes
@@ -139,3 +140,44 @@ def test_static_workspace_entry_point_rejects_oversize_descriptions_without_a_gp
     with pytest.raises(P.SimError) as ei:
         P.sim_create_static(d, 16384)
     assert ei.value.code == -2 and "static workspace holds" in str(ei.value)
+
+
+@pytest.mark.parametrize("kind,maker", [(1, "make_ant"), (2, "make_humanoid")])
+def test_built_in_robot_tables_equal_the_shared_input_recipe(kind, maker):
+    """The library's own ant and humanoid (sim_builtin_robot) are the robots of the benchmark
+    configurations: every number of the tables equals the one the input module builds (host
+    arithmetic in double on both sides; r ** 3 against r * r * r allows a last-digit difference),
+    and the default parameters are the configurations'."""
+    import paper_1810_05762_amd as P
+    rob = getattr(scenes, maker)()
+    ref, _keep = P.make_desc(scenes.make_scene(rob, scenes.make_plane(), 4))
+    d = P.sim_builtin_robot(kind)
+    assert (d.n_bodies, d.n_joints, d.root_body, d.n_feet) == (ref.n_bodies, ref.n_joints, ref.root_body, ref.n_feet)
+    assert list(d.foot_bodies)[:d.n_feet] == list(ref.foot_bodies)[:ref.n_feet]
+    assert (d.term_height, d.alive_bonus) == (ref.term_height, ref.alive_bonus)
+    for b in range(d.n_bodies):
+        x, y = d.bodies[b], ref.bodies[b]
+        assert x.axis == y.axis
+        got = [x.radius, x.half_len, x.mass, *x.inertia, *x.rest_pos]
+        want = [y.radius, y.half_len, y.mass, *y.inertia, *y.rest_pos]
+        np.testing.assert_allclose(got, want, rtol=1e-14, atol=0)
+    n_act = 0
+    for j in range(d.n_joints):
+        x, y = d.joints[j], ref.joints[j]
+        assert (x.parent, x.child, list(x.mode), list(x.act)) == (y.parent, y.child, list(y.mode), list(y.act))
+        got = [*x.anchor, *[v for row in x.axes for v in row], *x.lo, *x.hi, *x.gear]
+        want = [*y.anchor, *[v for row in y.axes for v in row], *y.lo, *y.hi, *y.gear]
+        np.testing.assert_allclose(got, want, rtol=1e-14, atol=1e-300)
+        n_act += sum(1 for m in x.mode if m == 1)
+    assert n_act == rob.n_dofs
+    for f in ("max_episode_steps", "mu", "contact_margin", "beta_joint", "beta_contact", "max_depen_vel", "lin_damping",
+              "ang_damping", "max_ang_vel", "reset_noise", "gyroscopic", "contacts", "height_map", "group_size",
+              "warm_start", "solver", "krylov_iterations"):
+        assert getattr(d, f) == getattr(ref, f), f
+    assert list(d.gravity) == list(ref.gravity) and d.terrain_kind == 0 and d.n_collide_pairs == 0
+    with pytest.raises(P.SimError):
+        P.sim_builtin_robot(3)
+    # complete once the caller has added where the envs stand: the same workspace as the recipe's
+    org = np.ascontiguousarray(scenes.make_scene(rob, scenes.make_plane(), 4).env_origins, np.float64)
+    d.env_origins = org.ctypes.data_as(type(d.env_origins))
+    assert P.sim_workspace_bytes(d, 4) == P.sim_workspace_bytes(ref, 4)
