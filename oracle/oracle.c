@@ -713,6 +713,14 @@ static void newton_solve(const model* m, row_t* rows, int nrows, v3 (*R)[3], int
     on = (int*)malloc(sizeof(int) * cap);
   }
   const int B = m->B;
+  /* The scratch vectors are reused from solve to solve: every entry of this solve's range starts
+   * as NaN, so that a value read before it is written cannot pass for a number (a friction pair
+   * once left the compliance of its second row unset on the branch without normal impulse; what
+   * lay in memory was then multiplied by zero, which only works as long as it is finite). */
+  for (int i = 0; i < nrows; ++i) {
+    lam[i] = diag[i] = sres[i] = known[i] = rhs[i] = x[i] = z[i] = p[i] = q[i] = az[i] = tmp[i] = comp[i] = pd[i] = NAN;
+    on[i] = -1;
+  }
   for (int i = 0; i < nrows; ++i) {
     const row_t* r = &rows[i];
     double k = 0;
@@ -741,9 +749,9 @@ static void newton_solve(const model* m, row_t* rows, int nrows, v3 (*R)[3], int
       t->sum_lambda_n = sl;
     }
     /* branch of every row */
+    for (int i = 0; i < nrows; ++i) { known[i] = 0; comp[i] = 0; }
     for (int i = 0; i < nrows; ++i) {
       const row_t* r = &rows[i];
-      known[i] = 0; comp[i] = 0;
       if (r->type == 0) on[i] = 1;
       else if (r->type == 1) {
         on[i] = diag[i] > 0 && (lam[i] - sres[i] / diag[i] > 0);
@@ -903,6 +911,7 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
         joint_theta(m, e, j, th);
         for (int k = 0; k < 6; ++k) {
           row_t* r = &rows[nrows++];
+          memset(r, 0xff, sizeof *r);   /* (every field is set below; a forgotten one reads as NaN / -1) */
           r->a = a >= 0 ? f0 + a : -1; r->b = f0 + b; r->slot = -1;
           r->lambda = m->warm * e->lam_j[j][k];
           r->sca = a >= 0 ? W[f0 + a] : 0.0; r->scb = W[f0 + b];
@@ -946,6 +955,7 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
         v3 dirs[3] = {n, t1, t2};
         for (int k = 0; k < 3; ++k) {
           row_t* r = &rows[nrows++];
+          memset(r, 0xff, sizeof *r);   /* (every field is set below; a forgotten one reads as NaN / -1) */
           r->a = -1; r->b = f0 + b; r->slot = s;
           r->lambda = e->lam_s_on[s] ? m->warm * e->lam_s[s][k] : 0.0;
           r->sca = 0.0; r->scb = W[f0 + b] / wslot[g * S + s];
@@ -970,6 +980,7 @@ static void substep(const model* m, env_state* envs, int e0, int G, oracle_pair_
       v3 dirs[3] = {n, t1, t2};
       for (int k = 0; k < 3; ++k) {
         row_t* r = &rows[nrows++];
+        memset(r, 0xff, sizeof *r);   /* (every field is set below; a forgotten one reads as NaN / -1) */
         r->a = fb; r->b = fa; r->slot = S + q; r->lambda = 0;
         r->sca = W[fb] / c->w; r->scb = W[fa] / c->w;
         r->jlb = dirs[k]; r->jab = vcross(ra, dirs[k]);
