@@ -1,0 +1,69 @@
+"""The step kernels read nothing they have not written: filling the LDS of every compute unit with
+NaN / infinity / random bit patterns before every launch, and handing the library device memory
+that is full of such patterns, changes no bit of any result.  (LDS and fresh device memory hold
+whatever the previous kernel or process left there; a kernel that relied on zeros would pass on
+a fresh machine and fail later.)"""
+import ctypes as C
+import dataclasses
+import os
+
+import numpy as np
+import pytest
+
+import scenes
+
+pytestmark = pytest.mark.gpu
+HELPER = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblds_fill.so")
+
+
+def _scene(name, n):
+    from test_gpu_groups import _crowd_scene
+    if name in ("collisions", "collisions_warm"):
+        return _crowd_scene(n, 4, 7.0, "heightfield", warm=0.8 if name.endswith("warm") else 0.0)[1]
+    sc, _cfg = scenes.config_scene(3, num_envs=n)
+    extra = {"plain": {}, "warm": {"warm_start": 0.8}, "newton": {"solver": 1, "krylov_iters": 8},
+             "task_height_map": {"height_map": 1}}[name]
+    sc.params = dataclasses.replace(sc.params, **extra)
+    return sc
+
+
+@pytest.mark.parametrize("name", ["plain", "warm", "newton", "collisions", "collisions_warm", "task_height_map"])
+def test_results_do_not_depend_on_what_lds_and_device_memory_held_before(name):
+    import torch
+    import paper_1810_05762_amd as P
+    if not os.path.exists(HELPER):
+        pytest.skip("tests/liblds_fill.so is not built (python -c 'import __graft_entry__ as g; g.build()')")
+    L = C.CDLL(HELPER)
+    L.lds_fill.argtypes = [C.c_uint32, C.c_void_p, C.c_void_p]
+    sink = torch.zeros(2048, dtype=torch.int32, device="cuda")
+    n = 64
+    sc = _scene(name, n)
+    its = 3 if name == "newton" else 20
+
+    def run(lds_pattern, mem_byte):
+        if mem_byte is not None:
+            # what the caching allocator hands out next is full of this byte
+            junk = [torch.full((32 << 20,), mem_byte, dtype=torch.uint8, device="cuda") for _ in range(4)]
+            del junk
+        sim = P.Sim(sc)
+        sim.reset(5)
+        if name == "task_height_map":
+            sim.set_task(scenes.TaskParams(fall_grace_frames=3, target_period=11, push_min_frames=5, push_max_frames=9,
+                                           auto_reset=1, seed=4))
+        stream = torch.cuda.current_stream().cuda_stream
+        for s in range(25):
+            if lds_pattern is not None:
+                assert L.lds_fill(lds_pattern, sink.data_ptr(), stream) == 0
+            if name.startswith("collisions") and s % 5 == 0:
+                sim.regroup(1.5, 1.2)
+            obs, rew, done = sim.step_obs(scenes.actions_for_step(5, s, n, sc.robot.n_dofs), 1.0 / 60.0, 4, its)
+        out = [t.cpu().numpy().copy() for t in (sim.get_state(), obs, rew, done)]
+        sim.check(); sim.close()
+        return out
+
+    ref = run(None, None)
+    assert np.isfinite(ref[0]).all()
+    for lds_pattern, mem_byte in ((0xFFFFFFFF, 0xFF), (0x7F800000, 0x7F), (0xDEADBEEF, 0x3F)):   # NaN, +inf / 3.4e38, random
+        got = run(lds_pattern, mem_byte)
+        for a, b, what in zip(ref, got, ("state", "obs", "reward", "done")):
+            assert np.array_equal(a, b), (name, hex(lds_pattern), what)
