@@ -249,3 +249,58 @@ def test_regrouping_and_step_captured_in_one_graph_replay_like_eager_calls():
     assert not np.array_equal(eager.get_groups(), np.arange(n))
     graphed.check(); eager.check()
     graphed.close(); eager.close()
+
+
+def test_full_size_crowd_regrouped_order_and_sampled_groups_match_the_oracle():
+    """4096 humanoids in one square on the plane at 0.3 agents per square metre, numbered in no
+    spatial order, in the launch shape `bench.py --crowd 0.3` times.  After the robots have fallen
+    over each other: the whole order of the agents and the pair counts equal the oracle's bit for
+    bit; then 24 sampled groups (those with the most contacts between agents among them) are
+    recomputed by the oracle as a small scene holding their agents in place order."""
+    P = _P()
+    n, group = 4096, 4
+    rob = scenes.make_humanoid()
+    p = scenes.SimParams(self_collide=1, group_size=group)
+    sc = scenes.make_scene(rob, scenes.make_plane(), n, seed=21, params=p)
+    sc.env_origins = scenes.crowd_origins(n, 0.3, 1002)
+    sim = P.Sim(sc)
+    sim.reset(5)
+    sim.record_contacts(True)
+    dt, sub, its = float(np.float32(1.0 / 60.0)), 4, 20
+    for s in range(60):
+        if s % 10 == 0:
+            sim.regroup(2.4, 1.2)
+        sim.step(scenes.actions_for_step(9, s, n, rob.n_dofs), dt, sub, its)
+    # order and counts of the whole crowd
+    full = oracle.OracleSim(sc, threads=8)
+    full.set_state(sim.get_state().cpu().numpy().astype(np.float64))
+    sim.regroup(2.4, 1.2); full.regroup(2.4, 1.2)
+    places = sim.get_groups()
+    assert np.array_equal(places, full.get_groups())
+    near = sim.count_near_pairs(1.2)
+    assert near == full.count_near_pairs(1.2) and near[0] > 500 and near[1] < 0.25 * near[0]
+    # sampled groups, stepped by the oracle on their own
+    sim.step(scenes.actions_for_step(9, 60, n, rob.n_dofs), dt, sub, its)
+    pg, dropped = sim.get_pair_contacts(cap=400000)
+    place_of = np.empty(n, np.int64); place_of[places] = np.arange(n)
+    between = pg[pg["env_a"] != pg["env_b"]]
+    busy = np.bincount(place_of[between["env_a"]] // group, minlength=n // group)
+    groups = np.argsort(-busy, kind="stable")[:20].tolist() + [0, 1, n // group - 2, n // group - 1]
+    pick = np.concatenate([places[g * group:(g + 1) * group] for g in groups])
+    small = scenes.make_scene(rob, scenes.make_plane(), len(pick), seed=21, params=p)
+    small.env_origins = sc.env_origins[pick].copy()
+    ref = oracle.OracleSim(small, threads=8)
+    ref.set_state(sim.get_state().cpu().numpy()[pick].astype(np.float64))
+    errs = {}
+    for s in range(10):
+        a = scenes.actions_for_step(9, 61 + s, n, rob.n_dofs)
+        sim.step(a, dt, sub, its); ref.step(a[pick], dt, sub, its)
+        if s in (0, 9):
+            errs[s + 1] = rel_err(sim.get_state().cpu().numpy()[pick].astype(np.float64), ref.get_state())
+    print(f"full-size crowd: {near[0]} agent pairs within 1.2 m, {near[1]} of them in different groups; {len(pg)} capsule contacts, "
+          f"{len(between)} between agents, {busy[groups[0]]} in the busiest group; sampled groups: 1 step {errs[1].max():.2e}, "
+          f"10 steps median {np.median(errs[10]):.2e} max {errs[10].max():.2e}")
+    assert sim.launch_info()["envs_per_block"] == 16 and dropped == 0 and len(between) > 500 and busy[groups[0]] >= 3
+    assert errs[1].max() <= TOL_1
+    assert np.median(errs[10]) <= TOL_1 and errs[10].max() <= TOL_10
+    sim.check(); sim.close()
