@@ -228,7 +228,7 @@ class OracleSim:
         return int(self._L.oracle_set_pair_cap(self._h, int(cap), int(envs_per_unit)))
 
     def regroup(self, cell, reach):
-        """Interaction groups from the agents' positions: order along the Z-order curve of a grid
+        """Interaction groups from the agents' positions: order along the Hilbert curve through a grid
         of `cell` metres; inside windows of that order, groups of agents within `reach` of each other."""
         self._L.oracle_regroup(self._h, float(cell), float(reach))
 

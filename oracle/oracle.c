@@ -1723,8 +1723,9 @@ int32_t oracle_generate_pair_contacts(oracle_sim* o, oracle_pair_contact* out, i
 /* ---- interaction groups chosen from where the agents are (Section 3.1: all agents share one
  * scene; Section 4.1: the agents of the flagrun tasks collide with each other).  A uniform grid
  * of `cell` metres over the ground plane; an agent's cell is that of its root body's world
- * position; agents are ordered along the Z-order curve of the cells (ties: agent number), and
- * every G consecutive agents of that order form a group.  All decisions in single precision. */
+ * position; agents are ordered along the Hilbert curve through the cells (ties: agent number);
+ * inside windows of that order the groups are formed from agents within reach of each other
+ * (oracle_regroup below).  All decisions in single precision. */
 /* position of cell (x, y), 16 bits each, along the Hilbert curve of order 16: level by level
  * from the top bit, quadrant (rx, ry) contributes ((3 rx) xor ry) quadrant sizes; inside the
  * quadrant the coordinates are reflected (lower right quadrant) and exchanged (both lower

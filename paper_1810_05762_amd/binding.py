@@ -474,7 +474,7 @@ class Sim:
         return buf.cpu().numpy().view(PAIR_CONTACT_DTYPE)[:min(n, cap)].copy(), dropped
 
     def regroup(self, cell, reach):
-        """Interaction groups from the agents' positions: order along the Z-order curve of a grid of
+        """Interaction groups from the agents' positions: order along the Hilbert curve through a grid of
         `cell` metres, then groups of agents within `reach` of each other inside windows of that order."""
         sim_regroup(self.h, cell, reach, self._stream())
 
