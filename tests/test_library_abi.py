@@ -181,3 +181,13 @@ def test_built_in_robot_tables_equal_the_shared_input_recipe(kind, maker):
     org = np.ascontiguousarray(scenes.make_scene(rob, scenes.make_plane(), 4).env_origins, np.float64)
     d.env_origins = org.ctypes.data_as(type(d.env_origins))
     assert P.sim_workspace_bytes(d, 4) == P.sim_workspace_bytes(ref, 4)
+
+
+def test_header_is_a_plain_c_header():
+    """include/sim.h compiles as C11 and as C++17 on its own (no HIP, no other header of the build)."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "sim.h")
+    for cmd in (["gcc", "-std=c11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                ["g++", "-std=c++17", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++", hdr]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
