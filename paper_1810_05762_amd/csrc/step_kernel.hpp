@@ -312,6 +312,18 @@ __device__ __forceinline__ void build_contact_rows(ContactRows& c, const float* 
   c.bias = d >= 0.0f ? d / h : fmaxf(beta_c * d / h, -v_depen);
 }
 
+// Friction pair (l1, l2) brought back onto the disc of radius lim >= 0 (Section 3.1: isotropic
+// Coulomb friction).  Runs in every sweep of every contact, so the test compares squares and the
+// scale lim / |l| comes from the hardware's reciprocal square root (1 ulp) instead of a correctly
+// rounded square root and division; the floor keeps a denormal |l|^2 from turning into infinity.
+__device__ __forceinline__ void project_on_disc(float& l1, float& l2, float lim) {
+  const float n2 = l1 * l1 + l2 * l2;
+  if (n2 > lim * lim) {
+    const float sc = lim * __builtin_amdgcn_rsqf(fmaxf(n2, 1e-30f));
+    l1 *= sc; l2 *= sc;
+  }
+}
+
 // One sweep of a contact block on its private copy (vv, ww) of the body velocity:
 // normal row (impulse >= 0), then the friction pair projected on the disc mu * lambda_n.
 __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv[3], float ww[3]) {
@@ -326,8 +338,8 @@ __device__ __forceinline__ void relax_contact(ContactRows& c, float mu, float vv
   float jv1 = dot(c.dir[1], vv) + dot(c.ang[1], ww);
   float jv2 = dot(c.dir[2], vv) + dot(c.ang[2], ww);
   float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
-  float lim = mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
-  if (nrm > lim) { float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
+  const float lim = mu * c.lam[0];
+  project_on_disc(l1, l2, lim);
   float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
   c.lam[1] = l1; c.lam[2] = l2;
   for (int k = 0; k < 3; ++k) {
@@ -440,8 +452,8 @@ __device__ __forceinline__ void relax_pair_side(PairSide& c, float mu, float v[3
   const float p1 = dot(c.sd[1], v) + dot(c.sa[1], w), p2 = dot(c.sd[2], v) + dot(c.sa[2], w);
   const float jv1 = p1 + lane_swap1(p1), jv2 = p2 + lane_swap1(p2);
   float l1 = c.lam[1] - c.meff[1] * jv1, l2 = c.lam[2] - c.meff[2] * jv2;
-  const float lim = mu * c.lam[0], nrm = sqrtf(l1 * l1 + l2 * l2);
-  if (nrm > lim) { const float sc = nrm > 0.0f ? lim / nrm : 0.0f; l1 *= sc; l2 *= sc; }
+  const float lim = mu * c.lam[0];
+  project_on_disc(l1, l2, lim);
   const float d1 = l1 - c.lam[1], d2 = l2 - c.lam[2];
   c.lam[1] = l1; c.lam[2] = l2;
   for (int k = 0; k < 3; ++k) {
@@ -1950,14 +1962,17 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           if (jr.onesided & (1 << k)) jr.nl[k] = -l0;
         }
       }
+      // own body's velocity rows, found once (the world's side of a joint reads body 0's and writes
+      // nothing): looked up inside the loop, the body index costs every sweep an LDS round trip
+      // ahead of the reads that depend on it
+      const int js_ob = js_side ? Ltjoint[js_j < J ? js_j : 0].child : Ltjoint[js_j < J ? js_j : 0].parent;
+      const int js_voff = (js_ob < 0 ? 0 : js_ob) * kVS * E + js_e;
       for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
         if (js_on) {
-          const JointTab& jt = Ltjoint[js_j];
           const int e = js_e;
-          const int ob = js_side ? jt.child : jt.parent;
-          const int bo = ob < 0 ? 0 : ob;
+          const int ob = js_ob;
           float vo[3], wo[3];
-          for (int c = 0; c < 3; ++c) { vo[c] = Lvel[(bo * kVS + c) * E + e]; wo[c] = Lvel[(bo * kVS + 3 + c) * E + e]; }
+          for (int c = 0; c < 3; ++c) { vo[c] = Lvel[js_voff + c * E]; wo[c] = Lvel[js_voff + (3 + c) * E]; }
   #pragma unroll
           for (int k = 0; k < 3; ++k) {
             float dl;
