@@ -192,14 +192,32 @@ __device__ __forceinline__ void cross_unit(const float r[3], int k, float o[3]) 
   else { o[0] = r[1]; o[1] = -r[0]; o[2] = 0.0f; }
 }
 // rotation vector of conj(qa) * qb, short way round
+// atan2(y, x) for y >= 0, x >= 0 (not both zero), to about 2 ulp: the argument is brought into
+// [0, tan(pi/8)] by the identities atan(t) = pi/2 - atan(1/t) and atan(t) = pi/4 + atan((t-1)/(t+1)),
+// where an odd polynomial of degree 9 does (the classic single-precision arctangent of the Cephes
+// library; coefficients as published there).  Runs once per joint side and substep, on the path
+// everybody waits for, where the general library routine and two correctly rounded divisions
+// cost several times as much.
+__device__ __forceinline__ float atan2_first_quadrant(float y, float x) {
+  const bool big = y > 2.414213562373095f * x, mid = y > 0.4142135623730950f * x;
+  // t = y / x, or -x / y, or (y - x) / (y + x)
+  const float num = big ? -x : (mid ? y - x : y), den = big ? y : (mid ? y + x : x);
+  const float t = num * __builtin_amdgcn_rcpf(den);
+  const float base = big ? 1.5707963267948966f : (mid ? 0.7853981633974483f : 0.0f);
+  const float z = t * t;
+  const float p = (((8.05374449538e-2f * z - 1.38776856032e-1f) * z + 1.99777106478e-1f) * z - 3.33329491539e-1f) * z * t + t;
+  return base + p;
+}
+
 __device__ __forceinline__ void rel_rotvec(const float qa[4], const float qb[4], float phi[3]) {
   float w = qa[0] * qb[0] + qa[1] * qb[1] + qa[2] * qb[2] + qa[3] * qb[3];
   float x = qa[0] * qb[1] - qa[1] * qb[0] - qa[2] * qb[3] + qa[3] * qb[2];
   float y = qa[0] * qb[2] + qa[1] * qb[3] - qa[2] * qb[0] - qa[3] * qb[1];
   float z = qa[0] * qb[3] - qa[1] * qb[2] + qa[2] * qb[1] - qa[3] * qb[0];
   if (w < 0.0f) { w = -w; x = -x; y = -y; z = -z; }
-  float s = sqrtf(x * x + y * y + z * z);
-  float k = (s < 1e-12f) ? 2.0f : 2.0f * atan2f(s, w) / s;
+  const float s2 = x * x + y * y + z * z;
+  const float inv_s = __builtin_amdgcn_rsqf(fmaxf(s2, 1e-30f)), s = s2 * inv_s;
+  float k = (s < 1e-12f) ? 2.0f : 2.0f * atan2_first_quadrant(s, w) * inv_s;
   phi[0] = k * x; phi[1] = k * y; phi[2] = k * z;
 }
 
@@ -1492,14 +1510,14 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       for (int c = 0; c < 3; ++c) jr.sr[c] = sgl * r[c];
       jr.sg = sgl;
       jr.sv = sg * no * imo;
-      const float bh = p_beta_j / h;
+      const float inv_h = __builtin_amdgcn_rcpf(h), bh = p_beta_j * inv_h;
       for (int k = 0; k < 3; ++k) {
         float cr[3], y[3];
         cross_unit(r, k, cr);
         sym_vec(iwo, cr, y);
         const float kp = no * (imo + dot(cr, y));
         const float keff = kp + lane_swap1(kp);
-        jr.pme[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
+        jr.pme[k] = keff > 0.0f ? -__builtin_amdgcn_rcpf(keff) : 0.0f;
         jr.pnb[k] = jr.pme[k] * (bh * C[k]);
         jr.pD[k] = keff; jr.pb[k] = bh * C[k];
         for (int c = 0; c < 3; ++c) jr.Y[k][c] = sg * no * y[c];
@@ -1522,14 +1540,14 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         } else {
           float glo = th - jt.lo[k], ghi = jt.hi[k] - th, g;
           if (glo < ghi) { g = glo; } else { g = ghi; sgn = -1.0f; jr.upper |= 1 << k; }
-          bias = g >= 0.0f ? g / h : bh * g;
+          bias = g >= 0.0f ? g * inv_h : bh * g;
           jr.onesided |= 1 << k;
         }
         for (int c = 0; c < 3; ++c) ak[c] *= sgn;
         sym_vec(iwo, ak, z);
         const float kp = no * dot(ak, z);
         const float keff = kp + lane_swap1(kp);
-        jr.ame[k] = keff > 0.0f ? -1.0f / keff : 0.0f;
+        jr.ame[k] = keff > 0.0f ? -__builtin_amdgcn_rcpf(keff) : 0.0f;
         jr.anb[k] = jr.ame[k] * bias;
         jr.aD[k] = keff; jr.ab[k] = bias;
         jr.lam[k] = 0.0f;
@@ -2080,10 +2098,10 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       for (int c = 0; c < 4; ++c) q[c] = Lpos[(b * 7 + 3 + c) * E + e];
       // the solved velocities were left in LDS by the threads that averaged them
       for (int c = 0; c < 3; ++c) { v[c] = Lvel[(b * kVS + c) * E + e]; w[c] = Lvel[(b * kVS + 3 + c) * E + e]; }
-      float dl = 1.0f / (1.0f + h * p_clin), da = 1.0f / (1.0f + h * p_cang);
+      float dl = __builtin_amdgcn_rcpf(1.0f + h * p_clin), da = __builtin_amdgcn_rcpf(1.0f + h * p_cang);
       for (int c = 0; c < 3; ++c) { v[c] *= dl; w[c] *= da; }
-      float wn = sqrtf(dot(w, w));
-      if (wn > p_wmax) { float sc = p_wmax / wn; for (int c = 0; c < 3; ++c) w[c] *= sc; }
+      const float w2 = dot(w, w);
+      if (w2 > p_wmax * p_wmax) { float sc = p_wmax * __builtin_amdgcn_rsqf(w2); for (int c = 0; c < 3; ++c) w[c] *= sc; }
       for (int c = 0; c < 3; ++c) x[c] += h * v[c];
       float dq[4];
       dq[0] = -w[0] * q[1] - w[1] * q[2] - w[2] * q[3];
@@ -2092,7 +2110,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       dq[3] = w[0] * q[2] - w[1] * q[1] + w[2] * q[0];
       float hh = 0.5f * h;
       for (int c = 0; c < 4; ++c) q[c] += hh * dq[c];
-      float inv = 1.0f / sqrtf(q[0] * q[0] + q[1] * q[1] + q[2] * q[2] + q[3] * q[3]);
+      float inv = __builtin_amdgcn_rsqf(q[0] * q[0] + q[1] * q[1] + q[2] * q[2] + q[3] * q[3]);
       for (int c = 0; c < 4; ++c) q[c] *= inv;
     }
     __syncthreads();  // the next substep overwrites pose, counters and lists read above

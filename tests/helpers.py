@@ -54,7 +54,8 @@ def rel_err4(g, o):
     return np.stack(out, 1)
 
 
-def gate_after_10_steps(e10q, forked, many_impacts=False, label="", sets_seen_every_substep=True, min_same=None):
+def gate_after_10_steps(e10q, forked, many_impacts=False, label="", sets_seen_every_substep=True, min_same=None,
+                        interacting=False):
     """The 10-step state gate, split by whether the two sides ever disagreed on a contact set.
 
     e10q [N][4] from rel_err4; forked [N] bool: in some substep the HIP path and the oracle
@@ -70,6 +71,13 @@ def gate_after_10_steps(e10q, forked, many_impacts=False, label="", sets_seen_ev
            Without sets_seen_every_substep (whole env-steps in one launch: only the sets of each
            step's last substep can be compared, so some forks go unseen) one env in a hundred may
            lie between 1e-3 and 5e-3.
+           With interacting agents (capsule-capsule contacts between the agents of a group) a
+           contact passes every difference in one agent on to the other: identical sets do not
+           bound the growth as they do for an agent on its own, and the all-fp32 twin of the oracle
+           leaves 1e-3 for up to a fifth of such agents
+           (tests/test_oracle_sensitivity.py, the crowd).  There nine in ten stay within 1e-3, all
+           within 5e-3 in position and orientation and within 5e-2 in the velocities (a closing
+           contact divides a position difference by h = 1/240 s, see above).
       (ii) envs that forked follow another branch of a discontinuous map: reported, and bounded
            coarsely (nine in ten within 1e-3, all within 1e-2), the spread the oracle shows
            against its own fp32-stored copy in test_oracle_sensitivity.py.
@@ -85,14 +93,17 @@ def gate_after_10_steps(e10q, forked, many_impacts=False, label="", sets_seen_ev
     # (min_same: with interacting agents a fork spreads to everybody its agent shares a group with,
     #  so fewer stay on the common branch; the caller says how many it still expects)
     assert same.sum() >= (max(1, len(e10) // 4) if min_same is None else min_same), "too few envs kept identical contact sets to gate anything"
-    assert e10q[same, :2].max() <= TOL_10, line
-    if many_impacts:
+    if interacting:
+        assert (e10[same] <= TOL_10).mean() >= 0.9 and e10q[same, :2].max() <= 5e-3 and e10q[same, 2:].max() <= 5e-2, line
+    elif many_impacts:
+        assert e10q[same, :2].max() <= TOL_10, line
         ev = e10q[same, 2:].max(1)
         assert (ev <= TOL_10).mean() >= 0.97 and ev.max() <= 5e-3, line
     elif not sets_seen_every_substep:
-        ev = e10q[same, 2:].max(1)
-        assert (ev <= TOL_10).mean() >= 0.99 and ev.max() <= 5e-3, line
+        # (an unseen fork moves positions as well as velocities)
+        assert (e10[same] <= TOL_10).mean() >= 0.99 and e10[same].max() <= 5e-3, line
     else:
+        assert e10q[same, :2].max() <= TOL_10, line
         assert e10q[same, 2:].max() <= TOL_10, line
     if forked.any():
         assert np.quantile(e10[forked], 0.9) <= TOL_10 and e10[forked].max() <= 1e-2, line

@@ -147,7 +147,8 @@ def test_crowd_with_regrouping_every_few_steps(group, terrain, warm):
     assert errs[1].max() <= TOL_1
     # (on the heightfield most fallen humanoids meet equal distances to two terrain features
     #  sooner or later, and a fork counts for the whole group from then on)
-    gate_after_10_steps(errs[10], forked, label=f"crowd, group {group} {terrain}: ", min_same=8 if terrain != "plane" else None)
+    gate_after_10_steps(errs[10], forked, label=f"crowd, group {group} {terrain}: ", min_same=8 if terrain != "plane" else None,
+                        interacting=True)
     assert np.median(errs[10].max(1)) <= TOL_1
     sim.check(); sim.close()
 

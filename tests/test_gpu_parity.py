@@ -317,13 +317,13 @@ def test_nonfinite_state_is_detected_by_check():
 @pytest.mark.parametrize("share", [0.0, 0.8])
 def test_full_size_headline_config_sampled_envs_match_oracle(share):
     """4096 humanoids on the heightfield in the launch shape the benchmark times (`share` > 0: with
-    the warm start, as `bench.py --warm-start` runs it); 64 sampled envs are recomputed one by one
+    the warm start, as `bench.py --warm-start` runs it); 512 sampled envs are recomputed one by one
     by the oracle."""
     import dataclasses
     P = _P()
     sc, cfg = scenes.config_scene(3)
     sc.params = dataclasses.replace(sc.params, warm_start=share)
-    N = sc.num_envs
+    N, n_pick = sc.num_envs, 512
     sim = P.Sim(sc)
     sim.reset(cfg["seed"])
     dt = float(np.float32(cfg["dt"]))
@@ -331,27 +331,32 @@ def test_full_size_headline_config_sampled_envs_match_oracle(share):
         sim.step(scenes.actions_for_step(cfg["seed"], s, N, 21), dt, cfg["substeps"], cfg["iterations"])
     if share > 0:
         sim.set_state(sim.get_state())        # both sides start with nothing kept
-    pick = np.random.default_rng(0).choice(N, 64, replace=False)
+    pick = np.random.default_rng(0).choice(N, n_pick, replace=False)
     pick[:2] = (0, N - 1)
-    sub, _ = scenes.config_scene(3, num_envs=64)
+    sub, _ = scenes.config_scene(3, num_envs=n_pick)
     sub.params = dataclasses.replace(sub.params, warm_start=share)
     sub.env_origins = sc.env_origins[pick].copy()
     ref = oracle.OracleSim(sub, threads=8)
     ref.set_state(sim.get_state().cpu().numpy()[pick].astype(np.float64))
+    sim.record_contacts(True)
+    forked = np.zeros(n_pick, bool)
     for s in range(40, 50):
         a = scenes.actions_for_step(cfg["seed"], s, N, 21)
         sim.step(a, dt, cfg["substeps"], cfg["iterations"])
         ref.step(a[pick], dt, cfg["substeps"], cfg["iterations"])
+        cg, co = sim.get_contacts()[pick], ref.get_contacts()
+        forked |= np.any([(cg[f] != co[f]).any(1) for f in ("active", "kind", "feat")], axis=0)
         if s == 40:
             e1 = rel_err(sim.get_state().cpu().numpy()[pick].astype(np.float64), ref.get_state()).max()
     sim.check()
     g = sim.get_state().cpu().numpy().astype(np.float64)
-    e10 = rel_err(g[pick], ref.get_state()).max(1)
-    print(f"full size: 1 step {e1:.2e}, 10 steps median {np.median(e10):.2e} max {e10.max():.2e}")
-    # whole steps in the benchmark's launch shape: contact sets are not compared per substep here,
-    # so every sampled env has to stay within the tolerances, forked or not
+    e10 = rel_err(g[pick], ref.get_state())
+    print(f"full size: 1 step {e1:.2e}, 10 steps median {np.median(e10.max(1)):.2e} max {e10.max():.2e}")
     assert e1 <= TOL_1
-    assert e10.max() <= TOL_10 and np.median(e10) <= TOL_1
+    # whole steps in the benchmark's launch shape: the contact sets are seen at each step's last
+    # substep only, so a few forks go unseen (an env in a hundred may pass 1e-3, none 5e-3)
+    gate_after_10_steps(e10, forked, label="full size: ", sets_seen_every_substep=False)
+    assert np.median(e10.max(1)) <= TOL_1
     # properties that hold at any size
     assert np.isfinite(g).all()
     np.testing.assert_allclose(np.linalg.norm(g[:, :, 3:7], axis=2), 1.0, atol=1e-5)
@@ -362,7 +367,7 @@ def test_full_size_headline_config_sampled_envs_match_oracle(share):
 def test_full_size_other_configs_sampled_envs_match_oracle(k):
     """Configurations 1, 2 (1024 envs) and 4 (8192 fallen humanoids, 8 x 32 sweeps) at their full
     size in the launch shape `bench.py --config k` times (whole env-steps, default envs per
-    workgroup); 64 sampled envs are recomputed one by one by the oracle."""
+    workgroup); 256 sampled envs are recomputed one by one by the oracle."""
     P = _P()
     sc, cfg = scenes.config_scene(k)
     N, D = sc.num_envs, sc.robot.n_dofs
@@ -375,14 +380,14 @@ def test_full_size_other_configs_sampled_envs_match_oracle(k):
     warm = 30 if cfg["fallen"] else 40
     for s in range(warm):
         sim.step(scenes.actions_for_step(cfg["seed"], s, N, D), dt, cfg["substeps"], cfg["iterations"])
-    pick = np.random.default_rng(k).choice(N, 64, replace=False)
+    pick = np.random.default_rng(k).choice(N, 256, replace=False)
     pick[:2] = (0, N - 1)
-    sub, _ = scenes.config_scene(k, num_envs=64)
+    sub, _ = scenes.config_scene(k, num_envs=256)
     sub.env_origins = sc.env_origins[pick].copy()
     ref = oracle.OracleSim(sub, threads=8)
     ref.set_state(sim.get_state().cpu().numpy()[pick].astype(np.float64))
     sim.record_contacts(True)
-    forked = np.zeros(64, bool)
+    forked = np.zeros(256, bool)
     for s in range(warm, warm + 10):
         a = scenes.actions_for_step(cfg["seed"], s, N, D)
         sim.step(a, dt, cfg["substeps"], cfg["iterations"])
