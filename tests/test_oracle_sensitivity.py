@@ -130,14 +130,14 @@ def test_plain_single_precision_twin_leaves_1e_3_in_a_crowd_of_colliding_humanoi
     (interaction groups of 4 chosen from positions, warm start), the workload of
     tests/test_gpu_groups.py.  Among the agents whose terrain and capsule-capsule contact sets never
     differ from the oracle's - and whose group mates' never do - the all-fp32 twin of the oracle
-    still leaves 1e-3 in ten steps for some: a contact between two capsules passes every
+    still leaves 1e-3 in ten steps for some (and an agent whose sets did differ is found at 9e-2): a contact between two capsules passes every
     difference in one agent on to the other, so identical sets do not bound the growth the way they
     do for an agent on its own.  The gate of the HIP path on this workload is therefore a share of
     the agents within 1e-3 and a coarse bound for all (tests/helpers.py, gate_after_10_steps)."""
     from helpers import rel_err4
     from test_gpu_groups import _crowd_scene
     f32 = _single_precision_twin(tmp_path)
-    n, group, seed = 118, 4, 7
+    n, group, seed = 118, 4, 8
     rob, sc = _crowd_scene(n, group, 7.0, "heightfield", warm=0.8)
     a, b = oracle.OracleSim(sc, threads=8), f32.OracleSim(sc, threads=8)
     a.reset(seed)
@@ -169,10 +169,12 @@ def test_plain_single_precision_twin_leaves_1e_3_in_a_crowd_of_colliding_humanoi
     e10 = rel_err4(b.get_state().astype(np.float64), a.get_state()).max(1)
     same = ~forked
     print(f"fp32 twin, crowd: median {np.median(e10):.2e}; {same.sum()} agents with identical sets, max {e10[same].max():.2e}, "
-          f"{100 * (e10[same] <= 1e-3).mean():.0f} % within 1e-3")
+          f"{100 * (e10[same] <= 1e-3).mean():.0f} % within 1e-3; the others: p90 {np.quantile(e10[forked], .9):.2e} max {e10[forked].max():.2e}")
     assert same.sum() >= 10
     assert e10[same].max() > 1e-3
     assert np.median(e10) < 5e-4
+    # an agent on another branch of the step map: no bound short of the scale of the state
+    assert e10[forked].max() > 1e-2
 
 
 def test_cut_off_newton_iterate_flips_branches_between_single_and_double_precision(tmp_path):
