@@ -898,12 +898,13 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     __syncthreads();
 
     TMARK(1);
-    // ---- B: joint torques (stored once per joint; the body applies the sign), by the threads at
-    //         the low end of the workgroup: the per-slot pass below hands out its slots from the
-    //         top down, so the two mostly run on different wavefronts.
+    // ---- B: joint torques (stored once per joint; the body applies the sign).  They go through
+    //         LDS only, so they are computed by the upper half of the workgroup when the joints fit
+    //         there: the lower half runs the per-body pass below at the same time.
     {
-      const int tj = tid / E, te = tid % E;
-      if (tj < J && blockIdx.x * E + te < N) {
+      const int tq_base = J * E <= kThreads / 2 ? kThreads / 2 : 0;
+      const int tj = (tid - tq_base) / E, te = (tid - tq_base) % E;
+      if (tid >= tq_base && tj < J && blockIdx.x * E + te < N) {
         const JointTab& jt = Ltjoint[tj];
         float qa[4] = {1, 0, 0, 0};
         if (jt.parent >= 0)
@@ -930,11 +931,10 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     //          then runs on the last wavefronts while the first ones hold the joint threads.
     // forces -> velocities (torques, gravity, push, explicit gyroscopic term): body threads, needs
     // the joint torques and nothing of the contacts
-    auto forces_of = [&](int b, int e) {
-      float v[3], w[3];
+    auto forces = [&]() {
+      if (!is_body) return;
       float tau[3] = {0, 0, 0};
-      const int njs = Ltjs[b * (kMaxBodyJoints + 3)];
-      for (int k = 0; k < njs; ++k) {
+      for (int k = 0; k < my_njs; ++k) {
         const int js = Ltjs[b * (kMaxBodyJoints + 3) + 3 + k];
         const float sg = (js & 1) ? 1.0f : -1.0f;
         for (int c = 0; c < 3; ++c) tau[c] += sg * Ltq[((js >> 1) * 3 + c) * E + e];
@@ -964,22 +964,45 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       for (int c = 0; c < 3; ++c) w[c] += dww[c];
       for (int c = 0; c < 3; ++c) { Lvel[(b * kVS + c) * E + e] = v[c]; Lvel[(b * kVS + 3 + c) * E + e] = w[c]; }
     };
-    auto forces = [&]() { if (is_body) forces_of(b, e); };
-    // On the heightfield (Jacobi variants) the forces are integrated later, by the wavefronts that
-    // hold no joint rows while the others build theirs: here they would lengthen the way of the
-    // wavefronts that also run the per-slot pass.
-    const bool forces_late = NS == 0 && m_terrain == 1 && n_reg >= 64;
-    const int n_b1 = S * E;      // slots the per-slot pass visits
-    // (A pass of one thread per body that tested the whole capsule's box first and listed only the
-    //  slots of the bodies near the ground used to run here: with the humanoids fallen it passed
-    //  nearly every body and cost more than it saved, and in the air the per-slot test is as quick
-    //  to say no.)
-    if (m_terrain == 1 && !forces_late) {
-      __syncthreads();           // the torques are complete
+    int n_b1 = S * E;            // slots the per-slot pass visits
+    unsigned* Lslots = Lcand;    // heightfield: list of the slots of the bodies near the ground
+    if (m_terrain == 1) {
+      // ---- B1a: one thread per body: reach test of the whole capsule (box of its segment);
+      //           the slots of a body that passes are listed for the per-slot pass, the others
+      //           are inactive.  A slot can only pass its own test if its body passes this one.
+      for (int i = tid; i < B * E; i += kThreads) {
+        const int ee = i % E, bb = i / E;
+        const int env_i = blockIdx.x * E + ee;
+        const int s0 = Ltjs[bb * (kMaxBodyJoints + 3) + 1], ns = Ltjs[bb * (kMaxBodyJoints + 3) + 2];
+        bool near = false;
+        if (env_i < N && m_contacts) {
+          float bx[3], bq[4], bo[3];
+          for (int c = 0; c < 3; ++c) bx[c] = Lpos[(bb * 7 + c) * E + ee];
+          for (int c = 0; c < 4; ++c) bq[c] = Lpos[(bb * 7 + 3 + c) * E + ee];
+          for (int c = 0; c < 3; ++c) bo[c] = Lorg[c * E + ee];
+          SlotGeom g = slot_geom(Ltbody[4 * bb], Ltbody[4 * bb + 1], __float_as_int(Ltbody[4 * bb + 2]), p_margin, bx, bq,
+                                 2, bo);
+          Field H = H0;
+          if (use_patch) { H.patch = (const lds_float*)(Lpatch + ee * (kPatch * kPatch)); H.mip = (const lds_float*)(Lmip + ee * (kPatchBlocks * kPatchBlocks)); H.pi0 = Lporg[2 * ee]; H.pj0 = Lporg[2 * ee + 1]; H.ps = kPatch; }
+          near = slot_reach(H, g, false);
+        }
+        const int pos = wave_alloc<2>(near ? ns : 0, &Lcount[7]);
+        for (int k = 0; k < ns; ++k) {
+          if (near) Lslots[pos + k] = (unsigned)((s0 + k) * E + ee);
+          else {
+            Lreci[((s0 + k) * kRecWords + 0) * E + ee] = 0;
+            Lrec[((s0 + k) * kRecWords + 10) * E + ee] = 0.0f;
+          }
+        }
+      }
+      __syncthreads();
+      TMARK(24);
+      n_b1 = Lcount[7];
+      // the lower wavefronts integrate the forces while the upper ones run the per-slot pass
       forces();
     }
     for (int x = kThreads - 1 - tid; x < n_b1; x += kThreads) {
-      const int i = x;
+      const int i = m_terrain == 1 ? (int)Lslots[x] : x;
       int ee = i % E, s = i / E;
       int env_i = blockIdx.x * E + ee;
       ContactOut co = no_contact();
@@ -1962,7 +1985,6 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       // ahead of the reads that depend on it
       const int js_ob = js_side ? Ltjoint[js_j < J ? js_j : 0].child : Ltjoint[js_j < J ? js_j : 0].parent;
       const int js_voff = (js_ob < 0 ? 0 : js_ob) * kVS * E + js_e;
-      if (forces_late) __syncthreads();   // the other wavefronts have integrated the forces
       for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
         if (js_on) {
           const int e = js_e;
@@ -2026,16 +2048,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           if (!Lreci[(i / E * kRecWords + 0) * E + i % E])
             for (int r = 0; r < 3; ++r) Lwc[(i / E * 3 + r) * E + i % E] = 0.0f;
       }
-      if (forces_late)
-        for (int i = tid - joint_threads; i < B * E; i += n_reg)
-          if (blockIdx.x * E + i % E < N) forces_of(i / E, i % E);
       build_contact();
       build_pair();
       // the starting impulses of the contacts beyond one per thread are set by the thread that
       // relaxes them in every sweep below (same index mapping), so no other thread's store is read
       for (int k = n_reg + (kThreads - 1 - tid); k < n_active; k += n_reg)
         for (int r = 0; r < 3; ++r) overflow_lam(k, r) = WS ? p_warm * overflow_lam(k, r) : 0.0f;
-      if (forces_late) __syncthreads();
       for (int it = WS ? -1 : 0; it < a.iterations; ++it) {
         if (has_contact) {
           const int ee = cr.slot_e % E, sl = cr.slot_e / E;
