@@ -112,11 +112,12 @@ typedef struct sim_desc {
   int32_t n_collide_pairs;
   const int32_t* collide_pairs;
   int32_t group_size;
-  /* Warm start of the Jacobi rows (a stiffness gain within the relaxation scheme of Section
+  /* Warm start of the rows (a stiffness gain within the relaxation scheme of Section
    * 3.1): every joint row, and every terrain contact slot that was active in the previous
    * substep, starts a substep from warm_start (0..1; 0 = off) times the impulse it ended the
    * previous one with (a limit row only if it still stands for the same limit); these impulses
-   * are applied to the bodies before the first sweep.  What is kept survives from one sim_step
+   * are applied to the bodies before the first sweep (Jacobi) or are the first Newton iterate
+   * (solver 1, where 0.8 is worth about one Newton iteration in three).  What is kept survives from one sim_step
    * to the next and is cleared for an env by its reset and for all by sim_set_state.  About 0.8
    * halves the sweeps needed for the same penetration; with few sweeps values near 1 can build
    * up without bound (the kept impulse integrates the position error).  Capsule-capsule contacts
@@ -132,7 +133,7 @@ typedef struct sim_desc {
    * sim_step are then Newton iterations per substep (3 with 8 inner iterations is a sensible start).  It solves the joints
    * far more stiffly per unit of work where loads are carried (a hanging chain does not sag), costs
    * about 3.3 times a 20-sweep step, runs at most 8 envs per workgroup, and is not available together
-   * with the warm start or capsule-capsule collisions (SIM_ERR_ARG). */
+   * with capsule-capsule collisions (SIM_ERR_ARG). */
   int32_t solver;
   int32_t krylov_iterations;
   double newton_reg;

@@ -231,7 +231,6 @@ static int build_model(const sim_desc_t* d, int num_envs, Model* m) {
   if (d->solver == 1 && (d->krylov_iterations < 1 || d->krylov_iterations > 64)) return fail(SIM_ERR_ARG, "krylov_iterations %d outside 1..64", d->krylov_iterations);
   if (d->solver == 1 && !(d->newton_reg >= 0.0 && d->newton_reg <= 1.0)) return fail(SIM_ERR_ARG, "newton_reg outside 0..1");
   m->solver = d->solver; m->krylov = d->solver == 1 ? d->krylov_iterations : 0; m->newton_reg = (float)d->newton_reg;
-  if (m->solver == 1 && m->warm > 0.0f) return fail(SIM_ERR_ARG, "the Newton solver is not available together with the warm start");
   m->term_height = (float)d->term_height; m->alive_bonus = (float)d->alive_bonus;
   m->max_steps = d->max_episode_steps; m->gyro = d->gyroscopic; m->contacts = d->contacts;
   // Height map of the complex-terrain task (Section 4.1: 15 x 11, follows the centre of mass,
@@ -497,7 +496,9 @@ static int launch_step(sim* s, const float* actions, float h, int substeps, int 
   const bool few = m.max_joint_sides <= 4;
   if (m.solver == 1 && !newton_fits(m, s->E))
     return fail(SIM_ERR_ARG, "this robot does not fit the Newton solver's workgroup (a contact thread per slot)");
-  int lrc = m.solver == 1 ? ((s->E == 8 && few) ? launch(&step_kernel<8, 4, 0, kThreads, 0, 1>)
+  int lrc = (m.solver == 1 && m.warm > 0.0f) ? ((s->E == 8 && few) ? launch(&step_kernel<8, 4, 0, kThreads, 1, 1>)
+                             : few ? launch(&step_kernel<0, 4, 0, kThreads, 1, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 1, 1>))
+            : m.solver == 1 ? ((s->E == 8 && few) ? launch(&step_kernel<8, 4, 0, kThreads, 0, 1>)
                              : few ? launch(&step_kernel<0, 4, 0, kThreads, 0, 1>) : launch(&step_kernel<0, kMaxBodyJoints, 0, kThreads, 0, 1>))
             : (m.warm > 0.0f && pairs) ? ((s->E == 16 && few) ? launch(&step_kernel<16, 4, 1, kThreads, 1>)
                              : (s->E == 8 && few) ? launch(&step_kernel<8, 4, 1, kThreads, 1>)

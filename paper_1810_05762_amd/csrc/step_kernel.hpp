@@ -1732,6 +1732,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       constexpr float kFrictionEps = 1e-3f;   // m/s
       constexpr int kRedParts = 4;            // (J + S <= 64 blocks: at most sixteen per part)
       const bool jrole = joint_wave;
+      if constexpr (WS != 0) {
+        // a slot that is not active in this substep hands nothing on to the next one
+        for (int i = tid; i < S * E; i += kThreads)
+          if (!Lreci[(i / E * kRecWords + 0) * E + i % E])
+            for (int r = 0; r < 3; ++r) Lwc[(i / E * 3 + r) * E + i % E] = 0.0f;
+      }
       if (jrole) build_joint_side(); else build_contact();
       for (int i = tid; i < 3 * nblk * E; i += kThreads) Lred[i] = 0.0f;   // inactive slots contribute nothing
       const int nr = jrole ? 6 : 3;
@@ -1742,7 +1748,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       //   contact:    K[0..8] directions n, t1, t2, K[9..17] lever x direction, K[18..26] angular
       //               response, K[27] linear response.
       float K[32], Dg[6], bs[6];
-      int ones = 0, c_body = 0, c_slot_e = 0;
+      int ones = 0, uppers = 0, c_body = 0, c_slot_e = 0;
       if (jrole) {
         for (int k = 0; k < 3; ++k) {
           K[k] = jr.sr[k];
@@ -1751,6 +1757,7 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         }
         K[3] = jr.sv; K[4] = jr.sg;
         ones = jr.onesided;
+        uppers = jr.upper;
       } else {
         for (int r = 0; r < 3; ++r) {
           for (int c = 0; c < 3; ++c) { K[3 * r + c] = cr.dir[r][c]; K[9 + 3 * r + c] = cr.ang[r][c]; K[18 + 3 * r + c] = cr.Y[r][c]; }
@@ -1863,6 +1870,27 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         tc = (vals[8] + vals[9]) + (vals[10] + vals[11]);
       };
       float lam[6] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+      if constexpr (WS != 0) {
+        // Warm start: the first iterate is the share of what the rows ended the last substep with
+        // (a limit row only if it stands for the same limit as then; a slot that was not active
+        // then holds zero).
+        if (jrole) {
+          if (js_on) {
+            for (int k = 0; k < 3; ++k) lam[k] = p_warm * Lwj[(js_j * 6 + k) * E + js_e];
+            for (int k = 0; k < 3; ++k) {
+              const float kept = Lwj[(js_j * 6 + 3 + k) * E + js_e];
+              float l0 = p_warm * kept;
+              if ((ones >> k) & 1) {
+                const bool was_upper = __float_as_int(kept) < 0, is_upper = (uppers >> k) & 1;
+                l0 = was_upper == is_upper ? fabsf(l0) : 0.0f;
+              }
+              lam[3 + k] = l0;
+            }
+          }
+        } else if (has_contact) {
+          for (int r = 0; r < 3; ++r) lam[r] = cr.lam[r];
+        }
+      }
       for (int it = 0; it < a.iterations; ++it) {
         float sres[6], known[6], cp[6], ipd[6], tmp[6];
         int on = 0;
@@ -1959,6 +1987,20 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
       __syncthreads();
       gather_sum(true, Lvel);
       __syncthreads();
+      if constexpr (WS != 0) {
+        // kept for the next substep (both lanes of a joint hold the same impulses; everybody has
+        // read the old ones before the barriers above)
+        if (jrole) {
+          if (js_on && js_side == 0) {
+            for (int k = 0; k < 3; ++k) Lwj[(js_j * 6 + k) * E + js_e] = lam[k];
+            for (int k = 0; k < 3; ++k)
+              Lwj[(js_j * 6 + 3 + k) * E + js_e] = ((ones & uppers) >> k) & 1 ? -lam[3 + k] : lam[3 + k];
+          }
+        } else if (has_contact) {
+          const int ee = c_slot_e % E, sl = c_slot_e / E;
+          for (int r = 0; r < 3; ++r) Lwc[(sl * 3 + r) * E + ee] = lam[r];
+        }
+      }
     } else
     if (joint_wave) {
       build_joint_side();

@@ -22,12 +22,12 @@ def _scene(name, n):
         return _crowd_scene(n, 4, 7.0, "heightfield", warm=0.8 if name.endswith("warm") else 0.0)[1]
     sc, _cfg = scenes.config_scene(3, num_envs=n)
     extra = {"plain": {}, "warm": {"warm_start": 0.8}, "newton": {"solver": 1, "krylov_iters": 8},
-             "task_height_map": {"height_map": 1}}[name]
+             "newton_warm": {"solver": 1, "krylov_iters": 8, "warm_start": 0.8}, "task_height_map": {"height_map": 1}}[name]
     sc.params = dataclasses.replace(sc.params, **extra)
     return sc
 
 
-@pytest.mark.parametrize("name", ["plain", "warm", "newton", "collisions", "collisions_warm", "task_height_map"])
+@pytest.mark.parametrize("name", ["plain", "warm", "newton", "newton_warm", "collisions", "collisions_warm", "task_height_map"])
 def test_results_do_not_depend_on_what_lds_and_device_memory_held_before(name):
     import torch
     import paper_1810_05762_amd as P
@@ -38,7 +38,7 @@ def test_results_do_not_depend_on_what_lds_and_device_memory_held_before(name):
     sink = torch.zeros(2048, dtype=torch.int32, device="cuda")
     n = 64
     sc = _scene(name, n)
-    its = 3 if name == "newton" else 20
+    its = 3 if name.startswith("newton") else 20
 
     def run(lds_pattern, mem_byte):
         if mem_byte is not None:

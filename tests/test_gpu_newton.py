@@ -31,16 +31,18 @@ def _newton_gate(e1, e10):
     assert np.median(e10) <= TOL_1 and np.quantile(e10, 0.85) <= TOL_10 and np.isfinite(e10).all()
 
 
-def _newton_scene(k, n_envs):
+def _newton_scene(k, n_envs, share=0.0):
     sc, cfg = scenes.config_scene(k, num_envs=n_envs)
-    sc.params = dataclasses.replace(sc.params, solver=1, krylov_iters=KRYLOV)
+    sc.params = dataclasses.replace(sc.params, solver=1, krylov_iters=KRYLOV, warm_start=share)
     return sc, cfg
 
 
-@pytest.mark.parametrize("k,n_envs,warm,epb", [(1, 90, 40, None), (2, 77, 40, 8), (3, 77, 40, 8), (3, 21, 40, 5)])
-def test_newton_states_match_the_oracle_after_1_and_10_steps(k, n_envs, warm, epb):
+@pytest.mark.parametrize("k,n_envs,warm,epb,share", [(1, 90, 40, None, 0.0), (2, 77, 40, 8, 0.0), (3, 77, 40, 8, 0.0), (3, 21, 40, 5, 0.0),
+                                                     (3, 77, 40, 8, 0.8), (1, 45, 40, 5, 0.8)])
+def test_newton_states_match_the_oracle_after_1_and_10_steps(k, n_envs, warm, epb, share):
+    """`share` > 0: the rows' kept impulses are the first Newton iterate (warm start)."""
     P = _P()
-    sc, cfg = _newton_scene(k, n_envs)
+    sc, cfg = _newton_scene(k, n_envs, share)
     sim = P.Sim(sc)
     if epb:
         sim.set_envs_per_block(epb)
@@ -49,6 +51,8 @@ def test_newton_states_match_the_oracle_after_1_and_10_steps(k, n_envs, warm, ep
     for s in range(warm):
         sim.step(scenes.actions_for_step(cfg["seed"], s, n_envs, sc.robot.n_dofs), dt, sub, NEWTON_ITS)
     ref = oracle.OracleSim(sc, threads=8)
+    if share > 0:
+        sim.set_state(sim.get_state())        # both sides start with nothing kept
     ref.set_state(sim.get_state().cpu().numpy().astype(np.float64))
     sim.record_contacts(True)
     h = dt / sub
@@ -68,6 +72,14 @@ def test_newton_states_match_the_oracle_after_1_and_10_steps(k, n_envs, warm, ep
           f"10 steps median {np.median(e10):.2e} p90 {np.quantile(e10, .9):.2e} max {e10.max():.2e} ({forked.sum()} forked)")
     assert ref.get_contacts()["active"].sum() > n_envs // 2
     _newton_gate(e1, e10)
+    if share > 0:
+        # the kept impulses themselves, after the last substep, relative to the largest
+        lj, ls = sim.get_kept_impulses()
+        oj, os_ = ref.get_warm()
+        ej = np.abs(lj.cpu().numpy().astype(np.float64).reshape(oj.shape) - oj).reshape(n_envs, -1).max(1) / max(1.0, np.abs(oj).max())
+        es = np.abs(ls.cpu().numpy().astype(np.float64).reshape(os_.shape) - os_).reshape(n_envs, -1).max(1) / max(1.0, np.abs(os_).max())
+        assert np.abs(oj).max() > 0.1 and np.abs(os_).max() > 0.01
+        assert np.median(ej) <= TOL_10 and np.median(es) <= TOL_10
     sim.close()
 
 
@@ -101,11 +113,6 @@ def test_newton_solver_limits_are_reported():
     with pytest.raises(P.SimError):
         sim.set_envs_per_block(16)
     sim.close()
-    both = dataclasses.replace(sc.params, warm_start=0.5)
-    sc2 = scenes.make_scene(sc.robot, sc.terrain, 8, params=both)
-    with pytest.raises(P.SimError) as ei:
-        P.sim_workspace_bytes(P.make_desc(sc2)[0], 8)
-    assert ei.value.code == -1
     bad = dataclasses.replace(sc.params, krylov_iters=0)
     with pytest.raises(P.SimError):
         P.sim_workspace_bytes(P.make_desc(scenes.make_scene(sc.robot, sc.terrain, 8, params=bad))[0], 8)

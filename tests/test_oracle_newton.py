@@ -224,3 +224,54 @@ def test_envs_are_independent_and_deterministic_under_the_newton_solver():
     for s in range(40):
         o.step(scenes.actions_for_step(cfg["seed"], s, 6, 21)[4:5], cfg["dt"], 4, 3)
     assert np.array_equal(o.get_state()[0], outs[0][4])
+
+
+def _one_substep(rob, p, state, its, warm_from=None, share=1.0, dt=1 / 240):
+    """Velocities and kept impulses after one substep from `state`; with warm_from = (lam_j, lam_s)
+    the rows start from `share` of those impulses."""
+    o = oracle.OracleSim(single_scene(rob, params=p))
+    o.set_state(state)
+    if warm_from is not None:
+        o.set_warm_start(share)
+        o.set_warm(*warm_from)
+        o.set_warm_flags(-np.ones((1, o.J, 3), np.int32), np.ones((1, o.S), np.int32))
+    o.substep_phases(None, dt, its, oracle.PH_ALL)
+    return o.get_state()[0, :, 7:13].copy(), o.get_warm()
+
+
+def test_newton_warm_start_is_the_first_iterate_chain():
+    """The kept impulses times the share are the Newton method's first iterate (the paper names no
+    starting point; zero is the other choice).  A swinging chain has one solution: started from that
+    solution's own impulses a single Newton iteration with a single inner iteration - which from zero
+    is far from solved - finds nothing left to do and returns the solved velocities; started from
+    half of them it does not."""
+    rob = scenes.make_chain(n_links=4)
+    st = scenes.rest_state(rob, 1)
+    st[0, :, 7:13] = np.random.default_rng(5).uniform(-1, 1, (4, 6))
+    solved, kept = _one_substep(rob, newton(30, contacts=0), st, 3)
+    weak = newton(1, contacts=0)
+    cold, _ = _one_substep(rob, weak, st, 1)
+    warm, kept_again = _one_substep(rob, weak, st, 1, warm_from=kept)
+    half, _ = _one_substep(rob, weak, st, 1, warm_from=kept, share=0.5)
+    assert np.abs(cold - solved).max() > 1e-2
+    np.testing.assert_allclose(warm, solved, atol=1e-9)
+    np.testing.assert_allclose(kept_again[0], kept[0], atol=1e-9)
+    assert np.abs(half - solved).max() > 1e-3
+
+
+def test_newton_warm_start_is_the_first_iterate_contact_with_friction():
+    """The same for a capsule held on a tilted plane by friction (normal and both friction rows
+    carry impulses): from the solved impulses one weak iteration stays at the solution."""
+    th = np.radians(35.0)
+    p = newton(24, gravity=(G * np.sin(th), 0.0, -G * np.cos(th)))
+    rob, o = _lying_capsule(p)
+    for _ in range(30):
+        o.step(None, 1 / 60, 4, 6)
+    st = o.get_state()
+    solved, kept = _one_substep(rob, p, st, 60)      # (the friction law's compliance settles slowly)
+    assert np.abs(kept[1][0, :, 0]).max() > 1e-3 and np.abs(kept[1][0, :, 1:]).max() > 1e-4    # normal and friction impulses
+    weak = newton(1, gravity=(G * np.sin(th), 0.0, -G * np.cos(th)))
+    cold, _ = _one_substep(rob, weak, st, 1)
+    warm, _ = _one_substep(rob, weak, st, 1, warm_from=kept)
+    assert np.abs(cold - solved).max() > 1e-3
+    np.testing.assert_allclose(warm, solved, atol=1e-9)
