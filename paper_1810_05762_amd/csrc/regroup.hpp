@@ -64,19 +64,31 @@ __global__ void order_words_kernel(const float* __restrict__ state, const float*
 // number), so the ranks are a permutation.  Quadratic in N on purpose: no scratch memory, a
 // result that does not depend on scheduling, and a few milliseconds at 65536 agents.
 __global__ void rank_places_kernel(const unsigned long long* __restrict__ words, int N, int32_t* __restrict__ place_env) {
+  // A workgroup ranks 16 agents, 16 threads each: thread (agent a, part q) counts the smaller words
+  // among those at positions q, q + 16, ... of every tile, and the 16 counts of an agent are added
+  // up in LDS.  (One thread per agent left all but N / 256 compute units idle.)
   __shared__ unsigned long long tile[256];
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  __shared__ int part_rank[16][17];
+  const int al = threadIdx.x & 15, q = threadIdx.x >> 4;
+  const int i = blockIdx.x * 16 + al;
   const unsigned long long mine = i < N ? words[i] : ~0ull;
   int rank = 0;
   for (int j0 = 0; j0 < N; j0 += 256) {
     const int j = j0 + threadIdx.x;
-    tile[threadIdx.x] = j < N ? words[j] : ~0ull;
+    tile[threadIdx.x] = j < N ? words[j] : ~0ull;     // (a padding word is smaller than nothing)
     __syncthreads();
-    const int n_here = min(256, N - j0);
-    for (int k = 0; k < n_here; ++k) rank += tile[k] < mine ? 1 : 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) rank += tile[16 * k + q] < mine ? 1 : 0;
     __syncthreads();
   }
-  if (i < N) place_env[rank] = i;
+  part_rank[al][q] = rank;
+  __syncthreads();
+  if (q == 0 && i < N) {
+    int r = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) r += part_rank[al][k];
+    place_env[r] = i;
+  }
 }
 
 // Second pass: the agents of a window of W consecutive places (W a multiple of the group size G, at
@@ -96,7 +108,7 @@ __global__ void cluster_windows_kernel(const float* __restrict__ state, const fl
                                        int root, int G, int W, float reach, int32_t* __restrict__ place_env) {
   __shared__ float wp[3][kWindow];
   __shared__ unsigned long long adj[kWindow][4];
-  __shared__ unsigned long long free_mask[4], frontier[4];
+  __shared__ unsigned long long has_nb[4];
   __shared__ int agent_of[kWindow];
   __shared__ short seq[kWindow], csize[kWindow / 2], pick[kWindow];
   const int lane = threadIdx.x, w0 = blockIdx.x * W;
@@ -117,40 +129,68 @@ __global__ void cluster_windows_kernel(const float* __restrict__ state, const fl
       if (k != lane && d2 <= r2) mine[k >> 6] |= 1ull << (k & 63);
     }
   for (int w = 0; w < 4; ++w) adj[lane][w] = mine[w];
+  // which agents have a neighbour at all: one word per wavefront
+  {
+    const unsigned long long hn = __ballot((mine[0] | mine[1] | mine[2] | mine[3]) != 0ull);
+    if ((lane & 63) == 0) has_nb[lane >> 6] = hn;
+  }
   __syncthreads();
   if (lane == 0) {
+    // The sets of free agents and of a cluster's candidates live in registers (four 64-bit words
+    // each, indexed through unrolled loops): this thread works alone, and a set kept in LDS would
+    // cost it a round trip per look.
+    unsigned long long fm[4], fr[4], hn[4];
+#pragma unroll
     for (int w = 0; w < 4; ++w) {
       const int lo = 64 * w;
-      free_mask[w] = n >= lo + 64 ? ~0ull : (n > lo ? (1ull << (n - lo)) - 1ull : 0ull);
+      fm[w] = n >= lo + 64 ? ~0ull : (n > lo ? (1ull << (n - lo)) - 1ull : 0ull);
+      hn[w] = has_nb[w];
     }
     auto first_of = [&](const unsigned long long* m) -> int {
-      for (int w = 0; w < 4; ++w) if (m[w]) return 64 * w + __ffsll((long long)m[w]) - 1;
-      return -1;
+      int r = -1;
+#pragma unroll
+      for (int w = 3; w >= 0; --w) if (m[w]) r = 64 * w + __ffsll((long long)m[w]) - 1;
+      return r;
+    };
+    auto clear_bit = [&](unsigned long long* m, int i) {
+      const unsigned long long bit = 1ull << (i & 63);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) m[w] &= ~((i >> 6) == w ? bit : 0ull);
     };
     // 1. clusters
     int n_seq = 0, n_cl = 0;
-    for (int seed = 0; seed < n; ++seed) {
-      if (!((free_mask[seed >> 6] >> (seed & 63)) & 1ull)) continue;
-      unsigned long long any = 0ull;
-      for (int w = 0; w < 4; ++w) { frontier[w] = adj[seed][w] & free_mask[w]; any |= frontier[w]; }
-      if (!any) continue;
-      free_mask[seed >> 6] &= ~(1ull << (seed & 63));
-      seq[n_seq++] = (short)seed;
-      int cnt = 1;
-      while (cnt < G) {
-        const int nx = first_of(frontier);
-        if (nx < 0) break;
-        free_mask[nx >> 6] &= ~(1ull << (nx & 63));
-        seq[n_seq++] = (short)nx;
-        ++cnt;
-        for (int w = 0; w < 4; ++w) frontier[w] = (frontier[w] | adj[nx][w]) & free_mask[w];
+#pragma unroll
+    for (int sw = 0; sw < 4; ++sw) {
+      // seeds of this word in rising order: free agents that have neighbours at all (one without
+      // any can neither start a cluster nor be taken by one)
+      unsigned long long todo = fm[sw] & hn[sw];
+      while (todo) {
+        const int sb = __ffsll((long long)todo) - 1, seed = 64 * sw + sb;
+        todo &= todo - 1ull;
+        if (!((fm[sw] >> sb) & 1ull)) continue;          // taken by an earlier cluster meanwhile
+        unsigned long long any = 0ull;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { fr[w] = adj[seed][w] & fm[w]; any |= fr[w]; }
+        if (!any) continue;
+        clear_bit(fm, seed);
+        seq[n_seq++] = (short)seed;
+        int cnt = 1;
+        while (cnt < G) {
+          const int nx = first_of(fr);
+          if (nx < 0) break;
+          clear_bit(fm, nx);
+          seq[n_seq++] = (short)nx;
+          ++cnt;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) fr[w] = (fr[w] | adj[nx][w]) & fm[w];
+        }
+        csize[n_cl++] = (short)cnt;
       }
-      csize[n_cl++] = (short)cnt;
     }
     // 2. packing
     auto next_single = [&]() -> int {
-      const int sgl = first_of(free_mask);
-      if (sgl >= 0) free_mask[sgl >> 6] &= ~(1ull << (sgl & 63));
+      const int sgl = first_of(fm);
+      if (sgl >= 0) clear_bit(fm, sgl);
       return sgl;
     };
     int out = 0, pos = 0, filled = 0;

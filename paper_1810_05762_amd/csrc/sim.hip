@@ -944,7 +944,7 @@ extern "C" int sim_regroup(sim_t* s, float cell, float reach, void* stream) {
                      reinterpret_cast<const float*>(s->ws + s->lay.state),
                      reinterpret_cast<const float*>(s->ws + s->lay.origins), m.B, s->N, m.root, cell, words);
   HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(rank_places_kernel, dim3(blocks_for(s->N)), dim3(256), 0, st, words, s->N,
+  hipLaunchKernelGGL(rank_places_kernel, dim3(blocks_for(s->N, 16)), dim3(256), 0, st, words, s->N,
                      reinterpret_cast<int32_t*>(s->ws + s->lay.place_env));
   HIP_TRY(hipGetLastError());
   const int W = (kWindow / m.group) * m.group;   // window of the second pass: whole groups, one workgroup
