@@ -430,3 +430,34 @@ def test_height_map_observation_parity():
             assert np.abs(hm_g - hm_o).max() < 2e-4, (s, np.abs(hm_g - hm_o).max())
             assert np.ptp(hm_o, axis=1).min() > 0.01      # the terrain under the grid is not flat
     sim.close()
+
+
+def test_angles_of_the_observation_from_identical_states_agree_to_rounding():
+    """The kernel takes the joint angles, roll and the heading terms of the observation (Table 2)
+    from an arctangent of its own and hardware reciprocals; the oracle from the C library in
+    double precision.  Packed from the same fp32 states (flailing and fallen humanoids, joint angles
+    up to their limits of 2 rad, every heading), the two agree to a few ulp of single precision."""
+    P = _P()
+    sc, cfg = scenes.config_scene(3, num_envs=96)
+    sim, ref = P.Sim(sc), oracle.OracleSim(sc, threads=8)
+    sim.reset(cfg["seed"])
+    D = sc.robot.n_dofs
+    dt = float(np.float32(cfg["dt"]))
+    worst_angle = worst_root = 0.0
+    seen = 0.0
+    for s in range(60):
+        sim.step(scenes.actions_for_step(cfg["seed"], s, 96, D), dt, cfg["substeps"], cfg["iterations"])
+        if s % 6 != 5:
+            continue
+        st = sim.get_state()
+        sim.set_state(st)                                   # (packs the observation of exactly this state)
+        ref.set_state(st.cpu().numpy().astype(np.float64))
+        obs = sim.get_obs()[0].cpu().numpy().astype(np.float64)
+        eo = ref.get_obs()[0]
+        worst_angle = max(worst_angle, np.abs(obs[:, 11:11 + D] - eo[:, 11:11 + D]).max())
+        worst_root = max(worst_root, np.abs(obs[:, [1, 2, 9, 10]] - eo[:, [1, 2, 9, 10]]).max())
+        seen = max(seen, np.abs(eo[:, 11:11 + D]).max())
+    print(f"joint angles up to {seen:.2f} rad: largest difference {worst_angle:.2e}; roll, pitch, sin and cos of the heading error: {worst_root:.2e}")
+    assert seen > 1.0
+    assert worst_angle <= 2e-6 and worst_root <= 5e-6
+    sim.close()
