@@ -1404,9 +1404,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     for (int j = 0; j < kPairList; ++j) gp_off[j] = kPairCap * 12;
     bool gp_many = false;
     float gp_wsum = 0.0f;
+    int gp_cnt = 0;
     if constexpr (PC != 0) {
       if (g_on) {
         const int cnt = n_pc > 0 ? Lpbcnt[g_ref] : 0;
+        gp_cnt = cnt;
         if (cnt > 0 && cnt <= kPairList) {
           // the body's list (bytes 2 * queue index + side), sorted into queue order
           int v[kPairList];
@@ -1431,6 +1433,10 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         gp_many = cnt > kPairList;
       }
     }
+    // no body of this wavefront has more than two capsule-capsule contacts (the usual case): its
+    // averages read two list entries instead of six
+    constexpr int kPairFew = 2;
+    const bool gp_few = PC != 0 && __ballot(gp_cnt > kPairFew) == 0ull;
     // ---- C: block weight sums (and, on the plane, forces -> velocities)
     float nbf = 0.0f;
     if (is_body) {
@@ -1616,6 +1622,13 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         if constexpr (NS != 0) gat_w[NJ + k] = (used && Lreci[((g_slot0 + k) * kRecWords + 0) * E + e]) ? 1.0f : 0.0f;
       }
     }
+    // no body of this wavefront has more than two joint sides: its averages read two joint copies
+    // instead of NJ (the same in all lanes, so the choice is a scalar branch)
+    bool g_few = NJ > 2;
+#pragma unroll
+    for (int k = 2; k < NJ; ++k) g_few = g_few && __ballot(gat_w[k] != 0.0f) == 0ull;
+    // no slot of a body of this wavefront holds a contact in this substep: no slot copies are read
+    const bool g_noc = __ballot(gat_w[NJ] != 0.0f || gat_w[NJ + 1] != 0.0f || gat_w[NJ + 2] != 0.0f) == 0ull;
     // ---- S: sweeps
     // Wavefronts that hold joint threads run only the joint rows, the others only the contact
     // rows (a wave-uniform branch, so neither path carries the other's registers); both paths
@@ -1632,25 +1645,41 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
         // rounds at their magnitude and the velocity is rounded once per sweep, where a weighted
         // sum of the copies themselves would round it once per copy.
         const int ho = c0 * E;
-        float val[NJ + 3][NC], v0[NC];
+        float v0[NC], acc[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) v0[c] = Lvel[(g_b * kVS + c) * E + e + ho];
+        // the first KJ joint copies and the three slots' copies
+        auto sum_copies = [&](auto kj_tag, auto hc_tag) {
+          constexpr int KJ = decltype(kj_tag)::value, HC = decltype(hc_tag)::value;
+          float val[KJ + 3][NC];
 #pragma unroll
-        for (int k = 0; k < NJ; ++k)
+          for (int k = 0; k < KJ; ++k)
 #pragma unroll
-          for (int c = 0; c < NC; ++c) val[k][c] = Loutj[gat_off[k] + ho + c * E];
+            for (int c = 0; c < NC; ++c) val[k][c] = Loutj[gat_off[k] + ho + c * E];
+          if constexpr (HC != 0) {
 #pragma unroll
-        for (int k = 0; k < 3; ++k)
+            for (int k = 0; k < 3; ++k)
 #pragma unroll
-          for (int c = 0; c < NC; ++c) val[NJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
-        __builtin_amdgcn_sched_group_barrier(0x100, NC == 3 ? (NJ + 4) * 2 : NJ + 4, 0);  // the DS reads first
-        float acc[NC];
+              for (int c = 0; c < NC; ++c) val[KJ + k][c] = Loutc[gat_slot[k] + ho + c * E];
+          }
+          __builtin_amdgcn_sched_group_barrier(0x100, NC == 3 ? (KJ + 1 + 3 * HC) * 2 : KJ + 1 + 3 * HC, 0);  // the DS reads first
 #pragma unroll
-        for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
+          for (int c = 0; c < NC; ++c) acc[c] = 0.0f;
 #pragma unroll
-        for (int k = 0; k < NJ + 3; ++k)
+          for (int k = 0; k < KJ; ++k)
 #pragma unroll
-          for (int c = 0; c < NC; ++c) acc[c] += gat_w[k] * (val[k][c] - v0[c]);
+            for (int c = 0; c < NC; ++c) acc[c] += gat_w[k] * (val[k][c] - v0[c]);
+          if constexpr (HC != 0) {
+#pragma unroll
+            for (int k = 0; k < 3; ++k)
+#pragma unroll
+              for (int c = 0; c < NC; ++c) acc[c] += gat_w[NJ + k] * (val[KJ + k][c] - v0[c]);
+          }
+        };
+        constexpr int kFew = NJ > 2 ? 2 : NJ;
+        if (g_few && g_noc) sum_copies(std::integral_constant<int, kFew>{}, std::integral_constant<int, 0>{});
+        else if (g_few) sum_copies(std::integral_constant<int, kFew>{}, std::integral_constant<int, 1>{});
+        else sum_copies(std::integral_constant<int, NJ>{}, std::integral_constant<int, 1>{});
         if constexpr (PC != 0) {
           if (n_pc > 0) {
             if (gp_many) {
@@ -1664,16 +1693,22 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
               }
               for (int c = 0; c < NC; ++c) acc[c] -= gp_wsum * v0[c];   // (their copies come multiplied by the weights)
             } else {
-              // the (weighted) copies of the listed contacts; unused entries point at zeros
-              float pv[kPairList][NC];
+              // the (weighted) copies of the listed contacts (the list holds the used entries first);
+              // unused entries point at zeros
+              auto sum_pairs = [&](auto kp_tag) {
+                constexpr int KP = decltype(kp_tag)::value;
+                float pv[KP][NC];
 #pragma unroll
-              for (int j = 0; j < kPairList; ++j)
+                for (int j = 0; j < KP; ++j)
 #pragma unroll
-                for (int c = 0; c < NC; ++c) pv[j][c] = Lpo[gp_off[j] + c0 + c];
+                  for (int c = 0; c < NC; ++c) pv[j][c] = Lpo[gp_off[j] + c0 + c];
 #pragma unroll
-              for (int j = 0; j < kPairList; ++j)
+                for (int j = 0; j < KP; ++j)
 #pragma unroll
-                for (int c = 0; c < NC; ++c) acc[c] += pv[j][c];
+                  for (int c = 0; c < NC; ++c) acc[c] += pv[j][c];
+              };
+              if (gp_few) sum_pairs(std::integral_constant<int, kPairFew>{});
+              else sum_pairs(std::integral_constant<int, kPairList>{});
               // (the listed copies come multiplied by their weights: the snapshot's share goes off in one piece)
 #pragma unroll
               for (int c = 0; c < NC; ++c) acc[c] -= gp_wsum * v0[c];
