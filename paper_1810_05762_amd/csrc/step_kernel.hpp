@@ -1435,8 +1435,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     }
     // no body of this wavefront has more than two capsule-capsule contacts (the usual case): its
     // averages read two list entries instead of six
+    // (only where a wavefront holds few bodies: with four envs per workgroup it holds sixteen, the
+    // short forms are never taken and the choice itself costs 5 %)
+    constexpr bool g_variants = EC >= 8;
     constexpr int kPairFew = 2;
-    const bool gp_few = PC != 0 && __ballot(gp_cnt > kPairFew) == 0ull;
+    const bool gp_few = g_variants && PC != 0 && __ballot(gp_cnt > kPairFew) == 0ull;
     // ---- C: block weight sums (and, on the plane, forces -> velocities)
     float nbf = 0.0f;
     if (is_body) {
@@ -1624,11 +1627,11 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
     }
     // no body of this wavefront has more than two joint sides: its averages read two joint copies
     // instead of NJ (the same in all lanes, so the choice is a scalar branch)
-    bool g_few = NJ > 2;
+    bool g_few = g_variants && NJ > 2;
 #pragma unroll
     for (int k = 2; k < NJ; ++k) g_few = g_few && __ballot(gat_w[k] != 0.0f) == 0ull;
     // no slot of a body of this wavefront holds a contact in this substep: no slot copies are read
-    const bool g_noc = __ballot(gat_w[NJ] != 0.0f || gat_w[NJ + 1] != 0.0f || gat_w[NJ + 2] != 0.0f) == 0ull;
+    const bool g_noc = g_variants && __ballot(gat_w[NJ] != 0.0f || gat_w[NJ + 1] != 0.0f || gat_w[NJ + 2] != 0.0f) == 0ull;
     // ---- S: sweeps
     // Wavefronts that hold joint threads run only the joint rows, the others only the contact
     // rows (a wave-uniform branch, so neither path carries the other's registers); both paths
@@ -1677,9 +1680,13 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
           }
         };
         constexpr int kFew = NJ > 2 ? 2 : NJ;
-        if (g_few && g_noc) sum_copies(std::integral_constant<int, kFew>{}, std::integral_constant<int, 0>{});
-        else if (g_few) sum_copies(std::integral_constant<int, kFew>{}, std::integral_constant<int, 1>{});
-        else sum_copies(std::integral_constant<int, NJ>{}, std::integral_constant<int, 1>{});
+        if constexpr (g_variants) {
+          if (g_few && g_noc) sum_copies(std::integral_constant<int, kFew>{}, std::integral_constant<int, 0>{});
+          else if (g_few) sum_copies(std::integral_constant<int, kFew>{}, std::integral_constant<int, 1>{});
+          else sum_copies(std::integral_constant<int, NJ>{}, std::integral_constant<int, 1>{});
+        } else {
+          sum_copies(std::integral_constant<int, NJ>{}, std::integral_constant<int, 1>{});
+        }
         if constexpr (PC != 0) {
           if (n_pc > 0) {
             if (gp_many) {
@@ -1707,8 +1714,12 @@ __global__ __launch_bounds__(NT) void step_kernel(StepArgs a) {
 #pragma unroll
                   for (int c = 0; c < NC; ++c) acc[c] += pv[j][c];
               };
-              if (gp_few) sum_pairs(std::integral_constant<int, kPairFew>{});
-              else sum_pairs(std::integral_constant<int, kPairList>{});
+              if constexpr (g_variants) {
+                if (gp_few) sum_pairs(std::integral_constant<int, kPairFew>{});
+                else sum_pairs(std::integral_constant<int, kPairList>{});
+              } else {
+                sum_pairs(std::integral_constant<int, kPairList>{});
+              }
               // (the listed copies come multiplied by their weights: the snapshot's share goes off in one piece)
 #pragma unroll
               for (int c = 0; c < NC; ++c) acc[c] -= gp_wsum * v0[c];
