@@ -33,14 +33,17 @@ def _statistics(robot, st, recs):
     sep = _joint_separation(robot, st)
     act = recs["active"] != 0
     return {"joint separation, median": np.median(sep), "joint separation, 99 %": np.quantile(sep, 0.99),
-            "active contacts per env": act.sum(1).mean(), "penetration, 99 %": np.quantile(-recs["d"][act], 0.99)}
+            "active contacts per env": act.sum(1).mean(), "penetration, 90 %": np.quantile(-recs["d"][act], 0.90)}
 
 
-def test_ten_seconds_of_the_headline_workload_keep_the_invariants_and_the_oracles_statistics():
+@pytest.mark.parametrize("k", [3, 2, 1])
+def test_ten_seconds_of_a_workload_keep_the_invariants_and_the_oracles_statistics(k):
+    """k = 3: the headline workload (4096 humanoids on the heightfield, wide workgroups); 2 and 1:
+    1024 humanoids and 1024 ants on the plane (four envs per workgroup)."""
     import paper_1810_05762_amd as P
-    sc, cfg = scenes.config_scene(3)
+    sc, cfg = scenes.config_scene(k)
     N, D, n_ref = sc.num_envs, sc.robot.n_dofs, 256
-    sub, _ = scenes.config_scene(3, num_envs=n_ref)
+    sub, _ = scenes.config_scene(k, num_envs=n_ref)
     sub.env_origins = sc.env_origins[:n_ref].copy()
     sim = P.Sim(sc)
     sim.reset(cfg["seed"])
@@ -53,7 +56,7 @@ def test_ten_seconds_of_the_headline_workload_keep_the_invariants_and_the_oracle
     for s in range(600):
         sim.step(acts[s % 16], dt, cfg["substeps"], cfg["iterations"])
         ref.step(acts[s % 16][:n_ref], dt, cfg["substeps"], cfg["iterations"])
-        if s >= 199 and s % 100 == 99:      # the humanoids have fallen by then: one regime
+        if s >= 199 and s % 25 == 24:       # the robots have landed or fallen by then: one regime
             g = sim.get_state().cpu().numpy().astype(np.float64)
             # invariants of the integrator: unit quaternions, the angular-velocity cap
             assert np.isfinite(g).all()
@@ -62,12 +65,12 @@ def test_ten_seconds_of_the_headline_workload_keep_the_invariants_and_the_oracle
             samples_g.append(_statistics(sc.robot, g, sim.get_contacts()))
             samples_o.append(_statistics(sub.robot, ref.get_state(), ref.get_contacts()))
     sim.check()
-    # the same distribution on both sides (five samples each; the oracle's 256 envs leave a
+    # the same distribution on both sides (sixteen samples each; the oracle's 256 envs leave a
     # sampling noise of a few per cent in the medians and about 10 % in the 99 % quantiles)
     # (measured differences: 1.3 %, 2 %, 0.8 %, 2.7 %)
     for name, tol in (("joint separation, median", 0.06), ("joint separation, 99 %", 0.12),
-                      ("active contacts per env", 0.08), ("penetration, 99 %", 0.15)):
+                      ("active contacts per env", 0.08), ("penetration, 90 %", 0.15)):
         vg, vo = np.mean([d[name] for d in samples_g]), np.mean([d[name] for d in samples_o])
-        print(f"{name}: gpu {vg:.4g}, oracle {vo:.4g}")
+        print(f"config {k}: {name}: gpu {vg:.4g}, oracle {vo:.4g}")
         assert abs(vg - vo) <= tol * vo, name
     sim.close()
